@@ -1,0 +1,301 @@
+/*
+ * CPU oracle for the RecD deduplicated-embedding hot path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * Plain, slow, single-threaded C that writes out the paper's definitions directly.  It is the
+ * parity reference for the HIP library and shares no code, header, table or helper with it.
+ * Only tests, the smoke check and the benchmark's CPU-baseline leg may call it; the product
+ * path never does.
+ *
+ * There is deliberately no hashing, no blocking and no reordering here: duplicate detection is
+ * a linear search with element-by-element list comparison, sums run in list order in double.
+ *
+ * Every function is pinned by the CPU test-suite against values printed in the paper
+ * (Sec. 4.2 worked example of features b, c, d; Sec. 5 "Deduplicated Pooling" sums), against
+ * brute-force pairwise list comparison, against closed forms and against independent library
+ * routines (embedding_bag / index_select / autograd in fp64).  No function is "parity unpinned".
+ *
+ * Conventions shared by all entry points
+ *   KJT (Sec. 4.2): values[N] feature-major; offsets[F*B+1], offsets[f*B+b] = start of row b of
+ *   feature f, one trailing sentinel (the paper's offsets slice is the first F*B entries; the
+ *   last row's length is |values| - offsets[last], which the sentinel states explicitly).
+ *   IKJT (Sec. 4.2): u_values, u_offsets[U+1] (positions into u_values, trailing sentinel),
+ *   inverse[F*B] with inverse[f*B+b] in [0,U_f) local to feature f, feat_uoff[F+1] = prefix sum
+ *   of the per-feature unique counts U_f.
+ *   Return value: 0 = ok, negative = a precondition of the definition does not hold.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#include <math.h>
+
+enum { OR_F32 = 0, OR_F16 = 1, OR_BF16 = 2 };
+
+/* ---- element decoding: IEEE binary16 / bfloat16 bit patterns to double, exactly ---------- */
+double oracle_half_to_double(uint16_t h)
+{
+    int sign = (h >> 15) & 1;
+    int exp = (h >> 10) & 0x1f;
+    int man = h & 0x3ff;
+    double v;
+    if (exp == 0)
+        v = ldexp((double)man, -24); /* subnormal or zero: man * 2^-10 * 2^-14 */
+    else if (exp == 31)
+        v = man ? NAN : INFINITY;
+    else
+        v = ldexp(1.0 + (double)man / 1024.0, exp - 15);
+    return sign ? -v : v;
+}
+
+double oracle_bf16_to_double(uint16_t h)
+{
+    /* bfloat16 is the upper half of a binary32 */
+    uint32_t bits = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (double)f;
+}
+
+static double elem(const void *table, int dtype, int64_t idx)
+{
+    if (dtype == OR_F32)
+        return (double)((const float *)table)[idx];
+    if (dtype == OR_F16)
+        return oracle_half_to_double(((const uint16_t *)table)[idx]);
+    return oracle_bf16_to_double(((const uint16_t *)table)[idx]);
+}
+
+/* ---- precondition check (Sec. 4.2: offsets point to row starts inside values) ------------ */
+int oracle_check_kjt(int F, int64_t B, int64_t N, const int64_t *values, const int64_t *offsets,
+                     const int64_t *rows /* [F] or NULL */)
+{
+    if (F < 0 || B < 0 || N < 0)
+        return -1;
+    int64_t L = (int64_t)F * B;
+    if (offsets[0] != 0 || offsets[L] != N)
+        return -2;
+    for (int64_t i = 0; i < L; i++)
+        if (offsets[i + 1] < offsets[i])
+            return -3;
+    if (rows)
+        for (int f = 0; f < F; f++)
+            for (int64_t j = offsets[(int64_t)f * B]; j < offsets[(int64_t)(f + 1) * B]; j++)
+                if (values[j] < 0 || values[j] >= rows[f])
+                    return -4;
+    return 0;
+}
+
+/* ---- KJT -> IKJT (Sec. 4.2 "InverseKeyedJaggedTensor") -------------------------------------
+ * Two rows of a feature are duplicates iff their lists have the same length and the same ids in
+ * the same order (Sec. 3: "exactly the same list"; exact matches only).  Scanning b upwards, a
+ * row whose list was met before points at that earlier slot; otherwise it opens the next slot
+ * and its list is stored once.  Slots are therefore numbered in first-occurrence order, which
+ * is what the worked example of feature b shows (rows 0 and 2 both point at offsets[0]).
+ * Features are independent (each its own group); unique arrays are concatenated feature-major.
+ */
+int oracle_build_ikjt(int F, int64_t B, const int64_t *values, const int64_t *offsets,
+                      int64_t *u_values, int64_t *u_offsets, int32_t *inverse, int64_t *feat_uoff)
+{
+    int64_t U = 0, M = 0;
+    u_offsets[0] = 0;
+    for (int f = 0; f < F; f++) {
+        int64_t first_slot = U;
+        feat_uoff[f] = U;
+        for (int64_t b = 0; b < B; b++) {
+            const int64_t *list = values + offsets[(int64_t)f * B + b];
+            int64_t len = offsets[(int64_t)f * B + b + 1] - offsets[(int64_t)f * B + b];
+            int64_t found = -1;
+            for (int64_t s = first_slot; s < U && found < 0; s++) {
+                if (u_offsets[s + 1] - u_offsets[s] != len)
+                    continue;
+                const int64_t *cand = u_values + u_offsets[s];
+                int64_t k = 0;
+                while (k < len && cand[k] == list[k])
+                    k++;
+                if (k == len)
+                    found = s;
+            }
+            if (found < 0) {
+                for (int64_t k = 0; k < len; k++)
+                    u_values[M + k] = list[k];
+                M += len;
+                found = U++;
+                u_offsets[U] = M;
+            }
+            inverse[(int64_t)f * B + b] = (int32_t)(found - first_slot);
+        }
+    }
+    feat_uoff[F] = U;
+    return 0;
+}
+
+/* ---- sum-pooled embedding-bag lookup (Sec. 2.2 pooling; Sec. 5 "EMB Lookups",
+ * "Deduplicated Pooling") --------------------------------------------------------------------
+ * out[l,:] = sum over the ids j of list l, in list order, of W_f[values[j],:], accumulated in
+ * double.  The same routine serves the KJT (list_off[f] = f*B, offsets = KJT offsets) and the
+ * unique lists of an IKJT (list_off = feat_uoff, offsets = u_offsets): the lists of feature f
+ * are l in [list_off[f], list_off[f+1]).  An empty list pools to the zero vector.
+ */
+int oracle_pooled_lookup(int F, int D, int dtype, const void *const *tables, const int64_t *rows,
+                         const int64_t *values, const int64_t *offsets, const int64_t *list_off,
+                         double *out)
+{
+    for (int f = 0; f < F; f++) {
+        for (int64_t l = list_off[f]; l < list_off[f + 1]; l++) {
+            double *o = out + l * D;
+            for (int d = 0; d < D; d++)
+                o[d] = 0.0;
+            for (int64_t j = offsets[l]; j < offsets[l + 1]; j++) {
+                int64_t id = values[j];
+                if (id < 0 || id >= rows[f])
+                    return -4;
+                for (int d = 0; d < D; d++)
+                    o[d] += elem(tables[f], dtype, id * D + d);
+            }
+        }
+    }
+    return 0;
+}
+
+/* ---- IKJT -> KJT for pooled rows (Sec. 5 "Jagged Index Select": index_select by the inverse)
+ * out[f,b,:] = pooled[feat_uoff[f] + inverse[f,b], :]
+ */
+int oracle_expand_inverse(int F, int64_t B, int D, const double *pooled, const int64_t *feat_uoff,
+                          const int32_t *inverse, double *out)
+{
+    for (int f = 0; f < F; f++)
+        for (int64_t b = 0; b < B; b++) {
+            int64_t u = inverse[(int64_t)f * B + b];
+            if (u < 0 || u >= feat_uoff[f + 1] - feat_uoff[f])
+                return -5;
+            memcpy(out + ((int64_t)f * B + b) * D, pooled + (feat_uoff[f] + u) * D,
+                   sizeof(double) * D);
+        }
+    return 0;
+}
+
+static int cmp_i64(const void *a, const void *b)
+{
+    int64_t x = *(const int64_t *)a, y = *(const int64_t *)b;
+    return (x > y) - (x < y);
+}
+
+/* sorted distinct ids of ids[0..n): returns the count, writes them to dst */
+static int64_t sorted_distinct(const int64_t *ids, int64_t n, int64_t *dst)
+{
+    if (n == 0)
+        return 0;
+    int64_t *tmp = (int64_t *)malloc(sizeof(int64_t) * n);
+    memcpy(tmp, ids, sizeof(int64_t) * n);
+    qsort(tmp, n, sizeof(int64_t), cmp_i64);
+    int64_t r = 0;
+    for (int64_t i = 0; i < n; i++)
+        if (i == 0 || tmp[i] != tmp[i - 1])
+            dst[r++] = tmp[i];
+    free(tmp);
+    return r;
+}
+
+static int64_t find_row(const int64_t *sorted, int64_t n, int64_t key)
+{
+    const int64_t *p = (const int64_t *)bsearch(&key, sorted, n, sizeof(int64_t), cmp_i64);
+    return p ? (int64_t)(p - sorted) : -1;
+}
+
+/* ---- backward of expand + pooled lookup on the IKJT (chain rule of the two forward steps;
+ * the paper only states that IKJTs encode the same logical data, Sec. 6.2 "Accuracy") ---------
+ * step 1  g_u[u,:]  = sum over b ascending with inverse[f,b] == u of grad_out[f,b,:]
+ * step 2  G_f[r,:]  = sum over positions j ascending of feature f's unique ids with
+ *                     u_values[j] == r of g_u[list containing j, :]
+ * Output: touched_rows = per feature the ascending distinct ids (feature-major, feat_roff[F+1]
+ * prefix counts), grad_rows[R,D] aligned with touched_rows.  All sums in double.
+ */
+int oracle_backward_dedup(int F, int64_t B, int D, const float *grad_out, const int32_t *inverse,
+                          const int64_t *feat_uoff, const int64_t *u_values,
+                          const int64_t *u_offsets, int64_t *touched_rows, int64_t *feat_roff,
+                          double *grad_rows)
+{
+    int64_t U = feat_uoff[F];
+    double *g_u = (double *)calloc((size_t)(U > 0 ? U : 1) * D, sizeof(double));
+    if (!g_u)
+        return -9;
+    for (int f = 0; f < F; f++)
+        for (int64_t b = 0; b < B; b++) {
+            int64_t u = feat_uoff[f] + inverse[(int64_t)f * B + b];
+            const float *g = grad_out + ((int64_t)f * B + b) * D;
+            for (int d = 0; d < D; d++)
+                g_u[u * D + d] += (double)g[d];
+        }
+    int64_t R = 0;
+    for (int f = 0; f < F; f++) {
+        feat_roff[f] = R;
+        int64_t j0 = u_offsets[feat_uoff[f]], j1 = u_offsets[feat_uoff[f + 1]];
+        int64_t r_f = sorted_distinct(u_values + j0, j1 - j0, touched_rows + R);
+        double *G = grad_rows + R * D;
+        for (int64_t i = 0; i < r_f * D; i++)
+            G[i] = 0.0;
+        for (int64_t u = feat_uoff[f]; u < feat_uoff[f + 1]; u++)
+            for (int64_t j = u_offsets[u]; j < u_offsets[u + 1]; j++) {
+                int64_t k = find_row(touched_rows + R, r_f, u_values[j]);
+                for (int d = 0; d < D; d++)
+                    G[k * D + d] += g_u[u * D + d];
+            }
+        R += r_f;
+    }
+    feat_roff[F] = R;
+    free(g_u);
+    return 0;
+}
+
+/* ---- the same gradient straight from the KJT, never looking at the IKJT -------------------
+ * G_f[r,:] = sum over b ascending, over positions j of list (f,b) with values[j] == r, of
+ * grad_out[f,b,:].  Must agree with oracle_backward_dedup up to double rounding order.
+ */
+int oracle_backward_kjt(int F, int64_t B, int D, const float *grad_out, const int64_t *values,
+                        const int64_t *offsets, int64_t *touched_rows, int64_t *feat_roff,
+                        double *grad_rows)
+{
+    int64_t R = 0;
+    for (int f = 0; f < F; f++) {
+        feat_roff[f] = R;
+        int64_t j0 = offsets[(int64_t)f * B], j1 = offsets[(int64_t)(f + 1) * B];
+        int64_t r_f = sorted_distinct(values + j0, j1 - j0, touched_rows + R);
+        double *G = grad_rows + R * D;
+        for (int64_t i = 0; i < r_f * D; i++)
+            G[i] = 0.0;
+        for (int64_t b = 0; b < B; b++) {
+            const float *g = grad_out + ((int64_t)f * B + b) * D;
+            for (int64_t j = offsets[(int64_t)f * B + b]; j < offsets[(int64_t)f * B + b + 1]; j++) {
+                int64_t k = find_row(touched_rows + R, r_f, values[j]);
+                for (int d = 0; d < D; d++)
+                    G[k * D + d] += (double)g[d];
+            }
+        }
+        R += r_f;
+    }
+    feat_roff[F] = R;
+    return 0;
+}
+
+/* ---- row-wise Adagrad on the touched rows (not in the paper; the benchmark configuration
+ * fixes lr and eps, the form is this build's reading) -------------------------------------------
+ * One accumulator m[r] per table row.  For each touched row, once per step with the aggregated
+ * gradient:  m[r] += (1/D) * sum_d G[r,d]^2 ;  W[r,d] -= lr * G[r,d] / (sqrt(m[r]) + eps).
+ * Inputs: current rows and accumulators of the touched rows only (w_rows[R,D], m_rows[R]);
+ * outputs the updated ones.  Untouched rows are by definition unchanged.
+ */
+int oracle_rowwise_adagrad(int64_t R, int D, const double *grad_rows, const double *w_rows,
+                           const double *m_rows, double lr, double eps, double *w_new,
+                           double *m_new)
+{
+    for (int64_t r = 0; r < R; r++) {
+        double ss = 0.0;
+        for (int d = 0; d < D; d++)
+            ss += grad_rows[r * D + d] * grad_rows[r * D + d];
+        double m = m_rows[r] + ss / (double)D;
+        m_new[r] = m;
+        double denom = sqrt(m) + eps;
+        for (int d = 0; d < D; d++)
+            w_new[r * D + d] = w_rows[r * D + d] - lr * grad_rows[r * D + d] / denom;
+    }
+    return 0;
+}

@@ -1,0 +1,207 @@
+"""ctypes front-end of the plain C oracle (oracle/recd_oracle.c).  TEST INFRASTRUCTURE ONLY.
+
+The arithmetic lives in the C file; this module only marshals numpy arrays.  The two
+closed-form functions of the paper's duplication model (Sec. 4.2 "Using IKJTs") are written
+here because they are one line each.
+"""
+from __future__ import annotations
+
+import ctypes as C
+from typing import List, Sequence, Tuple
+
+import numpy as np
+
+from . import build as _build
+
+_lib = C.CDLL(_build.build())
+
+_i64p = C.POINTER(C.c_int64)
+_i32p = C.POINTER(C.c_int32)
+_f64p = C.POINTER(C.c_double)
+_f32p = C.POINTER(C.c_float)
+
+DTYPES = {"f32": 0, "f16": 1, "bf16": 2}
+
+_lib.oracle_half_to_double.restype = C.c_double
+_lib.oracle_half_to_double.argtypes = [C.c_uint16]
+_lib.oracle_bf16_to_double.restype = C.c_double
+_lib.oracle_bf16_to_double.argtypes = [C.c_uint16]
+
+
+def _p(a: np.ndarray, t):
+    assert a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(t)
+
+
+def _i64(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.int64)
+
+
+class OracleError(ValueError):
+    pass
+
+
+def _check(rc: int, what: str):
+    if rc != 0:
+        raise OracleError(f"{what}: precondition violated (code {rc})")
+
+
+def half_to_double(bits: int) -> float:
+    return float(_lib.oracle_half_to_double(C.c_uint16(bits)))
+
+
+def bf16_to_double(bits: int) -> float:
+    return float(_lib.oracle_bf16_to_double(C.c_uint16(bits)))
+
+
+def check_kjt(F: int, B: int, values, offsets, rows=None) -> int:
+    values, offsets = _i64(values), _i64(offsets)
+    r = _i64(rows) if rows is not None else None
+    return int(_lib.oracle_check_kjt(C.c_int(F), C.c_int64(B), C.c_int64(values.shape[0]),
+                                     _p(values, _i64p), _p(offsets, _i64p),
+                                     _p(r, _i64p) if r is not None else None))
+
+
+def build_ikjt(F: int, B: int, values, offsets):
+    """KJT -> IKJT (Sec. 4.2). Returns (u_values[M], u_offsets[U+1], inverse[F*B] int32, feat_uoff[F+1])."""
+    values, offsets = _i64(values), _i64(offsets)
+    _check(check_kjt(F, B, values, offsets), "build_ikjt")
+    N, L = values.shape[0], F * B
+    u_values = np.zeros(max(N, 1), dtype=np.int64)
+    u_offsets = np.zeros(L + 1, dtype=np.int64)
+    inverse = np.zeros(max(L, 1), dtype=np.int32)
+    feat_uoff = np.zeros(F + 1, dtype=np.int64)
+    rc = _lib.oracle_build_ikjt(C.c_int(F), C.c_int64(B), _p(values, _i64p), _p(offsets, _i64p),
+                                _p(u_values, _i64p), _p(u_offsets, _i64p), _p(inverse, _i32p),
+                                _p(feat_uoff, _i64p))
+    _check(rc, "build_ikjt")
+    U = int(feat_uoff[F])
+    M = int(u_offsets[U])
+    return u_values[:M].copy(), u_offsets[:U + 1].copy(), inverse[:L].copy(), feat_uoff
+
+
+def _table_ptrs(tables: Sequence[np.ndarray], dtype: str):
+    keep = []
+    for t in tables:
+        if dtype == "f32":
+            assert t.dtype == np.float32
+        elif dtype == "f16":
+            assert t.dtype == np.float16
+        else:
+            assert t.dtype == np.uint16
+        keep.append(np.ascontiguousarray(t))
+    arr = (C.c_void_p * len(keep))(*[t.ctypes.data for t in keep])
+    return arr, keep
+
+
+def pooled_lookup(tables: Sequence[np.ndarray], dtype: str, values, offsets, list_off) -> np.ndarray:
+    """Sum-pooled lookup (Sec. 2.2, Sec. 5) of the lists [list_off[f], list_off[f+1]) of each
+    feature f in table f.  Returns float64 [L, D]."""
+    F = len(tables)
+    values, offsets, list_off = _i64(values), _i64(offsets), _i64(list_off)
+    D = int(tables[0].shape[1]) if F else 1
+    rows = _i64([t.shape[0] for t in tables])
+    L = int(list_off[F]) if F else 0
+    out = np.zeros((max(L, 1), D), dtype=np.float64)
+    ptrs, keep = _table_ptrs(tables, dtype)
+    rc = _lib.oracle_pooled_lookup(C.c_int(F), C.c_int(D), C.c_int(DTYPES[dtype]), ptrs,
+                                   _p(rows, _i64p), _p(values, _i64p), _p(offsets, _i64p),
+                                   _p(list_off, _i64p), _p(out, _f64p))
+    _check(rc, "pooled_lookup")
+    del keep
+    return out[:L]
+
+
+def kjt_pooled_lookup(tables, dtype: str, B: int, values, offsets) -> np.ndarray:
+    """Non-deduplicated lookup over every row of the batch. float64 [F, B, D]."""
+    F = len(tables)
+    list_off = np.arange(F + 1, dtype=np.int64) * B
+    out = pooled_lookup(tables, dtype, values, offsets, list_off)
+    return out.reshape(F, B, -1)
+
+
+def expand_inverse(F: int, B: int, pooled: np.ndarray, feat_uoff, inverse) -> np.ndarray:
+    """out[f,b,:] = pooled[feat_uoff[f] + inverse[f,b], :]  (Sec. 5 index_select). float64 [F,B,D]."""
+    pooled = np.ascontiguousarray(pooled, dtype=np.float64)
+    D = pooled.shape[1]
+    feat_uoff = _i64(feat_uoff)
+    inverse = np.ascontiguousarray(inverse, dtype=np.int32)
+    out = np.zeros((F, B, D), dtype=np.float64)
+    rc = _lib.oracle_expand_inverse(C.c_int(F), C.c_int64(B), C.c_int(D), _p(pooled, _f64p),
+                                    _p(feat_uoff, _i64p), _p(inverse, _i32p), _p(out, _f64p))
+    _check(rc, "expand_inverse")
+    return out
+
+
+def backward_dedup(F: int, B: int, grad_out: np.ndarray, inverse, feat_uoff, u_values, u_offsets):
+    """Returns (touched_rows[R] int64, feat_roff[F+1], grad_rows[R,D] float64)."""
+    grad_out = np.ascontiguousarray(grad_out, dtype=np.float32)
+    D = grad_out.shape[-1]
+    inverse = np.ascontiguousarray(inverse, dtype=np.int32)
+    feat_uoff, u_values, u_offsets = _i64(feat_uoff), _i64(u_values), _i64(u_offsets)
+    M = u_values.shape[0]
+    touched = np.zeros(max(M, 1), dtype=np.int64)
+    feat_roff = np.zeros(F + 1, dtype=np.int64)
+    grad_rows = np.zeros((max(M, 1), D), dtype=np.float64)
+    rc = _lib.oracle_backward_dedup(C.c_int(F), C.c_int64(B), C.c_int(D), _p(grad_out, _f32p),
+                                    _p(inverse, _i32p), _p(feat_uoff, _i64p), _p(u_values, _i64p),
+                                    _p(u_offsets, _i64p), _p(touched, _i64p), _p(feat_roff, _i64p),
+                                    _p(grad_rows, _f64p))
+    _check(rc, "backward_dedup")
+    R = int(feat_roff[F])
+    return touched[:R].copy(), feat_roff, grad_rows[:R].copy()
+
+
+def backward_kjt(F: int, B: int, grad_out: np.ndarray, values, offsets):
+    """Same gradient computed from the KJT alone. Returns (touched_rows, feat_roff, grad_rows)."""
+    grad_out = np.ascontiguousarray(grad_out, dtype=np.float32)
+    D = grad_out.shape[-1]
+    values, offsets = _i64(values), _i64(offsets)
+    N = values.shape[0]
+    touched = np.zeros(max(N, 1), dtype=np.int64)
+    feat_roff = np.zeros(F + 1, dtype=np.int64)
+    grad_rows = np.zeros((max(N, 1), D), dtype=np.float64)
+    rc = _lib.oracle_backward_kjt(C.c_int(F), C.c_int64(B), C.c_int(D), _p(grad_out, _f32p),
+                                  _p(values, _i64p), _p(offsets, _i64p), _p(touched, _i64p),
+                                  _p(feat_roff, _i64p), _p(grad_rows, _f64p))
+    _check(rc, "backward_kjt")
+    R = int(feat_roff[F])
+    return touched[:R].copy(), feat_roff, grad_rows[:R].copy()
+
+
+def rowwise_adagrad(grad_rows, w_rows, m_rows, lr: float, eps: float) -> Tuple[np.ndarray, np.ndarray]:
+    """Row-wise Adagrad on the touched rows: returns (w_new[R,D], m_new[R]) in float64."""
+    grad_rows = np.ascontiguousarray(grad_rows, dtype=np.float64)
+    w_rows = np.ascontiguousarray(w_rows, dtype=np.float64)
+    m_rows = np.ascontiguousarray(m_rows, dtype=np.float64)
+    R, D = grad_rows.shape
+    w_new = np.zeros((max(R, 1), D), dtype=np.float64)
+    m_new = np.zeros(max(R, 1), dtype=np.float64)
+    rc = _lib.oracle_rowwise_adagrad(C.c_int64(R), C.c_int(D), _p(grad_rows, _f64p),
+                                     _p(w_rows, _f64p), _p(m_rows, _f64p), C.c_double(lr),
+                                     C.c_double(eps), _p(w_new, _f64p), _p(m_new, _f64p))
+    _check(rc, "rowwise_adagrad")
+    return w_new[:R], m_new[:R]
+
+
+# ---- duplication model (Sec. 4.2 "Using IKJTs") --------------------------------------------
+def dedupe_len(l: float, B: float, S: float, d: float) -> float:
+    """Expected size of the values slice after deduplicating a feature."""
+    return l * B * (1.0 - (S - 1.0) / S * d)
+
+
+def dedupe_factor(l: float, B: float, S: float, d: float) -> float:
+    """Ratio of the original values slice length to the deduplicated one."""
+    return l * B / dedupe_len(l, B, S, d)
+
+
+def decode_ikjt(F: int, B: int, u_values, u_offsets, inverse, feat_uoff) -> List[List[List[int]]]:
+    """Rebuild the per-row lists an IKJT encodes (Sec. 6.2: same logical data as the KJT)."""
+    out = []
+    for f in range(F):
+        rows = []
+        for b in range(B):
+            u = int(feat_uoff[f]) + int(inverse[f * B + b])
+            rows.append([int(x) for x in u_values[int(u_offsets[u]):int(u_offsets[u + 1])]])
+        out.append(rows)
+    return out
