@@ -1,0 +1,166 @@
+/*
+ * recd.h — C ABI of the MI355X (gfx950) deduplicated-embedding hot path of RecD.
+ *
+ * The path (paper Sec. 4.2 "Tensor Encoding for Deduplication", Sec. 5 "RecD in Training"):
+ *   1. KJT -> IKJT        deduplicate identical per-sample lists of every sparse feature of a batch
+ *   2. pooled lookup      sum-pooled embedding-bag lookup on the unique lists only
+ *   3. expand             index_select of the pooled rows through the per-sample inverse index
+ *   4. backward           gradient of 3 and 2 (+ optional row-wise Adagrad on the touched rows)
+ *   5. KJT pooled lookup  the non-deduplicated comparison path
+ *
+ * General rules
+ *   - Every array argument marked "device" is a pointer into GPU memory owned by the caller and
+ *     valid on the context's device; "host" arguments are ordinary host memory read during the
+ *     call.  The library never allocates anything the caller sees and never frees caller memory.
+ *   - Calls enqueue kernels on the context's HIP stream and return without synchronising, except
+ *     where stated (host result requested, validation enabled).  Inputs are never modified;
+ *     embedding tables and optimizer state are modified only by the optimizer branch of
+ *     recd_backward_dedup.
+ *   - Every call returns a recd_status; nothing throws or aborts.  On failure
+ *     recd_last_error(ctx) holds a message.  F = 0, B = 0 and N = 0 are valid (no-op) sizes.
+ *   - Preconditions (offsets[0] = 0, offsets non-decreasing, offsets[F*B] = N, ids within the
+ *     table) are checked on the device only when RECD_OPT_VALIDATE is set (the call then
+ *     synchronises and returns RECD_EBOUNDS without running the operation); otherwise behaviour
+ *     for inputs that violate them is undefined.
+ *   - One context serves one stream; calls on one context must not overlap (they share its
+ *     workspace).  Use one context per stream.
+ *
+ * Data layout
+ *   KJT (Sec. 4.2):   values  int64 [N], feature-major (all rows of feature 0, then feature 1, ...)
+ *                     offsets int64 [F*B+1]; offsets[f*B+b] = start of row b of feature f in
+ *                     values; one trailing sentinel offsets[F*B] = N (the paper's offsets slice is
+ *                     the first F*B entries; it derives the last length from |values|).
+ *   IKJT (Sec. 4.2):  u_values  int64 [M]    unique lists, feature-major, within a feature in order of
+ *                                            first occurrence in the batch
+ *                     u_offsets int64 [U+1]  start of unique list u in u_values, sentinel u_offsets[U] = M
+ *                     inverse   int32 [F*B]  inverse[f*B+b] in [0, U_f): slot of row b among feature
+ *                                            f's unique lists (the paper's inverse_lookup)
+ *                     feat_uoff int64 [F+1]  prefix sum of U_f; unique list of (f,b) is
+ *                                            feat_uoff[f] + inverse[f*B+b]; feat_uoff[F] = U
+ *   Every feature is its own deduplication group.
+ *   Tables: row-major [rows_f, D]; pooled / expanded outputs: row-major [lists, D].
+ */
+#ifndef RECD_H
+#define RECD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct recd_ctx recd_ctx; /* opaque: stream, device workspace, error text */
+
+typedef enum {
+    RECD_OK = 0,
+    RECD_EINVAL = -1,    /* bad argument (null pointer, negative size, unsupported D or dtype)  */
+    RECD_ENOMEM = -2,    /* workspace allocation failed                                        */
+    RECD_EHIP = -3,      /* a HIP runtime call failed; message holds the HIP error string       */
+    RECD_EBOUNDS = -4,   /* validation found an id outside its table or malformed offsets        */
+    RECD_ECAPACITY = -5  /* a caller-provided capacity is too small for the result               */
+} recd_status;
+
+typedef enum { RECD_F32 = 0, RECD_F16 = 1, RECD_BF16 = 2 } recd_dtype;
+
+typedef enum {
+    RECD_OPT_VALIDATE = 1,  /* value != 0: check preconditions on the device before each operation  */
+    RECD_OPT_WEAK_HASH = 2  /* test hook, value != 0: the builder hashes a list to its length only,
+                               so that unequal lists collide constantly and only the exact list
+                               comparison keeps them apart.  Results must not change.            */
+} recd_option;
+
+/* Largest number of features per call and largest row size in bytes (D * element size). */
+#define RECD_MAX_FEATURES 1024
+#define RECD_MAX_ROW_BYTES 4096
+
+/* Create a context bound to `device` and to `hip_stream` (a hipStream_t passed as void*; NULL =
+ * the default stream).  `workspace_hint_bytes` pre-allocates the device workspace (0 = grow on
+ * demand; growth synchronises the stream and reallocates).  The context is owned by the caller
+ * and released with recd_destroy. */
+recd_status recd_create(recd_ctx **out, int device, void *hip_stream, size_t workspace_hint_bytes);
+recd_status recd_destroy(recd_ctx *ctx);
+recd_status recd_set_option(recd_ctx *ctx, recd_option opt, int64_t value);
+/* Message of the last failing call on this context ("" if none). Valid until the next call. */
+const char *recd_last_error(const recd_ctx *ctx);
+const char *recd_status_string(recd_status s);
+/* Upper bound of the workspace any call needs for these sizes (N = ids in the KJT). */
+recd_status recd_workspace_bytes(int F, int64_t B, int64_t N, int D, size_t *out_bytes);
+
+/* 1. KJT -> IKJT (Sec. 4.2 "InverseKeyedJaggedTensor": rows holding exactly the same list — same
+ *    length, same ids, same order — share one stored copy; inverse_lookup[i] points at the entry
+ *    of the deduplicated offsets for row i).  Duplicates are searched over the whole batch, per
+ *    feature.  Unique lists are numbered in order of first occurrence, which makes the result
+ *    canonical: independent of hashing and of thread scheduling.
+ *    values [N], offsets [F*B+1]: device, read-only.
+ *    u_values: device, capacity N.  u_offsets: device, capacity F*B+1.  inverse: device [F*B].
+ *    feat_uoff: device [F+1].  Entries of u_values / u_offsets beyond M / U+1 are left untouched.
+ *    host_U_M: optional host int64[2]; if non-NULL the call synchronises the stream and stores
+ *    U and M there. */
+recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t N,
+                            const int64_t *values, const int64_t *offsets,
+                            int64_t *u_values, int64_t *u_offsets, int32_t *inverse,
+                            int64_t *feat_uoff, int64_t *host_U_M);
+
+/* 2. Sum-pooled lookup on the unique lists (Sec. 5 "EMB Lookups", "Deduplicated Pooling"):
+ *    pooled[u,:] = sum over the ids j of unique list u of table_f[u_values[j],:], fp32 accumulation,
+ *    rounded once to out_dt.  An empty list pools to zero.
+ *    tables: HOST array of F device pointers, table f is [rows[f], D] of table_dt.
+ *    rows: HOST int64 [F] (used by validation only, may be NULL when validation is off).
+ *    u_values, u_offsets, feat_uoff: device (outputs of recd_build_ikjt).
+ *    max_lists: any upper bound of U known to the host (F*B always is); sizes nothing the caller
+ *    sees.  pooled: device [U, D] of out_dt, capacity max_lists rows.
+ *    D*sizeof(element) must be a multiple of 16 and at most RECD_MAX_ROW_BYTES for both dtypes.
+ *    out_dt must be table_dt or RECD_F32. */
+recd_status recd_pooled_lookup_unique(recd_ctx *ctx, int F, int D, recd_dtype table_dt,
+                                      recd_dtype out_dt, const void *const *tables,
+                                      const int64_t *rows, const int64_t *u_values,
+                                      const int64_t *u_offsets, const int64_t *feat_uoff,
+                                      int64_t max_lists, void *pooled);
+
+/* 3. Expand through the inverse index (Sec. 5 "Jagged Index Select", dense pooled case):
+ *    out[f,b,:] = pooled[feat_uoff[f] + inverse[f*B+b], :].  A pure copy (bit-exact).
+ *    pooled: device [U, D] of dt; out: device [F, B, D] of dt. */
+recd_status recd_expand_inverse(recd_ctx *ctx, int F, int64_t B, int D, recd_dtype dt,
+                                const void *pooled, const int64_t *feat_uoff,
+                                const int32_t *inverse, void *out);
+
+/* 4. Comparison path: the same pooled lookup over every row of the KJT, no deduplication
+ *    (Sec. 5 "EMB Lookups", the pre-RecD behaviour).  out: device [F, B, D] of out_dt.
+ *    The summation order of a list depends on the list alone, so out equals the result of calls
+ *    1-3 bit for bit. */
+recd_status recd_kjt_pooled_lookup(recd_ctx *ctx, int F, int64_t B, int D, recd_dtype table_dt,
+                                   recd_dtype out_dt, const void *const *tables,
+                                   const int64_t *rows, const int64_t *values,
+                                   const int64_t *offsets, void *out);
+
+/* 5. Backward of calls 3 and 2 (chain rule; Sec. 2.2 names the EMB update of the backward pass,
+ *    Sec. 6.2 "Accuracy" states that an IKJT carries the same logical data as the KJT):
+ *      g_u[u,:] = sum over rows b (ascending) with inverse[f*B+b] = u of grad_out[f,b,:]
+ *      G_f[r,:] = sum over the positions j (ascending) of feature f's unique ids with
+ *                 u_values[j] = r of g_u[list of j, :]
+ *    computed as stable radix sorts followed by segment sums in sorted order: no floating-point
+ *    atomics, bit-identical from run to run.
+ *    grad_out: device fp32 [F, B, D].  rows: HOST int64 [F] table sizes (bounds the sort key).
+ *    M_cap: host upper bound of M (N always is; the exact M avoids idle work).
+ *    touched_rows: device int64, capacity M_cap: per feature the ascending distinct ids.
+ *    feat_roff: device int64 [F+1] prefix sum of the per-feature distinct counts R_f.
+ *    grad_rows: device fp32 [R, D], capacity M_cap rows, aligned with touched_rows.
+ *    Optimizer (this build's reading, not in the paper): if tables != NULL, row-wise Adagrad is
+ *    applied once per touched row with the aggregated gradient:
+ *      m[r] += mean_d G[r,d]^2 ;  W[r,d] -= lr * G[r,d] / (sqrt(m[r]) + eps)
+ *    tables: HOST array of F device pointers to fp32 [rows_f, D], updated in place;
+ *    adagrad_state: HOST array of F device pointers to fp32 [rows_f], updated in place.
+ *    host_R: optional host int64[1]; if non-NULL the call synchronises and stores R. */
+recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int D, const float *grad_out,
+                                const int32_t *inverse, const int64_t *feat_uoff,
+                                const int64_t *u_values, const int64_t *u_offsets,
+                                const int64_t *rows, int64_t M_cap, int64_t *touched_rows,
+                                int64_t *feat_roff, float *grad_rows, void *const *tables,
+                                float *const *adagrad_state, float lr, float eps,
+                                int64_t *host_R);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RECD_H */

@@ -1,0 +1,614 @@
+// Backward of expand + pooled lookup on an IKJT, and row-wise Adagrad on the touched rows.
+//
+//   step A  g_u[u,:] = sum_{b : inverse[f,b] = u} grad_out[f,b,:]            (b ascending)
+//   step B  G_f[r,:] = sum_{j : u_values[j] = r} g_u[list of j,:]            (j ascending)
+// Each step is "group the contributions by destination, then sum every group in a fixed order":
+// a stable least-significant-digit radix sort of (destination key, source row) pairs puts equal
+// destinations next to each other with their sources still ascending, head flags + a scan number
+// the groups, and the segmented gather-sum kernel of the forward pass adds each group's rows.
+// There are no floating-point atomics, so two runs give bit-identical gradients.
+//
+// Radix sort pass (8-bit digit): per-tile digit histograms -> exclusive scan in (digit, tile) order
+// -> scatter.  Inside a tile the stable rank of a key among equal digits is found per wave with
+// eight ballots (which lanes hold my digit), per-(round, wave) digit counts in LDS and a short
+// serial prefix over the 32 (round, wave) cells.
+#include "recd_internal.h"
+
+namespace {
+
+constexpr int kSortThreads = 256;
+constexpr int kIPT = 8;                       // keys per thread in a tile
+constexpr int kTile = kSortThreads * kIPT;    // 2048 keys per tile
+constexpr int kRadix = 256;
+constexpr int kScanItems = 16;                // items per thread in the generic scan
+constexpr int kScanTile = 256 * kScanItems;
+
+// ---------------------------------------------------------------- generic exclusive scan (uint32)
+__device__ __forceinline__ uint32_t block_excl_scan_u32(uint32_t v, uint32_t &total)
+{
+    __shared__ uint32_t s_w[16];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    uint32_t inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        uint32_t x = __shfl_up(inc, d);
+        if (lane >= d)
+            inc += x;
+    }
+    __syncthreads();
+    if (lane == 63)
+        s_w[w] = inc;
+    __syncthreads();
+    uint32_t off = 0;
+    total = 0;
+    for (int i = 0; i < (int)(blockDim.x >> 6); i++) {
+        if (i < w)
+            off += s_w[i];
+        total += s_w[i];
+    }
+    return off + inc - v;
+}
+
+// n may live on the device (n_dev != nullptr) or be given directly
+__device__ __forceinline__ int64_t count_of(const int64_t *n_dev, int64_t n_host)
+{
+    return n_dev ? *n_dev : n_host;
+}
+
+__global__ __launch_bounds__(256) void k_scan_reduce(const uint32_t *__restrict__ data,
+                                                     const int64_t *n_dev, int64_t n_host,
+                                                     uint32_t *__restrict__ bsum)
+{
+    const int64_t n = count_of(n_dev, n_host);
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+    uint32_t s = 0;
+#pragma unroll
+    for (int k = 0; k < kScanItems; k++)
+        if (base + k < n)
+            s += data[base + k];
+    uint32_t total;
+    block_excl_scan_u32(s, total);
+    if (threadIdx.x == 0)
+        bsum[blockIdx.x] = total;
+}
+
+__global__ __launch_bounds__(1024) void k_scan_small(uint32_t *a, int64_t n)
+{
+    uint32_t carry = 0;
+    for (int64_t base = 0; base < n; base += 1024) {
+        const int64_t i = base + threadIdx.x;
+        const uint32_t v = i < n ? a[i] : 0;
+        uint32_t total;
+        const uint32_t e = block_excl_scan_u32(v, total);
+        if (i < n)
+            a[i] = carry + e;
+        carry += total;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_scan_apply(uint32_t *__restrict__ data, const int64_t *n_dev,
+                                                    int64_t n_host, const uint32_t *__restrict__ bsum)
+{
+    const int64_t n = count_of(n_dev, n_host);
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+    uint32_t v[kScanItems], s = 0;
+#pragma unroll
+    for (int k = 0; k < kScanItems; k++) {
+        v[k] = base + k < n ? data[base + k] : 0;
+        s += v[k];
+    }
+    uint32_t total;
+    uint32_t run = bsum[blockIdx.x] + block_excl_scan_u32(s, total);
+#pragma unroll
+    for (int k = 0; k < kScanItems; k++) {
+        if (base + k < n)
+            data[base + k] = run;
+        run += v[k];
+    }
+}
+
+// in-place exclusive scan of data[0..n), n <= n_cap (host bound that sizes the grid)
+recd_status scan_u32(recd_ctx *ctx, uint32_t *data, const int64_t *n_dev, int64_t n_cap,
+                     uint32_t *bsum)
+{
+    const int64_t nb = (n_cap + kScanTile - 1) / kScanTile;
+    if (nb == 0)
+        return RECD_OK;
+    hipStream_t st = ctx->stream;
+    hipLaunchKernelGGL(k_scan_reduce, dim3((unsigned)nb), dim3(256), 0, st, data, n_dev, n_cap, bsum);
+    hipLaunchKernelGGL(k_scan_small, dim3(1), dim3(1024), 0, st, bsum, nb);
+    hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)nb), dim3(256), 0, st, data, n_dev, n_cap, bsum);
+    RECD_HIP(ctx, hipGetLastError());
+    return RECD_OK;
+}
+
+// ---------------------------------------------------------------- stable LSD radix sort of pairs
+template <typename KeyT>
+__global__ __launch_bounds__(kSortThreads) void k_sort_hist(const KeyT *__restrict__ keys,
+                                                            const int64_t *n_dev, int64_t n_host,
+                                                            int shift, uint32_t *__restrict__ hist,
+                                                            int ntiles)
+{
+    __shared__ uint32_t s_h[kRadix];
+    s_h[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t n = count_of(n_dev, n_host);
+    const int64_t base = (int64_t)blockIdx.x * kTile;
+#pragma unroll
+    for (int k = 0; k < kIPT; k++) {
+        const int64_t i = base + k * kSortThreads + threadIdx.x;
+        if (i < n)
+            atomicAdd(&s_h[(uint32_t)(keys[i] >> shift) & (kRadix - 1)], 1u);
+    }
+    __syncthreads();
+    hist[(int64_t)threadIdx.x * ntiles + blockIdx.x] = s_h[threadIdx.x];
+}
+
+template <typename KeyT>
+__global__ __launch_bounds__(kSortThreads) void k_sort_scatter(
+    const KeyT *__restrict__ kin, const uint32_t *__restrict__ pin, KeyT *__restrict__ kout,
+    uint32_t *__restrict__ pout, const int64_t *n_dev, int64_t n_host, int shift,
+    const uint32_t *__restrict__ hist_scanned, int ntiles)
+{
+    constexpr int W = kSortThreads / 64;
+    __shared__ uint16_t s_cnt[kIPT][W][kRadix];
+    __shared__ uint32_t s_base[kRadix];
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t n = count_of(n_dev, n_host);
+    const int64_t base = (int64_t)blockIdx.x * kTile;
+    if (base >= n)
+        return;  // whole block: nothing in this tile
+    for (int i = tid; i < kIPT * W * kRadix; i += kSortThreads)
+        (&s_cnt[0][0][0])[i] = 0;
+    __syncthreads();
+
+    KeyT key[kIPT];
+    uint32_t rank[kIPT];
+    const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+#pragma unroll
+    for (int k = 0; k < kIPT; k++) {
+        const int64_t i = base + k * kSortThreads + tid;
+        const bool valid = i < n;
+        key[k] = valid ? kin[i] : (KeyT)0;
+        const uint32_t d = (uint32_t)(key[k] >> shift) & (kRadix - 1);
+        uint64_t mask = __ballot(valid);
+#pragma unroll
+        for (int bit = 0; bit < 8; bit++) {
+            const bool one = (d >> bit) & 1u;
+            const uint64_t bal = __ballot(one);
+            mask &= one ? bal : ~bal;
+        }
+        rank[k] = (uint32_t)__popcll(mask & lt_mask);
+        if (valid && rank[k] == 0)
+            s_cnt[k][w][d] = (uint16_t)__popcll(mask);
+    }
+    __syncthreads();
+    {
+        uint32_t run = 0;
+#pragma unroll
+        for (int k = 0; k < kIPT; k++)
+#pragma unroll
+            for (int ww = 0; ww < W; ww++) {
+                const uint32_t c = s_cnt[k][ww][tid];
+                s_cnt[k][ww][tid] = (uint16_t)run;
+                run += c;
+            }
+        s_base[tid] = hist_scanned[(int64_t)tid * ntiles + blockIdx.x];
+    }
+    __syncthreads();
+#pragma unroll
+    for (int k = 0; k < kIPT; k++) {
+        const int64_t i = base + k * kSortThreads + tid;
+        if (i < n) {
+            const uint32_t d = (uint32_t)(key[k] >> shift) & (kRadix - 1);
+            const int64_t dst = (int64_t)s_base[d] + s_cnt[k][w][d] + rank[k];
+            kout[dst] = key[k];
+            pout[dst] = pin[i];
+        }
+    }
+}
+
+// Sorts (keys, pay) by the low `bits` bits of the key; returns through *kres/*pres which of the two
+// buffer pairs holds the result.
+template <typename KeyT>
+recd_status radix_sort_pairs(recd_ctx *ctx, KeyT *k0, uint32_t *p0, KeyT *k1, uint32_t *p1,
+                             const int64_t *n_dev, int64_t n_cap, int bits, uint32_t *hist,
+                             uint32_t *bsum, KeyT **kres, uint32_t **pres)
+{
+    const int ntiles = (int)((n_cap + kTile - 1) / kTile);
+    hipStream_t st = ctx->stream;
+    KeyT *ka = k0, *kb = k1;
+    uint32_t *pa = p0, *pb = p1;
+    for (int shift = 0; shift < bits && ntiles > 0; shift += 8) {
+        hipLaunchKernelGGL((k_sort_hist<KeyT>), dim3(ntiles), dim3(kSortThreads), 0, st, ka, n_dev,
+                           n_cap, shift, hist, ntiles);
+        RECD_TRY(scan_u32(ctx, hist, nullptr, (int64_t)kRadix * ntiles, bsum));
+        hipLaunchKernelGGL((k_sort_scatter<KeyT>), dim3(ntiles), dim3(kSortThreads), 0, st, ka, pa, kb,
+                           pb, n_dev, n_cap, shift, hist, ntiles);
+        KeyT *tk = ka; ka = kb; kb = tk;
+        uint32_t *tp = pa; pa = pb; pb = tp;
+    }
+    RECD_HIP(ctx, hipGetLastError());
+    *kres = ka;
+    *pres = pa;
+    return RECD_OK;
+}
+
+// ---------------------------------------------------------------- keys
+// step A: destination = global unique-list index, source = row (f,b) of grad_out
+__global__ void k_keys_rows(const int32_t *__restrict__ inverse, const int64_t *__restrict__ feat_uoff,
+                            int64_t B, int64_t n_lists, uint32_t *__restrict__ keys,
+                            uint32_t *__restrict__ pay, int64_t *n_out)
+{
+    const int64_t l = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (l == 0)
+        *n_out = n_lists;
+    if (l < n_lists) {
+        keys[l] = (uint32_t)(feat_uoff[l / B] + inverse[l]);
+        pay[l] = (uint32_t)l;
+    }
+}
+
+// step B: destination = (feature, table row), source = unique list holding position j
+template <typename KeyT, int SG>
+__global__ __launch_bounds__(256) void k_keys_ids(const int64_t *__restrict__ u_values,
+                                                  const int64_t *__restrict__ u_offsets,
+                                                  const int64_t *__restrict__ feat_uoff, int F,
+                                                  int row_bits, int64_t lists_cap, int64_t M_cap,
+                                                  KeyT *__restrict__ keys, uint32_t *__restrict__ pay,
+                                                  int64_t *n_out)
+{
+    const int s = threadIdx.x % SG;
+    const int64_t u = (int64_t)blockIdx.x * (256 / SG) + threadIdx.x / SG;
+    const int64_t U = feat_uoff[F];
+    if (u == 0 && s == 0) {
+        // never write past the caller's capacity; n_out[1] tells the host that M_cap was too small
+        const int64_t M = u_offsets[U];
+        n_out[0] = M < M_cap ? M : M_cap;
+        n_out[1] = M > M_cap ? 1 : 0;
+    }
+    if (u >= U || u >= lists_cap)
+        return;
+    int lo = 0, hi = F;  // feature of u: feat_uoff[f] <= u < feat_uoff[f+1]
+    while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (feat_uoff[mid] <= u)
+            lo = mid;
+        else
+            hi = mid;
+    }
+    const KeyT fkey = (KeyT)lo << row_bits;
+    const int64_t j0 = u_offsets[u];
+    const int64_t j1 = u_offsets[u + 1] < M_cap ? u_offsets[u + 1] : M_cap;
+    for (int64_t j = j0 + s; j < j1; j += SG) {
+        keys[j] = fkey | (KeyT)u_values[j];
+        pay[j] = (uint32_t)u;
+    }
+}
+
+// ---------------------------------------------------------------- segments of equal keys
+template <typename KeyT>
+__global__ void k_heads(const KeyT *__restrict__ keys, const int64_t *n_dev, uint32_t *__restrict__ flag)
+{
+    const int64_t n = *n_dev;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x)
+        flag[i] = (i == 0 || keys[i] != keys[i - 1]) ? 1u : 0u;
+}
+
+// segidx = exclusive scan of the head flags.  Heads record where their segment starts; the last
+// element closes the list (seg_start[R] = n, list_off = {0, R}).  With row_bits >= 0 the key is
+// (feature, row): also emit the row ids and the per-feature prefix of distinct-row counts.
+template <typename KeyT>
+__global__ void k_segments(const KeyT *__restrict__ keys, const int64_t *n_dev,
+                           const uint32_t *__restrict__ segidx, int64_t *__restrict__ seg_start,
+                           int64_t *__restrict__ list_off, int row_bits, int F,
+                           int64_t *__restrict__ touched_rows, int64_t *__restrict__ feat_roff)
+{
+    const int64_t n = *n_dev;
+    if (n == 0) {
+        if (blockIdx.x == 0 && threadIdx.x == 0) {
+            seg_start[0] = 0;
+            list_off[0] = 0;
+            list_off[1] = 0;
+            if (row_bits >= 0)
+                for (int f = 0; f <= F; f++)
+                    feat_roff[f] = 0;
+        }
+        return;
+    }
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const bool head = i == 0 || keys[i] != keys[i - 1];
+        const int64_t sidx = segidx[i];  // for a head: its segment number; else that number + 1
+        if (head) {
+            seg_start[sidx] = i;
+            if (row_bits >= 0) {
+                touched_rows[sidx] = (int64_t)(keys[i] & (((KeyT)1 << row_bits) - 1));
+                const int f = (int)(keys[i] >> row_bits);
+                const int fprev = i == 0 ? -1 : (int)(keys[i - 1] >> row_bits);
+                for (int ff = fprev + 1; ff <= f; ff++)
+                    feat_roff[ff] = sidx;
+            }
+        }
+        if (i == n - 1) {
+            const int64_t R = sidx + (head ? 1 : 0);
+            seg_start[R] = n;
+            list_off[0] = 0;
+            list_off[1] = R;
+            if (row_bits >= 0) {
+                const int f = (int)(keys[i] >> row_bits);
+                for (int ff = f + 1; ff <= F; ff++)
+                    feat_roff[ff] = R;
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------- row-wise Adagrad
+// One 32-lane group per touched row k (rows of features [f0, f0+nf) only):
+//   m[r] += mean_d G[k,d]^2 ;  W[r,d] -= lr * G[k,d] / (sqrt(m[r]) + eps)
+struct OptPtrs {
+    float *w[RECD_F_PER_LAUNCH];
+    float *m[RECD_F_PER_LAUNCH];
+};
+
+__global__ __launch_bounds__(256) void k_adagrad(const float *__restrict__ grad_rows,
+                                                 const int64_t *__restrict__ touched_rows,
+                                                 const int64_t *__restrict__ feat_roff, int f0, int nf,
+                                                 int D, OptPtrs ptrs, float lr, float eps)
+{
+    constexpr int SG = 32;
+    const int s = threadIdx.x % SG;
+    const int64_t k0 = feat_roff[f0], k1 = feat_roff[f0 + nf];
+    const int vecs = D / 4;
+    for (int64_t k = k0 + (int64_t)blockIdx.x * (256 / SG) + threadIdx.x / SG; k < k1;
+         k += (int64_t)gridDim.x * (256 / SG)) {
+        int lo = f0, hi = f0 + nf;
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (feat_roff[mid] <= k)
+                lo = mid;
+            else
+                hi = mid;
+        }
+        const int64_t r = touched_rows[k];
+        const float4 *g = reinterpret_cast<const float4 *>(grad_rows + k * D);
+        float ss = 0.f;
+        for (int v = s; v < vecs; v += SG) {
+            const float4 x = g[v];
+            ss += x.x * x.x;
+            ss += x.y * x.y;
+            ss += x.z * x.z;
+            ss += x.w * x.w;
+        }
+#pragma unroll
+        for (int m = SG / 2; m > 0; m >>= 1)
+            ss += __shfl_xor(ss, m, SG);
+        float *mp = ptrs.m[lo - f0] + r;
+        const float mnew = *mp + ss / (float)D;
+        const float scale = lr / (sqrtf(mnew) + eps);
+        float4 *w = reinterpret_cast<float4 *>(ptrs.w[lo - f0] + r * D);
+        for (int v = s; v < vecs; v += SG) {
+            const float4 x = g[v];
+            float4 y = w[v];
+            y.x -= scale * x.x;
+            y.y -= scale * x.y;
+            y.z -= scale * x.z;
+            y.w -= scale * x.w;
+            w[v] = y;
+        }
+        // every lane has read *mp before any lane of the group overwrites it
+        __builtin_amdgcn_wave_barrier();
+        if (s == 0)
+            *mp = mnew;
+    }
+}
+
+__global__ void k_no_rows(int F, int64_t *feat_roff, int64_t *list_off)
+{
+    for (int f = threadIdx.x; f <= F; f += blockDim.x)
+        feat_roff[f] = 0;
+    if (threadIdx.x == 0) {
+        list_off[0] = 0;
+        list_off[1] = 0;
+    }
+}
+
+int bits_for(uint64_t max_value)
+{
+    int b = 1;
+    while (b < 64 && (max_value >> b) != 0)
+        b++;
+    return b;
+}
+
+struct BwdWs {
+    int64_t *n_dev, *list_off, *seg_start;
+    void *k0, *k1;
+    uint32_t *p0, *p1, *flag, *hist, *bsum;
+    float *g_u;
+    size_t bytes;
+};
+
+BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D)
+{
+    WsCarver c(base);
+    BwdWs w;
+    const int64_t n_max = n_lists > M_cap ? n_lists : M_cap;
+    const int64_t ntiles = (n_max + kTile - 1) / kTile;
+    const int64_t hist_n = (int64_t)kRadix * ntiles;
+    const int64_t scan_max = hist_n > n_max ? hist_n : n_max;
+    int64_t u_cap = M_cap + F < n_lists ? M_cap + F : n_lists;
+    w.n_dev = c.take<int64_t>(2);
+    w.list_off = c.take<int64_t>(2);
+    w.seg_start = c.take<int64_t>(n_max + 1);
+    w.k0 = c.take<uint64_t>(n_max);
+    w.k1 = c.take<uint64_t>(n_max);
+    w.p0 = c.take<uint32_t>(n_max);
+    w.p1 = c.take<uint32_t>(n_max);
+    w.flag = c.take<uint32_t>(n_max);
+    w.hist = c.take<uint32_t>(hist_n);
+    w.bsum = c.take<uint32_t>((scan_max + kScanTile - 1) / kScanTile + 1);
+    w.g_u = c.take<float>((size_t)u_cap * D);
+    w.bytes = c.off;
+    return w;
+}
+
+template <typename KeyT>
+recd_status group_and_sum(recd_ctx *ctx, const BwdWs &w, KeyT *k0, KeyT *k1, int64_t n_cap, int bits,
+                          int row_bits, int F, const void *table, int D, void *out,
+                          int64_t *touched_rows, int64_t *feat_roff)
+{
+    KeyT *ks;
+    uint32_t *ps;
+    RECD_TRY(radix_sort_pairs<KeyT>(ctx, k0, w.p0, k1, w.p1, w.n_dev, n_cap, bits, w.hist, w.bsum,
+                                    &ks, &ps));
+    hipStream_t st = ctx->stream;
+    int blocks = (int)((n_cap + 255) / 256 < 2048 ? (n_cap + 255) / 256 : 2048);
+    if (blocks < 1)
+        blocks = 1;
+    hipLaunchKernelGGL((k_heads<KeyT>), dim3(blocks), dim3(256), 0, st, ks, w.n_dev, w.flag);
+    RECD_TRY(scan_u32(ctx, w.flag, w.n_dev, n_cap, w.bsum));
+    hipLaunchKernelGGL((k_segments<KeyT>), dim3(blocks), dim3(256), 0, st, ks, w.n_dev, w.flag,
+                       w.seg_start, w.list_off, row_bits, F, touched_rows, feat_roff);
+    RECD_HIP(ctx, hipGetLastError());
+    SegSumArgs a{};
+    a.F = 1;
+    a.D = D;
+    a.table_dt = RECD_F32;
+    a.out_dt = RECD_F32;
+    a.tables.p[0] = table;
+    a.values = ps;
+    a.values_are_i32 = 1;
+    a.offsets = w.seg_start;
+    a.list_off = w.list_off;
+    a.out = out;
+    return recd_launch_segsum(ctx, a);
+}
+
+} // namespace
+
+size_t recd_backward_workspace(int F, int64_t B, int64_t M_cap, int D)
+{
+    return carve_bwd(nullptr, (int64_t)F * B, M_cap, F, D).bytes;
+}
+
+extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int D,
+                                           const float *grad_out, const int32_t *inverse,
+                                           const int64_t *feat_uoff, const int64_t *u_values,
+                                           const int64_t *u_offsets, const int64_t *rows,
+                                           int64_t M_cap, int64_t *touched_rows, int64_t *feat_roff,
+                                           float *grad_rows, void *const *tables,
+                                           float *const *adagrad_state, float lr, float eps,
+                                           int64_t *host_R)
+{
+    if (!ctx)
+        return RECD_EINVAL;
+    if (F < 0 || F > RECD_MAX_FEATURES || B < 0 || M_cap < 0)
+        return recd_fail(ctx, RECD_EINVAL, "bad sizes");
+    if (D <= 0 || D % 4 != 0 || (size_t)D * 4 > RECD_MAX_ROW_BYTES ||
+        (D * 4 / 16 > 64 && D * 4 / 16 != 128 && D * 4 / 16 != 256))
+        return recd_fail(ctx, RECD_EINVAL, "unsupported D=%d", D);
+    const int64_t n_lists = (int64_t)F * B;
+    if (n_lists >= (int64_t)1 << 31 || M_cap >= (int64_t)1 << 31)
+        return recd_fail(ctx, RECD_EINVAL, "F*B and M_cap must stay below 2^31");
+    if (!feat_roff || !feat_uoff || !u_offsets || (F > 0 && !rows))
+        return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
+    if (n_lists > 0 && (!grad_out || !inverse))
+        return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
+    if (M_cap > 0 && (!u_values || !touched_rows || !grad_rows))
+        return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
+    if ((tables == nullptr) != (adagrad_state == nullptr))
+        return recd_fail(ctx, RECD_EINVAL, "tables and adagrad_state must be given together");
+    int64_t max_rows = 1;
+    for (int f = 0; f < F; f++) {
+        if (rows[f] <= 0)
+            return recd_fail(ctx, RECD_EINVAL, "rows[%d] <= 0", f);
+        if (rows[f] > max_rows)
+            max_rows = rows[f];
+        if (tables && (!tables[f] || !adagrad_state[f]))
+            return recd_fail(ctx, RECD_EINVAL, "tables[%d] or adagrad_state[%d] is null", f, f);
+    }
+    RECD_HIP(ctx, hipSetDevice(ctx->device));
+    RECD_TRY(recd_reserve(ctx, recd_backward_workspace(F, B, M_cap, D)));
+    const BwdWs w = carve_bwd(ctx->ws, n_lists, M_cap, F, D);
+    hipStream_t st = ctx->stream;
+
+    if (n_lists == 0 || M_cap == 0) {
+        // no id anywhere: no row is touched
+        hipLaunchKernelGGL(k_no_rows, dim3(1), dim3(64), 0, st, F, feat_roff, w.list_off);
+        RECD_HIP(ctx, hipGetLastError());
+        if (host_R) {
+            RECD_HIP(ctx, hipStreamSynchronize(st));
+            host_R[0] = 0;
+        }
+        return RECD_OK;
+    }
+
+    // ---- step A: group rows (f,b) by unique list, sum grad_out rows into g_u --------------------
+    {
+        uint32_t *k0 = static_cast<uint32_t *>(w.k0), *k1 = static_cast<uint32_t *>(w.k1);
+        hipLaunchKernelGGL(k_keys_rows, dim3((unsigned)((n_lists + 255) / 256)), dim3(256), 0, st,
+                           inverse, feat_uoff, B, n_lists, k0, w.p0, w.n_dev);
+        RECD_TRY(group_and_sum<uint32_t>(ctx, w, k0, k1, n_lists, bits_for((uint64_t)n_lists), -1, F,
+                                         grad_out, D, w.g_u, nullptr, nullptr));
+    }
+    // ---- step B: group unique-id positions by (feature, row), sum g_u rows into grad_rows --------
+    {
+        const int row_bits = bits_for((uint64_t)(max_rows - 1));
+        const int bits = row_bits + bits_for((uint64_t)(F > 1 ? F - 1 : 1));
+        constexpr int SG = 16;
+        const unsigned kb = (unsigned)((n_lists + (256 / SG) - 1) / (256 / SG));
+        if (bits <= 32) {
+            uint32_t *k0 = static_cast<uint32_t *>(w.k0), *k1 = static_cast<uint32_t *>(w.k1);
+            hipLaunchKernelGGL((k_keys_ids<uint32_t, SG>), dim3(kb), dim3(256), 0, st, u_values,
+                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.p0, w.n_dev);
+            RECD_TRY(group_and_sum<uint32_t>(ctx, w, k0, k1, M_cap, bits, row_bits, F, w.g_u, D,
+                                             grad_rows, touched_rows, feat_roff));
+        } else {
+            uint64_t *k0 = static_cast<uint64_t *>(w.k0), *k1 = static_cast<uint64_t *>(w.k1);
+            hipLaunchKernelGGL((k_keys_ids<uint64_t, SG>), dim3(kb), dim3(256), 0, st, u_values,
+                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.p0, w.n_dev);
+            RECD_TRY(group_and_sum<uint64_t>(ctx, w, k0, k1, M_cap, bits, row_bits, F, w.g_u, D,
+                                             grad_rows, touched_rows, feat_roff));
+        }
+    }
+    // ---- optimizer -------------------------------------------------------------------------------
+    if (tables) {
+        for (int f0 = 0; f0 < F; f0 += RECD_F_PER_LAUNCH) {
+            OptPtrs ptrs;
+            const int nf = F - f0 < RECD_F_PER_LAUNCH ? F - f0 : RECD_F_PER_LAUNCH;
+            for (int f = 0; f < nf; f++) {
+                ptrs.w[f] = static_cast<float *>(tables[f0 + f]);
+                ptrs.m[f] = adagrad_state[f0 + f];
+            }
+            hipLaunchKernelGGL(k_adagrad, dim3(ctx->num_cu * 8), dim3(256), 0, st, grad_rows,
+                               touched_rows, feat_roff, f0, nf, D, ptrs, lr, eps);
+        }
+        RECD_HIP(ctx, hipGetLastError());
+    }
+    if (host_R) {
+        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, w.list_off + 1, sizeof(int64_t),
+                                     hipMemcpyDeviceToHost, st));
+        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned + 1, w.n_dev + 1, sizeof(int64_t),
+                                     hipMemcpyDeviceToHost, st));
+        RECD_HIP(ctx, hipStreamSynchronize(st));
+        host_R[0] = ctx->host_pinned[0];
+        if (ctx->host_pinned[1])
+            return recd_fail(ctx, RECD_ECAPACITY, "M_cap=%lld is smaller than M", (long long)M_cap);
+    }
+    return RECD_OK;
+}
+
+size_t recd_build_workspace(int F, int64_t B);
+
+extern "C" recd_status recd_workspace_bytes(int F, int64_t B, int64_t N, int D, size_t *out_bytes)
+{
+    if (!out_bytes || F < 0 || B < 0 || N < 0 || D <= 0)
+        return RECD_EINVAL;
+    const size_t a = recd_build_workspace(F, B);
+    const size_t b = recd_backward_workspace(F, B, N, D);
+    *out_bytes = (a > b ? a : b) + 4096;
+    return RECD_OK;
+}

@@ -1,0 +1,348 @@
+// KJT -> IKJT builder (paper Sec. 4.2): which rows of a feature hold exactly the same list?
+//
+// Steps, all on the device, no host round trip:
+//   hash+insert  a group of SG lanes per list: 64-bit hash of the list (position-salted sum of mixed
+//                ids, so lanes can hash strided pieces and add), then open addressing into a
+//                per-feature table whose slots hold (hash tag, sample index).  A slot belongs to one
+//                list *content*: a newcomer whose tag matches compares its list element by element
+//                with the slot's current sample and, if equal, lowers the slot's sample index with
+//                an atomic min; if not, it probes on.  Hash collisions therefore never merge lists.
+//   rep+flags    rep[f,b] = final sample index of the slot = smallest b' with the same list;
+//                first[f,b] = (rep == b); per-block sums of (first, first*len).
+//   scan         exclusive scan of those pairs over all F*B lists in (f,b) order: the unique-list
+//                number and the position of its ids in u_values, both in first-occurrence order.
+//   emit         inverse[f,b] = number[rep] - number[f,0]; first occurrences copy their ids.
+// The atomic min makes the result independent of insertion order: integer outputs are canonical.
+#include "recd_internal.h"
+
+namespace {
+
+constexpr uint64_t kEmpty = ~0ull;
+constexpr int kScanBlock = 1024;
+
+__device__ __forceinline__ uint64_t mix64(uint64_t x)
+{
+    x ^= x >> 30;
+    x *= 0xbf58476d1ce4e5b9ull;
+    x ^= x >> 27;
+    x *= 0x94d049bb133111ebull;
+    x ^= x >> 31;
+    return x;
+}
+
+__global__ void k_fill_u64(uint64_t *p, int64_t n, uint64_t v)
+{
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+
+template <int SG>
+__global__ __launch_bounds__(256) void k_hash_insert(const int64_t *__restrict__ values,
+                                                     const int64_t *__restrict__ offsets, int64_t B,
+                                                     int64_t n_lists, uint64_t *table,
+                                                     uint32_t cap_mask, int32_t *__restrict__ slot_of,
+                                                     int weak_hash)
+{
+    const int s = threadIdx.x % SG;
+    const int64_t l = (int64_t)blockIdx.x * (256 / SG) + threadIdx.x / SG;
+    if (l >= n_lists)
+        return;  // whole lane group leaves together
+    const int64_t f = l / B;
+    const int64_t b = l - f * B;
+    const int64_t start = offsets[l];
+    const int64_t len = offsets[l + 1] - start;
+
+    uint64_t h = 0;
+    for (int64_t t = s; t < len; t += SG)
+        h += mix64((uint64_t)values[start + t] + (uint64_t)(t + 1) * 0x9e3779b97f4a7c15ull);
+#pragma unroll
+    for (int m = SG / 2; m > 0; m >>= 1)
+        h += __shfl_xor((unsigned long long)h, m, SG);
+    h = mix64(h ^ ((uint64_t)len * 0xd6e8feb86659fd93ull + 1ull));
+    if (weak_hash)
+        h = (uint64_t)len;  // test hook: only the exact comparison separates lists
+
+    const uint64_t tag = h >> 32;
+    const uint64_t mine = (tag << 32) | (uint64_t)b;
+    uint64_t *tab = table + (uint64_t)f * ((uint64_t)cap_mask + 1);
+    uint32_t slot = (uint32_t)h & cap_mask;
+    // The table has at least 2*B slots per feature, so an empty slot or the list's own class is met.
+    for (;;) {
+        unsigned long long old = 0;
+        if (s == 0)
+            old = atomicCAS(reinterpret_cast<unsigned long long *>(&tab[slot]), kEmpty, mine);
+        old = __shfl(old, 0, SG);
+        if (old == kEmpty)
+            break;
+        if ((old >> 32) == tag) {
+            const int64_t ol = f * B + (int64_t)(old & 0xffffffffull);
+            const int64_t ostart = offsets[ol];
+            int eq = (offsets[ol + 1] - ostart) == len;
+            if (eq)
+                for (int64_t t = s; t < len; t += SG)
+                    if (values[start + t] != values[ostart + t]) {
+                        eq = 0;
+                        break;
+                    }
+#pragma unroll
+            for (int m = SG / 2; m > 0; m >>= 1)
+                eq &= __shfl_xor(eq, m, SG);
+            if (eq) {
+                if (s == 0)
+                    atomicMin(reinterpret_cast<unsigned long long *>(&tab[slot]), mine);
+                break;
+            }
+        }
+        slot = (slot + 1) & cap_mask;
+    }
+    if (s == 0)
+        slot_of[l] = (int32_t)slot;
+}
+
+// exclusive scan of a pair of int64 over a block of kScanBlock threads; totals returned to all
+__device__ __forceinline__ void block_scan2(int64_t a, int64_t b, int64_t &ea, int64_t &eb,
+                                            int64_t &ta, int64_t &tb)
+{
+    __shared__ int64_t s_a[kScanBlock / 64], s_b[kScanBlock / 64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    int64_t ia = a, ib = b;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        int64_t xa = __shfl_up(ia, d), xb = __shfl_up(ib, d);
+        if (lane >= d) {
+            ia += xa;
+            ib += xb;
+        }
+    }
+    __syncthreads();  // protect s_a/s_b against the previous use
+    if (lane == 63) {
+        s_a[w] = ia;
+        s_b[w] = ib;
+    }
+    __syncthreads();
+    int64_t oa = 0, ob = 0;
+    ta = 0;
+    tb = 0;
+    for (int i = 0; i < (int)(blockDim.x >> 6); i++) {
+        if (i < w) {
+            oa += s_a[i];
+            ob += s_b[i];
+        }
+        ta += s_a[i];
+        tb += s_b[i];
+    }
+    ea = oa + ia - a;
+    eb = ob + ib - b;
+}
+
+__global__ __launch_bounds__(kScanBlock) void k_rep_flags(const int64_t *__restrict__ offsets,
+                                                          int64_t B, int64_t n_lists,
+                                                          const uint64_t *__restrict__ table,
+                                                          uint32_t cap_mask,
+                                                          const int32_t *__restrict__ slot_of,
+                                                          int32_t *__restrict__ rep,
+                                                          int64_t *__restrict__ bs_cnt,
+                                                          int64_t *__restrict__ bs_len)
+{
+    const int64_t l = (int64_t)blockIdx.x * kScanBlock + threadIdx.x;
+    int64_t first = 0, flen = 0;
+    if (l < n_lists) {
+        const int64_t f = l / B, b = l - f * B;
+        const uint64_t e = table[(uint64_t)f * ((uint64_t)cap_mask + 1) + (uint32_t)slot_of[l]];
+        const int32_t r = (int32_t)(e & 0xffffffffull);
+        rep[l] = r;
+        if (r == b) {
+            first = 1;
+            flen = offsets[l + 1] - offsets[l];
+        }
+    }
+    int64_t ea, eb, ta, tb;
+    block_scan2(first, flen, ea, eb, ta, tb);
+    if (threadIdx.x == 0) {
+        bs_cnt[blockIdx.x] = ta;
+        bs_len[blockIdx.x] = tb;
+    }
+}
+
+// in-place exclusive scan of two int64 arrays of n entries by one block
+__global__ __launch_bounds__(kScanBlock) void k_scan_pairs(int64_t *a, int64_t *b, int64_t n)
+{
+    int64_t ca = 0, cb = 0;
+    for (int64_t base = 0; base < n; base += kScanBlock) {
+        const int64_t i = base + threadIdx.x;
+        const int64_t va = i < n ? a[i] : 0, vb = i < n ? b[i] : 0;
+        int64_t ea, eb, ta, tb;
+        block_scan2(va, vb, ea, eb, ta, tb);
+        if (i < n) {
+            a[i] = ca + ea;
+            b[i] = cb + eb;
+        }
+        ca += ta;
+        cb += tb;
+    }
+}
+
+__global__ __launch_bounds__(kScanBlock) void k_number(const int64_t *__restrict__ offsets, int64_t B,
+                                                       int64_t n_lists, int F,
+                                                       const int32_t *__restrict__ rep,
+                                                       const int64_t *__restrict__ bs_cnt,
+                                                       const int64_t *__restrict__ bs_len,
+                                                       int32_t *__restrict__ number,
+                                                       int64_t *__restrict__ u_offsets,
+                                                       int64_t *__restrict__ feat_uoff,
+                                                       int64_t *__restrict__ counts)
+{
+    const int64_t l = (int64_t)blockIdx.x * kScanBlock + threadIdx.x;
+    int64_t first = 0, flen = 0, b = -1, f = 0;
+    if (l < n_lists) {
+        f = l / B;
+        b = l - f * B;
+        if (rep[l] == b) {
+            first = 1;
+            flen = offsets[l + 1] - offsets[l];
+        }
+    }
+    int64_t ea, eb, ta, tb;
+    block_scan2(first, flen, ea, eb, ta, tb);
+    if (l < n_lists) {
+        const int64_t num = bs_cnt[blockIdx.x] + ea;  // unique lists before (f,b), all features
+        const int64_t pos = bs_len[blockIdx.x] + eb;  // their ids
+        number[l] = (int32_t)num;
+        if (first)
+            u_offsets[num] = pos;
+        if (b == 0)
+            feat_uoff[f] = num;
+        if (l == n_lists - 1) {
+            const int64_t U = num + first, M = pos + flen;
+            u_offsets[U] = M;
+            feat_uoff[F] = U;
+            counts[0] = U;
+            counts[1] = M;
+        }
+    }
+}
+
+template <int SG>
+__global__ __launch_bounds__(256) void k_emit(const int64_t *__restrict__ values,
+                                              const int64_t *__restrict__ offsets, int64_t B,
+                                              int64_t n_lists, const int32_t *__restrict__ rep,
+                                              const int32_t *__restrict__ number,
+                                              const int64_t *__restrict__ u_offsets,
+                                              int64_t *__restrict__ u_values,
+                                              int32_t *__restrict__ inverse)
+{
+    const int s = threadIdx.x % SG;
+    const int64_t l = (int64_t)blockIdx.x * (256 / SG) + threadIdx.x / SG;
+    if (l >= n_lists)
+        return;
+    const int64_t f = l / B, b = l - f * B;
+    const int64_t r = rep[l];
+    if (s == 0)
+        inverse[l] = number[f * B + r] - number[f * B];
+    if (r == b) {
+        const int64_t start = offsets[l], len = offsets[l + 1] - start;
+        const int64_t dst = u_offsets[number[l]];
+        for (int64_t t = s; t < len; t += SG)
+            u_values[dst + t] = values[start + t];
+    }
+}
+
+__global__ void k_empty_ikjt(int F, int64_t *u_offsets, int64_t *feat_uoff, int64_t *counts)
+{
+    for (int f = threadIdx.x; f <= F; f += blockDim.x)
+        feat_uoff[f] = 0;
+    if (threadIdx.x == 0) {
+        u_offsets[0] = 0;
+        counts[0] = 0;
+        counts[1] = 0;
+    }
+}
+
+uint64_t table_cap(int64_t B)
+{
+    uint64_t cap = 64;
+    while (cap < 2 * (uint64_t)B)
+        cap <<= 1;
+    return cap;
+}
+
+} // namespace
+
+size_t recd_build_workspace(int F, int64_t B)
+{
+    WsCarver c(nullptr);
+    const int64_t n_lists = (int64_t)F * B;
+    const int64_t nblk = (n_lists + kScanBlock - 1) / kScanBlock;
+    c.take<int64_t>(2);
+    c.take<uint64_t>((size_t)F * table_cap(B));
+    c.take<int32_t>(n_lists);
+    c.take<int32_t>(n_lists);
+    c.take<int32_t>(n_lists);
+    c.take<int64_t>(nblk + 1);
+    c.take<int64_t>(nblk + 1);
+    return c.off;
+}
+
+recd_status recd_validate_kjt_offsets(recd_ctx *ctx, int F, int64_t B, int64_t N, const int64_t *offsets);
+
+extern "C" recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t N,
+                                       const int64_t *values, const int64_t *offsets,
+                                       int64_t *u_values, int64_t *u_offsets, int32_t *inverse,
+                                       int64_t *feat_uoff, int64_t *host_U_M)
+{
+    if (!ctx)
+        return RECD_EINVAL;
+    if (F < 0 || F > RECD_MAX_FEATURES || B < 0 || N < 0)
+        return recd_fail(ctx, RECD_EINVAL, "bad sizes F=%d B=%lld N=%lld", F, (long long)B, (long long)N);
+    const int64_t n_lists = (int64_t)F * B;
+    if (n_lists >= (int64_t)1 << 31 || B >= (int64_t)1 << 30)
+        return recd_fail(ctx, RECD_EINVAL, "F*B must stay below 2^31");
+    if (!u_offsets || !feat_uoff || (n_lists > 0 && (!offsets || !inverse)) ||
+        (N > 0 && (!values || !u_values)))
+        return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
+    RECD_HIP(ctx, hipSetDevice(ctx->device));
+    if (ctx->validate && n_lists > 0)
+        RECD_TRY(recd_validate_kjt_offsets(ctx, F, B, N, offsets));
+
+    RECD_TRY(recd_reserve(ctx, recd_build_workspace(F, B)));
+    WsCarver c(ctx->ws);
+    const int64_t nblk = (n_lists + kScanBlock - 1) / kScanBlock;
+    const uint64_t cap = table_cap(B);
+    int64_t *counts = c.take<int64_t>(2);
+    uint64_t *table = c.take<uint64_t>((size_t)F * cap);
+    int32_t *slot_of = c.take<int32_t>(n_lists);
+    int32_t *rep = c.take<int32_t>(n_lists);
+    int32_t *number = c.take<int32_t>(n_lists);
+    int64_t *bs_cnt = c.take<int64_t>(nblk + 1);
+    int64_t *bs_len = c.take<int64_t>(nblk + 1);
+    hipStream_t st = ctx->stream;
+
+    if (n_lists == 0) {
+        hipLaunchKernelGGL(k_empty_ikjt, dim3(1), dim3(256), 0, st, F, u_offsets, feat_uoff, counts);
+    } else {
+        constexpr int SG = 16;
+        const int64_t tab_n = (int64_t)F * (int64_t)cap;
+        int fill_blocks = (int)((tab_n + 1023) / 1024 < 4096 ? (tab_n + 1023) / 1024 : 4096);
+        hipLaunchKernelGGL(k_fill_u64, dim3(fill_blocks), dim3(256), 0, st, table, tab_n, kEmpty);
+        const int64_t gblocks = (n_lists + (256 / SG) - 1) / (256 / SG);
+        hipLaunchKernelGGL((k_hash_insert<SG>), dim3((unsigned)gblocks), dim3(256), 0, st, values,
+                           offsets, B, n_lists, table, (uint32_t)(cap - 1), slot_of, ctx->weak_hash);
+        hipLaunchKernelGGL(k_rep_flags, dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets, B,
+                           n_lists, table, (uint32_t)(cap - 1), slot_of, rep, bs_cnt, bs_len);
+        hipLaunchKernelGGL(k_scan_pairs, dim3(1), dim3(kScanBlock), 0, st, bs_cnt, bs_len, nblk);
+        hipLaunchKernelGGL(k_number, dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets, B, n_lists,
+                           F, rep, bs_cnt, bs_len, number, u_offsets, feat_uoff, counts);
+        hipLaunchKernelGGL((k_emit<SG>), dim3((unsigned)gblocks), dim3(256), 0, st, values, offsets, B,
+                           n_lists, rep, number, u_offsets, u_values, inverse);
+    }
+    RECD_HIP(ctx, hipGetLastError());
+    if (host_U_M) {
+        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, counts, 2 * sizeof(int64_t),
+                                     hipMemcpyDeviceToHost, st));
+        RECD_HIP(ctx, hipStreamSynchronize(st));
+        host_U_M[0] = ctx->host_pinned[0];
+        host_U_M[1] = ctx->host_pinned[1];
+    }
+    return RECD_OK;
+}

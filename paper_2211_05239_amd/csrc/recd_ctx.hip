@@ -1,0 +1,123 @@
+// Context, workspace and status plumbing of librecd.
+#include <stdarg.h>
+
+#include "recd_internal.h"
+
+recd_status recd_fail(recd_ctx *ctx, recd_status s, const char *fmt, ...)
+{
+    if (ctx) {
+        char buf[512];
+        va_list ap;
+        va_start(ap, fmt);
+        vsnprintf(buf, sizeof buf, fmt, ap);
+        va_end(ap);
+        ctx->err = buf;
+    }
+    return s;
+}
+
+recd_status recd_reserve(recd_ctx *ctx, size_t bytes)
+{
+    if (bytes <= ctx->ws_bytes)
+        return RECD_OK;
+    // Growing: earlier kernels may still use the old block.
+    RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->ws) {
+        RECD_HIP(ctx, hipFree(ctx->ws));
+        ctx->ws = nullptr;
+        ctx->ws_bytes = 0;
+    }
+    size_t want = bytes + bytes / 4 + (1u << 20);
+    void *p = nullptr;
+    if (hipMalloc(&p, want) != hipSuccess) {
+        (void)hipGetLastError();
+        return recd_fail(ctx, RECD_ENOMEM, "workspace allocation of %zu bytes failed", want);
+    }
+    ctx->ws = static_cast<char *>(p);
+    ctx->ws_bytes = want;
+    return RECD_OK;
+}
+
+extern "C" {
+
+const char *recd_status_string(recd_status s)
+{
+    switch (s) {
+    case RECD_OK: return "RECD_OK";
+    case RECD_EINVAL: return "RECD_EINVAL";
+    case RECD_ENOMEM: return "RECD_ENOMEM";
+    case RECD_EHIP: return "RECD_EHIP";
+    case RECD_EBOUNDS: return "RECD_EBOUNDS";
+    case RECD_ECAPACITY: return "RECD_ECAPACITY";
+    }
+    return "RECD_UNKNOWN";
+}
+
+recd_status recd_create(recd_ctx **out, int device, void *hip_stream, size_t workspace_hint_bytes)
+{
+    if (!out || device < 0)
+        return RECD_EINVAL;
+    *out = nullptr;
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || device >= ndev) {
+        (void)hipGetLastError();
+        return RECD_EHIP;
+    }
+    recd_ctx *ctx = new (std::nothrow) recd_ctx();
+    if (!ctx)
+        return RECD_ENOMEM;
+    ctx->device = device;
+    ctx->stream = static_cast<hipStream_t>(hip_stream);
+    bool ok = hipSetDevice(device) == hipSuccess;
+    hipDeviceProp_t prop;
+    if (ok && hipGetDeviceProperties(&prop, device) == hipSuccess && prop.multiProcessorCount > 0)
+        ctx->num_cu = prop.multiProcessorCount;
+    void *p = nullptr;
+    ok = ok && hipHostMalloc(&p, 8 * sizeof(int64_t), hipHostMallocDefault) == hipSuccess;
+    ctx->host_pinned = static_cast<int64_t *>(p);
+    p = nullptr;
+    ok = ok && hipMalloc(&p, 64 * sizeof(uint32_t)) == hipSuccess;
+    ctx->queue_ctr = static_cast<uint32_t *>(p);
+    ok = ok && hipMemset(ctx->queue_ctr, 0, 64 * sizeof(uint32_t)) == hipSuccess;
+    ok = ok && hipDeviceSynchronize() == hipSuccess;
+    if (ok && workspace_hint_bytes)
+        ok = recd_reserve(ctx, workspace_hint_bytes) == RECD_OK;
+    if (!ok) {
+        (void)hipGetLastError();
+        recd_destroy(ctx);
+        return RECD_EHIP;
+    }
+    *out = ctx;
+    return RECD_OK;
+}
+
+recd_status recd_destroy(recd_ctx *ctx)
+{
+    if (!ctx)
+        return RECD_OK;
+    (void)hipSetDevice(ctx->device);
+    (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->ws)
+        (void)hipFree(ctx->ws);
+    if (ctx->queue_ctr)
+        (void)hipFree(ctx->queue_ctr);
+    if (ctx->host_pinned)
+        (void)hipHostFree(ctx->host_pinned);
+    delete ctx;
+    return RECD_OK;
+}
+
+recd_status recd_set_option(recd_ctx *ctx, recd_option opt, int64_t value)
+{
+    if (!ctx)
+        return RECD_EINVAL;
+    switch (opt) {
+    case RECD_OPT_VALIDATE: ctx->validate = value != 0; return RECD_OK;
+    case RECD_OPT_WEAK_HASH: ctx->weak_hash = value != 0; return RECD_OK;
+    }
+    return recd_fail(ctx, RECD_EINVAL, "unknown option %d", (int)opt);
+}
+
+const char *recd_last_error(const recd_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+} // extern "C"

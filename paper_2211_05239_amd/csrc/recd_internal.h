@@ -1,0 +1,78 @@
+// Internal declarations shared by the translation units of librecd (not part of the C ABI).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stdio.h>
+#include <string>
+
+#include "recd.h"
+
+struct recd_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    char *ws = nullptr;          // device workspace
+    size_t ws_bytes = 0;
+    int64_t *host_pinned = nullptr;  // 8 x int64 pinned staging for scalar results
+    uint32_t *queue_ctr = nullptr;   // device: 16 x uint32 work-queue counters, zero between kernels
+    int validate = 0;
+    int weak_hash = 0;
+    int num_cu = 256;
+    std::string err;
+};
+
+recd_status recd_fail(recd_ctx *ctx, recd_status s, const char *fmt, ...);
+recd_status recd_reserve(recd_ctx *ctx, size_t bytes);
+
+#define RECD_HIP(ctx, call)                                                                   \
+    do {                                                                                      \
+        hipError_t e_ = (call);                                                               \
+        if (e_ != hipSuccess)                                                                 \
+            return recd_fail((ctx), RECD_EHIP, "%s failed: %s", #call, hipGetErrorString(e_)); \
+    } while (0)
+
+#define RECD_TRY(expr)            \
+    do {                          \
+        recd_status s_ = (expr);  \
+        if (s_ != RECD_OK)        \
+            return s_;            \
+    } while (0)
+
+// Bump allocator over the context workspace (256-byte aligned pieces).
+struct WsCarver {
+    char *base;
+    size_t off = 0;
+    explicit WsCarver(char *b) : base(b) {}
+    template <typename T> T *take(size_t count)
+    {
+        size_t bytes = (count * sizeof(T) + 255) & ~size_t(255);
+        T *p = base ? reinterpret_cast<T *>(base + off) : nullptr;
+        off += bytes;
+        return p;
+    }
+};
+
+static inline size_t elem_size(recd_dtype dt) { return dt == RECD_F32 ? 4 : 2; }
+
+// Tables of up to this many features travel to a kernel by value.
+#define RECD_F_PER_LAUNCH 128
+struct TablePtrs {
+    const void *p[RECD_F_PER_LAUNCH];
+};
+
+// ---- cross-file entry points (host side launchers) -------------------------------------------
+// Exclusive scan of n int64 pairs is private to each file; the segmented gather-sum is shared.
+struct SegSumArgs {
+    int F;                    // features in this launch (<= RECD_F_PER_LAUNCH)
+    int D;
+    recd_dtype table_dt, out_dt;
+    TablePtrs tables;
+    const void *values;       // int64 or int32 ids
+    int values_are_i32;
+    const int64_t *offsets;   // list l spans offsets[l]..offsets[l+1]
+    const int64_t *list_off;  // device [F+1] or nullptr -> list_off[f] = f * lists_per_feature
+    int64_t lists_per_feature;
+    int64_t list_base;        // added to every list index (feature chunking of the KJT path)
+    void *out;                // [lists, D]
+};
+recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a);

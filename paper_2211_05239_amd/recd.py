@@ -1,0 +1,163 @@
+"""Thin ctypes binding of librecd (the HIP library behind include/recd.h).
+
+Argument marshalling only: every step of the path runs in the library's kernels.  torch is used
+for device memory (tensors own the buffers) and for the stream handle.  There is no CPU fallback:
+importing this module raises if the library has not been built.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librecd.so")
+
+if not os.path.exists(LIB_PATH):
+    raise ImportError(
+        f"{LIB_PATH} is missing: build it with `python -m paper_2211_05239_amd.build` "
+        "(hipcc, gfx950). There is no fallback path.")
+
+_lib = C.CDLL(LIB_PATH)
+
+RECD_OK = 0
+RECD_EINVAL, RECD_ENOMEM, RECD_EHIP, RECD_EBOUNDS, RECD_ECAPACITY = -1, -2, -3, -4, -5
+RECD_F32, RECD_F16, RECD_BF16 = 0, 1, 2
+RECD_OPT_VALIDATE, RECD_OPT_WEAK_HASH = 1, 2
+
+EXPORTED = [
+    "recd_create", "recd_destroy", "recd_set_option", "recd_last_error", "recd_status_string",
+    "recd_workspace_bytes", "recd_build_ikjt", "recd_pooled_lookup_unique", "recd_expand_inverse",
+    "recd_kjt_pooled_lookup", "recd_backward_dedup",
+]
+
+_vp = C.c_void_p
+_lib.recd_create.argtypes = [C.POINTER(_vp), C.c_int, _vp, C.c_size_t]
+_lib.recd_destroy.argtypes = [_vp]
+_lib.recd_set_option.argtypes = [_vp, C.c_int, C.c_int64]
+_lib.recd_last_error.argtypes = [_vp]
+_lib.recd_last_error.restype = C.c_char_p
+_lib.recd_status_string.argtypes = [C.c_int]
+_lib.recd_status_string.restype = C.c_char_p
+_lib.recd_workspace_bytes.argtypes = [C.c_int, C.c_int64, C.c_int64, C.c_int, C.POINTER(C.c_size_t)]
+_lib.recd_build_ikjt.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.recd_pooled_lookup_unique.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, _vp,
+                                           _vp, C.c_int64, _vp]
+_lib.recd_expand_inverse.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, C.c_int, _vp, _vp, _vp, _vp]
+_lib.recd_kjt_pooled_lookup.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp,
+                                        _vp, _vp]
+_lib.recd_backward_dedup.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, _vp, _vp, _vp, _vp, _vp, _vp,
+                                     C.c_int64, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]
+for _n in EXPORTED:
+    if _n not in ("recd_last_error", "recd_status_string"):
+        getattr(_lib, _n).restype = C.c_int
+
+_DT = {torch.float32: RECD_F32, torch.float16: RECD_F16, torch.bfloat16: RECD_BF16}
+
+
+class RecdError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_lib.recd_status_string(status).decode()}: {message}")
+        self.status = status
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous()
+    return t.data_ptr()
+
+
+def workspace_bytes(F: int, B: int, N: int, D: int) -> int:
+    out = C.c_size_t(0)
+    st = _lib.recd_workspace_bytes(F, B, N, D, C.byref(out))
+    if st != RECD_OK:
+        raise RecdError(st, "recd_workspace_bytes")
+    return int(out.value)
+
+
+class Context:
+    """One recd_ctx bound to a device and to torch's current stream on it."""
+
+    def __init__(self, device: int = 0, workspace_hint_bytes: int = 0, stream: Optional[int] = None):
+        self._h = _vp()
+        if stream is None:
+            stream = torch.cuda.current_stream(device).cuda_stream
+        st = _lib.recd_create(C.byref(self._h), device, _vp(stream), workspace_hint_bytes)
+        if st != RECD_OK:
+            raise RecdError(st, "recd_create failed")
+        self.device = device
+
+    def close(self):
+        if self._h:
+            _lib.recd_destroy(self._h)
+            self._h = _vp()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _check(self, st: int):
+        if st != RECD_OK:
+            raise RecdError(st, _lib.recd_last_error(self._h).decode())
+
+    def set_option(self, opt: int, value: int):
+        self._check(_lib.recd_set_option(self._h, opt, value))
+
+    # -- the five calls; tensors are caller-allocated device tensors ---------------------------
+    def build_ikjt(self, F: int, B: int, values, offsets, u_values, u_offsets, inverse, feat_uoff,
+                   want_counts: bool = False):
+        host = (C.c_int64 * 2)(0, 0) if want_counts else None
+        self._check(_lib.recd_build_ikjt(self._h, F, B, values.numel(), _ptr(values), _ptr(offsets),
+                                         _ptr(u_values), _ptr(u_offsets), _ptr(inverse),
+                                         _ptr(feat_uoff), host))
+        return (int(host[0]), int(host[1])) if want_counts else None
+
+    @staticmethod
+    def _table_array(tables: Sequence[torch.Tensor]):
+        return (_vp * len(tables))(*[t.data_ptr() for t in tables])
+
+    @staticmethod
+    def _rows_array(tables: Sequence[torch.Tensor]):
+        return (C.c_int64 * len(tables))(*[t.shape[0] for t in tables])
+
+    def pooled_lookup_unique(self, tables, u_values, u_offsets, feat_uoff, max_lists: int, pooled):
+        F = len(tables)
+        D = tables[0].shape[1] if F else pooled.shape[-1]
+        tdt = _DT[tables[0].dtype] if F else _DT[pooled.dtype]
+        self._check(_lib.recd_pooled_lookup_unique(
+            self._h, F, D, tdt, _DT[pooled.dtype], self._table_array(tables), self._rows_array(tables),
+            _ptr(u_values), _ptr(u_offsets), _ptr(feat_uoff), max_lists, _ptr(pooled)))
+
+    def expand_inverse(self, F: int, B: int, pooled, feat_uoff, inverse, out):
+        D = pooled.shape[-1]
+        assert out.dtype == pooled.dtype
+        self._check(_lib.recd_expand_inverse(self._h, F, B, D, _DT[pooled.dtype], _ptr(pooled),
+                                             _ptr(feat_uoff), _ptr(inverse), _ptr(out)))
+
+    def kjt_pooled_lookup(self, tables, B: int, values, offsets, out):
+        F = len(tables)
+        D = tables[0].shape[1] if F else out.shape[-1]
+        tdt = _DT[tables[0].dtype] if F else _DT[out.dtype]
+        self._check(_lib.recd_kjt_pooled_lookup(
+            self._h, F, B, D, tdt, _DT[out.dtype], self._table_array(tables), self._rows_array(tables),
+            _ptr(values), _ptr(offsets), _ptr(out)))
+
+    def backward_dedup(self, F: int, B: int, grad_out, inverse, feat_uoff, u_values, u_offsets,
+                       rows: Sequence[int], M_cap: int, touched_rows, feat_roff, grad_rows,
+                       tables=None, adagrad_state=None, lr: float = 0.0, eps: float = 0.0,
+                       want_count: bool = False):
+        D = grad_out.shape[-1]
+        rows_arr = (C.c_int64 * len(rows))(*rows)
+        tabs = self._table_array(tables) if tables is not None else None
+        state = self._table_array(adagrad_state) if adagrad_state is not None else None
+        host = (C.c_int64 * 1)(0) if want_count else None
+        self._check(_lib.recd_backward_dedup(
+            self._h, F, B, D, _ptr(grad_out), _ptr(inverse), _ptr(feat_uoff), _ptr(u_values),
+            _ptr(u_offsets), rows_arr, M_cap, _ptr(touched_rows), _ptr(feat_roff), _ptr(grad_rows),
+            tabs, state, lr, eps, host))
+        return int(host[0]) if want_count else None

@@ -1,0 +1,84 @@
+"""Helpers of the GPU parity tests: upload a seeded batch, run the HIP path through the C ABI,
+bring results back as numpy.  No arithmetic of the method lives here."""
+import numpy as np
+import torch
+
+TORCH_DT = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+
+def to_dev(a, dtype=None):
+    t = torch.from_numpy(np.ascontiguousarray(a))
+    if dtype is not None:
+        t = t.to(dtype)
+    return t.cuda()
+
+
+def tables_to_dev(tabs, dtype):
+    out = []
+    for t in tabs:
+        if dtype == "bf16":
+            out.append(torch.from_numpy(t.astype(np.int16)).view(torch.bfloat16).cuda())
+        else:
+            out.append(torch.from_numpy(t).cuda())
+    return out
+
+
+def out_to_f64(t):
+    return t.detach().to(torch.float64).cpu().numpy()
+
+
+class DeviceIKJT:
+    def __init__(self, F, B, N):
+        L = F * B
+        self.F, self.B = F, B
+        self.u_values = torch.full((max(N, 1),), -7, dtype=torch.int64, device="cuda")
+        self.u_offsets = torch.full((L + 1,), -7, dtype=torch.int64, device="cuda")
+        self.inverse = torch.full((max(L, 1),), -7, dtype=torch.int32, device="cuda")
+        self.feat_uoff = torch.full((F + 1,), -7, dtype=torch.int64, device="cuda")
+        self.U = self.M = None
+
+    def numpy(self):
+        U, M = self.U, self.M
+        return (self.u_values[:M].cpu().numpy(), self.u_offsets[:U + 1].cpu().numpy(),
+                self.inverse[:self.F * self.B].cpu().numpy(), self.feat_uoff.cpu().numpy())
+
+
+def gpu_build(ctx, batch):
+    values, offsets = to_dev(batch.values), to_dev(batch.offsets)
+    if values.numel() == 0:
+        values = torch.zeros(1, dtype=torch.int64, device="cuda")[:0]
+    ik = DeviceIKJT(batch.F, batch.B, batch.N)
+    ik.U, ik.M = ctx.build_ikjt(batch.F, batch.B, values, offsets, ik.u_values, ik.u_offsets,
+                                ik.inverse, ik.feat_uoff, want_counts=True)
+    return values, offsets, ik
+
+
+def gpu_forward(ctx, batch, dev_tables, out_dtype):
+    """Returns (ikjt, pooled[U,D], expanded[F,B,D], kjt_out[F,B,D]) as device tensors."""
+    F, B = batch.F, batch.B
+    D = dev_tables[0].shape[1]
+    values, offsets, ik = gpu_build(ctx, batch)
+    pooled = torch.full((max(F * B, 1), D), float("nan"), dtype=out_dtype, device="cuda")
+    ctx.pooled_lookup_unique(dev_tables, ik.u_values, ik.u_offsets, ik.feat_uoff, F * B, pooled)
+    out = torch.full((F, B, D), float("nan"), dtype=out_dtype, device="cuda")
+    ctx.expand_inverse(F, B, pooled, ik.feat_uoff, ik.inverse, out)
+    kjt = torch.full((F, B, D), float("nan"), dtype=out_dtype, device="cuda")
+    ctx.kjt_pooled_lookup(dev_tables, B, values, offsets, kjt)
+    torch.cuda.synchronize()
+    return ik, pooled, out, kjt
+
+
+def assert_close_f32(got, ref, what=""):
+    """fp32 bar: |err| <= 1e-5 * (1 + |ref|)."""
+    err = np.abs(got - ref)
+    bound = 1e-5 * (1.0 + np.abs(ref))
+    bad = err > bound
+    assert not bad.any(), f"{what}: {bad.sum()} elements beyond 1e-5*(1+|ref|), max err {err.max()}"
+
+
+def assert_close_16(got, ref, what=""):
+    """fp16/bf16 bar: 1e-2 relative, with an absolute floor of 1e-6 for sums that cancel to ~0."""
+    err = np.abs(got - ref)
+    bound = 1e-2 * np.abs(ref) + 1e-6
+    bad = err > bound
+    assert not bad.any(), f"{what}: {bad.sum()} elements beyond 1e-2 relative, max err {err.max()}"

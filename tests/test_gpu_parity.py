@@ -1,0 +1,303 @@
+"""GPU parity tests: the HIP path (through the C ABI) against the CPU oracle, element by element,
+on the same seeded inputs.  Integer outputs bit-exact; floats within
+|err| <= 1e-5*(1+|ref|) (fp32) or 1e-2 relative (fp16/bf16)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import recd_oracle as orc
+from paper_2211_05239_amd import synth
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def recd():
+    from paper_2211_05239_amd import recd as mod
+    return mod
+
+
+@pytest.fixture(scope="module")
+def ctx(recd):
+    c = recd.Context(0)
+    yield c
+    c.close()
+
+
+def _bits(t):
+    return t.view(torch.int32 if t.element_size() == 4 else torch.int16)
+
+
+def _check_ikjt(ik, batch):
+    ref = orc.build_ikjt(batch.F, batch.B, batch.values, batch.offsets)
+    got = ik.numpy()
+    assert ik.U == int(ref[3][-1]) and ik.M == len(ref[0])
+    for name, g, r in zip(("u_values", "u_offsets", "inverse", "feat_uoff"), got, ref):
+        assert g.dtype == r.dtype and np.array_equal(g, r), name
+    return ref
+
+
+# ------------------------------------------------------------------ builder
+@pytest.mark.parametrize("seed", range(8))
+@pytest.mark.parametrize("weak", [0, 1])
+def test_build_tiny_random(ctx, recd, seed, weak):
+    rng = np.random.default_rng(4000 + seed)
+    F, B = int(rng.integers(1, 6)), int(rng.integers(1, 300))
+    batch = synth.tiny_batch(rng, F, B, int(rng.integers(2, 6)), int(rng.integers(0, 7)))
+    ctx.set_option(recd.RECD_OPT_WEAK_HASH, weak)
+    try:
+        _, _, ik = gu.gpu_build(ctx, batch)
+    finally:
+        ctx.set_option(recd.RECD_OPT_WEAK_HASH, 0)
+    _check_ikjt(ik, batch)
+
+
+def test_build_adversarial_and_degenerate(ctx, recd):
+    cases = [
+        [[[1, 2, 3], [1, 2, 4], [1, 2], [2, 1], [1, 2, 3, 3], [], [1, 2], [3, 2, 1], [1, 2, 3], [],
+          [1, 1], [1], [1, 1, 1], [2, 1]]],
+        [[[]] * 5, [[]] * 5],                                  # all empty
+        [[[4, 4, 2]] * 70],                                    # all identical
+        [[[i, i + 1] for i in range(130)]],                    # all distinct
+        [[[1], [2], [3], [1]], [[1], [1], [2], [3]]],          # duplicates far apart; never across features
+        [[list(range(300)), list(range(299)) + [7], list(range(300)), list(range(301))]],  # long lists
+        [[[5]]],                                               # B = 1
+    ]
+    for weak in (0, 1):
+        ctx.set_option(recd.RECD_OPT_WEAK_HASH, weak)
+        try:
+            for lists in cases:
+                batch = synth.batch_from_lists(lists)
+                _, _, ik = gu.gpu_build(ctx, batch)
+                _check_ikjt(ik, batch)
+        finally:
+            ctx.set_option(recd.RECD_OPT_WEAK_HASH, 0)
+
+
+def test_build_empty_sizes(ctx):
+    for F, B in ((3, 0), (0, 5), (0, 0)):
+        batch = synth.Batch(F, B, np.zeros(0, np.int64), np.zeros(F * B + 1, np.int64),
+                            np.zeros(B, np.int32), 1.0)
+        _, _, ik = gu.gpu_build(ctx, batch)
+        assert (ik.U, ik.M) == (0, 0)
+        assert ik.feat_uoff.cpu().tolist() == [0] * (F + 1)
+        assert int(ik.u_offsets[0]) == 0
+
+
+@pytest.mark.parametrize("name", ["cfg1", "cfg2s", "cfg3s", "cfg4s"])
+def test_build_workloads(ctx, name):
+    w = {"cfg1": synth.WORKLOADS["cfg1"],
+         "cfg2s": synth.scaled(synth.WORKLOADS["cfg2"], F=5, B=4099),
+         "cfg3s": synth.scaled(synth.WORKLOADS["cfg3"], F=3, B=3001),
+         "cfg4s": synth.scaled(synth.sweep_workload(2), F=2, B=1500)}[name]
+    batch = synth.make_batch(w, 1)
+    _, _, ik = gu.gpu_build(ctx, batch)
+    _check_ikjt(ik, batch)
+    # the result does not depend on the hash function
+    _, _, ik2 = gu.gpu_build(ctx, batch)
+    assert torch.equal(ik.inverse, ik2.inverse) and torch.equal(ik.u_values[:ik.M], ik2.u_values[:ik2.M])
+
+
+def test_build_weak_hash_medium(ctx, recd):
+    w = synth.scaled(synth.WORKLOADS["cfg1"], B=700, F=2)
+    batch = synth.make_batch(w, 2)
+    ctx.set_option(recd.RECD_OPT_WEAK_HASH, 1)
+    try:
+        _, _, ik = gu.gpu_build(ctx, batch)
+    finally:
+        ctx.set_option(recd.RECD_OPT_WEAK_HASH, 0)
+    _check_ikjt(ik, batch)
+
+
+# ------------------------------------------------------------------ forward floats
+def _forward_case(ctx, w, batch_index, out_dtype=None, rows=None):
+    if rows is not None:
+        w = synth.scaled(w, rows=rows)
+    batch = synth.make_batch(w, batch_index)
+    tabs = synth.make_tables(w)
+    dev_tabs = gu.tables_to_dev(tabs, w.table_dtype)
+    odt = out_dtype or gu.TORCH_DT[w.table_dtype]
+    ik, pooled, out, kjt = gu.gpu_forward(ctx, batch, dev_tabs, odt)
+    uv, uo, inv, fu = _check_ikjt(ik, batch)
+    ref_pooled = orc.pooled_lookup(tabs, w.table_dtype, uv, uo, fu)
+    ref_out = orc.expand_inverse(w.F, w.B, ref_pooled, fu, inv)
+    ref_kjt = orc.kjt_pooled_lookup(tabs, w.table_dtype, w.B, batch.values, batch.offsets)
+    close = gu.assert_close_f32 if odt == torch.float32 and w.table_dtype == "f32" else gu.assert_close_16
+    if odt == torch.float32 and w.table_dtype != "f32":
+        close = gu.assert_close_f32  # 16-bit tables decode exactly; fp32 accumulation and output
+    close(gu.out_to_f64(pooled[:ik.U]), ref_pooled, "pooled unique")
+    close(gu.out_to_f64(out), ref_out, "expanded")
+    close(gu.out_to_f64(kjt), ref_kjt, "kjt lookup")
+    # expand is a pure copy of pooled rows
+    idx = (torch.from_numpy(fu[:-1]).cuda().repeat_interleave(w.B) + ik.inverse[:w.F * w.B].long())
+    assert torch.equal(out.view(w.F * w.B, -1), pooled[idx])
+    # summation order depends on the list alone: dedup path == non-dedup path, bit for bit
+    assert torch.equal(_bits(out), _bits(kjt))
+    return batch, dev_tabs, ik, pooled, out, kjt
+
+
+def test_forward_cfg1(ctx):
+    _forward_case(ctx, synth.WORKLOADS["cfg1"], 0)
+
+
+@pytest.mark.parametrize("dt,odt", [("f32", None), ("f16", None), ("f16", torch.float32),
+                                    ("bf16", None), ("bf16", torch.float32)])
+def test_forward_dtypes(ctx, dt, odt):
+    w = synth.scaled(synth.WORKLOADS["cfg3"], F=3, B=1031, rows=50_000, table_dtype=dt)
+    _forward_case(ctx, w, 0, odt)
+
+
+@pytest.mark.parametrize("D", [4, 8, 24, 32, 64, 96, 128, 256, 512, 1024])
+def test_forward_row_shapes_f32(ctx, D):
+    w = synth.scaled(synth.WORKLOADS["cfg2"], F=2, B=517, rows=3000, D=D)
+    _forward_case(ctx, w, 0)
+
+
+@pytest.mark.parametrize("D", [8, 64, 128, 256, 1024, 2048])
+def test_forward_row_shapes_f16(ctx, D):
+    w = synth.scaled(synth.WORKLOADS["cfg3"], F=2, B=517, rows=3000, D=D)
+    _forward_case(ctx, w, 0)
+
+
+def test_forward_many_features(ctx):
+    """More features than travel in one launch (tables are passed to the kernel in groups)."""
+    w = synth.scaled(synth.WORKLOADS["cfg1"], F=131, B=67, rows=500, D=16)
+    _forward_case(ctx, w, 0)
+
+
+def test_forward_cfg2_scaled(ctx):
+    w = synth.scaled(synth.WORKLOADS["cfg2"], F=6, B=4096, rows=200_000)
+    _forward_case(ctx, w, 0)
+
+
+def test_forward_deterministic(ctx):
+    w = synth.scaled(synth.WORKLOADS["cfg2"], F=4, B=2048, rows=100_000)
+    a = _forward_case(ctx, w, 3)
+    b = _forward_case(ctx, w, 3)
+    for x, y in zip(a[3:], b[3:]):
+        assert torch.equal(_bits(x), _bits(y))  # rows of pooled beyond U keep their NaN fill
+
+
+def test_empty_lists_pool_to_zero(ctx):
+    batch = synth.batch_from_lists([[[], [2], [], [2, 2]]])
+    tab = [np.full((4, 8), 1.5, np.float32)]
+    ik, pooled, out, kjt = gu.gpu_forward(ctx, batch, gu.tables_to_dev(tab, "f32"), torch.float32)
+    assert out[0, 0].abs().sum().item() == 0.0 and out[0, 2].abs().sum().item() == 0.0
+    assert torch.all(out[0, 1] == 1.5) and torch.all(out[0, 3] == 3.0)
+    assert torch.equal(out, kjt)
+
+
+# ------------------------------------------------------------------ errors
+def test_argument_errors(ctx, recd):
+    t = [torch.zeros(10, 6, device="cuda")]  # D = 6: 24-byte rows are not a multiple of 16
+    v = torch.zeros(4, dtype=torch.int64, device="cuda")
+    o = torch.tensor([0, 2, 4], dtype=torch.int64, device="cuda")
+    out = torch.zeros(1, 2, 6, device="cuda")
+    with pytest.raises(recd.RecdError) as e:
+        ctx.kjt_pooled_lookup(t, 2, v, o, out)
+    assert e.value.status == recd.RECD_EINVAL
+    t16 = [torch.zeros(10, 8, device="cuda", dtype=torch.float16)]
+    with pytest.raises(recd.RecdError) as e:  # f32 table with f16 output is not offered
+        ctx.kjt_pooled_lookup([torch.zeros(10, 8, device="cuda")], 2, v, o,
+                              torch.zeros(1, 2, 8, device="cuda", dtype=torch.float16))
+    assert e.value.status == recd.RECD_EINVAL
+    del t16
+
+
+def test_validation_reports_bad_inputs(ctx, recd):
+    tab = [torch.zeros(10, 8, device="cuda")]
+    out = torch.zeros(1, 2, 8, device="cuda")
+    good_v = torch.tensor([1, 9, 3], dtype=torch.int64, device="cuda")
+    bad_v = torch.tensor([1, 10, 3], dtype=torch.int64, device="cuda")
+    neg_v = torch.tensor([1, -1, 3], dtype=torch.int64, device="cuda")
+    good_o = torch.tensor([0, 1, 3], dtype=torch.int64, device="cuda")
+    bad_o = torch.tensor([0, 3, 2], dtype=torch.int64, device="cuda")
+    ctx.set_option(recd.RECD_OPT_VALIDATE, 1)
+    try:
+        ctx.kjt_pooled_lookup(tab, 2, good_v, good_o, out)
+        for v, o in ((bad_v, good_o), (neg_v, good_o), (good_v, bad_o)):
+            with pytest.raises(recd.RecdError) as e:
+                ctx.kjt_pooled_lookup(tab, 2, v, o, out)
+            assert e.value.status == recd.RECD_EBOUNDS
+        ik = gu.DeviceIKJT(1, 2, 3)
+        with pytest.raises(recd.RecdError) as e:
+            ctx.build_ikjt(1, 2, good_v, bad_o, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff)
+        assert e.value.status == recd.RECD_EBOUNDS
+    finally:
+        ctx.set_option(recd.RECD_OPT_VALIDATE, 0)
+
+
+# ------------------------------------------------------------------ backward
+def _backward_case(ctx, w, batch_index, with_adagrad=True):
+    batch = synth.make_batch(w, batch_index)
+    F, B, D = w.F, w.B, w.D
+    gout = synth.make_grad_out(w, batch_index)
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    uv, uo, inv, fu = _check_ikjt(ik, batch)
+    M = max(ik.M, 1)
+    touched = torch.full((M,), -7, dtype=torch.int64, device="cuda")
+    feat_roff = torch.full((F + 1,), -7, dtype=torch.int64, device="cuda")
+    grad_rows = torch.full((M, D), float("nan"), dtype=torch.float32, device="cuda")
+    d_gout = gu.to_dev(gout)
+    tabs = synth.make_tables(w)
+    d_tabs = gu.tables_to_dev(tabs, "f32")
+    state0 = [np.abs(np.random.default_rng(5 + f).standard_normal(w.rows)).astype(np.float32) * 1e-4
+              for f in range(F)]
+    d_state = [gu.to_dev(s) for s in state0]
+    lr, eps = 0.01, 1e-8
+    R = ctx.backward_dedup(F, B, d_gout, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets,
+                           [w.rows] * F, ik.M, touched, feat_roff, grad_rows,
+                           tables=d_tabs if with_adagrad else None,
+                           adagrad_state=d_state if with_adagrad else None, lr=lr, eps=eps,
+                           want_count=True)
+    tr, fr, gr = orc.backward_dedup(F, B, gout, inv, fu, uv, uo)
+    assert R == len(tr)
+    assert np.array_equal(touched[:R].cpu().numpy(), tr)
+    assert np.array_equal(feat_roff.cpu().numpy(), fr)
+    g_gpu = grad_rows[:R].cpu().numpy()
+    gu.assert_close_f32(g_gpu.astype(np.float64), gr, "grad_rows")
+    if with_adagrad:
+        for f in range(F):
+            rows_f = tr[fr[f]:fr[f + 1]]
+            w_new, m_new = orc.rowwise_adagrad(gr[fr[f]:fr[f + 1]], tabs[f][rows_f].astype(np.float64),
+                                               state0[f][rows_f].astype(np.float64), lr, eps)
+            Wg = d_tabs[f].cpu().numpy()
+            mg = d_state[f].cpu().numpy()
+            gu.assert_close_f32(Wg[rows_f].astype(np.float64), w_new, "adagrad rows")
+            gu.assert_close_f32(mg[rows_f].astype(np.float64), m_new, "adagrad state")
+            untouched = np.ones(w.rows, bool)
+            untouched[rows_f] = False
+            assert np.array_equal(Wg[untouched], tabs[f][untouched])       # bit for bit
+            assert np.array_equal(mg[untouched], state0[f][untouched])
+    return touched[:R].clone(), feat_roff.clone(), grad_rows[:R].clone()
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_backward_small(ctx, seed):
+    w = synth.scaled(synth.WORKLOADS["cfg1"], F=3, B=257 + 100 * seed, rows=900, D=32)
+    _backward_case(ctx, w, seed)
+
+
+def test_backward_skewed_ids(ctx):
+    """Zipf ids: one row collects a large share of all positions (long segments)."""
+    w = synth.scaled(synth.WORKLOADS["cfg5"], F=3, B=2048, rows=30_000, D=128)
+    _backward_case(ctx, w, 0)
+
+
+def test_backward_deterministic(ctx):
+    w = synth.scaled(synth.WORKLOADS["cfg2"], F=4, B=1024, rows=20_000, D=64)
+    a = _backward_case(ctx, w, 1, with_adagrad=False)
+    b = _backward_case(ctx, w, 1, with_adagrad=False)
+    for x, y in zip(a, b):
+        assert torch.equal(x, y)
+
+
+def test_backward_no_ids(ctx):
+    batch = synth.batch_from_lists([[[], []], [[], []]])
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    feat_roff = torch.full((3,), -7, dtype=torch.int64, device="cuda")
+    gout = torch.zeros(2, 2, 8, device="cuda")
+    R = ctx.backward_dedup(2, 2, gout, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [5, 5], 0,
+                           None, feat_roff, None, want_count=True)
+    assert R == 0 and feat_roff.cpu().tolist() == [0, 0, 0]
