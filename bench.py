@@ -1,0 +1,348 @@
+#!/usr/bin/env python3
+"""Benchmark of the deduplicated-embedding hot path on one MI355X.
+
+One "step" = one pass of the whole path over one synthetic session-structured batch:
+  recd_build_ikjt -> recd_pooled_lookup_unique -> recd_expand_inverse -> recd_backward_dedup
+  (inverse aggregation, sorted segment-reduce, row-wise Adagrad).
+Inputs (KJT, tables, upstream gradient) are resident in HBM before the timed region; steps rotate
+over several different seeded batches so that table rows are not served from a warm cache.
+The non-deduplicated KJT lookup (comparison path) is timed separately on the same batches.
+
+Prints ONE JSON line.  `value` = pooled lookups per second = B*F / step time.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X published HBM3E bandwidth
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=4)
+    ap.add_argument("--workload", default="cfg5",
+                    help="cfg1..cfg5 or cfg4_S<k> (duplication sweep member)")
+    ap.add_argument("--batches", type=int, default=4, help="distinct seeded batches to rotate over")
+    ap.add_argument("--cpu-features", type=int, default=24,
+                    help="features of batch 0 the CPU oracle is timed on (0 = skip)")
+    ap.add_argument("--sweep", action="store_true", help="also run the duplication sweep (cfg4, S in 1,2,4,8,32)")
+    ap.add_argument("--forward-only", action="store_true", help="leave the backward pass out of the step")
+    ap.add_argument("--calib-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (calibrates hardware byte counters)")
+    return ap.parse_args()
+
+
+class DeviceProblem:
+    """Everything one workload needs on the device, allocated once at worst-case sizes."""
+
+    def __init__(self, torch, recd, synth, w, n_batches, need_backward):
+        self.torch, self.w = torch, w
+        F, B, D = w.F, w.B, w.D
+        self.tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[w.table_dtype]
+        self.batches = [synth.make_batch(w, i) for i in range(n_batches)]
+        self.values = [torch.from_numpy(b.values).cuda() for b in self.batches]
+        self.offsets = [torch.from_numpy(b.offsets).cuda() for b in self.batches]
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(synth.BASE_SEED + 1000 * w.index + 777)
+        self.tables = []
+        for _ in range(F):
+            t = torch.empty(w.rows, D, dtype=torch.float32, device="cuda")
+            t.normal_(0.0, 0.01, generator=gen)
+            self.tables.append(t.to(self.tdt) if self.tdt != torch.float32 else t)
+        Nmax = max(b.N for b in self.batches)
+        # one IKJT per batch, so that the per-call timings can run the same call on all batches
+        # back to back
+        self.u_values = [torch.zeros(b.N, dtype=torch.int64, device="cuda") for b in self.batches]
+        self.u_offsets = [torch.zeros(F * B + 1, dtype=torch.int64, device="cuda") for _ in self.batches]
+        self.inverse = [torch.zeros(F * B, dtype=torch.int32, device="cuda") for _ in self.batches]
+        self.feat_uoff = [torch.zeros(F + 1, dtype=torch.int64, device="cuda") for _ in self.batches]
+        self.pooled = torch.zeros(F * B, D, dtype=self.tdt, device="cuda")
+        self.out = torch.zeros(F, B, D, dtype=self.tdt, device="cuda")
+        self.kjt_out = torch.zeros(F, B, D, dtype=self.tdt, device="cuda")
+        self.need_backward = need_backward
+        ws = recd.workspace_bytes(F, B, Nmax, D)
+        self.ctx = recd.Context(0, workspace_hint_bytes=ws)
+        # unique-list counts of every batch (U, M): size the backward outputs by the largest M
+        self.counts = [self.build(i) for i in range(n_batches)]
+        if need_backward:
+            Mmax = max(c[1] for c in self.counts)
+            g = torch.Generator(device="cuda")
+            g.manual_seed(synth.BASE_SEED + 1000 * w.index + 500)
+            self.grad_out = torch.empty(F, B, D, dtype=torch.float32, device="cuda")
+            self.grad_out.normal_(0.0, 0.01, generator=g)
+            self.touched = torch.zeros(Mmax, dtype=torch.int64, device="cuda")
+            self.feat_roff = torch.zeros(F + 1, dtype=torch.int64, device="cuda")
+            self.grad_rows = torch.zeros(Mmax, D, dtype=torch.float32, device="cuda")
+            self.state = [torch.zeros(w.rows, dtype=torch.float32, device="cuda") for _ in range(F)]
+        self.rows = [w.rows] * F
+
+    # --- the calls of one step; each returns nothing and enqueues on torch's current stream ----
+    def build(self, i, counts=True):
+        w = self.w
+        return self.ctx.build_ikjt(w.F, w.B, self.values[i], self.offsets[i], self.u_values[i],
+                                   self.u_offsets[i], self.inverse[i], self.feat_uoff[i],
+                                   want_counts=counts)
+
+    def lookup(self, i, U=None):
+        w = self.w
+        self.ctx.pooled_lookup_unique(self.tables, self.u_values[i], self.u_offsets[i],
+                                      self.feat_uoff[i], w.F * w.B if U is None else U, self.pooled)
+
+    def expand(self, i):
+        w = self.w
+        self.ctx.expand_inverse(w.F, w.B, self.pooled, self.feat_uoff[i], self.inverse[i], self.out)
+
+    def backward(self, i, U, M, want_count=False):
+        w = self.w
+        return self.ctx.backward_dedup(w.F, w.B, self.grad_out, self.inverse[i], self.feat_uoff[i],
+                                       self.u_values[i], self.u_offsets[i], self.rows, U, M, self.touched,
+                                       self.feat_roff, self.grad_rows, tables=self.tables,
+                                       adagrad_state=self.state, lr=0.01, eps=1e-8,
+                                       want_count=want_count)
+
+    def kjt(self, i):
+        w = self.w
+        self.ctx.kjt_pooled_lookup(self.tables, w.B, self.values[i], self.offsets[i], self.kjt_out)
+
+    def step(self, i):
+        U, M = self.build(i)           # U and M come back to the host: they size the later launches
+        self.lookup(i, U)
+        self.expand(i)
+        if self.need_backward:
+            self.backward(i, U, M)
+        return U, M
+
+
+def event_ms(torch, fn, reps):
+    """Average HIP-event time of fn() on torch's current stream (the stream the library uses)."""
+    s = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
+    for k in range(reps):
+        s[k].record()
+        fn(k)
+        e[k].record()
+    torch.cuda.synchronize()
+    ts = sorted(a.elapsed_time(b) for a, b in zip(s, e))
+    return float(np.mean(ts)), float(ts[len(ts) // 2])
+
+
+def run_workload(torch, recd, synth, w, args, need_backward, detail=True):
+    P = DeviceProblem(torch, recd, synth, w, args.batches, need_backward)
+    nb = len(P.batches)
+    F, B, D = w.F, w.B, w.D
+    e = 4 if w.table_dtype == "f32" else 2
+    o = e
+
+    stats = []
+    for i in range(nb):  # per-batch sizes (also warms the workspace)
+        U, M = P.build(i)
+        P.lookup(i, U)
+        P.expand(i)
+        R = P.backward(i, U, M, want_count=True) if need_backward else None
+        stats.append((U, M, R))
+    for k in range(args.warmup):
+        P.step(k % nb)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        P.step(k % nb)
+    torch.cuda.synchronize()
+    step_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    res = {"step_ms": step_ms, "B": B, "F": F, "D": D}
+    N = float(np.mean([b.N for b in P.batches]))
+    U = float(np.mean([s[0] for s in stats]))
+    M = float(np.mean([s[1] for s in stats]))
+    res.update({"N": N, "U": U, "M": M, "dedupe_factor": N / max(M, 1.0),
+                "mean_session": float(np.mean([b.mean_session for b in P.batches]))})
+    if not detail:
+        P.ctx.close()
+        return res, P
+
+    reps = max(args.steps // nb, 3)
+    # Per-call HIP-event timings on the library's stream (torch's current stream).  Each call is
+    # issued for all batches back to back between one pair of events, behind a kernel that keeps
+    # the GPU busy while the host marshals the first call, so the pair brackets GPU time only.
+    # lookup, expand and kjt are one kernel launch per call.
+    cnt = [P.build(i) for i in range(nb)]     # every batch's IKJT is resident from here on
+
+    def timed(fn):
+        s_ev, e_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        P.expand(0)
+        s_ev.record()
+        for i in range(nb):
+            fn(i)
+        e_ev.record()
+        torch.cuda.synchronize()
+        return s_ev.elapsed_time(e_ev) / nb
+
+    lookup_t, expand_t, kjt_t, bwd_t, build_t = [], [], [], [], []
+    for _ in range(reps):
+        lookup_t.append(timed(lambda i: P.lookup(i, cnt[i][0])))
+        expand_t.append(timed(P.expand))
+        kjt_t.append(timed(P.kjt))
+        build_t.append(timed(lambda i: P.build(i, counts=False)))
+        if need_backward:
+            bwd_t.append(timed(lambda i: P.backward(i, cnt[i][0], cnt[i][1])))
+    build_ms = float(np.mean(build_t))
+    lookup_ms, expand_ms, kjt_ms = (float(np.mean(x)) for x in (lookup_t, expand_t, kjt_t))
+    res.update({"build_ms": build_ms, "lookup_unique_ms": lookup_ms, "expand_ms": expand_ms,
+                "kjt_lookup_ms": kjt_ms})
+    if need_backward:
+        res["backward_ms"] = float(np.mean(bwd_t))
+        R = float(np.mean([s[2] for s in stats]))
+        res["R"] = R
+    else:
+        R = None
+
+    # algorithmic bytes per launch (upper: every gathered row counted; compulsory: each distinct
+    # row once per launch)
+    look_upper = M * 8 + (U + 1) * 8 + M * D * e + U * D * o
+    exp_bytes = F * B * 4 + U * D * o + F * B * D * o
+    kjt_upper = N * 8 + (F * B + 1) * 8 + N * D * e + F * B * D * o
+    res["bytes"] = {"lookup_unique_upper": look_upper, "expand": exp_bytes, "kjt_upper": kjt_upper}
+    if R is not None:
+        res["bytes"]["lookup_unique_compulsory"] = M * 8 + (U + 1) * 8 + R * D * e + U * D * o
+        res["bytes"]["kjt_compulsory"] = N * 8 + (F * B + 1) * 8 + R * D * e + F * B * D * o
+    res["gbs"] = {
+        "lookup_unique_upper": look_upper / lookup_ms / 1e6,
+        "expand": exp_bytes / expand_ms / 1e6,
+        "lookup_plus_expand_upper": (look_upper + exp_bytes) / (lookup_ms + expand_ms) / 1e6,
+        "kjt_upper": kjt_upper / kjt_ms / 1e6,
+    }
+    if R is not None:
+        res["gbs"]["lookup_unique_compulsory"] = res["bytes"]["lookup_unique_compulsory"] / lookup_ms / 1e6
+        res["gbs"]["kjt_compulsory"] = res["bytes"]["kjt_compulsory"] / kjt_ms / 1e6
+    res["speedup_vs_kjt"] = kjt_ms / (lookup_ms + expand_ms)
+    res["speedup_vs_kjt_with_build"] = kjt_ms / (build_ms + lookup_ms + expand_ms)
+    res["predicted_speedup_bytes_model"] = kjt_upper / (look_upper + F * B * 4 + 2 * F * B * D * o)
+    return res, P
+
+
+def cpu_baseline(torch, synth, P, n_feat):
+    """The CPU oracle, as it stands, on the first n_feat features of batch 0 (features are
+    independent): build + unique lookup + expand + backward + Adagrad, single thread."""
+    from oracle import recd_oracle as orc
+    w = P.w
+    n_feat = min(n_feat, w.F)
+    b = P.batches[0]
+    B, D = w.B, w.D
+    hi = int(b.offsets[n_feat * B])
+    values, offsets = b.values[:hi], b.offsets[:n_feat * B + 1]
+    dt = w.table_dtype
+    tabs = []
+    for f in range(n_feat):
+        t = P.tables[f]
+        tabs.append(t.view(torch.int16).cpu().numpy().view(np.uint16) if dt == "bf16" else t.cpu().numpy())
+    gout = P.grad_out[:n_feat].cpu().numpy() if P.need_backward else None
+    t0 = time.perf_counter()
+    uv, uo, inv, fu = orc.build_ikjt(n_feat, B, values, offsets)
+    pooled = orc.pooled_lookup(tabs, dt, uv, uo, fu)
+    orc.expand_inverse(n_feat, B, pooled, fu, inv)
+    if gout is not None:
+        tr, fr, gr = orc.backward_dedup(n_feat, B, gout, inv, fu, uv, uo)
+        for f in range(n_feat):
+            rows_f = tr[fr[f]:fr[f + 1]]
+            orc.rowwise_adagrad(gr[fr[f]:fr[f + 1]], tabs[f][rows_f].astype(np.float64),
+                                np.zeros(len(rows_f)), 0.01, 1e-8)
+    dt_s = time.perf_counter() - t0
+    return {"value": B * n_feat / dt_s, "unit": "pooled lookups/s", "cores": 1, "kind": "oracle",
+            "seconds": dt_s,
+            "sample": f"features 0..{n_feat - 1} of batch 0 ({n_feat} of {w.F} features, all "
+                      f"B={B} rows): build + unique lookup + expand"
+                      + (" + backward + Adagrad" if gout is not None else "")}
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is single-GPU (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    from paper_2211_05239_amd import recd, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+
+    if args.calib_copy:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+        b = torch.ones(1 << 28, dtype=torch.float32, device="cuda")
+        for _ in range(3):
+            a.copy_(b)
+        torch.cuda.synchronize()
+        del a, b
+        torch.cuda.empty_cache()
+
+    name = args.workload
+    if name.startswith("cfg4_S"):
+        w = synth.sweep_workload(int(name[6:]))
+    else:
+        w = synth.WORKLOADS[name]
+    need_backward = not args.forward_only
+    res, P = run_workload(torch, recd, synth, w, args, need_backward)
+
+    value = w.B * w.F / (res["step_ms"] * 1e-3)
+    look_bytes = res["bytes"].get("lookup_unique_compulsory", res["bytes"]["lookup_unique_upper"])
+    achieved = look_bytes / res["lookup_unique_ms"] / 1e6
+    line = {
+        "metric": "deduped pooled lookups/sec",
+        "value": value,
+        "unit": "pooled lookups/s",
+        "samples_per_s": w.B / (res["step_ms"] * 1e-3),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": res["step_ms"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32" if w.table_dtype == "f32" else f"{w.table_dtype} tables, f32 accumulation",
+        "data": "synthetic",
+        "config": {"workload": f"{w.name}: B={w.B}, F={w.F}, mean session {w.S}, rows={w.rows}, D={w.D}, "
+                               f"{w.table_dtype} tables; step = build_ikjt + pooled_lookup_unique + "
+                               f"expand_inverse" + (" + backward_dedup with row-wise Adagrad" if need_backward else ""),
+                   "batches_rotated": len(P.batches)},
+        "roofline": {"bound": "hbm", "kernel": "k_segsum (recd_pooled_lookup_unique)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "algorithmic_bytes": look_bytes,
+                     "bytes_form": "compulsory (each distinct table row once per launch)"
+                     if "lookup_unique_compulsory" in res["bytes"] else "upper",
+                     "avg_launch_ms": res["lookup_unique_ms"]},
+        "regions": res,
+    }
+    if args.cpu_features > 0:
+        line["cpu_baseline"] = cpu_baseline(torch, synth, P, args.cpu_features)
+    P.ctx.close()
+    del P
+    torch.cuda.empty_cache()
+
+    if args.sweep:
+        sweep = []
+        for S in synth.SWEEP_SESSION_SIZES:
+            ws = synth.sweep_workload(S)
+            r, Ps = run_workload(torch, recd, synth, ws, args, need_backward=False)
+            Ps.ctx.close()
+            del Ps
+            torch.cuda.empty_cache()
+            sweep.append({"S": S, "measured_session": r["mean_session"], "dedupe_factor": r["dedupe_factor"],
+                          "lookup_unique_ms": r["lookup_unique_ms"], "expand_ms": r["expand_ms"],
+                          "build_ms": r["build_ms"], "kjt_lookup_ms": r["kjt_lookup_ms"],
+                          "speedup_vs_kjt": r["speedup_vs_kjt"],
+                          "speedup_vs_kjt_with_build": r["speedup_vs_kjt_with_build"],
+                          "predicted": r["predicted_speedup_bytes_model"], "gbs": r["gbs"]})
+        line["duplication_sweep"] = sweep
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

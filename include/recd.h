@@ -65,9 +65,14 @@ typedef enum { RECD_F32 = 0, RECD_F16 = 1, RECD_BF16 = 2 } recd_dtype;
 
 typedef enum {
     RECD_OPT_VALIDATE = 1,  /* value != 0: check preconditions on the device before each operation  */
-    RECD_OPT_WEAK_HASH = 2  /* test hook, value != 0: the builder hashes a list to its length only,
+    RECD_OPT_WEAK_HASH = 2, /* test hook, value != 0: the builder hashes a list to its length only,
                                so that unequal lists collide constantly and only the exact list
                                comparison keeps them apart.  Results must not change.            */
+    RECD_OPT_TUNE_SEGSUM = 3 /* tuning knob of the gather-sum kernel's launch shape, 0 = automatic:
+                               value = lists per block (4, 8 or 16) + 100 * lists in flight per wave
+                               (1, 2 or 4) + 10000 * block generations per CU (< 100) + 1000000 * (1 = no
+                               XCD-aware block mapping).  Results must not
+                               change (the summation order of a list never depends on it).        */
 } recd_option;
 
 /* Largest number of features per call and largest row size in bytes (D * element size). */
@@ -142,7 +147,8 @@ recd_status recd_kjt_pooled_lookup(recd_ctx *ctx, int F, int64_t B, int D, recd_
  *    computed as stable radix sorts followed by segment sums in sorted order: no floating-point
  *    atomics, bit-identical from run to run.
  *    grad_out: device fp32 [F, B, D].  rows: HOST int64 [F] table sizes (bounds the sort key).
- *    M_cap: host upper bound of M (N always is; the exact M avoids idle work).
+ *    U_cap, M_cap: host upper bounds of U and M (F*B and N always are; the exact values, as
+ *    returned by recd_build_ikjt, avoid idle work).
  *    touched_rows: device int64, capacity M_cap: per feature the ascending distinct ids.
  *    feat_roff: device int64 [F+1] prefix sum of the per-feature distinct counts R_f.
  *    grad_rows: device fp32 [R, D], capacity M_cap rows, aligned with touched_rows.
@@ -155,7 +161,8 @@ recd_status recd_kjt_pooled_lookup(recd_ctx *ctx, int F, int64_t B, int D, recd_
 recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int D, const float *grad_out,
                                 const int32_t *inverse, const int64_t *feat_uoff,
                                 const int64_t *u_values, const int64_t *u_offsets,
-                                const int64_t *rows, int64_t M_cap, int64_t *touched_rows,
+                                const int64_t *rows, int64_t U_cap, int64_t M_cap,
+                                int64_t *touched_rows,
                                 int64_t *feat_roff, float *grad_rows, void *const *tables,
                                 float *const *adagrad_state, float lr, float eps,
                                 int64_t *host_R);

@@ -456,9 +456,9 @@ BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D)
 }
 
 template <typename KeyT>
-recd_status group_and_sum(recd_ctx *ctx, const BwdWs &w, KeyT *k0, KeyT *k1, int64_t n_cap, int bits,
-                          int row_bits, int F, const void *table, int D, void *out,
-                          int64_t *touched_rows, int64_t *feat_roff)
+recd_status group_and_sum(recd_ctx *ctx, const BwdWs &w, KeyT *k0, KeyT *k1, int64_t n_cap,
+                          int64_t seg_bound, int bits, int row_bits, int F, const void *table,
+                          int D, void *out, int64_t *touched_rows, int64_t *feat_roff)
 {
     KeyT *ks;
     uint32_t *ps;
@@ -483,6 +483,8 @@ recd_status group_and_sum(recd_ctx *ctx, const BwdWs &w, KeyT *k0, KeyT *k1, int
     a.values_are_i32 = 1;
     a.offsets = w.seg_start;
     a.list_off = w.list_off;
+    a.lists_bound = seg_bound;
+    a.flat = 1;
     a.out = out;
     return recd_launch_segsum(ctx, a);
 }
@@ -498,15 +500,18 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
                                            const float *grad_out, const int32_t *inverse,
                                            const int64_t *feat_uoff, const int64_t *u_values,
                                            const int64_t *u_offsets, const int64_t *rows,
-                                           int64_t M_cap, int64_t *touched_rows, int64_t *feat_roff,
+                                           int64_t U_cap, int64_t M_cap, int64_t *touched_rows,
+                                           int64_t *feat_roff,
                                            float *grad_rows, void *const *tables,
                                            float *const *adagrad_state, float lr, float eps,
                                            int64_t *host_R)
 {
     if (!ctx)
         return RECD_EINVAL;
-    if (F < 0 || F > RECD_MAX_FEATURES || B < 0 || M_cap < 0)
+    if (F < 0 || F > RECD_MAX_FEATURES || B < 0 || M_cap < 0 || U_cap < 0)
         return recd_fail(ctx, RECD_EINVAL, "bad sizes");
+    if (U_cap > (int64_t)F * B)
+        U_cap = (int64_t)F * B;
     if (D <= 0 || D % 4 != 0 || (size_t)D * 4 > RECD_MAX_ROW_BYTES ||
         (D * 4 / 16 > 64 && D * 4 / 16 != 128 && D * 4 / 16 != 256))
         return recd_fail(ctx, RECD_EINVAL, "unsupported D=%d", D);
@@ -551,7 +556,7 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
         uint32_t *k0 = static_cast<uint32_t *>(w.k0), *k1 = static_cast<uint32_t *>(w.k1);
         hipLaunchKernelGGL(k_keys_rows, dim3((unsigned)((n_lists + 255) / 256)), dim3(256), 0, st,
                            inverse, feat_uoff, B, n_lists, k0, w.p0, w.n_dev);
-        RECD_TRY(group_and_sum<uint32_t>(ctx, w, k0, k1, n_lists, bits_for((uint64_t)n_lists), -1, F,
+        RECD_TRY(group_and_sum<uint32_t>(ctx, w, k0, k1, n_lists, U_cap, bits_for((uint64_t)n_lists), -1, F,
                                          grad_out, D, w.g_u, nullptr, nullptr));
     }
     // ---- step B: group unique-id positions by (feature, row), sum g_u rows into grad_rows --------
@@ -564,13 +569,13 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
             uint32_t *k0 = static_cast<uint32_t *>(w.k0), *k1 = static_cast<uint32_t *>(w.k1);
             hipLaunchKernelGGL((k_keys_ids<uint32_t, SG>), dim3(kb), dim3(256), 0, st, u_values,
                                u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.p0, w.n_dev);
-            RECD_TRY(group_and_sum<uint32_t>(ctx, w, k0, k1, M_cap, bits, row_bits, F, w.g_u, D,
+            RECD_TRY(group_and_sum<uint32_t>(ctx, w, k0, k1, M_cap, M_cap, bits, row_bits, F, w.g_u, D,
                                              grad_rows, touched_rows, feat_roff));
         } else {
             uint64_t *k0 = static_cast<uint64_t *>(w.k0), *k1 = static_cast<uint64_t *>(w.k1);
             hipLaunchKernelGGL((k_keys_ids<uint64_t, SG>), dim3(kb), dim3(256), 0, st, u_values,
                                u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.p0, w.n_dev);
-            RECD_TRY(group_and_sum<uint64_t>(ctx, w, k0, k1, M_cap, bits, row_bits, F, w.g_u, D,
+            RECD_TRY(group_and_sum<uint64_t>(ctx, w, k0, k1, M_cap, M_cap, bits, row_bits, F, w.g_u, D,
                                              grad_rows, touched_rows, feat_roff));
         }
     }

@@ -75,11 +75,6 @@ recd_status recd_create(recd_ctx **out, int device, void *hip_stream, size_t wor
     void *p = nullptr;
     ok = ok && hipHostMalloc(&p, 8 * sizeof(int64_t), hipHostMallocDefault) == hipSuccess;
     ctx->host_pinned = static_cast<int64_t *>(p);
-    p = nullptr;
-    ok = ok && hipMalloc(&p, 64 * sizeof(uint32_t)) == hipSuccess;
-    ctx->queue_ctr = static_cast<uint32_t *>(p);
-    ok = ok && hipMemset(ctx->queue_ctr, 0, 64 * sizeof(uint32_t)) == hipSuccess;
-    ok = ok && hipDeviceSynchronize() == hipSuccess;
     if (ok && workspace_hint_bytes)
         ok = recd_reserve(ctx, workspace_hint_bytes) == RECD_OK;
     if (!ok) {
@@ -99,8 +94,6 @@ recd_status recd_destroy(recd_ctx *ctx)
     (void)hipStreamSynchronize(ctx->stream);
     if (ctx->ws)
         (void)hipFree(ctx->ws);
-    if (ctx->queue_ctr)
-        (void)hipFree(ctx->queue_ctr);
     if (ctx->host_pinned)
         (void)hipHostFree(ctx->host_pinned);
     delete ctx;
@@ -114,6 +107,19 @@ recd_status recd_set_option(recd_ctx *ctx, recd_option opt, int64_t value)
     switch (opt) {
     case RECD_OPT_VALIDATE: ctx->validate = value != 0; return RECD_OK;
     case RECD_OPT_WEAK_HASH: ctx->weak_hash = value != 0; return RECD_OK;
+    case RECD_OPT_TUNE_SEGSUM:
+        // value = lists_per_block + 100 * lists_in_flight_per_wave + 10000 * block_generations
+        //         + 1000000 * (1 = never use the XCD-aware mapping)
+        ctx->tune_lb = (int)(value % 100);
+        ctx->tune_nl = (int)(value / 100 % 100);
+        ctx->tune_gens = (int)(value / 10000 % 100);
+        ctx->tune_flat = (int)(value / 1000000 % 10);
+        if ((ctx->tune_lb != 0 && ctx->tune_lb != 4 && ctx->tune_lb != 8 && ctx->tune_lb != 16) ||
+            (ctx->tune_nl != 0 && ctx->tune_nl != 1 && ctx->tune_nl != 2 && ctx->tune_nl != 4)) {
+            ctx->tune_lb = ctx->tune_nl = ctx->tune_gens = ctx->tune_flat = 0;
+            return recd_fail(ctx, RECD_EINVAL, "bad RECD_OPT_TUNE_SEGSUM value");
+        }
+        return RECD_OK;
     }
     return recd_fail(ctx, RECD_EINVAL, "unknown option %d", (int)opt);
 }

@@ -14,9 +14,9 @@ struct recd_ctx {
     char *ws = nullptr;          // device workspace
     size_t ws_bytes = 0;
     int64_t *host_pinned = nullptr;  // 8 x int64 pinned staging for scalar results
-    uint32_t *queue_ctr = nullptr;   // device: 16 x uint32 work-queue counters, zero between kernels
     int validate = 0;
     int weak_hash = 0;
+    int tune_lb = 0, tune_nl = 0, tune_gens = 0, tune_flat = 0;  // launch-shape overrides of the gather-sum kernel (0 = automatic)
     int num_cu = 256;
     std::string err;
 };
@@ -73,6 +73,8 @@ struct SegSumArgs {
     const int64_t *list_off;  // device [F+1] or nullptr -> list_off[f] = f * lists_per_feature
     int64_t lists_per_feature;
     int64_t list_base;        // added to every list index (feature chunking of the KJT path)
+    int64_t lists_bound;      // host upper bound of the number of lists in this launch (sizes the grid)
+    int flat;                 // 1: no XCD-aware feature->block mapping
     void *out;                // [lists, D]
 };
 recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a);

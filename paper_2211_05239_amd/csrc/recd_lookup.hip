@@ -6,35 +6,32 @@
 //
 // Mapping to the machine (gfx950: 64-lane waves, 8 XCDs each with a private L2):
 //   * a row of D elements is covered by LPR lanes x 16 bytes (x VPL vectors per lane when the row is
-//     longer than 1 KiB); the 64/LPR lane groups of a wave take the ids of one list round-robin
-//     (id k of the list goes to group k mod G) and are combined by a fixed butterfly at the end, so
-//     the summation order is a function of the list alone, never of where the list sits in a batch;
-//   * every load instruction of a wave therefore fetches G whole rows as 16-byte-per-lane
-//     contiguous pieces, and UNR of them are issued before the first add to keep many rows in flight;
-//   * work is handed out in items of CH consecutive lists from eight queues, queue q holding the
-//     lists of the features f with f mod 8 = q.  A wave first drains the queue of the XCD it runs
-//     on, so that the hot rows of a table stay in one XCD's L2, then helps the other queues.
-//     The grid is persistent (a fixed number of blocks); the queues are atomic counters that the
-//     last wave to leave resets, so no host-side knowledge of the number of unique lists is needed.
+//     longer than 1 KiB).  The G = 64/LPR lane groups of a wave take the ids of a list round-robin
+//     (id k goes to group k mod G), each group adds its rows in order, and a fixed butterfly folds
+//     the groups.  Every load instruction of a wave thus fetches G whole rows as contiguous 16-byte
+//     pieces, and UNR loads are issued before the first add so that many rows are in flight.
+//   * a block of four waves owns LB consecutive lists.  Lists of at most 64 ids are summed by one
+//     wave each.  A longer list is summed by the whole block: its 64-id chunks go to the waves
+//     round-robin, the four wave partials are added in wave order.  Which path a list takes and the
+//     order of every addition depend on the list's length and content only, never on where the
+//     list sits in a batch: the deduplicated and the non-deduplicated lookup agree bit for bit.
+//   * blocks are dealt to lists statically (no atomics; the hardware's block dispatch balances the
+//     load).  With F a multiple of 8 the mapping is XCD-aware: block b serves the features
+//     f with f mod 8 = b mod 8, and since consecutive blocks go to consecutive XCDs, the hot rows of
+//     a table stay in one XCD's L2.  The number of lists may live on the device only (unique
+//     lists): the grid is sized from a host-side bound and every block strides until its queue is
+//     exhausted, so any grid size is correct.
 #include "recd_internal.h"
 
 #include <hip/hip_fp16.h>
 
 namespace {
 
-constexpr int kNQ = 8;                          // work queues = XCDs
-constexpr int kQF = RECD_F_PER_LAUNCH / kNQ;     // features per queue in one launch
-constexpr int kCH = 4;                          // lists per work item
+constexpr int kNQ = 8;         // XCDs
 constexpr int kBlock = 256;
-constexpr int kWavesPerBlock = kBlock / 64;
-
-__device__ __forceinline__ int xcc_id()
-{
-    // XCC_ID hardware register, bits [3:0]: the XCD this wave runs on.  Only locality depends on it.
-    int v;
-    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID, 0, 4)" : "=s"(v));
-    return v & (kNQ - 1);
-}
+constexpr int kWaves = kBlock / 64;
+constexpr int kMaxLB = 16;     // lists per block item (upper bound)
+constexpr int kChunk = 64;     // ids per chunk: a wave loads a chunk's ids with one instruction
 
 __device__ __forceinline__ int64_t uniform64(int64_t v)
 {
@@ -83,7 +80,7 @@ template <int TT> __device__ __forceinline__ void accumulate(float *acc, const u
     }
 }
 
-// store n fp32 accumulators (n = 4 or 8) as elements of type OT at dst (16-byte aligned pieces)
+// store N fp32 accumulators (N = 4 or 8) as elements of type OT at dst
 template <int OT, int N> __device__ __forceinline__ void store_row_piece(void *dst, const float *acc)
 {
     if constexpr (OT == RECD_F32) {
@@ -119,173 +116,325 @@ struct SegSumParams {
     int64_t lists_per_feature;
     int64_t list_base;
     void *out;
-    uint32_t *ctr;  // [0..7] queue heads, [8] waves done
     int F;
     int D;
     int vecs_per_row;  // D / elements per 16-byte vector
+    int nq;            // 8: XCD-aware queues (feature f -> queue f mod 8); 1: one flat queue
+    int lb;            // lists per block item, <= kMaxLB
 };
 
-template <int LPR, int VPL, int TT, int OT, typename IdxT>
-__global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p)
+// Adds the rows of NL chunks (chunk j: ns[j] <= 64 ids starting at values[starts[j]], rows of
+// tables[j]) into acc[j], all NL chunks in flight together.  Inside a chunk, lane group g adds the ids
+// g, g+G, g+2G, ... in that order, whatever NL and US are.
+template <int LPR, int VPL, int TT, typename IdxT, int NL, int US>
+__device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL],
+                                           const char *const *tables, const IdxT *values,
+                                           const int64_t *starts, const int *ns, int64_t row_bytes,
+                                           int lane, int g, int r, bool piece_ok)
 {
     constexpr int EPV = Elem<TT>::per_vec;
     constexpr int G = 64 / LPR;
-    constexpr int UNR = (VPL == 1) ? 8 : (VPL == 2 ? 4 : 2);
+    int64_t my_id[NL];
+    int nmax = 0;
+#pragma unroll
+    for (int j = 0; j < NL; j++) {
+        my_id[j] = lane < ns[j] ? (int64_t)values[starts[j] + lane] : 0;
+        nmax = ns[j] > nmax ? ns[j] : nmax;
+    }
+    for (int k0 = 0; k0 < nmax; k0 += G * US) {
+        uint4 v[NL][US][VPL];
+#pragma unroll
+        for (int j = 0; j < NL; j++)
+#pragma unroll
+            for (int u = 0; u < US; u++) {
+                const int idx = k0 + u * G + g;
+                const int64_t id = __shfl(my_id[j], idx & 63);
+                const char *src = tables[j] + id * row_bytes + (int64_t)r * 16;
+#pragma unroll
+                for (int w = 0; w < VPL; w++) {
+                    if (idx < ns[j] && piece_ok)
+                        v[j][u][w] = *reinterpret_cast<const uint4 *>(src + (int64_t)w * LPR * 16);
+                    else
+                        v[j][u][w] = make_uint4(0, 0, 0, 0);
+                }
+            }
+#pragma unroll
+        for (int j = 0; j < NL; j++)
+#pragma unroll
+            for (int u = 0; u < US; u++)
+#pragma unroll
+                for (int w = 0; w < VPL; w++)
+                    accumulate<TT>(acc[j] + w * EPV, v[j][u][w]);
+    }
+}
+
+template <int LPR, int VPL, int TT, int OT, typename IdxT, int NL>
+__global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p)
+{
+    constexpr int EPV = Elem<TT>::per_vec;
     constexpr int NACC = EPV * VPL;
+    constexpr int ROWF = LPR * NACC;                      // floats of one (padded) row
+    constexpr int OB = (OT == RECD_F32) ? EPV * 4 : 16;   // bytes a lane writes per vector
+    constexpr int UNR = (VPL == 1) ? 8 : (VPL == 2 ? 4 : 2);
+    constexpr int US = UNR / NL > 0 ? UNR / NL : 1;       // loads per list and round when NL lists share a wave
+    constexpr int LL = ROWF <= 256 ? 4 : (ROWF <= 512 ? 2 : 1);  // long lists folded per barrier pair
 
     __shared__ int64_t s_loff[RECD_F_PER_LAUNCH + 1];
-    __shared__ int64_t s_qpref[kNQ][kQF + 1];
+    __shared__ int64_t s_qpref[RECD_F_PER_LAUNCH + 1];
+    __shared__ int64_t s_start[kMaxLB], s_end[kMaxLB], s_list[kMaxLB];
+    __shared__ int s_feat[kMaxLB];
+    __shared__ float s_part[LL][kWaves][ROWF];
 
     const int tid = threadIdx.x;
+    const int lane = tid & 63, wv = tid >> 6;
+    const int nq = p.nq;
+    const int q = nq == 1 ? 0 : (int)(blockIdx.x % kNQ);
+    const int64_t item0 = nq == 1 ? blockIdx.x : blockIdx.x / kNQ;
+    const int64_t item_stride = nq == 1 ? gridDim.x : gridDim.x / kNQ;
+    const int nslots = (p.F - q + nq - 1) / nq;  // features in my queue: q, q+nq, ...
+
     for (int f = tid; f <= p.F; f += kBlock)
         s_loff[f] = p.list_off ? p.list_off[f] : (int64_t)f * p.lists_per_feature;
     __syncthreads();
-    if (tid < kNQ) {
-        int64_t run = 0;
-        s_qpref[tid][0] = 0;
-        for (int k = 0; k < kQF; k++) {
-            int f = tid + k * kNQ;
-            if (f < p.F)
-                run += s_loff[f + 1] - s_loff[f];
-            s_qpref[tid][k + 1] = run;
+    if (wv == 0) {
+        // exclusive prefix of my queue's per-feature list counts: two slots per lane
+        const int k0 = 2 * lane, k1 = 2 * lane + 1;
+        const int f0 = q + k0 * nq, f1 = q + k1 * nq;
+        const int64_t c0 = k0 < nslots ? s_loff[f0 + 1] - s_loff[f0] : 0;
+        const int64_t c1 = k1 < nslots ? s_loff[f1 + 1] - s_loff[f1] : 0;
+        int64_t inc = c0 + c1;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int64_t x = __shfl_up(inc, d);
+            if (lane >= d)
+                inc += x;
         }
+        const int64_t ex = inc - c0 - c1;
+        if (k0 < nslots)
+            s_qpref[k0] = ex;
+        if (k1 < nslots)
+            s_qpref[k1] = ex + c0;
+        const int64_t all = __shfl(inc, 63);
+        if (lane == 0)
+            s_qpref[nslots] = all;
     }
     __syncthreads();
+    const int64_t total = s_qpref[nslots];
 
-    const int lane = tid & 63;
-    const int g = lane / LPR;       // lane group = which of the G rows of a load
-    const int r = lane % LPR;       // 16-byte piece of the row
+    const int g = lane / LPR;   // lane group = which of the G rows of a load
+    const int r = lane % LPR;   // 16-byte piece of the row
     const bool piece_ok = r < p.vecs_per_row || VPL > 1;
     const IdxT *values = static_cast<const IdxT *>(p.values);
     const int64_t row_bytes = (int64_t)p.D * (TT == RECD_F32 ? 4 : 2);
     const int64_t out_row_bytes = (int64_t)p.D * (OT == RECD_F32 ? 4 : 2);
+    const int lb = p.lb;
 
-    int q = xcc_id();
-    for (int tried = 0; tried < kNQ;) {
-        uint32_t item = 0;
-        if (lane == 0)
-            item = atomicAdd(&p.ctr[q], 1u);
-        item = __builtin_amdgcn_readfirstlane(item);
-        const int64_t total = s_qpref[q][kQF];
-        int64_t t0 = (int64_t)item * kCH;
-        if (t0 >= total) {
-            q = (q + 1) & (kNQ - 1);
-            tried++;
-            continue;
-        }
-        int64_t t1 = t0 + kCH < total ? t0 + kCH : total;
-        int k = 0;
-        for (int64_t t = t0; t < t1; t++) {
-            while (t >= s_qpref[q][k + 1])
-                k++;
-            const int f = q + k * kNQ;
-            const int64_t l = p.list_base + s_loff[f] + (t - s_qpref[q][k]);
-            const char *table = static_cast<const char *>(p.tables.p[f]);
-            const int64_t start = uniform64(p.offsets[l]), end = uniform64(p.offsets[l + 1]);
-
-            float acc[NACC];
+    auto fold_groups = [&](float *acc) {
+#pragma unroll
+        for (int s = LPR; s < 64; s <<= 1)
 #pragma unroll
             for (int i = 0; i < NACC; i++)
-                acc[i] = 0.f;
+                acc[i] += __shfl_xor(acc[i], s);
+    };
 
-            for (int64_t base = start; base < end; base += 64) {
-                const int n = (int)((end - base) < 64 ? (end - base) : 64);
-                int64_t my_id = 0;
-                if (lane < n)
-                    my_id = (int64_t)values[base + lane];
-                for (int k0 = 0; k0 < n; k0 += G * UNR) {
-                    uint4 v[UNR][VPL];
-#pragma unroll
-                    for (int u = 0; u < UNR; u++) {
-                        const int idx = k0 + u * G + g;
-                        const int64_t id = __shfl(my_id, idx & 63);
-                        const char *src = table + id * row_bytes + (int64_t)r * 16;
-#pragma unroll
-                        for (int w = 0; w < VPL; w++) {
-                            if (idx < n && piece_ok)
-                                v[u][w] = *reinterpret_cast<const uint4 *>(src + (int64_t)w * LPR * 16);
-                            else
-                                v[u][w] = make_uint4(0, 0, 0, 0);
-                        }
-                    }
-#pragma unroll
-                    for (int u = 0; u < UNR; u++)
-#pragma unroll
-                        for (int w = 0; w < VPL; w++)
-                            accumulate<TT>(acc + w * EPV, v[u][w]);
-                }
+    for (int64_t item = item0; item * lb < total; item += item_stride) {
+        const int64_t t0 = item * lb;
+        const int cnt = (int)(total - t0 < lb ? total - t0 : lb);
+        __syncthreads();  // the previous item no longer reads the shared arrays
+        if (tid < cnt) {
+            const int64_t t = t0 + tid;
+            int lo = 0, hi = nslots;  // slot with s_qpref[slot] <= t < s_qpref[slot+1]
+            while (hi - lo > 1) {
+                const int mid = (lo + hi) >> 1;
+                if (s_qpref[mid] <= t)
+                    lo = mid;
+                else
+                    hi = mid;
             }
-            // fold the G lane groups: fixed butterfly, group 0 ends up with the total
-#pragma unroll
-            for (int s = LPR; s < 64; s <<= 1)
+            const int f = q + lo * nq;
+            const int64_t l = p.list_base + s_loff[f] + (t - s_qpref[lo]);
+            s_feat[tid] = f;
+            s_list[tid] = l;
+            s_start[tid] = p.offsets[l];
+            s_end[tid] = p.offsets[l + 1];
+        }
+        __syncthreads();
+
+        // ---- long lists (> 64 ids): the whole block; the list's 64-id chunks go to the waves
+        //      round-robin, the four wave partials are added in wave order ------------------------
+        int batch[LL];
+        int nb = 0;
+        for (int j = 0; j <= cnt; j++) {
+            const bool is_long = j < cnt && s_end[j] - s_start[j] > kChunk;  // block-uniform
+            if (is_long) {
+                const int64_t start = s_start[j], end = s_end[j];
+                const char *table = static_cast<const char *>(p.tables.p[s_feat[j]]);
+                float acc[1][NACC];
 #pragma unroll
                 for (int i = 0; i < NACC; i++)
-                    acc[i] += __shfl_xor(acc[i], s);
-
-            if (g == 0 && piece_ok) {
-                char *dst = static_cast<char *>(p.out) + l * out_row_bytes;
-#pragma unroll
-                for (int w = 0; w < VPL; w++) {
-                    constexpr int OB = (OT == RECD_F32) ? EPV * 4 : 16;  // bytes this lane writes per vector
-                    store_row_piece<OT, EPV>(dst + ((int64_t)w * LPR + r) * OB, acc + w * EPV);
+                    acc[0][i] = 0.f;
+                for (int64_t base = start + (int64_t)wv * kChunk; base < end; base += kWaves * kChunk) {
+                    const int n = (int)(end - base < kChunk ? end - base : kChunk);
+                    add_chunks<LPR, VPL, TT, IdxT, 1, UNR>(acc, &table, values, &base, &n, row_bytes, lane,
+                                                           g, r, piece_ok);
                 }
+                fold_groups(acc[0]);
+                if (g == 0) {
+#pragma unroll
+                    for (int w = 0; w < VPL; w++)
+#pragma unroll
+                        for (int i = 0; i < EPV; i++)
+                            s_part[nb][wv][(w * LPR + r) * EPV + i] = acc[0][w * EPV + i];
+                }
+                batch[nb++] = j;
+            }
+            if (nb == LL || (j == cnt && nb > 0)) {
+                __syncthreads();
+                for (int e = wv; e < nb; e += kWaves) {
+                    if (g == 0 && piece_ok) {
+                        char *dst = static_cast<char *>(p.out) + s_list[batch[e]] * out_row_bytes;
+#pragma unroll
+                        for (int w = 0; w < VPL; w++) {
+                            float tot[EPV];
+#pragma unroll
+                            for (int i = 0; i < EPV; i++) {
+                                const int x = (w * LPR + r) * EPV + i;
+                                tot[i] = ((s_part[e][0][x] + s_part[e][1][x]) + s_part[e][2][x]) +
+                                         s_part[e][3][x];
+                            }
+                            store_row_piece<OT, EPV>(dst + ((int64_t)w * LPR + r) * OB, tot);
+                        }
+                    }
+                }
+                __syncthreads();
+                nb = 0;
             }
         }
-    }
 
-    // the last wave to leave re-arms the queues for the next launch
-    if (lane == 0) {
-        __threadfence();
-        const uint32_t waves = gridDim.x * kWavesPerBlock;
-        if (atomicAdd(&p.ctr[kNQ], 1u) == waves - 1) {
-            for (int i = 0; i <= kNQ; i++)
-                atomicExch(&p.ctr[i], 0u);
+        // ---- short lists (one chunk at most): wave w takes lists w, w+4, ... of the item, NL of
+        //      them in flight together -----------------------------------------------------------
+        for (int k0 = 0; wv + k0 * kWaves < cnt; k0 += NL) {
+            const char *tabs[NL];
+            int64_t starts[NL];
+            int ns[NL];
+            bool any = false;
+#pragma unroll
+            for (int k = 0; k < NL; k++) {
+                const int j = wv + (k0 + k) * kWaves;
+                tabs[k] = static_cast<const char *>(p.tables.p[0]);
+                starts[k] = 0;
+                ns[k] = -1;
+                if (j < cnt) {
+                    const int64_t len = s_end[j] - s_start[j];
+                    if (len <= kChunk) {
+                        tabs[k] = static_cast<const char *>(p.tables.p[s_feat[j]]);
+                        starts[k] = s_start[j];
+                        ns[k] = (int)len;
+                        any = true;
+                    }
+                }
+            }
+            if (!any)
+                continue;
+            float acc[NL][NACC];
+#pragma unroll
+            for (int k = 0; k < NL; k++)
+#pragma unroll
+                for (int i = 0; i < NACC; i++)
+                    acc[k][i] = 0.f;
+            add_chunks<LPR, VPL, TT, IdxT, NL, US>(acc, tabs, values, starts, ns, row_bytes, lane, g, r,
+                                                   piece_ok);
+#pragma unroll
+            for (int k = 0; k < NL; k++) {
+                if (ns[k] >= 0) {
+                    fold_groups(acc[k]);
+                    if (g == 0 && piece_ok) {
+                        char *dst = static_cast<char *>(p.out) +
+                                    s_list[wv + (k0 + k) * kWaves] * out_row_bytes;
+#pragma unroll
+                        for (int w = 0; w < VPL; w++)
+                            store_row_piece<OT, EPV>(dst + ((int64_t)w * LPR + r) * OB, acc[k] + w * EPV);
+                    }
+                }
+            }
         }
     }
 }
 
 template <int LPR, int VPL, int TT, int OT, typename IdxT>
-void launch_one(hipStream_t st, int blocks, const SegSumParams &p)
+void launch_one(hipStream_t st, int blocks, int nl, const SegSumParams &p)
 {
-    hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT>), dim3(blocks), dim3(kBlock), 0, st, p);
+    if (nl == 4)
+        hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT, 4>), dim3(blocks), dim3(kBlock), 0, st, p);
+    else if (nl == 2)
+        hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT, 2>), dim3(blocks), dim3(kBlock), 0, st, p);
+    else
+        hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT, 1>), dim3(blocks), dim3(kBlock), 0, st, p);
 }
 
 template <int TT, int OT, typename IdxT>
-bool launch_shape(hipStream_t st, int blocks, int vecs, const SegSumParams &p)
+bool launch_shape(hipStream_t st, int blocks, int nl, int vecs, const SegSumParams &p)
 {
-    if (vecs <= 8) launch_one<8, 1, TT, OT, IdxT>(st, blocks, p);
-    else if (vecs <= 16) launch_one<16, 1, TT, OT, IdxT>(st, blocks, p);
-    else if (vecs <= 32) launch_one<32, 1, TT, OT, IdxT>(st, blocks, p);
-    else if (vecs <= 64) launch_one<64, 1, TT, OT, IdxT>(st, blocks, p);
-    else if (vecs == 128) launch_one<64, 2, TT, OT, IdxT>(st, blocks, p);
-    else if (vecs == 256) launch_one<64, 4, TT, OT, IdxT>(st, blocks, p);
+    if (vecs <= 8) launch_one<8, 1, TT, OT, IdxT>(st, blocks, nl, p);
+    else if (vecs <= 16) launch_one<16, 1, TT, OT, IdxT>(st, blocks, nl, p);
+    else if (vecs <= 32) launch_one<32, 1, TT, OT, IdxT>(st, blocks, nl, p);
+    else if (vecs <= 64) launch_one<64, 1, TT, OT, IdxT>(st, blocks, nl, p);
+    else if (vecs == 128) launch_one<64, 2, TT, OT, IdxT>(st, blocks, nl, p);
+    else if (vecs == 256) launch_one<64, 4, TT, OT, IdxT>(st, blocks, nl, p);
     else return false;
     return true;
 }
 
 // ---- expand: out[f,b,:] = pooled[feat_uoff[f] + inverse[f,b], :]  (16-byte pieces) ------------
-__global__ __launch_bounds__(kBlock) void k_expand(const uint4 *__restrict__ pooled,
+// A block copies kExpandRPT sweeps of (256 / vecs_per_row) consecutive output rows.  Every thread
+// first loads the inverse entries of all its rows, then all its pooled pieces, then stores them
+// with streaming (non-temporal) stores: the output is written once and never re-read here, while
+// the pooled rows, shared by the consecutive samples of a session, should stay in L2.
+constexpr int kExpandRPT = 8;
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+template <bool TWO_FEATURES>
+__global__ __launch_bounds__(kBlock) void k_expand(const u32x4 *__restrict__ pooled,
                                                    const int64_t *__restrict__ feat_uoff,
                                                    const int32_t *__restrict__ inverse,
-                                                   uint4 *__restrict__ out, int64_t B,
-                                                   int64_t n_rows, int vecs_per_row,
-                                                   int rows_per_block)
+                                                   u32x4 *__restrict__ out, uint32_t B,
+                                                   uint32_t n_rows, int vecs_per_row)
 {
-    // a block copies rows_per_block consecutive output rows; thread t moves piece (t % vecs) of row
-    // (t / vecs) and strides by blockDim/vecs rows
-    const int64_t row0 = (int64_t)blockIdx.x * rows_per_block;
-    const int lanes_rows = kBlock / vecs_per_row;  // rows moved per sweep (vecs_per_row <= 256)
-    const int piece = threadIdx.x % vecs_per_row;
-    const int sub = threadIdx.x / vecs_per_row;
-    if (sub >= lanes_rows)
+    const uint32_t rows_per_sweep = kBlock / vecs_per_row;  // vecs_per_row <= 256
+    const uint32_t piece = threadIdx.x % vecs_per_row;
+    const uint32_t sub = threadIdx.x / vecs_per_row;
+    if (sub >= rows_per_sweep)
         return;
-    for (int i = sub; i < rows_per_block; i += lanes_rows) {
-        const int64_t row = row0 + i;
-        if (row >= n_rows)
-            break;
-        const int64_t f = row / B;
-        const int64_t u = feat_uoff[f] + (int64_t)inverse[row];
-        out[row * vecs_per_row + piece] = pooled[u * vecs_per_row + piece];
+    const uint32_t row0 = blockIdx.x * rows_per_sweep * kExpandRPT;
+    // TWO_FEATURES: B >= rows per block, so the block's rows lie in features f0 and f0 + 1 only
+    const uint32_t f0 = row0 / B;
+    const uint32_t next_start = (f0 + 1) * B;
+    const int64_t base0 = feat_uoff[f0];
+    const int64_t base1 = TWO_FEATURES ? feat_uoff[f0 + (next_start < n_rows ? 1 : 0)] : 0;
+    // loads use a clamped row so that none of them is conditional; only the store is predicated
+    int32_t inv[kExpandRPT];
+    uint32_t rows[kExpandRPT];
+#pragma unroll
+    for (int k = 0; k < kExpandRPT; k++) {
+        const uint32_t row = row0 + k * rows_per_sweep + sub;
+        rows[k] = row < n_rows ? row : n_rows - 1;
+        inv[k] = inverse[rows[k]];
+    }
+    u32x4 v[kExpandRPT];
+#pragma unroll
+    for (int k = 0; k < kExpandRPT; k++) {
+        int64_t base;
+        if (TWO_FEATURES)
+            base = rows[k] >= next_start ? base1 : base0;
+        else
+            base = feat_uoff[rows[k] / B];
+        v[k] = pooled[(base + inv[k]) * vecs_per_row + piece];
+    }
+#pragma unroll
+    for (int k = 0; k < kExpandRPT; k++) {
+        const uint32_t row = row0 + k * rows_per_sweep + sub;
+        if (row < n_rows)
+            __builtin_nontemporal_store(v[k], &out[(int64_t)row * vecs_per_row + piece]);
     }
 }
 
@@ -328,28 +477,42 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     p.lists_per_feature = a.lists_per_feature;
     p.list_base = a.list_base;
     p.out = a.out;
-    p.ctr = ctx->queue_ctr;
     p.F = a.F;
     p.D = a.D;
     const int epv = a.table_dt == RECD_F32 ? 4 : 8;
     p.vecs_per_row = a.D / epv;
-    const int blocks = ctx->num_cu * 8;
+    // Launch shape.  Any grid is correct (blocks stride over their queue); these choices only
+    // decide how well the chip is filled.
+    const int64_t n = a.lists_bound > 0 ? a.lists_bound : 1;
+    p.nq = (a.F >= kNQ && a.F % kNQ == 0 && !a.flat && !ctx->tune_flat) ? kNQ : 1;
+    p.lb = n >= (512 << 10) ? 16 : (n >= (128 << 10) ? 8 : 4);
+    int nl = 1;
+    if (ctx->tune_lb > 0)
+        p.lb = ctx->tune_lb;
+    if (ctx->tune_nl > 0)
+        nl = ctx->tune_nl;
+    const int64_t items = (n + p.lb - 1) / p.lb;
+    int64_t nblk = p.nq == 1 ? items : kNQ * ((items + kNQ - 1) / kNQ + (items / kNQ) / 8 + 1);
+    const int64_t cap = (int64_t)ctx->num_cu * 8 * (ctx->tune_gens > 0 ? ctx->tune_gens : 64);
+    if (nblk > cap)
+        nblk = cap / kNQ * kNQ;
+    const int blocks = (int)nblk;
     bool ok = false;
     hipStream_t st = ctx->stream;
     const int v = p.vecs_per_row;
     if (a.values_are_i32) {
         if (a.table_dt == RECD_F32 && a.out_dt == RECD_F32)
-            ok = launch_shape<RECD_F32, RECD_F32, int32_t>(st, blocks, v, p);
+            ok = launch_shape<RECD_F32, RECD_F32, int32_t>(st, blocks, nl, v, p);
     } else if (a.table_dt == RECD_F32 && a.out_dt == RECD_F32)
-        ok = launch_shape<RECD_F32, RECD_F32, int64_t>(st, blocks, v, p);
+        ok = launch_shape<RECD_F32, RECD_F32, int64_t>(st, blocks, nl, v, p);
     else if (a.table_dt == RECD_F16 && a.out_dt == RECD_F16)
-        ok = launch_shape<RECD_F16, RECD_F16, int64_t>(st, blocks, v, p);
+        ok = launch_shape<RECD_F16, RECD_F16, int64_t>(st, blocks, nl, v, p);
     else if (a.table_dt == RECD_F16 && a.out_dt == RECD_F32)
-        ok = launch_shape<RECD_F16, RECD_F32, int64_t>(st, blocks, v, p);
+        ok = launch_shape<RECD_F16, RECD_F32, int64_t>(st, blocks, nl, v, p);
     else if (a.table_dt == RECD_BF16 && a.out_dt == RECD_BF16)
-        ok = launch_shape<RECD_BF16, RECD_BF16, int64_t>(st, blocks, v, p);
+        ok = launch_shape<RECD_BF16, RECD_BF16, int64_t>(st, blocks, nl, v, p);
     else if (a.table_dt == RECD_BF16 && a.out_dt == RECD_F32)
-        ok = launch_shape<RECD_BF16, RECD_F32, int64_t>(st, blocks, v, p);
+        ok = launch_shape<RECD_BF16, RECD_F32, int64_t>(st, blocks, nl, v, p);
     if (!ok)
         return recd_fail(ctx, RECD_EINVAL, "unsupported row shape: D=%d table dtype %d out dtype %d",
                          a.D, (int)a.table_dt, (int)a.out_dt);
@@ -459,6 +622,7 @@ recd_status recd_pooled_lookup_unique(recd_ctx *ctx, int F, int D, recd_dtype ta
         a.values_are_i32 = 0;
         a.offsets = u_offsets;
         a.list_off = feat_uoff + f0;
+        a.lists_bound = max_lists;
         a.out = pooled;
         RECD_TRY(recd_launch_segsum(ctx, a));
     }
@@ -500,6 +664,7 @@ recd_status recd_kjt_pooled_lookup(recd_ctx *ctx, int F, int64_t B, int D, recd_
         a.list_off = nullptr;
         a.lists_per_feature = B;
         a.list_base = (int64_t)f0 * B;
+        a.lists_bound = (int64_t)a.F * B;
         a.out = out;
         RECD_TRY(recd_launch_segsum(ctx, a));
     }
@@ -520,13 +685,20 @@ recd_status recd_expand_inverse(recd_ctx *ctx, int F, int64_t B, int D, recd_dty
     RECD_HIP(ctx, hipSetDevice(ctx->device));
     const int vecs = (int)((size_t)D * elem_size(dt) / 16);
     const int64_t n_rows = (int64_t)F * B;
-    const int rows_per_block = 32;
+    const int64_t rows_per_block = (int64_t)(kBlock / vecs) * kExpandRPT;
     const int64_t blocks = (n_rows + rows_per_block - 1) / rows_per_block;
     if (blocks > 0x7fffffff)
         return recd_fail(ctx, RECD_EINVAL, "F*B too large");
-    hipLaunchKernelGGL(k_expand, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
-                       static_cast<const uint4 *>(pooled), feat_uoff, inverse,
-                       static_cast<uint4 *>(out), B, n_rows, vecs, rows_per_block);
+    if (n_rows >= (int64_t)1 << 31)
+        return recd_fail(ctx, RECD_EINVAL, "F*B must stay below 2^31");
+    if (B >= rows_per_block)
+        hipLaunchKernelGGL(k_expand<true>, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
+                           static_cast<const u32x4 *>(pooled), feat_uoff, inverse,
+                           static_cast<u32x4 *>(out), (uint32_t)B, (uint32_t)n_rows, vecs);
+    else
+        hipLaunchKernelGGL(k_expand<false>, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
+                           static_cast<const u32x4 *>(pooled), feat_uoff, inverse,
+                           static_cast<u32x4 *>(out), (uint32_t)B, (uint32_t)n_rows, vecs);
     RECD_HIP(ctx, hipGetLastError());
     return RECD_OK;
 }

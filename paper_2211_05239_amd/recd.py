@@ -25,7 +25,7 @@ _lib = C.CDLL(LIB_PATH)
 RECD_OK = 0
 RECD_EINVAL, RECD_ENOMEM, RECD_EHIP, RECD_EBOUNDS, RECD_ECAPACITY = -1, -2, -3, -4, -5
 RECD_F32, RECD_F16, RECD_BF16 = 0, 1, 2
-RECD_OPT_VALIDATE, RECD_OPT_WEAK_HASH = 1, 2
+RECD_OPT_VALIDATE, RECD_OPT_WEAK_HASH, RECD_OPT_TUNE_SEGSUM = 1, 2, 3
 
 EXPORTED = [
     "recd_create", "recd_destroy", "recd_set_option", "recd_last_error", "recd_status_string",
@@ -49,7 +49,8 @@ _lib.recd_expand_inverse.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, C.c_int, 
 _lib.recd_kjt_pooled_lookup.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp,
                                         _vp, _vp]
 _lib.recd_backward_dedup.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, _vp, _vp, _vp, _vp, _vp, _vp,
-                                     C.c_int64, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]
+                                     C.c_int64, C.c_int64, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float,
+                                     _vp]
 for _n in EXPORTED:
     if _n not in ("recd_last_error", "recd_status_string"):
         getattr(_lib, _n).restype = C.c_int
@@ -148,7 +149,7 @@ class Context:
             _ptr(values), _ptr(offsets), _ptr(out)))
 
     def backward_dedup(self, F: int, B: int, grad_out, inverse, feat_uoff, u_values, u_offsets,
-                       rows: Sequence[int], M_cap: int, touched_rows, feat_roff, grad_rows,
+                       rows: Sequence[int], U_cap: int, M_cap: int, touched_rows, feat_roff, grad_rows,
                        tables=None, adagrad_state=None, lr: float = 0.0, eps: float = 0.0,
                        want_count: bool = False):
         D = grad_out.shape[-1]
@@ -158,6 +159,6 @@ class Context:
         host = (C.c_int64 * 1)(0) if want_count else None
         self._check(_lib.recd_backward_dedup(
             self._h, F, B, D, _ptr(grad_out), _ptr(inverse), _ptr(feat_uoff), _ptr(u_values),
-            _ptr(u_offsets), rows_arr, M_cap, _ptr(touched_rows), _ptr(feat_roff), _ptr(grad_rows),
+            _ptr(u_offsets), rows_arr, U_cap, M_cap, _ptr(touched_rows), _ptr(feat_roff), _ptr(grad_rows),
             tabs, state, lr, eps, host))
         return int(host[0]) if want_count else None

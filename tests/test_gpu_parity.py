@@ -247,7 +247,7 @@ def _backward_case(ctx, w, batch_index, with_adagrad=True):
     d_state = [gu.to_dev(s) for s in state0]
     lr, eps = 0.01, 1e-8
     R = ctx.backward_dedup(F, B, d_gout, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets,
-                           [w.rows] * F, ik.M, touched, feat_roff, grad_rows,
+                           [w.rows] * F, ik.U, ik.M, touched, feat_roff, grad_rows,
                            tables=d_tabs if with_adagrad else None,
                            adagrad_state=d_state if with_adagrad else None, lr=lr, eps=eps,
                            want_count=True)
@@ -298,6 +298,6 @@ def test_backward_no_ids(ctx):
     values, offsets, ik = gu.gpu_build(ctx, batch)
     feat_roff = torch.full((3,), -7, dtype=torch.int64, device="cuda")
     gout = torch.zeros(2, 2, 8, device="cuda")
-    R = ctx.backward_dedup(2, 2, gout, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [5, 5], 0,
+    R = ctx.backward_dedup(2, 2, gout, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [5, 5], ik.U, 0,
                            None, feat_roff, None, want_count=True)
     assert R == 0 and feat_roff.cpu().tolist() == [0, 0, 0]
