@@ -37,6 +37,9 @@ def parse_args():
                     help="features of batch 0 the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--sweep", action="store_true", help="also run the duplication sweep (cfg4, S in 1,2,4,8,32)")
     ap.add_argument("--forward-only", action="store_true", help="leave the backward pass out of the step")
+    ap.add_argument("--store-grad", action="store_true",
+                    help="also store the per-row gradients (default: the fused Adagrad update consumes them "
+                         "from registers)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates hardware byte counters)")
     return ap.parse_args()
@@ -45,7 +48,7 @@ def parse_args():
 class DeviceProblem:
     """Everything one workload needs on the device, allocated once at worst-case sizes."""
 
-    def __init__(self, torch, recd, synth, w, n_batches, need_backward):
+    def __init__(self, torch, recd, synth, w, n_batches, need_backward, store_grad=False):
         self.torch, self.w = torch, w
         F, B, D = w.F, w.B, w.D
         self.tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[w.table_dtype]
@@ -82,7 +85,7 @@ class DeviceProblem:
             self.grad_out.normal_(0.0, 0.01, generator=g)
             self.touched = torch.zeros(Mmax, dtype=torch.int64, device="cuda")
             self.feat_roff = torch.zeros(F + 1, dtype=torch.int64, device="cuda")
-            self.grad_rows = torch.zeros(Mmax, D, dtype=torch.float32, device="cuda")
+            self.grad_rows = torch.zeros(Mmax, D, dtype=torch.float32, device="cuda") if store_grad else None
             self.state = [torch.zeros(w.rows, dtype=torch.float32, device="cuda") for _ in range(F)]
         self.rows = [w.rows] * F
 
@@ -137,7 +140,7 @@ def event_ms(torch, fn, reps):
 
 
 def run_workload(torch, recd, synth, w, args, need_backward, detail=True):
-    P = DeviceProblem(torch, recd, synth, w, args.batches, need_backward)
+    P = DeviceProblem(torch, recd, synth, w, args.batches, need_backward, getattr(args, "store_grad", False))
     nb = len(P.batches)
     F, B, D = w.F, w.B, w.D
     e = 4 if w.table_dtype == "f32" else 2
@@ -309,7 +312,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B}, F={w.F}, mean session {w.S}, rows={w.rows}, D={w.D}, "
                                f"{w.table_dtype} tables; step = build_ikjt + pooled_lookup_unique + "
-                               f"expand_inverse" + (" + backward_dedup with row-wise Adagrad" if need_backward else ""),
+                               f"expand_inverse" + (" + backward_dedup with fused row-wise Adagrad"
+                                                     + ("" if args.store_grad else " (gradient rows consumed in registers, not stored)")
+                                                     if need_backward else ""),
                    "batches_rotated": len(P.batches)},
         "roofline": {"bound": "hbm", "kernel": "k_segsum (recd_pooled_lookup_unique)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",

@@ -151,7 +151,9 @@ recd_status recd_kjt_pooled_lookup(recd_ctx *ctx, int F, int64_t B, int D, recd_
  *    returned by recd_build_ikjt, avoid idle work).
  *    touched_rows: device int64, capacity M_cap: per feature the ascending distinct ids.
  *    feat_roff: device int64 [F+1] prefix sum of the per-feature distinct counts R_f.
- *    grad_rows: device fp32 [R, D], capacity M_cap rows, aligned with touched_rows.
+ *    grad_rows: device fp32 [R, D], capacity M_cap rows, aligned with touched_rows.  May be NULL
+ *    when the optimizer is on and F <= 128: the gradient rows are then consumed by the update
+ *    from registers and never stored.
  *    Optimizer (this build's reading, not in the paper): if tables != NULL, row-wise Adagrad is
  *    applied once per touched row with the aggregated gradient:
  *      m[r] += mean_d G[r,d]^2 ;  W[r,d] -= lr * G[r,d] / (sqrt(m[r]) + eps)

@@ -303,7 +303,8 @@ template <typename KeyT>
 __global__ void k_segments(const KeyT *__restrict__ keys, const int64_t *n_dev,
                            const uint32_t *__restrict__ segidx, int64_t *__restrict__ seg_start,
                            int64_t *__restrict__ list_off, int row_bits, int F,
-                           int64_t *__restrict__ touched_rows, int64_t *__restrict__ feat_roff)
+                           int64_t *__restrict__ touched_rows, int64_t *__restrict__ feat_roff,
+                           int32_t *__restrict__ seg_feat)
 {
     const int64_t n = *n_dev;
     if (n == 0) {
@@ -326,6 +327,7 @@ __global__ void k_segments(const KeyT *__restrict__ keys, const int64_t *n_dev,
             if (row_bits >= 0) {
                 touched_rows[sidx] = (int64_t)(keys[i] & (((KeyT)1 << row_bits) - 1));
                 const int f = (int)(keys[i] >> row_bits);
+                seg_feat[sidx] = f;
                 const int fprev = i == 0 ? -1 : (int)(keys[i - 1] >> row_bits);
                 for (int ff = fprev + 1; ff <= f; ff++)
                     feat_roff[ff] = sidx;
@@ -427,6 +429,7 @@ struct BwdWs {
     int64_t *n_dev, *list_off, *seg_start;
     void *k0, *k1;
     uint32_t *p0, *p1, *flag, *hist, *bsum;
+    int32_t *seg_feat;
     float *g_u;
     size_t bytes;
 };
@@ -448,6 +451,7 @@ BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D)
     w.p0 = c.take<uint32_t>(n_max);
     w.p1 = c.take<uint32_t>(n_max);
     w.flag = c.take<uint32_t>(n_max);
+    w.seg_feat = c.take<int32_t>(n_max);
     w.hist = c.take<uint32_t>(hist_n);
     w.bsum = c.take<uint32_t>((scan_max + kScanTile - 1) / kScanTile + 1);
     w.g_u = c.take<float>((size_t)u_cap * D);
@@ -458,7 +462,8 @@ BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D)
 template <typename KeyT>
 recd_status group_and_sum(recd_ctx *ctx, const BwdWs &w, KeyT *k0, KeyT *k1, int64_t n_cap,
                           int64_t seg_bound, int bits, int row_bits, int F, const void *table,
-                          int D, void *out, int64_t *touched_rows, int64_t *feat_roff)
+                          int D, void *out, int64_t *touched_rows, int64_t *feat_roff,
+                          const SegSumArgs *opt)
 {
     KeyT *ks;
     uint32_t *ps;
@@ -471,9 +476,14 @@ recd_status group_and_sum(recd_ctx *ctx, const BwdWs &w, KeyT *k0, KeyT *k1, int
     hipLaunchKernelGGL((k_heads<KeyT>), dim3(blocks), dim3(256), 0, st, ks, w.n_dev, w.flag);
     RECD_TRY(scan_u32(ctx, w.flag, w.n_dev, n_cap, w.bsum));
     hipLaunchKernelGGL((k_segments<KeyT>), dim3(blocks), dim3(256), 0, st, ks, w.n_dev, w.flag,
-                       w.seg_start, w.list_off, row_bits, F, touched_rows, feat_roff);
+                       w.seg_start, w.list_off, row_bits, F, touched_rows, feat_roff, w.seg_feat);
     RECD_HIP(ctx, hipGetLastError());
     SegSumArgs a{};
+    if (opt)
+        a = *opt;  // optimizer fields of the row-gradient site
+    a.site = row_bits >= 0 ? RECD_SITE_GRAD_ROWS : RECD_SITE_GRAD_LISTS;
+    a.opt_touched_rows = touched_rows;
+    a.opt_seg_feat = w.seg_feat;
     a.F = 1;
     a.D = D;
     a.table_dt = RECD_F32;
@@ -522,8 +532,12 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
         return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
     if (n_lists > 0 && (!grad_out || !inverse))
         return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
-    if (M_cap > 0 && (!u_values || !touched_rows || !grad_rows))
+    if (M_cap > 0 && (!u_values || !touched_rows))
         return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
+    if (M_cap > 0 && !grad_rows && !(tables && F <= RECD_F_PER_LAUNCH))
+        return recd_fail(ctx, RECD_EINVAL,
+                         "grad_rows may be NULL only with the optimizer and at most %d features",
+                         RECD_F_PER_LAUNCH);
     if ((tables == nullptr) != (adagrad_state == nullptr))
         return recd_fail(ctx, RECD_EINVAL, "tables and adagrad_state must be given together");
     int64_t max_rows = 1;
@@ -557,9 +571,20 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
         hipLaunchKernelGGL(k_keys_rows, dim3((unsigned)((n_lists + 255) / 256)), dim3(256), 0, st,
                            inverse, feat_uoff, B, n_lists, k0, w.p0, w.n_dev);
         RECD_TRY(group_and_sum<uint32_t>(ctx, w, k0, k1, n_lists, U_cap, bits_for((uint64_t)n_lists), -1, F,
-                                         grad_out, D, w.g_u, nullptr, nullptr));
+                                         grad_out, D, w.g_u, nullptr, nullptr, nullptr));
     }
     // ---- step B: group unique-id positions by (feature, row), sum g_u rows into grad_rows --------
+    // Row-wise Adagrad runs inside the row-gradient segment sum while the sum is still in
+    // registers; with more features than one launch carries it runs as a kernel of its own.
+    const bool fused = tables != nullptr && F <= RECD_F_PER_LAUNCH;
+    SegSumArgs oa{};
+    if (fused) {
+        oa.opt_n_feat = F;
+        oa.opt_w = reinterpret_cast<float *const *>(tables);
+        oa.opt_m = adagrad_state;
+        oa.opt_lr = lr;
+        oa.opt_eps = eps;
+    }
     {
         const int row_bits = bits_for((uint64_t)(max_rows - 1));
         const int bits = row_bits + bits_for((uint64_t)(F > 1 ? F - 1 : 1));
@@ -570,17 +595,17 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
             hipLaunchKernelGGL((k_keys_ids<uint32_t, SG>), dim3(kb), dim3(256), 0, st, u_values,
                                u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.p0, w.n_dev);
             RECD_TRY(group_and_sum<uint32_t>(ctx, w, k0, k1, M_cap, M_cap, bits, row_bits, F, w.g_u, D,
-                                             grad_rows, touched_rows, feat_roff));
+                                             grad_rows, touched_rows, feat_roff, fused ? &oa : nullptr));
         } else {
             uint64_t *k0 = static_cast<uint64_t *>(w.k0), *k1 = static_cast<uint64_t *>(w.k1);
             hipLaunchKernelGGL((k_keys_ids<uint64_t, SG>), dim3(kb), dim3(256), 0, st, u_values,
                                u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.p0, w.n_dev);
             RECD_TRY(group_and_sum<uint64_t>(ctx, w, k0, k1, M_cap, M_cap, bits, row_bits, F, w.g_u, D,
-                                             grad_rows, touched_rows, feat_roff));
+                                             grad_rows, touched_rows, feat_roff, fused ? &oa : nullptr));
         }
     }
     // ---- optimizer -------------------------------------------------------------------------------
-    if (tables) {
+    if (tables && !fused) {
         for (int f0 = 0; f0 < F; f0 += RECD_F_PER_LAUNCH) {
             OptPtrs ptrs;
             const int nf = F - f0 < RECD_F_PER_LAUNCH ? F - f0 : RECD_F_PER_LAUNCH;

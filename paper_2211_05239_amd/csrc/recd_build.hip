@@ -1,16 +1,20 @@
 // KJT -> IKJT builder (paper Sec. 4.2): which rows of a feature hold exactly the same list?
 //
 // Steps, all on the device, no host round trip:
-//   hash+insert  a group of SG lanes per list: 64-bit hash of the list (position-salted sum of mixed
-//                ids, so lanes can hash strided pieces and add), then open addressing into a
+//   hash+insert  a group of SG lanes per list.  A list equal to its predecessor in the batch (the
+//                common case once a session's samples are adjacent, Sec. 4.1) is only marked as a
+//                follower.  Any other list is a run head: its 64-bit hash (position-salted sum of mixed
+//                ids, so lanes hash strided pieces and add) is inserted by open addressing into a
 //                per-feature table whose slots hold (hash tag, sample index).  A slot belongs to one
 //                list *content*: a newcomer whose tag matches compares its list element by element
 //                with the slot's current sample and, if equal, lowers the slot's sample index with
 //                an atomic min; if not, it probes on.  Hash collisions therefore never merge lists.
-//   rep+flags    rep[f,b] = final sample index of the slot = smallest b' with the same list;
-//                first[f,b] = (rep == b); per-block sums of (first, first*len).
-//   scan         exclusive scan of those pairs over all F*B lists in (f,b) order: the unique-list
-//                number and the position of its ids in u_values, both in first-occurrence order.
+//   flags        a run head is a first occurrence iff its slot's final sample index is its own;
+//                per-block sums of (first, first*len) and the last run head of the block.
+//   scan         exclusive scan of those over all F*B lists in (f,b) order: the unique-list number
+//                and the position of its ids in u_values, both in first-occurrence order, and for
+//                followers the run head they copy (rep[f,b] = rep of the head = smallest b' with the
+//                same list).
 //   emit         inverse[f,b] = number[rep] - number[f,0]; first occurrences copy their ids.
 // The atomic min makes the result independent of insertion order: integer outputs are canonical.
 #include "recd_internal.h"
@@ -37,6 +41,10 @@ __global__ void k_fill_u64(uint64_t *p, int64_t n, uint64_t v)
         p[i] = v;
 }
 
+// Lists per lane group and launch: the group's lists are consecutive, and the first loads of all of
+// them are issued together so that one group keeps several memory requests in flight.
+constexpr int kLPG = 1;
+
 template <int SG>
 __global__ __launch_bounds__(256) void k_hash_insert(const int64_t *__restrict__ values,
                                                      const int64_t *__restrict__ offsets, int64_t B,
@@ -45,167 +53,274 @@ __global__ __launch_bounds__(256) void k_hash_insert(const int64_t *__restrict__
                                                      int weak_hash)
 {
     const int s = threadIdx.x % SG;
-    const int64_t l = (int64_t)blockIdx.x * (256 / SG) + threadIdx.x / SG;
-    if (l >= n_lists)
+    const int64_t l0 = ((int64_t)blockIdx.x * (256 / SG) + threadIdx.x / SG) * kLPG;
+    if (l0 >= n_lists)
         return;  // whole lane group leaves together
-    const int64_t f = l / B;
-    const int64_t b = l - f * B;
-    const int64_t start = offsets[l];
-    const int64_t len = offsets[l + 1] - start;
 
-    uint64_t h = 0;
-    for (int64_t t = s; t < len; t += SG)
-        h += mix64((uint64_t)values[start + t] + (uint64_t)(t + 1) * 0x9e3779b97f4a7c15ull);
+    // offsets of rows l0-1 .. l0+kLPG (clamped to the array)
+    int64_t off[kLPG + 2];
 #pragma unroll
-    for (int m = SG / 2; m > 0; m >>= 1)
-        h += __shfl_xor((unsigned long long)h, m, SG);
-    h = mix64(h ^ ((uint64_t)len * 0xd6e8feb86659fd93ull + 1ull));
-    if (weak_hash)
-        h = (uint64_t)len;  // test hook: only the exact comparison separates lists
-
-    const uint64_t tag = h >> 32;
-    const uint64_t mine = (tag << 32) | (uint64_t)b;
-    uint64_t *tab = table + (uint64_t)f * ((uint64_t)cap_mask + 1);
-    uint32_t slot = (uint32_t)h & cap_mask;
-    // The table has at least 2*B slots per feature, so an empty slot or the list's own class is met.
-    for (;;) {
-        unsigned long long old = 0;
-        if (s == 0)
-            old = atomicCAS(reinterpret_cast<unsigned long long *>(&tab[slot]), kEmpty, mine);
-        old = __shfl(old, 0, SG);
-        if (old == kEmpty)
-            break;
-        if ((old >> 32) == tag) {
-            const int64_t ol = f * B + (int64_t)(old & 0xffffffffull);
-            const int64_t ostart = offsets[ol];
-            int eq = (offsets[ol + 1] - ostart) == len;
-            if (eq)
-                for (int64_t t = s; t < len; t += SG)
-                    if (values[start + t] != values[ostart + t]) {
-                        eq = 0;
-                        break;
-                    }
+    for (int k = 0; k < kLPG + 2; k++) {
+        int64_t i = l0 - 1 + k;
+        i = i < 0 ? 0 : (i > n_lists ? n_lists : i);
+        off[k] = offsets[i];
+    }
+    int64_t start[kLPG], len[kLPG], pstart[kLPG];
+    int follows[kLPG];
+    bool live[kLPG];
+    uint64_t h[kLPG];
 #pragma unroll
-            for (int m = SG / 2; m > 0; m >>= 1)
-                eq &= __shfl_xor(eq, m, SG);
-            if (eq) {
-                if (s == 0)
-                    atomicMin(reinterpret_cast<unsigned long long *>(&tab[slot]), mine);
-                break;
+    for (int k = 0; k < kLPG; k++) {
+        const int64_t l = l0 + k;
+        live[k] = l < n_lists;
+        start[k] = off[k + 1];
+        len[k] = live[k] ? off[k + 2] - off[k + 1] : 0;
+        pstart[k] = off[k];
+        // the previous row of the same feature ends where this one starts
+        follows[k] = live[k] && (l % B) != 0 && (start[k] - pstart[k]) == len[k];
+        h[k] = 0;
+    }
+    // first SG ids of every list and of its predecessor: all loads in flight together
+    int64_t v[kLPG], pv[kLPG];
+#pragma unroll
+    for (int k = 0; k < kLPG; k++) {
+        v[k] = s < len[k] ? values[start[k] + s] : 0;
+        pv[k] = (follows[k] && s < len[k]) ? values[pstart[k] + s] : 0;
+    }
+#pragma unroll
+    for (int k = 0; k < kLPG; k++) {
+        if (s < len[k]) {
+            follows[k] &= pv[k] == v[k];
+            h[k] = mix64((uint64_t)v[k] + (uint64_t)(s + 1) * 0x9e3779b97f4a7c15ull);
+        }
+        // lists longer than the group: four strides per trip, all eight loads issued before use
+        for (int64_t t0 = s + SG; t0 < len[k]; t0 += 4 * SG) {
+            int64_t x[4], px[4];
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const int64_t t = t0 + u * SG;
+                x[u] = t < len[k] ? values[start[k] + t] : 0;
+                px[u] = (follows[k] && t < len[k]) ? values[pstart[k] + t] : 0;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; u++) {
+                const int64_t t = t0 + u * SG;
+                if (t < len[k]) {
+                    follows[k] &= px[u] == x[u];
+                    h[k] += mix64((uint64_t)x[u] + (uint64_t)(t + 1) * 0x9e3779b97f4a7c15ull);
+                }
             }
         }
-        slot = (slot + 1) & cap_mask;
     }
-    if (s == 0)
-        slot_of[l] = (int32_t)slot;
+#pragma unroll
+    for (int m = SG / 2; m > 0; m >>= 1)
+#pragma unroll
+        for (int k = 0; k < kLPG; k++) {
+            h[k] += __shfl_xor((unsigned long long)h[k], m, SG);
+            follows[k] &= __shfl_xor(follows[k], m, SG);
+        }
+
+#pragma unroll
+    for (int k = 0; k < kLPG; k++) {
+        if (!live[k])
+            continue;
+        const int64_t l = l0 + k;
+        if (follows[k]) {  // same list as the previous row: no table traffic at all
+            if (s == 0)
+                slot_of[l] = -1;
+            continue;
+        }
+        const int64_t f = l / B;
+        const int64_t b = l - f * B;
+        uint64_t hh = mix64(h[k] ^ ((uint64_t)len[k] * 0xd6e8feb86659fd93ull + 1ull));
+        if (weak_hash)
+            hh = (uint64_t)len[k];  // test hook: only the exact comparison separates lists
+        const uint64_t tag = hh >> 32;
+        const uint64_t mine = (tag << 32) | (uint64_t)b;
+        uint64_t *tab = table + (uint64_t)f * ((uint64_t)cap_mask + 1);
+        uint32_t slot = (uint32_t)hh & cap_mask;
+        // The table has at least 2*B slots per feature, so an empty slot or the list's own class
+        // is met.
+        for (;;) {
+            unsigned long long old = 0;
+            if (s == 0)
+                old = atomicCAS(reinterpret_cast<unsigned long long *>(&tab[slot]), kEmpty, mine);
+            old = __shfl(old, 0, SG);
+            if (old == kEmpty)
+                break;
+            if ((old >> 32) == tag) {
+                const int64_t ol = f * B + (int64_t)(old & 0xffffffffull);
+                const int64_t ostart = offsets[ol];
+                int eq = (offsets[ol + 1] - ostart) == len[k];
+                if (eq)
+                    for (int64_t t = s; t < len[k]; t += SG)
+                        if (values[start[k] + t] != values[ostart + t]) {
+                            eq = 0;
+                            break;
+                        }
+#pragma unroll
+                for (int m = SG / 2; m > 0; m >>= 1)
+                    eq &= __shfl_xor(eq, m, SG);
+                if (eq) {
+                    if (s == 0)
+                        atomicMin(reinterpret_cast<unsigned long long *>(&tab[slot]), mine);
+                    break;
+                }
+            }
+            slot = (slot + 1) & cap_mask;
+        }
+        if (s == 0)
+            slot_of[l] = (int32_t)slot;
+    }
 }
 
-// exclusive scan of a pair of int64 over a block of kScanBlock threads; totals returned to all
-__device__ __forceinline__ void block_scan2(int64_t a, int64_t b, int64_t &ea, int64_t &eb,
-                                            int64_t &ta, int64_t &tb)
+// Block-wide scan of (a, b, c): exclusive sums of a and b, and for c the maximum over the threads
+// up to and including this one.  Totals (sum a, sum b, max c) are returned to every thread.
+__device__ __forceinline__ void block_scan3(int64_t a, int64_t b, int64_t c, int64_t &ea, int64_t &eb,
+                                            int64_t &ic, int64_t &ta, int64_t &tb, int64_t &tc)
 {
-    __shared__ int64_t s_a[kScanBlock / 64], s_b[kScanBlock / 64];
+    __shared__ int64_t s_a[kScanBlock / 64], s_b[kScanBlock / 64], s_c[kScanBlock / 64];
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     int64_t ia = a, ib = b;
+    ic = c;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
-        int64_t xa = __shfl_up(ia, d), xb = __shfl_up(ib, d);
+        const int64_t xa = __shfl_up(ia, d), xb = __shfl_up(ib, d), xc = __shfl_up(ic, d);
         if (lane >= d) {
             ia += xa;
             ib += xb;
+            ic = xc > ic ? xc : ic;
         }
     }
-    __syncthreads();  // protect s_a/s_b against the previous use
+    __syncthreads();  // protect the shared arrays against the previous use
     if (lane == 63) {
         s_a[w] = ia;
         s_b[w] = ib;
+        s_c[w] = ic;
     }
     __syncthreads();
     int64_t oa = 0, ob = 0;
     ta = 0;
     tb = 0;
+    tc = -1;
     for (int i = 0; i < (int)(blockDim.x >> 6); i++) {
         if (i < w) {
             oa += s_a[i];
             ob += s_b[i];
+            ic = s_c[i] > ic ? s_c[i] : ic;
         }
         ta += s_a[i];
         tb += s_b[i];
+        tc = s_c[i] > tc ? s_c[i] : tc;
     }
     ea = oa + ia - a;
     eb = ob + ib - b;
 }
 
-__global__ __launch_bounds__(kScanBlock) void k_rep_flags(const int64_t *__restrict__ offsets,
-                                                          int64_t B, int64_t n_lists,
-                                                          const uint64_t *__restrict__ table,
-                                                          uint32_t cap_mask,
-                                                          const int32_t *__restrict__ slot_of,
-                                                          int32_t *__restrict__ rep,
-                                                          int64_t *__restrict__ bs_cnt,
-                                                          int64_t *__restrict__ bs_len)
+__global__ __launch_bounds__(kScanBlock) void k_flags(const int64_t *__restrict__ offsets, int64_t B,
+                                                      int64_t n_lists,
+                                                      const uint64_t *__restrict__ table,
+                                                      uint32_t cap_mask,
+                                                      const int32_t *__restrict__ slot_of,
+                                                      int64_t *__restrict__ bs_cnt,
+                                                      int64_t *__restrict__ bs_len,
+                                                      int64_t *__restrict__ bs_head)
 {
     const int64_t l = (int64_t)blockIdx.x * kScanBlock + threadIdx.x;
-    int64_t first = 0, flen = 0;
+    int64_t first = 0, flen = 0, head = -1;
     if (l < n_lists) {
-        const int64_t f = l / B, b = l - f * B;
-        const uint64_t e = table[(uint64_t)f * ((uint64_t)cap_mask + 1) + (uint32_t)slot_of[l]];
-        const int32_t r = (int32_t)(e & 0xffffffffull);
-        rep[l] = r;
-        if (r == b) {
-            first = 1;
-            flen = offsets[l + 1] - offsets[l];
+        const int32_t slot = slot_of[l];
+        if (slot >= 0) {
+            head = l;
+            const int64_t f = l / B, b = l - f * B;
+            const uint64_t e = table[(uint64_t)f * ((uint64_t)cap_mask + 1) + (uint32_t)slot];
+            if ((int64_t)(e & 0xffffffffull) == b) {
+                first = 1;
+                flen = offsets[l + 1] - offsets[l];
+            }
         }
     }
-    int64_t ea, eb, ta, tb;
-    block_scan2(first, flen, ea, eb, ta, tb);
+    int64_t ea, eb, ic, ta, tb, tc;
+    block_scan3(first, flen, head, ea, eb, ic, ta, tb, tc);
     if (threadIdx.x == 0) {
         bs_cnt[blockIdx.x] = ta;
         bs_len[blockIdx.x] = tb;
+        bs_head[blockIdx.x] = tc;
     }
 }
 
-// in-place exclusive scan of two int64 arrays of n entries by one block
-__global__ __launch_bounds__(kScanBlock) void k_scan_pairs(int64_t *a, int64_t *b, int64_t n)
+// one block, in place: exclusive sums of a and b, exclusive running maximum of c (-1 before the
+// first entry)
+__global__ __launch_bounds__(kScanBlock) void k_scan_blocks(int64_t *a, int64_t *b, int64_t *c, int64_t n)
 {
-    int64_t ca = 0, cb = 0;
+    int64_t ca = 0, cb = 0, cc = -1;
     for (int64_t base = 0; base < n; base += kScanBlock) {
         const int64_t i = base + threadIdx.x;
-        const int64_t va = i < n ? a[i] : 0, vb = i < n ? b[i] : 0;
-        int64_t ea, eb, ta, tb;
-        block_scan2(va, vb, ea, eb, ta, tb);
+        const int64_t va = i < n ? a[i] : 0, vb = i < n ? b[i] : 0, vc = i < n ? c[i] : -1;
+        int64_t ea, eb, ic, ta, tb, tc;
+        block_scan3(va, vb, vc, ea, eb, ic, ta, tb, tc);
+        // exclusive maximum: shift the inclusive one by one thread
+        int64_t prev = __shfl_up(ic, 1);
+        __shared__ int64_t s_last[kScanBlock / 64];
+        if ((threadIdx.x & 63) == 63)
+            s_last[threadIdx.x >> 6] = ic;
+        __syncthreads();
+        if ((threadIdx.x & 63) == 0)
+            prev = threadIdx.x == 0 ? -1 : s_last[(threadIdx.x >> 6) - 1];
+        __syncthreads();
         if (i < n) {
             a[i] = ca + ea;
             b[i] = cb + eb;
+            c[i] = prev > cc ? prev : cc;
         }
         ca += ta;
         cb += tb;
+        cc = tc > cc ? tc : cc;
     }
 }
 
 __global__ __launch_bounds__(kScanBlock) void k_number(const int64_t *__restrict__ offsets, int64_t B,
                                                        int64_t n_lists, int F,
-                                                       const int32_t *__restrict__ rep,
+                                                       const uint64_t *__restrict__ table,
+                                                       uint32_t cap_mask,
+                                                       const int32_t *__restrict__ slot_of,
                                                        const int64_t *__restrict__ bs_cnt,
                                                        const int64_t *__restrict__ bs_len,
+                                                       const int64_t *__restrict__ bs_head,
+                                                       int32_t *__restrict__ rep,
                                                        int32_t *__restrict__ number,
                                                        int64_t *__restrict__ u_offsets,
                                                        int64_t *__restrict__ feat_uoff,
                                                        int64_t *__restrict__ counts)
 {
     const int64_t l = (int64_t)blockIdx.x * kScanBlock + threadIdx.x;
-    int64_t first = 0, flen = 0, b = -1, f = 0;
+    int64_t first = 0, flen = 0, head = -1, b = -1, f = 0, my_rep = -1;
     if (l < n_lists) {
         f = l / B;
         b = l - f * B;
-        if (rep[l] == b) {
-            first = 1;
-            flen = offsets[l + 1] - offsets[l];
+        const int32_t slot = slot_of[l];
+        if (slot >= 0) {
+            head = l;
+            const uint64_t e = table[(uint64_t)f * ((uint64_t)cap_mask + 1) + (uint32_t)slot];
+            my_rep = (int64_t)(e & 0xffffffffull);
+            if (my_rep == b) {
+                first = 1;
+                flen = offsets[l + 1] - offsets[l];
+            }
         }
     }
-    int64_t ea, eb, ta, tb;
-    block_scan2(first, flen, ea, eb, ta, tb);
+    int64_t ea, eb, ic, ta, tb, tc;
+    block_scan3(first, flen, head, ea, eb, ic, ta, tb, tc);
     if (l < n_lists) {
+        if (head < 0) {
+            // follower: copy the representative of the run head (the nearest head at or before l;
+            // row 0 of a feature is always a head, so the run never leaves the feature)
+            const int64_t carry = bs_head[blockIdx.x];
+            const int64_t hl = ic > carry ? ic : carry;
+            const uint64_t e = table[(uint64_t)f * ((uint64_t)cap_mask + 1) + (uint32_t)slot_of[hl]];
+            my_rep = (int64_t)(e & 0xffffffffull);
+        }
+        rep[l] = (int32_t)my_rep;
         const int64_t num = bs_cnt[blockIdx.x] + ea;  // unique lists before (f,b), all features
         const int64_t pos = bs_len[blockIdx.x] + eb;  // their ids
         number[l] = (int32_t)num;
@@ -281,6 +396,7 @@ size_t recd_build_workspace(int F, int64_t B)
     c.take<int32_t>(n_lists);
     c.take<int64_t>(nblk + 1);
     c.take<int64_t>(nblk + 1);
+    c.take<int64_t>(nblk + 1);
     return c.off;
 }
 
@@ -316,23 +432,27 @@ extern "C" recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t 
     int32_t *number = c.take<int32_t>(n_lists);
     int64_t *bs_cnt = c.take<int64_t>(nblk + 1);
     int64_t *bs_len = c.take<int64_t>(nblk + 1);
+    int64_t *bs_head = c.take<int64_t>(nblk + 1);
     hipStream_t st = ctx->stream;
 
     if (n_lists == 0) {
         hipLaunchKernelGGL(k_empty_ikjt, dim3(1), dim3(256), 0, st, F, u_offsets, feat_uoff, counts);
     } else {
-        constexpr int SG = 16;
+        constexpr int SG = 8;
         const int64_t tab_n = (int64_t)F * (int64_t)cap;
         int fill_blocks = (int)((tab_n + 1023) / 1024 < 4096 ? (tab_n + 1023) / 1024 : 4096);
         hipLaunchKernelGGL(k_fill_u64, dim3(fill_blocks), dim3(256), 0, st, table, tab_n, kEmpty);
         const int64_t gblocks = (n_lists + (256 / SG) - 1) / (256 / SG);
-        hipLaunchKernelGGL((k_hash_insert<SG>), dim3((unsigned)gblocks), dim3(256), 0, st, values,
+        const int64_t hblocks = (n_lists + (256 / SG) * kLPG - 1) / ((256 / SG) * kLPG);
+        hipLaunchKernelGGL((k_hash_insert<SG>), dim3((unsigned)hblocks), dim3(256), 0, st, values,
                            offsets, B, n_lists, table, (uint32_t)(cap - 1), slot_of, ctx->weak_hash);
-        hipLaunchKernelGGL(k_rep_flags, dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets, B,
-                           n_lists, table, (uint32_t)(cap - 1), slot_of, rep, bs_cnt, bs_len);
-        hipLaunchKernelGGL(k_scan_pairs, dim3(1), dim3(kScanBlock), 0, st, bs_cnt, bs_len, nblk);
+        hipLaunchKernelGGL(k_flags, dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets, B, n_lists,
+                           table, (uint32_t)(cap - 1), slot_of, bs_cnt, bs_len, bs_head);
+        hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(kScanBlock), 0, st, bs_cnt, bs_len, bs_head,
+                           nblk);
         hipLaunchKernelGGL(k_number, dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets, B, n_lists,
-                           F, rep, bs_cnt, bs_len, number, u_offsets, feat_uoff, counts);
+                           F, table, (uint32_t)(cap - 1), slot_of, bs_cnt, bs_len, bs_head, rep, number,
+                           u_offsets, feat_uoff, counts);
         hipLaunchKernelGGL((k_emit<SG>), dim3((unsigned)gblocks), dim3(256), 0, st, values, offsets, B,
                            n_lists, rep, number, u_offsets, u_values, inverse);
     }

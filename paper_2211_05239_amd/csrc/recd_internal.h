@@ -62,6 +62,7 @@ struct TablePtrs {
 
 // ---- cross-file entry points (host side launchers) -------------------------------------------
 // Exclusive scan of n int64 pairs is private to each file; the segmented gather-sum is shared.
+enum { RECD_SITE_UNIQUE = 0, RECD_SITE_KJT = 1, RECD_SITE_GRAD_LISTS = 2, RECD_SITE_GRAD_ROWS = 3 };
 struct SegSumArgs {
     int F;                    // features in this launch (<= RECD_F_PER_LAUNCH)
     int D;
@@ -75,6 +76,14 @@ struct SegSumArgs {
     int64_t list_base;        // added to every list index (feature chunking of the KJT path)
     int64_t lists_bound;      // host upper bound of the number of lists in this launch (sizes the grid)
     int flat;                 // 1: no XCD-aware feature->block mapping
+    int site;                 // RECD_SITE_*: which call site (each has its own kernel instantiation)
+    // RECD_SITE_GRAD_ROWS only: fused row-wise Adagrad (opt_n_feat == 0: none)
+    int opt_n_feat;
+    float *const *opt_w;      // host arrays of opt_n_feat device pointers
+    float *const *opt_m;
+    const int64_t *opt_touched_rows;
+    const int32_t *opt_seg_feat;
+    float opt_lr, opt_eps;
     void *out;                // [lists, D]
 };
 recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a);

@@ -80,14 +80,21 @@ template <int TT> __device__ __forceinline__ void accumulate(float *acc, const u
     }
 }
 
-// store N fp32 accumulators (N = 4 or 8) as elements of type OT at dst
-template <int OT, int N> __device__ __forceinline__ void store_row_piece(void *dst, const float *acc)
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+// store N fp32 accumulators (N = 4 or 8) as elements of type OT at dst; NT = streaming store for
+// outputs that are written once and not read again by the path
+template <int OT, int N, bool NT> __device__ __forceinline__ void store_row_piece(void *dst, const float *acc)
 {
     if constexpr (OT == RECD_F32) {
 #pragma unroll
         for (int i = 0; i < N; i += 4) {
-            float4 o = make_float4(acc[i], acc[i + 1], acc[i + 2], acc[i + 3]);
-            reinterpret_cast<float4 *>(dst)[i / 4] = o;
+            const u32x4 o = {__float_as_uint(acc[i]), __float_as_uint(acc[i + 1]),
+                             __float_as_uint(acc[i + 2]), __float_as_uint(acc[i + 3])};
+            if constexpr (NT)
+                __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(dst) + i / 4);
+            else
+                reinterpret_cast<u32x4 *>(dst)[i / 4] = o;
         }
     } else {
         static_assert(OT == RECD_F32 || N == 8, "16-bit outputs come from 16-bit tables");
@@ -104,9 +111,31 @@ template <int OT, int N> __device__ __forceinline__ void store_row_piece(void *d
             }
             w[i] = lo | (hi << 16);
         }
-        *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+        const u32x4 o = {w[0], w[1], w[2], w[3]};
+        if constexpr (NT)
+            __builtin_nontemporal_store(o, reinterpret_cast<u32x4 *>(dst));
+        else
+            *reinterpret_cast<u32x4 *>(dst) = o;
     }
 }
+
+// Call sites of the gather-sum kernel.  Each gets its own instantiation (and symbol).
+enum { SITE_UNIQUE = 0, SITE_KJT = 1, SITE_GRAD_LISTS = 2, SITE_GRAD_ROWS = 3 };
+
+// Optional epilogue of SITE_GRAD_ROWS: row-wise Adagrad applied to the table row a segment belongs
+// to, straight from the registers that hold the segment's sum.
+struct OptNone {};
+struct OptAdagrad {
+    float *w[RECD_F_PER_LAUNCH];   // tables (nullptr array <=> n_feat == 0: no optimizer)
+    float *m[RECD_F_PER_LAUNCH];   // accumulators
+    const int64_t *touched_rows;   // [R] table row of every segment
+    const int32_t *seg_feat;       // [R] feature of every segment
+    int n_feat;
+    int write_grad;                // 0: the summed gradient rows are not stored
+    float lr, eps;
+};
+template <int SITE> struct OptOf { typedef OptNone type; };
+template <> struct OptOf<SITE_GRAD_ROWS> { typedef OptAdagrad type; };
 
 struct SegSumParams {
     TablePtrs tables;
@@ -168,9 +197,11 @@ __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL]
     }
 }
 
-template <int LPR, int VPL, int TT, int OT, typename IdxT, int NL>
-__global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p)
+template <int LPR, int VPL, int TT, int OT, typename IdxT, int NL, int SITE>
+__global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p,
+                                                   const typename OptOf<SITE>::type opt)
 {
+    constexpr bool NT = SITE == SITE_KJT || SITE == SITE_GRAD_ROWS;  // streaming outputs
     constexpr int EPV = Elem<TT>::per_vec;
     constexpr int NACC = EPV * VPL;
     constexpr int ROWF = LPR * NACC;                      // floats of one (padded) row
@@ -183,6 +214,8 @@ __global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p)
     __shared__ int64_t s_qpref[RECD_F_PER_LAUNCH + 1];
     __shared__ int64_t s_start[kMaxLB], s_end[kMaxLB], s_list[kMaxLB];
     __shared__ int s_feat[kMaxLB];
+    __shared__ int s_dfeat[kMaxLB];      // SITE_GRAD_ROWS: feature and table row the segment updates
+    __shared__ int64_t s_drow[kMaxLB];
     __shared__ float s_part[LL][kWaves][ROWF];
 
     const int tid = threadIdx.x;
@@ -237,6 +270,77 @@ __global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p)
                 acc[i] += __shfl_xor(acc[i], s);
     };
 
+    // A finished row: lanes of group 0 hold its NACC-element pieces in vals.  Store it and, at
+    // SITE_GRAD_ROWS with an optimizer, apply row-wise Adagrad to the table row it belongs to:
+    //   m += mean_d G[d]^2 ;  W[d] -= lr * G[d] / (sqrt(m) + eps)
+    // Optimizer operands of the row a segment updates, fetched before the segment is summed so that
+    // their latency overlaps the gather (lanes of group 0 only).
+    auto fetch_dest = [&](int j, float *wv_, float &m_) {
+        if constexpr (SITE == SITE_GRAD_ROWS) {
+            if (opt.n_feat > 0 && g == 0) {
+                const int f = s_dfeat[j];
+                const int64_t row = s_drow[j];
+                m_ = opt.m[f][row];
+                if (piece_ok) {
+                    const float *wrow = opt.w[f] + row * p.D;
+#pragma unroll
+                    for (int w = 0; w < VPL; w++) {
+                        const float4 x = *reinterpret_cast<const float4 *>(wrow + (w * LPR + r) * EPV);
+                        wv_[w * EPV + 0] = x.x;
+                        wv_[w * EPV + 1] = x.y;
+                        wv_[w * EPV + 2] = x.z;
+                        wv_[w * EPV + 3] = x.w;
+                    }
+                }
+            }
+        }
+    };
+    // A finished row: lanes of group 0 hold its NACC-element pieces in vals.  Store it and, at
+    // SITE_GRAD_ROWS with an optimizer, apply row-wise Adagrad to the table row it belongs to:
+    //   m += mean_d G[d]^2 ;  W[d] -= lr * G[d] / (sqrt(m) + eps)
+    auto finish_row = [&](int j, const float *vals, const float *wv_, float m_) {
+        bool store = true;
+        if constexpr (SITE == SITE_GRAD_ROWS) {
+            store = opt.write_grad != 0;
+            if (opt.n_feat > 0) {
+                float ss = 0.f;
+                if (g == 0 && piece_ok)
+#pragma unroll
+                    for (int i = 0; i < NACC; i++)
+                        ss += vals[i] * vals[i];
+#pragma unroll
+                for (int s = 1; s < LPR; s <<= 1)
+                    ss += __shfl_xor(ss, s);
+                if (g == 0) {
+                    const int f = s_dfeat[j];
+                    const int64_t row = s_drow[j];
+                    const float mnew = m_ + ss / (float)p.D;
+                    const float scale = opt.lr / (sqrtf(mnew) + opt.eps);
+                    if (piece_ok) {
+                        float *wrow = opt.w[f] + row * p.D;
+#pragma unroll
+                        for (int w = 0; w < VPL; w++) {
+                            float4 x;
+                            x.x = wv_[w * EPV + 0] - scale * vals[w * EPV + 0];
+                            x.y = wv_[w * EPV + 1] - scale * vals[w * EPV + 1];
+                            x.z = wv_[w * EPV + 2] - scale * vals[w * EPV + 2];
+                            x.w = wv_[w * EPV + 3] - scale * vals[w * EPV + 3];
+                            *reinterpret_cast<float4 *>(wrow + (w * LPR + r) * EPV) = x;
+                        }
+                    }
+                    if (r == 0)
+                        opt.m[f][row] = mnew;
+                }
+            }
+        }
+        if (store && g == 0 && piece_ok) {
+            char *dst = static_cast<char *>(p.out) + s_list[j] * out_row_bytes;
+#pragma unroll
+            for (int w = 0; w < VPL; w++)
+                store_row_piece<OT, EPV, NT>(dst + ((int64_t)w * LPR + r) * OB, vals + w * EPV);
+        }
+    };
+
     for (int64_t item = item0; item * lb < total; item += item_stride) {
         const int64_t t0 = item * lb;
         const int cnt = (int)(total - t0 < lb ? total - t0 : lb);
@@ -257,6 +361,12 @@ __global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p)
             s_list[tid] = l;
             s_start[tid] = p.offsets[l];
             s_end[tid] = p.offsets[l + 1];
+            if constexpr (SITE == SITE_GRAD_ROWS) {
+                if (opt.n_feat > 0) {
+                    s_dfeat[tid] = opt.seg_feat[l];
+                    s_drow[tid] = opt.touched_rows[l];
+                }
+            }
         }
         __syncthreads();
 
@@ -291,20 +401,18 @@ __global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p)
             if (nb == LL || (j == cnt && nb > 0)) {
                 __syncthreads();
                 for (int e = wv; e < nb; e += kWaves) {
-                    if (g == 0 && piece_ok) {
-                        char *dst = static_cast<char *>(p.out) + s_list[batch[e]] * out_row_bytes;
+                    float tot[NACC];
 #pragma unroll
-                        for (int w = 0; w < VPL; w++) {
-                            float tot[EPV];
+                    for (int w = 0; w < VPL; w++)
 #pragma unroll
-                            for (int i = 0; i < EPV; i++) {
-                                const int x = (w * LPR + r) * EPV + i;
-                                tot[i] = ((s_part[e][0][x] + s_part[e][1][x]) + s_part[e][2][x]) +
-                                         s_part[e][3][x];
-                            }
-                            store_row_piece<OT, EPV>(dst + ((int64_t)w * LPR + r) * OB, tot);
+                        for (int i = 0; i < EPV; i++) {
+                            const int x = (w * LPR + r) * EPV + i;
+                            tot[w * EPV + i] = ((s_part[e][0][x] + s_part[e][1][x]) + s_part[e][2][x]) +
+                                               s_part[e][3][x];
                         }
-                    }
+                    float dw[NACC], dm = 0.f;
+                    fetch_dest(batch[e], dw, dm);
+                    finish_row(batch[e], tot, dw, dm);
                 }
                 __syncthreads();
                 nb = 0;
@@ -337,52 +445,77 @@ __global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p)
             if (!any)
                 continue;
             float acc[NL][NACC];
+            float dw[NL][NACC], dm[NL];
 #pragma unroll
-            for (int k = 0; k < NL; k++)
+            for (int k = 0; k < NL; k++) {
 #pragma unroll
                 for (int i = 0; i < NACC; i++)
                     acc[k][i] = 0.f;
+                dm[k] = 0.f;
+                if (ns[k] >= 0)
+                    fetch_dest(wv + (k0 + k) * kWaves, dw[k], dm[k]);
+            }
             add_chunks<LPR, VPL, TT, IdxT, NL, US>(acc, tabs, values, starts, ns, row_bytes, lane, g, r,
                                                    piece_ok);
 #pragma unroll
             for (int k = 0; k < NL; k++) {
                 if (ns[k] >= 0) {
                     fold_groups(acc[k]);
-                    if (g == 0 && piece_ok) {
-                        char *dst = static_cast<char *>(p.out) +
-                                    s_list[wv + (k0 + k) * kWaves] * out_row_bytes;
-#pragma unroll
-                        for (int w = 0; w < VPL; w++)
-                            store_row_piece<OT, EPV>(dst + ((int64_t)w * LPR + r) * OB, acc[k] + w * EPV);
-                    }
+                    finish_row(wv + (k0 + k) * kWaves, acc[k], dw[k], dm[k]);
                 }
             }
         }
     }
 }
 
-template <int LPR, int VPL, int TT, int OT, typename IdxT>
-void launch_one(hipStream_t st, int blocks, int nl, const SegSumParams &p)
+template <int LPR, int VPL, int TT, int OT, typename IdxT, int SITE>
+void launch_one(hipStream_t st, int blocks, int nl, const SegSumParams &p,
+                const typename OptOf<SITE>::type &opt)
 {
-    if (nl == 4)
-        hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT, 4>), dim3(blocks), dim3(kBlock), 0, st, p);
-    else if (nl == 2)
-        hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT, 2>), dim3(blocks), dim3(kBlock), 0, st, p);
-    else
-        hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT, 1>), dim3(blocks), dim3(kBlock), 0, st, p);
+    if constexpr (SITE == SITE_GRAD_LISTS || SITE == SITE_GRAD_ROWS) {
+        if (nl == 4) {
+            hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT, 4, SITE>), dim3(blocks), dim3(kBlock), 0, st,
+                               p, opt);
+            return;
+        }
+        if (nl == 2) {
+            hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT, 2, SITE>), dim3(blocks), dim3(kBlock), 0, st,
+                               p, opt);
+            return;
+        }
+    }
+    hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT, 1, SITE>), dim3(blocks), dim3(kBlock), 0, st, p, opt);
 }
 
-template <int TT, int OT, typename IdxT>
-bool launch_shape(hipStream_t st, int blocks, int nl, int vecs, const SegSumParams &p)
+template <int TT, int OT, typename IdxT, int SITE>
+bool launch_shape(hipStream_t st, int blocks, int nl, int vecs, const SegSumParams &p,
+                  const typename OptOf<SITE>::type &opt)
 {
-    if (vecs <= 8) launch_one<8, 1, TT, OT, IdxT>(st, blocks, nl, p);
-    else if (vecs <= 16) launch_one<16, 1, TT, OT, IdxT>(st, blocks, nl, p);
-    else if (vecs <= 32) launch_one<32, 1, TT, OT, IdxT>(st, blocks, nl, p);
-    else if (vecs <= 64) launch_one<64, 1, TT, OT, IdxT>(st, blocks, nl, p);
-    else if (vecs == 128) launch_one<64, 2, TT, OT, IdxT>(st, blocks, nl, p);
-    else if (vecs == 256) launch_one<64, 4, TT, OT, IdxT>(st, blocks, nl, p);
+    if (vecs <= 8) launch_one<8, 1, TT, OT, IdxT, SITE>(st, blocks, nl, p, opt);
+    else if (vecs <= 16) launch_one<16, 1, TT, OT, IdxT, SITE>(st, blocks, nl, p, opt);
+    else if (vecs <= 32) launch_one<32, 1, TT, OT, IdxT, SITE>(st, blocks, nl, p, opt);
+    else if (vecs <= 64) launch_one<64, 1, TT, OT, IdxT, SITE>(st, blocks, nl, p, opt);
+    else if (vecs == 128) launch_one<64, 2, TT, OT, IdxT, SITE>(st, blocks, nl, p, opt);
+    else if (vecs == 256) launch_one<64, 4, TT, OT, IdxT, SITE>(st, blocks, nl, p, opt);
     else return false;
     return true;
+}
+
+template <int SITE>
+bool launch_forward(hipStream_t st, int blocks, int v, const SegSumArgs &a, const SegSumParams &p)
+{
+    const OptNone none;
+    if (a.table_dt == RECD_F32 && a.out_dt == RECD_F32)
+        return launch_shape<RECD_F32, RECD_F32, int64_t, SITE>(st, blocks, 1, v, p, none);
+    if (a.table_dt == RECD_F16 && a.out_dt == RECD_F16)
+        return launch_shape<RECD_F16, RECD_F16, int64_t, SITE>(st, blocks, 1, v, p, none);
+    if (a.table_dt == RECD_F16 && a.out_dt == RECD_F32)
+        return launch_shape<RECD_F16, RECD_F32, int64_t, SITE>(st, blocks, 1, v, p, none);
+    if (a.table_dt == RECD_BF16 && a.out_dt == RECD_BF16)
+        return launch_shape<RECD_BF16, RECD_BF16, int64_t, SITE>(st, blocks, 1, v, p, none);
+    if (a.table_dt == RECD_BF16 && a.out_dt == RECD_F32)
+        return launch_shape<RECD_BF16, RECD_F32, int64_t, SITE>(st, blocks, 1, v, p, none);
+    return false;
 }
 
 // ---- expand: out[f,b,:] = pooled[feat_uoff[f] + inverse[f,b], :]  (16-byte pieces) ------------
@@ -391,7 +524,6 @@ bool launch_shape(hipStream_t st, int blocks, int nl, int vecs, const SegSumPara
 // with streaming (non-temporal) stores: the output is written once and never re-read here, while
 // the pooled rows, shared by the consecutive samples of a session, should stay in L2.
 constexpr int kExpandRPT = 8;
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 template <bool TWO_FEATURES>
 __global__ __launch_bounds__(kBlock) void k_expand(const u32x4 *__restrict__ pooled,
@@ -500,19 +632,28 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     bool ok = false;
     hipStream_t st = ctx->stream;
     const int v = p.vecs_per_row;
-    if (a.values_are_i32) {
-        if (a.table_dt == RECD_F32 && a.out_dt == RECD_F32)
-            ok = launch_shape<RECD_F32, RECD_F32, int32_t>(st, blocks, nl, v, p);
-    } else if (a.table_dt == RECD_F32 && a.out_dt == RECD_F32)
-        ok = launch_shape<RECD_F32, RECD_F32, int64_t>(st, blocks, nl, v, p);
-    else if (a.table_dt == RECD_F16 && a.out_dt == RECD_F16)
-        ok = launch_shape<RECD_F16, RECD_F16, int64_t>(st, blocks, nl, v, p);
-    else if (a.table_dt == RECD_F16 && a.out_dt == RECD_F32)
-        ok = launch_shape<RECD_F16, RECD_F32, int64_t>(st, blocks, nl, v, p);
-    else if (a.table_dt == RECD_BF16 && a.out_dt == RECD_BF16)
-        ok = launch_shape<RECD_BF16, RECD_BF16, int64_t>(st, blocks, nl, v, p);
-    else if (a.table_dt == RECD_BF16 && a.out_dt == RECD_F32)
-        ok = launch_shape<RECD_BF16, RECD_F32, int64_t>(st, blocks, nl, v, p);
+    if (a.site == RECD_SITE_UNIQUE && !a.values_are_i32)
+        ok = launch_forward<SITE_UNIQUE>(st, blocks, v, a, p);
+    else if (a.site == RECD_SITE_KJT && !a.values_are_i32)
+        ok = launch_forward<SITE_KJT>(st, blocks, v, a, p);
+    else if (a.values_are_i32 && a.table_dt == RECD_F32 && a.out_dt == RECD_F32) {
+        if (a.site == RECD_SITE_GRAD_LISTS) {
+            ok = launch_shape<RECD_F32, RECD_F32, int32_t, SITE_GRAD_LISTS>(st, blocks, nl, v, p, OptNone());
+        } else if (a.site == RECD_SITE_GRAD_ROWS) {
+            OptAdagrad o;
+            o.n_feat = a.opt_n_feat;
+            for (int f = 0; f < a.opt_n_feat; f++) {
+                o.w[f] = a.opt_w[f];
+                o.m[f] = a.opt_m[f];
+            }
+            o.touched_rows = a.opt_touched_rows;
+            o.seg_feat = a.opt_seg_feat;
+            o.write_grad = a.out != nullptr;
+            o.lr = a.opt_lr;
+            o.eps = a.opt_eps;
+            ok = launch_shape<RECD_F32, RECD_F32, int32_t, SITE_GRAD_ROWS>(st, blocks, nl, v, p, o);
+        }
+    }
     if (!ok)
         return recd_fail(ctx, RECD_EINVAL, "unsupported row shape: D=%d table dtype %d out dtype %d",
                          a.D, (int)a.table_dt, (int)a.out_dt);
@@ -623,6 +764,7 @@ recd_status recd_pooled_lookup_unique(recd_ctx *ctx, int F, int D, recd_dtype ta
         a.offsets = u_offsets;
         a.list_off = feat_uoff + f0;
         a.lists_bound = max_lists;
+        a.site = RECD_SITE_UNIQUE;
         a.out = pooled;
         RECD_TRY(recd_launch_segsum(ctx, a));
     }
@@ -665,6 +807,7 @@ recd_status recd_kjt_pooled_lookup(recd_ctx *ctx, int F, int64_t B, int D, recd_
         a.lists_per_feature = B;
         a.list_base = (int64_t)f0 * B;
         a.lists_bound = (int64_t)a.F * B;
+        a.site = RECD_SITE_KJT;
         a.out = out;
         RECD_TRY(recd_launch_segsum(ctx, a));
     }

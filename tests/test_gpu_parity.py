@@ -293,6 +293,30 @@ def test_backward_deterministic(ctx):
         assert torch.equal(x, y)
 
 
+def test_backward_fused_update_without_stored_gradient(ctx):
+    """grad_rows = NULL: the update consumes the row gradients from registers; same tables, bit for bit."""
+    w = synth.scaled(synth.WORKLOADS["cfg5"], F=8, B=1024, rows=20_000, D=128)
+    batch = synth.make_batch(w, 0)
+    gout = gu.to_dev(synth.make_grad_out(w, 0))
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    tabs = synth.make_tables(w)
+    results = []
+    for store in (True, False):
+        d_tabs = gu.tables_to_dev(tabs, "f32")
+        d_state = [torch.zeros(w.rows, device="cuda") for _ in range(w.F)]
+        touched = torch.zeros(ik.M, dtype=torch.int64, device="cuda")
+        feat_roff = torch.zeros(w.F + 1, dtype=torch.int64, device="cuda")
+        grad_rows = torch.zeros(ik.M, w.D, device="cuda") if store else None
+        ctx.backward_dedup(w.F, w.B, gout, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets,
+                           [w.rows] * w.F, ik.U, ik.M, touched, feat_roff, grad_rows, tables=d_tabs,
+                           adagrad_state=d_state, lr=0.01, eps=1e-8)
+        torch.cuda.synchronize()
+        results.append((d_tabs, d_state, touched))
+    for a, b in zip(results[0][0] + results[0][1], results[1][0] + results[1][1]):
+        assert torch.equal(a, b)
+    assert torch.equal(results[0][2], results[1][2])
+
+
 def test_backward_no_ids(ctx):
     batch = synth.batch_from_lists([[[], []], [[], []]])
     values, offsets, ik = gu.gpu_build(ctx, batch)
