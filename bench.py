@@ -40,6 +40,7 @@ def parse_args():
     ap.add_argument("--store-grad", action="store_true",
                     help="also store the per-row gradients (default: the fused Adagrad update consumes them "
                          "from registers)")
+    ap.add_argument("--tune", type=int, default=0, help="RECD_OPT_TUNE_SEGSUM value (0 = automatic)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates hardware byte counters)")
     return ap.parse_args()
@@ -48,7 +49,7 @@ def parse_args():
 class DeviceProblem:
     """Everything one workload needs on the device, allocated once at worst-case sizes."""
 
-    def __init__(self, torch, recd, synth, w, n_batches, need_backward, store_grad=False):
+    def __init__(self, torch, recd, synth, w, n_batches, need_backward, store_grad=False, tune=0):
         self.torch, self.w = torch, w
         F, B, D = w.F, w.B, w.D
         self.tdt = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}[w.table_dtype]
@@ -75,6 +76,8 @@ class DeviceProblem:
         self.need_backward = need_backward
         ws = recd.workspace_bytes(F, B, Nmax, D)
         self.ctx = recd.Context(0, workspace_hint_bytes=ws)
+        if tune:
+            self.ctx.set_option(recd.RECD_OPT_TUNE_SEGSUM, tune)
         # unique-list counts of every batch (U, M): size the backward outputs by the largest M
         self.counts = [self.build(i) for i in range(n_batches)]
         if need_backward:
@@ -140,7 +143,7 @@ def event_ms(torch, fn, reps):
 
 
 def run_workload(torch, recd, synth, w, args, need_backward, detail=True):
-    P = DeviceProblem(torch, recd, synth, w, args.batches, need_backward, getattr(args, "store_grad", False))
+    P = DeviceProblem(torch, recd, synth, w, args.batches, need_backward, getattr(args, "store_grad", False), getattr(args, "tune", 0))
     nb = len(P.batches)
     F, B, D = w.F, w.B, w.D
     e = 4 if w.table_dtype == "f32" else 2

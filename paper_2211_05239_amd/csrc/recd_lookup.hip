@@ -152,22 +152,25 @@ struct SegSumParams {
     int lb;            // lists per block item, <= kMaxLB
 };
 
-// Adds the rows of NL chunks (chunk j: ns[j] <= 64 ids starting at values[starts[j]], rows of
-// tables[j]) into acc[j], all NL chunks in flight together.  Inside a chunk, lane group g adds the ids
-// g, g+G, g+2G, ... in that order, whatever NL and US are.
+// Adds the rows of NL chunks (chunk j: ns[j] <= 64 ids starting at values[starts[j]], rows of the
+// table whose per-lane base pointer is bases[j]) into acc[j], all NL chunks in flight together.
+// Inside a chunk, lane group g adds the ids g, g+G, g+2G, ... in that order, whatever NL and US are.
+// ns[] and starts[] are wave-uniform, so every "is this load slot used" test is a scalar branch and
+// unused slots cost nothing; only a chunk's last slot can hold lane groups beyond the end (they
+// fetch row 0, which exists, and are masked out of the add).  Ids are used modulo 2^32.
 template <int LPR, int VPL, int TT, typename IdxT, int NL, int US>
 __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL],
-                                           const char *const *tables, const IdxT *values,
-                                           const int64_t *starts, const int *ns, int64_t row_bytes,
-                                           int lane, int g, int r, bool piece_ok)
+                                           const char *const *bases, const IdxT *values,
+                                           const int64_t *starts, const int *ns, uint32_t row_bytes,
+                                           int lane, int g)
 {
     constexpr int EPV = Elem<TT>::per_vec;
     constexpr int G = 64 / LPR;
-    int64_t my_id[NL];
+    uint32_t my_id[NL];
     int nmax = 0;
 #pragma unroll
     for (int j = 0; j < NL; j++) {
-        my_id[j] = lane < ns[j] ? (int64_t)values[starts[j] + lane] : 0;
+        my_id[j] = lane < ns[j] ? (uint32_t)values[starts[j] + lane] : 0u;
         nmax = ns[j] > nmax ? ns[j] : nmax;
     }
     for (int k0 = 0; k0 < nmax; k0 += G * US) {
@@ -176,24 +179,30 @@ __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL]
         for (int j = 0; j < NL; j++)
 #pragma unroll
             for (int u = 0; u < US; u++) {
-                const int idx = k0 + u * G + g;
-                const int64_t id = __shfl(my_id[j], idx & 63);
-                const char *src = tables[j] + id * row_bytes + (int64_t)r * 16;
+                if (k0 + u * G < ns[j]) {  // scalar test
+                    const uint32_t id = __shfl(my_id[j], k0 + u * G + g);
+                    const char *src = bases[j] + (uint64_t)id * row_bytes;
 #pragma unroll
-                for (int w = 0; w < VPL; w++) {
-                    if (idx < ns[j] && piece_ok)
-                        v[j][u][w] = *reinterpret_cast<const uint4 *>(src + (int64_t)w * LPR * 16);
-                    else
-                        v[j][u][w] = make_uint4(0, 0, 0, 0);
+                    for (int w = 0; w < VPL; w++)
+                        v[j][u][w] = *reinterpret_cast<const uint4 *>(src + w * LPR * 16);
                 }
             }
 #pragma unroll
         for (int j = 0; j < NL; j++)
 #pragma unroll
-            for (int u = 0; u < US; u++)
+            for (int u = 0; u < US; u++) {
+                if (k0 + u * G + G <= ns[j]) {  // scalar test: every lane group holds a real id
 #pragma unroll
-                for (int w = 0; w < VPL; w++)
-                    accumulate<TT>(acc[j] + w * EPV, v[j][u][w]);
+                    for (int w = 0; w < VPL; w++)
+                        accumulate<TT>(acc[j] + w * EPV, v[j][u][w]);
+                } else if (k0 + u * G < ns[j]) {
+                    if (k0 + u * G + g < ns[j]) {
+#pragma unroll
+                        for (int w = 0; w < VPL; w++)
+                            accumulate<TT>(acc[j] + w * EPV, v[j][u][w]);
+                    }
+                }
+            }
     }
 }
 
@@ -219,7 +228,8 @@ __global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p,
     __shared__ float s_part[LL][kWaves][ROWF];
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wv = tid >> 6;
+    const int lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, kept in a scalar register
     const int nq = p.nq;
     const int q = nq == 1 ? 0 : (int)(blockIdx.x % kNQ);
     const int64_t item0 = nq == 1 ? blockIdx.x : blockIdx.x / kNQ;
@@ -258,7 +268,10 @@ __global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p,
     const int r = lane % LPR;   // 16-byte piece of the row
     const bool piece_ok = r < p.vecs_per_row || VPL > 1;
     const IdxT *values = static_cast<const IdxT *>(p.values);
-    const int64_t row_bytes = (int64_t)p.D * (TT == RECD_F32 ? 4 : 2);
+    const uint32_t row_bytes = (uint32_t)p.D * (TT == RECD_F32 ? 4 : 2);
+    // lanes beyond the row's last 16-byte piece (rows shorter than LPR pieces) read piece 0; they
+    // never store
+    const int lane_off = piece_ok ? r * 16 : 0;
     const int64_t out_row_bytes = (int64_t)p.D * (OT == RECD_F32 ? 4 : 2);
     const int lb = p.lb;
 
@@ -377,16 +390,15 @@ __global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p,
         for (int j = 0; j <= cnt; j++) {
             const bool is_long = j < cnt && s_end[j] - s_start[j] > kChunk;  // block-uniform
             if (is_long) {
-                const int64_t start = s_start[j], end = s_end[j];
-                const char *table = static_cast<const char *>(p.tables.p[s_feat[j]]);
+                const int64_t start = uniform64(s_start[j]), end = uniform64(s_end[j]);
+                const char *table = static_cast<const char *>(p.tables.p[s_feat[j]]) + lane_off;
                 float acc[1][NACC];
 #pragma unroll
                 for (int i = 0; i < NACC; i++)
                     acc[0][i] = 0.f;
                 for (int64_t base = start + (int64_t)wv * kChunk; base < end; base += kWaves * kChunk) {
                     const int n = (int)(end - base < kChunk ? end - base : kChunk);
-                    add_chunks<LPR, VPL, TT, IdxT, 1, UNR>(acc, &table, values, &base, &n, row_bytes, lane,
-                                                           g, r, piece_ok);
+                    add_chunks<LPR, VPL, TT, IdxT, 1, UNR>(acc, &table, values, &base, &n, row_bytes, lane, g);
                 }
                 fold_groups(acc[0]);
                 if (g == 0) {
@@ -433,10 +445,11 @@ __global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p,
                 starts[k] = 0;
                 ns[k] = -1;
                 if (j < cnt) {
-                    const int64_t len = s_end[j] - s_start[j];
+                    const int64_t st_ = uniform64(s_start[j]);
+                    const int64_t len = uniform64(s_end[j]) - st_;
                     if (len <= kChunk) {
-                        tabs[k] = static_cast<const char *>(p.tables.p[s_feat[j]]);
-                        starts[k] = s_start[j];
+                        tabs[k] = static_cast<const char *>(p.tables.p[s_feat[j]]) + lane_off;
+                        starts[k] = st_;
                         ns[k] = (int)len;
                         any = true;
                     }
@@ -455,8 +468,7 @@ __global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p,
                 if (ns[k] >= 0)
                     fetch_dest(wv + (k0 + k) * kWaves, dw[k], dm[k]);
             }
-            add_chunks<LPR, VPL, TT, IdxT, NL, US>(acc, tabs, values, starts, ns, row_bytes, lane, g, r,
-                                                   piece_ok);
+            add_chunks<LPR, VPL, TT, IdxT, NL, US>(acc, tabs, values, starts, ns, row_bytes, lane, g);
 #pragma unroll
             for (int k = 0; k < NL; k++) {
                 if (ns[k] >= 0) {
