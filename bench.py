@@ -33,7 +33,7 @@ def parse_args():
     ap.add_argument("--workload", default="cfg5",
                     help="cfg1..cfg5 or cfg4_S<k> (duplication sweep member)")
     ap.add_argument("--batches", type=int, default=4, help="distinct seeded batches to rotate over")
-    ap.add_argument("--cpu-features", type=int, default=24,
+    ap.add_argument("--cpu-features", type=int, default=32,
                     help="features of batch 0 the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--sweep", action="store_true", help="also run the duplication sweep (cfg4, S in 1,2,4,8,32)")
     ap.add_argument("--forward-only", action="store_true", help="leave the backward pass out of the step")
@@ -236,37 +236,53 @@ def run_workload(torch, recd, synth, w, args, need_backward, detail=True):
 
 
 def cpu_baseline(torch, synth, P, n_feat):
-    """The CPU oracle, as it stands, on the first n_feat features of batch 0 (features are
-    independent): build + unique lookup + expand + backward + Adagrad, single thread."""
+    """The CPU oracle, as it stands, single thread, on the first n_feat features (features are
+    independent) of every rotated batch: build + unique lookup + expand (+ backward + Adagrad)."""
     from oracle import recd_oracle as orc
     w = P.w
     n_feat = min(n_feat, w.F)
-    b = P.batches[0]
-    B, D = w.B, w.D
-    hi = int(b.offsets[n_feat * B])
-    values, offsets = b.values[:hi], b.offsets[:n_feat * B + 1]
+    B = w.B
     dt = w.table_dtype
     tabs = []
     for f in range(n_feat):
         t = P.tables[f]
         tabs.append(t.view(torch.int16).cpu().numpy().view(np.uint16) if dt == "bf16" else t.cpu().numpy())
     gout = P.grad_out[:n_feat].cpu().numpy() if P.need_backward else None
-    t0 = time.perf_counter()
-    uv, uo, inv, fu = orc.build_ikjt(n_feat, B, values, offsets)
-    pooled = orc.pooled_lookup(tabs, dt, uv, uo, fu)
-    orc.expand_inverse(n_feat, B, pooled, fu, inv)
-    if gout is not None:
-        tr, fr, gr = orc.backward_dedup(n_feat, B, gout, inv, fu, uv, uo)
-        for f in range(n_feat):
-            rows_f = tr[fr[f]:fr[f + 1]]
-            orc.rowwise_adagrad(gr[fr[f]:fr[f + 1]], tabs[f][rows_f].astype(np.float64),
-                                np.zeros(len(rows_f)), 0.01, 1e-8)
-    dt_s = time.perf_counter() - t0
-    return {"value": B * n_feat / dt_s, "unit": "pooled lookups/s", "cores": 1, "kind": "oracle",
-            "seconds": dt_s,
-            "sample": f"features 0..{n_feat - 1} of batch 0 ({n_feat} of {w.F} features, all "
-                      f"B={B} rows): build + unique lookup + expand"
-                      + (" + backward + Adagrad" if gout is not None else "")}
+    total_s, n_done = 0.0, 0
+    for b in P.batches:
+        hi = int(b.offsets[n_feat * B])
+        values, offsets = b.values[:hi], b.offsets[:n_feat * B + 1]
+        t0 = time.perf_counter()
+        uv, uo, inv, fu = orc.build_ikjt(n_feat, B, values, offsets)
+        pooled = orc.pooled_lookup(tabs, dt, uv, uo, fu)
+        orc.expand_inverse(n_feat, B, pooled, fu, inv)
+        if gout is not None:
+            tr, fr, gr = orc.backward_dedup(n_feat, B, gout, inv, fu, uv, uo)
+            for f in range(n_feat):
+                rows_f = tr[fr[f]:fr[f + 1]]
+                orc.rowwise_adagrad(gr[fr[f]:fr[f + 1]], tabs[f][rows_f].astype(np.float64),
+                                    np.zeros(len(rows_f)), 0.01, 1e-8)
+        total_s += time.perf_counter() - t0
+        n_done += 1
+        if total_s > 20.0:
+            break
+    return {"value": B * n_feat * n_done / total_s, "unit": "pooled lookups/s", "cores": 1,
+            "kind": "oracle", "seconds": total_s,
+            "sample": f"features 0..{n_feat - 1} ({n_feat} of {w.F}) of {n_done} batch(es), all B={B} rows: "
+                      f"build + unique lookup + expand" + (" + backward + Adagrad" if gout is not None else "")}
+
+
+def measured_traffic(workload_name):
+    """HBM bytes per launch of the unique-lookup kernel, from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE and WRITE_SIZE, calibrated against a plain copy); None if there is none."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload_name}.md")
+    try:
+        for line in open(path):
+            if line.startswith("lookup_unique_traffic_bytes:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
 
 
 def main():
@@ -321,7 +337,7 @@ def main():
                    "batches_rotated": len(P.batches)},
         "roofline": {"bound": "hbm", "kernel": "k_segsum (recd_pooled_lookup_unique)",
                      "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": measured_traffic(w.name),
                      "algorithmic_bytes": look_bytes,
                      "bytes_form": "compulsory (each distinct table row once per launch)"
                      if "lookup_unique_compulsory" in res["bytes"] else "upper",

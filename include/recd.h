@@ -37,7 +37,7 @@
  *                                            f's unique lists (the paper's inverse_lookup)
  *                     feat_uoff int64 [F+1]  prefix sum of U_f; unique list of (f,b) is
  *                                            feat_uoff[f] + inverse[f*B+b]; feat_uoff[F] = U
- *   Every feature is its own deduplication group.
+ *   Every feature is its own deduplication group.  Ids are stored as int64 and must lie in [0, 2^31).
  *   Tables: row-major [rows_f, D]; pooled / expanded outputs: row-major [lists, D].
  */
 #ifndef RECD_H
