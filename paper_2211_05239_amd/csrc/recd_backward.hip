@@ -8,18 +8,19 @@
 // the groups, and the segmented gather-sum kernel of the forward pass adds each group's rows.
 // There are no floating-point atomics, so two runs give bit-identical gradients.
 //
-// Radix sort pass (8-bit digit): per-tile digit histograms -> exclusive scan in (digit, tile) order
-// -> scatter.  Inside a tile the stable rank of a key among equal digits is found per wave with
-// eight ballots (which lanes hold my digit), per-(round, wave) digit counts in LDS and a short
-// serial prefix over the 32 (round, wave) cells.
+// Radix sort pass (digits of up to 9 bits): per-tile digit histograms -> one block per digit scans its
+// row of tile counts -> scatter (which first scans the digit totals itself).  Inside a tile every
+// wave owns a contiguous run of keys and walks it 64 keys at a time: ballots tell each lane which
+// lanes hold its digit (its rank among them), a per-wave running digit count in LDS gives the rank
+// among the wave's earlier keys, and a prefix over the four waves completes the stable rank.
 #include "recd_internal.h"
 
 namespace {
 
 constexpr int kSortThreads = 256;
-constexpr int kIPT = 8;                       // keys per thread in a tile
-constexpr int kTile = kSortThreads * kIPT;    // 2048 keys per tile
-constexpr int kRadix = 256;
+constexpr int kIPT = 16;                      // keys per thread in a tile
+constexpr int kTile = kSortThreads * kIPT;    // 4096 keys per tile
+constexpr int kRadixMax = 512;                // digits of up to 9 bits
 constexpr int kScanItems = 16;                // items per thread in the generic scan
 constexpr int kScanTile = 256 * kScanItems;
 
@@ -126,11 +127,13 @@ recd_status scan_u32(recd_ctx *ctx, uint32_t *data, const int64_t *n_dev, int64_
 template <typename KeyT>
 __global__ __launch_bounds__(kSortThreads) void k_sort_hist(const KeyT *__restrict__ keys,
                                                             const int64_t *n_dev, int64_t n_host,
-                                                            int shift, uint32_t *__restrict__ hist,
-                                                            int ntiles)
+                                                            int shift, int dbits,
+                                                            uint32_t *__restrict__ hist, int ntiles)
 {
-    __shared__ uint32_t s_h[kRadix];
-    s_h[threadIdx.x] = 0;
+    __shared__ uint32_t s_h[kRadixMax];
+    const uint32_t radix = 1u << dbits;
+    for (uint32_t d = threadIdx.x; d < radix; d += kSortThreads)
+        s_h[d] = 0;
     __syncthreads();
     const int64_t n = count_of(n_dev, n_host);
     const int64_t base = (int64_t)blockIdx.x * kTile;
@@ -138,70 +141,111 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_hist(const KeyT *__restri
     for (int k = 0; k < kIPT; k++) {
         const int64_t i = base + k * kSortThreads + threadIdx.x;
         if (i < n)
-            atomicAdd(&s_h[(uint32_t)(keys[i] >> shift) & (kRadix - 1)], 1u);
+            atomicAdd(&s_h[(uint32_t)(keys[i] >> shift) & (radix - 1)], 1u);
     }
     __syncthreads();
-    hist[(int64_t)threadIdx.x * ntiles + blockIdx.x] = s_h[threadIdx.x];
+    for (uint32_t d = threadIdx.x; d < radix; d += kSortThreads)
+        hist[(int64_t)d * ntiles + blockIdx.x] = s_h[d];
+}
+
+// one block per digit: in-place exclusive scan of the digit's row of tile counts; row total out
+__global__ __launch_bounds__(256) void k_sort_rowscan(uint32_t *__restrict__ hist, int ntiles,
+                                                      uint32_t *__restrict__ digit_total)
+{
+    uint32_t *row = hist + (int64_t)blockIdx.x * ntiles;
+    uint32_t carry = 0;
+    for (int base = 0; base < ntiles; base += 256) {
+        const int i = base + threadIdx.x;
+        const uint32_t v = i < ntiles ? row[i] : 0;
+        uint32_t total;
+        const uint32_t e = block_excl_scan_u32(v, total);
+        if (i < ntiles)
+            row[i] = carry + e;
+        carry += total;
+    }
+    if (threadIdx.x == 0)
+        digit_total[blockIdx.x] = carry;
 }
 
 template <typename KeyT>
 __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(
     const KeyT *__restrict__ kin, const uint32_t *__restrict__ pin, KeyT *__restrict__ kout,
-    uint32_t *__restrict__ pout, const int64_t *n_dev, int64_t n_host, int shift,
-    const uint32_t *__restrict__ hist_scanned, int ntiles)
+    uint32_t *__restrict__ pout, const int64_t *n_dev, int64_t n_host, int shift, int dbits,
+    const uint32_t *__restrict__ hist_scanned, const uint32_t *__restrict__ digit_total, int ntiles)
 {
     constexpr int W = kSortThreads / 64;
-    __shared__ uint16_t s_cnt[kIPT][W][kRadix];
-    __shared__ uint32_t s_base[kRadix];
+    constexpr int kPerWave = 64 * kIPT;  // contiguous keys of one wave
+    __shared__ uint32_t s_run[W][kRadixMax];  // per wave: keys seen so far per digit
+    __shared__ uint32_t s_base[kRadixMax];    // where this tile's keys of a digit start in the output
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const uint32_t radix = 1u << dbits;
     const int64_t n = count_of(n_dev, n_host);
     const int64_t base = (int64_t)blockIdx.x * kTile;
     if (base >= n)
         return;  // whole block: nothing in this tile
-    for (int i = tid; i < kIPT * W * kRadix; i += kSortThreads)
-        (&s_cnt[0][0][0])[i] = 0;
+    // digit bases = exclusive scan of the digit totals (two digits per thread), plus this tile's
+    // offset inside the digit
+    {
+        const uint32_t d0 = 2 * tid, d1 = 2 * tid + 1;
+        const uint32_t t0 = d0 < radix ? digit_total[d0] : 0, t1 = d1 < radix ? digit_total[d1] : 0;
+        uint32_t total;
+        const uint32_t e = block_excl_scan_u32(t0 + t1, total);
+        if (d0 < radix)
+            s_base[d0] = e + hist_scanned[(int64_t)d0 * ntiles + blockIdx.x];
+        if (d1 < radix)
+            s_base[d1] = e + t0 + hist_scanned[(int64_t)d1 * ntiles + blockIdx.x];
+    }
+    for (int i = tid; i < W * kRadixMax; i += kSortThreads)
+        (&s_run[0][0])[i] = 0;
     __syncthreads();
 
     KeyT key[kIPT];
     uint32_t rank[kIPT];
     const uint64_t lt_mask = lane == 0 ? 0ull : (~0ull >> (64 - lane));
+    const int64_t wbase = base + (int64_t)w * kPerWave;
 #pragma unroll
     for (int k = 0; k < kIPT; k++) {
-        const int64_t i = base + k * kSortThreads + tid;
+        const int64_t i = wbase + k * 64 + lane;
         const bool valid = i < n;
         key[k] = valid ? kin[i] : (KeyT)0;
-        const uint32_t d = (uint32_t)(key[k] >> shift) & (kRadix - 1);
+        const uint32_t d = (uint32_t)(key[k] >> shift) & (radix - 1);
         uint64_t mask = __ballot(valid);
 #pragma unroll
-        for (int bit = 0; bit < 8; bit++) {
-            const bool one = (d >> bit) & 1u;
-            const uint64_t bal = __ballot(one);
-            mask &= one ? bal : ~bal;
+        for (int bit = 0; bit < 9; bit++) {
+            if (bit < dbits) {  // uniform
+                const bool one = (d >> bit) & 1u;
+                const uint64_t bal = __ballot(one);
+                mask &= one ? bal : ~bal;
+            }
         }
-        rank[k] = (uint32_t)__popcll(mask & lt_mask);
-        if (valid && rank[k] == 0)
-            s_cnt[k][w][d] = (uint16_t)__popcll(mask);
+        const uint32_t in_round = (uint32_t)__popcll(mask & lt_mask);
+        // keys of this digit in the wave's earlier rounds; the first lane of each digit then adds
+        // this round's count (same wave: the read above is complete before the write is issued)
+        const uint32_t before = valid ? s_run[w][d] : 0;
+        __builtin_amdgcn_wave_barrier();
+        if (valid && in_round == 0)
+            s_run[w][d] = before + (uint32_t)__popcll(mask);
+        __builtin_amdgcn_wave_barrier();
+        rank[k] = before + in_round;
     }
     __syncthreads();
-    {
+    // s_run[w][d] now holds wave w's count of digit d: exclusive prefix over the waves
+    for (uint32_t d = tid; d < radix; d += kSortThreads) {
         uint32_t run = 0;
 #pragma unroll
-        for (int k = 0; k < kIPT; k++)
-#pragma unroll
-            for (int ww = 0; ww < W; ww++) {
-                const uint32_t c = s_cnt[k][ww][tid];
-                s_cnt[k][ww][tid] = (uint16_t)run;
-                run += c;
-            }
-        s_base[tid] = hist_scanned[(int64_t)tid * ntiles + blockIdx.x];
+        for (int ww = 0; ww < W; ww++) {
+            const uint32_t c = s_run[ww][d];
+            s_run[ww][d] = run;
+            run += c;
+        }
     }
     __syncthreads();
 #pragma unroll
     for (int k = 0; k < kIPT; k++) {
-        const int64_t i = base + k * kSortThreads + tid;
+        const int64_t i = wbase + k * 64 + lane;
         if (i < n) {
-            const uint32_t d = (uint32_t)(key[k] >> shift) & (kRadix - 1);
-            const int64_t dst = (int64_t)s_base[d] + s_cnt[k][w][d] + rank[k];
+            const uint32_t d = (uint32_t)(key[k] >> shift) & (radix - 1);
+            const int64_t dst = (int64_t)s_base[d] + s_run[w][d] + rank[k];
             kout[dst] = key[k];
             pout[dst] = pin[i];
         }
@@ -219,12 +263,15 @@ recd_status radix_sort_pairs(recd_ctx *ctx, KeyT *k0, uint32_t *p0, KeyT *k1, ui
     hipStream_t st = ctx->stream;
     KeyT *ka = k0, *kb = k1;
     uint32_t *pa = p0, *pb = p1;
-    for (int shift = 0; shift < bits && ntiles > 0; shift += 8) {
+    // fewest passes with digits of at most 9 bits, digits as even as possible
+    const int passes = (bits + 8) / 9;
+    const int dbits = passes > 0 ? (bits + passes - 1) / passes : 0;
+    for (int shift = 0; shift < bits && ntiles > 0; shift += dbits) {
         hipLaunchKernelGGL((k_sort_hist<KeyT>), dim3(ntiles), dim3(kSortThreads), 0, st, ka, n_dev,
-                           n_cap, shift, hist, ntiles);
-        RECD_TRY(scan_u32(ctx, hist, nullptr, (int64_t)kRadix * ntiles, bsum));
+                           n_cap, shift, dbits, hist, ntiles);
+        hipLaunchKernelGGL(k_sort_rowscan, dim3(1u << dbits), dim3(256), 0, st, hist, ntiles, bsum);
         hipLaunchKernelGGL((k_sort_scatter<KeyT>), dim3(ntiles), dim3(kSortThreads), 0, st, ka, pa, kb,
-                           pb, n_dev, n_cap, shift, hist, ntiles);
+                           pb, n_dev, n_cap, shift, dbits, hist, bsum, ntiles);
         KeyT *tk = ka; ka = kb; kb = tk;
         uint32_t *tp = pa; pa = pb; pb = tp;
     }
@@ -288,9 +335,12 @@ __global__ __launch_bounds__(256) void k_keys_ids(const int64_t *__restrict__ u_
 
 // ---------------------------------------------------------------- segments of equal keys
 template <typename KeyT>
-__global__ void k_heads(const KeyT *__restrict__ keys, const int64_t *n_dev, uint32_t *__restrict__ flag)
+__global__ void k_heads(const KeyT *__restrict__ keys, const int64_t *n_dev, uint32_t *__restrict__ flag,
+                        int64_t *long_count)
 {
     const int64_t n = *n_dev;
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        *long_count = 0;
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
          i += (int64_t)gridDim.x * blockDim.x)
         flag[i] = (i == 0 || keys[i] != keys[i - 1]) ? 1u : 0u;
@@ -407,6 +457,143 @@ __global__ __launch_bounds__(256) void k_adagrad(const float *__restrict__ grad_
     }
 }
 
+// ---------------------------------------------------------------- row-gradient segment sum
+// Step B has very many very short segments (a table row is named by a handful of unique lists, a
+// few hot rows by thousands).  Here a group of LPR lanes owns a whole segment: G = 64/LPR segments
+// advance side by side in one wave, each lane carries up to four 16-byte pieces of the row, no
+// cross-lane fold is needed, and the Adagrad update of the destination row follows in the same
+// lanes.  Segments longer than 64 entries are only recorded; the block-cooperative gather-sum
+// kernel sums them afterwards.  Order of additions inside a segment: ascending position.
+struct RowSumParams {
+    const float *table;        // g_u [U, D]
+    const uint32_t *pay;       // sorted payload: unique-list index of every position
+    const int64_t *seg_start;  // [R+1]
+    const int64_t *n_seg;      // device: R
+    float *out;                // grad_rows [R, D] or nullptr
+    int D;
+    int pieces;                // D / 4
+    int32_t *long_list;        // segments left to the cooperative kernel ...
+    int64_t *long_count;       // ... and how many
+};
+
+template <int LPR>
+__global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const OptAdagrad opt)
+{
+    constexpr int G = 64 / LPR, VPL = 4, US = 2;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int g = lane / LPR, r = lane % LPR;
+    const int64_t R = *p.n_seg;
+    const int per_block = (256 / 64) * G;
+    const float4 *table = reinterpret_cast<const float4 *>(p.table);
+    bool piece[VPL];
+#pragma unroll
+    for (int w = 0; w < VPL; w++)
+        piece[w] = w * LPR + r < p.pieces;
+
+    for (int64_t t0 = (int64_t)blockIdx.x * per_block; t0 < R; t0 += (int64_t)gridDim.x * per_block) {
+        const int64_t t = t0 + wv * G + g;
+        int64_t start = 0;
+        int n = 0;
+        if (t < R) {
+            start = p.seg_start[t];
+            const int64_t len = p.seg_start[t + 1] - start;
+            if (len > 64) {
+                if (r == 0) {
+                    const unsigned long long pos =
+                        atomicAdd(reinterpret_cast<unsigned long long *>(p.long_count), 1ull);
+                    p.long_list[pos] = (int32_t)t;
+                }
+            } else {
+                n = (int)len;
+            }
+        }
+        const bool mine = n > 0;  // uniform inside the lane group
+        const bool update = mine && opt.n_feat > 0;
+        float4 wreg[VPL];
+        float mreg = 0.f;
+        float *wrow = nullptr, *mp = nullptr;
+        if (update) {
+            const int f = opt.seg_feat[t];
+            const int64_t row = opt.touched_rows[t];
+            mp = opt.m[f] + row;
+            wrow = opt.w[f] + row * p.D;
+            mreg = *mp;
+#pragma unroll
+            for (int w = 0; w < VPL; w++)
+                if (piece[w])
+                    wreg[w] = reinterpret_cast<const float4 *>(wrow)[w * LPR + r];
+        }
+        float4 acc[VPL];
+#pragma unroll
+        for (int w = 0; w < VPL; w++)
+            acc[w] = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int i = 0; i < n; i += US) {
+            uint32_t id[US];
+#pragma unroll
+            for (int u = 0; u < US; u++)
+                id[u] = p.pay[start + (i + u < n ? i + u : i)];
+            float4 v[US][VPL];
+#pragma unroll
+            for (int u = 0; u < US; u++)
+#pragma unroll
+                for (int w = 0; w < VPL; w++)
+                    if (piece[w])
+                        v[u][w] = table[(int64_t)id[u] * p.pieces + w * LPR + r];
+#pragma unroll
+            for (int u = 0; u < US; u++)
+                if (i + u < n)
+#pragma unroll
+                    for (int w = 0; w < VPL; w++)
+                        if (piece[w]) {
+                            acc[w].x += v[u][w].x;
+                            acc[w].y += v[u][w].y;
+                            acc[w].z += v[u][w].z;
+                            acc[w].w += v[u][w].w;
+                        }
+        }
+        if (mine) {
+            if (update) {
+                float ss = 0.f;
+#pragma unroll
+                for (int w = 0; w < VPL; w++)
+                    if (piece[w]) {
+                        ss += acc[w].x * acc[w].x;
+                        ss += acc[w].y * acc[w].y;
+                        ss += acc[w].z * acc[w].z;
+                        ss += acc[w].w * acc[w].w;
+                    }
+#pragma unroll
+                for (int s = 1; s < LPR; s <<= 1)
+                    ss += __shfl_xor(ss, s);
+                const float mnew = mreg + ss / (float)p.D;
+                const float scale = opt.lr / (sqrtf(mnew) + opt.eps);
+#pragma unroll
+                for (int w = 0; w < VPL; w++)
+                    if (piece[w]) {
+                        float4 x = wreg[w];
+                        x.x -= scale * acc[w].x;
+                        x.y -= scale * acc[w].y;
+                        x.z -= scale * acc[w].z;
+                        x.w -= scale * acc[w].w;
+                        reinterpret_cast<float4 *>(wrow)[w * LPR + r] = x;
+                    }
+                if (r == 0)
+                    *mp = mnew;
+            }
+            if (p.out) {
+                float4 *dst = reinterpret_cast<float4 *>(p.out + t * p.D);
+#pragma unroll
+                for (int w = 0; w < VPL; w++)
+                    if (piece[w]) {
+                        typedef float f32x4 __attribute__((ext_vector_type(4)));
+                        const f32x4 o = {acc[w].x, acc[w].y, acc[w].z, acc[w].w};
+                        __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(&dst[w * LPR + r]));
+                    }
+            }
+        }
+    }
+}
+
 __global__ void k_no_rows(int F, int64_t *feat_roff, int64_t *list_off)
 {
     for (int f = threadIdx.x; f <= F; f += blockDim.x)
@@ -429,7 +616,8 @@ struct BwdWs {
     int64_t *n_dev, *list_off, *seg_start;
     void *k0, *k1;
     uint32_t *p0, *p1, *flag, *hist, *bsum;
-    int32_t *seg_feat;
+    int32_t *seg_feat, *long_list;
+    int64_t *long_count;
     float *g_u;
     size_t bytes;
 };
@@ -440,7 +628,7 @@ BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D)
     BwdWs w;
     const int64_t n_max = n_lists > M_cap ? n_lists : M_cap;
     const int64_t ntiles = (n_max + kTile - 1) / kTile;
-    const int64_t hist_n = (int64_t)kRadix * ntiles;
+    const int64_t hist_n = (int64_t)kRadixMax * ntiles;
     const int64_t scan_max = hist_n > n_max ? hist_n : n_max;
     int64_t u_cap = M_cap + F < n_lists ? M_cap + F : n_lists;
     w.n_dev = c.take<int64_t>(2);
@@ -452,8 +640,10 @@ BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D)
     w.p1 = c.take<uint32_t>(n_max);
     w.flag = c.take<uint32_t>(n_max);
     w.seg_feat = c.take<int32_t>(n_max);
+    w.long_list = c.take<int32_t>(n_max / 65 + 16);
+    w.long_count = c.take<int64_t>(1);
     w.hist = c.take<uint32_t>(hist_n);
-    w.bsum = c.take<uint32_t>((scan_max + kScanTile - 1) / kScanTile + 1);
+    w.bsum = c.take<uint32_t>((scan_max + kScanTile - 1) / kScanTile + 1 + kRadixMax);  // also digit totals
     w.g_u = c.take<float>((size_t)u_cap * D);
     w.bytes = c.off;
     return w;
@@ -473,7 +663,7 @@ recd_status group_and_sum(recd_ctx *ctx, const BwdWs &w, KeyT *k0, KeyT *k1, int
     int blocks = (int)((n_cap + 255) / 256 < 2048 ? (n_cap + 255) / 256 : 2048);
     if (blocks < 1)
         blocks = 1;
-    hipLaunchKernelGGL((k_heads<KeyT>), dim3(blocks), dim3(256), 0, st, ks, w.n_dev, w.flag);
+    hipLaunchKernelGGL((k_heads<KeyT>), dim3(blocks), dim3(256), 0, st, ks, w.n_dev, w.flag, w.long_count);
     RECD_TRY(scan_u32(ctx, w.flag, w.n_dev, n_cap, w.bsum));
     hipLaunchKernelGGL((k_segments<KeyT>), dim3(blocks), dim3(256), 0, st, ks, w.n_dev, w.flag,
                        w.seg_start, w.list_off, row_bits, F, touched_rows, feat_roff, w.seg_feat);
@@ -496,6 +686,52 @@ recd_status group_and_sum(recd_ctx *ctx, const BwdWs &w, KeyT *k0, KeyT *k1, int
     a.lists_bound = seg_bound;
     a.flat = 1;
     a.out = out;
+    if (row_bits >= 0) {
+        // short segments: one lane group per segment; long ones are recorded and summed by the
+        // block-cooperative kernel right after
+        RowSumParams rp;
+        rp.table = static_cast<const float *>(table);
+        rp.pay = ps;
+        rp.seg_start = w.seg_start;
+        rp.n_seg = w.list_off + 1;
+        rp.out = static_cast<float *>(out);
+        rp.D = D;
+        rp.pieces = D / 4;
+        rp.long_list = w.long_list;
+        rp.long_count = w.long_count;
+        OptAdagrad o;
+        o.n_feat = a.opt_n_feat;
+        for (int f = 0; f < a.opt_n_feat; f++) {
+            o.w[f] = a.opt_w[f];
+            o.m[f] = a.opt_m[f];
+        }
+        o.touched_rows = touched_rows;
+        o.seg_feat = w.seg_feat;
+        o.write_grad = out != nullptr;
+        o.lr = a.opt_lr;
+        o.eps = a.opt_eps;
+        const int P = rp.pieces;
+        const int lpr = P <= 16 ? 4 : (P <= 32 ? 8 : (P <= 64 ? 16 : (P <= 128 ? 32 : 64)));
+        const int per_block = 4 * (64 / lpr);
+        int64_t nblk = (seg_bound + per_block - 1) / per_block;
+        const int64_t cap = (int64_t)ctx->num_cu * 64;
+        if (nblk > cap)
+            nblk = cap;
+        if (nblk < 1)
+            nblk = 1;
+        const dim3 grid((unsigned)nblk), block(256);
+        switch (lpr) {
+        case 4: hipLaunchKernelGGL(k_segsum_rows<4>, grid, block, 0, st, rp, o); break;
+        case 8: hipLaunchKernelGGL(k_segsum_rows<8>, grid, block, 0, st, rp, o); break;
+        case 16: hipLaunchKernelGGL(k_segsum_rows<16>, grid, block, 0, st, rp, o); break;
+        case 32: hipLaunchKernelGGL(k_segsum_rows<32>, grid, block, 0, st, rp, o); break;
+        default: hipLaunchKernelGGL(k_segsum_rows<64>, grid, block, 0, st, rp, o); break;
+        }
+        RECD_HIP(ctx, hipGetLastError());
+        a.indirect = w.long_list;
+        a.indirect_count = w.long_count;
+        a.lists_bound = n_cap / 65 + 1;
+    }
     return recd_launch_segsum(ctx, a);
 }
 
@@ -570,7 +806,7 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
         uint32_t *k0 = static_cast<uint32_t *>(w.k0), *k1 = static_cast<uint32_t *>(w.k1);
         hipLaunchKernelGGL(k_keys_rows, dim3((unsigned)((n_lists + 255) / 256)), dim3(256), 0, st,
                            inverse, feat_uoff, B, n_lists, k0, w.p0, w.n_dev);
-        RECD_TRY(group_and_sum<uint32_t>(ctx, w, k0, k1, n_lists, U_cap, bits_for((uint64_t)n_lists), -1, F,
+        RECD_TRY(group_and_sum<uint32_t>(ctx, w, k0, k1, n_lists, U_cap, bits_for((uint64_t)(U_cap > 0 ? U_cap - 1 : 0)), -1, F,
                                          grad_out, D, w.g_u, nullptr, nullptr, nullptr));
     }
     // ---- step B: group unique-id positions by (feature, row), sum g_u rows into grad_rows --------

@@ -60,6 +60,19 @@ struct TablePtrs {
     const void *p[RECD_F_PER_LAUNCH];
 };
 
+// Optional epilogue of the row-gradient segment sums: row-wise Adagrad applied to the table row a
+// segment belongs to, straight from the registers that hold the segment's sum.
+struct OptNone {};
+struct OptAdagrad {
+    float *w[RECD_F_PER_LAUNCH];   // tables (n_feat == 0: no optimizer)
+    float *m[RECD_F_PER_LAUNCH];   // accumulators
+    const int64_t *touched_rows;   // [R] table row of every segment
+    const int32_t *seg_feat;       // [R] feature of every segment
+    int n_feat;
+    int write_grad;                // 0: the summed gradient rows are not stored
+    float lr, eps;
+};
+
 // ---- cross-file entry points (host side launchers) -------------------------------------------
 // Exclusive scan of n int64 pairs is private to each file; the segmented gather-sum is shared.
 enum { RECD_SITE_UNIQUE = 0, RECD_SITE_KJT = 1, RECD_SITE_GRAD_LISTS = 2, RECD_SITE_GRAD_ROWS = 3 };
@@ -76,6 +89,8 @@ struct SegSumArgs {
     int64_t list_base;        // added to every list index (feature chunking of the KJT path)
     int64_t lists_bound;      // host upper bound of the number of lists in this launch (sizes the grid)
     int flat;                 // 1: no XCD-aware feature->block mapping
+    const int32_t *indirect;        // optional (single table, flat): list numbers to process ...
+    const int64_t *indirect_count;  // ... and how many (device)
     int site;                 // RECD_SITE_*: which call site (each has its own kernel instantiation)
     // RECD_SITE_GRAD_ROWS only: fused row-wise Adagrad (opt_n_feat == 0: none)
     int opt_n_feat;

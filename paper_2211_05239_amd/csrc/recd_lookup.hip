@@ -29,7 +29,6 @@ namespace {
 
 constexpr int kNQ = 8;         // XCDs
 constexpr int kBlock = 256;
-constexpr int kWaves = kBlock / 64;
 constexpr int kMaxLB = 16;     // lists per block item (upper bound)
 constexpr int kChunk = 64;     // ids per chunk: a wave loads a chunk's ids with one instruction
 
@@ -124,16 +123,6 @@ enum { SITE_UNIQUE = 0, SITE_KJT = 1, SITE_GRAD_LISTS = 2, SITE_GRAD_ROWS = 3 };
 
 // Optional epilogue of SITE_GRAD_ROWS: row-wise Adagrad applied to the table row a segment belongs
 // to, straight from the registers that hold the segment's sum.
-struct OptNone {};
-struct OptAdagrad {
-    float *w[RECD_F_PER_LAUNCH];   // tables (nullptr array <=> n_feat == 0: no optimizer)
-    float *m[RECD_F_PER_LAUNCH];   // accumulators
-    const int64_t *touched_rows;   // [R] table row of every segment
-    const int32_t *seg_feat;       // [R] feature of every segment
-    int n_feat;
-    int write_grad;                // 0: the summed gradient rows are not stored
-    float lr, eps;
-};
 template <int SITE> struct OptOf { typedef OptNone type; };
 template <> struct OptOf<SITE_GRAD_ROWS> { typedef OptAdagrad type; };
 
@@ -150,6 +139,9 @@ struct SegSumParams {
     int vecs_per_row;  // D / elements per 16-byte vector
     int nq;            // 8: XCD-aware queues (feature f -> queue f mod 8); 1: one flat queue
     int lb;            // lists per block item, <= kMaxLB
+    // optional indirection (flat queue only): the lists to sum are indirect[0 .. *indirect_count)
+    const int32_t *indirect;
+    const int64_t *indirect_count;
 };
 
 // Adds the rows of NL chunks (chunk j: ns[j] <= 64 ids starting at values[starts[j]], rows of the
@@ -206,10 +198,13 @@ __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL]
     }
 }
 
-template <int LPR, int VPL, int TT, int OT, typename IdxT, int NL, int SITE>
-__global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p,
-                                                   const typename OptOf<SITE>::type opt)
+template <int LPR, int VPL, int TT, int OT, typename IdxT, int WAVES, int SITE>
+__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(VPL == 1 && WAVES == 4 ? 7 : 1))) void k_segsum(const SegSumParams p,
+                                                       const typename OptOf<SITE>::type opt)
 {
+    constexpr int NL = 1;            // lists a wave keeps in flight together
+    constexpr int kWaves = WAVES;    // waves per block (4; 16 for the long-segment pass of the backward)
+    constexpr int kBlock = 64 * WAVES;
     constexpr bool NT = SITE == SITE_KJT || SITE == SITE_GRAD_ROWS;  // streaming outputs
     constexpr int EPV = Elem<TT>::per_vec;
     constexpr int NACC = EPV * VPL;
@@ -217,7 +212,7 @@ __global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p,
     constexpr int OB = (OT == RECD_F32) ? EPV * 4 : 16;   // bytes a lane writes per vector
     constexpr int UNR = (VPL == 1) ? 8 : (VPL == 2 ? 4 : 2);
     constexpr int US = UNR / NL > 0 ? UNR / NL : 1;       // loads per list and round when NL lists share a wave
-    constexpr int LL = ROWF <= 256 ? 4 : (ROWF <= 512 ? 2 : 1);  // long lists folded per barrier pair
+    constexpr int LL = ROWF * WAVES <= 1024 ? 4 : (ROWF * WAVES <= 2048 ? 2 : 1);  // long lists folded per barrier pair
 
     __shared__ int64_t s_loff[RECD_F_PER_LAUNCH + 1];
     __shared__ int64_t s_qpref[RECD_F_PER_LAUNCH + 1];
@@ -262,7 +257,7 @@ __global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p,
             s_qpref[nslots] = all;
     }
     __syncthreads();
-    const int64_t total = s_qpref[nslots];
+    const int64_t total = p.indirect ? *p.indirect_count : s_qpref[nslots];
 
     const int g = lane / LPR;   // lane group = which of the G rows of a load
     const int r = lane % LPR;   // 16-byte piece of the row
@@ -369,7 +364,8 @@ __global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p,
                     hi = mid;
             }
             const int f = q + lo * nq;
-            const int64_t l = p.list_base + s_loff[f] + (t - s_qpref[lo]);
+            const int64_t l = p.indirect ? (int64_t)p.indirect[t]
+                                         : p.list_base + s_loff[f] + (t - s_qpref[lo]);
             s_feat[tid] = f;
             s_list[tid] = l;
             s_start[tid] = p.offsets[l];
@@ -419,8 +415,11 @@ __global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p,
 #pragma unroll
                         for (int i = 0; i < EPV; i++) {
                             const int x = (w * LPR + r) * EPV + i;
-                            tot[w * EPV + i] = ((s_part[e][0][x] + s_part[e][1][x]) + s_part[e][2][x]) +
-                                               s_part[e][3][x];
+                            float t_ = s_part[e][0][x];
+#pragma unroll
+                            for (int w2 = 1; w2 < kWaves; w2++)
+                                t_ += s_part[e][w2][x];  // wave order
+                            tot[w * EPV + i] = t_;
                         }
                     float dw[NACC], dm = 0.f;
                     fetch_dest(batch[e], dw, dm);
@@ -481,22 +480,17 @@ __global__ __launch_bounds__(kBlock) void k_segsum(const SegSumParams p,
 }
 
 template <int LPR, int VPL, int TT, int OT, typename IdxT, int SITE>
-void launch_one(hipStream_t st, int blocks, int nl, const SegSumParams &p,
+void launch_one(hipStream_t st, int blocks, int waves, const SegSumParams &p,
                 const typename OptOf<SITE>::type &opt)
 {
-    if constexpr (SITE == SITE_GRAD_LISTS || SITE == SITE_GRAD_ROWS) {
-        if (nl == 4) {
-            hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT, 4, SITE>), dim3(blocks), dim3(kBlock), 0, st,
-                               p, opt);
-            return;
-        }
-        if (nl == 2) {
-            hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT, 2, SITE>), dim3(blocks), dim3(kBlock), 0, st,
+    if constexpr (SITE == SITE_GRAD_ROWS) {
+        if (waves == 16) {
+            hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT, 16, SITE>), dim3(blocks), dim3(1024), 0, st,
                                p, opt);
             return;
         }
     }
-    hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT, 1, SITE>), dim3(blocks), dim3(kBlock), 0, st, p, opt);
+    hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT, 4, SITE>), dim3(blocks), dim3(256), 0, st, p, opt);
 }
 
 template <int TT, int OT, typename IdxT, int SITE>
@@ -518,15 +512,15 @@ bool launch_forward(hipStream_t st, int blocks, int v, const SegSumArgs &a, cons
 {
     const OptNone none;
     if (a.table_dt == RECD_F32 && a.out_dt == RECD_F32)
-        return launch_shape<RECD_F32, RECD_F32, int64_t, SITE>(st, blocks, 1, v, p, none);
+        return launch_shape<RECD_F32, RECD_F32, int64_t, SITE>(st, blocks, 4, v, p, none);
     if (a.table_dt == RECD_F16 && a.out_dt == RECD_F16)
-        return launch_shape<RECD_F16, RECD_F16, int64_t, SITE>(st, blocks, 1, v, p, none);
+        return launch_shape<RECD_F16, RECD_F16, int64_t, SITE>(st, blocks, 4, v, p, none);
     if (a.table_dt == RECD_F16 && a.out_dt == RECD_F32)
-        return launch_shape<RECD_F16, RECD_F32, int64_t, SITE>(st, blocks, 1, v, p, none);
+        return launch_shape<RECD_F16, RECD_F32, int64_t, SITE>(st, blocks, 4, v, p, none);
     if (a.table_dt == RECD_BF16 && a.out_dt == RECD_BF16)
-        return launch_shape<RECD_BF16, RECD_BF16, int64_t, SITE>(st, blocks, 1, v, p, none);
+        return launch_shape<RECD_BF16, RECD_BF16, int64_t, SITE>(st, blocks, 4, v, p, none);
     if (a.table_dt == RECD_BF16 && a.out_dt == RECD_F32)
-        return launch_shape<RECD_BF16, RECD_F32, int64_t, SITE>(st, blocks, 1, v, p, none);
+        return launch_shape<RECD_BF16, RECD_F32, int64_t, SITE>(st, blocks, 4, v, p, none);
     return false;
 }
 
@@ -621,6 +615,8 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     p.lists_per_feature = a.lists_per_feature;
     p.list_base = a.list_base;
     p.out = a.out;
+    p.indirect = a.indirect;
+    p.indirect_count = a.indirect_count;
     p.F = a.F;
     p.D = a.D;
     const int epv = a.table_dt == RECD_F32 ? 4 : 8;
@@ -628,18 +624,23 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     // Launch shape.  Any grid is correct (blocks stride over their queue); these choices only
     // decide how well the chip is filled.
     const int64_t n = a.lists_bound > 0 ? a.lists_bound : 1;
-    p.nq = (a.F >= kNQ && a.F % kNQ == 0 && !a.flat && !ctx->tune_flat) ? kNQ : 1;
+    p.nq = (a.F >= kNQ && a.F % kNQ == 0 && !a.flat && !ctx->tune_flat && !a.indirect) ? kNQ : 1;
     p.lb = n >= (512 << 10) ? 16 : (n >= (128 << 10) ? 8 : 4);
-    int nl = 1;
+    // the long-segment pass of the backward: few, very long lists -> 16 waves per list
+    const int nl = (a.site == RECD_SITE_GRAD_ROWS && a.indirect) ? 16 : 4;
     if (ctx->tune_lb > 0)
         p.lb = ctx->tune_lb;
-    if (ctx->tune_nl > 0)
-        nl = ctx->tune_nl;
+    if (a.indirect)
+        p.lb = 1;  // every list of this pass is long: one block per list
     const int64_t items = (n + p.lb - 1) / p.lb;
     int64_t nblk = p.nq == 1 ? items : kNQ * ((items + kNQ - 1) / kNQ + (items / kNQ) / 8 + 1);
     const int64_t cap = (int64_t)ctx->num_cu * 8 * (ctx->tune_gens > 0 ? ctx->tune_gens : 64);
     if (nblk > cap)
         nblk = cap / kNQ * kNQ;
+    // the indirect pass knows its true list count only on the device and it is usually far below
+    // the host bound: a resident-sized grid that strides wastes no blocks
+    if (a.indirect && nblk > (int64_t)ctx->num_cu * 2)
+        nblk = (int64_t)ctx->num_cu * 2;
     const int blocks = (int)nblk;
     bool ok = false;
     hipStream_t st = ctx->stream;
