@@ -109,13 +109,12 @@ __global__ __launch_bounds__(256) void k_scan_apply(uint32_t *__restrict__ data,
 }
 
 // in-place exclusive scan of data[0..n), n <= n_cap (host bound that sizes the grid)
-recd_status scan_u32(recd_ctx *ctx, uint32_t *data, const int64_t *n_dev, int64_t n_cap,
-                     uint32_t *bsum)
+recd_status scan_u32(recd_ctx *ctx, hipStream_t st, uint32_t *data, const int64_t *n_dev,
+                     int64_t n_cap, uint32_t *bsum)
 {
     const int64_t nb = (n_cap + kScanTile - 1) / kScanTile;
     if (nb == 0)
         return RECD_OK;
-    hipStream_t st = ctx->stream;
     hipLaunchKernelGGL(k_scan_reduce, dim3((unsigned)nb), dim3(256), 0, st, data, n_dev, n_cap, bsum);
     hipLaunchKernelGGL(k_scan_small, dim3(1), dim3(1024), 0, st, bsum, nb);
     hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)nb), dim3(256), 0, st, data, n_dev, n_cap, bsum);
@@ -255,12 +254,11 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(
 // Sorts (keys, pay) by the low `bits` bits of the key; returns through *kres/*pres which of the two
 // buffer pairs holds the result.
 template <typename KeyT>
-recd_status radix_sort_pairs(recd_ctx *ctx, KeyT *k0, uint32_t *p0, KeyT *k1, uint32_t *p1,
-                             const int64_t *n_dev, int64_t n_cap, int bits, uint32_t *hist,
-                             uint32_t *bsum, KeyT **kres, uint32_t **pres)
+recd_status radix_sort_pairs(recd_ctx *ctx, hipStream_t st, KeyT *k0, uint32_t *p0, KeyT *k1,
+                             uint32_t *p1, const int64_t *n_dev, int64_t n_cap, int bits,
+                             uint32_t *hist, uint32_t *bsum, KeyT **kres, uint32_t **pres)
 {
     const int ntiles = (int)((n_cap + kTile - 1) / kTile);
-    hipStream_t st = ctx->stream;
     KeyT *ka = k0, *kb = k1;
     uint32_t *pa = p0, *pb = p1;
     // fewest passes with digits of at most 9 bits, digits as even as possible
@@ -612,60 +610,77 @@ int bits_for(uint64_t max_value)
     return b;
 }
 
-struct BwdWs {
-    int64_t *n_dev, *list_off, *seg_start;
+// Buffers of one sort (the two sorts of a backward call run on two streams at the same time).
+struct SortSet {
+    int64_t *n_dev;  // [0] number of pairs, [1] capacity-overflow flag
     void *k0, *k1;
-    uint32_t *p0, *p1, *flag, *hist, *bsum;
+    uint32_t *p0, *p1, *hist, *bsum;
+};
+
+struct BwdWs {
+    SortSet a, b;
+    int64_t *list_off, *seg_start;
+    uint32_t *flag;
     int32_t *seg_feat, *long_list;
     int64_t *long_count;
     float *g_u;
     size_t bytes;
 };
 
+SortSet carve_sort(WsCarver &c, int64_t n, bool wide_keys)
+{
+    SortSet s;
+    const int64_t ntiles = (n + kTile - 1) / kTile;
+    const int64_t hist_n = (int64_t)kRadixMax * ntiles;
+    s.n_dev = c.take<int64_t>(2);
+    if (wide_keys) {
+        s.k0 = c.take<uint64_t>(n);
+        s.k1 = c.take<uint64_t>(n);
+    } else {
+        s.k0 = c.take<uint32_t>(n);
+        s.k1 = c.take<uint32_t>(n);
+    }
+    s.p0 = c.take<uint32_t>(n);
+    s.p1 = c.take<uint32_t>(n);
+    s.hist = c.take<uint32_t>(hist_n);
+    // block sums of the head-flag scan, and the digit totals of a sort pass
+    s.bsum = c.take<uint32_t>((n + kScanTile - 1) / kScanTile + 1 + kRadixMax);
+    return s;
+}
+
 BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D)
 {
     WsCarver c(base);
     BwdWs w;
     const int64_t n_max = n_lists > M_cap ? n_lists : M_cap;
-    const int64_t ntiles = (n_max + kTile - 1) / kTile;
-    const int64_t hist_n = (int64_t)kRadixMax * ntiles;
-    const int64_t scan_max = hist_n > n_max ? hist_n : n_max;
     int64_t u_cap = M_cap + F < n_lists ? M_cap + F : n_lists;
-    w.n_dev = c.take<int64_t>(2);
+    w.a = carve_sort(c, n_lists, false);
+    w.b = carve_sort(c, M_cap, true);
     w.list_off = c.take<int64_t>(2);
     w.seg_start = c.take<int64_t>(n_max + 1);
-    w.k0 = c.take<uint64_t>(n_max);
-    w.k1 = c.take<uint64_t>(n_max);
-    w.p0 = c.take<uint32_t>(n_max);
-    w.p1 = c.take<uint32_t>(n_max);
     w.flag = c.take<uint32_t>(n_max);
     w.seg_feat = c.take<int32_t>(n_max);
     w.long_list = c.take<int32_t>(n_max / 65 + 16);
     w.long_count = c.take<int64_t>(1);
-    w.hist = c.take<uint32_t>(hist_n);
-    w.bsum = c.take<uint32_t>((scan_max + kScanTile - 1) / kScanTile + 1 + kRadixMax);  // also digit totals
     w.g_u = c.take<float>((size_t)u_cap * D);
     w.bytes = c.off;
     return w;
 }
 
+// Segments of equal keys in the sorted pairs (ks, ps) of `set`, then the sum of every segment's rows.
 template <typename KeyT>
-recd_status group_and_sum(recd_ctx *ctx, const BwdWs &w, KeyT *k0, KeyT *k1, int64_t n_cap,
-                          int64_t seg_bound, int bits, int row_bits, int F, const void *table,
-                          int D, void *out, int64_t *touched_rows, int64_t *feat_roff,
-                          const SegSumArgs *opt)
+recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, const KeyT *ks,
+                            const uint32_t *ps, int64_t n_cap, int64_t seg_bound, int row_bits, int F,
+                            const void *table, int D, void *out, int64_t *touched_rows,
+                            int64_t *feat_roff, const SegSumArgs *opt)
 {
-    KeyT *ks;
-    uint32_t *ps;
-    RECD_TRY(radix_sort_pairs<KeyT>(ctx, k0, w.p0, k1, w.p1, w.n_dev, n_cap, bits, w.hist, w.bsum,
-                                    &ks, &ps));
     hipStream_t st = ctx->stream;
     int blocks = (int)((n_cap + 255) / 256 < 2048 ? (n_cap + 255) / 256 : 2048);
     if (blocks < 1)
         blocks = 1;
-    hipLaunchKernelGGL((k_heads<KeyT>), dim3(blocks), dim3(256), 0, st, ks, w.n_dev, w.flag, w.long_count);
-    RECD_TRY(scan_u32(ctx, w.flag, w.n_dev, n_cap, w.bsum));
-    hipLaunchKernelGGL((k_segments<KeyT>), dim3(blocks), dim3(256), 0, st, ks, w.n_dev, w.flag,
+    hipLaunchKernelGGL((k_heads<KeyT>), dim3(blocks), dim3(256), 0, st, ks, set.n_dev, w.flag, w.long_count);
+    RECD_TRY(scan_u32(ctx, st, w.flag, set.n_dev, n_cap, set.bsum));
+    hipLaunchKernelGGL((k_segments<KeyT>), dim3(blocks), dim3(256), 0, st, ks, set.n_dev, w.flag,
                        w.seg_start, w.list_off, row_bits, F, touched_rows, feat_roff, w.seg_feat);
     RECD_HIP(ctx, hipGetLastError());
     SegSumArgs a{};
@@ -801,15 +816,6 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
         return RECD_OK;
     }
 
-    // ---- step A: group rows (f,b) by unique list, sum grad_out rows into g_u --------------------
-    {
-        uint32_t *k0 = static_cast<uint32_t *>(w.k0), *k1 = static_cast<uint32_t *>(w.k1);
-        hipLaunchKernelGGL(k_keys_rows, dim3((unsigned)((n_lists + 255) / 256)), dim3(256), 0, st,
-                           inverse, feat_uoff, B, n_lists, k0, w.p0, w.n_dev);
-        RECD_TRY(group_and_sum<uint32_t>(ctx, w, k0, k1, n_lists, U_cap, bits_for((uint64_t)(U_cap > 0 ? U_cap - 1 : 0)), -1, F,
-                                         grad_out, D, w.g_u, nullptr, nullptr, nullptr));
-    }
-    // ---- step B: group unique-id positions by (feature, row), sum g_u rows into grad_rows --------
     // Row-wise Adagrad runs inside the row-gradient segment sum while the sum is still in
     // registers; with more features than one launch carries it runs as a kernel of its own.
     const bool fused = tables != nullptr && F <= RECD_F_PER_LAUNCH;
@@ -821,25 +827,58 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
         oa.opt_lr = lr;
         oa.opt_eps = eps;
     }
+    const int row_bits = bits_for((uint64_t)(max_rows - 1));
+    const int bits_b = row_bits + bits_for((uint64_t)(F > 1 ? F - 1 : 1));
+    const int bits_a = bits_for((uint64_t)(U_cap > 1 ? U_cap - 1 : 1));
+    const bool wide = bits_b > 32;
+
+    // ---- the sort of step B needs nothing from step A: it runs on the side stream meanwhile ------
+    hipStream_t side = ctx->side_stream;
+    RECD_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
+    RECD_HIP(ctx, hipStreamWaitEvent(side, ctx->ev_fork, 0));
+    void *ks_b = nullptr;
+    uint32_t *ps_b = nullptr;
     {
-        const int row_bits = bits_for((uint64_t)(max_rows - 1));
-        const int bits = row_bits + bits_for((uint64_t)(F > 1 ? F - 1 : 1));
         constexpr int SG = 16;
         const unsigned kb = (unsigned)((n_lists + (256 / SG) - 1) / (256 / SG));
-        if (bits <= 32) {
-            uint32_t *k0 = static_cast<uint32_t *>(w.k0), *k1 = static_cast<uint32_t *>(w.k1);
-            hipLaunchKernelGGL((k_keys_ids<uint32_t, SG>), dim3(kb), dim3(256), 0, st, u_values,
-                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.p0, w.n_dev);
-            RECD_TRY(group_and_sum<uint32_t>(ctx, w, k0, k1, M_cap, M_cap, bits, row_bits, F, w.g_u, D,
-                                             grad_rows, touched_rows, feat_roff, fused ? &oa : nullptr));
+        if (!wide) {
+            uint32_t *k0 = static_cast<uint32_t *>(w.b.k0), *k1 = static_cast<uint32_t *>(w.b.k1), *ks;
+            hipLaunchKernelGGL((k_keys_ids<uint32_t, SG>), dim3(kb), dim3(256), 0, side, u_values,
+                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev);
+            RECD_TRY(radix_sort_pairs<uint32_t>(ctx, side, k0, w.b.p0, k1, w.b.p1, w.b.n_dev, M_cap, bits_b,
+                                                w.b.hist, w.b.bsum, &ks, &ps_b));
+            ks_b = ks;
         } else {
-            uint64_t *k0 = static_cast<uint64_t *>(w.k0), *k1 = static_cast<uint64_t *>(w.k1);
-            hipLaunchKernelGGL((k_keys_ids<uint64_t, SG>), dim3(kb), dim3(256), 0, st, u_values,
-                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.p0, w.n_dev);
-            RECD_TRY(group_and_sum<uint64_t>(ctx, w, k0, k1, M_cap, M_cap, bits, row_bits, F, w.g_u, D,
-                                             grad_rows, touched_rows, feat_roff, fused ? &oa : nullptr));
+            uint64_t *k0 = static_cast<uint64_t *>(w.b.k0), *k1 = static_cast<uint64_t *>(w.b.k1), *ks;
+            hipLaunchKernelGGL((k_keys_ids<uint64_t, SG>), dim3(kb), dim3(256), 0, side, u_values,
+                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev);
+            RECD_TRY(radix_sort_pairs<uint64_t>(ctx, side, k0, w.b.p0, k1, w.b.p1, w.b.n_dev, M_cap, bits_b,
+                                                w.b.hist, w.b.bsum, &ks, &ps_b));
+            ks_b = ks;
         }
+        RECD_HIP(ctx, hipGetLastError());
+        RECD_HIP(ctx, hipEventRecord(ctx->ev_join, side));
     }
+    // ---- step A: group rows (f,b) by unique list, sum grad_out rows into g_u --------------------
+    {
+        uint32_t *k0 = static_cast<uint32_t *>(w.a.k0), *k1 = static_cast<uint32_t *>(w.a.k1), *ks, *ps;
+        hipLaunchKernelGGL(k_keys_rows, dim3((unsigned)((n_lists + 255) / 256)), dim3(256), 0, st,
+                           inverse, feat_uoff, B, n_lists, k0, w.a.p0, w.a.n_dev);
+        RECD_TRY(radix_sort_pairs<uint32_t>(ctx, st, k0, w.a.p0, k1, w.a.p1, w.a.n_dev, n_lists, bits_a,
+                                            w.a.hist, w.a.bsum, &ks, &ps));
+        RECD_TRY(segment_and_sum<uint32_t>(ctx, w, w.a, ks, ps, n_lists, U_cap, -1, F, grad_out, D, w.g_u,
+                                           nullptr, nullptr, nullptr));
+    }
+    // ---- step B: group unique-id positions by (feature, row), sum g_u rows into grad_rows --------
+    RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
+    if (!wide)
+        RECD_TRY(segment_and_sum<uint32_t>(ctx, w, w.b, static_cast<const uint32_t *>(ks_b), ps_b, M_cap,
+                                           M_cap, row_bits, F, w.g_u, D, grad_rows, touched_rows,
+                                           feat_roff, fused ? &oa : nullptr));
+    else
+        RECD_TRY(segment_and_sum<uint64_t>(ctx, w, w.b, static_cast<const uint64_t *>(ks_b), ps_b, M_cap,
+                                           M_cap, row_bits, F, w.g_u, D, grad_rows, touched_rows,
+                                           feat_roff, fused ? &oa : nullptr));
     // ---- optimizer -------------------------------------------------------------------------------
     if (tables && !fused) {
         for (int f0 = 0; f0 < F; f0 += RECD_F_PER_LAUNCH) {
@@ -857,7 +896,7 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
     if (host_R) {
         RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, w.list_off + 1, sizeof(int64_t),
                                      hipMemcpyDeviceToHost, st));
-        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned + 1, w.n_dev + 1, sizeof(int64_t),
+        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned + 1, w.b.n_dev + 1, sizeof(int64_t),
                                      hipMemcpyDeviceToHost, st));
         RECD_HIP(ctx, hipStreamSynchronize(st));
         host_R[0] = ctx->host_pinned[0];

@@ -72,6 +72,9 @@ recd_status recd_create(recd_ctx **out, int device, void *hip_stream, size_t wor
     hipDeviceProp_t prop;
     if (ok && hipGetDeviceProperties(&prop, device) == hipSuccess && prop.multiProcessorCount > 0)
         ctx->num_cu = prop.multiProcessorCount;
+    ok = ok && hipStreamCreateWithFlags(&ctx->side_stream, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) == hipSuccess;
     void *p = nullptr;
     ok = ok && hipHostMalloc(&p, 8 * sizeof(int64_t), hipHostMallocDefault) == hipSuccess;
     ctx->host_pinned = static_cast<int64_t *>(p);
@@ -92,6 +95,14 @@ recd_status recd_destroy(recd_ctx *ctx)
         return RECD_OK;
     (void)hipSetDevice(ctx->device);
     (void)hipStreamSynchronize(ctx->stream);
+    if (ctx->side_stream) {
+        (void)hipStreamSynchronize(ctx->side_stream);
+        (void)hipStreamDestroy(ctx->side_stream);
+    }
+    if (ctx->ev_fork)
+        (void)hipEventDestroy(ctx->ev_fork);
+    if (ctx->ev_join)
+        (void)hipEventDestroy(ctx->ev_join);
     if (ctx->ws)
         (void)hipFree(ctx->ws);
     if (ctx->host_pinned)

@@ -11,6 +11,8 @@
 struct recd_ctx {
     int device = 0;
     hipStream_t stream = nullptr;
+    hipStream_t side_stream = nullptr;   // independent work of one call (default priority, non-blocking)
+    hipEvent_t ev_fork = nullptr, ev_join = nullptr;
     char *ws = nullptr;          // device workspace
     size_t ws_bytes = 0;
     int64_t *host_pinned = nullptr;  // 8 x int64 pinned staging for scalar results
