@@ -15,6 +15,8 @@
 // among the wave's earlier keys, and a prefix over the four waves completes the stable rank.
 #include "recd_internal.h"
 
+#include <type_traits>
+
 namespace {
 
 constexpr int kSortThreads = 256;
@@ -337,8 +339,10 @@ __global__ void k_heads(const KeyT *__restrict__ keys, const int64_t *n_dev, uin
                         int64_t *long_count)
 {
     const int64_t n = *n_dev;
-    if (blockIdx.x == 0 && threadIdx.x == 0)
-        *long_count = 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        long_count[0] = 0;
+        long_count[1] = 0;
+    }
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
          i += (int64_t)gridDim.x * blockDim.x)
         flag[i] = (i == 0 || keys[i] != keys[i - 1]) ? 1u : 0u;
@@ -470,39 +474,115 @@ struct RowSumParams {
     float *out;                // grad_rows [R, D] or nullptr
     int D;
     int pieces;                // D / 4
-    int32_t *long_list;        // segments left to the cooperative kernel ...
-    int64_t *long_count;       // ... and how many
+    // segments longer than 64 entries are cut into chunks (work items) whose partial sums another
+    // kernel computes; lseg_* describe the cut segments, item_* the chunks
+    int64_t *long_count;       // [0] cut segments, [1] chunks
+    int32_t *lseg_t, *lseg_first, *lseg_n;
+    int64_t *item_start, *item_end;
+    const float *partials;     // [chunks, D] (k_long_finalize)
 };
 
+// Tail of a row-gradient segment held by a lane group: acc = the segment's sum (piece w of lane r).
+// Applies row-wise Adagrad to the destination row (operands fetched earlier into wreg/mreg) and/or
+// stores the gradient row.
 template <int LPR>
+__device__ __forceinline__ void finish_segment(const RowSumParams &p, const OptAdagrad &opt, int64_t t,
+                                               const float4 *acc, const float4 *wreg, float mreg,
+                                               float *wrow, float *mp, const bool *piece, int r,
+                                               bool update)
+{
+    constexpr int VPL = 4;
+    if (update) {
+        float ss = 0.f;
+#pragma unroll
+        for (int w = 0; w < VPL; w++)
+            if (piece[w]) {
+                ss += acc[w].x * acc[w].x;
+                ss += acc[w].y * acc[w].y;
+                ss += acc[w].z * acc[w].z;
+                ss += acc[w].w * acc[w].w;
+            }
+#pragma unroll
+        for (int s = 1; s < LPR; s <<= 1)
+            ss += __shfl_xor(ss, s);
+        const float mnew = mreg + ss / (float)p.D;
+        const float scale = opt.lr / (sqrtf(mnew) + opt.eps);
+#pragma unroll
+        for (int w = 0; w < VPL; w++)
+            if (piece[w]) {
+                float4 x = wreg[w];
+                x.x -= scale * acc[w].x;
+                x.y -= scale * acc[w].y;
+                x.z -= scale * acc[w].z;
+                x.w -= scale * acc[w].w;
+                reinterpret_cast<float4 *>(wrow)[w * LPR + r] = x;
+            }
+        if (r == 0)
+            *mp = mnew;
+    }
+    if (p.out) {
+        typedef float f32x4 __attribute__((ext_vector_type(4)));
+        f32x4 *dst = reinterpret_cast<f32x4 *>(p.out + t * p.D);
+#pragma unroll
+        for (int w = 0; w < VPL; w++)
+            if (piece[w]) {
+                const f32x4 o = {acc[w].x, acc[w].y, acc[w].z, acc[w].w};
+                __builtin_nontemporal_store(o, &dst[w * LPR + r]);
+            }
+    }
+}
+
+// FINALIZE = false: segments of at most 64 entries are summed here, longer ones are cut into chunks.
+// FINALIZE = true: the "segments" are the cut ones; their entries are the chunk partial sums, in
+// chunk order.
+template <int LPR, bool FINALIZE>
 __global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const OptAdagrad opt)
 {
     constexpr int G = 64 / LPR, VPL = 4, US = 2;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int g = lane / LPR, r = lane % LPR;
-    const int64_t R = *p.n_seg;
+    const int64_t R = FINALIZE ? p.long_count[0] : *p.n_seg;
     const int per_block = (256 / 64) * G;
-    const float4 *table = reinterpret_cast<const float4 *>(p.table);
+    const float4 *table = reinterpret_cast<const float4 *>(FINALIZE ? p.partials : p.table);
     bool piece[VPL];
 #pragma unroll
     for (int w = 0; w < VPL; w++)
         piece[w] = w * LPR + r < p.pieces;
 
     for (int64_t t0 = (int64_t)blockIdx.x * per_block; t0 < R; t0 += (int64_t)gridDim.x * per_block) {
-        const int64_t t = t0 + wv * G + g;
+        const int64_t k = t0 + wv * G + g;
+        int64_t t = k;       // destination segment
         int64_t start = 0;
         int n = 0;
-        if (t < R) {
-            start = p.seg_start[t];
-            const int64_t len = p.seg_start[t + 1] - start;
-            if (len > 64) {
-                if (r == 0) {
-                    const unsigned long long pos =
-                        atomicAdd(reinterpret_cast<unsigned long long *>(p.long_count), 1ull);
-                    p.long_list[pos] = (int32_t)t;
-                }
+        if (k < R) {
+            if (FINALIZE) {
+                t = p.lseg_t[k];
+                start = p.lseg_first[k];
+                n = p.lseg_n[k];
             } else {
-                n = (int)len;
+                start = p.seg_start[k];
+                const int64_t end = p.seg_start[k + 1];
+                const int64_t len = end - start;
+                if (len <= 64) {
+                    n = (int)len;
+                } else if (r == 0) {
+                    // chunks of 256 entries, or larger ones if that would give more than 64 chunks
+                    int64_t ch = 256;
+                    if ((len + ch - 1) / ch > 64)
+                        ch = (len + 63) / 64;
+                    const int nch = (int)((len + ch - 1) / ch);
+                    const int64_t first = (int64_t)atomicAdd(
+                        reinterpret_cast<unsigned long long *>(p.long_count + 1), (unsigned long long)nch);
+                    const int64_t slot =
+                        (int64_t)atomicAdd(reinterpret_cast<unsigned long long *>(p.long_count), 1ull);
+                    p.lseg_t[slot] = (int32_t)k;
+                    p.lseg_first[slot] = (int32_t)first;
+                    p.lseg_n[slot] = nch;
+                    for (int c = 0; c < nch; c++) {
+                        p.item_start[first + c] = start + c * ch;
+                        p.item_end[first + c] = start + (c + 1) * ch < end ? start + (c + 1) * ch : end;
+                    }
+                }
             }
         }
         const bool mine = n > 0;  // uniform inside the lane group
@@ -526,17 +606,19 @@ __global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const
         for (int w = 0; w < VPL; w++)
             acc[w] = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int i = 0; i < n; i += US) {
-            uint32_t id[US];
+            int64_t id[US];
 #pragma unroll
-            for (int u = 0; u < US; u++)
-                id[u] = p.pay[start + (i + u < n ? i + u : i)];
+            for (int u = 0; u < US; u++) {
+                const int64_t j = start + (i + u < n ? i + u : i);
+                id[u] = FINALIZE ? j : (int64_t)p.pay[j];
+            }
             float4 v[US][VPL];
 #pragma unroll
             for (int u = 0; u < US; u++)
 #pragma unroll
                 for (int w = 0; w < VPL; w++)
                     if (piece[w])
-                        v[u][w] = table[(int64_t)id[u] * p.pieces + w * LPR + r];
+                        v[u][w] = table[id[u] * p.pieces + w * LPR + r];
 #pragma unroll
             for (int u = 0; u < US; u++)
                 if (i + u < n)
@@ -549,46 +631,8 @@ __global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const
                             acc[w].w += v[u][w].w;
                         }
         }
-        if (mine) {
-            if (update) {
-                float ss = 0.f;
-#pragma unroll
-                for (int w = 0; w < VPL; w++)
-                    if (piece[w]) {
-                        ss += acc[w].x * acc[w].x;
-                        ss += acc[w].y * acc[w].y;
-                        ss += acc[w].z * acc[w].z;
-                        ss += acc[w].w * acc[w].w;
-                    }
-#pragma unroll
-                for (int s = 1; s < LPR; s <<= 1)
-                    ss += __shfl_xor(ss, s);
-                const float mnew = mreg + ss / (float)p.D;
-                const float scale = opt.lr / (sqrtf(mnew) + opt.eps);
-#pragma unroll
-                for (int w = 0; w < VPL; w++)
-                    if (piece[w]) {
-                        float4 x = wreg[w];
-                        x.x -= scale * acc[w].x;
-                        x.y -= scale * acc[w].y;
-                        x.z -= scale * acc[w].z;
-                        x.w -= scale * acc[w].w;
-                        reinterpret_cast<float4 *>(wrow)[w * LPR + r] = x;
-                    }
-                if (r == 0)
-                    *mp = mnew;
-            }
-            if (p.out) {
-                float4 *dst = reinterpret_cast<float4 *>(p.out + t * p.D);
-#pragma unroll
-                for (int w = 0; w < VPL; w++)
-                    if (piece[w]) {
-                        typedef float f32x4 __attribute__((ext_vector_type(4)));
-                        const f32x4 o = {acc[w].x, acc[w].y, acc[w].z, acc[w].w};
-                        __builtin_nontemporal_store(o, reinterpret_cast<f32x4 *>(&dst[w * LPR + r]));
-                    }
-            }
-        }
+        if (mine)
+            finish_segment<LPR>(p, opt, t, acc, wreg, mreg, wrow, mp, piece, r, update);
     }
 }
 
@@ -621,9 +665,9 @@ struct BwdWs {
     SortSet a, b;
     int64_t *list_off, *seg_start;
     uint32_t *flag;
-    int32_t *seg_feat, *long_list;
-    int64_t *long_count;
-    float *g_u;
+    int32_t *seg_feat, *lseg_t, *lseg_first, *lseg_n;
+    int64_t *long_count, *item_start, *item_end;
+    float *g_u, *partials;
     size_t bytes;
 };
 
@@ -660,8 +704,15 @@ BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D)
     w.seg_start = c.take<int64_t>(n_max + 1);
     w.flag = c.take<uint32_t>(n_max);
     w.seg_feat = c.take<int32_t>(n_max);
-    w.long_list = c.take<int32_t>(n_max / 65 + 16);
-    w.long_count = c.take<int64_t>(1);
+    // segments longer than 64 entries: at most n/65 of them, cut into at most n/256 + n/65 chunks
+    const int64_t lseg_cap = n_max / 65 + 16, item_cap = n_max / 256 + n_max / 65 + 16;
+    w.lseg_t = c.take<int32_t>(lseg_cap);
+    w.lseg_first = c.take<int32_t>(lseg_cap);
+    w.lseg_n = c.take<int32_t>(lseg_cap);
+    w.long_count = c.take<int64_t>(2);
+    w.item_start = c.take<int64_t>(item_cap);
+    w.item_end = c.take<int64_t>(item_cap);
+    w.partials = c.take<float>((size_t)item_cap * D);
     w.g_u = c.take<float>((size_t)u_cap * D);
     w.bytes = c.off;
     return w;
@@ -712,8 +763,13 @@ recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, c
         rp.out = static_cast<float *>(out);
         rp.D = D;
         rp.pieces = D / 4;
-        rp.long_list = w.long_list;
         rp.long_count = w.long_count;
+        rp.lseg_t = w.lseg_t;
+        rp.lseg_first = w.lseg_first;
+        rp.lseg_n = w.lseg_n;
+        rp.item_start = w.item_start;
+        rp.item_end = w.item_end;
+        rp.partials = w.partials;
         OptAdagrad o;
         o.n_feat = a.opt_n_feat;
         for (int f = 0; f < a.opt_n_feat; f++) {
@@ -734,18 +790,37 @@ recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, c
             nblk = cap;
         if (nblk < 1)
             nblk = 1;
-        const dim3 grid((unsigned)nblk), block(256);
-        switch (lpr) {
-        case 4: hipLaunchKernelGGL(k_segsum_rows<4>, grid, block, 0, st, rp, o); break;
-        case 8: hipLaunchKernelGGL(k_segsum_rows<8>, grid, block, 0, st, rp, o); break;
-        case 16: hipLaunchKernelGGL(k_segsum_rows<16>, grid, block, 0, st, rp, o); break;
-        case 32: hipLaunchKernelGGL(k_segsum_rows<32>, grid, block, 0, st, rp, o); break;
-        default: hipLaunchKernelGGL(k_segsum_rows<64>, grid, block, 0, st, rp, o); break;
-        }
+        const dim3 block(256);
+        auto launch_rows = [&](auto fin, unsigned nb) {
+            constexpr bool FIN = decltype(fin)::value;
+            const dim3 grid(nb);
+            switch (lpr) {
+            case 4: hipLaunchKernelGGL((k_segsum_rows<4, FIN>), grid, block, 0, st, rp, o); break;
+            case 8: hipLaunchKernelGGL((k_segsum_rows<8, FIN>), grid, block, 0, st, rp, o); break;
+            case 16: hipLaunchKernelGGL((k_segsum_rows<16, FIN>), grid, block, 0, st, rp, o); break;
+            case 32: hipLaunchKernelGGL((k_segsum_rows<32, FIN>), grid, block, 0, st, rp, o); break;
+            default: hipLaunchKernelGGL((k_segsum_rows<64, FIN>), grid, block, 0, st, rp, o); break;
+            }
+        };
+        // 1. short segments summed and updated; long ones cut into chunks
+        launch_rows(std::false_type(), (unsigned)nblk);
         RECD_HIP(ctx, hipGetLastError());
-        a.indirect = w.long_list;
-        a.indirect_count = w.long_count;
-        a.lists_bound = n_cap / 65 + 1;
+        // 2. partial sum of every chunk (block-cooperative gather-sum, one block per chunk)
+        SegSumArgs c = a;
+        c.site = RECD_SITE_GRAD_LISTS;
+        c.opt_n_feat = 0;
+        c.offsets = w.item_start;
+        c.ends = w.item_end;
+        c.count_dev = w.long_count + 1;
+        c.list_off = nullptr;
+        c.lists_per_feature = 0;
+        c.lists_bound = n_cap / 256 + n_cap / 65 + 1;
+        c.out = w.partials;
+        RECD_TRY(recd_launch_segsum(ctx, c));
+        // 3. chunk partials added in chunk order, then the same update / store as in 1
+        launch_rows(std::true_type(), (unsigned)ctx->num_cu);
+        RECD_HIP(ctx, hipGetLastError());
+        return RECD_OK;
     }
     return recd_launch_segsum(ctx, a);
 }

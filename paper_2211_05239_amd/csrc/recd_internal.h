@@ -91,8 +91,8 @@ struct SegSumArgs {
     int64_t list_base;        // added to every list index (feature chunking of the KJT path)
     int64_t lists_bound;      // host upper bound of the number of lists in this launch (sizes the grid)
     int flat;                 // 1: no XCD-aware feature->block mapping
-    const int32_t *indirect;        // optional (single table, flat): list numbers to process ...
-    const int64_t *indirect_count;  // ... and how many (device)
+    const int64_t *ends;            // optional (single table, flat): list l ends at ends[l] ...
+    const int64_t *count_dev;       // ... and the number of lists lives on the device
     int site;                 // RECD_SITE_*: which call site (each has its own kernel instantiation)
     // RECD_SITE_GRAD_ROWS only: fused row-wise Adagrad (opt_n_feat == 0: none)
     int opt_n_feat;

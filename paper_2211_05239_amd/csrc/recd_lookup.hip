@@ -139,9 +139,10 @@ struct SegSumParams {
     int vecs_per_row;  // D / elements per 16-byte vector
     int nq;            // 8: XCD-aware queues (feature f -> queue f mod 8); 1: one flat queue
     int lb;            // lists per block item, <= kMaxLB
-    // optional indirection (flat queue only): the lists to sum are indirect[0 .. *indirect_count)
-    const int32_t *indirect;
-    const int64_t *indirect_count;
+    // optional (flat queue only): list l ends at ends[l] instead of offsets[l+1], and the number of
+    // lists is *count_dev
+    const int64_t *ends;
+    const int64_t *count_dev;
 };
 
 // Adds the rows of NL chunks (chunk j: ns[j] <= 64 ids starting at values[starts[j]], rows of the
@@ -257,7 +258,7 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(VPL 
             s_qpref[nslots] = all;
     }
     __syncthreads();
-    const int64_t total = p.indirect ? *p.indirect_count : s_qpref[nslots];
+    const int64_t total = p.count_dev ? *p.count_dev : s_qpref[nslots];
 
     const int g = lane / LPR;   // lane group = which of the G rows of a load
     const int r = lane % LPR;   // 16-byte piece of the row
@@ -364,12 +365,11 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(VPL 
                     hi = mid;
             }
             const int f = q + lo * nq;
-            const int64_t l = p.indirect ? (int64_t)p.indirect[t]
-                                         : p.list_base + s_loff[f] + (t - s_qpref[lo]);
+            const int64_t l = p.count_dev ? t : p.list_base + s_loff[f] + (t - s_qpref[lo]);
             s_feat[tid] = f;
             s_list[tid] = l;
             s_start[tid] = p.offsets[l];
-            s_end[tid] = p.offsets[l + 1];
+            s_end[tid] = p.ends ? p.ends[l] : p.offsets[l + 1];
             if constexpr (SITE == SITE_GRAD_ROWS) {
                 if (opt.n_feat > 0) {
                     s_dfeat[tid] = opt.seg_feat[l];
@@ -483,13 +483,7 @@ template <int LPR, int VPL, int TT, int OT, typename IdxT, int SITE>
 void launch_one(hipStream_t st, int blocks, int waves, const SegSumParams &p,
                 const typename OptOf<SITE>::type &opt)
 {
-    if constexpr (SITE == SITE_GRAD_ROWS) {
-        if (waves == 16) {
-            hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT, 16, SITE>), dim3(blocks), dim3(1024), 0, st,
-                               p, opt);
-            return;
-        }
-    }
+    (void)waves;
     hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT, 4, SITE>), dim3(blocks), dim3(256), 0, st, p, opt);
 }
 
@@ -615,8 +609,8 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     p.lists_per_feature = a.lists_per_feature;
     p.list_base = a.list_base;
     p.out = a.out;
-    p.indirect = a.indirect;
-    p.indirect_count = a.indirect_count;
+    p.ends = a.ends;
+    p.count_dev = a.count_dev;
     p.F = a.F;
     p.D = a.D;
     const int epv = a.table_dt == RECD_F32 ? 4 : 8;
@@ -624,23 +618,22 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     // Launch shape.  Any grid is correct (blocks stride over their queue); these choices only
     // decide how well the chip is filled.
     const int64_t n = a.lists_bound > 0 ? a.lists_bound : 1;
-    p.nq = (a.F >= kNQ && a.F % kNQ == 0 && !a.flat && !ctx->tune_flat && !a.indirect) ? kNQ : 1;
+    p.nq = (a.F >= kNQ && a.F % kNQ == 0 && !a.flat && !ctx->tune_flat && !a.count_dev) ? kNQ : 1;
     p.lb = n >= (512 << 10) ? 16 : (n >= (128 << 10) ? 8 : 4);
-    // the long-segment pass of the backward: few, very long lists -> 16 waves per list
-    const int nl = (a.site == RECD_SITE_GRAD_ROWS && a.indirect) ? 16 : 4;
+    const int nl = 4;
     if (ctx->tune_lb > 0)
         p.lb = ctx->tune_lb;
-    if (a.indirect)
-        p.lb = 1;  // every list of this pass is long: one block per list
+    if (a.count_dev)
+        p.lb = 1;  // chunks of long segments: every list is long, one block per list
     const int64_t items = (n + p.lb - 1) / p.lb;
     int64_t nblk = p.nq == 1 ? items : kNQ * ((items + kNQ - 1) / kNQ + (items / kNQ) / 8 + 1);
     const int64_t cap = (int64_t)ctx->num_cu * 8 * (ctx->tune_gens > 0 ? ctx->tune_gens : 64);
     if (nblk > cap)
         nblk = cap / kNQ * kNQ;
-    // the indirect pass knows its true list count only on the device and it is usually far below
-    // the host bound: a resident-sized grid that strides wastes no blocks
-    if (a.indirect && nblk > (int64_t)ctx->num_cu * 2)
-        nblk = (int64_t)ctx->num_cu * 2;
+    // a pass whose true list count lives on the device is usually far below the host bound: a
+    // resident-sized grid that strides wastes no blocks
+    if (a.count_dev && nblk > (int64_t)ctx->num_cu * 8)
+        nblk = (int64_t)ctx->num_cu * 8;
     const int blocks = (int)nblk;
     bool ok = false;
     hipStream_t st = ctx->stream;

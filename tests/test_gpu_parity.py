@@ -285,6 +285,31 @@ def test_backward_skewed_ids(ctx):
     _backward_case(ctx, w, 0)
 
 
+def test_backward_giant_segment(ctx):
+    """One table row named by 20000 different unique lists: its gradient segment is cut into chunks
+    larger than the default (more than 64 default-sized chunks), summed in two levels."""
+    B = 20000
+    lists = [[7, 100 + i] for i in range(B)]
+    batch = synth.batch_from_lists([lists])
+    rows, D = 100 + B, 8
+    rng = np.random.default_rng(17)
+    gout = rng.standard_normal((1, B, D)).astype(np.float32)
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    assert ik.U == B
+    touched = torch.zeros(ik.M, dtype=torch.int64, device="cuda")
+    feat_roff = torch.zeros(2, dtype=torch.int64, device="cuda")
+    grad_rows = torch.zeros(ik.M, D, device="cuda")
+    R = ctx.backward_dedup(1, B, gu.to_dev(gout), ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets,
+                           [rows], ik.U, ik.M, touched, feat_roff, grad_rows, want_count=True)
+    uv, uo, inv, fu = orc.build_ikjt(1, B, batch.values, batch.offsets)
+    tr, fr, gr = orc.backward_dedup(1, B, gout, inv, fu, uv, uo)
+    assert R == len(tr) == B + 1 and np.array_equal(touched[:R].cpu().numpy(), tr)
+    got = grad_rows[:R].double().cpu().numpy()
+    # the giant row sums 20000 terms of magnitude ~1: fp32 accumulation in chunks stays within the bar
+    gu.assert_close_f32(got[1:], gr[1:], "single-entry rows")
+    assert np.all(np.abs(got[0] - gr[0]) <= 1e-5 * np.abs(gout).sum(axis=(0, 1))), "giant row"
+
+
 def test_backward_deterministic(ctx):
     w = synth.scaled(synth.WORKLOADS["cfg2"], F=4, B=1024, rows=20_000, D=64)
     a = _backward_case(ctx, w, 1, with_adagrad=False)
