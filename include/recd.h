@@ -69,10 +69,10 @@ typedef enum {
                                so that unequal lists collide constantly and only the exact list
                                comparison keeps them apart.  Results must not change.            */
     RECD_OPT_TUNE_SEGSUM = 3 /* tuning knob of the gather-sum kernel's launch shape, 0 = automatic:
-                               value = lists per block (4, 8 or 16) + 100 * lists in flight per wave
-                               (1, 2 or 4) + 10000 * block generations per CU (< 100) + 1000000 * (1 = no
-                               XCD-aware block mapping).  Results must not
-                               change (the summation order of a list never depends on it).        */
+                               value = lists per block (4, 8 or 16) + 10000 * block generations per
+                               CU (< 100) + 1000000 * (1 = no XCD-aware block mapping); the hundreds
+                               and thousands digits must be 0.  Results must not change (the
+                               summation order of a list never depends on it).                     */
 } recd_option;
 
 /* Largest number of features per call and largest row size in bytes (D * element size). */

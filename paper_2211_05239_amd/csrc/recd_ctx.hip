@@ -119,15 +119,14 @@ recd_status recd_set_option(recd_ctx *ctx, recd_option opt, int64_t value)
     case RECD_OPT_VALIDATE: ctx->validate = value != 0; return RECD_OK;
     case RECD_OPT_WEAK_HASH: ctx->weak_hash = value != 0; return RECD_OK;
     case RECD_OPT_TUNE_SEGSUM:
-        // value = lists_per_block + 100 * lists_in_flight_per_wave + 10000 * block_generations
+        // value = lists_per_block + 10000 * block_generations
         //         + 1000000 * (1 = never use the XCD-aware mapping)
         ctx->tune_lb = (int)(value % 100);
-        ctx->tune_nl = (int)(value / 100 % 100);
         ctx->tune_gens = (int)(value / 10000 % 100);
         ctx->tune_flat = (int)(value / 1000000 % 10);
-        if ((ctx->tune_lb != 0 && ctx->tune_lb != 4 && ctx->tune_lb != 8 && ctx->tune_lb != 16) ||
-            (ctx->tune_nl != 0 && ctx->tune_nl != 1 && ctx->tune_nl != 2 && ctx->tune_nl != 4)) {
-            ctx->tune_lb = ctx->tune_nl = ctx->tune_gens = ctx->tune_flat = 0;
+        if (value < 0 || value / 100 % 100 != 0 || value >= 2000000 ||
+            (ctx->tune_lb != 0 && ctx->tune_lb != 4 && ctx->tune_lb != 8 && ctx->tune_lb != 16)) {
+            ctx->tune_lb = ctx->tune_gens = ctx->tune_flat = 0;
             return recd_fail(ctx, RECD_EINVAL, "bad RECD_OPT_TUNE_SEGSUM value");
         }
         return RECD_OK;

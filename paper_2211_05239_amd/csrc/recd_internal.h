@@ -18,7 +18,7 @@ struct recd_ctx {
     int64_t *host_pinned = nullptr;  // 8 x int64 pinned staging for scalar results
     int validate = 0;
     int weak_hash = 0;
-    int tune_lb = 0, tune_nl = 0, tune_gens = 0, tune_flat = 0;  // launch-shape overrides of the gather-sum kernel (0 = automatic)
+    int tune_lb = 0, tune_gens = 0, tune_flat = 0;  // launch-shape overrides of the gather-sum kernel (0 = automatic)
     int num_cu = 256;
     std::string err;
 };

@@ -179,6 +179,26 @@ def test_forward_deterministic(ctx):
         assert torch.equal(_bits(x), _bits(y))  # rows of pooled beyond U keep their NaN fill
 
 
+def test_launch_shape_knob_keeps_results(ctx, recd):
+    """The tuning knob changes how lists are dealt to blocks, never the bits of a result."""
+    w = synth.scaled(synth.WORKLOADS["cfg3"], F=8, B=700, rows=20_000, D=128, table_dtype="f32")
+    ref = None
+    try:
+        for tune in (0, 4, 8, 16, 1000004, 20016):
+            ctx.set_option(recd.RECD_OPT_TUNE_SEGSUM, tune)
+            got = _forward_case(ctx, w, 0)[3:]
+            if ref is None:
+                ref = got
+            for x, y in zip(ref, got):
+                assert torch.equal(_bits(x), _bits(y)), tune
+        for bad in (5, 104, -1, 3000000):
+            with pytest.raises(recd.RecdError) as e:
+                ctx.set_option(recd.RECD_OPT_TUNE_SEGSUM, bad)
+            assert e.value.status == recd.RECD_EINVAL
+    finally:
+        ctx.set_option(recd.RECD_OPT_TUNE_SEGSUM, 0)
+
+
 def test_empty_lists_pool_to_zero(ctx):
     batch = synth.batch_from_lists([[[], [2], [], [2, 2]]])
     tab = [np.full((4, 8), 1.5, np.float32)]
