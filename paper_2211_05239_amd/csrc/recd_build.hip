@@ -44,6 +44,7 @@ __global__ void k_fill_u64(uint64_t *p, int64_t n, uint64_t v)
 // Lists per lane group and launch: the group's lists are consecutive, and the first loads of all of
 // them are issued together so that one group keeps several memory requests in flight.
 constexpr int kLPG = 1;
+constexpr int kHU = 4;   // strides of the long-list loop whose loads are issued together
 
 template <int SG>
 __global__ __launch_bounds__(256) void k_hash_insert(const int64_t *__restrict__ values,
@@ -93,17 +94,17 @@ __global__ __launch_bounds__(256) void k_hash_insert(const int64_t *__restrict__
             follows[k] &= pv[k] == v[k];
             h[k] = mix64((uint64_t)v[k] + (uint64_t)(s + 1) * 0x9e3779b97f4a7c15ull);
         }
-        // lists longer than the group: four strides per trip, all eight loads issued before use
-        for (int64_t t0 = s + SG; t0 < len[k]; t0 += 4 * SG) {
-            int64_t x[4], px[4];
+        // lists longer than the group: kHU strides per trip, all loads issued before use
+        for (int64_t t0 = s + SG; t0 < len[k]; t0 += kHU * SG) {
+            int64_t x[kHU], px[kHU];
 #pragma unroll
-            for (int u = 0; u < 4; u++) {
+            for (int u = 0; u < kHU; u++) {
                 const int64_t t = t0 + u * SG;
                 x[u] = t < len[k] ? values[start[k] + t] : 0;
                 px[u] = (follows[k] && t < len[k]) ? values[pstart[k] + t] : 0;
             }
 #pragma unroll
-            for (int u = 0; u < 4; u++) {
+            for (int u = 0; u < kHU; u++) {
                 const int64_t t = t0 + u * SG;
                 if (t < len[k]) {
                     follows[k] &= px[u] == x[u];
@@ -289,6 +290,7 @@ __global__ __launch_bounds__(kScanBlock) void k_number(const int64_t *__restrict
                                                        const int64_t *__restrict__ bs_head,
                                                        int32_t *__restrict__ rep,
                                                        int32_t *__restrict__ number,
+                                                       int32_t *__restrict__ src_of,
                                                        int64_t *__restrict__ u_offsets,
                                                        int64_t *__restrict__ feat_uoff,
                                                        int64_t *__restrict__ counts)
@@ -324,8 +326,10 @@ __global__ __launch_bounds__(kScanBlock) void k_number(const int64_t *__restrict
         const int64_t num = bs_cnt[blockIdx.x] + ea;  // unique lists before (f,b), all features
         const int64_t pos = bs_len[blockIdx.x] + eb;  // their ids
         number[l] = (int32_t)num;
-        if (first)
+        if (first) {
             u_offsets[num] = pos;
+            src_of[num] = (int32_t)l;
+        }
         if (b == 0)
             feat_uoff[f] = num;
         if (l == n_lists - 1) {
@@ -338,26 +342,37 @@ __global__ __launch_bounds__(kScanBlock) void k_number(const int64_t *__restrict
     }
 }
 
+// Last builder kernel, two kinds of blocks in one launch:
+//   blocks [0, inv_blocks): one thread per row, inverse[f,b] = number[rep] - number[f,0];
+//   the others: one group of SG lanes per *unique* list (source row recorded by k_number), striding
+//   until the device-side count U is reached, copy the list's ids into u_values.
 template <int SG>
 __global__ __launch_bounds__(256) void k_emit(const int64_t *__restrict__ values,
                                               const int64_t *__restrict__ offsets, int64_t B,
                                               int64_t n_lists, const int32_t *__restrict__ rep,
                                               const int32_t *__restrict__ number,
+                                              const int32_t *__restrict__ src_of,
                                               const int64_t *__restrict__ u_offsets,
+                                              const int64_t *__restrict__ counts,
                                               int64_t *__restrict__ u_values,
-                                              int32_t *__restrict__ inverse)
+                                              int32_t *__restrict__ inverse, unsigned inv_blocks)
 {
-    const int s = threadIdx.x % SG;
-    const int64_t l = (int64_t)blockIdx.x * (256 / SG) + threadIdx.x / SG;
-    if (l >= n_lists)
+    if (blockIdx.x < inv_blocks) {
+        const int64_t l = (int64_t)blockIdx.x * 256 + threadIdx.x;
+        if (l < n_lists) {
+            const int64_t f = l / B;
+            inverse[l] = number[f * B + rep[l]] - number[f * B];
+        }
         return;
-    const int64_t f = l / B, b = l - f * B;
-    const int64_t r = rep[l];
-    if (s == 0)
-        inverse[l] = number[f * B + r] - number[f * B];
-    if (r == b) {
+    }
+    const int s = threadIdx.x % SG;
+    const int64_t U = counts[0];
+    const int64_t stride = (int64_t)(gridDim.x - inv_blocks) * (256 / SG);
+    for (int64_t u = (int64_t)(blockIdx.x - inv_blocks) * (256 / SG) + threadIdx.x / SG; u < U;
+         u += stride) {
+        const int64_t l = src_of[u];
         const int64_t start = offsets[l], len = offsets[l + 1] - start;
-        const int64_t dst = u_offsets[number[l]];
+        const int64_t dst = u_offsets[u];
         for (int64_t t = s; t < len; t += SG)
             u_values[dst + t] = values[start + t];
     }
@@ -391,6 +406,7 @@ size_t recd_build_workspace(int F, int64_t B)
     const int64_t nblk = (n_lists + kScanBlock - 1) / kScanBlock;
     c.take<int64_t>(2);
     c.take<uint64_t>((size_t)F * table_cap(B));
+    c.take<int32_t>(n_lists);
     c.take<int32_t>(n_lists);
     c.take<int32_t>(n_lists);
     c.take<int32_t>(n_lists);
@@ -430,6 +446,7 @@ extern "C" recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t 
     int32_t *slot_of = c.take<int32_t>(n_lists);
     int32_t *rep = c.take<int32_t>(n_lists);
     int32_t *number = c.take<int32_t>(n_lists);
+    int32_t *src_of = c.take<int32_t>(n_lists);
     int64_t *bs_cnt = c.take<int64_t>(nblk + 1);
     int64_t *bs_len = c.take<int64_t>(nblk + 1);
     int64_t *bs_head = c.take<int64_t>(nblk + 1);
@@ -442,7 +459,6 @@ extern "C" recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t 
         const int64_t tab_n = (int64_t)F * (int64_t)cap;
         int fill_blocks = (int)((tab_n + 1023) / 1024 < 4096 ? (tab_n + 1023) / 1024 : 4096);
         hipLaunchKernelGGL(k_fill_u64, dim3(fill_blocks), dim3(256), 0, st, table, tab_n, kEmpty);
-        const int64_t gblocks = (n_lists + (256 / SG) - 1) / (256 / SG);
         const int64_t hblocks = (n_lists + (256 / SG) * kLPG - 1) / ((256 / SG) * kLPG);
         hipLaunchKernelGGL((k_hash_insert<SG>), dim3((unsigned)hblocks), dim3(256), 0, st, values,
                            offsets, B, n_lists, table, (uint32_t)(cap - 1), slot_of, ctx->weak_hash);
@@ -452,9 +468,14 @@ extern "C" recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t 
                            nblk);
         hipLaunchKernelGGL(k_number, dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets, B, n_lists,
                            F, table, (uint32_t)(cap - 1), slot_of, bs_cnt, bs_len, bs_head, rep, number,
-                           u_offsets, feat_uoff, counts);
-        hipLaunchKernelGGL((k_emit<SG>), dim3((unsigned)gblocks), dim3(256), 0, st, values, offsets, B,
-                           n_lists, rep, number, u_offsets, u_values, inverse);
+                           src_of, u_offsets, feat_uoff, counts);
+        const unsigned inv_blocks = (unsigned)((n_lists + 255) / 256);
+        int64_t copy_blocks = (n_lists + (256 / 16) - 1) / (256 / 16);
+        if (copy_blocks > (int64_t)ctx->num_cu * 8)
+            copy_blocks = (int64_t)ctx->num_cu * 8;
+        hipLaunchKernelGGL((k_emit<16>), dim3(inv_blocks + (unsigned)copy_blocks), dim3(256), 0, st, values,
+                           offsets, B, n_lists, rep, number, src_of, u_offsets, counts, u_values, inverse,
+                           inv_blocks);
     }
     RECD_HIP(ctx, hipGetLastError());
     if (host_U_M) {
