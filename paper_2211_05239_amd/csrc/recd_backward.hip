@@ -723,7 +723,7 @@ template <typename KeyT>
 recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, const KeyT *ks,
                             const uint32_t *ps, int64_t n_cap, int64_t seg_bound, int row_bits, int F,
                             const void *table, int D, void *out, int64_t *touched_rows,
-                            int64_t *feat_roff, const SegSumArgs *opt)
+                            int64_t *feat_roff, const OptAdagrad *opt)
 {
     hipStream_t st = ctx->stream;
     int blocks = (int)((n_cap + 255) / 256 < 2048 ? (n_cap + 255) / 256 : 2048);
@@ -735,11 +735,7 @@ recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, c
                        w.seg_start, w.list_off, row_bits, F, touched_rows, feat_roff, w.seg_feat);
     RECD_HIP(ctx, hipGetLastError());
     SegSumArgs a{};
-    if (opt)
-        a = *opt;  // optimizer fields of the row-gradient site
-    a.site = row_bits >= 0 ? RECD_SITE_GRAD_ROWS : RECD_SITE_GRAD_LISTS;
-    a.opt_touched_rows = touched_rows;
-    a.opt_seg_feat = w.seg_feat;
+    a.site = RECD_SITE_GRAD_LISTS;
     a.F = 1;
     a.D = D;
     a.table_dt = RECD_F32;
@@ -771,16 +767,12 @@ recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, c
         rp.item_end = w.item_end;
         rp.partials = w.partials;
         OptAdagrad o;
-        o.n_feat = a.opt_n_feat;
-        for (int f = 0; f < a.opt_n_feat; f++) {
-            o.w[f] = a.opt_w[f];
-            o.m[f] = a.opt_m[f];
-        }
+        if (opt)
+            o = *opt;
+        else
+            o.n_feat = 0;
         o.touched_rows = touched_rows;
         o.seg_feat = w.seg_feat;
-        o.write_grad = out != nullptr;
-        o.lr = a.opt_lr;
-        o.eps = a.opt_eps;
         const int P = rp.pieces;
         const int lpr = P <= 16 ? 4 : (P <= 32 ? 8 : (P <= 64 ? 16 : (P <= 128 ? 32 : 64)));
         const int per_block = 4 * (64 / lpr);
@@ -807,8 +799,6 @@ recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, c
         RECD_HIP(ctx, hipGetLastError());
         // 2. partial sum of every chunk (block-cooperative gather-sum, one block per chunk)
         SegSumArgs c = a;
-        c.site = RECD_SITE_GRAD_LISTS;
-        c.opt_n_feat = 0;
         c.offsets = w.item_start;
         c.ends = w.item_end;
         c.count_dev = w.long_count + 1;
@@ -894,13 +884,16 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
     // Row-wise Adagrad runs inside the row-gradient segment sum while the sum is still in
     // registers; with more features than one launch carries it runs as a kernel of its own.
     const bool fused = tables != nullptr && F <= RECD_F_PER_LAUNCH;
-    SegSumArgs oa{};
+    OptAdagrad oa;
+    oa.n_feat = 0;
     if (fused) {
-        oa.opt_n_feat = F;
-        oa.opt_w = reinterpret_cast<float *const *>(tables);
-        oa.opt_m = adagrad_state;
-        oa.opt_lr = lr;
-        oa.opt_eps = eps;
+        oa.n_feat = F;
+        for (int f = 0; f < F; f++) {
+            oa.w[f] = static_cast<float *>(tables[f]);
+            oa.m[f] = adagrad_state[f];
+        }
+        oa.lr = lr;
+        oa.eps = eps;
     }
     const int row_bits = bits_for((uint64_t)(max_rows - 1));
     const int bits_b = row_bits + bits_for((uint64_t)(F > 1 ? F - 1 : 1));

@@ -64,20 +64,18 @@ struct TablePtrs {
 
 // Optional epilogue of the row-gradient segment sums: row-wise Adagrad applied to the table row a
 // segment belongs to, straight from the registers that hold the segment's sum.
-struct OptNone {};
 struct OptAdagrad {
     float *w[RECD_F_PER_LAUNCH];   // tables (n_feat == 0: no optimizer)
     float *m[RECD_F_PER_LAUNCH];   // accumulators
     const int64_t *touched_rows;   // [R] table row of every segment
     const int32_t *seg_feat;       // [R] feature of every segment
     int n_feat;
-    int write_grad;                // 0: the summed gradient rows are not stored
     float lr, eps;
 };
 
 // ---- cross-file entry points (host side launchers) -------------------------------------------
 // Exclusive scan of n int64 pairs is private to each file; the segmented gather-sum is shared.
-enum { RECD_SITE_UNIQUE = 0, RECD_SITE_KJT = 1, RECD_SITE_GRAD_LISTS = 2, RECD_SITE_GRAD_ROWS = 3 };
+enum { RECD_SITE_UNIQUE = 0, RECD_SITE_KJT = 1, RECD_SITE_GRAD_LISTS = 2 };
 struct SegSumArgs {
     int F;                    // features in this launch (<= RECD_F_PER_LAUNCH)
     int D;
@@ -94,13 +92,6 @@ struct SegSumArgs {
     const int64_t *ends;            // optional (single table, flat): list l ends at ends[l] ...
     const int64_t *count_dev;       // ... and the number of lists lives on the device
     int site;                 // RECD_SITE_*: which call site (each has its own kernel instantiation)
-    // RECD_SITE_GRAD_ROWS only: fused row-wise Adagrad (opt_n_feat == 0: none)
-    int opt_n_feat;
-    float *const *opt_w;      // host arrays of opt_n_feat device pointers
-    float *const *opt_m;
-    const int64_t *opt_touched_rows;
-    const int32_t *opt_seg_feat;
-    float opt_lr, opt_eps;
     void *out;                // [lists, D]
 };
 recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a);

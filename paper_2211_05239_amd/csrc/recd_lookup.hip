@@ -118,13 +118,9 @@ template <int OT, int N, bool NT> __device__ __forceinline__ void store_row_piec
     }
 }
 
-// Call sites of the gather-sum kernel.  Each gets its own instantiation (and symbol).
-enum { SITE_UNIQUE = 0, SITE_KJT = 1, SITE_GRAD_LISTS = 2, SITE_GRAD_ROWS = 3 };
-
-// Optional epilogue of SITE_GRAD_ROWS: row-wise Adagrad applied to the table row a segment belongs
-// to, straight from the registers that hold the segment's sum.
-template <int SITE> struct OptOf { typedef OptNone type; };
-template <> struct OptOf<SITE_GRAD_ROWS> { typedef OptAdagrad type; };
+// Call sites of the gather-sum kernel.  Each gets its own instantiation (and symbol): the unique
+// lookup, the KJT comparison lookup, and the backward's sums over grad_out rows / chunk partials.
+enum { SITE_UNIQUE = 0, SITE_KJT = 1, SITE_GRAD_LISTS = 2 };
 
 struct SegSumParams {
     TablePtrs tables;
@@ -199,28 +195,25 @@ __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL]
     }
 }
 
-template <int LPR, int VPL, int TT, int OT, typename IdxT, int WAVES, int SITE>
-__global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(VPL == 1 && WAVES == 4 ? 7 : 1))) void k_segsum(const SegSumParams p,
-                                                       const typename OptOf<SITE>::type opt)
+// Occupancy target: 7 waves per SIMD (71 VGPRs) measured best for one-vector-per-lane rows; more
+// loads in flight per wave at lower occupancy, or fewer at 8 waves, were both slower.
+template <int LPR, int VPL, int TT, int OT, typename IdxT, int SITE>
+__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VPL == 1 ? 7 : 1)))
+void k_segsum(const SegSumParams p)
 {
-    constexpr int NL = 1;            // lists a wave keeps in flight together
-    constexpr int kWaves = WAVES;    // waves per block (4; 16 for the long-segment pass of the backward)
-    constexpr int kBlock = 64 * WAVES;
-    constexpr bool NT = SITE == SITE_KJT || SITE == SITE_GRAD_ROWS;  // streaming outputs
+    constexpr int kWaves = kBlock / 64;
+    constexpr bool NT = SITE == SITE_KJT;  // streaming output
     constexpr int EPV = Elem<TT>::per_vec;
     constexpr int NACC = EPV * VPL;
     constexpr int ROWF = LPR * NACC;                      // floats of one (padded) row
     constexpr int OB = (OT == RECD_F32) ? EPV * 4 : 16;   // bytes a lane writes per vector
     constexpr int UNR = (VPL == 1) ? 8 : (VPL == 2 ? 4 : 2);
-    constexpr int US = UNR / NL > 0 ? UNR / NL : 1;       // loads per list and round when NL lists share a wave
-    constexpr int LL = ROWF * WAVES <= 1024 ? 4 : (ROWF * WAVES <= 2048 ? 2 : 1);  // long lists folded per barrier pair
+    constexpr int LL = ROWF <= 256 ? 4 : (ROWF <= 512 ? 2 : 1);  // long lists folded per barrier pair
 
     __shared__ int64_t s_loff[RECD_F_PER_LAUNCH + 1];
     __shared__ int64_t s_qpref[RECD_F_PER_LAUNCH + 1];
     __shared__ int64_t s_start[kMaxLB], s_end[kMaxLB], s_list[kMaxLB];
     __shared__ int s_feat[kMaxLB];
-    __shared__ int s_dfeat[kMaxLB];      // SITE_GRAD_ROWS: feature and table row the segment updates
-    __shared__ int64_t s_drow[kMaxLB];
     __shared__ float s_part[LL][kWaves][ROWF];
 
     const int tid = threadIdx.x;
@@ -279,70 +272,9 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(VPL 
                 acc[i] += __shfl_xor(acc[i], s);
     };
 
-    // A finished row: lanes of group 0 hold its NACC-element pieces in vals.  Store it and, at
-    // SITE_GRAD_ROWS with an optimizer, apply row-wise Adagrad to the table row it belongs to:
-    //   m += mean_d G[d]^2 ;  W[d] -= lr * G[d] / (sqrt(m) + eps)
-    // Optimizer operands of the row a segment updates, fetched before the segment is summed so that
-    // their latency overlaps the gather (lanes of group 0 only).
-    auto fetch_dest = [&](int j, float *wv_, float &m_) {
-        if constexpr (SITE == SITE_GRAD_ROWS) {
-            if (opt.n_feat > 0 && g == 0) {
-                const int f = s_dfeat[j];
-                const int64_t row = s_drow[j];
-                m_ = opt.m[f][row];
-                if (piece_ok) {
-                    const float *wrow = opt.w[f] + row * p.D;
-#pragma unroll
-                    for (int w = 0; w < VPL; w++) {
-                        const float4 x = *reinterpret_cast<const float4 *>(wrow + (w * LPR + r) * EPV);
-                        wv_[w * EPV + 0] = x.x;
-                        wv_[w * EPV + 1] = x.y;
-                        wv_[w * EPV + 2] = x.z;
-                        wv_[w * EPV + 3] = x.w;
-                    }
-                }
-            }
-        }
-    };
-    // A finished row: lanes of group 0 hold its NACC-element pieces in vals.  Store it and, at
-    // SITE_GRAD_ROWS with an optimizer, apply row-wise Adagrad to the table row it belongs to:
-    //   m += mean_d G[d]^2 ;  W[d] -= lr * G[d] / (sqrt(m) + eps)
-    auto finish_row = [&](int j, const float *vals, const float *wv_, float m_) {
-        bool store = true;
-        if constexpr (SITE == SITE_GRAD_ROWS) {
-            store = opt.write_grad != 0;
-            if (opt.n_feat > 0) {
-                float ss = 0.f;
-                if (g == 0 && piece_ok)
-#pragma unroll
-                    for (int i = 0; i < NACC; i++)
-                        ss += vals[i] * vals[i];
-#pragma unroll
-                for (int s = 1; s < LPR; s <<= 1)
-                    ss += __shfl_xor(ss, s);
-                if (g == 0) {
-                    const int f = s_dfeat[j];
-                    const int64_t row = s_drow[j];
-                    const float mnew = m_ + ss / (float)p.D;
-                    const float scale = opt.lr / (sqrtf(mnew) + opt.eps);
-                    if (piece_ok) {
-                        float *wrow = opt.w[f] + row * p.D;
-#pragma unroll
-                        for (int w = 0; w < VPL; w++) {
-                            float4 x;
-                            x.x = wv_[w * EPV + 0] - scale * vals[w * EPV + 0];
-                            x.y = wv_[w * EPV + 1] - scale * vals[w * EPV + 1];
-                            x.z = wv_[w * EPV + 2] - scale * vals[w * EPV + 2];
-                            x.w = wv_[w * EPV + 3] - scale * vals[w * EPV + 3];
-                            *reinterpret_cast<float4 *>(wrow + (w * LPR + r) * EPV) = x;
-                        }
-                    }
-                    if (r == 0)
-                        opt.m[f][row] = mnew;
-                }
-            }
-        }
-        if (store && g == 0 && piece_ok) {
+    // A finished row: lanes of group 0 hold its NACC-element pieces in vals.
+    auto finish_row = [&](int j, const float *vals) {
+        if (g == 0 && piece_ok) {
             char *dst = static_cast<char *>(p.out) + s_list[j] * out_row_bytes;
 #pragma unroll
             for (int w = 0; w < VPL; w++)
@@ -370,12 +302,6 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(VPL 
             s_list[tid] = l;
             s_start[tid] = p.offsets[l];
             s_end[tid] = p.ends ? p.ends[l] : p.offsets[l + 1];
-            if constexpr (SITE == SITE_GRAD_ROWS) {
-                if (opt.n_feat > 0) {
-                    s_dfeat[tid] = opt.seg_feat[l];
-                    s_drow[tid] = opt.touched_rows[l];
-                }
-            }
         }
         __syncthreads();
 
@@ -421,82 +347,42 @@ __global__ __launch_bounds__(64 * WAVES) __attribute__((amdgpu_waves_per_eu(VPL 
                                 t_ += s_part[e][w2][x];  // wave order
                             tot[w * EPV + i] = t_;
                         }
-                    float dw[NACC], dm = 0.f;
-                    fetch_dest(batch[e], dw, dm);
-                    finish_row(batch[e], tot, dw, dm);
+                    finish_row(batch[e], tot);
                 }
                 __syncthreads();
                 nb = 0;
             }
         }
 
-        // ---- short lists (one chunk at most): wave w takes lists w, w+4, ... of the item, NL of
-        //      them in flight together -----------------------------------------------------------
-        for (int k0 = 0; wv + k0 * kWaves < cnt; k0 += NL) {
-            const char *tabs[NL];
-            int64_t starts[NL];
-            int ns[NL];
-            bool any = false;
-#pragma unroll
-            for (int k = 0; k < NL; k++) {
-                const int j = wv + (k0 + k) * kWaves;
-                tabs[k] = static_cast<const char *>(p.tables.p[0]);
-                starts[k] = 0;
-                ns[k] = -1;
-                if (j < cnt) {
-                    const int64_t st_ = uniform64(s_start[j]);
-                    const int64_t len = uniform64(s_end[j]) - st_;
-                    if (len <= kChunk) {
-                        tabs[k] = static_cast<const char *>(p.tables.p[s_feat[j]]) + lane_off;
-                        starts[k] = st_;
-                        ns[k] = (int)len;
-                        any = true;
-                    }
-                }
-            }
-            if (!any)
+        // ---- short lists (one chunk at most): wave w takes lists w, w+4, ... of the item ----------
+        for (int j = wv; j < cnt; j += kWaves) {
+            const int64_t start = uniform64(s_start[j]);
+            const int64_t len = uniform64(s_end[j]) - start;
+            if (len > kChunk)
                 continue;
-            float acc[NL][NACC];
-            float dw[NL][NACC], dm[NL];
+            const char *table = static_cast<const char *>(p.tables.p[s_feat[j]]) + lane_off;
+            const int n = (int)len;
+            float acc[1][NACC];
 #pragma unroll
-            for (int k = 0; k < NL; k++) {
-#pragma unroll
-                for (int i = 0; i < NACC; i++)
-                    acc[k][i] = 0.f;
-                dm[k] = 0.f;
-                if (ns[k] >= 0)
-                    fetch_dest(wv + (k0 + k) * kWaves, dw[k], dm[k]);
-            }
-            add_chunks<LPR, VPL, TT, IdxT, NL, US>(acc, tabs, values, starts, ns, row_bytes, lane, g);
-#pragma unroll
-            for (int k = 0; k < NL; k++) {
-                if (ns[k] >= 0) {
-                    fold_groups(acc[k]);
-                    finish_row(wv + (k0 + k) * kWaves, acc[k], dw[k], dm[k]);
-                }
-            }
+            for (int i = 0; i < NACC; i++)
+                acc[0][i] = 0.f;
+            add_chunks<LPR, VPL, TT, IdxT, 1, UNR>(acc, &table, values, &start, &n, row_bytes, lane, g);
+            fold_groups(acc[0]);
+            finish_row(j, acc[0]);
         }
     }
 }
 
-template <int LPR, int VPL, int TT, int OT, typename IdxT, int SITE>
-void launch_one(hipStream_t st, int blocks, int waves, const SegSumParams &p,
-                const typename OptOf<SITE>::type &opt)
-{
-    (void)waves;
-    hipLaunchKernelGGL((k_segsum<LPR, VPL, TT, OT, IdxT, 4, SITE>), dim3(blocks), dim3(256), 0, st, p, opt);
-}
-
 template <int TT, int OT, typename IdxT, int SITE>
-bool launch_shape(hipStream_t st, int blocks, int nl, int vecs, const SegSumParams &p,
-                  const typename OptOf<SITE>::type &opt)
+bool launch_shape(hipStream_t st, int blocks, int vecs, const SegSumParams &p)
 {
-    if (vecs <= 8) launch_one<8, 1, TT, OT, IdxT, SITE>(st, blocks, nl, p, opt);
-    else if (vecs <= 16) launch_one<16, 1, TT, OT, IdxT, SITE>(st, blocks, nl, p, opt);
-    else if (vecs <= 32) launch_one<32, 1, TT, OT, IdxT, SITE>(st, blocks, nl, p, opt);
-    else if (vecs <= 64) launch_one<64, 1, TT, OT, IdxT, SITE>(st, blocks, nl, p, opt);
-    else if (vecs == 128) launch_one<64, 2, TT, OT, IdxT, SITE>(st, blocks, nl, p, opt);
-    else if (vecs == 256) launch_one<64, 4, TT, OT, IdxT, SITE>(st, blocks, nl, p, opt);
+    const dim3 grid(blocks), block(kBlock);
+    if (vecs <= 8) hipLaunchKernelGGL((k_segsum<8, 1, TT, OT, IdxT, SITE>), grid, block, 0, st, p);
+    else if (vecs <= 16) hipLaunchKernelGGL((k_segsum<16, 1, TT, OT, IdxT, SITE>), grid, block, 0, st, p);
+    else if (vecs <= 32) hipLaunchKernelGGL((k_segsum<32, 1, TT, OT, IdxT, SITE>), grid, block, 0, st, p);
+    else if (vecs <= 64) hipLaunchKernelGGL((k_segsum<64, 1, TT, OT, IdxT, SITE>), grid, block, 0, st, p);
+    else if (vecs == 128) hipLaunchKernelGGL((k_segsum<64, 2, TT, OT, IdxT, SITE>), grid, block, 0, st, p);
+    else if (vecs == 256) hipLaunchKernelGGL((k_segsum<64, 4, TT, OT, IdxT, SITE>), grid, block, 0, st, p);
     else return false;
     return true;
 }
@@ -504,17 +390,16 @@ bool launch_shape(hipStream_t st, int blocks, int nl, int vecs, const SegSumPara
 template <int SITE>
 bool launch_forward(hipStream_t st, int blocks, int v, const SegSumArgs &a, const SegSumParams &p)
 {
-    const OptNone none;
     if (a.table_dt == RECD_F32 && a.out_dt == RECD_F32)
-        return launch_shape<RECD_F32, RECD_F32, int64_t, SITE>(st, blocks, 4, v, p, none);
+        return launch_shape<RECD_F32, RECD_F32, int64_t, SITE>(st, blocks, v, p);
     if (a.table_dt == RECD_F16 && a.out_dt == RECD_F16)
-        return launch_shape<RECD_F16, RECD_F16, int64_t, SITE>(st, blocks, 4, v, p, none);
+        return launch_shape<RECD_F16, RECD_F16, int64_t, SITE>(st, blocks, v, p);
     if (a.table_dt == RECD_F16 && a.out_dt == RECD_F32)
-        return launch_shape<RECD_F16, RECD_F32, int64_t, SITE>(st, blocks, 4, v, p, none);
+        return launch_shape<RECD_F16, RECD_F32, int64_t, SITE>(st, blocks, v, p);
     if (a.table_dt == RECD_BF16 && a.out_dt == RECD_BF16)
-        return launch_shape<RECD_BF16, RECD_BF16, int64_t, SITE>(st, blocks, 4, v, p, none);
+        return launch_shape<RECD_BF16, RECD_BF16, int64_t, SITE>(st, blocks, v, p);
     if (a.table_dt == RECD_BF16 && a.out_dt == RECD_F32)
-        return launch_shape<RECD_BF16, RECD_F32, int64_t, SITE>(st, blocks, 4, v, p, none);
+        return launch_shape<RECD_BF16, RECD_F32, int64_t, SITE>(st, blocks, v, p);
     return false;
 }
 
@@ -620,7 +505,6 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     const int64_t n = a.lists_bound > 0 ? a.lists_bound : 1;
     p.nq = (a.F >= kNQ && a.F % kNQ == 0 && !a.flat && !ctx->tune_flat && !a.count_dev) ? kNQ : 1;
     p.lb = n >= (512 << 10) ? 16 : (n >= (128 << 10) ? 8 : 4);
-    const int nl = 4;
     if (ctx->tune_lb > 0)
         p.lb = ctx->tune_lb;
     if (a.count_dev)
@@ -642,24 +526,9 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
         ok = launch_forward<SITE_UNIQUE>(st, blocks, v, a, p);
     else if (a.site == RECD_SITE_KJT && !a.values_are_i32)
         ok = launch_forward<SITE_KJT>(st, blocks, v, a, p);
-    else if (a.values_are_i32 && a.table_dt == RECD_F32 && a.out_dt == RECD_F32) {
-        if (a.site == RECD_SITE_GRAD_LISTS) {
-            ok = launch_shape<RECD_F32, RECD_F32, int32_t, SITE_GRAD_LISTS>(st, blocks, nl, v, p, OptNone());
-        } else if (a.site == RECD_SITE_GRAD_ROWS) {
-            OptAdagrad o;
-            o.n_feat = a.opt_n_feat;
-            for (int f = 0; f < a.opt_n_feat; f++) {
-                o.w[f] = a.opt_w[f];
-                o.m[f] = a.opt_m[f];
-            }
-            o.touched_rows = a.opt_touched_rows;
-            o.seg_feat = a.opt_seg_feat;
-            o.write_grad = a.out != nullptr;
-            o.lr = a.opt_lr;
-            o.eps = a.opt_eps;
-            ok = launch_shape<RECD_F32, RECD_F32, int32_t, SITE_GRAD_ROWS>(st, blocks, nl, v, p, o);
-        }
-    }
+    else if (a.site == RECD_SITE_GRAD_LISTS && a.values_are_i32 && a.table_dt == RECD_F32 &&
+             a.out_dt == RECD_F32)
+        ok = launch_shape<RECD_F32, RECD_F32, int32_t, SITE_GRAD_LISTS>(st, blocks, v, p);
     if (!ok)
         return recd_fail(ctx, RECD_EINVAL, "unsupported row shape: D=%d table dtype %d out dtype %d",
                          a.D, (int)a.table_dt, (int)a.out_dt);
