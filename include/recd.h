@@ -19,7 +19,7 @@
  *   - Every call returns a recd_status; nothing throws or aborts.  On failure
  *     recd_last_error(ctx) holds a message.  F = 0, B = 0 and N = 0 are valid (no-op) sizes.
  *   - Preconditions (offsets[0] = 0, offsets non-decreasing, offsets[F*B] = N, ids within the
- *     table) are checked on the device only when RECD_OPT_VALIDATE is set (the call then
+ *     table, inverse entries within [0, U_f)) are checked on the device only when RECD_OPT_VALIDATE is set (the call then
  *     synchronises and returns RECD_EBOUNDS without running the operation); otherwise behaviour
  *     for inputs that violate them is undefined.
  *   - One context serves one stream; calls on one context must not overlap (they share its

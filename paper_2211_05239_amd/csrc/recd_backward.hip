@@ -866,6 +866,8 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
             return recd_fail(ctx, RECD_EINVAL, "tables[%d] or adagrad_state[%d] is null", f, f);
     }
     RECD_HIP(ctx, hipSetDevice(ctx->device));
+    if (ctx->validate && n_lists > 0)
+        RECD_TRY(recd_validate_inverse(ctx, F, B, feat_uoff, inverse));
     RECD_TRY(recd_reserve(ctx, recd_backward_workspace(F, B, M_cap, D)));
     const BwdWs w = carve_bwd(ctx->ws, n_lists, M_cap, F, D);
     hipStream_t st = ctx->stream;

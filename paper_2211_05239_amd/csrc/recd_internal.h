@@ -95,3 +95,5 @@ struct SegSumArgs {
     void *out;                // [lists, D]
 };
 recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a);
+recd_status recd_validate_inverse(recd_ctx *ctx, int F, int64_t B, const int64_t *feat_uoff,
+                                  const int32_t *inverse);

@@ -482,6 +482,23 @@ __global__ void k_validate_ids(const int64_t *values, const int64_t *offsets,
 
 __global__ void k_read_i64(const int64_t *src, int64_t *dst) { *dst = *src; }
 
+// err[0] |= 4: feat_uoff is not a prefix sum starting at 0, or an inverse entry is outside its
+// feature's [0, U_f)
+__global__ void k_validate_inverse(const int32_t *inverse, const int64_t *feat_uoff, int F, int64_t B,
+                                   int *err)
+{
+    const int64_t n = (int64_t)F * B;
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i <= F && ((i == 0 && feat_uoff[0] != 0) || (i > 0 && feat_uoff[i] < feat_uoff[i - 1])))
+        atomicOr(err, 4);
+    if (i < n) {
+        const int64_t f = i / B;
+        const int64_t inv = inverse[i];
+        if (inv < 0 || inv >= feat_uoff[f + 1] - feat_uoff[f])
+            atomicOr(err, 4);
+    }
+}
+
 } // namespace
 
 recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
@@ -584,6 +601,24 @@ static recd_status validate_lists(recd_ctx *ctx, int F, const int64_t *rows, con
         if ((int)ctx->host_pinned[0] & 2)
             return recd_fail(ctx, RECD_EBOUNDS, "an id lies outside its embedding table");
     }
+    return RECD_OK;
+}
+
+// Checks an inverse index against feat_uoff (used by the expand and the backward).  Synchronises.
+recd_status recd_validate_inverse(recd_ctx *ctx, int F, int64_t B, const int64_t *feat_uoff,
+                                  const int32_t *inverse)
+{
+    RECD_TRY(recd_reserve(ctx, 512));
+    int *err = reinterpret_cast<int *>(ctx->ws);
+    RECD_HIP(ctx, hipMemsetAsync(err, 0, sizeof(int), ctx->stream));
+    const int64_t n = (int64_t)F * B > F + 1 ? (int64_t)F * B : F + 1;
+    hipLaunchKernelGGL(k_validate_inverse, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, ctx->stream,
+                       inverse, feat_uoff, F, B, err);
+    ctx->host_pinned[0] = 0;
+    RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, err, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+    RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if ((int)ctx->host_pinned[0] & 4)
+        return recd_fail(ctx, RECD_EBOUNDS, "inverse index or feat_uoff is malformed");
     return RECD_OK;
 }
 
@@ -701,6 +736,8 @@ recd_status recd_expand_inverse(recd_ctx *ctx, int F, int64_t B, int D, recd_dty
     if (!pooled || !feat_uoff || !inverse || !out)
         return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
     RECD_HIP(ctx, hipSetDevice(ctx->device));
+    if (ctx->validate)
+        RECD_TRY(recd_validate_inverse(ctx, F, B, feat_uoff, inverse));
     const int vecs = (int)((size_t)D * elem_size(dt) / 16);
     const int64_t n_rows = (int64_t)F * B;
     const int64_t rows_per_block = (int64_t)(kBlock / vecs) * kExpandRPT;

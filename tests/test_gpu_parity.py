@@ -244,6 +244,14 @@ def test_validation_reports_bad_inputs(ctx, recd):
         with pytest.raises(recd.RecdError) as e:
             ctx.build_ikjt(1, 2, good_v, bad_o, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff)
         assert e.value.status == recd.RECD_EBOUNDS
+        # expand: an inverse entry beyond the feature's unique count is reported, not dereferenced
+        pooled = torch.zeros(2, 8, device="cuda")
+        fu = torch.tensor([0, 2], dtype=torch.int64, device="cuda")
+        ctx.expand_inverse(1, 2, pooled, fu, torch.tensor([1, 0], dtype=torch.int32, device="cuda"), out)
+        for inv in ([2, 0], [0, -1]):
+            with pytest.raises(recd.RecdError) as e:
+                ctx.expand_inverse(1, 2, pooled, fu, torch.tensor(inv, dtype=torch.int32, device="cuda"), out)
+            assert e.value.status == recd.RECD_EBOUNDS
     finally:
         ctx.set_option(recd.RECD_OPT_VALIDATE, 0)
 
