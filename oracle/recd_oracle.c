@@ -12,7 +12,8 @@
  * Every function is pinned by the CPU test-suite against values printed in the paper
  * (Sec. 4.2 worked example of features b, c, d; Sec. 5 "Deduplicated Pooling" sums), against
  * brute-force pairwise list comparison, against closed forms and against independent library
- * routines (embedding_bag / index_select / autograd in fp64).  No function is "parity unpinned".
+ * routines (embedding_bag / embedding / index_select on padded dense / autograd in fp64).  No
+ * function is "parity unpinned".
  *
  * Conventions shared by all entry points
  *   KJT (Sec. 4.2): values[N] feature-major; offsets[F*B+1], offsets[f*B+b] = start of row b of
@@ -169,6 +170,53 @@ int oracle_expand_inverse(int F, int64_t B, int D, const double *pooled, const i
                 return -5;
             memcpy(out + ((int64_t)f * B + b) * D, pooled + (feat_uoff[f] + u) * D,
                    sizeof(double) * D);
+        }
+    return 0;
+}
+
+/* ---- per-id activations (Sec. 2.2: an EMB produces a dense activation vector for each list
+ * element; Sec. 5 "EMB Inputs and Activations": with an IKJT only the unique values are looked up) --
+ * emb[j,:] = W_f[values[j],:] for every position j of the lists [list_off[f], list_off[f+1]) of
+ * feature f.  Serves the KJT (list_off[f] = f*B) and the unique lists of an IKJT alike.
+ */
+int oracle_sequence_lookup(int F, int D, int dtype, const void *const *tables, const int64_t *rows,
+                           const int64_t *values, const int64_t *offsets, const int64_t *list_off,
+                           double *emb)
+{
+    for (int f = 0; f < F; f++)
+        for (int64_t l = list_off[f]; l < list_off[f + 1]; l++)
+            for (int64_t j = offsets[l]; j < offsets[l + 1]; j++) {
+                int64_t id = values[j];
+                if (id < 0 || id >= rows[f])
+                    return -4;
+                for (int d = 0; d < D; d++)
+                    emb[j * D + d] = elem(tables[f], dtype, id * D + d);
+            }
+    return 0;
+}
+
+/* ---- jagged index select (Sec. 5 "Jagged Index Select": IKJT -> KJT for unpooled activations,
+ * without padding the jagged dimension to dense) -----------------------------------------------
+ * Row (f,b) of the batch has the list of unique slot u = feat_uoff[f] + inverse[f,b]; its
+ * activations are the slice emb[u_offsets[u] .. u_offsets[u+1]) and land at the row's own place in
+ * the KJT layout: out[offsets[f*B+b] + t, :] = emb[u_offsets[u] + t, :].
+ */
+int oracle_jagged_expand(int F, int64_t B, int D, const double *emb, const int64_t *u_offsets,
+                         const int64_t *feat_uoff, const int32_t *inverse, const int64_t *offsets,
+                         double *out)
+{
+    for (int f = 0; f < F; f++)
+        for (int64_t b = 0; b < B; b++) {
+            int64_t l = (int64_t)f * B + b;
+            int64_t inv = inverse[l];
+            if (inv < 0 || inv >= feat_uoff[f + 1] - feat_uoff[f])
+                return -5;
+            int64_t u = feat_uoff[f] + inv;
+            int64_t len = offsets[l + 1] - offsets[l];
+            if (u_offsets[u + 1] - u_offsets[u] != len)
+                return -6; /* the slot does not hold a list of this row's length */
+            for (int64_t t = 0; t < len; t++)
+                memcpy(out + (offsets[l] + t) * D, emb + (u_offsets[u] + t) * D, sizeof(double) * D);
         }
     return 0;
 }

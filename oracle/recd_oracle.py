@@ -133,6 +133,39 @@ def expand_inverse(F: int, B: int, pooled: np.ndarray, feat_uoff, inverse) -> np
     return out
 
 
+def sequence_lookup(tables: Sequence[np.ndarray], dtype: str, values, offsets, list_off) -> np.ndarray:
+    """Per-id activations (Sec. 2.2, Sec. 5): emb[j,:] = W_f[values[j],:] for every position j of the
+    lists [list_off[f], list_off[f+1]) of feature f.  Returns float64 [len(values), D]."""
+    F = len(tables)
+    values, offsets, list_off = _i64(values), _i64(offsets), _i64(list_off)
+    D = int(tables[0].shape[1]) if F else 1
+    rows = _i64([t.shape[0] for t in tables])
+    emb = np.zeros((max(values.shape[0], 1), D), dtype=np.float64)
+    ptrs, keep = _table_ptrs(tables, dtype)
+    rc = _lib.oracle_sequence_lookup(C.c_int(F), C.c_int(D), C.c_int(DTYPES[dtype]), ptrs,
+                                     _p(rows, _i64p), _p(values, _i64p), _p(offsets, _i64p),
+                                     _p(list_off, _i64p), _p(emb, _f64p))
+    _check(rc, "sequence_lookup")
+    del keep
+    return emb[:values.shape[0]]
+
+
+def jagged_expand(F: int, B: int, emb: np.ndarray, u_offsets, feat_uoff, inverse, offsets) -> np.ndarray:
+    """Jagged index select (Sec. 5): out[offsets[f*B+b] + t, :] = emb[u_offsets[u] + t, :] with
+    u = feat_uoff[f] + inverse[f,b].  Returns float64 [N, D] in the KJT's own jagged layout."""
+    emb = np.ascontiguousarray(emb, dtype=np.float64)
+    D = emb.shape[1]
+    u_offsets, feat_uoff, offsets = _i64(u_offsets), _i64(feat_uoff), _i64(offsets)
+    inverse = np.ascontiguousarray(inverse, dtype=np.int32)
+    N = int(offsets[F * B])
+    out = np.zeros((max(N, 1), D), dtype=np.float64)
+    rc = _lib.oracle_jagged_expand(C.c_int(F), C.c_int64(B), C.c_int(D), _p(emb, _f64p),
+                                   _p(u_offsets, _i64p), _p(feat_uoff, _i64p), _p(inverse, _i32p),
+                                   _p(offsets, _i64p), _p(out, _f64p))
+    _check(rc, "jagged_expand")
+    return out[:N]
+
+
 def backward_dedup(F: int, B: int, grad_out: np.ndarray, inverse, feat_uoff, u_values, u_offsets):
     """Returns (touched_rows[R] int64, feat_roff[F+1], grad_rows[R,D] float64)."""
     grad_out = np.ascontiguousarray(grad_out, dtype=np.float32)

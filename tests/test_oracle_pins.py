@@ -273,6 +273,69 @@ def test_half_and_bf16_decode_all_patterns():
         assert (np.isnan(a) and np.isnan(b)) or (a == b and np.signbit(a) == np.signbit(b)), i
 
 
+# ------------------------------------------------------------------ unpooled activations, jagged index select
+def test_paper_feature_b_jagged_expand(golden_dir):
+    """With W[r] = r (D = 1) the jagged expand of the unique activations reproduces the KJT's values."""
+    g = _golden(golden_dir, "paper_ikjt_feature_b.json")
+    kjt = synth.batch_from_lists([g["rows"]])
+    uv, uo, inv, fu = orc.build_ikjt(1, 3, kjt.values, kjt.offsets)
+    W = np.arange(8, dtype=np.float32).reshape(8, 1)
+    emb = orc.sequence_lookup([W], "f32", uv, uo, fu)
+    assert emb[:, 0].tolist() == g["ikjt_values"]
+    out = orc.jagged_expand(1, 3, emb, uo, fu, inv, kjt.offsets)
+    assert out[:, 0].tolist() == [x for row in g["rows"] for x in row]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_sequence_lookup_matches_embedding(dtype):
+    batch, tabs = _rand_problem(21, dtype=dtype)
+    lo = np.arange(batch.F + 1, dtype=np.int64) * batch.B
+    got = orc.sequence_lookup(tabs, dtype, batch.values, batch.offsets, lo)
+    t64 = _tables_as_f64(tabs, dtype)
+    for f in range(batch.F):
+        a, b = batch.offsets[f * batch.B], batch.offsets[(f + 1) * batch.B]
+        ref = torch.nn.functional.embedding(torch.from_numpy(batch.values[a:b]), t64[f]).numpy()
+        assert np.array_equal(got[a:b], ref)
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_jagged_expand_is_lossless_and_matches_padded_index_select(seed):
+    batch, tabs = _rand_problem(300 + seed, F=2, B=37, rows=9, D=5, max_len=4, alphabet=3)
+    F, B = batch.F, batch.B
+    uv, uo, inv, fu = orc.build_ikjt(F, B, batch.values, batch.offsets)
+    emb_u = orc.sequence_lookup(tabs, "f32", uv, uo, fu)
+    out = orc.jagged_expand(F, B, emb_u, uo, fu, inv, batch.offsets)
+    # the IKJT carries the same logical data: expanding the unique activations equals looking up
+    # every id of the KJT
+    direct = orc.sequence_lookup(tabs, "f32", batch.values, batch.offsets,
+                                 np.arange(F + 1, dtype=np.int64) * B)
+    assert np.array_equal(out, direct)
+    # the pre-RecD way: pad the unique lists to dense, index_select, drop the padding
+    D = emb_u.shape[1]
+    for f in range(F):
+        Uf = int(fu[f + 1] - fu[f])
+        lens = np.diff(uo[fu[f]:fu[f + 1] + 1])
+        Lmax = max(int(lens.max()) if Uf else 0, 1)
+        dense = torch.zeros(Uf, Lmax, D, dtype=torch.float64)
+        for k in range(Uf):
+            a = int(uo[fu[f] + k])
+            dense[k, :lens[k]] = torch.from_numpy(emb_u[a:a + lens[k]])
+        sel = torch.index_select(dense, 0, torch.from_numpy(inv[f * B:(f + 1) * B].astype(np.int64)))
+        for b in range(B):
+            l = f * B + b
+            n = int(batch.offsets[l + 1] - batch.offsets[l])
+            assert np.array_equal(out[batch.offsets[l]:batch.offsets[l + 1]], sel[b, :n].numpy())
+    # a slot whose list length differs from the row's is rejected
+    if fu[1] >= 2 and (np.diff(uo[:fu[1] + 1])[:2] != np.diff(uo[:fu[1] + 1])[0]).any():
+        bad = inv.copy()
+        lens0 = np.diff(uo[:fu[1] + 1])
+        b0 = 0
+        other = int(np.nonzero(lens0 != lens0[inv[b0]])[0][0])
+        bad[b0] = other
+        with pytest.raises(orc.OracleError):
+            orc.jagged_expand(F, B, emb_u, uo, fu, bad, batch.offsets)
+
+
 # ------------------------------------------------------------------ backward
 def _dense_grad(F, rows, D, touched, feat_roff, grad_rows):
     G = np.zeros((F, rows, D))
