@@ -7,6 +7,10 @@
  *   3. expand             index_select of the pooled rows through the per-sample inverse index
  *   4. backward           gradient of 3 and 2 (+ optional row-wise Adagrad on the touched rows)
  *   5. KJT pooled lookup  the non-deduplicated comparison path
+ * and, for sequence (unpooled) features (Sec. 5 "EMB Inputs and Activations", "Jagged Index Select"):
+ *   6. sequence lookup    one activation row per id of the unique lists
+ *   7. jagged expand      index select of whole unique lists back into the KJT's jagged layout
+ *   8. KJT sequence lookup, the non-deduplicated comparison path
  *
  * General rules
  *   - Every array argument marked "device" is a pointer into GPU memory owned by the caller and
@@ -57,7 +61,7 @@ typedef enum {
     RECD_EINVAL = -1,    /* bad argument (null pointer, negative size, unsupported D or dtype)  */
     RECD_ENOMEM = -2,    /* workspace allocation failed                                        */
     RECD_EHIP = -3,      /* a HIP runtime call failed; message holds the HIP error string       */
-    RECD_EBOUNDS = -4,   /* validation found an id outside its table or malformed offsets        */
+    RECD_EBOUNDS = -4,   /* validation found an id outside its table or a malformed index        */
     RECD_ECAPACITY = -5  /* a caller-provided capacity is too small for the result               */
 } recd_status;
 
@@ -168,6 +172,45 @@ recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int D, const fl
                                 int64_t *feat_roff, float *grad_rows, void *const *tables,
                                 float *const *adagrad_state, float lr, float eps,
                                 int64_t *host_R);
+
+/* 6. Unpooled lookup on the unique lists (Sec. 2.2: an EMB yields one activation vector per list
+ *    element; Sec. 5 "EMB Inputs and Activations": with an IKJT only the unique values are looked
+ *    up, which shrinks the activations by the deduplication factor):
+ *      emb[j,:] = table_f[u_values[j],:]   for every position j of feature f's unique lists,
+ *    i.e. j in [u_offsets[feat_uoff[f]], u_offsets[feat_uoff[f+1]]).  A copy (exact, also when a
+ *    16-bit table is widened to out_dt = RECD_F32).
+ *    tables, rows, u_values, u_offsets, feat_uoff, max_lists: as in call 2.
+ *    M_cap: host upper bound of M (N always is).  emb: device [M, D] of out_dt, capacity M_cap
+ *    rows; rows at and beyond M are left untouched, positions at and beyond M_cap are not written.
+ *    D*sizeof(table element) must be a multiple of 16 and at most RECD_MAX_ROW_BYTES. */
+recd_status recd_sequence_lookup_unique(recd_ctx *ctx, int F, int D, recd_dtype table_dt,
+                                        recd_dtype out_dt, const void *const *tables,
+                                        const int64_t *rows, const int64_t *u_values,
+                                        const int64_t *u_offsets, const int64_t *feat_uoff,
+                                        int64_t max_lists, int64_t M_cap, void *emb);
+
+/* 7. Jagged index select (Sec. 5 "Jagged Index Select": IKJT -> KJT for unpooled activations, on
+ *    the jagged data itself instead of padding it to dense for index_select):
+ *      out[offsets[f*B+b] + t, :] = emb[u_offsets[feat_uoff[f] + inverse[f*B+b]] + t, :]
+ *    for t in [0, offsets[f*B+b+1] - offsets[f*B+b]).  A pure copy (bit-exact).
+ *    emb: device [M, D] of dt, M_cap = its capacity in rows (reads are clamped to it).
+ *    u_offsets, feat_uoff, inverse: device, the IKJT; offsets: device [F*B+1], the KJT's offsets.
+ *    out: device [N, D] of dt, the KJT's own jagged layout.  F*B and N must stay below 2^31.
+ *    Precondition (checked under RECD_OPT_VALIDATE): the slot of every row holds a list of the
+ *    row's length. */
+recd_status recd_jagged_expand_inverse(recd_ctx *ctx, int F, int64_t B, int64_t N, int D,
+                                       recd_dtype dt, const void *emb, int64_t M_cap,
+                                       const int64_t *u_offsets, const int64_t *feat_uoff,
+                                       const int32_t *inverse, const int64_t *offsets, void *out);
+
+/* 8. Comparison path: the unpooled lookup over every id of the KJT, no deduplication
+ *    (Sec. 2.2; the pre-RecD behaviour): out[j,:] = table_f[values[j],:] for the positions j of
+ *    feature f's rows.  out: device [N, D] of out_dt.  Equals the result of calls 1, 6, 7 bit for
+ *    bit. */
+recd_status recd_kjt_sequence_lookup(recd_ctx *ctx, int F, int64_t B, int64_t N, int D,
+                                     recd_dtype table_dt, recd_dtype out_dt,
+                                     const void *const *tables, const int64_t *rows,
+                                     const int64_t *values, const int64_t *offsets, void *out);
 
 #ifdef __cplusplus
 }

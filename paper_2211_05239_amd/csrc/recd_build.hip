@@ -416,7 +416,6 @@ size_t recd_build_workspace(int F, int64_t B)
     return c.off;
 }
 
-recd_status recd_validate_kjt_offsets(recd_ctx *ctx, int F, int64_t B, int64_t N, const int64_t *offsets);
 
 extern "C" recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t N,
                                        const int64_t *values, const int64_t *offsets,

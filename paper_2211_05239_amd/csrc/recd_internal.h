@@ -97,3 +97,9 @@ struct SegSumArgs {
 recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a);
 recd_status recd_validate_inverse(recd_ctx *ctx, int F, int64_t B, const int64_t *feat_uoff,
                                   const int32_t *inverse);
+recd_status recd_validate_kjt_offsets(recd_ctx *ctx, int F, int64_t B, int64_t N, const int64_t *offsets);
+recd_status recd_validate_kjt_lists(recd_ctx *ctx, int F, int64_t B, int64_t N, const int64_t *rows,
+                                    const int64_t *values, const int64_t *offsets);
+recd_status recd_validate_unique_lists(recd_ctx *ctx, int F, const int64_t *rows,
+                                       const int64_t *u_values, const int64_t *u_offsets,
+                                       const int64_t *feat_uoff, int64_t max_lists, int64_t M_cap);

@@ -627,6 +627,43 @@ recd_status recd_validate_kjt_offsets(recd_ctx *ctx, int F, int64_t B, int64_t N
     return validate_lists(ctx, F, nullptr, nullptr, offsets, nullptr, B, (int64_t)F * B, N);
 }
 
+recd_status recd_validate_kjt_lists(recd_ctx *ctx, int F, int64_t B, int64_t N, const int64_t *rows,
+                                    const int64_t *values, const int64_t *offsets)
+{
+    if (!rows)
+        return recd_fail(ctx, RECD_EINVAL, "validation needs rows[]");
+    return validate_lists(ctx, F, rows, values, offsets, nullptr, B, (int64_t)F * B, N);
+}
+
+// Unique lists of an IKJT: feat_uoff[F] = U lives on the device and is fetched to size the offsets
+// check; U must not exceed max_lists and, when M_cap >= 0, the ids must number at most M_cap.
+recd_status recd_validate_unique_lists(recd_ctx *ctx, int F, const int64_t *rows,
+                                       const int64_t *u_values, const int64_t *u_offsets,
+                                       const int64_t *feat_uoff, int64_t max_lists, int64_t M_cap)
+{
+    if (!rows)
+        return recd_fail(ctx, RECD_EINVAL, "validation needs rows[]");
+    RECD_TRY(recd_reserve(ctx, 1024));
+    int64_t *tmp = reinterpret_cast<int64_t *>(ctx->ws + 256);
+    hipLaunchKernelGGL(k_read_i64, dim3(1), dim3(1), 0, ctx->stream, feat_uoff + F, tmp);
+    RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned + 1, tmp, 8, hipMemcpyDeviceToHost, ctx->stream));
+    RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    const int64_t U = ctx->host_pinned[1];
+    if (U < 0 || U > max_lists)
+        return recd_fail(ctx, RECD_ECAPACITY, "U=%lld exceeds max_lists=%lld", (long long)U,
+                         (long long)max_lists);
+    if (M_cap >= 0) {
+        hipLaunchKernelGGL(k_read_i64, dim3(1), dim3(1), 0, ctx->stream, u_offsets + U, tmp);
+        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned + 1, tmp, 8, hipMemcpyDeviceToHost, ctx->stream));
+        RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        const int64_t M = ctx->host_pinned[1];
+        if (M < 0 || M > M_cap)
+            return recd_fail(ctx, RECD_ECAPACITY, "M=%lld exceeds M_cap=%lld", (long long)M,
+                             (long long)M_cap);
+    }
+    return validate_lists(ctx, F, rows, u_values, u_offsets, feat_uoff, 0, U, -1);
+}
+
 extern "C" {
 
 recd_status recd_pooled_lookup_unique(recd_ctx *ctx, int F, int D, recd_dtype table_dt,
@@ -646,21 +683,8 @@ recd_status recd_pooled_lookup_unique(recd_ctx *ctx, int F, int D, recd_dtype ta
         if (!tables[f])
             return recd_fail(ctx, RECD_EINVAL, "tables[%d] is null", f);
     RECD_HIP(ctx, hipSetDevice(ctx->device));
-    if (ctx->validate) {
-        if (!rows)
-            return recd_fail(ctx, RECD_EINVAL, "validation needs rows[]");
-        // U lives on the device: fetch it to size the offsets check
-        RECD_TRY(recd_reserve(ctx, 512));
-        hipLaunchKernelGGL(k_read_i64, dim3(1), dim3(1), 0, ctx->stream, feat_uoff + F,
-                           reinterpret_cast<int64_t *>(ctx->ws + 256));
-        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned + 1, ctx->ws + 256, 8, hipMemcpyDeviceToHost, ctx->stream));
-        RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
-        const int64_t U = ctx->host_pinned[1];
-        if (U < 0 || U > max_lists)
-            return recd_fail(ctx, RECD_ECAPACITY, "U=%lld exceeds max_lists=%lld", (long long)U,
-                             (long long)max_lists);
-        RECD_TRY(validate_lists(ctx, F, rows, u_values, u_offsets, feat_uoff, 0, U, -1));
-    }
+    if (ctx->validate)
+        RECD_TRY(recd_validate_unique_lists(ctx, F, rows, u_values, u_offsets, feat_uoff, max_lists, -1));
     for (int f0 = 0; f0 < F; f0 += RECD_F_PER_LAUNCH) {
         SegSumArgs a{};
         a.F = F - f0 < RECD_F_PER_LAUNCH ? F - f0 : RECD_F_PER_LAUNCH;

@@ -30,7 +30,8 @@ RECD_OPT_VALIDATE, RECD_OPT_WEAK_HASH, RECD_OPT_TUNE_SEGSUM = 1, 2, 3
 EXPORTED = [
     "recd_create", "recd_destroy", "recd_set_option", "recd_last_error", "recd_status_string",
     "recd_workspace_bytes", "recd_build_ikjt", "recd_pooled_lookup_unique", "recd_expand_inverse",
-    "recd_kjt_pooled_lookup", "recd_backward_dedup",
+    "recd_kjt_pooled_lookup", "recd_backward_dedup", "recd_sequence_lookup_unique",
+    "recd_jagged_expand_inverse", "recd_kjt_sequence_lookup",
 ]
 
 _vp = C.c_void_p
@@ -51,6 +52,12 @@ _lib.recd_kjt_pooled_lookup.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, C.c_in
 _lib.recd_backward_dedup.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, _vp, _vp, _vp, _vp, _vp, _vp,
                                      C.c_int64, C.c_int64, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float,
                                      _vp]
+_lib.recd_sequence_lookup_unique.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, _vp,
+                                             _vp, C.c_int64, C.c_int64, _vp]
+_lib.recd_jagged_expand_inverse.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, _vp,
+                                            C.c_int64, _vp, _vp, _vp, _vp, _vp]
+_lib.recd_kjt_sequence_lookup.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int,
+                                          _vp, _vp, _vp, _vp, _vp]
 for _n in EXPORTED:
     if _n not in ("recd_last_error", "recd_status_string"):
         getattr(_lib, _n).restype = C.c_int
@@ -162,3 +169,27 @@ class Context:
             _ptr(u_offsets), rows_arr, U_cap, M_cap, _ptr(touched_rows), _ptr(feat_roff), _ptr(grad_rows),
             tabs, state, lr, eps, host))
         return int(host[0]) if want_count else None
+
+    # -- sequence (unpooled) features ---------------------------------------------------------
+    def sequence_lookup_unique(self, tables, u_values, u_offsets, feat_uoff, max_lists: int, emb):
+        F = len(tables)
+        D = tables[0].shape[1] if F else emb.shape[-1]
+        tdt = _DT[tables[0].dtype] if F else _DT[emb.dtype]
+        self._check(_lib.recd_sequence_lookup_unique(
+            self._h, F, D, tdt, _DT[emb.dtype], self._table_array(tables), self._rows_array(tables),
+            _ptr(u_values), _ptr(u_offsets), _ptr(feat_uoff), max_lists, emb.shape[0], _ptr(emb)))
+
+    def jagged_expand_inverse(self, F: int, B: int, emb, u_offsets, feat_uoff, inverse, offsets, out):
+        D = emb.shape[-1]
+        assert out.dtype == emb.dtype
+        self._check(_lib.recd_jagged_expand_inverse(
+            self._h, F, B, out.shape[0], D, _DT[emb.dtype], _ptr(emb), emb.shape[0], _ptr(u_offsets),
+            _ptr(feat_uoff), _ptr(inverse), _ptr(offsets), _ptr(out)))
+
+    def kjt_sequence_lookup(self, tables, B: int, values, offsets, out):
+        F = len(tables)
+        D = tables[0].shape[1] if F else out.shape[-1]
+        tdt = _DT[tables[0].dtype] if F else _DT[out.dtype]
+        self._check(_lib.recd_kjt_sequence_lookup(
+            self._h, F, B, values.numel(), D, tdt, _DT[out.dtype], self._table_array(tables),
+            self._rows_array(tables), _ptr(values), _ptr(offsets), _ptr(out)))

@@ -1,0 +1,154 @@
+"""GPU parity tests of the sequence (unpooled) path: per-id lookup on the unique lists, jagged index
+select back to the KJT layout, and the non-deduplicated comparison lookup, against the CPU oracle.
+All three are copies: the comparison is exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import recd_oracle as orc
+from paper_2211_05239_amd import synth
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def recd():
+    from paper_2211_05239_amd import recd as mod
+    return mod
+
+
+@pytest.fixture(scope="module")
+def ctx(recd):
+    c = recd.Context(0)
+    yield c
+    c.close()
+
+
+def _bits(t):
+    return t.view(torch.int32 if t.element_size() == 4 else torch.int16)
+
+
+def gpu_sequence(ctx, batch, dev_tables, out_dtype):
+    F, B, N = batch.F, batch.B, batch.N
+    D = dev_tables[0].shape[1]
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    emb = torch.full((max(N, 1), D), float("nan"), dtype=out_dtype, device="cuda")
+    ctx.sequence_lookup_unique(dev_tables, ik.u_values, ik.u_offsets, ik.feat_uoff, F * B, emb)
+    out = torch.full((max(N, 1), D), float("nan"), dtype=out_dtype, device="cuda")[:N]
+    ctx.jagged_expand_inverse(F, B, emb, ik.u_offsets, ik.feat_uoff, ik.inverse, offsets, out)
+    kjt = torch.full((max(N, 1), D), float("nan"), dtype=out_dtype, device="cuda")[:N]
+    ctx.kjt_sequence_lookup(dev_tables, B, values, offsets, kjt)
+    torch.cuda.synchronize()
+    return ik, emb, out, kjt
+
+
+def _sequence_case(ctx, w, batch_index=0, out_dtype=None):
+    batch = synth.make_batch(w, batch_index)
+    tabs = synth.make_tables(w)
+    dev_tabs = gu.tables_to_dev(tabs, w.table_dtype)
+    odt = out_dtype or gu.TORCH_DT[w.table_dtype]
+    ik, emb, out, kjt = gpu_sequence(ctx, batch, dev_tabs, odt)
+    uv, uo, inv, fu = orc.build_ikjt(w.F, w.B, batch.values, batch.offsets)
+    assert ik.M == len(uv)
+    ref_emb = orc.sequence_lookup(tabs, w.table_dtype, uv, uo, fu)
+    ref_out = orc.jagged_expand(w.F, w.B, ref_emb, uo, fu, inv, batch.offsets)
+    ref_kjt = orc.sequence_lookup(tabs, w.table_dtype, batch.values, batch.offsets,
+                                  np.arange(w.F + 1, dtype=np.int64) * w.B)
+    assert np.array_equal(gu.out_to_f64(emb[:ik.M]), ref_emb), "unique activations"
+    assert torch.isnan(emb[ik.M:]).all(), "rows beyond M must stay untouched"
+    assert np.array_equal(gu.out_to_f64(out), ref_out), "jagged expand"
+    assert np.array_equal(gu.out_to_f64(kjt), ref_kjt), "kjt sequence lookup"
+    assert torch.equal(_bits(out), _bits(kjt))
+    return ik, emb, out, kjt
+
+
+def test_sequence_cfg1(ctx):
+    _sequence_case(ctx, synth.WORKLOADS["cfg1"])
+
+
+@pytest.mark.parametrize("dt,odt", [("f32", None), ("f16", None), ("f16", torch.float32),
+                                    ("bf16", None), ("bf16", torch.float32)])
+def test_sequence_dtypes(ctx, dt, odt):
+    w = synth.scaled(synth.WORKLOADS["cfg3"], F=3, B=1031, rows=50_000, table_dtype=dt)
+    _sequence_case(ctx, w, 0, odt)
+
+
+@pytest.mark.parametrize("D", [4, 8, 24, 64, 96, 128, 256, 1024])
+def test_sequence_row_shapes_f32(ctx, D):
+    w = synth.scaled(synth.WORKLOADS["cfg2"], F=2, B=517, rows=3000, D=D)
+    _sequence_case(ctx, w)
+
+
+@pytest.mark.parametrize("D", [8, 136, 2048])
+def test_sequence_row_shapes_f16(ctx, D):
+    w = synth.scaled(synth.WORKLOADS["cfg3"], F=2, B=517, rows=3000, D=D)
+    _sequence_case(ctx, w)
+
+
+def test_sequence_many_features(ctx):
+    """More features than travel in one launch, and B far below a block's share of rows."""
+    w = synth.scaled(synth.WORKLOADS["cfg1"], F=131, B=67, rows=500, D=16)
+    _sequence_case(ctx, w)
+
+
+def test_sequence_uniform_long_lists(ctx):
+    w = synth.scaled(synth.WORKLOADS["cfg4"], F=5, B=1000, rows=100_000)
+    _sequence_case(ctx, w)
+
+
+def test_sequence_hand_cases(ctx):
+    # the worked example's shape: rows 0 and 2 share a list; plus empty rows and a lone feature
+    # whose rows are all empty (its position range is empty and must be skipped)
+    lists = [[[3, 4, 5], [4, 5, 6], [3, 4, 5], []], [[], [], [], []], [[1], [1], [], [2, 2, 2, 2, 2]]]
+    batch = synth.batch_from_lists(lists)
+    tabs = [np.arange(8 * 4, dtype=np.float32).reshape(8, 4) + 100 * f for f in range(3)]
+    ik, emb, out, kjt = gpu_sequence(ctx, batch, gu.tables_to_dev(tabs, "f32"), torch.float32)
+    flat = [(f, i) for f in range(3) for row in lists[f] for i in row]
+    want = np.stack([tabs[f][i] for f, i in flat])
+    assert np.array_equal(out.cpu().numpy(), want) and np.array_equal(kjt.cpu().numpy(), want)
+    assert ik.M == 6 + 0 + 6
+
+
+def test_sequence_no_ids(ctx):
+    batch = synth.batch_from_lists([[[], [], []], [[], [], []]])
+    tabs = [np.ones((4, 8), np.float32)] * 2
+    ik, emb, out, kjt = gpu_sequence(ctx, batch, gu.tables_to_dev(tabs, "f32"), torch.float32)
+    assert ik.M == 0 and out.numel() == 0 and torch.isnan(emb).all()
+
+
+def test_sequence_errors(ctx, recd):
+    tab = [torch.zeros(10, 8, device="cuda")]
+    values = torch.tensor([1, 2, 3, 1, 2], dtype=torch.int64, device="cuda")
+    offsets = torch.tensor([0, 2, 3, 5], dtype=torch.int64, device="cuda")
+    ik = gu.DeviceIKJT(1, 3, 5)
+    ctx.build_ikjt(1, 3, values, offsets, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff)
+    emb = torch.zeros(5, 8, device="cuda")
+    out = torch.zeros(5, 8, device="cuda")
+    with pytest.raises(recd.RecdError) as e:  # 24-byte rows
+        ctx.kjt_sequence_lookup([torch.zeros(10, 6, device="cuda")], 3, values, offsets,
+                                torch.zeros(5, 6, device="cuda"))
+    assert e.value.status == recd.RECD_EINVAL
+    ctx.set_option(recd.RECD_OPT_VALIDATE, 1)
+    try:
+        ctx.sequence_lookup_unique(tab, ik.u_values, ik.u_offsets, ik.feat_uoff, 3, emb)
+        ctx.jagged_expand_inverse(1, 3, emb, ik.u_offsets, ik.feat_uoff, ik.inverse, offsets, out)
+        ctx.kjt_sequence_lookup(tab, 3, values, offsets, out)
+        # row 1 (one id) pointed at the slot of the two-id list
+        bad_inv = torch.tensor([0, 0, 0], dtype=torch.int32, device="cuda")
+        with pytest.raises(recd.RecdError) as e:
+            ctx.jagged_expand_inverse(1, 3, emb, ik.u_offsets, ik.feat_uoff, bad_inv, offsets, out)
+        assert e.value.status == recd.RECD_EBOUNDS
+        out_of_range = torch.tensor([0, 2, 0], dtype=torch.int32, device="cuda")
+        with pytest.raises(recd.RecdError) as e:
+            ctx.jagged_expand_inverse(1, 3, emb, ik.u_offsets, ik.feat_uoff, out_of_range, offsets, out)
+        assert e.value.status == recd.RECD_EBOUNDS
+        with pytest.raises(recd.RecdError) as e:  # id 12 is outside the 10-row table
+            ctx.kjt_sequence_lookup(tab, 3, torch.tensor([1, 2, 12, 1, 2], dtype=torch.int64, device="cuda"),
+                                    offsets, out)
+        assert e.value.status == recd.RECD_EBOUNDS
+        with pytest.raises(recd.RecdError) as e:  # emb too small for the M = 3 unique ids
+            ctx.sequence_lookup_unique(tab, ik.u_values, ik.u_offsets, ik.feat_uoff, 3, emb[:2])
+        assert e.value.status == recd.RECD_ECAPACITY
+    finally:
+        ctx.set_option(recd.RECD_OPT_VALIDATE, 0)
