@@ -40,6 +40,9 @@ def parse_args():
     ap.add_argument("--store-grad", action="store_true",
                     help="also store the per-row gradients (default: the fused Adagrad update consumes them "
                          "from registers)")
+    ap.add_argument("--sequence", action="store_true",
+                    help="also time the unpooled path (sequence lookup on the unique lists + jagged expand) "
+                         "and its non-deduplicated comparison; reported beside the step, not part of it")
     ap.add_argument("--tune", type=int, default=0, help="RECD_OPT_TUNE_SEGSUM value (0 = automatic)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates hardware byte counters)")
@@ -232,7 +235,53 @@ def run_workload(torch, recd, synth, w, args, need_backward, detail=True):
     res["speedup_vs_kjt"] = kjt_ms / (lookup_ms + expand_ms)
     res["speedup_vs_kjt_with_build"] = kjt_ms / (build_ms + lookup_ms + expand_ms)
     res["predicted_speedup_bytes_model"] = kjt_upper / (look_upper + F * B * 4 + 2 * F * B * D * o)
+    if getattr(args, "sequence", False):
+        res["sequence"] = sequence_regions(torch, P, cnt, timed, reps, R)
     return res, P
+
+
+def sequence_regions(torch, P, cnt, timed, reps, R):
+    """Unpooled path on the resident IKJTs: one activation row per id.  Every call is one copy
+    kernel; bytes are ids read + rows read + rows written (compulsory form: each distinct source
+    row once per launch)."""
+    w = P.w
+    F, B, D = w.F, w.B, w.D
+    e = 4 if w.table_dtype == "f32" else 2
+    Nmax = max(b.N for b in P.batches)
+    Mmax = max(c[1] for c in cnt)
+    emb = torch.empty(Mmax, D, dtype=P.tdt, device="cuda")
+    out = torch.empty(Nmax, D, dtype=P.tdt, device="cuda")
+
+    def seq(i):
+        P.ctx.sequence_lookup_unique(P.tables, P.u_values[i], P.u_offsets[i], P.feat_uoff[i], cnt[i][0], emb)
+
+    def jag(i):
+        P.ctx.jagged_expand_inverse(F, B, emb, P.u_offsets[i], P.feat_uoff[i], P.inverse[i], P.offsets[i],
+                                    out[:P.batches[i].N])
+
+    def kjt(i):
+        P.ctx.kjt_sequence_lookup(P.tables, B, P.values[i], P.offsets[i], out[:P.batches[i].N])
+
+    for i in range(len(P.batches)):
+        seq(i), jag(i), kjt(i)
+    t = {"seq": [], "jag": [], "kjt": []}
+    for _ in range(max(reps // 2, 2)):
+        t["seq"].append(timed(seq))
+        t["jag"].append(timed(jag))
+        t["kjt"].append(timed(kjt))
+    seq_ms, jag_ms, kjt_ms = (float(np.mean(t[k])) for k in ("seq", "jag", "kjt"))
+    N = float(np.mean([b.N for b in P.batches]))
+    U = float(np.mean([c[0] for c in cnt]))
+    M = float(np.mean([c[1] for c in cnt]))
+    rd = M if R is None else R
+    by = {"sequence_lookup_unique": M * 8 + rd * D * e + M * D * e,
+          "jagged_expand": F * B * (4 + 8) + U * 8 + M * D * e + N * D * e,
+          "kjt_sequence": N * 8 + rd * D * e + N * D * e}
+    ms = {"sequence_lookup_unique": seq_ms, "jagged_expand": jag_ms, "kjt_sequence": kjt_ms}
+    return {"sequence_lookup_unique_ms": seq_ms, "jagged_expand_ms": jag_ms, "kjt_sequence_ms": kjt_ms,
+            "bytes": by, "gbs": {k: by[k] / ms[k] / 1e6 for k in by},
+            "activation_bytes_unique": M * D * e, "activation_bytes_kjt": N * D * e,
+            "speedup_vs_kjt": kjt_ms / (seq_ms + jag_ms)}
 
 
 def cpu_baseline(torch, synth, P, n_feat):

@@ -13,10 +13,9 @@
 //   gather:  positions (ids) are dealt to blocks in tiles; the feature of a position - which table
 //            to read - is found from the F+1 position bounds kept in LDS (one search per tile, a
 //            short walk only for tiles that straddle a feature boundary).
-//   jagged:  a block owns kJagLists consecutive KJT rows.  Their source and destination starts go
-//            to LDS; the rows to copy are then numbered flat across the block's lists, so long and
-//            short lists load the threads alike, and each thread finds the list of its row by a
-//            fixed-depth search of the destination starts.
+//   jagged:  a block owns a few consecutive KJT rows, folds neighbours that share a unique slot
+//            into runs (read once, stored once per member) and numbers the rows to read flat
+//            across its runs, so long and short lists load the threads alike.
 #include "recd_internal.h"
 
 #include <hip/hip_fp16.h>
@@ -25,7 +24,6 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kRPT = 8;        // rows a thread has in flight
-constexpr int kJagLists = 64;  // KJT rows per block of the jagged expand
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // pb[f] = position of the first id of feature f, pb[F] = one past the last id
@@ -136,57 +134,110 @@ __global__ __launch_bounds__(kBlock) void k_seq_gather(TablePtrs tables, int Fc,
 
 // out[offsets[l] + t, :] = emb[u_offsets[feat_uoff[f] + inverse[l]] + t, :] for the rows
 // l = f*B + b of the KJT, t in [0, offsets[l+1] - offsets[l]).
+// A block owns LISTS <= 64 consecutive KJT rows.  Its first wave folds neighbouring rows that point
+// at the same unique slot into runs (the samples of a session are adjacent, so most duplicates
+// are): a run is read once and stored once per member.  The rows to read are numbered flat across
+// the block's runs, so long and short lists load the threads alike; a thread finds the run of its
+// row by a fixed-depth search of the runs' flat starts in LDS.
+template <int LISTS, int RPT>
 __global__ __launch_bounds__(kBlock) void k_jagged_expand(const u32x4 *__restrict__ emb,
                                                           const int64_t *__restrict__ u_offsets,
                                                           const int64_t *__restrict__ feat_uoff,
                                                           const int32_t *__restrict__ inverse,
                                                           const int64_t *__restrict__ offsets,
                                                           u32x4 *__restrict__ out, uint32_t B,
-                                                          uint32_t L, int vecs, int64_t emb_rows_cap)
+                                                          uint32_t L, int vecs, int64_t emb_rows_cap,
+                                                          int64_t out_rows)
 {
-    __shared__ int64_t src_s[kJagLists];
-    __shared__ uint32_t rel_s[kJagLists + 1];
-    const uint32_t l0 = blockIdx.x * kJagLists;
-    const uint32_t nl = L - l0 < (uint32_t)kJagLists ? L - l0 : (uint32_t)kJagLists;
+    static_assert(LISTS <= 64 && (LISTS & (LISTS - 1)) == 0, "one wave prepares the runs");
+    __shared__ int64_t run_src[LISTS];   // first emb row of the run's list
+    __shared__ uint32_t run_dst[LISTS];  // first output row of the run, relative to the block's
+    __shared__ uint32_t run_len[LISTS];  // ids per member list
+    __shared__ uint32_t run_cnt[LISTS];  // member lists
+    __shared__ uint32_t run_rel[LISTS + 1];  // flat number of the run's first row to read
+    __shared__ uint32_t n_runs_s;
+    const uint32_t l0 = blockIdx.x * LISTS;
+    const uint32_t nl = L - l0 < (uint32_t)LISTS ? L - l0 : (uint32_t)LISTS;
     const int64_t d0 = offsets[l0];
-    if (threadIdx.x < nl) {
-        const uint32_t l = l0 + threadIdx.x;
-        const int64_t u = feat_uoff[l / B] + inverse[l];
-        src_s[threadIdx.x] = u_offsets[u];
-        rel_s[threadIdx.x] = (uint32_t)(offsets[l] - d0);
+    if (threadIdx.x < 64) {
+        const uint32_t i = threadIdx.x;
+        const bool live = i < nl;
+        int64_t u = -1, src = 0;
+        uint32_t dst = 0, len = 0;
+        if (live) {
+            const uint32_t l = l0 + i;
+            u = feat_uoff[l / B] + inverse[l];  // slot index, distinct across features
+            src = u_offsets[u];
+            const int64_t o0 = offsets[l];
+            dst = (uint32_t)(o0 - d0);
+            len = (uint32_t)(offsets[l + 1] - o0);
+        }
+        const int64_t prev = __shfl_up(u, 1);
+        const bool head = live && (i == 0 || u != prev);
+        const uint64_t heads = __ballot(head);
+        uint32_t incl = head ? len : 0;  // inclusive scan over the run heads' lengths
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t t = __shfl_up(incl, d);
+            if (i >= (uint32_t)d)
+                incl += t;
+        }
+        if (head) {
+            const uint32_t r = __popcll(heads & ((1ull << i) - 1));
+            const uint64_t above = i == 63 ? 0 : heads >> (i + 1);
+            const uint32_t next = above ? i + 1 + (uint32_t)__builtin_ctzll(above) : nl;
+            run_src[r] = src;
+            run_dst[r] = dst;
+            run_len[r] = len;
+            run_cnt[r] = next - i;
+            run_rel[r] = incl - len;
+        }
+        if (i == 63) {
+            run_rel[__popcll(heads)] = incl;
+            n_runs_s = __popcll(heads);
+        }
     }
-    if (threadIdx.x == kBlock - 1)
-        rel_s[nl] = (uint32_t)(offsets[l0 + nl] - d0);
     __syncthreads();
-    const uint32_t total = rel_s[nl];
+    const uint32_t n_runs = n_runs_s;
+    const uint32_t total = run_rel[n_runs];
     const uint32_t rows_per_sweep = kBlock / vecs;
     const uint32_t piece = threadIdx.x % vecs;
     const uint32_t sub = threadIdx.x / vecs;
     if (sub >= rows_per_sweep)
         return;
-    for (uint32_t base = 0; base < total; base += rows_per_sweep * kRPT) {
-        u32x4 v[kRPT];
+    for (uint32_t base = 0; base < total; base += rows_per_sweep * RPT) {
+        u32x4 v[RPT] = {};
+        uint32_t run[RPT] = {};
 #pragma unroll
-        for (int k = 0; k < kRPT; k++) {
+        for (int k = 0; k < RPT; k++) {
+            if (base + k * rows_per_sweep >= total)
+                break;  // the whole sweep lies beyond the block's rows (same decision in every thread)
             const uint32_t r = base + k * rows_per_sweep + sub;
             const uint32_t rc = r < total ? r : total - 1;
-            // the last list i with rel_s[i] <= rc; rc < rel_s[nl], so list i is not empty
+            // the last run i with run_rel[i] <= rc; rc < run_rel[n_runs], so run i is not empty
             uint32_t i = 0;
 #pragma unroll
-            for (uint32_t s = kJagLists / 2; s >= 1; s >>= 1)
-                if (i + s < nl && rel_s[i + s] <= rc)
+            for (uint32_t s = LISTS / 2; s >= 1; s >>= 1)
+                if (i + s < n_runs && run_rel[i + s] <= rc)
                     i += s;
-            int64_t srow = src_s[i] + (rc - rel_s[i]);
+            run[k] = i;
+            int64_t srow = run_src[i] + (rc - run_rel[i]);
             // a slot whose list is shorter than the row (malformed input) must not read past emb
             srow = srow < emb_rows_cap ? srow : emb_rows_cap - 1;
             srow = srow < 0 ? 0 : srow;
             v[k] = emb[srow * vecs + piece];
         }
 #pragma unroll
-        for (int k = 0; k < kRPT; k++) {
+        for (int k = 0; k < RPT; k++) {
             const uint32_t r = base + k * rows_per_sweep + sub;
-            if (r < total)
-                __builtin_nontemporal_store(v[k], &out[(d0 + r) * vecs + piece]);
+            if (r < total) {
+                const uint32_t i = run[k];
+                const uint32_t len = run_len[i], cnt = run_cnt[i];
+                int64_t row = d0 + run_dst[i] + (r - run_rel[i]);
+                for (uint32_t j = 0; j < cnt; j++, row += len)
+                    if (row < out_rows)  // false only for malformed input (members of unequal length)
+                        __builtin_nontemporal_store(v[k], &out[row * vecs + piece]);
+            }
         }
     }
 }
@@ -346,10 +397,27 @@ recd_status recd_jagged_expand_inverse(recd_ctx *ctx, int F, int64_t B, int64_t 
             return recd_fail(ctx, RECD_EBOUNDS, "a row's unique slot holds a list of another length");
     }
     const int vecs = (int)((size_t)D * elem_size(dt) / 16);
-    const int64_t blocks = (L + kJagLists - 1) / kJagLists;
-    hipLaunchKernelGGL(k_jagged_expand, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
-                       static_cast<const u32x4 *>(emb), u_offsets, feat_uoff, inverse, offsets,
-                       static_cast<u32x4 *>(out), (uint32_t)B, (uint32_t)L, vecs, M_cap);
+    // Lists per block: about 128 rows to read and write per block.  Small blocks keep the region
+    // that the resident blocks write at any one time compact, which measures faster than large
+    // blocks although runs of duplicates are cut at block borders.
+    const double avg = (double)N / (double)L;
+    int lists = 2;
+    while (lists < 64 && 2.0 * lists * avg <= 192.0)
+        lists *= 2;
+#define JAG(LISTS)                                                                                \
+    hipLaunchKernelGGL((k_jagged_expand<LISTS, kRPT>), dim3((unsigned)((L + LISTS - 1) / LISTS)),  \
+                       dim3(kBlock), 0, ctx->stream, static_cast<const u32x4 *>(emb), u_offsets,   \
+                       feat_uoff, inverse, offsets, static_cast<u32x4 *>(out), (uint32_t)B,        \
+                       (uint32_t)L, vecs, M_cap, N)
+    switch (lists) {
+    case 2: JAG(2); break;
+    case 4: JAG(4); break;
+    case 8: JAG(8); break;
+    case 16: JAG(16); break;
+    case 32: JAG(32); break;
+    default: JAG(64); break;
+    }
+#undef JAG
     RECD_HIP(ctx, hipGetLastError());
     return RECD_OK;
 }

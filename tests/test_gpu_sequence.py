@@ -110,6 +110,35 @@ def test_sequence_hand_cases(ctx):
     assert ik.M == 6 + 0 + 6
 
 
+@pytest.mark.parametrize("mean_len", [1, 2, 3, 12, 40, 150])
+def test_jagged_expand_runs_of_duplicates(ctx, mean_len):
+    """Sessions of 1..150 adjacent rows repeating one list (some lists empty, some sessions returning
+    to an earlier list): runs longer than a block's share of rows, runs cut at block and feature
+    borders, and every launch shape (the lists per block follow the mean list length)."""
+    rng = np.random.default_rng(4000 + mean_len)
+    F, B = 3, 777
+    lists = []
+    for f in range(F):
+        rows, pool = [], []
+        while len(rows) < B:
+            if pool and rng.random() < 0.2:
+                lst = pool[int(rng.integers(len(pool)))]
+            else:
+                n = 0 if rng.random() < 0.1 else int(rng.integers(1, 2 * mean_len + 1))
+                lst = rng.integers(0, 50, size=n).tolist()
+                pool.append(lst)
+            rows += [lst] * int(rng.integers(1, 151 if f == 0 else 12))
+        lists.append(rows[:B])
+    batch = synth.batch_from_lists(lists)
+    tabs = [rng.standard_normal((50, 32)).astype(np.float32) for _ in range(F)]
+    ik, emb, out, kjt = gpu_sequence(ctx, batch, gu.tables_to_dev(tabs, "f32"), torch.float32)
+    uv, uo, inv, fu = orc.build_ikjt(F, B, batch.values, batch.offsets)
+    ref_emb = orc.sequence_lookup(tabs, "f32", uv, uo, fu)
+    ref_out = orc.jagged_expand(F, B, ref_emb, uo, fu, inv, batch.offsets)
+    assert np.array_equal(gu.out_to_f64(out), ref_out)
+    assert torch.equal(_bits(out), _bits(kjt))
+
+
 def test_sequence_no_ids(ctx):
     batch = synth.batch_from_lists([[[], [], []], [[], [], []]])
     tabs = [np.ones((4, 8), np.float32)] * 2
