@@ -146,3 +146,53 @@ def test_cfg5_training_step_full(recd):
         untouched[tr_f] = False
         assert np.array_equal(after[untouched], before[f][untouched])
     ctx.close()
+
+
+def _run_sequence(recd, w, batch_index, sample_features):
+    """Unpooled path at full size: every output row against the non-deduplicated lookup (bit for
+    bit), sampled features against the oracle (exact: the path only copies)."""
+    batch = synth.make_batch(w, batch_index)
+    F, B, D, N = w.F, w.B, w.D, batch.N
+    tdt = gu.TORCH_DT[w.table_dtype]
+    tabs = _device_tables(w, tdt)
+    ctx = recd.Context(0)
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    emb = torch.zeros(ik.M, D, dtype=tdt, device="cuda")
+    out = torch.zeros(N, D, dtype=tdt, device="cuda")
+    kjt = torch.zeros(N, D, dtype=tdt, device="cuda")
+    ctx.sequence_lookup_unique(tabs, ik.u_values, ik.u_offsets, ik.feat_uoff, ik.U, emb)
+    ctx.jagged_expand_inverse(F, B, emb, ik.u_offsets, ik.feat_uoff, ik.inverse, offsets, out)
+    ctx.kjt_sequence_lookup(tabs, B, values, offsets, kjt)
+    torch.cuda.synchronize()
+    bits = torch.int32 if tdt == torch.float32 else torch.int16
+    assert torch.equal(out.view(bits), kjt.view(bits))
+    del kjt
+    uv, uo, inv, fu = orc.build_ikjt(F, B, batch.values, batch.offsets)
+    assert ik.M == len(uv)
+    for f in sample_features:
+        host = _host_table(tabs[f], w.table_dtype)
+        v_f, o_f = _feature_slice(batch, f)
+        lo, hi = int(batch.offsets[f * B]), int(batch.offsets[(f + 1) * B])
+        ref = orc.sequence_lookup([host], w.table_dtype, v_f, o_f, np.array([0, B], dtype=np.int64))
+        assert np.array_equal(gu.out_to_f64(out[lo:hi]), ref), f"expanded activations of feature {f}"
+        ulo, uhi = int(uo[fu[f]]), int(uo[fu[f + 1]])
+        uo_f = uo[fu[f]:fu[f + 1] + 1] - ulo
+        ref_emb = orc.sequence_lookup([host], w.table_dtype, uv[ulo:uhi], uo_f,
+                                      np.array([0, fu[f + 1] - fu[f]], dtype=np.int64))
+        assert np.array_equal(gu.out_to_f64(emb[ulo:uhi]), ref_emb), f"unique activations of feature {f}"
+        ref_out = orc.jagged_expand(1, B, ref_emb, uo_f, np.array([0, fu[f + 1] - fu[f]], dtype=np.int64),
+                                    inv[f * B:(f + 1) * B], o_f)
+        assert np.array_equal(ref_out, ref)
+    ctx.close()
+
+
+def test_cfg2_sequence_full(recd):
+    _run_sequence(recd, synth.WORKLOADS["cfg2"], 0, sample_features=(0, 9, 15))
+
+
+def test_cfg3_sequence_full_fp16(recd):
+    _run_sequence(recd, synth.WORKLOADS["cfg3"], 0, sample_features=(5, 63))
+
+
+def test_cfg5_sequence_full(recd):
+    _run_sequence(recd, synth.WORKLOADS["cfg5"], 2, sample_features=(0, 33, 63))
