@@ -24,6 +24,7 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kRPT = 8;        // rows a thread has in flight
+constexpr int kXcds = 8;       // accelerator dies, each with a private L2
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 // pb[f] = position of the first id of feature f, pb[F] = one past the last id
@@ -77,7 +78,14 @@ __global__ __launch_bounds__(kBlock) void k_seq_gather(TablePtrs tables, int Fc,
     int64_t hi = pb_s[Fc];
     if (hi > out_rows_cap)
         hi = out_rows_cap;
-    for (int64_t t0 = lo + (int64_t)blockIdx.x * tile_rows; t0 < hi; t0 += (int64_t)gridDim.x * tile_rows) {
+    // KJT path (STREAM): within one sweep of the grid every XCD (consecutive blocks go to consecutive
+    // XCDs) takes a contiguous eighth of the tiles: neighbouring positions, which in a
+    // session-clustered batch mostly name the same table rows, then gather through the same L2
+    // (a quarter of the HBM reads at the benchmark shape).  The unique lists hold few repeats and
+    // measure faster with the plain order.
+    const uint32_t per_xcd = gridDim.x / kXcds;  // the grid is a multiple of kXcds
+    const uint32_t item = STREAM ? (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds : blockIdx.x;
+    for (int64_t t0 = lo + (int64_t)item * tile_rows; t0 < hi; t0 += (int64_t)gridDim.x * tile_rows) {
         // feature of the tile's first position: the last f with pb_s[f] <= t0 (t0 < pb_s[Fc], so
         // that feature is not empty)
         int f0 = 0;
@@ -156,7 +164,14 @@ __global__ __launch_bounds__(kBlock) void k_jagged_expand(const u32x4 *__restric
     __shared__ uint32_t run_cnt[LISTS];  // member lists
     __shared__ uint32_t run_rel[LISTS + 1];  // flat number of the run's first row to read
     __shared__ uint32_t n_runs_s;
-    const uint32_t l0 = blockIdx.x * LISTS;
+    // Consecutive blocks go to consecutive XCDs.  Each XCD takes one contiguous eighth of the rows
+    // instead, so that blocks which split a run of duplicates read its unique list through the
+    // same L2.
+    const uint32_t per_xcd = gridDim.x / kXcds;  // the grid is a multiple of kXcds
+    const uint32_t item = (blockIdx.x % kXcds) * per_xcd + blockIdx.x / kXcds;
+    if ((uint64_t)item * LISTS >= L)
+        return;
+    const uint32_t l0 = item * LISTS;
     const uint32_t nl = L - l0 < (uint32_t)LISTS ? L - l0 : (uint32_t)LISTS;
     const int64_t d0 = offsets[l0];
     if (threadIdx.x < 64) {
@@ -286,9 +301,12 @@ recd_status sequence_gather(recd_ctx *ctx, int F, int D, recd_dtype table_dt, re
     const int vecs = (int)((size_t)D * elem_size(table_dt) / 16);
     const int64_t tile_rows = (int64_t)(kBlock / vecs) * kRPT;
     int64_t blocks = (rows_cap + tile_rows - 1) / tile_rows;
-    const int64_t cap = (int64_t)ctx->num_cu * 8 * 16;
+    // rows_cap is exact for the KJT (one block per tile measures fastest); for unique lists it may
+    // be a loose bound, so the grid is capped and the kernel strides over the tiles
+    const int64_t cap = stream_out ? ((int64_t)1 << 30) : (int64_t)ctx->num_cu * 8 * 16;
     if (blocks > cap)
-        blocks = cap;  // the kernel strides over the tiles
+        blocks = cap;
+    blocks = (blocks + kXcds - 1) / kXcds * kXcds;
     const int conv = out_dt == table_dt ? 0 : (table_dt == RECD_F16 ? 1 : 2);
     for (int f0 = 0; f0 < F; f0 += RECD_F_PER_LAUNCH) {
         const int fc = F - f0 < RECD_F_PER_LAUNCH ? F - f0 : RECD_F_PER_LAUNCH;
@@ -405,7 +423,8 @@ recd_status recd_jagged_expand_inverse(recd_ctx *ctx, int F, int64_t B, int64_t 
     while (lists < 64 && 2.0 * lists * avg <= 192.0)
         lists *= 2;
 #define JAG(LISTS)                                                                                \
-    hipLaunchKernelGGL((k_jagged_expand<LISTS, kRPT>), dim3((unsigned)((L + LISTS - 1) / LISTS)),  \
+    hipLaunchKernelGGL((k_jagged_expand<LISTS, kRPT>),                                             \
+                       dim3((unsigned)(((L + LISTS - 1) / LISTS + kXcds - 1) / kXcds * kXcds)),     \
                        dim3(kBlock), 0, ctx->stream, static_cast<const u32x4 *>(emb), u_offsets,   \
                        feat_uoff, inverse, offsets, static_cast<u32x4 *>(out), (uint32_t)B,        \
                        (uint32_t)L, vecs, M_cap, N)
