@@ -129,6 +129,76 @@ int oracle_build_ikjt(int F, int64_t B, const int64_t *values, const int64_t *of
     return 0;
 }
 
+/* ---- KJT -> grouped IKJT (Sec. 4.2 "Grouped IKJTs") -------------------------------------------
+ * Group g holds the consecutive features [group_off[g], group_off[g+1]) and has ONE inverse_lookup
+ * for all of them: two rows of the batch share a slot iff, for every feature of the group, they
+ * hold the same list.  Rows that agree in some features of the group only are kept apart (the
+ * paper does not deduplicate unsynchronised rows, so that the shared inverse stays valid); such a
+ * feature then stores its list once per slot, duplicates included.  Slots are numbered in
+ * first-occurrence order as in the ungrouped case.  Every feature of the group stores one list per
+ * slot, in slot order: feature f's unique lists are u_offsets[feat_uoff[f] + k], k in [0, U_g),
+ * and the unique arrays are concatenated feature-major.  inverse_g[g*B + b] in [0, U_g);
+ * group_uoff = prefix sum of U_g.  Singleton groups give the ungrouped IKJT.
+ */
+int oracle_build_ikjt_grouped(int F, int64_t B, int G, const int32_t *group_off,
+                              const int64_t *values, const int64_t *offsets, int64_t *u_values,
+                              int64_t *u_offsets, int32_t *inverse_g, int64_t *group_uoff,
+                              int64_t *feat_uoff)
+{
+    if (G < 0 || group_off[0] != 0 || group_off[G] != F)
+        return -7;
+    for (int g = 0; g < G; g++)
+        if (group_off[g + 1] <= group_off[g])
+            return -7; /* groups are non-empty runs of consecutive features */
+    int64_t *slot_row = (int64_t *)malloc(sizeof(int64_t) * (size_t)(B > 0 ? B : 1));
+    if (!slot_row)
+        return -8;
+    int64_t U = 0, M = 0, UG = 0;
+    u_offsets[0] = 0;
+    for (int g = 0; g < G; g++) {
+        const int f0 = group_off[g], f1 = group_off[g + 1];
+        int64_t n_slots = 0;
+        group_uoff[g] = UG;
+        for (int64_t b = 0; b < B; b++) {
+            int64_t found = -1;
+            for (int64_t k = 0; k < n_slots && found < 0; k++) {
+                const int64_t r = slot_row[k];
+                int same = 1;
+                for (int f = f0; f < f1 && same; f++) {
+                    const int64_t lb = (int64_t)f * B + b, lr = (int64_t)f * B + r;
+                    const int64_t len = offsets[lb + 1] - offsets[lb];
+                    if (offsets[lr + 1] - offsets[lr] != len)
+                        same = 0;
+                    for (int64_t t = 0; t < len && same; t++)
+                        if (values[offsets[lb] + t] != values[offsets[lr] + t])
+                            same = 0;
+                }
+                if (same)
+                    found = k;
+            }
+            if (found < 0) {
+                found = n_slots;
+                slot_row[n_slots++] = b;
+            }
+            inverse_g[(int64_t)g * B + b] = (int32_t)found;
+        }
+        UG += n_slots;
+        for (int f = f0; f < f1; f++) {
+            feat_uoff[f] = U;
+            for (int64_t k = 0; k < n_slots; k++) {
+                const int64_t l = (int64_t)f * B + slot_row[k];
+                for (int64_t j = offsets[l]; j < offsets[l + 1]; j++)
+                    u_values[M++] = values[j];
+                u_offsets[++U] = M;
+            }
+        }
+    }
+    group_uoff[G] = UG;
+    feat_uoff[F] = U;
+    free(slot_row);
+    return 0;
+}
+
 /* ---- sum-pooled embedding-bag lookup (Sec. 2.2 pooling; Sec. 5 "EMB Lookups",
  * "Deduplicated Pooling") --------------------------------------------------------------------
  * out[l,:] = sum over the ids j of list l, in list order, of W_f[values[j],:], accumulated in
@@ -151,6 +221,33 @@ int oracle_pooled_lookup(int F, int D, int dtype, const void *const *tables, con
                     return -4;
                 for (int d = 0; d < D; d++)
                     o[d] += elem(tables[f], dtype, id * D + d);
+            }
+        }
+    }
+    return 0;
+}
+
+/* ---- a compute module on a grouped IKJT (Sec. 5 "Deduplicated Pooling": the element-wise sum
+ * over the features of a group, computed once per unique row) ----------------------------------
+ * combined[group_uoff[g] + k, :] = sum over the features f of group g, in feature order, of
+ * pooled[feat_uoff[f] + k, :], for k in [0, U_g).  The shared inverse then expands it
+ * (oracle_expand_inverse with the groups in the role of features).
+ */
+int oracle_group_sum(int F, int G, int D, const int32_t *group_off, const double *pooled,
+                     const int64_t *feat_uoff, const int64_t *group_uoff, double *combined)
+{
+    (void)F;
+    for (int g = 0; g < G; g++) {
+        const int64_t Ug = group_uoff[g + 1] - group_uoff[g];
+        for (int64_t k = 0; k < Ug; k++) {
+            double *o = combined + (group_uoff[g] + k) * D;
+            for (int d = 0; d < D; d++)
+                o[d] = 0.0;
+            for (int f = group_off[g]; f < group_off[g + 1]; f++) {
+                if (feat_uoff[f + 1] - feat_uoff[f] != Ug)
+                    return -9; /* every feature of a group holds one list per slot */
+                for (int d = 0; d < D; d++)
+                    o[d] += pooled[(feat_uoff[f] + k) * D + d];
             }
         }
     }

@@ -80,6 +80,30 @@ def build_ikjt(F: int, B: int, values, offsets):
     return u_values[:M].copy(), u_offsets[:U + 1].copy(), inverse[:L].copy(), feat_uoff
 
 
+def build_ikjt_grouped(F: int, B: int, group_off, values, offsets):
+    """KJT -> grouped IKJT (Sec. 4.2 "Grouped IKJTs"): group g = features [group_off[g], group_off[g+1])
+    shares one inverse.  Returns (u_values[M], u_offsets[U+1], inverse_g[G*B] int32, group_uoff[G+1],
+    feat_uoff[F+1]) with U = sum over features of their group's slot count."""
+    values, offsets = _i64(values), _i64(offsets)
+    group_off = np.ascontiguousarray(group_off, dtype=np.int32)
+    G = group_off.shape[0] - 1
+    _check(check_kjt(F, B, values, offsets), "build_ikjt_grouped")
+    N, L = values.shape[0], F * B
+    u_values = np.zeros(max(N, 1), dtype=np.int64)
+    u_offsets = np.zeros(L + 1, dtype=np.int64)
+    inverse_g = np.zeros(max(G * B, 1), dtype=np.int32)
+    group_uoff = np.zeros(G + 1, dtype=np.int64)
+    feat_uoff = np.zeros(F + 1, dtype=np.int64)
+    rc = _lib.oracle_build_ikjt_grouped(C.c_int(F), C.c_int64(B), C.c_int(G), _p(group_off, _i32p),
+                                        _p(values, _i64p), _p(offsets, _i64p), _p(u_values, _i64p),
+                                        _p(u_offsets, _i64p), _p(inverse_g, _i32p), _p(group_uoff, _i64p),
+                                        _p(feat_uoff, _i64p))
+    _check(rc, "build_ikjt_grouped")
+    U = int(feat_uoff[F])
+    M = int(u_offsets[U])
+    return u_values[:M].copy(), u_offsets[:U + 1].copy(), inverse_g[:G * B].copy(), group_uoff, feat_uoff
+
+
 def _table_ptrs(tables: Sequence[np.ndarray], dtype: str):
     keep = []
     for t in tables:
@@ -131,6 +155,20 @@ def expand_inverse(F: int, B: int, pooled: np.ndarray, feat_uoff, inverse) -> np
                                     _p(feat_uoff, _i64p), _p(inverse, _i32p), _p(out, _f64p))
     _check(rc, "expand_inverse")
     return out
+
+
+def group_sum(group_off, pooled: np.ndarray, feat_uoff, group_uoff) -> np.ndarray:
+    """Element-wise sum over the features of every group on the unique rows (Sec. 5 "Deduplicated
+    Pooling").  pooled float64 [U, D] -> float64 [sum of U_g, D]."""
+    group_off = np.ascontiguousarray(group_off, dtype=np.int32)
+    feat_uoff, group_uoff = _i64(feat_uoff), _i64(group_uoff)
+    pooled = np.ascontiguousarray(pooled, dtype=np.float64)
+    G, F, D = group_off.shape[0] - 1, feat_uoff.shape[0] - 1, pooled.shape[1]
+    out = np.zeros((max(int(group_uoff[G]), 1), D), dtype=np.float64)
+    rc = _lib.oracle_group_sum(C.c_int(F), C.c_int(G), C.c_int(D), _p(group_off, _i32p), _p(pooled, _f64p),
+                               _p(feat_uoff, _i64p), _p(group_uoff, _i64p), _p(out, _f64p))
+    _check(rc, "group_sum")
+    return out[:int(group_uoff[G])]
 
 
 def sequence_lookup(tables: Sequence[np.ndarray], dtype: str, values, offsets, list_off) -> np.ndarray:

@@ -273,6 +273,105 @@ def test_half_and_bf16_decode_all_patterns():
         assert (np.isnan(a) and np.isnan(b)) or (a == b and np.signbit(a) == np.signbit(b)), i
 
 
+# ------------------------------------------------------------------ grouped IKJTs
+def _per_feature_inverse(inv_g, group_off, B):
+    sizes = np.diff(np.asarray(group_off))
+    return np.concatenate([np.tile(inv_g[g * B:(g + 1) * B], int(n)) for g, n in enumerate(sizes)]) \
+        if len(sizes) else np.zeros(0, np.int32)
+
+
+def test_paper_grouped_cd_shared_inverse(golden_dir):
+    """Features c and d as ONE group: a common inverse_lookup, slot 0 = [7,8] for c and [9] for d, and
+    the deduplicated element-wise sum [24, 21] expanded to [24, 24, 21]."""
+    g = _golden(golden_dir, "paper_ikjt_features_cd.json")
+    table = np.arange(16, dtype=np.float32).reshape(16, 1)
+    for split in g["row2_splits"]:
+        kjt = synth.batch_from_lists([[g["c_rows01"], g["c_rows01"], split["c"]],
+                                      [g["d_rows01"], g["d_rows01"], split["d"]]])
+        uv, uo, inv_g, gu, fu = orc.build_ikjt_grouped(2, 3, [0, 2], kjt.values, kjt.offsets)
+        assert inv_g.tolist() == g["inverse_lookup"] and gu.tolist() == [0, 2] and fu.tolist() == [0, 2, 4]
+        assert uv[uo[fu[0]]:uo[fu[0] + 1]].tolist() == g["c_rows01"]
+        assert uv[uo[fu[1]]:uo[fu[1] + 1]].tolist() == g["d_rows01"]
+        pooled = orc.pooled_lookup([table, table], "f32", uv, uo, fu)
+        comb = orc.group_sum([0, 2], pooled, fu, gu)
+        assert comb[:, 0].tolist() == g["ikjt_sums"]
+        out = orc.expand_inverse(1, 3, comb, gu, inv_g)
+        assert out[0, :, 0].tolist() == g["kjt_sums"]
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_build_ikjt_grouped_brute_force(seed):
+    rng = np.random.default_rng(7000 + seed)
+    F = int(rng.integers(1, 6))
+    B = int(rng.integers(1, 40))
+    batch = synth.tiny_batch(rng, F, B, int(rng.integers(2, 4)), int(rng.integers(0, 3)))
+    cuts = sorted(set(rng.integers(1, F + 1, size=int(rng.integers(0, 3))).tolist()) | {F})
+    group_off = [0] + cuts
+    G = len(group_off) - 1
+    uv, uo, inv_g, gu, fu = orc.build_ikjt_grouped(F, B, group_off, batch.values, batch.offsets)
+    L = _lists(batch)
+    assert gu[0] == 0 and fu[0] == 0 and len(uo) == fu[F] + 1 and uo[-1] == len(uv)
+    for g in range(G):
+        f0, f1 = group_off[g], group_off[g + 1]
+        Ug = int(gu[g + 1] - gu[g])
+        iv = inv_g[g * B:(g + 1) * B]
+        assert sorted(set(iv.tolist())) == list(range(Ug))
+        rows = [tuple(tuple(L[f][b]) for f in range(f0, f1)) for b in range(B)]
+        for b0, b1 in itertools.combinations(range(B), 2):
+            assert (iv[b0] == iv[b1]) == (rows[b0] == rows[b1])
+        seen = -1
+        for b in range(B):  # first-occurrence numbering
+            assert iv[b] <= seen + 1
+            seen = max(seen, int(iv[b]))
+        for f in range(f0, f1):
+            assert fu[f + 1] - fu[f] == Ug
+    # the grouped IKJT is lossless too
+    assert orc.decode_ikjt(F, B, uv, uo, _per_feature_inverse(inv_g, group_off, B), fu) == L
+
+
+def test_build_ikjt_grouped_special_cases():
+    rng = np.random.default_rng(7100)
+    batch = synth.tiny_batch(rng, 4, 60, 3, 2)
+    # singleton groups: the ungrouped IKJT
+    uv, uo, inv_g, gu, fu = orc.build_ikjt_grouped(4, 60, [0, 1, 2, 3, 4], batch.values, batch.offsets)
+    ruv, ruo, rinv, rfu = orc.build_ikjt(4, 60, batch.values, batch.offsets)
+    assert np.array_equal(uv, ruv) and np.array_equal(uo, ruo) and np.array_equal(inv_g, rinv)
+    assert np.array_equal(gu, rfu) and np.array_equal(fu, rfu)
+    # one group of all features = the ungrouped IKJT of a single feature whose row b spells out the
+    # whole tuple (each list prefixed by its length, so the encoding is injective)
+    L = _lists(batch)
+    spelled = [[x for f in range(4) for x in [len(L[f][b])] + L[f][b]] for b in range(60)]
+    one = synth.batch_from_lists([spelled])
+    _, _, inv_one, fu_one = orc.build_ikjt(1, 60, one.values, one.offsets)
+    uv, uo, inv_g, gu, fu = orc.build_ikjt_grouped(4, 60, [0, 4], batch.values, batch.offsets)
+    assert np.array_equal(inv_g, inv_one) and gu.tolist() == [0, int(fu_one[1])]
+    # unsynchronised features: x never changes, y always does; the group keeps every row apart and
+    # x is stored once per slot (Sec. 4.2: unsynchronised rows are not deduplicated)
+    x = [[5, 6]] * 7
+    y = [[i] for i in range(7)]
+    kjt = synth.batch_from_lists([x, y])
+    uv, uo, inv_g, gu, fu = orc.build_ikjt_grouped(2, 7, [0, 2], kjt.values, kjt.offsets)
+    assert inv_g.tolist() == list(range(7)) and fu.tolist() == [0, 7, 14]
+    assert uv[:14].tolist() == [5, 6] * 7 and uv[14:].tolist() == list(range(7))
+    # malformed groups are refused
+    for bad in ([0, 1], [1, 2], [0, 1, 1, 2], [0, 2, 1]):
+        with pytest.raises(orc.OracleError):
+            orc.build_ikjt_grouped(2, 7, bad, kjt.values, kjt.offsets)
+
+
+def test_group_sum_matches_sum_of_expanded_features():
+    """Deduplicated compute: summing the group's features on the unique rows and expanding once equals
+    summing the per-feature KJT lookups (Sec. 5)."""
+    batch, tabs = _rand_problem(77, F=5, B=33, rows=11, D=3, max_len=3, alphabet=3)
+    group_off = [0, 2, 5]
+    uv, uo, inv_g, gu, fu = orc.build_ikjt_grouped(5, 33, group_off, batch.values, batch.offsets)
+    pooled = orc.pooled_lookup(tabs, "f32", uv, uo, fu)
+    out = orc.expand_inverse(2, 33, orc.group_sum(group_off, pooled, fu, gu), gu, inv_g)
+    full = orc.kjt_pooled_lookup(tabs, "f32", 33, batch.values, batch.offsets)
+    ref = np.stack([full[0:2].sum(axis=0), full[2:5].sum(axis=0)])
+    assert np.allclose(out, ref, rtol=1e-13, atol=1e-13)
+
+
 # ------------------------------------------------------------------ unpooled activations, jagged index select
 def test_paper_feature_b_jagged_expand(golden_dir):
     """With W[r] = r (D = 1) the jagged expand of the unique activations reproduces the KJT's values."""
