@@ -11,6 +11,8 @@
  *   6. sequence lookup    one activation row per id of the unique lists
  *   7. jagged expand      index select of whole unique lists back into the KJT's jagged layout
  *   8. KJT sequence lookup, the non-deduplicated comparison path
+ * and for feature groups that share one inverse index (Sec. 4.2 "Grouped IKJTs"):
+ *   9. grouped builder    10. element-wise sum over a group's features on the unique rows
  *
  * General rules
  *   - Every array argument marked "device" is a pointer into GPU memory owned by the caller and
@@ -211,6 +213,45 @@ recd_status recd_kjt_sequence_lookup(recd_ctx *ctx, int F, int64_t B, int64_t N,
                                      recd_dtype table_dt, recd_dtype out_dt,
                                      const void *const *tables, const int64_t *rows,
                                      const int64_t *values, const int64_t *offsets, void *out);
+
+/* 9. KJT -> grouped IKJT (Sec. 4.2 "Grouped IKJTs": several features deduplicated within one
+ *    IKJT share one inverse_lookup; rows whose features are not all duplicates together are not
+ *    deduplicated, so that the shared inverse stays valid).
+ *    group_off: HOST int32 [G+1], 0 = group_off[0] < ... < group_off[G] = F: group g holds the
+ *    consecutive features [group_off[g], group_off[g+1]) of the KJT.
+ *    Rows b, b' of group g share a slot iff they hold the same list in every feature of g.  Slots
+ *    are numbered in first-occurrence order.  Every feature of g stores one list per slot (its
+ *    own list of the slot's first row), in slot order; the unique arrays are feature-major.
+ *    values [N], offsets [F*B+1]: device, read-only.
+ *    u_values: device, capacity N.  u_offsets: device, capacity F*B+1.
+ *    inverse_g: device int32 [G*B], inverse_g[g*B+b] in [0, U_g).
+ *    group_uoff: device int64 [G+1], prefix sum of U_g.
+ *    feat_uoff: device int64 [F+1], prefix sum of the per-feature list counts (U_g of f's group):
+ *    with it calls 2 and 6 work on the result unchanged.
+ *    inverse_per_feature: optional device int32 [F*B]: the group's inverse repeated for each of
+ *    its features, in the layout calls 3, 5 and 7 expect; NULL to skip.
+ *    host_counts: optional host int64[3]; if non-NULL the call synchronises and stores the number
+ *    of stored lists (feat_uoff[F]), the number of stored ids M, and the sum of U_g.
+ *    Singleton groups give exactly the result of call 1. */
+recd_status recd_build_ikjt_grouped(recd_ctx *ctx, int F, int64_t B, int64_t N, int G,
+                                    const int32_t *group_off, const int64_t *values,
+                                    const int64_t *offsets, int64_t *u_values, int64_t *u_offsets,
+                                    int32_t *inverse_g, int64_t *group_uoff, int64_t *feat_uoff,
+                                    int32_t *inverse_per_feature, int64_t *host_counts);
+
+/* 10. A compute module run on the deduplicated rows of a grouped IKJT (Sec. 5 "Deduplicated
+ *    Pooling": the element-wise sum over the features of a group, computed once per unique row
+ *    and expanded through the shared inverse_lookup):
+ *      combined[group_uoff[g] + k, :] = sum over f in group g (feature order) of
+ *                                       pooled[feat_uoff[f] + k, :],  k in [0, U_g)
+ *    fp32 accumulation, rounded once to dt.  pooled: device [U, D] of dt (output of call 2 on a
+ *    grouped IKJT); combined: device [sum of U_g, D] of dt, capacity max_rows rows (G*B always
+ *    suffices).  recd_expand_inverse(ctx, G, B, D, dt, combined, group_uoff, inverse_g, out) then
+ *    yields the [G, B, D] result.  group_off: HOST int32 [G+1] as in call 9. */
+recd_status recd_group_sum_unique(recd_ctx *ctx, int F, int G, int D, recd_dtype dt,
+                                  const int32_t *group_off, const void *pooled,
+                                  const int64_t *feat_uoff, const int64_t *group_uoff,
+                                  int64_t max_rows, void *combined);
 
 #ifdef __cplusplus
 }

@@ -389,6 +389,173 @@ __global__ void k_empty_ikjt(int F, int64_t *u_offsets, int64_t *feat_uoff, int6
     }
 }
 
+// ---- grouped IKJT (Sec. 4.2 "Grouped IKJTs") ---------------------------------------------------
+// One inverse per group of consecutive features: the item is the row b of group g, i.e. the tuple
+// of the lists (f,b) over the group's features.  Same scheme as above with the tuple in the place
+// of the list: a row equal to its predecessor in every feature is a follower; run heads are hashed
+// over all their lists (feature-salted) and meet in a per-group table; a tag match is followed by
+// an exact comparison of the whole tuple.
+template <int SG>
+__global__ __launch_bounds__(256) void k_group_hash_insert(const int64_t *__restrict__ values,
+                                                           const int64_t *__restrict__ offsets,
+                                                           int64_t B, int64_t n_items,
+                                                           const int32_t *__restrict__ group_off,
+                                                           uint64_t *table, uint32_t cap_mask,
+                                                           int32_t *__restrict__ slot_of, int weak_hash)
+{
+    const int s = threadIdx.x % SG;
+    const int64_t item = (int64_t)blockIdx.x * (256 / SG) + threadIdx.x / SG;
+    if (item >= n_items)
+        return;  // whole lane group leaves together
+    const int64_t g = item / B, b = item - g * B;
+    const int f0 = group_off[g], f1 = group_off[g + 1];
+    int follows = b != 0;
+    uint64_t h = 0;
+    int64_t total_len = 0;
+    for (int f = f0; f < f1; f++) {
+        const int64_t l = (int64_t)f * B + b;
+        const int64_t o1 = offsets[l], len = offsets[l + 1] - o1;
+        const int64_t o0 = b != 0 ? offsets[l - 1] : o1;
+        follows &= (o1 - o0) == len;  // same for all lanes
+        const uint64_t salt = (uint64_t)(f - f0 + 1) * 0xc2b2ae3d27d4eb4full;
+        for (int64_t t = s; t < len; t += SG) {
+            const int64_t x = values[o1 + t];
+            if (follows)
+                follows &= values[o0 + t] == x;
+            h += mix64((uint64_t)x + (uint64_t)(t + 1) * 0x9e3779b97f4a7c15ull + salt);
+        }
+        if (s == 0)
+            h += mix64((uint64_t)len * 0xd6e8feb86659fd93ull + salt + 1ull);
+        total_len += len;
+    }
+#pragma unroll
+    for (int m = SG / 2; m > 0; m >>= 1) {
+        h += __shfl_xor((unsigned long long)h, m, SG);
+        follows &= __shfl_xor(follows, m, SG);
+    }
+    if (follows) {
+        if (s == 0)
+            slot_of[item] = -1;
+        return;
+    }
+    uint64_t hh = mix64(h);
+    if (weak_hash)
+        hh = (uint64_t)total_len;  // test hook: only the exact comparison separates tuples
+    const uint64_t tag = hh >> 32;
+    const uint64_t mine = (tag << 32) | (uint64_t)b;
+    uint64_t *tab = table + (uint64_t)g * ((uint64_t)cap_mask + 1);
+    uint32_t slot = (uint32_t)hh & cap_mask;
+    // at least 2*B slots per group: an empty slot or the tuple's own class is met
+    for (;;) {
+        unsigned long long old = 0;
+        if (s == 0)
+            old = atomicCAS(reinterpret_cast<unsigned long long *>(&tab[slot]), kEmpty, mine);
+        old = __shfl(old, 0, SG);
+        if (old == kEmpty)
+            break;
+        if ((old >> 32) == tag) {
+            const int64_t ob = (int64_t)(old & 0xffffffffull);
+            int eq = 1;
+            for (int f = f0; f < f1 && eq; f++) {  // eq is the same in all lanes at the loop test
+                const int64_t l = (int64_t)f * B + b, ol = (int64_t)f * B + ob;
+                const int64_t o1 = offsets[l], len = offsets[l + 1] - o1, oo = offsets[ol];
+                eq = (offsets[ol + 1] - oo) == len;
+                if (eq)
+                    for (int64_t t = s; t < len; t += SG)
+                        if (values[o1 + t] != values[oo + t]) {
+                            eq = 0;
+                            break;
+                        }
+#pragma unroll
+                for (int m = SG / 2; m > 0; m >>= 1)
+                    eq &= __shfl_xor(eq, m, SG);
+            }
+            if (eq) {
+                if (s == 0)
+                    atomicMin(reinterpret_cast<unsigned long long *>(&tab[slot]), mine);
+                break;
+            }
+        }
+        slot = (slot + 1) & cap_mask;
+    }
+    if (s == 0)
+        slot_of[item] = (int32_t)slot;
+}
+
+// Feature-level compaction of a grouped IKJT: list (f,b) is stored iff row b is the representative
+// of its slot in f's group.  Pass 1 (NUMBER = false): per-block sums of (stored, stored * length).
+// Pass 2 (NUMBER = true), after the scan of the block sums: positions of the stored lists.
+template <bool NUMBER>
+__global__ __launch_bounds__(kScanBlock) void k_group_compact(const int64_t *__restrict__ offsets,
+                                                              int64_t B, int64_t n_lists, int F,
+                                                              const int32_t *__restrict__ feat_group,
+                                                              const int32_t *__restrict__ rep_g,
+                                                              const int32_t *__restrict__ inverse_g,
+                                                              int64_t *__restrict__ bs_cnt,
+                                                              int64_t *__restrict__ bs_len,
+                                                              int64_t *__restrict__ bs_head,
+                                                              int32_t *__restrict__ src_of,
+                                                              int64_t *__restrict__ u_offsets,
+                                                              int64_t *__restrict__ feat_uoff,
+                                                              int32_t *__restrict__ inverse_f,
+                                                              int64_t *__restrict__ counts)
+{
+    const int64_t l = (int64_t)blockIdx.x * kScanBlock + threadIdx.x;
+    int64_t first = 0, flen = 0, f = 0, b = -1, item = 0;
+    if (l < n_lists) {
+        f = l / B;
+        b = l - f * B;
+        item = (int64_t)feat_group[f] * B + b;
+        if (rep_g[item] == b) {
+            first = 1;
+            flen = offsets[l + 1] - offsets[l];
+        }
+    }
+    int64_t ea, eb, ic, ta, tb, tc;
+    block_scan3(first, flen, -1, ea, eb, ic, ta, tb, tc);
+    if (!NUMBER) {
+        if (threadIdx.x == 0) {
+            bs_cnt[blockIdx.x] = ta;
+            bs_len[blockIdx.x] = tb;
+            bs_head[blockIdx.x] = -1;
+        }
+        return;
+    }
+    if (l < n_lists) {
+        const int64_t num = bs_cnt[blockIdx.x] + ea;
+        const int64_t pos = bs_len[blockIdx.x] + eb;
+        if (first) {
+            u_offsets[num] = pos;
+            src_of[num] = (int32_t)l;
+        }
+        if (b == 0)
+            feat_uoff[f] = num;
+        if (inverse_f)
+            inverse_f[l] = inverse_g[item];
+        if (l == n_lists - 1) {
+            const int64_t U = num + first, M = pos + flen;
+            u_offsets[U] = M;
+            feat_uoff[F] = U;
+            counts[0] = U;
+            counts[1] = M;
+        }
+    }
+}
+
+__global__ void k_empty_grouped(int F, int G, int64_t *u_offsets, int64_t *feat_uoff, int64_t *group_uoff,
+                                int64_t *counts, int64_t *counts_g)
+{
+    for (int f = threadIdx.x; f <= F; f += blockDim.x)
+        feat_uoff[f] = 0;
+    for (int g = threadIdx.x; g <= G; g += blockDim.x)
+        group_uoff[g] = 0;
+    if (threadIdx.x == 0) {
+        u_offsets[0] = 0;
+        counts[0] = counts[1] = 0;
+        counts_g[0] = counts_g[1] = 0;
+    }
+}
+
 uint64_t table_cap(int64_t B)
 {
     uint64_t cap = 64;
@@ -483,6 +650,146 @@ extern "C" recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t 
         RECD_HIP(ctx, hipStreamSynchronize(st));
         host_U_M[0] = ctx->host_pinned[0];
         host_U_M[1] = ctx->host_pinned[1];
+    }
+    return RECD_OK;
+}
+
+
+namespace {
+struct GroupedWs {
+    int64_t *counts, *counts_g;
+    uint64_t *table;
+    int32_t *slot_of, *rep_g, *number_g, *src_g, *src_of, *group_off, *feat_group;
+    int64_t *zero_off, *u_tmp, *bs_cnt, *bs_len, *bs_head;
+};
+GroupedWs carve_grouped(char *base, int F, int G, int64_t B, size_t *bytes)
+{
+    WsCarver c(base);
+    GroupedWs w;
+    const int64_t n_items = (int64_t)G * B, n_lists = (int64_t)F * B;
+    const int64_t nblk = (n_lists + kScanBlock - 1) / kScanBlock;
+    w.counts = c.take<int64_t>(2);
+    w.counts_g = c.take<int64_t>(2);
+    w.table = c.take<uint64_t>((size_t)G * table_cap(B));
+    w.slot_of = c.take<int32_t>(n_items);
+    w.rep_g = c.take<int32_t>(n_items);
+    w.number_g = c.take<int32_t>(n_items);
+    w.src_g = c.take<int32_t>(n_items);
+    w.src_of = c.take<int32_t>(n_lists);
+    w.group_off = c.take<int32_t>(G + 1);
+    w.feat_group = c.take<int32_t>(F + 1);
+    w.zero_off = c.take<int64_t>(n_items + 1);
+    w.u_tmp = c.take<int64_t>(n_items + 1);
+    w.bs_cnt = c.take<int64_t>(nblk + 1);
+    w.bs_len = c.take<int64_t>(nblk + 1);
+    w.bs_head = c.take<int64_t>(nblk + 1);
+    *bytes = c.off;
+    return w;
+}
+} // namespace
+
+extern "C" recd_status recd_build_ikjt_grouped(recd_ctx *ctx, int F, int64_t B, int64_t N, int G,
+                                               const int32_t *group_off, const int64_t *values,
+                                               const int64_t *offsets, int64_t *u_values,
+                                               int64_t *u_offsets, int32_t *inverse_g,
+                                               int64_t *group_uoff, int64_t *feat_uoff,
+                                               int32_t *inverse_per_feature, int64_t *host_counts)
+{
+    if (!ctx)
+        return RECD_EINVAL;
+    if (F < 0 || F > RECD_MAX_FEATURES || B < 0 || N < 0 || G < 0 || G > F)
+        return recd_fail(ctx, RECD_EINVAL, "bad sizes F=%d B=%lld N=%lld G=%d", F, (long long)B,
+                         (long long)N, G);
+    if (!group_off || group_off[0] != 0 || group_off[G] != F)
+        return recd_fail(ctx, RECD_EINVAL, "group_off must run from 0 to F");
+    for (int g = 0; g < G; g++)
+        if (group_off[g + 1] <= group_off[g])
+            return recd_fail(ctx, RECD_EINVAL, "group %d is empty or group_off decreases", g);
+    const int64_t n_lists = (int64_t)F * B, n_items = (int64_t)G * B;
+    if (n_lists >= (int64_t)1 << 31 || B >= (int64_t)1 << 30)
+        return recd_fail(ctx, RECD_EINVAL, "F*B must stay below 2^31");
+    if (!u_offsets || !feat_uoff || !group_uoff || (n_lists > 0 && (!offsets || !inverse_g)) ||
+        (N > 0 && (!values || !u_values)))
+        return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
+    RECD_HIP(ctx, hipSetDevice(ctx->device));
+    if (ctx->validate && n_lists > 0)
+        RECD_TRY(recd_validate_kjt_offsets(ctx, F, B, N, offsets));
+
+    size_t bytes = 0;
+    carve_grouped(nullptr, F, G, B, &bytes);
+    RECD_TRY(recd_reserve(ctx, bytes));
+    const GroupedWs w = carve_grouped(ctx->ws, F, G, B, &bytes);
+    hipStream_t st = ctx->stream;
+    if (n_lists == 0) {
+        hipLaunchKernelGGL(k_empty_grouped, dim3(1), dim3(256), 0, st, F, G, u_offsets, feat_uoff,
+                           group_uoff, w.counts, w.counts_g);
+    } else {
+        // group boundaries and the group of every feature, staged through pageable host memory (the
+        // runtime copies it before the call returns)
+        int32_t host_map[2 * RECD_MAX_FEATURES + 2];
+        for (int g = 0; g <= G; g++)
+            host_map[g] = group_off[g];
+        for (int g = 0; g < G; g++)
+            for (int f = group_off[g]; f < group_off[g + 1]; f++)
+                host_map[G + 1 + f] = g;
+        RECD_HIP(ctx, hipMemcpyAsync(w.group_off, host_map, sizeof(int32_t) * (G + 1),
+                                     hipMemcpyHostToDevice, st));
+        RECD_HIP(ctx, hipMemcpyAsync(w.feat_group, host_map + G + 1, sizeof(int32_t) * F,
+                                     hipMemcpyHostToDevice, st));
+        RECD_HIP(ctx, hipStreamSynchronize(st));  // host_map lives on this stack frame
+        constexpr int SG = 8;
+        const uint64_t cap = table_cap(B);
+        const int64_t tab_n = (int64_t)G * (int64_t)cap;
+        const int fill_blocks = (int)((tab_n + 1023) / 1024 < 4096 ? (tab_n + 1023) / 1024 : 4096);
+        hipLaunchKernelGGL(k_fill_u64, dim3(fill_blocks), dim3(256), 0, st, w.table, tab_n, kEmpty);
+        const int zero_blocks = (int)((n_items + 1 + 1023) / 1024 < 4096 ? (n_items + 1 + 1023) / 1024 : 4096);
+        hipLaunchKernelGGL(k_fill_u64, dim3(zero_blocks), dim3(256), 0, st,
+                           reinterpret_cast<uint64_t *>(w.zero_off), n_items + 1, 0ull);
+        const int64_t hblocks = (n_items + (256 / SG) - 1) / (256 / SG);
+        hipLaunchKernelGGL((k_group_hash_insert<SG>), dim3((unsigned)hblocks), dim3(256), 0, st, values,
+                           offsets, B, n_items, w.group_off, w.table, (uint32_t)(cap - 1), w.slot_of,
+                           ctx->weak_hash);
+        // numbering of the slots per group: the list-level kernels with the groups in the role of
+        // features and lists of length zero
+        const int64_t gblk = (n_items + kScanBlock - 1) / kScanBlock;
+        hipLaunchKernelGGL(k_flags, dim3((unsigned)gblk), dim3(kScanBlock), 0, st, w.zero_off, B, n_items,
+                           w.table, (uint32_t)(cap - 1), w.slot_of, w.bs_cnt, w.bs_len, w.bs_head);
+        hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(kScanBlock), 0, st, w.bs_cnt, w.bs_len, w.bs_head,
+                           gblk);
+        hipLaunchKernelGGL(k_number, dim3((unsigned)gblk), dim3(kScanBlock), 0, st, w.zero_off, B, n_items,
+                           G, w.table, (uint32_t)(cap - 1), w.slot_of, w.bs_cnt, w.bs_len, w.bs_head,
+                           w.rep_g, w.number_g, w.src_g, w.u_tmp, group_uoff, w.counts_g);
+        const unsigned inv_blocks = (unsigned)((n_items + 255) / 256);
+        hipLaunchKernelGGL((k_emit<16>), dim3(inv_blocks), dim3(256), 0, st, values, w.zero_off, B, n_items,
+                           w.rep_g, w.number_g, w.src_g, w.u_tmp, w.counts_g, u_values, inverse_g,
+                           inv_blocks);
+        // per feature: which lists are stored, where
+        const int64_t nblk = (n_lists + kScanBlock - 1) / kScanBlock;
+        hipLaunchKernelGGL((k_group_compact<false>), dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets,
+                           B, n_lists, F, w.feat_group, w.rep_g, inverse_g, w.bs_cnt, w.bs_len, w.bs_head,
+                           w.src_of, u_offsets, feat_uoff, inverse_per_feature, w.counts);
+        hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(kScanBlock), 0, st, w.bs_cnt, w.bs_len, w.bs_head,
+                           nblk);
+        hipLaunchKernelGGL((k_group_compact<true>), dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets,
+                           B, n_lists, F, w.feat_group, w.rep_g, inverse_g, w.bs_cnt, w.bs_len, w.bs_head,
+                           w.src_of, u_offsets, feat_uoff, inverse_per_feature, w.counts);
+        int64_t copy_blocks = (n_lists + (256 / 16) - 1) / (256 / 16);
+        if (copy_blocks > (int64_t)ctx->num_cu * 8)
+            copy_blocks = (int64_t)ctx->num_cu * 8;
+        hipLaunchKernelGGL((k_emit<16>), dim3((unsigned)copy_blocks), dim3(256), 0, st, values, offsets, B,
+                           n_lists, w.rep_g, w.number_g, w.src_of, u_offsets, w.counts, u_values,
+                           inverse_g, 0u);
+    }
+    RECD_HIP(ctx, hipGetLastError());
+    if (host_counts) {
+        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, w.counts, 2 * sizeof(int64_t),
+                                     hipMemcpyDeviceToHost, st));
+        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned + 2, w.counts_g, sizeof(int64_t),
+                                     hipMemcpyDeviceToHost, st));
+        RECD_HIP(ctx, hipStreamSynchronize(st));
+        host_counts[0] = ctx->host_pinned[0];
+        host_counts[1] = ctx->host_pinned[1];
+        host_counts[2] = ctx->host_pinned[2];
     }
     return RECD_OK;
 }

@@ -455,6 +455,46 @@ __global__ __launch_bounds__(kBlock) void k_expand(const u32x4 *__restrict__ poo
     }
 }
 
+// ---- a compute module on a grouped IKJT: element-wise sum over the features of a group ----------
+// combined[group_uoff[g] + k, :] = sum over f in group g, feature order, of pooled[feat_uoff[f] + k, :]
+// (fp32 accumulation, rounded once).  Thread = one 16-byte piece of one unique row of a group.
+template <int TT>
+__global__ __launch_bounds__(kBlock) void k_group_sum(const uint4 *__restrict__ pooled,
+                                                      const int64_t *__restrict__ feat_uoff,
+                                                      const int64_t *__restrict__ group_uoff,
+                                                      const int32_t *__restrict__ group_off, int G,
+                                                      int vecs, int64_t max_rows, void *__restrict__ out)
+{
+    __shared__ int64_t gu_s[RECD_MAX_FEATURES + 1];
+    __shared__ int32_t go_s[RECD_MAX_FEATURES + 1];
+    for (int i = threadIdx.x; i <= G; i += kBlock) {
+        gu_s[i] = group_uoff[i];
+        go_s[i] = group_off[i];
+    }
+    __syncthreads();
+    const int rows_per_block = kBlock / vecs;
+    const int piece = threadIdx.x % vecs, sub = threadIdx.x / vecs;
+    if (sub >= rows_per_block)
+        return;
+    int64_t total = gu_s[G];
+    if (total > max_rows)
+        total = max_rows;
+    constexpr int EPV = Elem<TT>::per_vec;
+    for (int64_t r = (int64_t)blockIdx.x * rows_per_block + sub; r < total;
+         r += (int64_t)gridDim.x * rows_per_block) {
+        int g = 0;  // the last group with gu_s[g] <= r; r < gu_s[G], so it is not empty
+#pragma unroll
+        for (int s = RECD_MAX_FEATURES / 2; s >= 1; s >>= 1)
+            if (g + s < G && gu_s[g + s] <= r)
+                g += s;
+        const int64_t k = r - gu_s[g];
+        float acc[EPV] = {};
+        for (int f = go_s[g]; f < go_s[g + 1]; f++)
+            accumulate<TT>(acc, pooled[(feat_uoff[f] + k) * vecs + piece]);
+        store_row_piece<TT, EPV, false>(static_cast<char *>(out) + (r * vecs + piece) * 16, acc);
+    }
+}
+
 // ---- validation --------------------------------------------------------------------------------
 // err[0] |= 1: offsets malformed, |= 2: id out of range
 __global__ void k_validate_offsets(const int64_t *offsets, int64_t n_lists, int64_t N, int *err)
@@ -778,6 +818,51 @@ recd_status recd_expand_inverse(recd_ctx *ctx, int F, int64_t B, int D, recd_dty
         hipLaunchKernelGGL(k_expand<false>, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
                            static_cast<const u32x4 *>(pooled), feat_uoff, inverse,
                            static_cast<u32x4 *>(out), (uint32_t)B, (uint32_t)n_rows, vecs);
+    RECD_HIP(ctx, hipGetLastError());
+    return RECD_OK;
+}
+
+recd_status recd_group_sum_unique(recd_ctx *ctx, int F, int G, int D, recd_dtype dt,
+                                  const int32_t *group_off, const void *pooled,
+                                  const int64_t *feat_uoff, const int64_t *group_uoff,
+                                  int64_t max_rows, void *combined)
+{
+    RECD_TRY(check_lookup_shape(ctx, F, D, dt, dt));
+    if (G < 0 || G > F || max_rows < 0)
+        return recd_fail(ctx, RECD_EINVAL, "bad sizes G=%d max_rows=%lld", G, (long long)max_rows);
+    if (!group_off || group_off[0] != 0 || group_off[G] != F)
+        return recd_fail(ctx, RECD_EINVAL, "group_off must run from 0 to F");
+    for (int g = 0; g < G; g++)
+        if (group_off[g + 1] <= group_off[g])
+            return recd_fail(ctx, RECD_EINVAL, "group %d is empty or group_off decreases", g);
+    if (G == 0 || max_rows == 0)
+        return RECD_OK;
+    if (!pooled || !feat_uoff || !group_uoff || !combined)
+        return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
+    RECD_HIP(ctx, hipSetDevice(ctx->device));
+    RECD_TRY(recd_reserve(ctx, 256 + sizeof(int32_t) * (RECD_MAX_FEATURES + 1)));
+    int32_t *go_dev = reinterpret_cast<int32_t *>(ctx->ws);
+    RECD_HIP(ctx, hipMemcpyAsync(go_dev, group_off, sizeof(int32_t) * (G + 1), hipMemcpyHostToDevice,
+                                 ctx->stream));
+    RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));  // group_off is the caller's memory
+    const int vecs = (int)((size_t)D * elem_size(dt) / 16);
+    if (vecs > kBlock)
+        return recd_fail(ctx, RECD_EINVAL, "row too long");
+    const int64_t rows_per_block = kBlock / vecs;
+    int64_t blocks = (max_rows + rows_per_block - 1) / rows_per_block;
+    if (blocks > (int64_t)ctx->num_cu * 32)
+        blocks = (int64_t)ctx->num_cu * 32;
+#define RECD_GS(TT)                                                                              \
+    hipLaunchKernelGGL((k_group_sum<TT>), dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,  \
+                       static_cast<const uint4 *>(pooled), feat_uoff, group_uoff, go_dev, G, vecs, \
+                       max_rows, combined)
+    if (dt == RECD_F32)
+        RECD_GS(RECD_F32);
+    else if (dt == RECD_F16)
+        RECD_GS(RECD_F16);
+    else
+        RECD_GS(RECD_BF16);
+#undef RECD_GS
     RECD_HIP(ctx, hipGetLastError());
     return RECD_OK;
 }

@@ -31,7 +31,8 @@ EXPORTED = [
     "recd_create", "recd_destroy", "recd_set_option", "recd_last_error", "recd_status_string",
     "recd_workspace_bytes", "recd_build_ikjt", "recd_pooled_lookup_unique", "recd_expand_inverse",
     "recd_kjt_pooled_lookup", "recd_backward_dedup", "recd_sequence_lookup_unique",
-    "recd_jagged_expand_inverse", "recd_kjt_sequence_lookup",
+    "recd_jagged_expand_inverse", "recd_kjt_sequence_lookup", "recd_build_ikjt_grouped",
+    "recd_group_sum_unique",
 ]
 
 _vp = C.c_void_p
@@ -58,6 +59,10 @@ _lib.recd_jagged_expand_inverse.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, 
                                             C.c_int64, _vp, _vp, _vp, _vp, _vp]
 _lib.recd_kjt_sequence_lookup.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, C.c_int,
                                           _vp, _vp, _vp, _vp, _vp]
+_lib.recd_build_ikjt_grouped.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, C.c_int, _vp, _vp, _vp, _vp, _vp,
+                                         _vp, _vp, _vp, _vp, _vp]
+_lib.recd_group_sum_unique.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, _vp,
+                                       C.c_int64, _vp]
 for _n in EXPORTED:
     if _n not in ("recd_last_error", "recd_status_string"):
         getattr(_lib, _n).restype = C.c_int
@@ -193,3 +198,24 @@ class Context:
         self._check(_lib.recd_kjt_sequence_lookup(
             self._h, F, B, values.numel(), D, tdt, _DT[out.dtype], self._table_array(tables),
             self._rows_array(tables), _ptr(values), _ptr(offsets), _ptr(out)))
+
+    # -- grouped IKJTs --------------------------------------------------------------------------
+    def build_ikjt_grouped(self, F: int, B: int, group_off: Sequence[int], values, offsets, u_values,
+                           u_offsets, inverse_g, group_uoff, feat_uoff, inverse_per_feature=None,
+                           want_counts: bool = False):
+        G = len(group_off) - 1
+        goff = (C.c_int32 * (G + 1))(*group_off)
+        host = (C.c_int64 * 3)(0, 0, 0) if want_counts else None
+        self._check(_lib.recd_build_ikjt_grouped(
+            self._h, F, B, values.numel(), G, goff, _ptr(values), _ptr(offsets), _ptr(u_values),
+            _ptr(u_offsets), _ptr(inverse_g), _ptr(group_uoff), _ptr(feat_uoff),
+            _ptr(inverse_per_feature), host))
+        return (int(host[0]), int(host[1]), int(host[2])) if want_counts else None
+
+    def group_sum_unique(self, F: int, group_off: Sequence[int], pooled, feat_uoff, group_uoff, combined):
+        G = len(group_off) - 1
+        goff = (C.c_int32 * (G + 1))(*group_off)
+        assert combined.dtype == pooled.dtype
+        self._check(_lib.recd_group_sum_unique(
+            self._h, F, G, pooled.shape[-1], _DT[pooled.dtype], goff, _ptr(pooled), _ptr(feat_uoff),
+            _ptr(group_uoff), combined.shape[0], _ptr(combined)))
