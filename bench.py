@@ -43,6 +43,10 @@ def parse_args():
     ap.add_argument("--sequence", action="store_true",
                     help="also time the unpooled path (sequence lookup on the unique lists + jagged expand) "
                          "and its non-deduplicated comparison; reported beside the step, not part of it")
+    ap.add_argument("--groups", type=int, default=0,
+                    help="also time the grouped IKJT path with groups of this many consecutive features "
+                         "(builder, group-sum module on the unique rows, one expand per group) beside the "
+                         "same module run on the expanded KJT rows")
     ap.add_argument("--tune", type=int, default=0, help="RECD_OPT_TUNE_SEGSUM value (0 = automatic)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates hardware byte counters)")
@@ -237,7 +241,62 @@ def run_workload(torch, recd, synth, w, args, need_backward, detail=True):
     res["predicted_speedup_bytes_model"] = kjt_upper / (look_upper + F * B * 4 + 2 * F * B * D * o)
     if getattr(args, "sequence", False):
         res["sequence"] = sequence_regions(torch, P, cnt, timed, reps, R)
+    if getattr(args, "groups", 0) > 0:
+        res["grouped"] = grouped_regions(torch, P, timed, reps, args.groups)
     return res, P
+
+
+def grouped_regions(torch, P, timed, reps, k):
+    """Grouped IKJTs: features in groups of k share one inverse.  Times the grouped builder, the
+    element-wise sum over a group's features on the unique rows and the single expand per group;
+    beside them the same sum on the expanded [F,B,D] rows (the module run without deduplication)."""
+    w = P.w
+    F, B, D = w.F, w.B, w.D
+    groups = list(range(0, F, k)) + [F]
+    G = len(groups) - 1
+    nb = len(P.batches)
+    inv_g = [torch.zeros(G * B, dtype=torch.int32, device="cuda") for _ in range(nb)]
+    g_uoff = [torch.zeros(G + 1, dtype=torch.int64, device="cuda") for _ in range(nb)]
+    inv_f = torch.zeros(F * B, dtype=torch.int32, device="cuda")
+    comb = torch.zeros(G * B, D, dtype=P.tdt, device="cuda")
+    gout = torch.zeros(G, B, D, dtype=P.tdt, device="cuda")
+    ident_f = torch.arange(F + 1, dtype=torch.int64, device="cuda") * B
+    ident_g = torch.arange(G + 1, dtype=torch.int64, device="cuda") * B
+
+    def build(i, counts=False):
+        return P.ctx.build_ikjt_grouped(F, B, groups, P.values[i], P.offsets[i], P.u_values[i], P.u_offsets[i],
+                                        inv_g[i], g_uoff[i], P.feat_uoff[i], inv_f, want_counts=counts)
+
+    cnt = [build(i, True) for i in range(nb)]  # the per-batch IKJTs are now the grouped ones
+
+    def lookup(i):
+        P.ctx.pooled_lookup_unique(P.tables, P.u_values[i], P.u_offsets[i], P.feat_uoff[i], cnt[i][0], P.pooled)
+
+    def gsum(i):
+        P.ctx.group_sum_unique(F, groups, P.pooled, P.feat_uoff[i], g_uoff[i], comb)
+
+    def gexpand(i):
+        P.ctx.expand_inverse(G, B, comb, g_uoff[i], inv_g[i], gout)
+
+    def kjt_sum(i):  # the same module on the expanded rows: every "slot" is a sample
+        P.ctx.group_sum_unique(F, groups, P.out.view(F * B, D), ident_f, ident_g, comb)
+
+    t = {n: [] for n in ("build", "lookup", "gsum", "gexpand", "kjt_sum")}
+    for _ in range(max(reps // 2, 2)):
+        t["build"].append(timed(build))
+        t["lookup"].append(timed(lookup))
+        t["gsum"].append(timed(gsum))
+        t["gexpand"].append(timed(gexpand))
+        t["kjt_sum"].append(timed(kjt_sum))
+    ms = {n: float(np.mean(v)) for n, v in t.items()}
+    for i in range(nb):   # leave the ungrouped IKJTs behind, as the other regions expect them
+        P.build(i)
+    return {"features_per_group": k, "G": G, "build_grouped_ms": ms["build"],
+            "lookup_unique_ms": ms["lookup"], "group_sum_unique_ms": ms["gsum"],
+            "expand_groups_ms": ms["gexpand"], "group_sum_on_kjt_rows_ms": ms["kjt_sum"],
+            "U_lists": float(np.mean([c[0] for c in cnt])), "M": float(np.mean([c[1] for c in cnt])),
+            "U_groups": float(np.mean([c[2] for c in cnt])),
+            "module_speedup": ms["kjt_sum"] / (ms["gsum"] + ms["gexpand"])}
 
 
 def sequence_regions(torch, P, cnt, timed, reps, R):

@@ -196,3 +196,50 @@ def test_cfg3_sequence_full_fp16(recd):
 
 def test_cfg5_sequence_full(recd):
     _run_sequence(recd, synth.WORKLOADS["cfg5"], 2, sample_features=(0, 33, 63))
+
+
+def test_cfg5_grouped_full(recd):
+    """Configuration 5 with its 64 features in 8 groups of 8: integers against the oracle in full, the
+    group-sum module expanded through the shared inverse against the oracle on sampled groups."""
+    w = synth.WORKLOADS["cfg5"]
+    F, B, D = w.F, w.B, w.D
+    groups = list(range(0, F + 1, 8))
+    G = len(groups) - 1
+    batch = synth.make_batch(w, 3)
+    tabs = _device_tables(w, torch.float32)
+    ctx = recd.Context(0)
+    values, offsets = gu.to_dev(batch.values), gu.to_dev(batch.offsets)
+    u_values = torch.zeros(batch.N, dtype=torch.int64, device="cuda")
+    u_offsets = torch.zeros(F * B + 1, dtype=torch.int64, device="cuda")
+    inverse_g = torch.zeros(G * B, dtype=torch.int32, device="cuda")
+    group_uoff = torch.zeros(G + 1, dtype=torch.int64, device="cuda")
+    feat_uoff = torch.zeros(F + 1, dtype=torch.int64, device="cuda")
+    inverse_f = torch.zeros(F * B, dtype=torch.int32, device="cuda")
+    U, M, UG = ctx.build_ikjt_grouped(F, B, groups, values, offsets, u_values, u_offsets, inverse_g,
+                                      group_uoff, feat_uoff, inverse_f, want_counts=True)
+    uv, uo, inv_g, gu_, fu = orc.build_ikjt_grouped(F, B, groups, batch.values, batch.offsets)
+    assert (U, M, UG) == (int(fu[-1]), len(uv), int(gu_[-1]))
+    assert np.array_equal(u_values[:M].cpu().numpy(), uv)
+    assert np.array_equal(u_offsets[:U + 1].cpu().numpy(), uo)
+    assert np.array_equal(inverse_g.cpu().numpy(), inv_g)
+    assert np.array_equal(group_uoff.cpu().numpy(), gu_) and np.array_equal(feat_uoff.cpu().numpy(), fu)
+    assert torch.equal(inverse_f.view(G, 8, B), inverse_g.view(G, 1, B).expand(G, 8, B))
+    pooled = torch.zeros(U, D, device="cuda")
+    ctx.pooled_lookup_unique(tabs, u_values, u_offsets, feat_uoff, U, pooled)
+    out = torch.zeros(F, B, D, device="cuda")
+    kjt = torch.zeros(F, B, D, device="cuda")
+    ctx.expand_inverse(F, B, pooled, feat_uoff, inverse_f, out)
+    ctx.kjt_pooled_lookup(tabs, B, values, offsets, kjt)
+    assert torch.equal(out, kjt)
+    comb = torch.zeros(UG, D, device="cuda")
+    ctx.group_sum_unique(F, groups, pooled, feat_uoff, group_uoff, comb)
+    gout = torch.zeros(G, B, D, device="cuda")
+    ctx.expand_inverse(G, B, comb, group_uoff, inverse_g, gout)
+    torch.cuda.synchronize()
+    for g in (0, 5):
+        ref = np.zeros((B, D))
+        for f in range(groups[g], groups[g + 1]):
+            v_f, o_f = _feature_slice(batch, f)
+            ref += orc.kjt_pooled_lookup([_host_table(tabs[f], "f32")], "f32", B, v_f, o_f)[0]
+        gu.assert_close_f32(gu.out_to_f64(gout[g]), ref, f"group {g} sum")
+    ctx.close()
