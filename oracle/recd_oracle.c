@@ -227,6 +227,43 @@ int oracle_pooled_lookup(int F, int D, int dtype, const void *const *tables, con
     return 0;
 }
 
+/* ---- the other pooling functions (Sec. 2.2: "average, sum, or max") --------------------------
+ * mode 0 = sum (as oracle_pooled_lookup), 1 = average: the sum divided by the number of ids of the
+ * list, 2 = max: element-wise maximum over the list's rows.  An empty list pools to the zero
+ * vector in every mode (the convention of the library routine the tests compare with).
+ */
+int oracle_pooled_lookup_mode(int mode, int F, int D, int dtype, const void *const *tables,
+                              const int64_t *rows, const int64_t *values, const int64_t *offsets,
+                              const int64_t *list_off, double *out)
+{
+    if (mode < 0 || mode > 2)
+        return -10;
+    for (int f = 0; f < F; f++) {
+        for (int64_t l = list_off[f]; l < list_off[f + 1]; l++) {
+            double *o = out + l * D;
+            const int64_t len = offsets[l + 1] - offsets[l];
+            for (int d = 0; d < D; d++)
+                o[d] = 0.0;
+            for (int64_t j = offsets[l]; j < offsets[l + 1]; j++) {
+                int64_t id = values[j];
+                if (id < 0 || id >= rows[f])
+                    return -4;
+                for (int d = 0; d < D; d++) {
+                    const double x = elem(tables[f], dtype, id * D + d);
+                    if (mode == 2)
+                        o[d] = (j == offsets[l] || x > o[d]) ? x : o[d];
+                    else
+                        o[d] += x;
+                }
+            }
+            if (mode == 1 && len > 0)
+                for (int d = 0; d < D; d++)
+                    o[d] /= (double)len;
+        }
+    }
+    return 0;
+}
+
 /* ---- a compute module on a grouped IKJT (Sec. 5 "Deduplicated Pooling": the element-wise sum
  * over the features of a group, computed once per unique row) ----------------------------------
  * combined[group_uoff[g] + k, :] = sum over the features f of group g, in feature order, of

@@ -136,6 +136,27 @@ def pooled_lookup(tables: Sequence[np.ndarray], dtype: str, values, offsets, lis
     return out[:L]
 
 
+POOLING = {"sum": 0, "mean": 1, "max": 2}
+
+
+def pooled_lookup_mode(mode: str, tables: Sequence[np.ndarray], dtype: str, values, offsets, list_off) -> np.ndarray:
+    """Pooled lookup with the pooling function `mode` in {"sum", "mean", "max"} (Sec. 2.2); an empty
+    list pools to zero.  Same arguments and result layout as pooled_lookup."""
+    F = len(tables)
+    values, offsets, list_off = _i64(values), _i64(offsets), _i64(list_off)
+    D = int(tables[0].shape[1]) if F else 1
+    rows = _i64([t.shape[0] for t in tables])
+    L = int(list_off[F]) if F else 0
+    out = np.zeros((max(L, 1), D), dtype=np.float64)
+    ptrs, keep = _table_ptrs(tables, dtype)
+    rc = _lib.oracle_pooled_lookup_mode(C.c_int(POOLING[mode]), C.c_int(F), C.c_int(D), C.c_int(DTYPES[dtype]),
+                                        ptrs, _p(rows, _i64p), _p(values, _i64p), _p(offsets, _i64p),
+                                        _p(list_off, _i64p), _p(out, _f64p))
+    _check(rc, "pooled_lookup_mode")
+    del keep
+    return out[:L]
+
+
 def kjt_pooled_lookup(tables, dtype: str, B: int, values, offsets) -> np.ndarray:
     """Non-deduplicated lookup over every row of the batch. float64 [F, B, D]."""
     F = len(tables)

@@ -214,6 +214,36 @@ def test_lookup_matches_embedding_bag(dtype):
         np.testing.assert_allclose(got[f], ref, rtol=1e-13, atol=1e-13)
 
 
+@pytest.mark.parametrize("mode", ["sum", "mean", "max"])
+@pytest.mark.parametrize("dtype", ["f32", "f16"])
+def test_pooling_modes_match_embedding_bag(mode, dtype):
+    batch, tabs = _rand_problem(11, dtype=dtype)
+    lo_ = np.arange(batch.F + 1, dtype=np.int64) * batch.B
+    got = orc.pooled_lookup_mode(mode, tabs, dtype, batch.values, batch.offsets, lo_).reshape(batch.F, batch.B, -1)
+    if mode == "sum":
+        assert np.array_equal(got, orc.kjt_pooled_lookup(tabs, dtype, batch.B, batch.values, batch.offsets))
+    t64 = _tables_as_f64(tabs, dtype)
+    for f in range(batch.F):
+        lo, hi = batch.offsets[f * batch.B], batch.offsets[(f + 1) * batch.B]
+        ids = torch.from_numpy(batch.values[lo:hi])
+        offs = torch.from_numpy(batch.offsets[f * batch.B:(f + 1) * batch.B] - lo)
+        ref = torch.nn.functional.embedding_bag(ids, t64[f], offs, mode=mode).numpy()
+        np.testing.assert_allclose(got[f], ref, rtol=1e-13, atol=1e-13)
+
+
+def test_pooling_modes_special_cases():
+    W = np.array([[1.0, -5.0], [-2.0, -1.0], [4.0, -3.0]], dtype=np.float32)
+    batch = synth.batch_from_lists([[[0, 1, 2], [1, 1], [], [2]]])
+    lo = np.array([0, 4], dtype=np.int64)
+    mean = orc.pooled_lookup_mode("mean", [W], "f32", batch.values, batch.offsets, lo)
+    mx = orc.pooled_lookup_mode("max", [W], "f32", batch.values, batch.offsets, lo)
+    assert np.allclose(mean, [[1.0, -3.0], [-2.0, -1.0], [0.0, 0.0], [4.0, -3.0]], atol=1e-15)
+    # the maximum of all-negative entries stays negative (no zero leaks in); empty pools to zero
+    assert np.array_equal(mx, [[4.0, -1.0], [-2.0, -1.0], [0.0, 0.0], [4.0, -3.0]])
+    with pytest.raises(KeyError):
+        orc.pooled_lookup_mode("median", [W], "f32", batch.values, batch.offsets, lo)
+
+
 def test_lookup_special_cases():
     W = np.arange(40, dtype=np.float32).reshape(10, 4)
     # single id: pooled row is the table row; repeated id counts twice; empty list is zero;
