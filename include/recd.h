@@ -69,6 +69,9 @@ typedef enum {
 
 typedef enum { RECD_F32 = 0, RECD_F16 = 1, RECD_BF16 = 2 } recd_dtype;
 
+/* Pooling functions of an embedding bag (Sec. 2.2: "average, sum, or max"). */
+typedef enum { RECD_POOL_SUM = 0, RECD_POOL_MEAN = 1, RECD_POOL_MAX = 2 } recd_pooling;
+
 typedef enum {
     RECD_OPT_VALIDATE = 1,  /* value != 0: check preconditions on the device before each operation  */
     RECD_OPT_WEAK_HASH = 2, /* test hook, value != 0: the builder hashes a list to its length only,
@@ -252,6 +255,22 @@ recd_status recd_group_sum_unique(recd_ctx *ctx, int F, int G, int D, recd_dtype
                                   const int32_t *group_off, const void *pooled,
                                   const int64_t *feat_uoff, const int64_t *group_uoff,
                                   int64_t max_rows, void *combined);
+
+/* 11. Calls 2 and 4 with another pooling function (Sec. 2.2 names average, sum and max; forward
+ *    only).  RECD_POOL_SUM is exactly call 2 / call 4.  RECD_POOL_MEAN: the sum (fp32, same order
+ *    of additions) divided by the number of ids of the list.  RECD_POOL_MAX: element-wise maximum
+ *    over the list's rows.  An empty list pools to zero in every mode.  As for the sum, the
+ *    order of operations depends on the list alone, so the expanded result of the deduplicated
+ *    lookup equals the KJT lookup bit for bit.  Arguments as in calls 2 and 4. */
+recd_status recd_pooled_lookup_unique_mode(recd_ctx *ctx, recd_pooling mode, int F, int D,
+                                           recd_dtype table_dt, recd_dtype out_dt,
+                                           const void *const *tables, const int64_t *rows,
+                                           const int64_t *u_values, const int64_t *u_offsets,
+                                           const int64_t *feat_uoff, int64_t max_lists, void *pooled);
+recd_status recd_kjt_pooled_lookup_mode(recd_ctx *ctx, recd_pooling mode, int F, int64_t B, int D,
+                                        recd_dtype table_dt, recd_dtype out_dt,
+                                        const void *const *tables, const int64_t *rows,
+                                        const int64_t *values, const int64_t *offsets, void *out);
 
 #ifdef __cplusplus
 }

@@ -92,6 +92,7 @@ struct SegSumArgs {
     const int64_t *ends;            // optional (single table, flat): list l ends at ends[l] ...
     const int64_t *count_dev;       // ... and the number of lists lives on the device
     int site;                 // RECD_SITE_*: which call site (each has its own kernel instantiation)
+    int mode;                 // recd_pooling (forward sites only; 0 = sum)
     void *out;                // [lists, D]
 };
 recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a);

@@ -54,27 +54,38 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float f)
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
 }
 
-// add the elements of one 16-byte vector into acc[0..per_vec)
-template <int TT> __device__ __forceinline__ void accumulate(float *acc, const uint4 &v)
+// Pooling functions (Sec. 2.2: sum, average, max).  The average is the sum scaled at the end.
+enum { POOL_SUM = 0, POOL_MEAN = 1, POOL_MAX = 2 };
+template <int MODE> __device__ __forceinline__ float pool2(float a, float x)
+{
+    return MODE == POOL_MAX ? fmaxf(a, x) : a + x;
+}
+template <int MODE> __device__ __forceinline__ float pool_identity()
+{
+    return MODE == POOL_MAX ? -INFINITY : 0.f;
+}
+
+// fold the elements of one 16-byte vector into acc[0..per_vec)
+template <int TT, int MODE = POOL_SUM> __device__ __forceinline__ void accumulate(float *acc, const uint4 &v)
 {
     if constexpr (TT == RECD_F32) {
-        acc[0] += __uint_as_float(v.x);
-        acc[1] += __uint_as_float(v.y);
-        acc[2] += __uint_as_float(v.z);
-        acc[3] += __uint_as_float(v.w);
+        acc[0] = pool2<MODE>(acc[0], __uint_as_float(v.x));
+        acc[1] = pool2<MODE>(acc[1], __uint_as_float(v.y));
+        acc[2] = pool2<MODE>(acc[2], __uint_as_float(v.z));
+        acc[3] = pool2<MODE>(acc[3], __uint_as_float(v.w));
     } else if constexpr (TT == RECD_F16) {
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            acc[2 * i] += __half2float(__ushort_as_half((unsigned short)(w[i] & 0xffffu)));
-            acc[2 * i + 1] += __half2float(__ushort_as_half((unsigned short)(w[i] >> 16)));
+            acc[2 * i] = pool2<MODE>(acc[2 * i], __half2float(__ushort_as_half((unsigned short)(w[i] & 0xffffu))));
+            acc[2 * i + 1] = pool2<MODE>(acc[2 * i + 1], __half2float(__ushort_as_half((unsigned short)(w[i] >> 16))));
         }
     } else {
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            acc[2 * i] += bf16_to_f32(w[i] & 0xffffu);
-            acc[2 * i + 1] += bf16_to_f32(w[i] >> 16);
+            acc[2 * i] = pool2<MODE>(acc[2 * i], bf16_to_f32(w[i] & 0xffffu));
+            acc[2 * i + 1] = pool2<MODE>(acc[2 * i + 1], bf16_to_f32(w[i] >> 16));
         }
     }
 }
@@ -147,7 +158,7 @@ struct SegSumParams {
 // ns[] and starts[] are wave-uniform, so every "is this load slot used" test is a scalar branch and
 // unused slots cost nothing; only a chunk's last slot can hold lane groups beyond the end (they
 // fetch row 0, which exists, and are masked out of the add).  Ids are used modulo 2^32.
-template <int LPR, int VPL, int TT, typename IdxT, int NL, int US>
+template <int LPR, int VPL, int TT, typename IdxT, int NL, int US, int MODE = POOL_SUM>
 __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL],
                                            const char *const *bases, const IdxT *values,
                                            const int64_t *starts, const int *ns, uint32_t row_bytes,
@@ -183,12 +194,12 @@ __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL]
                 if (k0 + u * G + G <= ns[j]) {  // scalar test: every lane group holds a real id
 #pragma unroll
                     for (int w = 0; w < VPL; w++)
-                        accumulate<TT>(acc[j] + w * EPV, v[j][u][w]);
+                        accumulate<TT, MODE>(acc[j] + w * EPV, v[j][u][w]);
                 } else if (k0 + u * G < ns[j]) {
                     if (k0 + u * G + g < ns[j]) {
 #pragma unroll
                         for (int w = 0; w < VPL; w++)
-                            accumulate<TT>(acc[j] + w * EPV, v[j][u][w]);
+                            accumulate<TT, MODE>(acc[j] + w * EPV, v[j][u][w]);
                     }
                 }
             }
@@ -197,7 +208,7 @@ __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL]
 
 // Occupancy target: 7 waves per SIMD (71 VGPRs) measured best for one-vector-per-lane rows; more
 // loads in flight per wave at lower occupancy, or fewer at 8 waves, were both slower.
-template <int LPR, int VPL, int TT, int OT, typename IdxT, int SITE>
+template <int LPR, int VPL, int TT, int OT, typename IdxT, int SITE, int MODE = POOL_SUM>
 __global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VPL == 1 ? 7 : 1)))
 void k_segsum(const SegSumParams p)
 {
@@ -269,11 +280,17 @@ void k_segsum(const SegSumParams p)
         for (int s = LPR; s < 64; s <<= 1)
 #pragma unroll
             for (int i = 0; i < NACC; i++)
-                acc[i] += __shfl_xor(acc[i], s);
+                acc[i] = pool2<MODE>(acc[i], __shfl_xor(acc[i], s));
     };
 
     // A finished row: lanes of group 0 hold its NACC-element pieces in vals.
-    auto finish_row = [&](int j, const float *vals) {
+    auto finish_row = [&](int j, float *vals) {
+        if (MODE != POOL_SUM) {
+            const int64_t len = s_end[j] - s_start[j];
+#pragma unroll
+            for (int i = 0; i < NACC; i++)
+                vals[i] = len == 0 ? 0.f : (MODE == POOL_MEAN ? vals[i] / (float)len : vals[i]);
+        }
         if (g == 0 && piece_ok) {
             char *dst = static_cast<char *>(p.out) + s_list[j] * out_row_bytes;
 #pragma unroll
@@ -317,10 +334,10 @@ void k_segsum(const SegSumParams p)
                 float acc[1][NACC];
 #pragma unroll
                 for (int i = 0; i < NACC; i++)
-                    acc[0][i] = 0.f;
+                    acc[0][i] = pool_identity<MODE>();
                 for (int64_t base = start + (int64_t)wv * kChunk; base < end; base += kWaves * kChunk) {
                     const int n = (int)(end - base < kChunk ? end - base : kChunk);
-                    add_chunks<LPR, VPL, TT, IdxT, 1, UNR>(acc, &table, values, &base, &n, row_bytes, lane, g);
+                    add_chunks<LPR, VPL, TT, IdxT, 1, UNR, MODE>(acc, &table, values, &base, &n, row_bytes, lane, g);
                 }
                 fold_groups(acc[0]);
                 if (g == 0) {
@@ -344,7 +361,7 @@ void k_segsum(const SegSumParams p)
                             float t_ = s_part[e][0][x];
 #pragma unroll
                             for (int w2 = 1; w2 < kWaves; w2++)
-                                t_ += s_part[e][w2][x];  // wave order
+                                t_ = pool2<MODE>(t_, s_part[e][w2][x]);  // wave order
                             tot[w * EPV + i] = t_;
                         }
                     finish_row(batch[e], tot);
@@ -365,41 +382,41 @@ void k_segsum(const SegSumParams p)
             float acc[1][NACC];
 #pragma unroll
             for (int i = 0; i < NACC; i++)
-                acc[0][i] = 0.f;
-            add_chunks<LPR, VPL, TT, IdxT, 1, UNR>(acc, &table, values, &start, &n, row_bytes, lane, g);
+                acc[0][i] = pool_identity<MODE>();
+            add_chunks<LPR, VPL, TT, IdxT, 1, UNR, MODE>(acc, &table, values, &start, &n, row_bytes, lane, g);
             fold_groups(acc[0]);
             finish_row(j, acc[0]);
         }
     }
 }
 
-template <int TT, int OT, typename IdxT, int SITE>
+template <int TT, int OT, typename IdxT, int SITE, int MODE = POOL_SUM>
 bool launch_shape(hipStream_t st, int blocks, int vecs, const SegSumParams &p)
 {
     const dim3 grid(blocks), block(kBlock);
-    if (vecs <= 8) hipLaunchKernelGGL((k_segsum<8, 1, TT, OT, IdxT, SITE>), grid, block, 0, st, p);
-    else if (vecs <= 16) hipLaunchKernelGGL((k_segsum<16, 1, TT, OT, IdxT, SITE>), grid, block, 0, st, p);
-    else if (vecs <= 32) hipLaunchKernelGGL((k_segsum<32, 1, TT, OT, IdxT, SITE>), grid, block, 0, st, p);
-    else if (vecs <= 64) hipLaunchKernelGGL((k_segsum<64, 1, TT, OT, IdxT, SITE>), grid, block, 0, st, p);
-    else if (vecs == 128) hipLaunchKernelGGL((k_segsum<64, 2, TT, OT, IdxT, SITE>), grid, block, 0, st, p);
-    else if (vecs == 256) hipLaunchKernelGGL((k_segsum<64, 4, TT, OT, IdxT, SITE>), grid, block, 0, st, p);
+    if (vecs <= 8) hipLaunchKernelGGL((k_segsum<8, 1, TT, OT, IdxT, SITE, MODE>), grid, block, 0, st, p);
+    else if (vecs <= 16) hipLaunchKernelGGL((k_segsum<16, 1, TT, OT, IdxT, SITE, MODE>), grid, block, 0, st, p);
+    else if (vecs <= 32) hipLaunchKernelGGL((k_segsum<32, 1, TT, OT, IdxT, SITE, MODE>), grid, block, 0, st, p);
+    else if (vecs <= 64) hipLaunchKernelGGL((k_segsum<64, 1, TT, OT, IdxT, SITE, MODE>), grid, block, 0, st, p);
+    else if (vecs == 128) hipLaunchKernelGGL((k_segsum<64, 2, TT, OT, IdxT, SITE, MODE>), grid, block, 0, st, p);
+    else if (vecs == 256) hipLaunchKernelGGL((k_segsum<64, 4, TT, OT, IdxT, SITE, MODE>), grid, block, 0, st, p);
     else return false;
     return true;
 }
 
-template <int SITE>
+template <int SITE, int MODE = POOL_SUM>
 bool launch_forward(hipStream_t st, int blocks, int v, const SegSumArgs &a, const SegSumParams &p)
 {
     if (a.table_dt == RECD_F32 && a.out_dt == RECD_F32)
-        return launch_shape<RECD_F32, RECD_F32, int64_t, SITE>(st, blocks, v, p);
+        return launch_shape<RECD_F32, RECD_F32, int64_t, SITE, MODE>(st, blocks, v, p);
     if (a.table_dt == RECD_F16 && a.out_dt == RECD_F16)
-        return launch_shape<RECD_F16, RECD_F16, int64_t, SITE>(st, blocks, v, p);
+        return launch_shape<RECD_F16, RECD_F16, int64_t, SITE, MODE>(st, blocks, v, p);
     if (a.table_dt == RECD_F16 && a.out_dt == RECD_F32)
-        return launch_shape<RECD_F16, RECD_F32, int64_t, SITE>(st, blocks, v, p);
+        return launch_shape<RECD_F16, RECD_F32, int64_t, SITE, MODE>(st, blocks, v, p);
     if (a.table_dt == RECD_BF16 && a.out_dt == RECD_BF16)
-        return launch_shape<RECD_BF16, RECD_BF16, int64_t, SITE>(st, blocks, v, p);
+        return launch_shape<RECD_BF16, RECD_BF16, int64_t, SITE, MODE>(st, blocks, v, p);
     if (a.table_dt == RECD_BF16 && a.out_dt == RECD_F32)
-        return launch_shape<RECD_BF16, RECD_F32, int64_t, SITE>(st, blocks, v, p);
+        return launch_shape<RECD_BF16, RECD_F32, int64_t, SITE, MODE>(st, blocks, v, p);
     return false;
 }
 
@@ -579,12 +596,21 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     bool ok = false;
     hipStream_t st = ctx->stream;
     const int v = p.vecs_per_row;
-    if (a.site == RECD_SITE_UNIQUE && !a.values_are_i32)
+    const bool fwd = !a.values_are_i32;
+    if (a.site == RECD_SITE_UNIQUE && fwd && a.mode == POOL_SUM)
         ok = launch_forward<SITE_UNIQUE>(st, blocks, v, a, p);
-    else if (a.site == RECD_SITE_KJT && !a.values_are_i32)
+    else if (a.site == RECD_SITE_KJT && fwd && a.mode == POOL_SUM)
         ok = launch_forward<SITE_KJT>(st, blocks, v, a, p);
+    else if (a.site == RECD_SITE_UNIQUE && fwd && a.mode == POOL_MEAN)
+        ok = launch_forward<SITE_UNIQUE, POOL_MEAN>(st, blocks, v, a, p);
+    else if (a.site == RECD_SITE_KJT && fwd && a.mode == POOL_MEAN)
+        ok = launch_forward<SITE_KJT, POOL_MEAN>(st, blocks, v, a, p);
+    else if (a.site == RECD_SITE_UNIQUE && fwd && a.mode == POOL_MAX)
+        ok = launch_forward<SITE_UNIQUE, POOL_MAX>(st, blocks, v, a, p);
+    else if (a.site == RECD_SITE_KJT && fwd && a.mode == POOL_MAX)
+        ok = launch_forward<SITE_KJT, POOL_MAX>(st, blocks, v, a, p);
     else if (a.site == RECD_SITE_GRAD_LISTS && a.values_are_i32 && a.table_dt == RECD_F32 &&
-             a.out_dt == RECD_F32)
+             a.out_dt == RECD_F32 && a.mode == POOL_SUM)
         ok = launch_shape<RECD_F32, RECD_F32, int32_t, SITE_GRAD_LISTS>(st, blocks, v, p);
     if (!ok)
         return recd_fail(ctx, RECD_EINVAL, "unsupported row shape: D=%d table dtype %d out dtype %d",
@@ -704,15 +730,14 @@ recd_status recd_validate_unique_lists(recd_ctx *ctx, int F, const int64_t *rows
     return validate_lists(ctx, F, rows, u_values, u_offsets, feat_uoff, 0, U, -1);
 }
 
-extern "C" {
-
-recd_status recd_pooled_lookup_unique(recd_ctx *ctx, int F, int D, recd_dtype table_dt,
-                                      recd_dtype out_dt, const void *const *tables,
-                                      const int64_t *rows, const int64_t *u_values,
-                                      const int64_t *u_offsets, const int64_t *feat_uoff,
-                                      int64_t max_lists, void *pooled)
+static recd_status lookup_unique(recd_ctx *ctx, int mode, int F, int D, recd_dtype table_dt,
+                                 recd_dtype out_dt, const void *const *tables, const int64_t *rows,
+                                 const int64_t *u_values, const int64_t *u_offsets,
+                                 const int64_t *feat_uoff, int64_t max_lists, void *pooled)
 {
     RECD_TRY(check_lookup_shape(ctx, F, D, table_dt, out_dt));
+    if (mode < 0 || mode > 2)
+        return recd_fail(ctx, RECD_EINVAL, "unknown pooling mode %d", mode);
     if (max_lists < 0)
         return recd_fail(ctx, RECD_EINVAL, "max_lists < 0");
     if (F == 0 || max_lists == 0)
@@ -739,18 +764,20 @@ recd_status recd_pooled_lookup_unique(recd_ctx *ctx, int F, int D, recd_dtype ta
         a.list_off = feat_uoff + f0;
         a.lists_bound = max_lists;
         a.site = RECD_SITE_UNIQUE;
+        a.mode = mode;
         a.out = pooled;
         RECD_TRY(recd_launch_segsum(ctx, a));
     }
     return RECD_OK;
 }
 
-recd_status recd_kjt_pooled_lookup(recd_ctx *ctx, int F, int64_t B, int D, recd_dtype table_dt,
-                                   recd_dtype out_dt, const void *const *tables,
-                                   const int64_t *rows, const int64_t *values,
-                                   const int64_t *offsets, void *out)
+static recd_status lookup_kjt(recd_ctx *ctx, int mode, int F, int64_t B, int D, recd_dtype table_dt,
+                              recd_dtype out_dt, const void *const *tables, const int64_t *rows,
+                              const int64_t *values, const int64_t *offsets, void *out)
 {
     RECD_TRY(check_lookup_shape(ctx, F, D, table_dt, out_dt));
+    if (mode < 0 || mode > 2)
+        return recd_fail(ctx, RECD_EINVAL, "unknown pooling mode %d", mode);
     if (B < 0)
         return recd_fail(ctx, RECD_EINVAL, "B < 0");
     if (F == 0 || B == 0)
@@ -782,10 +809,49 @@ recd_status recd_kjt_pooled_lookup(recd_ctx *ctx, int F, int64_t B, int D, recd_
         a.list_base = (int64_t)f0 * B;
         a.lists_bound = (int64_t)a.F * B;
         a.site = RECD_SITE_KJT;
+        a.mode = mode;
         a.out = out;
         RECD_TRY(recd_launch_segsum(ctx, a));
     }
     return RECD_OK;
+}
+
+extern "C" {
+
+recd_status recd_pooled_lookup_unique(recd_ctx *ctx, int F, int D, recd_dtype table_dt,
+                                      recd_dtype out_dt, const void *const *tables,
+                                      const int64_t *rows, const int64_t *u_values,
+                                      const int64_t *u_offsets, const int64_t *feat_uoff,
+                                      int64_t max_lists, void *pooled)
+{
+    return lookup_unique(ctx, RECD_POOL_SUM, F, D, table_dt, out_dt, tables, rows, u_values, u_offsets,
+                         feat_uoff, max_lists, pooled);
+}
+
+recd_status recd_kjt_pooled_lookup(recd_ctx *ctx, int F, int64_t B, int D, recd_dtype table_dt,
+                                   recd_dtype out_dt, const void *const *tables,
+                                   const int64_t *rows, const int64_t *values,
+                                   const int64_t *offsets, void *out)
+{
+    return lookup_kjt(ctx, RECD_POOL_SUM, F, B, D, table_dt, out_dt, tables, rows, values, offsets, out);
+}
+
+recd_status recd_pooled_lookup_unique_mode(recd_ctx *ctx, recd_pooling mode, int F, int D,
+                                           recd_dtype table_dt, recd_dtype out_dt,
+                                           const void *const *tables, const int64_t *rows,
+                                           const int64_t *u_values, const int64_t *u_offsets,
+                                           const int64_t *feat_uoff, int64_t max_lists, void *pooled)
+{
+    return lookup_unique(ctx, (int)mode, F, D, table_dt, out_dt, tables, rows, u_values, u_offsets,
+                         feat_uoff, max_lists, pooled);
+}
+
+recd_status recd_kjt_pooled_lookup_mode(recd_ctx *ctx, recd_pooling mode, int F, int64_t B, int D,
+                                        recd_dtype table_dt, recd_dtype out_dt,
+                                        const void *const *tables, const int64_t *rows,
+                                        const int64_t *values, const int64_t *offsets, void *out)
+{
+    return lookup_kjt(ctx, (int)mode, F, B, D, table_dt, out_dt, tables, rows, values, offsets, out);
 }
 
 recd_status recd_expand_inverse(recd_ctx *ctx, int F, int64_t B, int D, recd_dtype dt,

@@ -26,13 +26,15 @@ RECD_OK = 0
 RECD_EINVAL, RECD_ENOMEM, RECD_EHIP, RECD_EBOUNDS, RECD_ECAPACITY = -1, -2, -3, -4, -5
 RECD_F32, RECD_F16, RECD_BF16 = 0, 1, 2
 RECD_OPT_VALIDATE, RECD_OPT_WEAK_HASH, RECD_OPT_TUNE_SEGSUM = 1, 2, 3
+RECD_POOL_SUM, RECD_POOL_MEAN, RECD_POOL_MAX = 0, 1, 2
+POOLING = {"sum": RECD_POOL_SUM, "mean": RECD_POOL_MEAN, "max": RECD_POOL_MAX}
 
 EXPORTED = [
     "recd_create", "recd_destroy", "recd_set_option", "recd_last_error", "recd_status_string",
     "recd_workspace_bytes", "recd_build_ikjt", "recd_pooled_lookup_unique", "recd_expand_inverse",
     "recd_kjt_pooled_lookup", "recd_backward_dedup", "recd_sequence_lookup_unique",
     "recd_jagged_expand_inverse", "recd_kjt_sequence_lookup", "recd_build_ikjt_grouped",
-    "recd_group_sum_unique",
+    "recd_group_sum_unique", "recd_pooled_lookup_unique_mode", "recd_kjt_pooled_lookup_mode",
 ]
 
 _vp = C.c_void_p
@@ -63,6 +65,8 @@ _lib.recd_build_ikjt_grouped.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, C.c
                                          _vp, _vp, _vp, _vp, _vp]
 _lib.recd_group_sum_unique.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, _vp,
                                        C.c_int64, _vp]
+_lib.recd_pooled_lookup_unique_mode.argtypes = [_vp, C.c_int] + _lib.recd_pooled_lookup_unique.argtypes[1:]
+_lib.recd_kjt_pooled_lookup_mode.argtypes = [_vp, C.c_int] + _lib.recd_kjt_pooled_lookup.argtypes[1:]
 for _n in EXPORTED:
     if _n not in ("recd_last_error", "recd_status_string"):
         getattr(_lib, _n).restype = C.c_int
@@ -138,10 +142,17 @@ class Context:
     def _rows_array(tables: Sequence[torch.Tensor]):
         return (C.c_int64 * len(tables))(*[t.shape[0] for t in tables])
 
-    def pooled_lookup_unique(self, tables, u_values, u_offsets, feat_uoff, max_lists: int, pooled):
+    def pooled_lookup_unique(self, tables, u_values, u_offsets, feat_uoff, max_lists: int, pooled,
+                             mode: Optional[str] = None):
         F = len(tables)
         D = tables[0].shape[1] if F else pooled.shape[-1]
         tdt = _DT[tables[0].dtype] if F else _DT[pooled.dtype]
+        if mode is not None:
+            self._check(_lib.recd_pooled_lookup_unique_mode(
+                self._h, POOLING[mode], F, D, tdt, _DT[pooled.dtype], self._table_array(tables),
+                self._rows_array(tables), _ptr(u_values), _ptr(u_offsets), _ptr(feat_uoff), max_lists,
+                _ptr(pooled)))
+            return
         self._check(_lib.recd_pooled_lookup_unique(
             self._h, F, D, tdt, _DT[pooled.dtype], self._table_array(tables), self._rows_array(tables),
             _ptr(u_values), _ptr(u_offsets), _ptr(feat_uoff), max_lists, _ptr(pooled)))
@@ -152,10 +163,15 @@ class Context:
         self._check(_lib.recd_expand_inverse(self._h, F, B, D, _DT[pooled.dtype], _ptr(pooled),
                                              _ptr(feat_uoff), _ptr(inverse), _ptr(out)))
 
-    def kjt_pooled_lookup(self, tables, B: int, values, offsets, out):
+    def kjt_pooled_lookup(self, tables, B: int, values, offsets, out, mode: Optional[str] = None):
         F = len(tables)
         D = tables[0].shape[1] if F else out.shape[-1]
         tdt = _DT[tables[0].dtype] if F else _DT[out.dtype]
+        if mode is not None:
+            self._check(_lib.recd_kjt_pooled_lookup_mode(
+                self._h, POOLING[mode], F, B, D, tdt, _DT[out.dtype], self._table_array(tables),
+                self._rows_array(tables), _ptr(values), _ptr(offsets), _ptr(out)))
+            return
         self._check(_lib.recd_kjt_pooled_lookup(
             self._h, F, B, D, tdt, _DT[out.dtype], self._table_array(tables), self._rows_array(tables),
             _ptr(values), _ptr(offsets), _ptr(out)))

@@ -208,6 +208,64 @@ def test_empty_lists_pool_to_zero(ctx):
     assert torch.equal(out, kjt)
 
 
+# ------------------------------------------------------------------ other pooling functions
+@pytest.mark.parametrize("mode", ["sum", "mean", "max"])
+@pytest.mark.parametrize("dt,odt,D", [("f32", None, 128), ("f16", None, 64), ("bf16", torch.float32, 256),
+                                      ("f32", None, 24), ("f16", None, 2048)])
+def test_pooling_modes(ctx, mode, dt, odt, D):
+    """Average and max pooling (and the sum through the same entry point) on the unique lists and on
+    the KJT: against the oracle, and the two paths against each other bit for bit.  Lists of up to
+    256 ids take the one-wave path and the whole-block path."""
+    w = synth.scaled(synth.WORKLOADS["cfg3"], F=3, B=700, rows=5000, D=D, table_dtype=dt)
+    batch = synth.make_batch(w, 1)
+    tabs = synth.make_tables(w)
+    dev_tabs = gu.tables_to_dev(tabs, dt)
+    out_dtype = odt or gu.TORCH_DT[dt]
+    F, B = w.F, w.B
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    pooled = torch.full((F * B, D), float("nan"), dtype=out_dtype, device="cuda")
+    ctx.pooled_lookup_unique(dev_tabs, ik.u_values, ik.u_offsets, ik.feat_uoff, F * B, pooled, mode=mode)
+    out = torch.full((F, B, D), float("nan"), dtype=out_dtype, device="cuda")
+    ctx.expand_inverse(F, B, pooled, ik.feat_uoff, ik.inverse, out)
+    kjt = torch.full((F, B, D), float("nan"), dtype=out_dtype, device="cuda")
+    ctx.kjt_pooled_lookup(dev_tabs, B, values, offsets, kjt, mode=mode)
+    torch.cuda.synchronize()
+    assert torch.equal(_bits(out), _bits(kjt))
+    uv, uo, inv, fu = orc.build_ikjt(F, B, batch.values, batch.offsets)
+    ref_pooled = orc.pooled_lookup_mode(mode, tabs, dt, uv, uo, fu)
+    ref_kjt = orc.pooled_lookup_mode(mode, tabs, dt, batch.values, batch.offsets,
+                                     np.arange(F + 1, dtype=np.int64) * B).reshape(F, B, D)
+    close = gu.assert_close_f32 if out_dtype == torch.float32 else gu.assert_close_16
+    close(gu.out_to_f64(pooled[:ik.U]), ref_pooled, f"{mode} pooled unique")
+    close(gu.out_to_f64(kjt), ref_kjt, f"{mode} kjt")
+    if mode == "max":  # a maximum is one of the inputs: exact whenever the output type holds it
+        if out_dtype == torch.float32 or dt != "f32":
+            assert np.array_equal(gu.out_to_f64(kjt), ref_kjt)
+    if mode == "sum":  # the same kernel as the plain entry point
+        plain = torch.zeros(F, B, D, dtype=out_dtype, device="cuda")
+        ctx.kjt_pooled_lookup(dev_tabs, B, values, offsets, plain)
+        assert torch.equal(_bits(plain), _bits(kjt))
+
+
+def test_pooling_modes_hand_cases(ctx, recd):
+    W = [np.array([[1.0, -5.0, 0.5, 2.0], [-2.0, -1.0, 0.25, -2.0], [4.0, -3.0, -8.0, -2.5]], dtype=np.float32)]
+    batch = synth.batch_from_lists([[[0, 1, 2], [1, 1], [], [2], [1, 2] * 40]])
+    d = gu.tables_to_dev(W, "f32")
+    values, offsets = gu.to_dev(batch.values), gu.to_dev(batch.offsets)
+    out = torch.zeros(1, 5, 4, device="cuda")
+    ctx.kjt_pooled_lookup(d, 5, values, offsets, out, mode="max")
+    assert out[0].tolist() == [[4.0, -1.0, 0.5, 2.0], [-2.0, -1.0, 0.25, -2.0], [0.0] * 4,
+                               [4.0, -3.0, -8.0, -2.5], [4.0, -1.0, 0.25, -2.0]]
+    ctx.kjt_pooled_lookup(d, 5, values, offsets, out, mode="mean")
+    assert out[0, 2].tolist() == [0.0] * 4 and out[0, 1].tolist() == [-2.0, -1.0, 0.25, -2.0]
+    assert torch.allclose(out[0, 4], torch.tensor([1.0, -2.0, -3.875, -2.25], device="cuda"), rtol=1e-6)
+    with pytest.raises(recd.RecdError) as e:
+        ctx._check(recd._lib.recd_kjt_pooled_lookup_mode(ctx._h, 7, 1, 5, 4, 0, 0, ctx._table_array(d),
+                                                         ctx._rows_array(d), values.data_ptr(),
+                                                         offsets.data_ptr(), out.data_ptr()))
+    assert e.value.status == recd.RECD_EINVAL
+
+
 # ------------------------------------------------------------------ errors
 def test_argument_errors(ctx, recd):
     t = [torch.zeros(10, 6, device="cuda")]  # D = 6: 24-byte rows are not a multiple of 16
