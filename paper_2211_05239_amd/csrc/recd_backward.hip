@@ -20,8 +20,8 @@
 namespace {
 
 constexpr int kSortThreads = 256;
-constexpr int kIPT = 16;                      // keys per thread in a tile
-constexpr int kTile = kSortThreads * kIPT;    // 4096 keys per tile
+constexpr int kIPT = 8;                       // keys per thread in a tile
+constexpr int kTile = kSortThreads * kIPT;    // keys per tile
 constexpr int kRadixMax = 512;                // digits of up to 9 bits
 constexpr int kScanItems = 16;                // items per thread in the generic scan
 constexpr int kScanTile = 256 * kScanItems;
