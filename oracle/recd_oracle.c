@@ -199,6 +199,80 @@ int oracle_build_ikjt_grouped(int F, int64_t B, int G, const int32_t *group_off,
     return 0;
 }
 
+/* ---- KJT -> partial IKJT (Sec. 7 "Supporting Partial IKJTs") ----------------------------------
+ * The paper fixes the encoding - no offsets slice; every row is an [offset, length] window into
+ * the values slice, so that lists which are shifts of one another share storage - and prints one
+ * example (feature b: values [3,4,5,6], windows [0,3],[1,3],[0,3]).  It gives no construction.
+ * This build's reading, per feature, scanning b upwards:
+ *   - a row whose list was met before (exact match, as for the IKJT) takes that earlier window;
+ *   - any other row opens the next slot (first-occurrence numbering, identical to the IKJT's).
+ *     If the previous row b-1 holds the list of the latest slot - whose window ends where the
+ *     stored values end - the new list may continue it: with k the largest overlap, 1 <= k <=
+ *     min(lengths), such that the last k ids of that list equal the first k ids of the new one,
+ *     only the remaining ids are appended and the window starts k ids before the old end.
+ *     Otherwise, or if no k >= 1 exists, the whole list is appended.
+ * Outputs: p_values (stored ids, feature-major), win_start[u] (position in p_values) and
+ * win_len[u] per slot, inverse[f*B+b] and feat_uoff as for the IKJT, feat_poff = prefix of the
+ * per-feature stored lengths.  The paper's per-row inverse_lookup is
+ * [win_start[u], win_len[u]] with u = feat_uoff[f] + inverse[f*B+b].
+ */
+int oracle_build_partial_ikjt(int F, int64_t B, const int64_t *values, const int64_t *offsets,
+                              int64_t *p_values, int64_t *win_start, int64_t *win_len,
+                              int32_t *inverse, int64_t *feat_uoff, int64_t *feat_poff)
+{
+    int64_t U = 0, P = 0;
+    int64_t *slot_row = (int64_t *)malloc(sizeof(int64_t) * (size_t)(B > 0 ? B : 1));
+    if (!slot_row)
+        return -8;
+    for (int f = 0; f < F; f++) {
+        const int64_t first_slot = U;
+        feat_uoff[f] = U;
+        feat_poff[f] = P;
+        for (int64_t b = 0; b < B; b++) {
+            const int64_t l = (int64_t)f * B + b;
+            const int64_t *list = values + offsets[l];
+            const int64_t len = offsets[l + 1] - offsets[l];
+            int64_t found = -1;
+            for (int64_t s = first_slot; s < U && found < 0; s++) {
+                if (win_len[s] != len)
+                    continue;
+                const int64_t *cand = values + offsets[(int64_t)f * B + slot_row[s - first_slot]];
+                int64_t k = 0;
+                while (k < len && cand[k] == list[k])
+                    k++;
+                if (k == len)
+                    found = s;
+            }
+            if (found < 0) {
+                int64_t overlap = 0;
+                if (b > 0 && U > first_slot && inverse[l - 1] == (int32_t)(U - 1 - first_slot)) {
+                    const int64_t lt = (int64_t)f * B + slot_row[U - 1 - first_slot];
+                    const int64_t *last = values + offsets[lt];
+                    const int64_t last_len = offsets[lt + 1] - offsets[lt];
+                    for (int64_t k = (last_len < len ? last_len : len); k >= 1 && overlap == 0; k--) {
+                        int64_t t = 0;
+                        while (t < k && last[last_len - k + t] == list[t])
+                            t++;
+                        if (t == k)
+                            overlap = k;
+                    }
+                }
+                for (int64_t t = overlap; t < len; t++)
+                    p_values[P++] = list[t];
+                found = U++;
+                slot_row[found - first_slot] = b;
+                win_start[found] = P - len;
+                win_len[found] = len;
+            }
+            inverse[l] = (int32_t)(found - first_slot);
+        }
+    }
+    feat_uoff[F] = U;
+    feat_poff[F] = P;
+    free(slot_row);
+    return 0;
+}
+
 /* ---- sum-pooled embedding-bag lookup (Sec. 2.2 pooling; Sec. 5 "EMB Lookups",
  * "Deduplicated Pooling") --------------------------------------------------------------------
  * out[l,:] = sum over the ids j of list l, in list order, of W_f[values[j],:], accumulated in

@@ -104,6 +104,33 @@ def build_ikjt_grouped(F: int, B: int, group_off, values, offsets):
     return u_values[:M].copy(), u_offsets[:U + 1].copy(), inverse_g[:G * B].copy(), group_uoff, feat_uoff
 
 
+def build_partial_ikjt(F: int, B: int, values, offsets):
+    """KJT -> partial IKJT (Sec. 7).  Returns (p_values[P], win_start[U], win_len[U], inverse[F*B] int32,
+    feat_uoff[F+1], feat_poff[F+1]); see the C source for this build's reading of the construction."""
+    values, offsets = _i64(values), _i64(offsets)
+    _check(check_kjt(F, B, values, offsets), "build_partial_ikjt")
+    N, L = values.shape[0], F * B
+    p_values = np.zeros(max(N, 1), dtype=np.int64)
+    win_start = np.zeros(max(L, 1), dtype=np.int64)
+    win_len = np.zeros(max(L, 1), dtype=np.int64)
+    inverse = np.zeros(max(L, 1), dtype=np.int32)
+    feat_uoff = np.zeros(F + 1, dtype=np.int64)
+    feat_poff = np.zeros(F + 1, dtype=np.int64)
+    rc = _lib.oracle_build_partial_ikjt(C.c_int(F), C.c_int64(B), _p(values, _i64p), _p(offsets, _i64p),
+                                        _p(p_values, _i64p), _p(win_start, _i64p), _p(win_len, _i64p),
+                                        _p(inverse, _i32p), _p(feat_uoff, _i64p), _p(feat_poff, _i64p))
+    _check(rc, "build_partial_ikjt")
+    U, P = int(feat_uoff[F]), int(feat_poff[F])
+    return (p_values[:P].copy(), win_start[:U].copy(), win_len[:U].copy(), inverse[:L].copy(), feat_uoff,
+            feat_poff)
+
+
+def partial_row_windows(F: int, B: int, win_start, win_len, inverse, feat_uoff) -> np.ndarray:
+    """The paper's per-row inverse_lookup of a partial IKJT: int64 [F*B, 2] of [offset, length]."""
+    u = np.repeat(_i64(feat_uoff)[:F], B) + np.asarray(inverse, dtype=np.int64)
+    return np.stack([_i64(win_start)[u], _i64(win_len)[u]], axis=1) if F * B else np.zeros((0, 2), np.int64)
+
+
 def _table_ptrs(tables: Sequence[np.ndarray], dtype: str):
     keep = []
     for t in tables:

@@ -41,6 +41,8 @@ class Workload:
     D: int                # embedding dimension
     table_dtype: str      # "f32" | "f16" | "bf16"
     redraw: float = 0.0   # probability that a non-first sample of a session redraws all features
+    shift: float = 0.0    # probability that a non-first sample's list is the previous one shifted by
+                          # one id (oldest id dropped, a new id appended), drawn per feature
 
 
 WORKLOADS: Dict[str, Workload] = {
@@ -151,14 +153,27 @@ def make_batch(w: Workload, batch_index: int = 0, seed: Optional[int] = None) ->
 
     vals, offs = [], [np.zeros(1, dtype=np.int64)]
     base = 0
+    if w.shift > 0.0:
+        assert w.redraw == 0.0, "shifted lists are generated for sessions without redraws"
     for _f in range(F):
         dl = _draw_lengths(rng, w, K)
-        doff = np.concatenate([[0], np.cumsum(dl)])
+        if w.shift > 0.0:
+            # A session's samples are windows sliding over one id stream: a shifted sample starts one
+            # id later than its predecessor and keeps the session's list length.
+            moved = (rng.random(B) < w.shift) & (np.arange(B) != first_of)
+            cs = np.cumsum(moved)
+            sigma = (cs - cs[first_of]) * (dl[draw_index] > 0)   # shifts since the session's start
+            last_of = np.concatenate([first_of[1:][np.diff(first_of) != 0] - 1, [B - 1]])
+            stream = dl + sigma[last_of] * (dl > 0)
+        else:
+            sigma = 0
+            stream = dl
+        doff = np.concatenate([[0], np.cumsum(stream)])
         dids = _draw_ids(rng, w, int(doff[-1]))
         sl = dl[draw_index]                        # per-sample length
         soff = np.concatenate([[0], np.cumsum(sl)])
         n_f = int(soff[-1])
-        gather = np.repeat(doff[draw_index] - soff[:-1], sl) + np.arange(n_f, dtype=np.int64)
+        gather = np.repeat(doff[draw_index] + sigma - soff[:-1], sl) + np.arange(n_f, dtype=np.int64)
         vals.append(dids[gather])
         offs.append(soff[1:] + base)
         base += n_f

@@ -402,6 +402,106 @@ def test_group_sum_matches_sum_of_expanded_features():
     assert np.allclose(out, ref, rtol=1e-13, atol=1e-13)
 
 
+# ------------------------------------------------------------------ partial IKJTs
+def _check_partial(batch, pv, ws, wl, inv, fu, fp):
+    """Properties every partial IKJT has: lossless windows, the IKJT's slots, storage inside the
+    feature, and the largest admissible overlap where the construction allows one."""
+    F, B = batch.F, batch.B
+    L = _lists(batch)
+    ruv, ruo, rinv, rfu = orc.build_ikjt(F, B, batch.values, batch.offsets)
+    assert np.array_equal(inv, rinv) and np.array_equal(fu, rfu)      # same duplicates, same numbering
+    assert np.array_equal(wl, np.diff(ruo))
+    assert fp[0] == 0 and fp[F] == len(pv) and len(pv) <= len(ruv)
+    rows = orc.partial_row_windows(F, B, ws, wl, inv, fu)
+    for f in range(F):
+        for b in range(B):
+            o, n = rows[f * B + b]
+            assert fp[f] <= o and o + n <= fp[f + 1]
+            assert pv[o:o + n].tolist() == L[f][b]
+        first_row = {}
+        for b in range(B):
+            first_row.setdefault(int(inv[f * B + b]), b)
+        end = int(fp[f])
+        for k in range(int(fu[f + 1] - fu[f])):
+            u = int(fu[f]) + k
+            new_end = int(ws[u] + wl[u])
+            used = int(wl[u]) - (new_end - end)      # overlap with what was stored before
+            b = first_row[k]
+            cur = L[f][b]
+            if k > 0 and b > 0 and inv[f * B + b - 1] == k - 1:
+                prev = L[f][first_row[k - 1]]
+                best = max([j for j in range(1, min(len(prev), len(cur)) + 1) if prev[len(prev) - j:] == cur[:j]],
+                           default=0)
+                assert used == best, (f, k, used, best)
+            else:
+                assert used == 0
+            assert new_end >= end
+            end = new_end
+        assert end == fp[f + 1]
+
+
+def test_paper_partial_feature_b(golden_dir):
+    g = _golden(golden_dir, "paper_ikjt_feature_b.json")
+    kjt = synth.batch_from_lists([g["rows"]])
+    pv, ws, wl, inv, fu, fp = orc.build_partial_ikjt(1, 3, kjt.values, kjt.offsets)
+    assert pv.tolist() == g["partial_values"]
+    assert orc.partial_row_windows(1, 3, ws, wl, inv, fu).tolist() == g["partial_inverse"]
+    _check_partial(kjt, pv, ws, wl, inv, fu, fp)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_build_partial_ikjt_properties(seed):
+    rng = np.random.default_rng(9000 + seed)
+    F, B = int(rng.integers(1, 4)), int(rng.integers(1, 60))
+    if seed % 2:
+        batch = synth.tiny_batch(rng, F, B, int(rng.integers(2, 4)), int(rng.integers(0, 5)))
+    else:  # sessions whose lists slide over a stream
+        w = synth.scaled(synth.WORKLOADS["cfg1"], F=F, B=B, S=5, rows=6, shift=0.5, len_max=6)
+        batch = synth.make_batch(w, seed)
+    _check_partial(batch, *orc.build_partial_ikjt(F, B, batch.values, batch.offsets))
+
+
+def test_build_partial_ikjt_closed_forms():
+    A = [10, 11, 12, 13, 14]
+    sh = lambda k: list(range(10 + k, 15 + k))           # A shifted by k ids
+    # a window sliding one id at a time, with repeats in between: |A| + number of shifts ids stored
+    rows = [A, A, sh(1), sh(1), sh(1), sh(2), sh(3), sh(3)]
+    kjt = synth.batch_from_lists([rows])
+    pv, ws, wl, inv, fu, fp = orc.build_partial_ikjt(1, len(rows), kjt.values, kjt.offsets)
+    assert pv.tolist() == list(range(10, 18)) and inv.tolist() == [0, 0, 1, 1, 1, 2, 3, 3]
+    assert ws.tolist() == [0, 1, 2, 3] and wl.tolist() == [5] * 4
+    # an unrelated row in between breaks the chain: the shifted list is stored whole
+    X = [50, 51]
+    kjt = synth.batch_from_lists([[A, X, sh(1)]])
+    pv, ws, wl, inv, fu, fp = orc.build_partial_ikjt(1, 3, kjt.values, kjt.offsets)
+    assert pv.tolist() == A + X + sh(1) and ws.tolist() == [0, 5, 7]
+    # so does a return to an earlier list: its window does not end where the stored values end
+    kjt = synth.batch_from_lists([[A, X, A, sh(1)]])
+    pv, ws, wl, inv, fu, fp = orc.build_partial_ikjt(1, 4, kjt.values, kjt.offsets)
+    assert inv.tolist() == [0, 1, 0, 2] and pv.tolist() == A + X + sh(1)
+    # a list that is a suffix of its predecessor stores nothing; a list that grows appends the rest
+    kjt = synth.batch_from_lists([[A, A[2:], A[2:] + [99, 98]]])
+    pv, ws, wl, inv, fu, fp = orc.build_partial_ikjt(1, 3, kjt.values, kjt.offsets)
+    assert pv.tolist() == A + [99, 98] and ws.tolist() == [0, 2, 2] and wl.tolist() == [5, 3, 5]
+    # all ids distinct: nothing overlaps, the partial IKJT stores exactly the IKJT's values
+    rows = [[3 * i, 3 * i + 1, 3 * i + 2] for i in range(9)]
+    kjt = synth.batch_from_lists([rows, rows[::-1]])
+    pv, ws, wl, inv, fu, fp = orc.build_partial_ikjt(2, 9, kjt.values, kjt.offsets)
+    uv, uo, _, _ = orc.build_ikjt(2, 9, kjt.values, kjt.offsets)
+    assert np.array_equal(pv, uv) and np.array_equal(ws, uo[:-1]) and fp.tolist() == [0, 27, 54]
+    # windows never reach into another feature, although feature 1 starts with feature 0's last list
+    kjt = synth.batch_from_lists([[A], [A]])
+    pv, ws, wl, inv, fu, fp = orc.build_partial_ikjt(2, 1, kjt.values, kjt.offsets)
+    assert pv.tolist() == A + A and ws.tolist() == [0, 5]
+    # empty rows and an empty batch
+    kjt = synth.batch_from_lists([[[], [1], [], [1, 2]]])
+    pv, ws, wl, inv, fu, fp = orc.build_partial_ikjt(1, 4, kjt.values, kjt.offsets)
+    # row 3 follows an empty row, which is not the latest slot ([1]): no continuation
+    assert pv.tolist() == [1, 1, 2] and inv.tolist() == [0, 1, 0, 2] and ws.tolist() == [0, 0, 1]
+    pv, ws, wl, inv, fu, fp = orc.build_partial_ikjt(2, 0, np.zeros(0, np.int64), np.zeros(1, np.int64))
+    assert len(pv) == 0 and fu.tolist() == [0, 0, 0] and fp.tolist() == [0, 0, 0]
+
+
 # ------------------------------------------------------------------ unpooled activations, jagged index select
 def test_paper_feature_b_jagged_expand(golden_dir):
     """With W[r] = r (D = 1) the jagged expand of the unique activations reproduces the KJT's values."""
