@@ -13,6 +13,8 @@
  *   8. KJT sequence lookup, the non-deduplicated comparison path
  * and for feature groups that share one inverse index (Sec. 4.2 "Grouped IKJTs"):
  *   9. grouped builder    10. element-wise sum over a group's features on the unique rows
+ * other pooling functions (11), and partial IKJTs whose lists share storage when one continues
+ * another (Sec. 7): 12. partial builder   13. pooled lookup on the windows
  *
  * General rules
  *   - Every array argument marked "device" is a pointer into GPU memory owned by the caller and
@@ -271,6 +273,42 @@ recd_status recd_kjt_pooled_lookup_mode(recd_ctx *ctx, recd_pooling mode, int F,
                                         recd_dtype table_dt, recd_dtype out_dt,
                                         const void *const *tables, const int64_t *rows,
                                         const int64_t *values, const int64_t *offsets, void *out);
+
+/* 12. KJT -> partial IKJT (Sec. 7 "Supporting Partial IKJTs": no offsets slice; every row is an
+ *    [offset, length] window into the values slice, so that lists which are shifts of one another
+ *    share storage; the paper's example stores feature b as values [3,4,5,6] with the windows
+ *    [0,3], [1,3], [0,3]).  The paper prints no construction; this library's: the slots are those
+ *    of call 1 (same duplicates, same first-occurrence numbering, same inverse and feat_uoff).
+ *    A slot whose first row directly follows a row holding the previous slot's list continues
+ *    that list: with k >= 1 the largest overlap of the previous list's tail with the new list's
+ *    head, only the other ids are stored and the window starts k ids before the old end.  Every
+ *    other slot stores its whole list.
+ *    values [N], offsets [F*B+1]: device, read-only.  N must stay below 2^31.
+ *    p_values: device, capacity N: the stored ids, feature-major.
+ *    win_start, win_len: device int64, capacity F*B: window of slot u (position in p_values,
+ *    length); list u = p_values[win_start[u] .. win_start[u] + win_len[u]).
+ *    inverse [F*B], feat_uoff [F+1]: as in call 1.  feat_poff: device int64 [F+1], prefix sum of
+ *    the ids stored per feature; windows never leave their feature's range.
+ *    row_window: optional device int64 [F*B*2]: the paper's per-row inverse_lookup,
+ *    row_window[2*(f*B+b)] = offset, [.. + 1] = length; NULL to skip.
+ *    host_counts: optional host int64[3]; if non-NULL the call synchronises and stores U, the
+ *    number of stored ids P, and M (what call 1 would store). */
+recd_status recd_build_partial_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t N,
+                                    const int64_t *values, const int64_t *offsets, int64_t *p_values,
+                                    int64_t *win_start, int64_t *win_len, int32_t *inverse,
+                                    int64_t *feat_uoff, int64_t *feat_poff, int64_t *row_window,
+                                    int64_t *host_counts);
+
+/* 13. Call 2 on a partial IKJT: pooled[u,:] = sum over the ids of window u.  The windows hold the
+ *    lists of call 1's slots in the same order, and the order of additions depends on the list
+ *    alone, so the result equals call 2 on the IKJT of the same batch bit for bit; call 3 expands
+ *    it.  P_cap: host upper bound of the number of stored ids (used by validation only).
+ *    Other arguments as in call 2. */
+recd_status recd_pooled_lookup_partial(recd_ctx *ctx, int F, int D, recd_dtype table_dt,
+                                       recd_dtype out_dt, const void *const *tables,
+                                       const int64_t *rows, const int64_t *p_values, int64_t P_cap,
+                                       const int64_t *win_start, const int64_t *win_len,
+                                       const int64_t *feat_uoff, int64_t max_lists, void *pooled);
 
 #ifdef __cplusplus
 }

@@ -556,6 +556,150 @@ __global__ void k_empty_grouped(int F, int G, int64_t *u_offsets, int64_t *feat_
     }
 }
 
+// ---- partial IKJT (Sec. 7 "Supporting Partial IKJTs") ------------------------------------------
+// The slots are the IKJT's (same duplicates, same first-occurrence numbering); what changes is the
+// storage: a slot whose first row directly follows a row holding the previous slot's list may
+// continue that list - with k the largest overlap of the previous list's tail and the new list's
+// head, only the remaining ids are stored and the slot's window starts k ids before the old end.
+//
+// One wave per slot: the ids to store (list length minus overlap).  Candidate overlaps are the
+// positions of the new list's first id in the previous list, tried from the largest overlap down;
+// each is verified by the whole wave.
+__global__ __launch_bounds__(256) void k_partial_overlap(const int64_t *__restrict__ values,
+                                                         const int64_t *__restrict__ offsets, int64_t B,
+                                                         const int32_t *__restrict__ src_of,
+                                                         const int32_t *__restrict__ inverse,
+                                                         const int64_t *__restrict__ feat_uoff,
+                                                         const int64_t *__restrict__ counts,
+                                                         int64_t *__restrict__ win_len,
+                                                         int32_t *__restrict__ piece)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t U = counts[0];
+    const int64_t stride = (int64_t)gridDim.x * 4;
+    for (int64_t u = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6); u < U; u += stride) {
+        const int64_t l = src_of[u];
+        const int64_t f = l / B, b = l - f * B;
+        const int64_t sb = offsets[l], len = offsets[l + 1] - sb;
+        int64_t k = 0;
+        const int64_t first_slot = feat_uoff[f];
+        if (b > 0 && u > first_slot && (int64_t)inverse[l - 1] == u - 1 - first_slot && len > 0) {
+            const int64_t lt = src_of[u - 1];
+            const int64_t st = offsets[lt], len_t = offsets[lt + 1] - st;
+            const int64_t kmax = len_t < len ? len_t : len;
+            const int64_t head = values[sb];
+            for (int64_t p0 = len_t - kmax; p0 < len_t && k == 0; p0 += 64) {
+                const int64_t p = p0 + lane;
+                uint64_t cand = __ballot(p < len_t && values[st + p] == head);
+                while (cand != 0 && k == 0) {
+                    const int64_t pc = p0 + __builtin_ctzll(cand);
+                    cand &= cand - 1;
+                    const int64_t kk = len_t - pc;  // overlap if the previous list's tail matches
+                    bool ok = true;
+                    for (int64_t i = lane; i < kk && ok; i += 64)
+                        ok = values[st + pc + i] == values[sb + i];
+                    if (__ballot(!ok) == 0)
+                        k = kk;
+                }
+            }
+        }
+        if (lane == 0) {
+            win_len[u] = len;
+            piece[u] = (int32_t)(len - k);
+        }
+    }
+}
+
+// Positions of the stored pieces: exclusive scan of piece[] over the slots (pass 1: block sums;
+// pass 2, after k_scan_blocks: window starts, per-feature prefix, total).
+template <bool APPLY>
+__global__ __launch_bounds__(kScanBlock) void k_partial_scan(const int32_t *__restrict__ piece,
+                                                             const int64_t *__restrict__ win_len,
+                                                             const int32_t *__restrict__ src_of, int64_t B,
+                                                             int F, const int64_t *__restrict__ feat_uoff,
+                                                             int64_t *__restrict__ counts,
+                                                             int64_t *__restrict__ bs_cnt,
+                                                             int64_t *__restrict__ bs_len,
+                                                             int64_t *__restrict__ bs_head,
+                                                             int64_t *__restrict__ piece_pos,
+                                                             int64_t *__restrict__ win_start,
+                                                             int64_t *__restrict__ feat_poff)
+{
+    const int64_t U = counts[0];
+    const int64_t u = (int64_t)blockIdx.x * kScanBlock + threadIdx.x;
+    const int64_t pc = u < U ? piece[u] : 0;
+    int64_t ea, eb, ic, ta, tb, tc;
+    block_scan3(pc, 0, -1, ea, eb, ic, ta, tb, tc);
+    if (!APPLY) {
+        if (threadIdx.x == 0) {
+            bs_cnt[blockIdx.x] = ta;
+            bs_len[blockIdx.x] = 0;
+            bs_head[blockIdx.x] = -1;
+        }
+        return;
+    }
+    if (u < U) {
+        const int64_t pos = bs_cnt[blockIdx.x] + ea;  // where this slot's piece is stored
+        piece_pos[u] = pos;
+        win_start[u] = pos + pc - win_len[u];
+        const int64_t f = (int64_t)src_of[u] / B;
+        if (u == feat_uoff[f])
+            feat_poff[f] = pos;
+        if (u == U - 1) {
+            feat_poff[F] = pos + pc;
+            counts[2] = pos + pc;
+        }
+    }
+}
+
+// Copies every slot's piece (the tail of its first row's list) and writes the per-row windows.
+template <int SG>
+__global__ __launch_bounds__(256) void k_partial_emit(const int64_t *__restrict__ values,
+                                                      const int64_t *__restrict__ offsets, int64_t B,
+                                                      int64_t n_lists, const int32_t *__restrict__ src_of,
+                                                      const int32_t *__restrict__ piece,
+                                                      const int64_t *__restrict__ piece_pos,
+                                                      const int64_t *__restrict__ win_start,
+                                                      const int64_t *__restrict__ win_len,
+                                                      const int32_t *__restrict__ inverse,
+                                                      const int64_t *__restrict__ feat_uoff,
+                                                      const int64_t *__restrict__ counts,
+                                                      int64_t *__restrict__ p_values,
+                                                      int64_t *__restrict__ row_window, unsigned row_blocks)
+{
+    if (blockIdx.x < row_blocks) {
+        const int64_t l = (int64_t)blockIdx.x * 256 + threadIdx.x;
+        if (l < n_lists) {
+            const int64_t u = feat_uoff[l / B] + inverse[l];
+            row_window[2 * l] = win_start[u];
+            row_window[2 * l + 1] = win_len[u];
+        }
+        return;
+    }
+    const int s = threadIdx.x % SG;
+    const int64_t U = counts[0];
+    const int64_t stride = (int64_t)(gridDim.x - row_blocks) * (256 / SG);
+    for (int64_t u = (int64_t)(blockIdx.x - row_blocks) * (256 / SG) + threadIdx.x / SG; u < U;
+         u += stride) {
+        const int64_t l = src_of[u];
+        const int64_t n = piece[u];
+        const int64_t src = offsets[l + 1] - n;  // the last n ids of the list
+        const int64_t dst = piece_pos[u];
+        for (int64_t t = s; t < n; t += SG)
+            p_values[dst + t] = values[src + t];
+    }
+}
+
+__global__ void k_empty_partial(int F, int64_t *feat_uoff, int64_t *feat_poff, int64_t *counts)
+{
+    for (int f = threadIdx.x; f <= F; f += blockDim.x) {
+        feat_uoff[f] = 0;
+        feat_poff[f] = 0;
+    }
+    if (threadIdx.x == 0)
+        counts[0] = counts[1] = counts[2] = 0;
+}
+
 uint64_t table_cap(int64_t B)
 {
     uint64_t cap = 64;
@@ -790,6 +934,106 @@ extern "C" recd_status recd_build_ikjt_grouped(recd_ctx *ctx, int F, int64_t B, 
         host_counts[0] = ctx->host_pinned[0];
         host_counts[1] = ctx->host_pinned[1];
         host_counts[2] = ctx->host_pinned[2];
+    }
+    return RECD_OK;
+}
+
+
+extern "C" recd_status recd_build_partial_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t N,
+                                               const int64_t *values, const int64_t *offsets,
+                                               int64_t *p_values, int64_t *win_start, int64_t *win_len,
+                                               int32_t *inverse, int64_t *feat_uoff, int64_t *feat_poff,
+                                               int64_t *row_window, int64_t *host_counts)
+{
+    if (!ctx)
+        return RECD_EINVAL;
+    if (F < 0 || F > RECD_MAX_FEATURES || B < 0 || N < 0)
+        return recd_fail(ctx, RECD_EINVAL, "bad sizes F=%d B=%lld N=%lld", F, (long long)B, (long long)N);
+    const int64_t n_lists = (int64_t)F * B;
+    if (n_lists >= (int64_t)1 << 31 || B >= (int64_t)1 << 30 || N >= (int64_t)1 << 31)
+        return recd_fail(ctx, RECD_EINVAL, "F*B and N must stay below 2^31");
+    if (!feat_uoff || !feat_poff || (n_lists > 0 && (!offsets || !inverse || !win_start || !win_len)) ||
+        (N > 0 && (!values || !p_values)))
+        return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
+    RECD_HIP(ctx, hipSetDevice(ctx->device));
+    if (ctx->validate && n_lists > 0)
+        RECD_TRY(recd_validate_kjt_offsets(ctx, F, B, N, offsets));
+
+    const int64_t nblk = (n_lists + kScanBlock - 1) / kScanBlock;
+    const uint64_t cap = table_cap(B);
+    size_t bytes = 0;
+    int64_t *counts = nullptr, *u_off = nullptr, *piece_pos = nullptr, *bs_cnt = nullptr, *bs_len = nullptr,
+            *bs_head = nullptr;
+    uint64_t *table = nullptr;
+    int32_t *slot_of = nullptr, *rep = nullptr, *number = nullptr, *src_of = nullptr, *piece = nullptr;
+    for (int pass = 0; pass < 2; pass++) {
+        WsCarver c(pass ? ctx->ws : nullptr);
+        counts = c.take<int64_t>(4);
+        table = c.take<uint64_t>((size_t)F * cap);
+        slot_of = c.take<int32_t>(n_lists);
+        rep = c.take<int32_t>(n_lists);
+        number = c.take<int32_t>(n_lists);
+        src_of = c.take<int32_t>(n_lists);
+        piece = c.take<int32_t>(n_lists);
+        u_off = c.take<int64_t>(n_lists + 1);
+        piece_pos = c.take<int64_t>(n_lists);
+        bs_cnt = c.take<int64_t>(nblk + 1);
+        bs_len = c.take<int64_t>(nblk + 1);
+        bs_head = c.take<int64_t>(nblk + 1);
+        bytes = c.off;
+        if (!pass)
+            RECD_TRY(recd_reserve(ctx, bytes));
+    }
+    hipStream_t st = ctx->stream;
+    if (n_lists == 0) {
+        hipLaunchKernelGGL(k_empty_partial, dim3(1), dim3(256), 0, st, F, feat_uoff, feat_poff, counts);
+    } else {
+        constexpr int SG = 8;
+        const int64_t tab_n = (int64_t)F * (int64_t)cap;
+        const int fill_blocks = (int)((tab_n + 1023) / 1024 < 4096 ? (tab_n + 1023) / 1024 : 4096);
+        hipLaunchKernelGGL(k_fill_u64, dim3(fill_blocks), dim3(256), 0, st, table, tab_n, kEmpty);
+        const int64_t hblocks = (n_lists + (256 / SG) * kLPG - 1) / ((256 / SG) * kLPG);
+        hipLaunchKernelGGL((k_hash_insert<SG>), dim3((unsigned)hblocks), dim3(256), 0, st, values,
+                           offsets, B, n_lists, table, (uint32_t)(cap - 1), slot_of, ctx->weak_hash);
+        hipLaunchKernelGGL(k_flags, dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets, B, n_lists,
+                           table, (uint32_t)(cap - 1), slot_of, bs_cnt, bs_len, bs_head);
+        hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(kScanBlock), 0, st, bs_cnt, bs_len, bs_head,
+                           nblk);
+        hipLaunchKernelGGL(k_number, dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets, B, n_lists,
+                           F, table, (uint32_t)(cap - 1), slot_of, bs_cnt, bs_len, bs_head, rep, number,
+                           src_of, u_off, feat_uoff, counts);
+        const unsigned inv_blocks = (unsigned)((n_lists + 255) / 256);
+        hipLaunchKernelGGL((k_emit<16>), dim3(inv_blocks), dim3(256), 0, st, values, offsets, B, n_lists,
+                           rep, number, src_of, u_off, counts, p_values, inverse, inv_blocks);
+        int64_t ov_blocks = (n_lists + 3) / 4;
+        if (ov_blocks > (int64_t)ctx->num_cu * 16)
+            ov_blocks = (int64_t)ctx->num_cu * 16;
+        hipLaunchKernelGGL(k_partial_overlap, dim3((unsigned)ov_blocks), dim3(256), 0, st, values, offsets,
+                           B, src_of, inverse, feat_uoff, counts, win_len, piece);
+        hipLaunchKernelGGL((k_partial_scan<false>), dim3((unsigned)nblk), dim3(kScanBlock), 0, st, piece,
+                           win_len, src_of, B, F, feat_uoff, counts, bs_cnt, bs_len, bs_head, piece_pos,
+                           win_start, feat_poff);
+        hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(kScanBlock), 0, st, bs_cnt, bs_len, bs_head,
+                           nblk);
+        hipLaunchKernelGGL((k_partial_scan<true>), dim3((unsigned)nblk), dim3(kScanBlock), 0, st, piece,
+                           win_len, src_of, B, F, feat_uoff, counts, bs_cnt, bs_len, bs_head, piece_pos,
+                           win_start, feat_poff);
+        const unsigned row_blocks = row_window ? inv_blocks : 0u;
+        int64_t copy_blocks = (n_lists + (256 / 16) - 1) / (256 / 16);
+        if (copy_blocks > (int64_t)ctx->num_cu * 8)
+            copy_blocks = (int64_t)ctx->num_cu * 8;
+        hipLaunchKernelGGL((k_partial_emit<16>), dim3(row_blocks + (unsigned)copy_blocks), dim3(256), 0,
+                           st, values, offsets, B, n_lists, src_of, piece, piece_pos, win_start, win_len,
+                           inverse, feat_uoff, counts, p_values, row_window, row_blocks);
+    }
+    RECD_HIP(ctx, hipGetLastError());
+    if (host_counts) {
+        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, counts, 3 * sizeof(int64_t),
+                                     hipMemcpyDeviceToHost, st));
+        RECD_HIP(ctx, hipStreamSynchronize(st));
+        host_counts[0] = ctx->host_pinned[0];  // U
+        host_counts[1] = ctx->host_pinned[2];  // P: ids stored
+        host_counts[2] = ctx->host_pinned[1];  // M: ids an IKJT would store
     }
     return RECD_OK;
 }

@@ -91,6 +91,7 @@ struct SegSumArgs {
     int flat;                 // 1: no XCD-aware feature->block mapping
     const int64_t *ends;            // optional (single table, flat): list l ends at ends[l] ...
     const int64_t *count_dev;       // ... and the number of lists lives on the device
+    const int64_t *lens;            // optional: list l spans offsets[l] .. offsets[l] + lens[l]
     int site;                 // RECD_SITE_*: which call site (each has its own kernel instantiation)
     int mode;                 // recd_pooling (forward sites only; 0 = sum)
     void *out;                // [lists, D]

@@ -150,6 +150,8 @@ struct SegSumParams {
     // lists is *count_dev
     const int64_t *ends;
     const int64_t *count_dev;
+    // optional: list l spans offsets[l] .. offsets[l] + lens[l] (windows of a partial IKJT)
+    const int64_t *lens;
 };
 
 // Adds the rows of NL chunks (chunk j: ns[j] <= 64 ids starting at values[starts[j]], rows of the
@@ -317,8 +319,9 @@ void k_segsum(const SegSumParams p)
             const int64_t l = p.count_dev ? t : p.list_base + s_loff[f] + (t - s_qpref[lo]);
             s_feat[tid] = f;
             s_list[tid] = l;
-            s_start[tid] = p.offsets[l];
-            s_end[tid] = p.ends ? p.ends[l] : p.offsets[l + 1];
+            const int64_t start = p.offsets[l];
+            s_start[tid] = start;
+            s_end[tid] = p.ends ? p.ends[l] : (p.lens ? start + p.lens[l] : p.offsets[l + 1]);
         }
         __syncthreads();
 
@@ -539,6 +542,25 @@ __global__ void k_validate_ids(const int64_t *values, const int64_t *offsets,
 
 __global__ void k_read_i64(const int64_t *src, int64_t *dst) { *dst = *src; }
 
+// err[0] |= 16: a window of a partial IKJT leaves the stored values; |= 2: id outside its table
+__global__ void k_validate_windows(const int64_t *p_values, int64_t P_cap, const int64_t *win_start,
+                                   const int64_t *win_len, const int64_t *feat_uoff, int f,
+                                   int64_t rows_f, int *err)
+{
+    const int64_t u0 = feat_uoff[f], u1 = feat_uoff[f + 1];
+    for (int64_t u = u0 + blockIdx.x; u < u1; u += gridDim.x) {
+        const int64_t s = win_start[u], n = win_len[u];
+        if (s < 0 || n < 0 || s > P_cap || n > P_cap - s) {
+            if (threadIdx.x == 0)
+                atomicOr(err, 16);
+            continue;
+        }
+        for (int64_t t = threadIdx.x; t < n; t += blockDim.x)
+            if (p_values[s + t] < 0 || p_values[s + t] >= rows_f)
+                atomicOr(err, 2);
+    }
+}
+
 // err[0] |= 4: feat_uoff is not a prefix sum starting at 0, or an inverse entry is outside its
 // feature's [0, U_f)
 __global__ void k_validate_inverse(const int32_t *inverse, const int64_t *feat_uoff, int F, int64_t B,
@@ -570,6 +592,7 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     p.out = a.out;
     p.ends = a.ends;
     p.count_dev = a.count_dev;
+    p.lens = a.lens;
     p.F = a.F;
     p.D = a.D;
     const int epv = a.table_dt == RECD_F32 ? 4 : 8;
@@ -930,6 +953,70 @@ recd_status recd_group_sum_unique(recd_ctx *ctx, int F, int G, int D, recd_dtype
         RECD_GS(RECD_BF16);
 #undef RECD_GS
     RECD_HIP(ctx, hipGetLastError());
+    return RECD_OK;
+}
+
+recd_status recd_pooled_lookup_partial(recd_ctx *ctx, int F, int D, recd_dtype table_dt,
+                                       recd_dtype out_dt, const void *const *tables,
+                                       const int64_t *rows, const int64_t *p_values, int64_t P_cap,
+                                       const int64_t *win_start, const int64_t *win_len,
+                                       const int64_t *feat_uoff, int64_t max_lists, void *pooled)
+{
+    RECD_TRY(check_lookup_shape(ctx, F, D, table_dt, out_dt));
+    if (max_lists < 0 || P_cap < 0)
+        return recd_fail(ctx, RECD_EINVAL, "max_lists or P_cap < 0");
+    if (F == 0 || max_lists == 0)
+        return RECD_OK;
+    if (!tables || !win_start || !win_len || !feat_uoff || !pooled || (P_cap > 0 && !p_values))
+        return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
+    for (int f = 0; f < F; f++)
+        if (!tables[f])
+            return recd_fail(ctx, RECD_EINVAL, "tables[%d] is null", f);
+    RECD_HIP(ctx, hipSetDevice(ctx->device));
+    if (ctx->validate) {
+        if (!rows)
+            return recd_fail(ctx, RECD_EINVAL, "validation needs rows[]");
+        RECD_TRY(recd_reserve(ctx, 1024));
+        int64_t *tmp = reinterpret_cast<int64_t *>(ctx->ws + 256);
+        hipLaunchKernelGGL(k_read_i64, dim3(1), dim3(1), 0, ctx->stream, feat_uoff + F, tmp);
+        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned + 1, tmp, 8, hipMemcpyDeviceToHost, ctx->stream));
+        RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        const int64_t U = ctx->host_pinned[1];
+        if (U < 0 || U > max_lists)
+            return recd_fail(ctx, RECD_ECAPACITY, "U=%lld exceeds max_lists=%lld", (long long)U,
+                             (long long)max_lists);
+        int *err = reinterpret_cast<int *>(ctx->ws);
+        RECD_HIP(ctx, hipMemsetAsync(err, 0, sizeof(int), ctx->stream));
+        for (int f = 0; f < F; f++)
+            hipLaunchKernelGGL(k_validate_windows, dim3(64), dim3(256), 0, ctx->stream, p_values, P_cap,
+                               win_start, win_len, feat_uoff, f, rows[f], err);
+        ctx->host_pinned[0] = 0;
+        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, err, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+        RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        if ((int)ctx->host_pinned[0] & 16)
+            return recd_fail(ctx, RECD_EBOUNDS, "a window leaves the stored values");
+        if ((int)ctx->host_pinned[0] & 2)
+            return recd_fail(ctx, RECD_EBOUNDS, "an id lies outside its embedding table");
+    }
+    for (int f0 = 0; f0 < F; f0 += RECD_F_PER_LAUNCH) {
+        SegSumArgs a{};
+        a.F = F - f0 < RECD_F_PER_LAUNCH ? F - f0 : RECD_F_PER_LAUNCH;
+        a.D = D;
+        a.table_dt = table_dt;
+        a.out_dt = out_dt;
+        for (int f = 0; f < a.F; f++)
+            a.tables.p[f] = tables[f0 + f];
+        a.values = p_values;
+        a.values_are_i32 = 0;
+        a.offsets = win_start;
+        a.lens = win_len;
+        a.list_off = feat_uoff + f0;
+        a.lists_bound = max_lists;
+        a.site = RECD_SITE_UNIQUE;
+        a.mode = RECD_POOL_SUM;
+        a.out = pooled;
+        RECD_TRY(recd_launch_segsum(ctx, a));
+    }
     return RECD_OK;
 }
 

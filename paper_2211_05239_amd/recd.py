@@ -35,6 +35,7 @@ EXPORTED = [
     "recd_kjt_pooled_lookup", "recd_backward_dedup", "recd_sequence_lookup_unique",
     "recd_jagged_expand_inverse", "recd_kjt_sequence_lookup", "recd_build_ikjt_grouped",
     "recd_group_sum_unique", "recd_pooled_lookup_unique_mode", "recd_kjt_pooled_lookup_mode",
+    "recd_build_partial_ikjt", "recd_pooled_lookup_partial",
 ]
 
 _vp = C.c_void_p
@@ -67,6 +68,9 @@ _lib.recd_group_sum_unique.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_int, 
                                        C.c_int64, _vp]
 _lib.recd_pooled_lookup_unique_mode.argtypes = [_vp, C.c_int] + _lib.recd_pooled_lookup_unique.argtypes[1:]
 _lib.recd_kjt_pooled_lookup_mode.argtypes = [_vp, C.c_int] + _lib.recd_kjt_pooled_lookup.argtypes[1:]
+_lib.recd_build_partial_ikjt.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64] + [_vp] * 10
+_lib.recd_pooled_lookup_partial.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, C.c_int64,
+                                            _vp, _vp, _vp, C.c_int64, _vp]
 for _n in EXPORTED:
     if _n not in ("recd_last_error", "recd_status_string"):
         getattr(_lib, _n).restype = C.c_int
@@ -235,3 +239,21 @@ class Context:
         self._check(_lib.recd_group_sum_unique(
             self._h, F, G, pooled.shape[-1], _DT[pooled.dtype], goff, _ptr(pooled), _ptr(feat_uoff),
             _ptr(group_uoff), combined.shape[0], _ptr(combined)))
+
+    # -- partial IKJTs --------------------------------------------------------------------------
+    def build_partial_ikjt(self, F: int, B: int, values, offsets, p_values, win_start, win_len, inverse,
+                           feat_uoff, feat_poff, row_window=None, want_counts: bool = False):
+        host = (C.c_int64 * 3)(0, 0, 0) if want_counts else None
+        self._check(_lib.recd_build_partial_ikjt(
+            self._h, F, B, values.numel(), _ptr(values), _ptr(offsets), _ptr(p_values), _ptr(win_start),
+            _ptr(win_len), _ptr(inverse), _ptr(feat_uoff), _ptr(feat_poff), _ptr(row_window), host))
+        return (int(host[0]), int(host[1]), int(host[2])) if want_counts else None
+
+    def pooled_lookup_partial(self, tables, p_values, win_start, win_len, feat_uoff, max_lists: int, pooled):
+        F = len(tables)
+        D = tables[0].shape[1] if F else pooled.shape[-1]
+        tdt = _DT[tables[0].dtype] if F else _DT[pooled.dtype]
+        self._check(_lib.recd_pooled_lookup_partial(
+            self._h, F, D, tdt, _DT[pooled.dtype], self._table_array(tables), self._rows_array(tables),
+            _ptr(p_values), p_values.numel(), _ptr(win_start), _ptr(win_len), _ptr(feat_uoff), max_lists,
+            _ptr(pooled)))
