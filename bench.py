@@ -47,6 +47,9 @@ def parse_args():
                     help="also time the grouped IKJT path with groups of this many consecutive features "
                          "(builder, group-sum module on the unique rows, one expand per group) beside the "
                          "same module run on the expanded KJT rows")
+    ap.add_argument("--partial", type=float, default=0.0,
+                    help="also time the partial IKJT path on the workload with this probability of a "
+                         "sample's lists shifting by one id within a session (0 = skip)")
     ap.add_argument("--tune", type=int, default=0, help="RECD_OPT_TUNE_SEGSUM value (0 = automatic)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates hardware byte counters)")
@@ -243,7 +246,76 @@ def run_workload(torch, recd, synth, w, args, need_backward, detail=True):
         res["sequence"] = sequence_regions(torch, P, cnt, timed, reps, R)
     if getattr(args, "groups", 0) > 0:
         res["grouped"] = grouped_regions(torch, P, timed, reps, args.groups)
+    if getattr(args, "partial", 0.0) > 0.0:
+        res["partial"] = partial_regions(torch, synth, P, timed, reps, args.partial)
     return res, P
+
+
+def partial_regions(torch, synth, P, timed, reps, shift):
+    """Partial IKJTs on batches whose lists slide within a session: the partial builder and the pooled
+    lookup on its windows beside the IKJT builder and lookup on the same batches."""
+    import dataclasses
+    w = dataclasses.replace(P.w, shift=shift)
+    F, B, D = w.F, w.B, w.D
+    nb = min(len(P.batches), 2)
+    batches = [synth.make_batch(w, i) for i in range(nb)]
+    values = [torch.from_numpy(b.values).cuda() for b in batches]
+    offsets = [torch.from_numpy(b.offsets).cuda() for b in batches]
+    i64 = dict(dtype=torch.int64, device="cuda")
+    Nmax = max(b.N for b in batches)
+    pv = [torch.zeros(b.N, **i64) for b in batches]
+    ws = [torch.zeros(F * B, **i64) for _ in batches]
+    wl = [torch.zeros(F * B, **i64) for _ in batches]
+    inv = torch.zeros(F * B, dtype=torch.int32, device="cuda")
+    fu = [torch.zeros(F + 1, **i64) for _ in batches]
+    fp = torch.zeros(F + 1, **i64)
+    uv = [torch.zeros(b.N, **i64) for b in batches]
+    uo = [torch.zeros(F * B + 1, **i64) for _ in batches]
+    fu2 = [torch.zeros(F + 1, **i64) for _ in batches]
+
+    def build_p(i, counts=False):
+        return P.ctx.build_partial_ikjt(F, B, values[i], offsets[i], pv[i], ws[i], wl[i], inv, fu[i], fp,
+                                        None, want_counts=counts)
+
+    def build_i(i, counts=False):
+        return P.ctx.build_ikjt(F, B, values[i], offsets[i], uv[i], uo[i], inv, fu2[i], want_counts=counts)
+
+    cp = [build_p(i, True) for i in range(nb)]
+    ci = [build_i(i, True) for i in range(nb)]
+
+    def look_p(i):
+        P.ctx.pooled_lookup_partial(P.tables, pv[i], ws[i], wl[i], fu[i], cp[i][0], P.pooled)
+
+    def look_i(i):
+        P.ctx.pooled_lookup_unique(P.tables, uv[i], uo[i], fu2[i], ci[i][0], P.pooled)
+
+    def timed_n(fn):   # as `timed`, over this region's batches
+        s_ev, e_ev = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        P.expand(0)
+        s_ev.record()
+        for i in range(nb):
+            fn(i)
+        e_ev.record()
+        torch.cuda.synchronize()
+        return s_ev.elapsed_time(e_ev) / nb
+
+    t = {n: [] for n in ("build_p", "build_i", "look_p", "look_i")}
+    for _ in range(max(reps // 2, 2)):
+        t["build_p"].append(timed_n(build_p))
+        t["build_i"].append(timed_n(build_i))
+        t["look_p"].append(timed_n(look_p))
+        t["look_i"].append(timed_n(look_i))
+    ms = {n: float(np.mean(v)) for n, v in t.items()}
+    for i in range(len(P.batches)):
+        P.build(i)
+    N = float(np.mean([b.N for b in batches]))
+    Pn = float(np.mean([c[1] for c in cp]))
+    M = float(np.mean([c[2] for c in cp]))
+    return {"shift_probability": shift, "N": N, "U": float(np.mean([c[0] for c in cp])), "M_ikjt": M,
+            "P_partial": Pn, "extra_values_removed_fraction_of_N": (M - Pn) / N,
+            "dedupe_factor_ikjt": N / M, "dedupe_factor_partial": N / Pn,
+            "build_partial_ms": ms["build_p"], "build_ikjt_ms": ms["build_i"],
+            "lookup_partial_ms": ms["look_p"], "lookup_ikjt_ms": ms["look_i"]}
 
 
 def grouped_regions(torch, P, timed, reps, k):

@@ -243,3 +243,43 @@ def test_cfg5_grouped_full(recd):
             ref += orc.kjt_pooled_lookup([_host_table(tabs[f], "f32")], "f32", B, v_f, o_f)[0]
         gu.assert_close_f32(gu.out_to_f64(gout[g]), ref, f"group {g} sum")
     ctx.close()
+
+
+def test_cfg5_partial_full(recd):
+    """Configuration 5 with lists that slide within a session (a quarter of the samples shift by one
+    id): every integer output of the partial builder against the oracle, the pooled lookup on the
+    windows bit for bit against the lookup on the IKJT."""
+    w = synth.scaled(synth.WORKLOADS["cfg5"], shift=0.25)
+    F, B, D = w.F, w.B, w.D
+    batch = synth.make_batch(w, 0)
+    tabs = _device_tables(w, torch.float32)
+    ctx = recd.Context(0)
+    values, offsets = gu.to_dev(batch.values), gu.to_dev(batch.offsets)
+    i64 = dict(dtype=torch.int64, device="cuda")
+    p_values = torch.zeros(batch.N, **i64)
+    win_start, win_len = torch.zeros(F * B, **i64), torch.zeros(F * B, **i64)
+    inverse = torch.zeros(F * B, dtype=torch.int32, device="cuda")
+    feat_uoff, feat_poff = torch.zeros(F + 1, **i64), torch.zeros(F + 1, **i64)
+    row_window = torch.zeros(F * B, 2, **i64)
+    U, P, M = ctx.build_partial_ikjt(F, B, values, offsets, p_values, win_start, win_len, inverse,
+                                     feat_uoff, feat_poff, row_window, want_counts=True)
+    pv, ws, wl, inv, fu, fp = orc.build_partial_ikjt(F, B, batch.values, batch.offsets)
+    assert (U, P, M) == (len(ws), len(pv), int(wl.sum())) and P < M
+    assert np.array_equal(p_values[:P].cpu().numpy(), pv)
+    assert np.array_equal(win_start[:U].cpu().numpy(), ws) and np.array_equal(win_len[:U].cpu().numpy(), wl)
+    assert np.array_equal(inverse.cpu().numpy(), inv)
+    assert np.array_equal(feat_uoff.cpu().numpy(), fu) and np.array_equal(feat_poff.cpu().numpy(), fp)
+    assert np.array_equal(row_window.cpu().numpy(), orc.partial_row_windows(F, B, ws, wl, inv, fu))
+    # lossless: every row's window spells the row's list
+    rw = row_window.cpu().numpy()
+    lens = np.diff(batch.offsets)
+    assert np.array_equal(rw[:, 1], lens)
+    idx = np.repeat(rw[:, 0] - batch.offsets[:-1], lens) + np.arange(batch.N)
+    assert np.array_equal(pv[idx], batch.values)
+    pooled = torch.zeros(U, D, device="cuda")
+    ctx.pooled_lookup_partial(tabs, p_values, win_start, win_len, feat_uoff, U, pooled)
+    _, _, ik = gu.gpu_build(ctx, batch)
+    ref = torch.zeros(ik.U, D, device="cuda")
+    ctx.pooled_lookup_unique(tabs, ik.u_values, ik.u_offsets, ik.feat_uoff, ik.U, ref)
+    assert U == ik.U and torch.equal(pooled, ref)
+    ctx.close()
