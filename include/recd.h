@@ -71,7 +71,7 @@ typedef enum {
 
 typedef enum { RECD_F32 = 0, RECD_F16 = 1, RECD_BF16 = 2 } recd_dtype;
 
-/* Pooling functions of an embedding bag (Sec. 2.2: "average, sum, or max"). */
+/* Pooling functions of an embedding bag (Sec. 2.2 names average, sum and max). */
 typedef enum { RECD_POOL_SUM = 0, RECD_POOL_MEAN = 1, RECD_POOL_MAX = 2 } recd_pooling;
 
 typedef enum {

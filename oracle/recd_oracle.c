@@ -87,7 +87,7 @@ int oracle_check_kjt(int F, int64_t B, int64_t N, const int64_t *values, const i
 
 /* ---- KJT -> IKJT (Sec. 4.2 "InverseKeyedJaggedTensor") -------------------------------------
  * Two rows of a feature are duplicates iff their lists have the same length and the same ids in
- * the same order (Sec. 3: "exactly the same list"; exact matches only).  Scanning b upwards, a
+ * the same order (Sec. 3: identical lists; exact matches only).  Scanning b upwards, a
  * row whose list was met before points at that earlier slot; otherwise it opens the next slot
  * and its list is stored once.  Slots are therefore numbered in first-occurrence order, which
  * is what the worked example of feature b shows (rows 0 and 2 both point at offsets[0]).
@@ -301,7 +301,7 @@ int oracle_pooled_lookup(int F, int D, int dtype, const void *const *tables, con
     return 0;
 }
 
-/* ---- the other pooling functions (Sec. 2.2: "average, sum, or max") --------------------------
+/* ---- the other pooling functions (Sec. 2.2 names average, sum and max) --------------------------
  * mode 0 = sum (as oracle_pooled_lookup), 1 = average: the sum divided by the number of ids of the
  * list, 2 = max: element-wise maximum over the list's rows.  An empty list pools to the zero
  * vector in every mode (the convention of the library routine the tests compare with).
