@@ -50,6 +50,9 @@ def parse_args():
     ap.add_argument("--partial", type=float, default=0.0,
                     help="also time the partial IKJT path on the workload with this probability of a "
                          "sample's lists shifting by one id within a session (0 = skip)")
+    ap.add_argument("--reader", action="store_true",
+                    help="also report the builder alone (the conversion step of a reader) beside the CPU "
+                         "oracle's builder run feature-parallel on the host cores")
     ap.add_argument("--tune", type=int, default=0, help="RECD_OPT_TUNE_SEGSUM value (0 = automatic)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates hardware byte counters)")
@@ -452,6 +455,36 @@ def cpu_baseline(torch, synth, P, n_feat):
                       f"build + unique lookup + expand" + (" + backward + Adagrad" if gout is not None else "")}
 
 
+def reader_regions(P, build_ms, max_seconds=20.0):
+    """The KJT -> IKJT conversion alone: the GPU builder's time per batch beside the CPU oracle's
+    builder, one thread per group of features (features are independent; the oracle's C code runs
+    outside the interpreter lock), on as many features of batch 0 as fit the time bound."""
+    import concurrent.futures as cf
+    from oracle import recd_oracle as orc
+    w, b = P.w, P.batches[0]
+    B = w.B
+    cores = min(os.cpu_count() or 1, 16)
+
+    def one(f):
+        lo, hi = int(b.offsets[f * B]), int(b.offsets[(f + 1) * B])
+        orc.build_ikjt(1, B, b.values[lo:hi], b.offsets[f * B:(f + 1) * B + 1] - lo)
+
+    t0 = time.perf_counter()
+    one(0)
+    per_feature = time.perf_counter() - t0
+    n_feat = int(min(w.F, max(cores, cores * (max_seconds / max(per_feature, 1e-6)) // 1)))
+    t0 = time.perf_counter()
+    with cf.ThreadPoolExecutor(max_workers=cores) as ex:
+        list(ex.map(one, range(n_feat)))
+    cpu_s = time.perf_counter() - t0
+    gpu_lists_s = B * w.F / (build_ms * 1e-3)
+    cpu_lists_s = B * n_feat / cpu_s
+    return {"gpu_build_ms": build_ms, "gpu_lists_per_s": gpu_lists_s, "gpu_ids_per_s": b.N / (build_ms * 1e-3),
+            "cpu_oracle_lists_per_s": cpu_lists_s, "cpu_threads": cores,
+            "cpu_sample": f"oracle builder on features 0..{n_feat - 1} of batch 0, {cores} threads",
+            "gpu_over_cpu": gpu_lists_s / cpu_lists_s}
+
+
 def measured_traffic(workload_name):
     """HBM bytes per launch of the unique-lookup kernel, from the committed rocprofv3 --pmc summary
     (FETCH_SIZE and WRITE_SIZE, calibrated against a plain copy); None if there is none."""
@@ -526,6 +559,8 @@ def main():
     }
     if args.cpu_features > 0:
         line["cpu_baseline"] = cpu_baseline(torch, synth, P, args.cpu_features)
+    if args.reader:
+        line["regions"]["reader"] = reader_regions(P, res["build_ms"])
     P.ctx.close()
     del P
     torch.cuda.empty_cache()
