@@ -712,19 +712,19 @@ uint64_t table_cap(int64_t B)
 
 size_t recd_build_workspace(int F, int64_t B)
 {
-    WsCarver c(nullptr);
+    // Covers the three builders (plain, grouped with up to F groups, partial): the hash table, six
+    // int32 and three int64 arrays of one entry per list, the block sums and the small maps, each
+    // rounded up to the carver's 256-byte pieces.
     const int64_t n_lists = (int64_t)F * B;
     const int64_t nblk = (n_lists + kScanBlock - 1) / kScanBlock;
-    c.take<int64_t>(2);
-    c.take<uint64_t>((size_t)F * table_cap(B));
-    c.take<int32_t>(n_lists);
-    c.take<int32_t>(n_lists);
-    c.take<int32_t>(n_lists);
-    c.take<int32_t>(n_lists);
-    c.take<int64_t>(nblk + 1);
-    c.take<int64_t>(nblk + 1);
-    c.take<int64_t>(nblk + 1);
-    return c.off;
+    size_t bytes = 0;
+    bytes += (size_t)F * table_cap(B) * sizeof(uint64_t);
+    bytes += 6 * ((size_t)n_lists * sizeof(int32_t) + 256);
+    bytes += 3 * ((size_t)(n_lists + 1) * sizeof(int64_t) + 256);
+    bytes += 3 * ((size_t)(nblk + 1) * sizeof(int64_t) + 256);
+    bytes += 2 * ((size_t)(F + 2) * sizeof(int64_t) + 256);
+    bytes += 16 * 256;
+    return bytes;
 }
 
 
