@@ -26,7 +26,7 @@ constexpr int kRadixMax = 512;                // digits of up to 9 bits
 constexpr int kScanItems = 16;                // items per thread in the generic scan
 constexpr int kScanTile = 256 * kScanItems;
 
-// ---------------------------------------------------------------- generic exclusive scan (uint32)
+// ---------------------------------------------------------------- block-wide exclusive scan (uint32)
 __device__ __forceinline__ uint32_t block_excl_scan_u32(uint32_t v, uint32_t &total)
 {
     __shared__ uint32_t s_w[16];
@@ -58,23 +58,6 @@ __device__ __forceinline__ int64_t count_of(const int64_t *n_dev, int64_t n_host
     return n_dev ? *n_dev : n_host;
 }
 
-__global__ __launch_bounds__(256) void k_scan_reduce(const uint32_t *__restrict__ data,
-                                                     const int64_t *n_dev, int64_t n_host,
-                                                     uint32_t *__restrict__ bsum)
-{
-    const int64_t n = count_of(n_dev, n_host);
-    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
-    uint32_t s = 0;
-#pragma unroll
-    for (int k = 0; k < kScanItems; k++)
-        if (base + k < n)
-            s += data[base + k];
-    uint32_t total;
-    block_excl_scan_u32(s, total);
-    if (threadIdx.x == 0)
-        bsum[blockIdx.x] = total;
-}
-
 __global__ __launch_bounds__(1024) void k_scan_small(uint32_t *a, int64_t n)
 {
     uint32_t carry = 0;
@@ -87,41 +70,6 @@ __global__ __launch_bounds__(1024) void k_scan_small(uint32_t *a, int64_t n)
             a[i] = carry + e;
         carry += total;
     }
-}
-
-__global__ __launch_bounds__(256) void k_scan_apply(uint32_t *__restrict__ data, const int64_t *n_dev,
-                                                    int64_t n_host, const uint32_t *__restrict__ bsum)
-{
-    const int64_t n = count_of(n_dev, n_host);
-    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
-    uint32_t v[kScanItems], s = 0;
-#pragma unroll
-    for (int k = 0; k < kScanItems; k++) {
-        v[k] = base + k < n ? data[base + k] : 0;
-        s += v[k];
-    }
-    uint32_t total;
-    uint32_t run = bsum[blockIdx.x] + block_excl_scan_u32(s, total);
-#pragma unroll
-    for (int k = 0; k < kScanItems; k++) {
-        if (base + k < n)
-            data[base + k] = run;
-        run += v[k];
-    }
-}
-
-// in-place exclusive scan of data[0..n), n <= n_cap (host bound that sizes the grid)
-recd_status scan_u32(recd_ctx *ctx, hipStream_t st, uint32_t *data, const int64_t *n_dev,
-                     int64_t n_cap, uint32_t *bsum)
-{
-    const int64_t nb = (n_cap + kScanTile - 1) / kScanTile;
-    if (nb == 0)
-        return RECD_OK;
-    hipLaunchKernelGGL(k_scan_reduce, dim3((unsigned)nb), dim3(256), 0, st, data, n_dev, n_cap, bsum);
-    hipLaunchKernelGGL(k_scan_small, dim3(1), dim3(1024), 0, st, bsum, nb);
-    hipLaunchKernelGGL(k_scan_apply, dim3((unsigned)nb), dim3(256), 0, st, data, n_dev, n_cap, bsum);
-    RECD_HIP(ctx, hipGetLastError());
-    return RECD_OK;
 }
 
 // ---------------------------------------------------------------- stable LSD radix sort of pairs
@@ -334,29 +282,49 @@ __global__ __launch_bounds__(256) void k_keys_ids(const int64_t *__restrict__ u_
 }
 
 // ---------------------------------------------------------------- segments of equal keys
+// A head is an element whose key differs from its predecessor's (or the first element).  Numbering
+// the heads is an exclusive scan of the head flags; the flags are recomputed from the keys where
+// they are needed instead of being stored: k_head_count (heads per tile) -> k_scan_small (tile
+// offsets) -> k_segments (segment number of every head, and what hangs on it).
 template <typename KeyT>
-__global__ void k_heads(const KeyT *__restrict__ keys, const int64_t *n_dev, uint32_t *__restrict__ flag,
-                        int64_t *long_count)
+__global__ __launch_bounds__(256) void k_head_count(const KeyT *__restrict__ keys, const int64_t *n_dev,
+                                                    uint32_t *__restrict__ bsum, int64_t *long_count)
 {
     const int64_t n = *n_dev;
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         long_count[0] = 0;
         long_count[1] = 0;
     }
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
-         i += (int64_t)gridDim.x * blockDim.x)
-        flag[i] = (i == 0 || keys[i] != keys[i - 1]) ? 1u : 0u;
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+    KeyT prev = (base > 0 && base <= n) ? keys[base - 1] : (KeyT)0;
+    uint32_t s = 0;
+#pragma unroll
+    for (int k = 0; k < kScanItems; k++) {
+        const int64_t i = base + k;
+        if (i < n) {
+            const KeyT key = keys[i];
+            s += (i == 0 || key != prev) ? 1u : 0u;
+            prev = key;
+        }
+    }
+    uint32_t total;
+    block_excl_scan_u32(s, total);
+    if (threadIdx.x == 0)
+        bsum[blockIdx.x] = total;
 }
 
-// segidx = exclusive scan of the head flags.  Heads record where their segment starts; the last
-// element closes the list (seg_start[R] = n, list_off = {0, R}).  With row_bits >= 0 the key is
-// (feature, row): also emit the row ids and the per-feature prefix of distinct-row counts.
+// bsum holds the exclusive scan of the per-tile head counts.  Heads record where their segment
+// starts; the last element closes the list (seg_start[R] = n, list_off = {0, R}).  With
+// row_bits >= 0 the key is (feature, row): also emit the row ids, the feature of every segment and
+// the per-feature prefix of distinct-row counts.
 template <typename KeyT>
-__global__ void k_segments(const KeyT *__restrict__ keys, const int64_t *n_dev,
-                           const uint32_t *__restrict__ segidx, int64_t *__restrict__ seg_start,
-                           int64_t *__restrict__ list_off, int row_bits, int F,
-                           int64_t *__restrict__ touched_rows, int64_t *__restrict__ feat_roff,
-                           int32_t *__restrict__ seg_feat)
+__global__ __launch_bounds__(256) void k_segments(const KeyT *__restrict__ keys, const int64_t *n_dev,
+                                                  const uint32_t *__restrict__ bsum,
+                                                  int64_t *__restrict__ seg_start,
+                                                  int64_t *__restrict__ list_off, int row_bits, int F,
+                                                  int64_t *__restrict__ touched_rows,
+                                                  int64_t *__restrict__ feat_roff,
+                                                  int32_t *__restrict__ seg_feat)
 {
     const int64_t n = *n_dev;
     if (n == 0) {
@@ -370,31 +338,53 @@ __global__ void k_segments(const KeyT *__restrict__ keys, const int64_t *n_dev,
         }
         return;
     }
-    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
-         i += (int64_t)gridDim.x * blockDim.x) {
-        const bool head = i == 0 || keys[i] != keys[i - 1];
-        const int64_t sidx = segidx[i];  // for a head: its segment number; else that number + 1
-        if (head) {
-            seg_start[sidx] = i;
-            if (row_bits >= 0) {
-                touched_rows[sidx] = (int64_t)(keys[i] & (((KeyT)1 << row_bits) - 1));
-                const int f = (int)(keys[i] >> row_bits);
-                seg_feat[sidx] = f;
-                const int fprev = i == 0 ? -1 : (int)(keys[i - 1] >> row_bits);
-                for (int ff = fprev + 1; ff <= f; ff++)
-                    feat_roff[ff] = sidx;
-            }
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+    const KeyT before = (base > 0 && base <= n) ? keys[base - 1] : (KeyT)0;
+    KeyT key[kScanItems];
+    uint32_t s = 0;
+    {
+        KeyT prev = before;
+#pragma unroll
+        for (int k = 0; k < kScanItems; k++) {
+            const int64_t i = base + k;
+            key[k] = i < n ? keys[i] : (KeyT)0;
+            if (i < n)
+                s += (i == 0 || key[k] != prev) ? 1u : 0u;
+            prev = key[k];
         }
-        if (i == n - 1) {
-            const int64_t R = sidx + (head ? 1 : 0);
-            seg_start[R] = n;
-            list_off[0] = 0;
-            list_off[1] = R;
-            if (row_bits >= 0) {
-                const int f = (int)(keys[i] >> row_bits);
-                for (int ff = f + 1; ff <= F; ff++)
-                    feat_roff[ff] = R;
+    }
+    uint32_t total;
+    int64_t sidx = (int64_t)bsum[blockIdx.x] + block_excl_scan_u32(s, total);  // heads before `base`
+    KeyT prev = before;
+#pragma unroll
+    for (int k = 0; k < kScanItems; k++) {
+        const int64_t i = base + k;
+        if (i < n) {
+            const bool head = i == 0 || key[k] != prev;
+            if (head) {
+                seg_start[sidx] = i;
+                if (row_bits >= 0) {
+                    touched_rows[sidx] = (int64_t)(key[k] & (((KeyT)1 << row_bits) - 1));
+                    const int f = (int)(key[k] >> row_bits);
+                    seg_feat[sidx] = f;
+                    const int fprev = i == 0 ? -1 : (int)(prev >> row_bits);
+                    for (int ff = fprev + 1; ff <= f; ff++)
+                        feat_roff[ff] = sidx;
+                }
             }
+            if (i == n - 1) {
+                const int64_t R = sidx + (head ? 1 : 0);
+                seg_start[R] = n;
+                list_off[0] = 0;
+                list_off[1] = R;
+                if (row_bits >= 0) {
+                    const int f = (int)(key[k] >> row_bits);
+                    for (int ff = f + 1; ff <= F; ff++)
+                        feat_roff[ff] = R;
+                }
+            }
+            sidx += head ? 1 : 0;
+            prev = key[k];
         }
     }
 }
@@ -532,7 +522,36 @@ __device__ __forceinline__ void finish_segment(const RowSumParams &p, const OptA
     }
 }
 
-// FINALIZE = false: segments of at most 64 entries are summed here, longer ones are cut into chunks.
+// Segments longer than 64 entries are cut into chunks of 256 entries, or larger ones if that would
+// give more than 64 chunks.  The cut depends on the segment's length only; the order in which
+// segments and chunks are listed does not matter for the sums.
+__global__ __launch_bounds__(256) void k_find_long(const RowSumParams p)
+{
+    const int64_t R = *p.n_seg;
+    for (int64_t k = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; k < R;
+         k += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t start = p.seg_start[k], end = p.seg_start[k + 1];
+        const int64_t len = end - start;
+        if (len <= 64)
+            continue;
+        int64_t ch = 256;
+        if ((len + ch - 1) / ch > 64)
+            ch = (len + 63) / 64;
+        const int nch = (int)((len + ch - 1) / ch);
+        const int64_t first = (int64_t)atomicAdd(reinterpret_cast<unsigned long long *>(p.long_count + 1),
+                                                 (unsigned long long)nch);
+        const int64_t slot = (int64_t)atomicAdd(reinterpret_cast<unsigned long long *>(p.long_count), 1ull);
+        p.lseg_t[slot] = (int32_t)k;
+        p.lseg_first[slot] = (int32_t)first;
+        p.lseg_n[slot] = nch;
+        for (int c = 0; c < nch; c++) {
+            p.item_start[first + c] = start + c * ch;
+            p.item_end[first + c] = start + (c + 1) * ch < end ? start + (c + 1) * ch : end;
+        }
+    }
+}
+
+// FINALIZE = false: segments of at most 64 entries are summed here (longer ones are skipped).
 // FINALIZE = true: the "segments" are the cut ones; their entries are the chunk partial sums, in
 // chunk order.
 template <int LPR, bool FINALIZE>
@@ -563,26 +582,7 @@ __global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const
                 start = p.seg_start[k];
                 const int64_t end = p.seg_start[k + 1];
                 const int64_t len = end - start;
-                if (len <= 64) {
-                    n = (int)len;
-                } else if (r == 0) {
-                    // chunks of 256 entries, or larger ones if that would give more than 64 chunks
-                    int64_t ch = 256;
-                    if ((len + ch - 1) / ch > 64)
-                        ch = (len + 63) / 64;
-                    const int nch = (int)((len + ch - 1) / ch);
-                    const int64_t first = (int64_t)atomicAdd(
-                        reinterpret_cast<unsigned long long *>(p.long_count + 1), (unsigned long long)nch);
-                    const int64_t slot =
-                        (int64_t)atomicAdd(reinterpret_cast<unsigned long long *>(p.long_count), 1ull);
-                    p.lseg_t[slot] = (int32_t)k;
-                    p.lseg_first[slot] = (int32_t)first;
-                    p.lseg_n[slot] = nch;
-                    for (int c = 0; c < nch; c++) {
-                        p.item_start[first + c] = start + c * ch;
-                        p.item_end[first + c] = start + (c + 1) * ch < end ? start + (c + 1) * ch : end;
-                    }
-                }
+                n = len <= 64 ? (int)len : 0;  // longer segments were cut into chunks by k_find_long
             }
         }
         const bool mine = n > 0;  // uniform inside the lane group
@@ -664,7 +664,6 @@ struct SortSet {
 struct BwdWs {
     SortSet a, b;
     int64_t *list_off, *seg_start;
-    uint32_t *flag;
     int32_t *seg_feat, *lseg_t, *lseg_first, *lseg_n;
     int64_t *long_count, *item_start, *item_end;
     float *g_u, *partials;
@@ -702,7 +701,6 @@ BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D)
     w.b = carve_sort(c, M_cap, true);
     w.list_off = c.take<int64_t>(2);
     w.seg_start = c.take<int64_t>(n_max + 1);
-    w.flag = c.take<uint32_t>(n_max);
     w.seg_feat = c.take<int32_t>(n_max);
     // segments longer than 64 entries: at most n/65 of them, cut into at most n/256 + n/65 chunks
     const int64_t lseg_cap = n_max / 65 + 16, item_cap = n_max / 256 + n_max / 65 + 16;
@@ -726,12 +724,11 @@ recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, c
                             int64_t *feat_roff, const OptAdagrad *opt)
 {
     hipStream_t st = ctx->stream;
-    int blocks = (int)((n_cap + 255) / 256 < 2048 ? (n_cap + 255) / 256 : 2048);
-    if (blocks < 1)
-        blocks = 1;
-    hipLaunchKernelGGL((k_heads<KeyT>), dim3(blocks), dim3(256), 0, st, ks, set.n_dev, w.flag, w.long_count);
-    RECD_TRY(scan_u32(ctx, st, w.flag, set.n_dev, n_cap, set.bsum));
-    hipLaunchKernelGGL((k_segments<KeyT>), dim3(blocks), dim3(256), 0, st, ks, set.n_dev, w.flag,
+    const unsigned tiles = (unsigned)((n_cap + kScanTile - 1) / kScanTile > 0 ? (n_cap + kScanTile - 1) / kScanTile : 1);
+    hipLaunchKernelGGL((k_head_count<KeyT>), dim3(tiles), dim3(256), 0, st, ks, set.n_dev, set.bsum,
+                       w.long_count);
+    hipLaunchKernelGGL(k_scan_small, dim3(1), dim3(1024), 0, st, set.bsum, (int64_t)tiles);
+    hipLaunchKernelGGL((k_segments<KeyT>), dim3(tiles), dim3(256), 0, st, ks, set.n_dev, set.bsum,
                        w.seg_start, w.list_off, row_bits, F, touched_rows, feat_roff, w.seg_feat);
     RECD_HIP(ctx, hipGetLastError());
     SegSumArgs a{};
@@ -783,21 +780,29 @@ recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, c
         if (nblk < 1)
             nblk = 1;
         const dim3 block(256);
-        auto launch_rows = [&](auto fin, unsigned nb) {
+        auto launch_rows = [&](auto fin, unsigned nb, hipStream_t stream) {
             constexpr bool FIN = decltype(fin)::value;
             const dim3 grid(nb);
             switch (lpr) {
-            case 4: hipLaunchKernelGGL((k_segsum_rows<4, FIN>), grid, block, 0, st, rp, o); break;
-            case 8: hipLaunchKernelGGL((k_segsum_rows<8, FIN>), grid, block, 0, st, rp, o); break;
-            case 16: hipLaunchKernelGGL((k_segsum_rows<16, FIN>), grid, block, 0, st, rp, o); break;
-            case 32: hipLaunchKernelGGL((k_segsum_rows<32, FIN>), grid, block, 0, st, rp, o); break;
-            default: hipLaunchKernelGGL((k_segsum_rows<64, FIN>), grid, block, 0, st, rp, o); break;
+            case 4: hipLaunchKernelGGL((k_segsum_rows<4, FIN>), grid, block, 0, stream, rp, o); break;
+            case 8: hipLaunchKernelGGL((k_segsum_rows<8, FIN>), grid, block, 0, stream, rp, o); break;
+            case 16: hipLaunchKernelGGL((k_segsum_rows<16, FIN>), grid, block, 0, stream, rp, o); break;
+            case 32: hipLaunchKernelGGL((k_segsum_rows<32, FIN>), grid, block, 0, stream, rp, o); break;
+            default: hipLaunchKernelGGL((k_segsum_rows<64, FIN>), grid, block, 0, stream, rp, o); break;
             }
         };
-        // 1. short segments summed and updated; long ones cut into chunks
-        launch_rows(std::false_type(), (unsigned)nblk);
+        // 1. long segments cut into chunks (a short pass over the segment starts)
+        int64_t fblk = (seg_bound + 255) / 256;
+        if (fblk > (int64_t)ctx->num_cu * 8)
+            fblk = (int64_t)ctx->num_cu * 8;
+        hipLaunchKernelGGL(k_find_long, dim3((unsigned)(fblk < 1 ? 1 : fblk)), dim3(256), 0, st, rp);
         RECD_HIP(ctx, hipGetLastError());
-        // 2. partial sum of every chunk (block-cooperative gather-sum, one block per chunk)
+        // 2. on the side stream, next to 3: partial sum of every chunk (block-cooperative
+        //    gather-sum, one block per chunk), then the chunk partials added in chunk order and the
+        //    same update / store as for short segments.  Long and short segments name different rows.
+        hipStream_t side = ctx->side_stream;
+        RECD_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
+        RECD_HIP(ctx, hipStreamWaitEvent(side, ctx->ev_fork, 0));
         SegSumArgs c = a;
         c.offsets = w.item_start;
         c.ends = w.item_end;
@@ -806,10 +811,15 @@ recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, c
         c.lists_per_feature = 0;
         c.lists_bound = n_cap / 256 + n_cap / 65 + 1;
         c.out = w.partials;
+        c.stream = side;
         RECD_TRY(recd_launch_segsum(ctx, c));
-        // 3. chunk partials added in chunk order, then the same update / store as in 1
-        launch_rows(std::true_type(), (unsigned)ctx->num_cu);
+        launch_rows(std::true_type(), (unsigned)ctx->num_cu, side);
         RECD_HIP(ctx, hipGetLastError());
+        RECD_HIP(ctx, hipEventRecord(ctx->ev_join, side));
+        // 3. short segments summed and updated
+        launch_rows(std::false_type(), (unsigned)nblk, st);
+        RECD_HIP(ctx, hipGetLastError());
+        RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
         return RECD_OK;
     }
     return recd_launch_segsum(ctx, a);

@@ -95,6 +95,7 @@ struct SegSumArgs {
     int site;                 // RECD_SITE_*: which call site (each has its own kernel instantiation)
     int mode;                 // recd_pooling (forward sites only; 0 = sum)
     void *out;                // [lists, D]
+    hipStream_t stream;       // nullptr: the context's stream
 };
 recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a);
 recd_status recd_validate_inverse(recd_ctx *ctx, int F, int64_t B, const int64_t *feat_uoff,

@@ -617,7 +617,7 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
         nblk = (int64_t)ctx->num_cu * 8;
     const int blocks = (int)nblk;
     bool ok = false;
-    hipStream_t st = ctx->stream;
+    hipStream_t st = a.stream ? a.stream : ctx->stream;
     const int v = p.vecs_per_row;
     const bool fwd = !a.values_are_i32;
     if (a.site == RECD_SITE_UNIQUE && fwd && a.mode == POOL_SUM)
