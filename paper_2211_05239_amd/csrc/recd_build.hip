@@ -803,7 +803,7 @@ namespace {
 struct GroupedWs {
     int64_t *counts, *counts_g;
     uint64_t *table;
-    int32_t *slot_of, *rep_g, *number_g, *src_g, *src_of, *group_off, *feat_group;
+    int32_t *slot_of, *rep_g, *number_g, *src_g, *src_of;
     int64_t *zero_off, *u_tmp, *bs_cnt, *bs_len, *bs_head;
 };
 GroupedWs carve_grouped(char *base, int F, int G, int64_t B, size_t *bytes)
@@ -820,8 +820,6 @@ GroupedWs carve_grouped(char *base, int F, int G, int64_t B, size_t *bytes)
     w.number_g = c.take<int32_t>(n_items);
     w.src_g = c.take<int32_t>(n_items);
     w.src_of = c.take<int32_t>(n_lists);
-    w.group_off = c.take<int32_t>(G + 1);
-    w.feat_group = c.take<int32_t>(F + 1);
     w.zero_off = c.take<int64_t>(n_items + 1);
     w.u_tmp = c.take<int64_t>(n_items + 1);
     w.bs_cnt = c.take<int64_t>(nblk + 1);
@@ -868,19 +866,8 @@ extern "C" recd_status recd_build_ikjt_grouped(recd_ctx *ctx, int F, int64_t B, 
         hipLaunchKernelGGL(k_empty_grouped, dim3(1), dim3(256), 0, st, F, G, u_offsets, feat_uoff,
                            group_uoff, w.counts, w.counts_g);
     } else {
-        // group boundaries and the group of every feature, staged through pageable host memory (the
-        // runtime copies it before the call returns)
-        int32_t host_map[2 * RECD_MAX_FEATURES + 2];
-        for (int g = 0; g <= G; g++)
-            host_map[g] = group_off[g];
-        for (int g = 0; g < G; g++)
-            for (int f = group_off[g]; f < group_off[g + 1]; f++)
-                host_map[G + 1 + f] = g;
-        RECD_HIP(ctx, hipMemcpyAsync(w.group_off, host_map, sizeof(int32_t) * (G + 1),
-                                     hipMemcpyHostToDevice, st));
-        RECD_HIP(ctx, hipMemcpyAsync(w.feat_group, host_map + G + 1, sizeof(int32_t) * F,
-                                     hipMemcpyHostToDevice, st));
-        RECD_HIP(ctx, hipStreamSynchronize(st));  // host_map lives on this stack frame
+        const int32_t *dev_group_off = nullptr, *dev_feat_group = nullptr;
+        RECD_TRY(recd_group_map(ctx, F, G, group_off, &dev_group_off, &dev_feat_group));
         constexpr int SG = 8;
         const uint64_t cap = table_cap(B);
         const int64_t tab_n = (int64_t)G * (int64_t)cap;
@@ -891,7 +878,7 @@ extern "C" recd_status recd_build_ikjt_grouped(recd_ctx *ctx, int F, int64_t B, 
                            reinterpret_cast<uint64_t *>(w.zero_off), n_items + 1, 0ull);
         const int64_t hblocks = (n_items + (256 / SG) - 1) / (256 / SG);
         hipLaunchKernelGGL((k_group_hash_insert<SG>), dim3((unsigned)hblocks), dim3(256), 0, st, values,
-                           offsets, B, n_items, w.group_off, w.table, (uint32_t)(cap - 1), w.slot_of,
+                           offsets, B, n_items, dev_group_off, w.table, (uint32_t)(cap - 1), w.slot_of,
                            ctx->weak_hash);
         // numbering of the slots per group: the list-level kernels with the groups in the role of
         // features and lists of length zero
@@ -910,12 +897,12 @@ extern "C" recd_status recd_build_ikjt_grouped(recd_ctx *ctx, int F, int64_t B, 
         // per feature: which lists are stored, where
         const int64_t nblk = (n_lists + kScanBlock - 1) / kScanBlock;
         hipLaunchKernelGGL((k_group_compact<false>), dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets,
-                           B, n_lists, F, w.feat_group, w.rep_g, inverse_g, w.bs_cnt, w.bs_len, w.bs_head,
+                           B, n_lists, F, dev_feat_group, w.rep_g, inverse_g, w.bs_cnt, w.bs_len, w.bs_head,
                            w.src_of, u_offsets, feat_uoff, inverse_per_feature, w.counts);
         hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(kScanBlock), 0, st, w.bs_cnt, w.bs_len, w.bs_head,
                            nblk);
         hipLaunchKernelGGL((k_group_compact<true>), dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets,
-                           B, n_lists, F, w.feat_group, w.rep_g, inverse_g, w.bs_cnt, w.bs_len, w.bs_head,
+                           B, n_lists, F, dev_feat_group, w.rep_g, inverse_g, w.bs_cnt, w.bs_len, w.bs_head,
                            w.src_of, u_offsets, feat_uoff, inverse_per_feature, w.counts);
         int64_t copy_blocks = (n_lists + (256 / 16) - 1) / (256 / 16);
         if (copy_blocks > (int64_t)ctx->num_cu * 8)

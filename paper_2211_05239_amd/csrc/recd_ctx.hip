@@ -38,6 +38,30 @@ recd_status recd_reserve(recd_ctx *ctx, size_t bytes)
     return RECD_OK;
 }
 
+recd_status recd_group_map(recd_ctx *ctx, int F, int G, const int32_t *group_off,
+                           const int32_t **dev_group_off, const int32_t **dev_feat_group)
+{
+    constexpr int kHalf = RECD_MAX_FEATURES + 1;
+    std::vector<int32_t> map(2 * kHalf, 0);
+    for (int g = 0; g <= G; g++)
+        map[g] = group_off[g];
+    for (int g = 0; g < G; g++)
+        for (int f = group_off[g]; f < group_off[g + 1] && f < F; f++)
+            map[kHalf + f] = g;
+    if (!ctx->group_map_dev)
+        RECD_HIP(ctx, hipMalloc(reinterpret_cast<void **>(&ctx->group_map_dev), sizeof(int32_t) * 2 * kHalf));
+    if (map != ctx->group_map_host) {
+        // earlier calls on either stream may still read the old map
+        RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        RECD_HIP(ctx, hipMemcpy(ctx->group_map_dev, map.data(), sizeof(int32_t) * 2 * kHalf,
+                                hipMemcpyHostToDevice));
+        ctx->group_map_host.swap(map);
+    }
+    *dev_group_off = ctx->group_map_dev;
+    *dev_feat_group = ctx->group_map_dev + kHalf;
+    return RECD_OK;
+}
+
 extern "C" {
 
 const char *recd_status_string(recd_status s)
@@ -105,6 +129,8 @@ recd_status recd_destroy(recd_ctx *ctx)
         (void)hipEventDestroy(ctx->ev_join);
     if (ctx->ws)
         (void)hipFree(ctx->ws);
+    if (ctx->group_map_dev)
+        (void)hipFree(ctx->group_map_dev);
     if (ctx->host_pinned)
         (void)hipHostFree(ctx->host_pinned);
     delete ctx;

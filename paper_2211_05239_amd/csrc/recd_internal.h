@@ -5,6 +5,7 @@
 #include <stdint.h>
 #include <stdio.h>
 #include <string>
+#include <vector>
 
 #include "recd.h"
 
@@ -20,6 +21,10 @@ struct recd_ctx {
     int weak_hash = 0;
     int tune_lb = 0, tune_gens = 0, tune_flat = 0;  // launch-shape overrides of the gather-sum kernel (0 = automatic)
     int num_cu = 256;
+    // feature groups of the last grouped call, kept on the device: [0, G] boundaries, then the
+    // group of every feature from RECD_MAX_FEATURES + 1 on
+    int32_t *group_map_dev = nullptr;
+    std::vector<int32_t> group_map_host;
     std::string err;
 };
 
@@ -106,3 +111,7 @@ recd_status recd_validate_kjt_lists(recd_ctx *ctx, int F, int64_t B, int64_t N, 
 recd_status recd_validate_unique_lists(recd_ctx *ctx, int F, const int64_t *rows,
                                        const int64_t *u_values, const int64_t *u_offsets,
                                        const int64_t *feat_uoff, int64_t max_lists, int64_t M_cap);
+// Device copies of group_off[0..G] and of the group of every feature; copied (with a stream
+// synchronisation) only when the grouping differs from the previous call's.
+recd_status recd_group_map(recd_ctx *ctx, int F, int G, const int32_t *group_off,
+                           const int32_t **dev_group_off, const int32_t **dev_feat_group);

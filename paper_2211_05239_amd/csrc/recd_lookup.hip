@@ -929,11 +929,8 @@ recd_status recd_group_sum_unique(recd_ctx *ctx, int F, int G, int D, recd_dtype
     if (!pooled || !feat_uoff || !group_uoff || !combined)
         return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
     RECD_HIP(ctx, hipSetDevice(ctx->device));
-    RECD_TRY(recd_reserve(ctx, 256 + sizeof(int32_t) * (RECD_MAX_FEATURES + 1)));
-    int32_t *go_dev = reinterpret_cast<int32_t *>(ctx->ws);
-    RECD_HIP(ctx, hipMemcpyAsync(go_dev, group_off, sizeof(int32_t) * (G + 1), hipMemcpyHostToDevice,
-                                 ctx->stream));
-    RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));  // group_off is the caller's memory
+    const int32_t *go_dev = nullptr, *fg_dev = nullptr;
+    RECD_TRY(recd_group_map(ctx, F, G, group_off, &go_dev, &fg_dev));
     const int vecs = (int)((size_t)D * elem_size(dt) / 16);
     if (vecs > kBlock)
         return recd_fail(ctx, RECD_EINVAL, "row too long");
