@@ -727,6 +727,82 @@ size_t recd_build_workspace(int F, int64_t B)
     return bytes;
 }
 
+namespace {
+
+// Workspace of the slot search: hash table, per-item slot / representative / number / first row of
+// every slot, block sums of the scans.  `items` = lists (features x B) or group rows (groups x B).
+struct SlotWs {
+    int64_t *counts;
+    uint64_t *table;
+    uint64_t cap;
+    int32_t *slot_of, *rep, *number, *src_of;
+    int64_t *bs_cnt, *bs_len, *bs_head;
+};
+
+SlotWs carve_slots(WsCarver &c, int tables, int64_t B, int64_t items, int64_t scan_items)
+{
+    SlotWs w;
+    const int64_t nblk = (scan_items + kScanBlock - 1) / kScanBlock;
+    w.cap = table_cap(B);
+    w.counts = c.take<int64_t>(4);
+    w.table = c.take<uint64_t>((size_t)tables * w.cap);
+    w.slot_of = c.take<int32_t>(items);
+    w.rep = c.take<int32_t>(items);
+    w.number = c.take<int32_t>(items);
+    w.src_of = c.take<int32_t>(items);
+    w.bs_cnt = c.take<int64_t>(nblk + 1);
+    w.bs_len = c.take<int64_t>(nblk + 1);
+    w.bs_head = c.take<int64_t>(nblk + 1);
+    return w;
+}
+
+void clear_table(hipStream_t st, const SlotWs &w, int tables)
+{
+    const int64_t tab_n = (int64_t)tables * (int64_t)w.cap;
+    const int fill_blocks = (int)((tab_n + 1023) / 1024 < 4096 ? (tab_n + 1023) / 1024 : 4096);
+    hipLaunchKernelGGL(k_fill_u64, dim3(fill_blocks), dim3(256), 0, st, w.table, tab_n, kEmpty);
+}
+
+// Lists of a KJT into the per-feature tables: slot_of[l] (or -1 for a follower).
+void insert_lists(recd_ctx *ctx, hipStream_t st, const SlotWs &w, int F, int64_t B,
+                  const int64_t *values, const int64_t *offsets)
+{
+    constexpr int SG = 8;
+    const int64_t n_lists = (int64_t)F * B;
+    clear_table(st, w, F);
+    const int64_t hblocks = (n_lists + (256 / SG) * kLPG - 1) / ((256 / SG) * kLPG);
+    hipLaunchKernelGGL((k_hash_insert<SG>), dim3((unsigned)hblocks), dim3(256), 0, st, values, offsets, B,
+                       n_lists, w.table, (uint32_t)(w.cap - 1), w.slot_of, ctx->weak_hash);
+}
+
+// After the insertion: representative and first-occurrence number of every item, first row of
+// every slot, prefix of the slot counts per table (uoff) and, from the lengths that `offsets`
+// gives, the position of every slot's ids (u_off); counts = {slots, ids}.
+void number_slots(hipStream_t st, const SlotWs &w, int tables, int64_t B, const int64_t *offsets,
+                  int64_t *u_off, int64_t *uoff)
+{
+    const int64_t n = (int64_t)tables * B;
+    const unsigned nblk = (unsigned)((n + kScanBlock - 1) / kScanBlock);
+    const uint32_t mask = (uint32_t)(w.cap - 1);
+    hipLaunchKernelGGL(k_flags, dim3(nblk), dim3(kScanBlock), 0, st, offsets, B, n, w.table, mask, w.slot_of,
+                       w.bs_cnt, w.bs_len, w.bs_head);
+    hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(kScanBlock), 0, st, w.bs_cnt, w.bs_len, w.bs_head,
+                       (int64_t)nblk);
+    hipLaunchKernelGGL(k_number, dim3(nblk), dim3(kScanBlock), 0, st, offsets, B, n, tables, w.table, mask,
+                       w.slot_of, w.bs_cnt, w.bs_len, w.bs_head, w.rep, w.number, w.src_of, u_off, uoff,
+                       w.counts);
+}
+
+unsigned copy_blocks_for(const recd_ctx *ctx, int64_t n_lists)
+{
+    int64_t b = (n_lists + (256 / 16) - 1) / (256 / 16);
+    if (b > (int64_t)ctx->num_cu * 8)
+        b = (int64_t)ctx->num_cu * 8;
+    return (unsigned)b;
+}
+
+} // namespace
+
 
 extern "C" recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t N,
                                        const int64_t *values, const int64_t *offsets,
@@ -749,43 +825,19 @@ extern "C" recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t 
 
     RECD_TRY(recd_reserve(ctx, recd_build_workspace(F, B)));
     WsCarver c(ctx->ws);
-    const int64_t nblk = (n_lists + kScanBlock - 1) / kScanBlock;
-    const uint64_t cap = table_cap(B);
-    int64_t *counts = c.take<int64_t>(2);
-    uint64_t *table = c.take<uint64_t>((size_t)F * cap);
-    int32_t *slot_of = c.take<int32_t>(n_lists);
-    int32_t *rep = c.take<int32_t>(n_lists);
-    int32_t *number = c.take<int32_t>(n_lists);
-    int32_t *src_of = c.take<int32_t>(n_lists);
-    int64_t *bs_cnt = c.take<int64_t>(nblk + 1);
-    int64_t *bs_len = c.take<int64_t>(nblk + 1);
-    int64_t *bs_head = c.take<int64_t>(nblk + 1);
+    const SlotWs w = carve_slots(c, F, B, n_lists, n_lists);
+    int64_t *counts = w.counts;
     hipStream_t st = ctx->stream;
 
     if (n_lists == 0) {
         hipLaunchKernelGGL(k_empty_ikjt, dim3(1), dim3(256), 0, st, F, u_offsets, feat_uoff, counts);
     } else {
-        constexpr int SG = 8;
-        const int64_t tab_n = (int64_t)F * (int64_t)cap;
-        int fill_blocks = (int)((tab_n + 1023) / 1024 < 4096 ? (tab_n + 1023) / 1024 : 4096);
-        hipLaunchKernelGGL(k_fill_u64, dim3(fill_blocks), dim3(256), 0, st, table, tab_n, kEmpty);
-        const int64_t hblocks = (n_lists + (256 / SG) * kLPG - 1) / ((256 / SG) * kLPG);
-        hipLaunchKernelGGL((k_hash_insert<SG>), dim3((unsigned)hblocks), dim3(256), 0, st, values,
-                           offsets, B, n_lists, table, (uint32_t)(cap - 1), slot_of, ctx->weak_hash);
-        hipLaunchKernelGGL(k_flags, dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets, B, n_lists,
-                           table, (uint32_t)(cap - 1), slot_of, bs_cnt, bs_len, bs_head);
-        hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(kScanBlock), 0, st, bs_cnt, bs_len, bs_head,
-                           nblk);
-        hipLaunchKernelGGL(k_number, dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets, B, n_lists,
-                           F, table, (uint32_t)(cap - 1), slot_of, bs_cnt, bs_len, bs_head, rep, number,
-                           src_of, u_offsets, feat_uoff, counts);
+        insert_lists(ctx, st, w, F, B, values, offsets);
+        number_slots(st, w, F, B, offsets, u_offsets, feat_uoff);
         const unsigned inv_blocks = (unsigned)((n_lists + 255) / 256);
-        int64_t copy_blocks = (n_lists + (256 / 16) - 1) / (256 / 16);
-        if (copy_blocks > (int64_t)ctx->num_cu * 8)
-            copy_blocks = (int64_t)ctx->num_cu * 8;
-        hipLaunchKernelGGL((k_emit<16>), dim3(inv_blocks + (unsigned)copy_blocks), dim3(256), 0, st, values,
-                           offsets, B, n_lists, rep, number, src_of, u_offsets, counts, u_values, inverse,
-                           inv_blocks);
+        hipLaunchKernelGGL((k_emit<16>), dim3(inv_blocks + copy_blocks_for(ctx, n_lists)), dim3(256), 0, st,
+                           values, offsets, B, n_lists, w.rep, w.number, w.src_of, u_offsets, counts,
+                           u_values, inverse, inv_blocks);
     }
     RECD_HIP(ctx, hipGetLastError());
     if (host_U_M) {
@@ -798,37 +850,6 @@ extern "C" recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t 
     return RECD_OK;
 }
 
-
-namespace {
-struct GroupedWs {
-    int64_t *counts, *counts_g;
-    uint64_t *table;
-    int32_t *slot_of, *rep_g, *number_g, *src_g, *src_of;
-    int64_t *zero_off, *u_tmp, *bs_cnt, *bs_len, *bs_head;
-};
-GroupedWs carve_grouped(char *base, int F, int G, int64_t B, size_t *bytes)
-{
-    WsCarver c(base);
-    GroupedWs w;
-    const int64_t n_items = (int64_t)G * B, n_lists = (int64_t)F * B;
-    const int64_t nblk = (n_lists + kScanBlock - 1) / kScanBlock;
-    w.counts = c.take<int64_t>(2);
-    w.counts_g = c.take<int64_t>(2);
-    w.table = c.take<uint64_t>((size_t)G * table_cap(B));
-    w.slot_of = c.take<int32_t>(n_items);
-    w.rep_g = c.take<int32_t>(n_items);
-    w.number_g = c.take<int32_t>(n_items);
-    w.src_g = c.take<int32_t>(n_items);
-    w.src_of = c.take<int32_t>(n_lists);
-    w.zero_off = c.take<int64_t>(n_items + 1);
-    w.u_tmp = c.take<int64_t>(n_items + 1);
-    w.bs_cnt = c.take<int64_t>(nblk + 1);
-    w.bs_len = c.take<int64_t>(nblk + 1);
-    w.bs_head = c.take<int64_t>(nblk + 1);
-    *bytes = c.off;
-    return w;
-}
-} // namespace
 
 extern "C" recd_status recd_build_ikjt_grouped(recd_ctx *ctx, int F, int64_t B, int64_t N, int G,
                                                const int32_t *group_off, const int64_t *values,
@@ -857,65 +878,54 @@ extern "C" recd_status recd_build_ikjt_grouped(recd_ctx *ctx, int F, int64_t B, 
     if (ctx->validate && n_lists > 0)
         RECD_TRY(recd_validate_kjt_offsets(ctx, F, B, N, offsets));
 
-    size_t bytes = 0;
-    carve_grouped(nullptr, F, G, B, &bytes);
-    RECD_TRY(recd_reserve(ctx, bytes));
-    const GroupedWs w = carve_grouped(ctx->ws, F, G, B, &bytes);
+    RECD_TRY(recd_reserve(ctx, recd_build_workspace(F, B)));
+    WsCarver c(ctx->ws);
+    const SlotWs w = carve_slots(c, G, B, n_items, n_lists);  // slots of the group rows
+    int64_t *counts = c.take<int64_t>(2);                      // stored lists, stored ids
+    int32_t *src_of = c.take<int32_t>(n_lists);
+    int64_t *zero_off = c.take<int64_t>(n_items + 1);
+    int64_t *u_tmp = c.take<int64_t>(n_items + 1);
     hipStream_t st = ctx->stream;
     if (n_lists == 0) {
         hipLaunchKernelGGL(k_empty_grouped, dim3(1), dim3(256), 0, st, F, G, u_offsets, feat_uoff,
-                           group_uoff, w.counts, w.counts_g);
+                           group_uoff, counts, w.counts);
     } else {
         const int32_t *dev_group_off = nullptr, *dev_feat_group = nullptr;
         RECD_TRY(recd_group_map(ctx, F, G, group_off, &dev_group_off, &dev_feat_group));
         constexpr int SG = 8;
-        const uint64_t cap = table_cap(B);
-        const int64_t tab_n = (int64_t)G * (int64_t)cap;
-        const int fill_blocks = (int)((tab_n + 1023) / 1024 < 4096 ? (tab_n + 1023) / 1024 : 4096);
-        hipLaunchKernelGGL(k_fill_u64, dim3(fill_blocks), dim3(256), 0, st, w.table, tab_n, kEmpty);
+        clear_table(st, w, G);
         const int zero_blocks = (int)((n_items + 1 + 1023) / 1024 < 4096 ? (n_items + 1 + 1023) / 1024 : 4096);
         hipLaunchKernelGGL(k_fill_u64, dim3(zero_blocks), dim3(256), 0, st,
-                           reinterpret_cast<uint64_t *>(w.zero_off), n_items + 1, 0ull);
+                           reinterpret_cast<uint64_t *>(zero_off), n_items + 1, 0ull);
         const int64_t hblocks = (n_items + (256 / SG) - 1) / (256 / SG);
         hipLaunchKernelGGL((k_group_hash_insert<SG>), dim3((unsigned)hblocks), dim3(256), 0, st, values,
-                           offsets, B, n_items, dev_group_off, w.table, (uint32_t)(cap - 1), w.slot_of,
+                           offsets, B, n_items, dev_group_off, w.table, (uint32_t)(w.cap - 1), w.slot_of,
                            ctx->weak_hash);
         // numbering of the slots per group: the list-level kernels with the groups in the role of
         // features and lists of length zero
-        const int64_t gblk = (n_items + kScanBlock - 1) / kScanBlock;
-        hipLaunchKernelGGL(k_flags, dim3((unsigned)gblk), dim3(kScanBlock), 0, st, w.zero_off, B, n_items,
-                           w.table, (uint32_t)(cap - 1), w.slot_of, w.bs_cnt, w.bs_len, w.bs_head);
-        hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(kScanBlock), 0, st, w.bs_cnt, w.bs_len, w.bs_head,
-                           gblk);
-        hipLaunchKernelGGL(k_number, dim3((unsigned)gblk), dim3(kScanBlock), 0, st, w.zero_off, B, n_items,
-                           G, w.table, (uint32_t)(cap - 1), w.slot_of, w.bs_cnt, w.bs_len, w.bs_head,
-                           w.rep_g, w.number_g, w.src_g, w.u_tmp, group_uoff, w.counts_g);
+        number_slots(st, w, G, B, zero_off, u_tmp, group_uoff);
         const unsigned inv_blocks = (unsigned)((n_items + 255) / 256);
-        hipLaunchKernelGGL((k_emit<16>), dim3(inv_blocks), dim3(256), 0, st, values, w.zero_off, B, n_items,
-                           w.rep_g, w.number_g, w.src_g, w.u_tmp, w.counts_g, u_values, inverse_g,
-                           inv_blocks);
+        hipLaunchKernelGGL((k_emit<16>), dim3(inv_blocks), dim3(256), 0, st, values, zero_off, B, n_items,
+                           w.rep, w.number, w.src_of, u_tmp, w.counts, u_values, inverse_g, inv_blocks);
         // per feature: which lists are stored, where
         const int64_t nblk = (n_lists + kScanBlock - 1) / kScanBlock;
         hipLaunchKernelGGL((k_group_compact<false>), dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets,
-                           B, n_lists, F, dev_feat_group, w.rep_g, inverse_g, w.bs_cnt, w.bs_len, w.bs_head,
-                           w.src_of, u_offsets, feat_uoff, inverse_per_feature, w.counts);
+                           B, n_lists, F, dev_feat_group, w.rep, inverse_g, w.bs_cnt, w.bs_len, w.bs_head,
+                           src_of, u_offsets, feat_uoff, inverse_per_feature, counts);
         hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(kScanBlock), 0, st, w.bs_cnt, w.bs_len, w.bs_head,
                            nblk);
         hipLaunchKernelGGL((k_group_compact<true>), dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets,
-                           B, n_lists, F, dev_feat_group, w.rep_g, inverse_g, w.bs_cnt, w.bs_len, w.bs_head,
-                           w.src_of, u_offsets, feat_uoff, inverse_per_feature, w.counts);
-        int64_t copy_blocks = (n_lists + (256 / 16) - 1) / (256 / 16);
-        if (copy_blocks > (int64_t)ctx->num_cu * 8)
-            copy_blocks = (int64_t)ctx->num_cu * 8;
-        hipLaunchKernelGGL((k_emit<16>), dim3((unsigned)copy_blocks), dim3(256), 0, st, values, offsets, B,
-                           n_lists, w.rep_g, w.number_g, w.src_of, u_offsets, w.counts, u_values,
+                           B, n_lists, F, dev_feat_group, w.rep, inverse_g, w.bs_cnt, w.bs_len, w.bs_head,
+                           src_of, u_offsets, feat_uoff, inverse_per_feature, counts);
+        hipLaunchKernelGGL((k_emit<16>), dim3(copy_blocks_for(ctx, n_lists)), dim3(256), 0, st, values,
+                           offsets, B, n_lists, w.rep, w.number, src_of, u_offsets, counts, u_values,
                            inverse_g, 0u);
     }
     RECD_HIP(ctx, hipGetLastError());
     if (host_counts) {
-        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, w.counts, 2 * sizeof(int64_t),
+        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, counts, 2 * sizeof(int64_t),
                                      hipMemcpyDeviceToHost, st));
-        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned + 2, w.counts_g, sizeof(int64_t),
+        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned + 2, w.counts, sizeof(int64_t),
                                      hipMemcpyDeviceToHost, st));
         RECD_HIP(ctx, hipStreamSynchronize(st));
         host_counts[0] = ctx->host_pinned[0];
@@ -947,51 +957,24 @@ extern "C" recd_status recd_build_partial_ikjt(recd_ctx *ctx, int F, int64_t B, 
         RECD_TRY(recd_validate_kjt_offsets(ctx, F, B, N, offsets));
 
     const int64_t nblk = (n_lists + kScanBlock - 1) / kScanBlock;
-    const uint64_t cap = table_cap(B);
-    size_t bytes = 0;
-    int64_t *counts = nullptr, *u_off = nullptr, *piece_pos = nullptr, *bs_cnt = nullptr, *bs_len = nullptr,
-            *bs_head = nullptr;
-    uint64_t *table = nullptr;
-    int32_t *slot_of = nullptr, *rep = nullptr, *number = nullptr, *src_of = nullptr, *piece = nullptr;
-    for (int pass = 0; pass < 2; pass++) {
-        WsCarver c(pass ? ctx->ws : nullptr);
-        counts = c.take<int64_t>(4);
-        table = c.take<uint64_t>((size_t)F * cap);
-        slot_of = c.take<int32_t>(n_lists);
-        rep = c.take<int32_t>(n_lists);
-        number = c.take<int32_t>(n_lists);
-        src_of = c.take<int32_t>(n_lists);
-        piece = c.take<int32_t>(n_lists);
-        u_off = c.take<int64_t>(n_lists + 1);
-        piece_pos = c.take<int64_t>(n_lists);
-        bs_cnt = c.take<int64_t>(nblk + 1);
-        bs_len = c.take<int64_t>(nblk + 1);
-        bs_head = c.take<int64_t>(nblk + 1);
-        bytes = c.off;
-        if (!pass)
-            RECD_TRY(recd_reserve(ctx, bytes));
-    }
+    RECD_TRY(recd_reserve(ctx, recd_build_workspace(F, B)));
+    WsCarver c(ctx->ws);
+    const SlotWs w = carve_slots(c, F, B, n_lists, n_lists);
+    int64_t *counts = w.counts;  // [0] slots, [1] ids of an IKJT, [2] ids stored
+    int32_t *piece = c.take<int32_t>(n_lists);
+    int64_t *u_off = c.take<int64_t>(n_lists + 1);
+    int64_t *piece_pos = c.take<int64_t>(n_lists);
+    int32_t *src_of = w.src_of;
+    int64_t *bs_cnt = w.bs_cnt, *bs_len = w.bs_len, *bs_head = w.bs_head;
     hipStream_t st = ctx->stream;
     if (n_lists == 0) {
         hipLaunchKernelGGL(k_empty_partial, dim3(1), dim3(256), 0, st, F, feat_uoff, feat_poff, counts);
     } else {
-        constexpr int SG = 8;
-        const int64_t tab_n = (int64_t)F * (int64_t)cap;
-        const int fill_blocks = (int)((tab_n + 1023) / 1024 < 4096 ? (tab_n + 1023) / 1024 : 4096);
-        hipLaunchKernelGGL(k_fill_u64, dim3(fill_blocks), dim3(256), 0, st, table, tab_n, kEmpty);
-        const int64_t hblocks = (n_lists + (256 / SG) * kLPG - 1) / ((256 / SG) * kLPG);
-        hipLaunchKernelGGL((k_hash_insert<SG>), dim3((unsigned)hblocks), dim3(256), 0, st, values,
-                           offsets, B, n_lists, table, (uint32_t)(cap - 1), slot_of, ctx->weak_hash);
-        hipLaunchKernelGGL(k_flags, dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets, B, n_lists,
-                           table, (uint32_t)(cap - 1), slot_of, bs_cnt, bs_len, bs_head);
-        hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(kScanBlock), 0, st, bs_cnt, bs_len, bs_head,
-                           nblk);
-        hipLaunchKernelGGL(k_number, dim3((unsigned)nblk), dim3(kScanBlock), 0, st, offsets, B, n_lists,
-                           F, table, (uint32_t)(cap - 1), slot_of, bs_cnt, bs_len, bs_head, rep, number,
-                           src_of, u_off, feat_uoff, counts);
+        insert_lists(ctx, st, w, F, B, values, offsets);
+        number_slots(st, w, F, B, offsets, u_off, feat_uoff);
         const unsigned inv_blocks = (unsigned)((n_lists + 255) / 256);
         hipLaunchKernelGGL((k_emit<16>), dim3(inv_blocks), dim3(256), 0, st, values, offsets, B, n_lists,
-                           rep, number, src_of, u_off, counts, p_values, inverse, inv_blocks);
+                           w.rep, w.number, src_of, u_off, counts, p_values, inverse, inv_blocks);
         int64_t ov_blocks = (n_lists + 3) / 4;
         if (ov_blocks > (int64_t)ctx->num_cu * 16)
             ov_blocks = (int64_t)ctx->num_cu * 16;
@@ -1006,10 +989,7 @@ extern "C" recd_status recd_build_partial_ikjt(recd_ctx *ctx, int F, int64_t B, 
                            win_len, src_of, B, F, feat_uoff, counts, bs_cnt, bs_len, bs_head, piece_pos,
                            win_start, feat_poff);
         const unsigned row_blocks = row_window ? inv_blocks : 0u;
-        int64_t copy_blocks = (n_lists + (256 / 16) - 1) / (256 / 16);
-        if (copy_blocks > (int64_t)ctx->num_cu * 8)
-            copy_blocks = (int64_t)ctx->num_cu * 8;
-        hipLaunchKernelGGL((k_partial_emit<16>), dim3(row_blocks + (unsigned)copy_blocks), dim3(256), 0,
+        hipLaunchKernelGGL((k_partial_emit<16>), dim3(row_blocks + copy_blocks_for(ctx, n_lists)), dim3(256), 0,
                            st, values, offsets, B, n_lists, src_of, piece, piece_pos, win_start, win_len,
                            inverse, feat_uoff, counts, p_values, row_window, row_blocks);
     }
