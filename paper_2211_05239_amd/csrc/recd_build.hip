@@ -34,6 +34,8 @@ __device__ __forceinline__ uint64_t mix64(uint64_t x)
     return x;
 }
 
+__global__ void k_copy_i64(const int64_t *src, int64_t *dst) { *dst = *src; }
+
 __global__ void k_fill_u64(uint64_t *p, int64_t n, uint64_t v)
 {
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
@@ -840,13 +842,8 @@ extern "C" recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t 
                            u_values, inverse, inv_blocks);
     }
     RECD_HIP(ctx, hipGetLastError());
-    if (host_U_M) {
-        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, counts, 2 * sizeof(int64_t),
-                                     hipMemcpyDeviceToHost, st));
-        RECD_HIP(ctx, hipStreamSynchronize(st));
-        host_U_M[0] = ctx->host_pinned[0];
-        host_U_M[1] = ctx->host_pinned[1];
-    }
+    if (host_U_M)
+        RECD_TRY(recd_fetch_scalars(ctx, counts, 2, host_U_M));
     return RECD_OK;
 }
 
@@ -881,7 +878,7 @@ extern "C" recd_status recd_build_ikjt_grouped(recd_ctx *ctx, int F, int64_t B, 
     RECD_TRY(recd_reserve(ctx, recd_build_workspace(F, B)));
     WsCarver c(ctx->ws);
     const SlotWs w = carve_slots(c, G, B, n_items, n_lists);  // slots of the group rows
-    int64_t *counts = c.take<int64_t>(2);                      // stored lists, stored ids
+    int64_t *counts = c.take<int64_t>(4);                      // stored lists, stored ids
     int32_t *src_of = c.take<int32_t>(n_lists);
     int64_t *zero_off = c.take<int64_t>(n_items + 1);
     int64_t *u_tmp = c.take<int64_t>(n_items + 1);
@@ -923,14 +920,10 @@ extern "C" recd_status recd_build_ikjt_grouped(recd_ctx *ctx, int F, int64_t B, 
     }
     RECD_HIP(ctx, hipGetLastError());
     if (host_counts) {
-        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, counts, 2 * sizeof(int64_t),
-                                     hipMemcpyDeviceToHost, st));
-        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned + 2, w.counts, sizeof(int64_t),
-                                     hipMemcpyDeviceToHost, st));
-        RECD_HIP(ctx, hipStreamSynchronize(st));
-        host_counts[0] = ctx->host_pinned[0];
-        host_counts[1] = ctx->host_pinned[1];
-        host_counts[2] = ctx->host_pinned[2];
+        // counts = {stored lists, stored ids}, w.counts[0] = sum of the groups' slot counts; the
+        // two live next to each other in the workspace only by way of this copy
+        hipLaunchKernelGGL(k_copy_i64, dim3(1), dim3(1), 0, st, w.counts, counts + 2);
+        RECD_TRY(recd_fetch_scalars(ctx, counts, 3, host_counts));
     }
     return RECD_OK;
 }
@@ -995,12 +988,11 @@ extern "C" recd_status recd_build_partial_ikjt(recd_ctx *ctx, int F, int64_t B, 
     }
     RECD_HIP(ctx, hipGetLastError());
     if (host_counts) {
-        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, counts, 3 * sizeof(int64_t),
-                                     hipMemcpyDeviceToHost, st));
-        RECD_HIP(ctx, hipStreamSynchronize(st));
-        host_counts[0] = ctx->host_pinned[0];  // U
-        host_counts[1] = ctx->host_pinned[2];  // P: ids stored
-        host_counts[2] = ctx->host_pinned[1];  // M: ids an IKJT would store
+        int64_t h[3];
+        RECD_TRY(recd_fetch_scalars(ctx, counts, 3, h));
+        host_counts[0] = h[0];  // U
+        host_counts[1] = h[2];  // P: ids stored
+        host_counts[2] = h[1];  // M: ids an IKJT would store
     }
     return RECD_OK;
 }

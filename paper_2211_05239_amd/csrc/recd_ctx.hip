@@ -3,6 +3,9 @@
 
 #include "recd_internal.h"
 
+#include <atomic>
+#include <chrono>
+
 recd_status recd_fail(recd_ctx *ctx, recd_status s, const char *fmt, ...)
 {
     if (ctx) {
@@ -62,6 +65,55 @@ recd_status recd_group_map(recd_ctx *ctx, int F, int G, const int32_t *group_off
     return RECD_OK;
 }
 
+// values first, the sequence number last, each visible to the host before the next
+__global__ void k_publish(const int64_t *__restrict__ src, int n, int64_t *mailbox, int64_t seq)
+{
+    for (int i = 0; i < n; i++)
+        mailbox[i] = src[i];
+    __threadfence_system();
+    mailbox[7] = seq;
+    __threadfence_system();
+}
+
+recd_status recd_fetch_scalars(recd_ctx *ctx, const int64_t *dev, int n, int64_t *host_out)
+{
+    if (n < 0 || n > 6)
+        return recd_fail(ctx, RECD_EINVAL, "recd_fetch_scalars: n=%d", n);
+    if (ctx->mailbox) {
+        // The host polls the mailbox instead of sleeping in a stream synchronisation: the wake-up
+        // of a blocked thread costs more than the kernels of a small call.
+        const int64_t seq = ++ctx->mailbox_seq;
+        hipLaunchKernelGGL(k_publish, dim3(1), dim3(1), 0, ctx->stream, dev, n, ctx->mailbox_dev, seq);
+        RECD_HIP(ctx, hipGetLastError());
+        const auto t0 = std::chrono::steady_clock::now();
+        bool seen = false;
+        for (uint64_t spin = 0;; spin++) {
+            if (ctx->mailbox[7] == seq) {
+                seen = true;
+                break;
+            }
+            if ((spin & 0xfff) == 0xfff &&
+                std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(200))
+                break;  // a long queue ahead of us, or an error: let the runtime wait
+        }
+        if (!seen) {
+            RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
+            if (ctx->mailbox[7] != seq)
+                return recd_fail(ctx, RECD_EHIP, "result mailbox was not written");
+        }
+        std::atomic_thread_fence(std::memory_order_acquire);
+        for (int i = 0; i < n; i++)
+            host_out[i] = ctx->mailbox[i];
+        return RECD_OK;
+    }
+    RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, dev, n * sizeof(int64_t), hipMemcpyDeviceToHost,
+                                 ctx->stream));
+    RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    for (int i = 0; i < n; i++)
+        host_out[i] = ctx->host_pinned[i];
+    return RECD_OK;
+}
+
 extern "C" {
 
 const char *recd_status_string(recd_status s)
@@ -102,6 +154,20 @@ recd_status recd_create(recd_ctx **out, int device, void *hip_stream, size_t wor
     void *p = nullptr;
     ok = ok && hipHostMalloc(&p, 8 * sizeof(int64_t), hipHostMallocDefault) == hipSuccess;
     ctx->host_pinned = static_cast<int64_t *>(p);
+    void *mb = nullptr, *mb_dev = nullptr;
+    if (ok && hipHostMalloc(&mb, 8 * sizeof(int64_t), hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess) {
+        if (hipHostGetDevicePointer(&mb_dev, mb, 0) == hipSuccess) {
+            ctx->mailbox = static_cast<volatile int64_t *>(mb);
+            ctx->mailbox_dev = static_cast<int64_t *>(mb_dev);
+            for (int i = 0; i < 8; i++)
+                ctx->mailbox[i] = 0;
+        } else {
+            (void)hipGetLastError();
+            (void)hipHostFree(mb);
+        }
+    } else if (ok) {
+        (void)hipGetLastError();
+    }
     if (ok && workspace_hint_bytes)
         ok = recd_reserve(ctx, workspace_hint_bytes) == RECD_OK;
     if (!ok) {
@@ -133,6 +199,8 @@ recd_status recd_destroy(recd_ctx *ctx)
         (void)hipFree(ctx->group_map_dev);
     if (ctx->host_pinned)
         (void)hipHostFree(ctx->host_pinned);
+    if (ctx->mailbox)
+        (void)hipHostFree(const_cast<int64_t *>(ctx->mailbox));
     delete ctx;
     return RECD_OK;
 }

@@ -17,6 +17,11 @@ struct recd_ctx {
     char *ws = nullptr;          // device workspace
     size_t ws_bytes = 0;
     int64_t *host_pinned = nullptr;  // 8 x int64 pinned staging for scalar results
+    // Mailbox for scalar results the host waits for: pinned, coherent, mapped host memory that a
+    // one-thread kernel writes (values, then a sequence number); nullptr if it could not be set up.
+    volatile int64_t *mailbox = nullptr;
+    int64_t *mailbox_dev = nullptr;
+    int64_t mailbox_seq = 0;
     int validate = 0;
     int weak_hash = 0;
     int tune_lb = 0, tune_gens = 0, tune_flat = 0;  // launch-shape overrides of the gather-sum kernel (0 = automatic)
@@ -115,3 +120,6 @@ recd_status recd_validate_unique_lists(recd_ctx *ctx, int F, const int64_t *rows
 // synchronisation) only when the grouping differs from the previous call's.
 recd_status recd_group_map(recd_ctx *ctx, int F, int G, const int32_t *group_off,
                            const int32_t **dev_group_off, const int32_t **dev_feat_group);
+// Brings n <= 6 int64 values at `dev` to the host once everything enqueued on the context's stream
+// before the call has finished.
+recd_status recd_fetch_scalars(recd_ctx *ctx, const int64_t *dev, int n, int64_t *host_out);
