@@ -53,6 +53,9 @@ def parse_args():
     ap.add_argument("--reader", action="store_true",
                     help="also report the builder alone (the conversion step of a reader) beside the CPU "
                          "oracle's builder run feature-parallel on the host cores")
+    ap.add_argument("--no-pipeline", dest="pipeline", action="store_false",
+                    help="skip the extra run with the builder on a second stream (reported beside the step, "
+                         "never as `value`)")
     ap.add_argument("--tune", type=int, default=0, help="RECD_OPT_TUNE_SEGSUM value (0 = automatic)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates hardware byte counters)")
@@ -142,6 +145,48 @@ class DeviceProblem:
         return U, M
 
 
+def pipelined_steps(torch, recd, P, args):
+    """The same K steps with the builder of batch k+1 on a second stream (its own context and
+    workspace) next to lookup, expand and backward of batch k on the main stream.  Every step still
+    runs all four calls on its batch, in order; only the host's wait for U and M no longer idles
+    the GPU.  Returns ms per step."""
+    w = P.w
+    nb = len(P.batches)
+    s2 = torch.cuda.Stream()
+    ctx2 = recd.Context(0, workspace_hint_bytes=recd.workspace_bytes(w.F, w.B, max(b.N for b in P.batches), w.D),
+                        stream=s2.cuda_stream)
+    done = [torch.cuda.Event() for _ in range(nb)]   # main stream has finished with batch i's IKJT
+
+    def build_on_s2(i):
+        s2.wait_event(done[i])
+        return ctx2.build_ikjt(w.F, w.B, P.values[i], P.offsets[i], P.u_values[i], P.u_offsets[i],
+                               P.inverse[i], P.feat_uoff[i], want_counts=True)
+
+    def run(steps):
+        pending = build_on_s2(0)
+        for k in range(steps):
+            i = k % nb
+            U, M = pending
+            torch.cuda.current_stream().wait_stream(s2)   # the IKJT of batch i is complete
+            P.lookup(i, U)
+            P.expand(i)
+            if P.need_backward:
+                P.backward(i, U, M)
+            done[i].record()
+            if k + 1 < steps:
+                pending = build_on_s2((k + 1) % nb)
+        torch.cuda.synchronize()
+
+    for i in range(nb):
+        done[i].record()
+    run(max(args.warmup, 2))
+    t0 = time.perf_counter()
+    run(args.steps)
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    ctx2.close()
+    return ms
+
+
 def event_ms(torch, fn, reps):
     """Average HIP-event time of fn() on torch's current stream (the stream the library uses)."""
     s = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
@@ -155,7 +200,7 @@ def event_ms(torch, fn, reps):
     return float(np.mean(ts)), float(ts[len(ts) // 2])
 
 
-def run_workload(torch, recd, synth, w, args, need_backward, detail=True):
+def run_workload(torch, recd, synth, w, args, need_backward, detail=True, pipeline=True):
     P = DeviceProblem(torch, recd, synth, w, args.batches, need_backward, getattr(args, "store_grad", False), getattr(args, "tune", 0))
     nb = len(P.batches)
     F, B, D = w.F, w.B, w.D
@@ -179,6 +224,8 @@ def run_workload(torch, recd, synth, w, args, need_backward, detail=True):
     step_ms = (time.perf_counter() - t0) * 1e3 / args.steps
 
     res = {"step_ms": step_ms, "B": B, "F": F, "D": D}
+    if detail and pipeline and getattr(args, "pipeline", True):
+        res["pipelined_step_ms"] = pipelined_steps(torch, recd, P, args)
     N = float(np.mean([b.N for b in P.batches]))
     U = float(np.mean([s[0] for s in stats]))
     M = float(np.mean([s[1] for s in stats]))
@@ -557,6 +604,10 @@ def main():
                      "avg_launch_ms": res["lookup_unique_ms"]},
         "regions": res,
     }
+    if "pipelined_step_ms" in res:
+        line["pipelined"] = {"ms_per_step": res["pipelined_step_ms"],
+                             "value": w.B * w.F / (res["pipelined_step_ms"] * 1e-3), "unit": "pooled lookups/s",
+                             "note": "same K steps, builder of the next batch on a second stream; not `value`"}
     if args.cpu_features > 0:
         line["cpu_baseline"] = cpu_baseline(torch, synth, P, args.cpu_features)
     if args.reader:
@@ -569,7 +620,7 @@ def main():
         sweep = []
         for S in synth.SWEEP_SESSION_SIZES:
             ws = synth.sweep_workload(S)
-            r, Ps = run_workload(torch, recd, synth, ws, args, need_backward=False)
+            r, Ps = run_workload(torch, recd, synth, ws, args, need_backward=False, pipeline=False)
             Ps.ctx.close()
             del Ps
             torch.cuda.empty_cache()
