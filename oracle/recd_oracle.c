@@ -532,6 +532,84 @@ int oracle_backward_kjt(int F, int64_t B, int D, const float *grad_out, const in
     return 0;
 }
 
+/* ---- backward of the jagged expand + unpooled lookup (chain rule of the two forward steps of
+ * the sequence path; the paper describes the forward side only, Sec. 5) ---------------------------
+ * grad_out holds one gradient row per KJT position (the layout of the expanded activations).
+ * step 1  g_emb[u_offsets[u] + t, :] = sum over b ascending with inverse[f,b] == u of
+ *                                       grad_out[offsets[f*B+b] + t, :]
+ * step 2  G_f[r,:] = sum over positions j ascending of feature f's unique ids with
+ *                    u_values[j] == r of g_emb[j, :]
+ * Output as for oracle_backward_dedup.
+ */
+int oracle_backward_sequence_dedup(int F, int64_t B, int D, const float *grad_out,
+                                   const int64_t *offsets, const int32_t *inverse,
+                                   const int64_t *feat_uoff, const int64_t *u_values,
+                                   const int64_t *u_offsets, int64_t *touched_rows,
+                                   int64_t *feat_roff, double *grad_rows)
+{
+    int64_t U = feat_uoff[F], M = u_offsets[U];
+    double *g_emb = (double *)calloc((size_t)(M > 0 ? M : 1) * D, sizeof(double));
+    if (!g_emb)
+        return -9;
+    for (int f = 0; f < F; f++)
+        for (int64_t b = 0; b < B; b++) {
+            int64_t l = (int64_t)f * B + b;
+            int64_t u = feat_uoff[f] + inverse[l];
+            int64_t len = offsets[l + 1] - offsets[l];
+            if (u_offsets[u + 1] - u_offsets[u] != len) {
+                free(g_emb);
+                return -6;
+            }
+            for (int64_t t = 0; t < len; t++)
+                for (int d = 0; d < D; d++)
+                    g_emb[(u_offsets[u] + t) * D + d] += (double)grad_out[(offsets[l] + t) * D + d];
+        }
+    int64_t R = 0;
+    for (int f = 0; f < F; f++) {
+        feat_roff[f] = R;
+        int64_t j0 = u_offsets[feat_uoff[f]], j1 = u_offsets[feat_uoff[f + 1]];
+        int64_t r_f = sorted_distinct(u_values + j0, j1 - j0, touched_rows + R);
+        double *G = grad_rows + R * D;
+        for (int64_t i = 0; i < r_f * D; i++)
+            G[i] = 0.0;
+        for (int64_t j = j0; j < j1; j++) {
+            int64_t k = find_row(touched_rows + R, r_f, u_values[j]);
+            for (int d = 0; d < D; d++)
+                G[k * D + d] += g_emb[j * D + d];
+        }
+        R += r_f;
+    }
+    feat_roff[F] = R;
+    free(g_emb);
+    return 0;
+}
+
+/* ---- the same gradient straight from the KJT: G_f[r,:] = sum over the positions p ascending of
+ * feature f's rows with values[p] == r of grad_out[p,:] (the gradient of a plain embedding
+ * lookup).  Must agree with oracle_backward_sequence_dedup up to double rounding order. */
+int oracle_backward_sequence_kjt(int F, int64_t B, int D, const float *grad_out, const int64_t *values,
+                                 const int64_t *offsets, int64_t *touched_rows, int64_t *feat_roff,
+                                 double *grad_rows)
+{
+    int64_t R = 0;
+    for (int f = 0; f < F; f++) {
+        feat_roff[f] = R;
+        int64_t j0 = offsets[(int64_t)f * B], j1 = offsets[(int64_t)(f + 1) * B];
+        int64_t r_f = sorted_distinct(values + j0, j1 - j0, touched_rows + R);
+        double *G = grad_rows + R * D;
+        for (int64_t i = 0; i < r_f * D; i++)
+            G[i] = 0.0;
+        for (int64_t p = j0; p < j1; p++) {
+            int64_t k = find_row(touched_rows + R, r_f, values[p]);
+            for (int d = 0; d < D; d++)
+                G[k * D + d] += (double)grad_out[p * D + d];
+        }
+        R += r_f;
+    }
+    feat_roff[F] = R;
+    return 0;
+}
+
 /* ---- row-wise Adagrad on the touched rows (not in the paper; the benchmark configuration
  * fixes lr and eps, the form is this build's reading) -------------------------------------------
  * One accumulator m[r] per table row.  For each touched row, once per step with the aggregated

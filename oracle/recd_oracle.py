@@ -288,6 +288,44 @@ def backward_kjt(F: int, B: int, grad_out: np.ndarray, values, offsets):
     return touched[:R].copy(), feat_roff, grad_rows[:R].copy()
 
 
+def backward_sequence_dedup(F: int, B: int, grad_out: np.ndarray, offsets, inverse, feat_uoff, u_values,
+                            u_offsets):
+    """Backward of jagged expand + unpooled lookup; grad_out fp32 [N, D], one row per KJT position.
+    Returns (touched_rows, feat_roff, grad_rows float64 [R, D])."""
+    grad_out = np.ascontiguousarray(grad_out, dtype=np.float32)
+    D = grad_out.shape[-1]
+    offsets, feat_uoff, u_values, u_offsets = _i64(offsets), _i64(feat_uoff), _i64(u_values), _i64(u_offsets)
+    inverse = np.ascontiguousarray(inverse, dtype=np.int32)
+    M = u_values.shape[0]
+    touched = np.zeros(max(M, 1), dtype=np.int64)
+    feat_roff = np.zeros(F + 1, dtype=np.int64)
+    grad_rows = np.zeros((max(M, 1), D), dtype=np.float64)
+    rc = _lib.oracle_backward_sequence_dedup(C.c_int(F), C.c_int64(B), C.c_int(D), _p(grad_out, _f32p),
+                                             _p(offsets, _i64p), _p(inverse, _i32p), _p(feat_uoff, _i64p),
+                                             _p(u_values, _i64p), _p(u_offsets, _i64p), _p(touched, _i64p),
+                                             _p(feat_roff, _i64p), _p(grad_rows, _f64p))
+    _check(rc, "backward_sequence_dedup")
+    R = int(feat_roff[F])
+    return touched[:R].copy(), feat_roff, grad_rows[:R].copy()
+
+
+def backward_sequence_kjt(F: int, B: int, grad_out: np.ndarray, values, offsets):
+    """The same gradient computed from the KJT alone (gradient of a plain embedding lookup)."""
+    grad_out = np.ascontiguousarray(grad_out, dtype=np.float32)
+    D = grad_out.shape[-1]
+    values, offsets = _i64(values), _i64(offsets)
+    N = values.shape[0]
+    touched = np.zeros(max(N, 1), dtype=np.int64)
+    feat_roff = np.zeros(F + 1, dtype=np.int64)
+    grad_rows = np.zeros((max(N, 1), D), dtype=np.float64)
+    rc = _lib.oracle_backward_sequence_kjt(C.c_int(F), C.c_int64(B), C.c_int(D), _p(grad_out, _f32p),
+                                           _p(values, _i64p), _p(offsets, _i64p), _p(touched, _i64p),
+                                           _p(feat_roff, _i64p), _p(grad_rows, _f64p))
+    _check(rc, "backward_sequence_kjt")
+    R = int(feat_roff[F])
+    return touched[:R].copy(), feat_roff, grad_rows[:R].copy()
+
+
 def rowwise_adagrad(grad_rows, w_rows, m_rows, lr: float, eps: float) -> Tuple[np.ndarray, np.ndarray]:
     """Row-wise Adagrad on the touched rows: returns (w_new[R,D], m_new[R]) in float64."""
     grad_rows = np.ascontiguousarray(grad_rows, dtype=np.float64)

@@ -600,6 +600,45 @@ def test_backward_matches_autograd_and_kjt_form(seed):
         np.testing.assert_allclose(G[f], W.grad.numpy(), rtol=1e-12, atol=1e-13)
 
 
+@pytest.mark.parametrize("seed", range(3))
+def test_sequence_backward_two_definitions_and_autograd(seed):
+    """Backward of the sequence path: through the IKJT and straight from the KJT agree, and both equal
+    autograd through a plain embedding lookup in fp64 with loss = <activations, grad_out>."""
+    batch, tabs = _rand_problem(500 + seed, F=2, B=29, rows=7, D=3, max_len=4, alphabet=3)
+    F, B, N = batch.F, batch.B, batch.N
+    rng = np.random.default_rng(seed)
+    gout = rng.standard_normal((N, 3)).astype(np.float32)
+    uv, uo, inv, fu = orc.build_ikjt(F, B, batch.values, batch.offsets)
+    tr, fr, gr = orc.backward_sequence_dedup(F, B, gout, batch.offsets, inv, fu, uv, uo)
+    tr2, fr2, gr2 = orc.backward_sequence_kjt(F, B, gout, batch.values, batch.offsets)
+    assert np.array_equal(tr, tr2) and np.array_equal(fr, fr2)
+    np.testing.assert_allclose(gr, gr2, rtol=1e-12, atol=1e-13)
+    G = _dense_grad(F, 7, 3, tr, fr, gr)
+    for f in range(F):
+        W = torch.from_numpy(tabs[f]).double().requires_grad_(True)
+        lo, hi = batch.offsets[f * B], batch.offsets[(f + 1) * B]
+        act = torch.nn.functional.embedding(torch.from_numpy(batch.values[lo:hi]), W)
+        (act * torch.from_numpy(gout[lo:hi]).double()).sum().backward()
+        np.testing.assert_allclose(G[f], W.grad.numpy(), rtol=1e-12, atol=1e-13)
+    # a slot of another length than the row is refused
+    if len(set(np.diff(uo[:fu[1] + 1]).tolist())) > 1:
+        lens0 = np.diff(uo[:fu[1] + 1])
+        bad = inv.copy()
+        bad[0] = int(np.nonzero(lens0 != lens0[inv[0]])[0][0])
+        with pytest.raises(orc.OracleError):
+            orc.backward_sequence_dedup(F, B, gout, batch.offsets, bad, fu, uv, uo)
+
+
+def test_sequence_backward_hand_case():
+    # rows: [1,2], [1,2], [2]; gradient rows g0..g4 per position; unique lists [1,2] (rows 0,1), [2]
+    kjt = synth.batch_from_lists([[[1, 2], [1, 2], [2]]])
+    g = np.array([[1.0], [10.0], [100.0], [1000.0], [10000.0]], dtype=np.float32)
+    uv, uo, inv, fu = orc.build_ikjt(1, 3, kjt.values, kjt.offsets)
+    tr, fr, gr = orc.backward_sequence_dedup(1, 3, g, kjt.offsets, inv, fu, uv, uo)
+    assert tr.tolist() == [1, 2] and fr.tolist() == [0, 2]
+    assert gr[:, 0].tolist() == [101.0, 11010.0]   # id 1: positions 0, 2; id 2: positions 1, 3, 4
+
+
 def test_backward_finite_difference():
     F, B, rows, D = 1, 6, 5, 3
     batch = synth.batch_from_lists([[[0, 1], [0, 1], [4], [], [1, 1, 2], [0, 1]]])
