@@ -15,6 +15,7 @@
  *   9. grouped builder    10. element-wise sum over a group's features on the unique rows
  * other pooling functions (11), and partial IKJTs whose lists share storage when one continues
  * another (Sec. 7): 12. partial builder   13. pooled lookup on the windows
+ *   14. backward of the sequence path
  *
  * General rules
  *   - Every array argument marked "device" is a pointer into GPU memory owned by the caller and
@@ -309,6 +310,29 @@ recd_status recd_pooled_lookup_partial(recd_ctx *ctx, int F, int D, recd_dtype t
                                        const int64_t *rows, const int64_t *p_values, int64_t P_cap,
                                        const int64_t *win_start, const int64_t *win_len,
                                        const int64_t *feat_uoff, int64_t max_lists, void *pooled);
+
+/* 14. Backward of calls 7 and 6, the sequence path (chain rule; the paper describes the forward
+ *    side only, Sec. 5):
+ *      grad_emb[u_offsets[u] + t, :] = sum over rows b (ascending) with inverse[f*B+b] = u of
+ *                                      grad_out[offsets[f*B+b] + t, :]
+ *      G_f[r,:] = sum over the positions j (ascending) of feature f's unique ids with
+ *                 u_values[j] = r of grad_emb[j, :]
+ *    Same machinery and guarantees as call 5 (stable sorts, fixed summation order, no
+ *    floating-point atomics, optional fused row-wise Adagrad).
+ *    grad_out: device fp32 [N, D], one gradient row per KJT position (the layout of call 7's
+ *    output).  offsets: device [F*B+1], the KJT's offsets.  N must stay below 2^31.
+ *    grad_emb: device fp32 [M, D], capacity M_cap rows: OUTPUT, the gradient with respect to the
+ *    unique activations of call 6 (what a module between calls 6 and 7 would receive).
+ *    All other arguments as in call 5. */
+recd_status recd_backward_sequence_dedup(recd_ctx *ctx, int F, int64_t B, int64_t N, int D,
+                                         const float *grad_out, const int64_t *offsets,
+                                         const int32_t *inverse, const int64_t *feat_uoff,
+                                         const int64_t *u_values, const int64_t *u_offsets,
+                                         const int64_t *rows, int64_t U_cap, int64_t M_cap,
+                                         float *grad_emb, int64_t *touched_rows, int64_t *feat_roff,
+                                         float *grad_rows, void *const *tables,
+                                         float *const *adagrad_state, float lr, float eps,
+                                         int64_t *host_R);
 
 #ifdef __cplusplus
 }

@@ -251,7 +251,7 @@ __global__ __launch_bounds__(256) void k_keys_ids(const int64_t *__restrict__ u_
                                                   const int64_t *__restrict__ feat_uoff, int F,
                                                   int row_bits, int64_t lists_cap, int64_t M_cap,
                                                   KeyT *__restrict__ keys, uint32_t *__restrict__ pay,
-                                                  int64_t *n_out)
+                                                  int64_t *n_out, int pay_positions)
 {
     const int s = threadIdx.x % SG;
     const int64_t u = (int64_t)blockIdx.x * (256 / SG) + threadIdx.x / SG;
@@ -277,7 +277,7 @@ __global__ __launch_bounds__(256) void k_keys_ids(const int64_t *__restrict__ u_
     const int64_t j1 = u_offsets[u + 1] < M_cap ? u_offsets[u + 1] : M_cap;
     for (int64_t j = j0 + s; j < j1; j += SG) {
         keys[j] = fkey | (KeyT)u_values[j];
-        pay[j] = (uint32_t)u;
+        pay[j] = pay_positions ? (uint32_t)j : (uint32_t)u;  // source row of the later sum: g_emb[j] or g_u[u]
     }
 }
 
@@ -655,6 +655,91 @@ int bits_for(uint64_t max_value)
 }
 
 // Buffers of one sort (the two sorts of a backward call run on two streams at the same time).
+// ---------------------------------------------------------------- sequence path, step A
+// g_emb[u_offsets[u] + t, :] = sum over the rows l (ascending) of unique list u of
+// grad_out[offsets[l] + t, :].  The rows of u are ps[seg_start[u] .. seg_start[u+1]) (rows sorted by
+// unique list; every list has at least one row, so segment number = list number).  A block owns
+// LISTS consecutive unique lists and numbers their positions flat, so long and short lists load
+// the threads alike; a thread = one 16-byte piece of one position, four source rows in flight.
+template <int LISTS>
+__global__ __launch_bounds__(256) void k_jagged_reduce(const float4 *__restrict__ grad_out,
+                                                       const int64_t *__restrict__ offsets,
+                                                       const uint32_t *__restrict__ ps,
+                                                       const int64_t *__restrict__ seg_start,
+                                                       const int64_t *__restrict__ n_seg,
+                                                       const int64_t *__restrict__ u_offsets,
+                                                       float4 *__restrict__ g_emb, int vecs,
+                                                       int64_t n_rows, int64_t m_cap)
+{
+    static_assert(LISTS <= 64 && (LISTS & (LISTS - 1)) == 0, "one wave prepares the block's lists");
+    __shared__ uint32_t rel_s[LISTS + 1];
+    __shared__ int64_t pos_s[LISTS];
+    const int64_t U = *n_seg;
+    const uint32_t rows_per_sweep = 256 / vecs;
+    const uint32_t piece = threadIdx.x % vecs, sub = threadIdx.x / vecs;
+    for (int64_t u0 = (int64_t)blockIdx.x * LISTS; u0 < U; u0 += (int64_t)gridDim.x * LISTS) {
+        const uint32_t nl = U - u0 < LISTS ? (uint32_t)(U - u0) : (uint32_t)LISTS;
+        __syncthreads();  // the previous lists are done with the shared arrays
+        if (threadIdx.x < 64) {
+            const uint32_t i = threadIdx.x;
+            int64_t start = 0;
+            uint32_t len = 0;
+            if (i < nl) {
+                start = u_offsets[u0 + i];
+                len = (uint32_t)(u_offsets[u0 + i + 1] - start);
+            }
+            uint32_t incl = len;
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const uint32_t x = __shfl_up(incl, d);
+                if (i >= (uint32_t)d)
+                    incl += x;
+            }
+            if (i < nl) {
+                rel_s[i] = incl - len;
+                pos_s[i] = start;
+            }
+            if (i == 63)
+                rel_s[nl] = incl;
+        }
+        __syncthreads();
+        const uint32_t total = rel_s[nl];
+        if (sub >= rows_per_sweep)
+            continue;
+        for (uint32_t r = sub; r < total; r += rows_per_sweep) {
+            uint32_t a = 0;  // the last list with rel_s[a] <= r; r < rel_s[nl], so it is not empty
+#pragma unroll
+            for (uint32_t s = LISTS / 2; s >= 1; s >>= 1)
+                if (a + s < nl && rel_s[a + s] <= r)
+                    a += s;
+            const int64_t t = r - rel_s[a];
+            const int64_t s0 = seg_start[u0 + a], s1 = seg_start[u0 + a + 1];
+            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
+            for (int64_t i = s0; i < s1; i += 4) {
+                float4 v[4];
+#pragma unroll
+                for (int k = 0; k < 4; k++) {
+                    const int64_t l = ps[i + k < s1 ? i + k : s1 - 1];
+                    int64_t src = offsets[l] + t;
+                    src = src < n_rows ? src : n_rows - 1;  // only a malformed IKJT gets here
+                    v[k] = grad_out[src * vecs + piece];
+                }
+#pragma unroll
+                for (int k = 0; k < 4; k++)
+                    if (i + k < s1) {
+                        acc.x += v[k].x;
+                        acc.y += v[k].y;
+                        acc.z += v[k].z;
+                        acc.w += v[k].w;
+                    }
+            }
+            const int64_t j = pos_s[a] + t;
+            if (j < m_cap)
+                g_emb[j * vecs + piece] = acc;
+        }
+    }
+}
+
 struct SortSet {
     int64_t *n_dev;  // [0] number of pairs, [1] capacity-overflow flag
     void *k0, *k1;
@@ -716,12 +801,11 @@ BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D)
     return w;
 }
 
-// Segments of equal keys in the sorted pairs (ks, ps) of `set`, then the sum of every segment's rows.
+// Segments of equal keys in the sorted keys ks: seg_start, list_off = {0, R} and, for (feature, row)
+// keys, the row ids, the feature of every segment and feat_roff.
 template <typename KeyT>
-recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, const KeyT *ks,
-                            const uint32_t *ps, int64_t n_cap, int64_t seg_bound, int row_bits, int F,
-                            const void *table, int D, void *out, int64_t *touched_rows,
-                            int64_t *feat_roff, const OptAdagrad *opt)
+recd_status number_segments(recd_ctx *ctx, const BwdWs &w, const SortSet &set, const KeyT *ks, int64_t n_cap,
+                            int row_bits, int F, int64_t *touched_rows, int64_t *feat_roff)
 {
     hipStream_t st = ctx->stream;
     const unsigned tiles = (unsigned)((n_cap + kScanTile - 1) / kScanTile > 0 ? (n_cap + kScanTile - 1) / kScanTile : 1);
@@ -731,6 +815,18 @@ recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, c
     hipLaunchKernelGGL((k_segments<KeyT>), dim3(tiles), dim3(256), 0, st, ks, set.n_dev, set.bsum,
                        w.seg_start, w.list_off, row_bits, F, touched_rows, feat_roff, w.seg_feat);
     RECD_HIP(ctx, hipGetLastError());
+    return RECD_OK;
+}
+
+// Segments of equal keys in the sorted pairs (ks, ps) of `set`, then the sum of every segment's rows.
+template <typename KeyT>
+recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, const KeyT *ks,
+                            const uint32_t *ps, int64_t n_cap, int64_t seg_bound, int row_bits, int F,
+                            const void *table, int D, void *out, int64_t *touched_rows,
+                            int64_t *feat_roff, const OptAdagrad *opt)
+{
+    hipStream_t st = ctx->stream;
+    RECD_TRY(number_segments<KeyT>(ctx, w, set, ks, n_cap, row_bits, F, touched_rows, feat_roff));
     SegSumArgs a{};
     a.site = RECD_SITE_GRAD_LISTS;
     a.F = 1;
@@ -832,18 +928,21 @@ size_t recd_backward_workspace(int F, int64_t B, int64_t M_cap, int D)
     return carve_bwd(nullptr, (int64_t)F * B, M_cap, F, D).bytes;
 }
 
-extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int D,
-                                           const float *grad_out, const int32_t *inverse,
-                                           const int64_t *feat_uoff, const int64_t *u_values,
-                                           const int64_t *u_offsets, const int64_t *rows,
-                                           int64_t U_cap, int64_t M_cap, int64_t *touched_rows,
-                                           int64_t *feat_roff,
-                                           float *grad_rows, void *const *tables,
-                                           float *const *adagrad_state, float lr, float eps,
-                                           int64_t *host_R)
+// Backward of the pooled path (seq = false: grad_out is [F,B,D]) and of the sequence path (seq =
+// true: grad_out is [N,D], one row per KJT position; kjt_offsets, N and grad_emb are used).
+static recd_status backward_common(recd_ctx *ctx, bool seq, int F, int64_t B, int64_t N, int D,
+                                   const float *grad_out, const int64_t *kjt_offsets,
+                                   const int32_t *inverse, const int64_t *feat_uoff,
+                                   const int64_t *u_values, const int64_t *u_offsets,
+                                   const int64_t *rows, int64_t U_cap, int64_t M_cap, float *grad_emb,
+                                   int64_t *touched_rows, int64_t *feat_roff, float *grad_rows,
+                                   void *const *tables, float *const *adagrad_state, float lr,
+                                   float eps, int64_t *host_R)
 {
     if (!ctx)
         return RECD_EINVAL;
+    if (seq && (N < 0 || N >= (int64_t)1 << 31 || !kjt_offsets || (M_cap > 0 && !grad_emb)))
+        return recd_fail(ctx, RECD_EINVAL, "sequence backward: bad N or null offsets / grad_emb");
     if (F < 0 || F > RECD_MAX_FEATURES || B < 0 || M_cap < 0 || U_cap < 0)
         return recd_fail(ctx, RECD_EINVAL, "bad sizes");
     if (U_cap > (int64_t)F * B)
@@ -856,7 +955,7 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
         return recd_fail(ctx, RECD_EINVAL, "F*B and M_cap must stay below 2^31");
     if (!feat_roff || !feat_uoff || !u_offsets || (F > 0 && !rows))
         return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
-    if (n_lists > 0 && (!grad_out || !inverse))
+    if (n_lists > 0 && ((!grad_out && !(seq && N == 0)) || !inverse))
         return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
     if (M_cap > 0 && (!u_values || !touched_rows))
         return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
@@ -924,14 +1023,14 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
         if (!wide) {
             uint32_t *k0 = static_cast<uint32_t *>(w.b.k0), *k1 = static_cast<uint32_t *>(w.b.k1), *ks;
             hipLaunchKernelGGL((k_keys_ids<uint32_t, SG>), dim3(kb), dim3(256), 0, side, u_values,
-                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev);
+                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev, seq ? 1 : 0);
             RECD_TRY(radix_sort_pairs<uint32_t>(ctx, side, k0, w.b.p0, k1, w.b.p1, w.b.n_dev, M_cap, bits_b,
                                                 w.b.hist, w.b.bsum, &ks, &ps_b));
             ks_b = ks;
         } else {
             uint64_t *k0 = static_cast<uint64_t *>(w.b.k0), *k1 = static_cast<uint64_t *>(w.b.k1), *ks;
             hipLaunchKernelGGL((k_keys_ids<uint64_t, SG>), dim3(kb), dim3(256), 0, side, u_values,
-                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev);
+                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev, seq ? 1 : 0);
             RECD_TRY(radix_sort_pairs<uint64_t>(ctx, side, k0, w.b.p0, k1, w.b.p1, w.b.n_dev, M_cap, bits_b,
                                                 w.b.hist, w.b.bsum, &ks, &ps_b));
             ks_b = ks;
@@ -946,18 +1045,48 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
                            inverse, feat_uoff, B, n_lists, k0, w.a.p0, w.a.n_dev);
         RECD_TRY(radix_sort_pairs<uint32_t>(ctx, st, k0, w.a.p0, k1, w.a.p1, w.a.n_dev, n_lists, bits_a,
                                             w.a.hist, w.a.bsum, &ks, &ps));
-        RECD_TRY(segment_and_sum<uint32_t>(ctx, w, w.a, ks, ps, n_lists, U_cap, -1, F, grad_out, D, w.g_u,
-                                           nullptr, nullptr, nullptr));
+        if (!seq) {
+            RECD_TRY(segment_and_sum<uint32_t>(ctx, w, w.a, ks, ps, n_lists, U_cap, -1, F, grad_out, D, w.g_u,
+                                               nullptr, nullptr, nullptr));
+        } else {
+            RECD_TRY(number_segments<uint32_t>(ctx, w, w.a, ks, n_lists, -1, F, nullptr, nullptr));
+            // lists per block: about 128 positions
+            const double avg = (double)M_cap / (double)(U_cap > 0 ? U_cap : 1);
+            int lists = 1;
+            while (lists < 64 && 2.0 * lists * avg <= 192.0)
+                lists *= 2;
+            int64_t blocks = (U_cap + lists - 1) / lists;
+            if (blocks > (int64_t)ctx->num_cu * 64)
+                blocks = (int64_t)ctx->num_cu * 64;
+            if (blocks < 1)
+                blocks = 1;
+#define RECD_JR(L)                                                                                    \
+    hipLaunchKernelGGL((k_jagged_reduce<L>), dim3((unsigned)blocks), dim3(256), 0, st,                 \
+                       reinterpret_cast<const float4 *>(grad_out), kjt_offsets, ps, w.seg_start,       \
+                       w.list_off + 1, u_offsets, reinterpret_cast<float4 *>(grad_emb), D / 4, N, M_cap)
+            switch (lists) {
+            case 1: RECD_JR(1); break;
+            case 2: RECD_JR(2); break;
+            case 4: RECD_JR(4); break;
+            case 8: RECD_JR(8); break;
+            case 16: RECD_JR(16); break;
+            case 32: RECD_JR(32); break;
+            default: RECD_JR(64); break;
+            }
+#undef RECD_JR
+            RECD_HIP(ctx, hipGetLastError());
+        }
     }
+    const float *b_table = seq ? grad_emb : w.g_u;
     // ---- step B: group unique-id positions by (feature, row), sum g_u rows into grad_rows --------
     RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
     if (!wide)
         RECD_TRY(segment_and_sum<uint32_t>(ctx, w, w.b, static_cast<const uint32_t *>(ks_b), ps_b, M_cap,
-                                           M_cap, row_bits, F, w.g_u, D, grad_rows, touched_rows,
+                                           M_cap, row_bits, F, b_table, D, grad_rows, touched_rows,
                                            feat_roff, fused ? &oa : nullptr));
     else
         RECD_TRY(segment_and_sum<uint64_t>(ctx, w, w.b, static_cast<const uint64_t *>(ks_b), ps_b, M_cap,
-                                           M_cap, row_bits, F, w.g_u, D, grad_rows, touched_rows,
+                                           M_cap, row_bits, F, b_table, D, grad_rows, touched_rows,
                                            feat_roff, fused ? &oa : nullptr));
     // ---- optimizer -------------------------------------------------------------------------------
     if (tables && !fused) {
@@ -984,6 +1113,35 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
             return recd_fail(ctx, RECD_ECAPACITY, "M_cap=%lld is smaller than M", (long long)M_cap);
     }
     return RECD_OK;
+}
+
+extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int D,
+                                           const float *grad_out, const int32_t *inverse,
+                                           const int64_t *feat_uoff, const int64_t *u_values,
+                                           const int64_t *u_offsets, const int64_t *rows,
+                                           int64_t U_cap, int64_t M_cap, int64_t *touched_rows,
+                                           int64_t *feat_roff, float *grad_rows, void *const *tables,
+                                           float *const *adagrad_state, float lr, float eps,
+                                           int64_t *host_R)
+{
+    return backward_common(ctx, false, F, B, 0, D, grad_out, nullptr, inverse, feat_uoff, u_values,
+                           u_offsets, rows, U_cap, M_cap, nullptr, touched_rows, feat_roff, grad_rows, tables,
+                           adagrad_state, lr, eps, host_R);
+}
+
+extern "C" recd_status recd_backward_sequence_dedup(recd_ctx *ctx, int F, int64_t B, int64_t N, int D,
+                                                    const float *grad_out, const int64_t *offsets,
+                                                    const int32_t *inverse, const int64_t *feat_uoff,
+                                                    const int64_t *u_values, const int64_t *u_offsets,
+                                                    const int64_t *rows, int64_t U_cap, int64_t M_cap,
+                                                    float *grad_emb, int64_t *touched_rows,
+                                                    int64_t *feat_roff, float *grad_rows,
+                                                    void *const *tables, float *const *adagrad_state,
+                                                    float lr, float eps, int64_t *host_R)
+{
+    return backward_common(ctx, true, F, B, N, D, grad_out, offsets, inverse, feat_uoff, u_values, u_offsets,
+                           rows, U_cap, M_cap, grad_emb, touched_rows, feat_roff, grad_rows, tables,
+                           adagrad_state, lr, eps, host_R);
 }
 
 size_t recd_build_workspace(int F, int64_t B);

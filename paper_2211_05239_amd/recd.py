@@ -35,7 +35,7 @@ EXPORTED = [
     "recd_kjt_pooled_lookup", "recd_backward_dedup", "recd_sequence_lookup_unique",
     "recd_jagged_expand_inverse", "recd_kjt_sequence_lookup", "recd_build_ikjt_grouped",
     "recd_group_sum_unique", "recd_pooled_lookup_unique_mode", "recd_kjt_pooled_lookup_mode",
-    "recd_build_partial_ikjt", "recd_pooled_lookup_partial",
+    "recd_build_partial_ikjt", "recd_pooled_lookup_partial", "recd_backward_sequence_dedup",
 ]
 
 _vp = C.c_void_p
@@ -71,6 +71,9 @@ _lib.recd_kjt_pooled_lookup_mode.argtypes = [_vp, C.c_int] + _lib.recd_kjt_poole
 _lib.recd_build_partial_ikjt.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64] + [_vp] * 10
 _lib.recd_pooled_lookup_partial.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, C.c_int64,
                                             _vp, _vp, _vp, C.c_int64, _vp]
+_lib.recd_backward_sequence_dedup.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, C.c_int, _vp, _vp, _vp, _vp, _vp,
+                                              _vp, _vp, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp, _vp, _vp,
+                                              C.c_float, C.c_float, _vp]
 for _n in EXPORTED:
     if _n not in ("recd_last_error", "recd_status_string"):
         getattr(_lib, _n).restype = C.c_int
@@ -257,3 +260,18 @@ class Context:
             self._h, F, D, tdt, _DT[pooled.dtype], self._table_array(tables), self._rows_array(tables),
             _ptr(p_values), p_values.numel(), _ptr(win_start), _ptr(win_len), _ptr(feat_uoff), max_lists,
             _ptr(pooled)))
+
+    def backward_sequence_dedup(self, F: int, B: int, grad_out, offsets, inverse, feat_uoff, u_values, u_offsets,
+                                rows: Sequence[int], U_cap: int, M_cap: int, grad_emb, touched_rows, feat_roff,
+                                grad_rows, tables=None, adagrad_state=None, lr: float = 0.0, eps: float = 0.0,
+                                want_count: bool = False):
+        D = grad_out.shape[-1]
+        rows_arr = (C.c_int64 * len(rows))(*rows)
+        tabs = self._table_array(tables) if tables is not None else None
+        state = self._table_array(adagrad_state) if adagrad_state is not None else None
+        host = (C.c_int64 * 1)(0) if want_count else None
+        self._check(_lib.recd_backward_sequence_dedup(
+            self._h, F, B, grad_out.shape[0], D, _ptr(grad_out), _ptr(offsets), _ptr(inverse), _ptr(feat_uoff),
+            _ptr(u_values), _ptr(u_offsets), rows_arr, U_cap, M_cap, _ptr(grad_emb), _ptr(touched_rows),
+            _ptr(feat_roff), _ptr(grad_rows), tabs, state, lr, eps, host))
+        return int(host[0]) if want_count else None

@@ -139,6 +139,70 @@ def test_jagged_expand_runs_of_duplicates(ctx, mean_len):
     assert torch.equal(_bits(out), _bits(kjt))
 
 
+# ------------------------------------------------------------------ backward of the sequence path
+def _sequence_backward_case(ctx, w, batch_index=0, with_adagrad=True, seed=0):
+    batch = synth.make_batch(w, batch_index)
+    tabs = synth.make_tables(w)
+    F, B, D, N = w.F, w.B, w.D, batch.N
+    rng = np.random.default_rng(600 + seed)
+    gout = (rng.standard_normal((max(N, 1), D), dtype=np.float32) * np.float32(0.01))[:N]
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    d_tabs = gu.tables_to_dev(tabs, "f32")
+    state = [torch.zeros(w.rows, device="cuda") for _ in range(F)]
+    grad_emb = torch.full((max(ik.M, 1), D), float("nan"), device="cuda")
+    touched = torch.full((max(ik.M, 1),), -1, dtype=torch.int64, device="cuda")
+    feat_roff = torch.zeros(F + 1, dtype=torch.int64, device="cuda")
+    grad_rows = torch.zeros(max(ik.M, 1), D, device="cuda")
+    d_gout = gu.to_dev(gout) if N else torch.zeros(1, D, device="cuda")[:0]
+    R = ctx.backward_sequence_dedup(F, B, d_gout, offsets, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets,
+                                    [w.rows] * F, ik.U, ik.M, grad_emb, touched, feat_roff, grad_rows,
+                                    tables=d_tabs if with_adagrad else None,
+                                    adagrad_state=state if with_adagrad else None, lr=0.01, eps=1e-8,
+                                    want_count=True)
+    torch.cuda.synchronize()
+    uv, uo, inv, fu = orc.build_ikjt(F, B, batch.values, batch.offsets)
+    tr, fr, gr = orc.backward_sequence_kjt(F, B, gout, batch.values, batch.offsets)
+    assert R == len(tr) and np.array_equal(touched[:R].cpu().numpy(), tr)
+    assert np.array_equal(feat_roff.cpu().numpy(), fr)
+    gu.assert_close_f32(gu.out_to_f64(grad_rows[:R]), gr, "row gradients of the sequence path")
+    # the gradient of the unique activations: every KJT position added into its unique position
+    ref_emb = np.zeros((len(uv), D))
+    for f in range(F):
+        for b in range(B):
+            l = f * B + b
+            u = fu[f] + inv[l]
+            n = batch.offsets[l + 1] - batch.offsets[l]
+            ref_emb[uo[u]:uo[u] + n] += gout[batch.offsets[l]:batch.offsets[l] + n].astype(np.float64)
+    gu.assert_close_f32(gu.out_to_f64(grad_emb[:ik.M]), ref_emb, "grad_emb")
+    if with_adagrad:
+        for f in range(F):
+            rows_f = tr[fr[f]:fr[f + 1]]
+            w_new, m_new = orc.rowwise_adagrad(gr[fr[f]:fr[f + 1]], tabs[f][rows_f].astype(np.float64),
+                                               np.zeros(len(rows_f)), 0.01, 1e-8)
+            gu.assert_close_f32(d_tabs[f].cpu().numpy()[rows_f].astype(np.float64), w_new, f"updated rows {f}")
+            gu.assert_close_f32(state[f].cpu().numpy()[rows_f].astype(np.float64), m_new, f"state {f}")
+    return grad_emb, grad_rows, touched, R
+
+
+@pytest.mark.parametrize("name,F,B,D", [("cfg1", 3, 300, 64), ("cfg2", 4, 1500, 128), ("cfg4", 2, 400, 32),
+                                        ("cfg3", 2, 700, 256)])
+def test_sequence_backward(ctx, name, F, B, D):
+    w = synth.scaled(synth.WORKLOADS[name], F=F, B=B, rows=2000, D=D, table_dtype="f32")
+    _sequence_backward_case(ctx, w)
+
+
+def test_sequence_backward_without_optimizer_and_deterministic(ctx):
+    w = synth.scaled(synth.WORKLOADS["cfg2"], F=3, B=2000, rows=500, D=64)
+    a = _sequence_backward_case(ctx, w, with_adagrad=False)
+    b = _sequence_backward_case(ctx, w, with_adagrad=False)
+    assert torch.equal(_bits(a[0]), _bits(b[0])) and torch.equal(a[1][:a[3]], b[1][:b[3]])
+
+
+def test_sequence_backward_no_ids(ctx):
+    w = synth.scaled(synth.WORKLOADS["cfg1"], F=2, B=5, rows=10, D=8, len_max=0)
+    _sequence_backward_case(ctx, w, with_adagrad=False)
+
+
 def test_sequence_no_ids(ctx):
     batch = synth.batch_from_lists([[[], [], []], [[], [], []]])
     tabs = [np.ones((4, 8), np.float32)] * 2
