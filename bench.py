@@ -445,12 +445,31 @@ def sequence_regions(torch, P, cnt, timed, reps, R):
 
     for i in range(len(P.batches)):
         seq(i), jag(i), kjt(i)
-    t = {"seq": [], "jag": [], "kjt": []}
+    t = {"seq": [], "jag": [], "kjt": [], "bwd": []}
     for _ in range(max(reps // 2, 2)):
         t["seq"].append(timed(seq))
         t["jag"].append(timed(jag))
         t["kjt"].append(timed(kjt))
     seq_ms, jag_ms, kjt_ms = (float(np.mean(t[k])) for k in ("seq", "jag", "kjt"))
+    bwd_ms = None
+    if P.need_backward:
+        # backward of the sequence path: the KJT-shaped buffer now plays the upstream gradient
+        grad_emb = emb if emb.dtype == torch.float32 else torch.empty(Mmax, D, dtype=torch.float32, device="cuda")
+        gout = out if out.dtype == torch.float32 else None
+        if gout is not None:
+            gout.normal_(0.0, 0.01)
+
+            def bwd(i):
+                P.ctx.backward_sequence_dedup(F, B, gout[:P.batches[i].N], P.offsets[i], P.inverse[i],
+                                              P.feat_uoff[i], P.u_values[i], P.u_offsets[i], P.rows, cnt[i][0],
+                                              cnt[i][1], grad_emb, P.touched, P.feat_roff, None, tables=P.tables,
+                                              adagrad_state=P.state, lr=0.01, eps=1e-8)
+
+            for i in range(len(P.batches)):
+                bwd(i)
+            for _ in range(max(reps // 2, 2)):
+                t["bwd"].append(timed(bwd))
+            bwd_ms = float(np.mean(t["bwd"]))
     N = float(np.mean([b.N for b in P.batches]))
     U = float(np.mean([c[0] for c in cnt]))
     M = float(np.mean([c[1] for c in cnt]))
@@ -459,7 +478,12 @@ def sequence_regions(torch, P, cnt, timed, reps, R):
           "jagged_expand": F * B * (4 + 8) + U * 8 + M * D * e + N * D * e,
           "kjt_sequence": N * 8 + rd * D * e + N * D * e}
     ms = {"sequence_lookup_unique": seq_ms, "jagged_expand": jag_ms, "kjt_sequence": kjt_ms}
+    if bwd_ms is not None:
+        Rr = M if R is None else R
+        by["backward_sequence"] = N * D * 4 + F * B * (4 + 8) + M * D * 4 * 2 + Rr * (2 * D * 4 + 8)
+        ms["backward_sequence"] = bwd_ms
     return {"sequence_lookup_unique_ms": seq_ms, "jagged_expand_ms": jag_ms, "kjt_sequence_ms": kjt_ms,
+            "backward_sequence_ms": bwd_ms,
             "bytes": by, "gbs": {k: by[k] / ms[k] / 1e6 for k in by},
             "activation_bytes_unique": M * D * e, "activation_bytes_kjt": N * D * e,
             "speedup_vs_kjt": kjt_ms / (seq_ms + jag_ms)}

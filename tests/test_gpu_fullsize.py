@@ -283,3 +283,63 @@ def test_cfg5_partial_full(recd):
     ctx.pooled_lookup_unique(tabs, ik.u_values, ik.u_offsets, ik.feat_uoff, ik.U, ref)
     assert U == ik.U and torch.equal(pooled, ref)
     ctx.close()
+
+
+def test_cfg5_sequence_backward_full(recd):
+    """Backward of the sequence path at configuration 5's size (35 M gradient rows): touched rows of
+    every feature exactly, row gradients, the gradient of the unique activations and the Adagrad update
+    of sampled features against the oracle."""
+    w = synth.WORKLOADS["cfg5"]
+    F, B, D = w.F, w.B, w.D
+    batch = synth.make_batch(w, 1)
+    N = batch.N
+    tabs = _device_tables(w, torch.float32)
+    sample = (7, 50)
+    before = {f: tabs[f].cpu().numpy() for f in sample}
+    g = torch.Generator(device="cuda")
+    g.manual_seed(4242)
+    grad_out = torch.empty(N, D, dtype=torch.float32, device="cuda")
+    grad_out.normal_(0.0, 0.01, generator=g)
+    state = [torch.zeros(w.rows, device="cuda") for _ in range(F)]
+    ctx = recd.Context(0)
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    grad_emb = torch.zeros(ik.M, D, device="cuda")
+    touched = torch.full((ik.M,), -1, dtype=torch.int64, device="cuda")
+    feat_roff = torch.zeros(F + 1, dtype=torch.int64, device="cuda")
+    grad_rows = torch.zeros(ik.M, D, device="cuda")
+    R = ctx.backward_sequence_dedup(F, B, grad_out, offsets, ik.inverse, ik.feat_uoff, ik.u_values,
+                                    ik.u_offsets, [w.rows] * F, ik.U, ik.M, grad_emb, touched, feat_roff,
+                                    grad_rows, tables=tabs, adagrad_state=state, lr=0.01, eps=1e-8,
+                                    want_count=True)
+    torch.cuda.synchronize()
+    fr = feat_roff.cpu().numpy()
+    tr = touched[:R].cpu().numpy()
+    assert fr[0] == 0 and fr[-1] == R
+    for f in range(F):
+        lo, hi = batch.offsets[f * B], batch.offsets[(f + 1) * B]
+        assert np.array_equal(tr[fr[f]:fr[f + 1]], np.unique(batch.values[lo:hi])), f
+    uo = ik.u_offsets[:ik.U + 1].cpu().numpy()
+    fu = ik.feat_uoff.cpu().numpy()
+    for f in sample:
+        v_f, o_f = _feature_slice(batch, f)
+        lo, hi = int(batch.offsets[f * B]), int(batch.offsets[(f + 1) * B])
+        gout_f = grad_out[lo:hi].cpu().numpy()
+        tr_f, _, gr_f = orc.backward_sequence_kjt(1, B, gout_f, v_f, o_f)
+        assert np.array_equal(tr_f, tr[fr[f]:fr[f + 1]])
+        gu.assert_close_f32(grad_rows[fr[f]:fr[f + 1]].double().cpu().numpy(), gr_f, f"grad rows {f}")
+        uv_f, uo_f, inv_f, fu_f = orc.build_ikjt(1, B, v_f, o_f)
+        ref_emb = np.zeros((len(uv_f), D))
+        for b in range(B):
+            n = o_f[b + 1] - o_f[b]
+            u = inv_f[b]
+            ref_emb[uo_f[u]:uo_f[u] + n] += gout_f[o_f[b]:o_f[b] + n].astype(np.float64)
+        ulo, uhi = int(uo[fu[f]]), int(uo[fu[f + 1]])
+        gu.assert_close_f32(grad_emb[ulo:uhi].double().cpu().numpy(), ref_emb, f"grad_emb {f}")
+        w_new, m_new = orc.rowwise_adagrad(gr_f, before[f][tr_f].astype(np.float64), np.zeros(len(tr_f)),
+                                           0.01, 1e-8)
+        after = tabs[f].cpu().numpy()
+        gu.assert_close_f32(after[tr_f].astype(np.float64), w_new, f"updated rows {f}")
+        untouched = np.ones(w.rows, bool)
+        untouched[tr_f] = False
+        assert np.array_equal(after[untouched], before[f][untouched])
+    ctx.close()
