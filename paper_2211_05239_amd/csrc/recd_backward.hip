@@ -660,7 +660,10 @@ int bits_for(uint64_t max_value)
 // grad_out[offsets[l] + t, :].  The rows of u are ps[seg_start[u] .. seg_start[u+1]) (rows sorted by
 // unique list; every list has at least one row, so segment number = list number).  A block owns
 // LISTS consecutive unique lists and numbers their positions flat, so long and short lists load
-// the threads alike; a thread = one 16-byte piece of one position, four source rows in flight.
+// the threads alike.  The start offsets of up to 64 source rows per list are staged in LDS, so
+// the inner loop is row loads only, eight in flight per thread (a thread = one 16-byte piece of
+// one position); lists with more rows take further rounds that continue from the stored partial
+// sum - the same additions in the same order.
 template <int LISTS>
 __global__ __launch_bounds__(256) void k_jagged_reduce(const float4 *__restrict__ grad_out,
                                                        const int64_t *__restrict__ offsets,
@@ -672,8 +675,13 @@ __global__ __launch_bounds__(256) void k_jagged_reduce(const float4 *__restrict_
                                                        int64_t n_rows, int64_t m_cap)
 {
     static_assert(LISTS <= 64 && (LISTS & (LISTS - 1)) == 0, "one wave prepares the block's lists");
+    constexpr int kRound = 64;  // source rows per list and round
+    constexpr int kFly = 8;     // row loads in flight per thread
     __shared__ uint32_t rel_s[LISTS + 1];
-    __shared__ int64_t pos_s[LISTS];
+    __shared__ int64_t pos_s[LISTS], seg_s[LISTS];
+    __shared__ uint32_t cnt_s[LISTS];
+    __shared__ uint32_t cmax_s;
+    __shared__ int64_t off_s[LISTS][kRound];
     const int64_t U = *n_seg;
     const uint32_t rows_per_sweep = 256 / vecs;
     const uint32_t piece = threadIdx.x % vecs, sub = threadIdx.x / vecs;
@@ -682,60 +690,82 @@ __global__ __launch_bounds__(256) void k_jagged_reduce(const float4 *__restrict_
         __syncthreads();  // the previous lists are done with the shared arrays
         if (threadIdx.x < 64) {
             const uint32_t i = threadIdx.x;
-            int64_t start = 0;
-            uint32_t len = 0;
+            int64_t start = 0, s0 = 0;
+            uint32_t len = 0, c = 0;
             if (i < nl) {
                 start = u_offsets[u0 + i];
                 len = (uint32_t)(u_offsets[u0 + i + 1] - start);
+                s0 = seg_start[u0 + i];
+                c = (uint32_t)(seg_start[u0 + i + 1] - s0);
             }
-            uint32_t incl = len;
+            uint32_t incl = len, cmax = c;
 #pragma unroll
             for (int d = 1; d < 64; d <<= 1) {
                 const uint32_t x = __shfl_up(incl, d);
                 if (i >= (uint32_t)d)
                     incl += x;
+                const uint32_t y = __shfl_xor(cmax, d);
+                cmax = y > cmax ? y : cmax;
             }
             if (i < nl) {
                 rel_s[i] = incl - len;
                 pos_s[i] = start;
+                seg_s[i] = s0;
+                cnt_s[i] = c;
             }
-            if (i == 63)
+            if (i == 63) {
                 rel_s[nl] = incl;
+                cmax_s = cmax;
+            }
         }
         __syncthreads();
         const uint32_t total = rel_s[nl];
-        if (sub >= rows_per_sweep)
-            continue;
-        for (uint32_t r = sub; r < total; r += rows_per_sweep) {
-            uint32_t a = 0;  // the last list with rel_s[a] <= r; r < rel_s[nl], so it is not empty
-#pragma unroll
-            for (uint32_t s = LISTS / 2; s >= 1; s >>= 1)
-                if (a + s < nl && rel_s[a + s] <= r)
-                    a += s;
-            const int64_t t = r - rel_s[a];
-            const int64_t s0 = seg_start[u0 + a], s1 = seg_start[u0 + a + 1];
-            float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-            for (int64_t i = s0; i < s1; i += 4) {
-                float4 v[4];
-#pragma unroll
-                for (int k = 0; k < 4; k++) {
-                    const int64_t l = ps[i + k < s1 ? i + k : s1 - 1];
-                    int64_t src = offsets[l] + t;
-                    src = src < n_rows ? src : n_rows - 1;  // only a malformed IKJT gets here
-                    v[k] = grad_out[src * vecs + piece];
-                }
-#pragma unroll
-                for (int k = 0; k < 4; k++)
-                    if (i + k < s1) {
-                        acc.x += v[k].x;
-                        acc.y += v[k].y;
-                        acc.z += v[k].z;
-                        acc.w += v[k].w;
-                    }
+        const uint32_t cmax = cmax_s;
+        for (uint32_t c0 = 0; c0 < cmax; c0 += kRound) {
+            if (c0 > 0)
+                __syncthreads();  // the previous round's offsets have been used
+            for (uint32_t idx = threadIdx.x; idx < nl * kRound; idx += 256) {
+                const uint32_t a = idx / kRound, i = idx % kRound;
+                if (c0 + i < cnt_s[a])
+                    off_s[a][i] = offsets[ps[seg_s[a] + c0 + i]];
             }
-            const int64_t j = pos_s[a] + t;
-            if (j < m_cap)
+            __syncthreads();
+            if (sub >= rows_per_sweep)
+                continue;
+            for (uint32_t r = sub; r < total; r += rows_per_sweep) {
+                uint32_t a = 0;  // the last list with rel_s[a] <= r; r < rel_s[nl], so it is not empty
+#pragma unroll
+                for (uint32_t s = LISTS / 2; s >= 1; s >>= 1)
+                    if (a + s < nl && rel_s[a + s] <= r)
+                        a += s;
+                const uint32_t c = cnt_s[a];
+                if (c <= c0)
+                    continue;  // this list has no rows left in this round
+                const uint32_t n = c - c0 < (uint32_t)kRound ? c - c0 : (uint32_t)kRound;
+                const int64_t t = r - rel_s[a];
+                const int64_t j = pos_s[a] + t;
+                if (j >= m_cap)
+                    continue;
+                float4 acc = c0 == 0 ? make_float4(0.f, 0.f, 0.f, 0.f) : g_emb[j * vecs + piece];
+                for (uint32_t i = 0; i < n; i += kFly) {
+                    float4 v[kFly];
+#pragma unroll
+                    for (int k = 0; k < kFly; k++) {
+                        int64_t src = off_s[a][i + k < n ? i + k : n - 1] + t;
+                        src = src < n_rows ? src : n_rows - 1;  // only a malformed IKJT gets here
+                        v[k] = grad_out[src * vecs + piece];
+                    }
+#pragma unroll
+                    for (int k = 0; k < kFly; k++)
+                        if (i + k < n) {
+                            acc.x += v[k].x;
+                            acc.y += v[k].y;
+                            acc.z += v[k].z;
+                            acc.w += v[k].w;
+                        }
+                }
                 g_emb[j * vecs + piece] = acc;
+            }
         }
     }
 }
