@@ -145,7 +145,7 @@ recd_status recd_expand_inverse(recd_ctx *ctx, int F, int64_t B, int D, recd_dty
 /* 4. Comparison path: the same pooled lookup over every row of the KJT, no deduplication
  *    (Sec. 5 "EMB Lookups", the pre-RecD behaviour).  out: device [F, B, D] of out_dt.
  *    The summation order of a list depends on the list alone, so out equals the result of calls
- *    1-3 bit for bit. */
+ *    1-3 bit for bit.  values may be NULL when every list is empty. */
 recd_status recd_kjt_pooled_lookup(recd_ctx *ctx, int F, int64_t B, int D, recd_dtype table_dt,
                                    recd_dtype out_dt, const void *const *tables,
                                    const int64_t *rows, const int64_t *values,

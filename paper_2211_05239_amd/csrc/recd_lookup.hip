@@ -805,7 +805,7 @@ static recd_status lookup_kjt(recd_ctx *ctx, int mode, int F, int64_t B, int D, 
         return recd_fail(ctx, RECD_EINVAL, "B < 0");
     if (F == 0 || B == 0)
         return RECD_OK;
-    if (!tables || !values || !offsets || !out)
+    if (!tables || !offsets || !out)  // values may be null when every list is empty (N = 0)
         return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
     for (int f = 0; f < F; f++)
         if (!tables[f])
