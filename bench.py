@@ -33,7 +33,7 @@ def parse_args():
     ap.add_argument("--workload", default="cfg5",
                     help="cfg1..cfg5 or cfg4_S<k> (duplication sweep member)")
     ap.add_argument("--batches", type=int, default=4, help="distinct seeded batches to rotate over")
-    ap.add_argument("--cpu-features", type=int, default=32,
+    ap.add_argument("--cpu-features", type=int, default=64,
                     help="features of batch 0 the CPU oracle is timed on (0 = skip)")
     ap.add_argument("--sweep", action="store_true", help="also run the duplication sweep (cfg4, S in 1,2,4,8,32)")
     ap.add_argument("--forward-only", action="store_true", help="leave the backward pass out of the step")
