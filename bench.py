@@ -556,6 +556,42 @@ def reader_regions(P, build_ms, max_seconds=20.0):
             "gpu_over_cpu": gpu_lists_s / cpu_lists_s}
 
 
+def cpu_baseline_parallel(torch, P, max_seconds=20.0):
+    """The same oracle work feature-parallel: one task per feature of batch 0 (features are
+    independent; the oracle's C code runs outside the interpreter lock) on the host's cores."""
+    import concurrent.futures as cf
+    from oracle import recd_oracle as orc
+    w, b = P.w, P.batches[0]
+    B, dt = w.B, w.table_dtype
+    cores = min(os.cpu_count() or 1, 16)
+    gout = P.grad_out.cpu().numpy() if P.need_backward else None
+
+    tabs = [t.view(torch.int16).cpu().numpy().view(np.uint16) if dt == "bf16" else t.cpu().numpy()
+            for t in P.tables]
+
+    def one(f):
+        tab = tabs[f]
+        lo, hi = int(b.offsets[f * B]), int(b.offsets[(f + 1) * B])
+        values, offsets = b.values[lo:hi], b.offsets[f * B:(f + 1) * B + 1] - lo
+        t0 = time.perf_counter()
+        uv, uo, inv, fu = orc.build_ikjt(1, B, values, offsets)
+        pooled = orc.pooled_lookup([tab], dt, uv, uo, fu)
+        orc.expand_inverse(1, B, pooled, fu, inv)
+        if gout is not None:
+            tr, fr, gr = orc.backward_dedup(1, B, gout[f:f + 1], inv, fu, uv, uo)
+            orc.rowwise_adagrad(gr, tab[tr].astype(np.float64), np.zeros(len(tr)), 0.01, 1e-8)
+        return time.perf_counter() - t0
+
+    per = one(0)
+    n_feat = int(min(w.F, max(cores, cores * (max_seconds / max(per, 1e-6)) // 1)))
+    t0 = time.perf_counter()
+    with cf.ThreadPoolExecutor(max_workers=cores) as ex:
+        list(ex.map(one, range(n_feat)))
+    wall = time.perf_counter() - t0
+    return {"value": B * n_feat / wall, "unit": "pooled lookups/s", "cores": cores, "kind": "oracle",
+            "seconds": wall, "sample": f"features 0..{n_feat - 1} of batch 0, one task per feature on {cores} threads"}
+
+
 def measured_traffic(workload_name):
     """HBM bytes per launch of the unique-lookup kernel, from the committed rocprofv3 --pmc summary
     (FETCH_SIZE and WRITE_SIZE, calibrated against a plain copy); None if there is none."""
@@ -634,6 +670,7 @@ def main():
                              "note": "same K steps, builder of the next batch on a second stream; not `value`"}
     if args.cpu_features > 0:
         line["cpu_baseline"] = cpu_baseline(torch, synth, P, args.cpu_features)
+        line["cpu_baseline_parallel"] = cpu_baseline_parallel(torch, P)
     if args.reader:
         line["regions"]["reader"] = reader_regions(P, res["build_ms"])
     P.ctx.close()
