@@ -532,6 +532,80 @@ int oracle_backward_kjt(int F, int64_t B, int D, const float *grad_out, const in
     return 0;
 }
 
+/* ---- backward of expand + AVERAGE-pooled lookup (pooling modes: Sec. 2.2) --------------------
+ * Forward: pooled[u] = (1/len_u) * sum of the rows of list u (0 for an empty list), so every
+ * position j of list u receives g_u[u] / len_u:
+ * step 1  as oracle_backward_dedup
+ * step 2  G_f[r,:] = sum over positions j ascending with u_values[j] == r of
+ *                    g_u[list containing j, :] / len(list containing j)
+ */
+int oracle_backward_dedup_mean(int F, int64_t B, int D, const float *grad_out, const int32_t *inverse,
+                               const int64_t *feat_uoff, const int64_t *u_values,
+                               const int64_t *u_offsets, int64_t *touched_rows, int64_t *feat_roff,
+                               double *grad_rows)
+{
+    int64_t U = feat_uoff[F];
+    double *g_u = (double *)calloc((size_t)(U > 0 ? U : 1) * D, sizeof(double));
+    if (!g_u)
+        return -9;
+    for (int f = 0; f < F; f++)
+        for (int64_t b = 0; b < B; b++) {
+            int64_t u = feat_uoff[f] + inverse[(int64_t)f * B + b];
+            for (int d = 0; d < D; d++)
+                g_u[u * D + d] += (double)grad_out[((int64_t)f * B + b) * D + d];
+        }
+    int64_t R = 0;
+    for (int f = 0; f < F; f++) {
+        feat_roff[f] = R;
+        int64_t j0 = u_offsets[feat_uoff[f]], j1 = u_offsets[feat_uoff[f + 1]];
+        int64_t r_f = sorted_distinct(u_values + j0, j1 - j0, touched_rows + R);
+        double *G = grad_rows + R * D;
+        for (int64_t i = 0; i < r_f * D; i++)
+            G[i] = 0.0;
+        for (int64_t u = feat_uoff[f]; u < feat_uoff[f + 1]; u++) {
+            double len = (double)(u_offsets[u + 1] - u_offsets[u]);
+            for (int64_t j = u_offsets[u]; j < u_offsets[u + 1]; j++) {
+                int64_t k = find_row(touched_rows + R, r_f, u_values[j]);
+                for (int d = 0; d < D; d++)
+                    G[k * D + d] += g_u[u * D + d] / len;
+            }
+        }
+        R += r_f;
+    }
+    feat_roff[F] = R;
+    free(g_u);
+    return 0;
+}
+
+/* the same gradient straight from the KJT: every position of list (f,b) receives
+ * grad_out[f,b,:] / len(f,b) */
+int oracle_backward_kjt_mean(int F, int64_t B, int D, const float *grad_out, const int64_t *values,
+                             const int64_t *offsets, int64_t *touched_rows, int64_t *feat_roff,
+                             double *grad_rows)
+{
+    int64_t R = 0;
+    for (int f = 0; f < F; f++) {
+        feat_roff[f] = R;
+        int64_t j0 = offsets[(int64_t)f * B], j1 = offsets[(int64_t)(f + 1) * B];
+        int64_t r_f = sorted_distinct(values + j0, j1 - j0, touched_rows + R);
+        double *G = grad_rows + R * D;
+        for (int64_t i = 0; i < r_f * D; i++)
+            G[i] = 0.0;
+        for (int64_t b = 0; b < B; b++) {
+            int64_t l = (int64_t)f * B + b;
+            double len = (double)(offsets[l + 1] - offsets[l]);
+            for (int64_t j = offsets[l]; j < offsets[l + 1]; j++) {
+                int64_t k = find_row(touched_rows + R, r_f, values[j]);
+                for (int d = 0; d < D; d++)
+                    G[k * D + d] += (double)grad_out[l * D + d] / len;
+            }
+        }
+        R += r_f;
+    }
+    feat_roff[F] = R;
+    return 0;
+}
+
 /* ---- backward of the jagged expand + unpooled lookup (chain rule of the two forward steps of
  * the sequence path; the paper describes the forward side only, Sec. 5) ---------------------------
  * grad_out holds one gradient row per KJT position (the layout of the expanded activations).

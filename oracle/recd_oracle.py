@@ -252,8 +252,9 @@ def jagged_expand(F: int, B: int, emb: np.ndarray, u_offsets, feat_uoff, inverse
     return out[:N]
 
 
-def backward_dedup(F: int, B: int, grad_out: np.ndarray, inverse, feat_uoff, u_values, u_offsets):
-    """Returns (touched_rows[R] int64, feat_roff[F+1], grad_rows[R,D] float64)."""
+def backward_dedup(F: int, B: int, grad_out: np.ndarray, inverse, feat_uoff, u_values, u_offsets,
+                   mode: str = "sum"):
+    """Returns (touched_rows[R] int64, feat_roff[F+1], grad_rows[R,D] float64); mode "sum" or "mean"."""
     grad_out = np.ascontiguousarray(grad_out, dtype=np.float32)
     D = grad_out.shape[-1]
     inverse = np.ascontiguousarray(inverse, dtype=np.int32)
@@ -262,16 +263,15 @@ def backward_dedup(F: int, B: int, grad_out: np.ndarray, inverse, feat_uoff, u_v
     touched = np.zeros(max(M, 1), dtype=np.int64)
     feat_roff = np.zeros(F + 1, dtype=np.int64)
     grad_rows = np.zeros((max(M, 1), D), dtype=np.float64)
-    rc = _lib.oracle_backward_dedup(C.c_int(F), C.c_int64(B), C.c_int(D), _p(grad_out, _f32p),
-                                    _p(inverse, _i32p), _p(feat_uoff, _i64p), _p(u_values, _i64p),
-                                    _p(u_offsets, _i64p), _p(touched, _i64p), _p(feat_roff, _i64p),
-                                    _p(grad_rows, _f64p))
+    fn = {"sum": _lib.oracle_backward_dedup, "mean": _lib.oracle_backward_dedup_mean}[mode]
+    rc = fn(C.c_int(F), C.c_int64(B), C.c_int(D), _p(grad_out, _f32p), _p(inverse, _i32p), _p(feat_uoff, _i64p),
+            _p(u_values, _i64p), _p(u_offsets, _i64p), _p(touched, _i64p), _p(feat_roff, _i64p), _p(grad_rows, _f64p))
     _check(rc, "backward_dedup")
     R = int(feat_roff[F])
     return touched[:R].copy(), feat_roff, grad_rows[:R].copy()
 
 
-def backward_kjt(F: int, B: int, grad_out: np.ndarray, values, offsets):
+def backward_kjt(F: int, B: int, grad_out: np.ndarray, values, offsets, mode: str = "sum"):
     """Same gradient computed from the KJT alone. Returns (touched_rows, feat_roff, grad_rows)."""
     grad_out = np.ascontiguousarray(grad_out, dtype=np.float32)
     D = grad_out.shape[-1]
@@ -280,9 +280,9 @@ def backward_kjt(F: int, B: int, grad_out: np.ndarray, values, offsets):
     touched = np.zeros(max(N, 1), dtype=np.int64)
     feat_roff = np.zeros(F + 1, dtype=np.int64)
     grad_rows = np.zeros((max(N, 1), D), dtype=np.float64)
-    rc = _lib.oracle_backward_kjt(C.c_int(F), C.c_int64(B), C.c_int(D), _p(grad_out, _f32p),
-                                  _p(values, _i64p), _p(offsets, _i64p), _p(touched, _i64p),
-                                  _p(feat_roff, _i64p), _p(grad_rows, _f64p))
+    fn = {"sum": _lib.oracle_backward_kjt, "mean": _lib.oracle_backward_kjt_mean}[mode]
+    rc = fn(C.c_int(F), C.c_int64(B), C.c_int(D), _p(grad_out, _f32p), _p(values, _i64p), _p(offsets, _i64p),
+            _p(touched, _i64p), _p(feat_roff, _i64p), _p(grad_rows, _f64p))
     _check(rc, "backward_kjt")
     R = int(feat_roff[F])
     return touched[:R].copy(), feat_roff, grad_rows[:R].copy()

@@ -639,6 +639,46 @@ def test_sequence_backward_hand_case():
     assert gr[:, 0].tolist() == [101.0, 11010.0]   # id 1: positions 0, 2; id 2: positions 1, 3, 4
 
 
+@pytest.mark.parametrize("seed", range(3))
+def test_mean_backward_matches_autograd_and_kjt_form(seed):
+    """Average pooling (Sec. 2.2): the gradient of the IKJT path against the KJT form and against
+    autograd through embedding_bag(mean) in fp64; lists include empty ones and repeated ids."""
+    F, B, rows, D = 2, 29, 9, 4
+    batch, tabs = _rand_problem(260 + seed, F=F, B=B, rows=rows, D=D, max_len=5, alphabet=rows)
+    assert (np.diff(batch.offsets) == 0).any()
+    gout = np.random.default_rng(seed).standard_normal((F, B, D)).astype(np.float32)
+    uv, uo, inv, fu = orc.build_ikjt(F, B, batch.values, batch.offsets)
+    tr, fr, gr = orc.backward_dedup(F, B, gout, inv, fu, uv, uo, mode="mean")
+    tr2, fr2, gr2 = orc.backward_kjt(F, B, gout, batch.values, batch.offsets, mode="mean")
+    assert np.array_equal(tr, tr2) and np.array_equal(fr, fr2)
+    np.testing.assert_allclose(gr, gr2, rtol=1e-12, atol=1e-14)
+    trs, _, grs = orc.backward_dedup(F, B, gout, inv, fu, uv, uo)
+    assert np.array_equal(tr, trs) and not np.allclose(gr, grs)  # differs from the sum form
+    G = _dense_grad(F, rows, D, tr, fr, gr)
+    for f in range(F):
+        W = torch.from_numpy(tabs[f]).double().requires_grad_(True)
+        lo, hi = batch.offsets[f * B], batch.offsets[(f + 1) * B]
+        out = torch.nn.functional.embedding_bag(
+            torch.from_numpy(batch.values[lo:hi]), W,
+            torch.from_numpy(batch.offsets[f * B:(f + 1) * B] - lo), mode="mean")
+        (out * torch.from_numpy(gout[f]).double()).sum().backward()
+        np.testing.assert_allclose(G[f], W.grad.numpy(), rtol=1e-12, atol=1e-13)
+
+
+def test_mean_backward_closed_form():
+    # rows [0,1],[0,1],[4],[],[1,1,2]: lists of length 2 (twice), 1, 0, 3
+    batch = synth.batch_from_lists([[[0, 1], [0, 1], [4], [], [1, 1, 2]]])
+    g = np.arange(5 * 2, dtype=np.float32).reshape(1, 5, 2) + 1
+    uv, uo, inv, fu = orc.build_ikjt(1, 5, batch.values, batch.offsets)
+    tr, fr, gr = orc.backward_dedup(1, 5, g, inv, fu, uv, uo, mode="mean")
+    assert tr.tolist() == [0, 1, 2, 4]
+    g = g[0].astype(np.float64)
+    np.testing.assert_allclose(gr[0], (g[0] + g[1]) / 2)
+    np.testing.assert_allclose(gr[1], (g[0] + g[1]) / 2 + 2 * g[4] / 3)
+    np.testing.assert_allclose(gr[2], g[4] / 3)
+    np.testing.assert_allclose(gr[3], g[2])
+
+
 def test_backward_finite_difference():
     F, B, rows, D = 1, 6, 5, 3
     batch = synth.batch_from_lists([[[0, 1], [0, 1], [4], [], [1, 1, 2], [0, 1]]])
