@@ -15,7 +15,7 @@
  *   9. grouped builder    10. element-wise sum over a group's features on the unique rows
  * other pooling functions (11), and partial IKJTs whose lists share storage when one continues
  * another (Sec. 7): 12. partial builder   13. pooled lookup on the windows
- *   14. backward of the sequence path
+ *   14. backward of the sequence path   15. backward of the averaged pooled lookup
  *
  * General rules
  *   - Every array argument marked "device" is a pointer into GPU memory owned by the caller and
@@ -333,6 +333,21 @@ recd_status recd_backward_sequence_dedup(recd_ctx *ctx, int F, int64_t B, int64_
                                          float *grad_rows, void *const *tables,
                                          float *const *adagrad_state, float lr, float eps,
                                          int64_t *host_R);
+
+/* 15. Call 5 for a pooled lookup made with another pooling function (Sec. 2.2 names sum, average
+ *    and max).  RECD_POOL_SUM is exactly call 5.  RECD_POOL_MEAN: the backward of the averaged
+ *    lookup of call 11: every position of unique list u receives g_u[u,:] / len(u), i.e.
+ *      G_f[r,:] = sum over positions j (ascending) with u_values[j] = r of g_u[list of j, :] / len
+ *    (g_u is divided once, in fp32, when it is formed).  RECD_POOL_MAX needs the forward's
+ *    arg-max and is not built: RECD_EINVAL.  All arguments as in call 5. */
+recd_status recd_backward_dedup_mode(recd_ctx *ctx, recd_pooling mode, int F, int64_t B, int D,
+                                     const float *grad_out, const int32_t *inverse,
+                                     const int64_t *feat_uoff, const int64_t *u_values,
+                                     const int64_t *u_offsets, const int64_t *rows, int64_t U_cap,
+                                     int64_t M_cap, int64_t *touched_rows, int64_t *feat_roff,
+                                     float *grad_rows, void *const *tables,
+                                     float *const *adagrad_state, float lr, float eps,
+                                     int64_t *host_R);
 
 #ifdef __cplusplus
 }

@@ -853,7 +853,7 @@ template <typename KeyT>
 recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, const KeyT *ks,
                             const uint32_t *ps, int64_t n_cap, int64_t seg_bound, int row_bits, int F,
                             const void *table, int D, void *out, int64_t *touched_rows,
-                            int64_t *feat_roff, const OptAdagrad *opt)
+                            int64_t *feat_roff, const OptAdagrad *opt, const int64_t *div_off = nullptr)
 {
     hipStream_t st = ctx->stream;
     RECD_TRY(number_segments<KeyT>(ctx, w, set, ks, n_cap, row_bits, F, touched_rows, feat_roff));
@@ -871,6 +871,7 @@ recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, c
     a.lists_bound = seg_bound;
     a.flat = 1;
     a.out = out;
+    a.div_off = div_off;
     if (row_bits >= 0) {
         // short segments: one lane group per segment; long ones are recorded and summed by the
         // block-cooperative kernel right after
@@ -960,7 +961,9 @@ size_t recd_backward_workspace(int F, int64_t B, int64_t M_cap, int D)
 
 // Backward of the pooled path (seq = false: grad_out is [F,B,D]) and of the sequence path (seq =
 // true: grad_out is [N,D], one row per KJT position; kjt_offsets, N and grad_emb are used).
-static recd_status backward_common(recd_ctx *ctx, bool seq, int F, int64_t B, int64_t N, int D,
+// mean: the pooled path averaged, so g_u[u] is divided by the length of unique list u (every
+// segment of step A is one unique list, in order: each has at least one row).
+static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, int64_t B, int64_t N, int D,
                                    const float *grad_out, const int64_t *kjt_offsets,
                                    const int32_t *inverse, const int64_t *feat_uoff,
                                    const int64_t *u_values, const int64_t *u_offsets,
@@ -1077,7 +1080,7 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, int F, int64_t B, in
                                             w.a.hist, w.a.bsum, &ks, &ps));
         if (!seq) {
             RECD_TRY(segment_and_sum<uint32_t>(ctx, w, w.a, ks, ps, n_lists, U_cap, -1, F, grad_out, D, w.g_u,
-                                               nullptr, nullptr, nullptr));
+                                               nullptr, nullptr, nullptr, mean ? u_offsets : nullptr));
         } else {
             RECD_TRY(number_segments<uint32_t>(ctx, w, w.a, ks, n_lists, -1, F, nullptr, nullptr));
             // lists per block: about 128 positions
@@ -1154,9 +1157,28 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
                                            float *const *adagrad_state, float lr, float eps,
                                            int64_t *host_R)
 {
-    return backward_common(ctx, false, F, B, 0, D, grad_out, nullptr, inverse, feat_uoff, u_values,
+    return backward_common(ctx, false, false, F, B, 0, D, grad_out, nullptr, inverse, feat_uoff, u_values,
                            u_offsets, rows, U_cap, M_cap, nullptr, touched_rows, feat_roff, grad_rows, tables,
                            adagrad_state, lr, eps, host_R);
+}
+
+extern "C" recd_status recd_backward_dedup_mode(recd_ctx *ctx, recd_pooling mode, int F, int64_t B, int D,
+                                                const float *grad_out, const int32_t *inverse,
+                                                const int64_t *feat_uoff, const int64_t *u_values,
+                                                const int64_t *u_offsets, const int64_t *rows,
+                                                int64_t U_cap, int64_t M_cap, int64_t *touched_rows,
+                                                int64_t *feat_roff, float *grad_rows, void *const *tables,
+                                                float *const *adagrad_state, float lr, float eps,
+                                                int64_t *host_R)
+{
+    if (!ctx)
+        return RECD_EINVAL;
+    if (mode != RECD_POOL_SUM && mode != RECD_POOL_MEAN)
+        return recd_fail(ctx, RECD_EINVAL,
+                         "backward: pooling mode %d is not supported (sum and mean are)", (int)mode);
+    return backward_common(ctx, false, mode == RECD_POOL_MEAN, F, B, 0, D, grad_out, nullptr, inverse,
+                           feat_uoff, u_values, u_offsets, rows, U_cap, M_cap, nullptr, touched_rows,
+                           feat_roff, grad_rows, tables, adagrad_state, lr, eps, host_R);
 }
 
 extern "C" recd_status recd_backward_sequence_dedup(recd_ctx *ctx, int F, int64_t B, int64_t N, int D,
@@ -1169,7 +1191,7 @@ extern "C" recd_status recd_backward_sequence_dedup(recd_ctx *ctx, int F, int64_
                                                     void *const *tables, float *const *adagrad_state,
                                                     float lr, float eps, int64_t *host_R)
 {
-    return backward_common(ctx, true, F, B, N, D, grad_out, offsets, inverse, feat_uoff, u_values, u_offsets,
+    return backward_common(ctx, true, false, F, B, N, D, grad_out, offsets, inverse, feat_uoff, u_values, u_offsets,
                            rows, U_cap, M_cap, grad_emb, touched_rows, feat_roff, grad_rows, tables,
                            adagrad_state, lr, eps, host_R);
 }

@@ -152,6 +152,9 @@ struct SegSumParams {
     const int64_t *count_dev;
     // optional: list l spans offsets[l] .. offsets[l] + lens[l] (windows of a partial IKJT)
     const int64_t *lens;
+    // optional (SITE_GRAD_LISTS only): the finished row of list l is divided by
+    // div_off[l+1] - div_off[l] when that is positive (backward of average pooling)
+    const int64_t *div_off;
 };
 
 // Adds the rows of NL chunks (chunk j: ns[j] <= 64 ids starting at values[starts[j]], rows of the
@@ -292,6 +295,14 @@ void k_segsum(const SegSumParams p)
 #pragma unroll
             for (int i = 0; i < NACC; i++)
                 vals[i] = len == 0 ? 0.f : (MODE == POOL_MEAN ? vals[i] / (float)len : vals[i]);
+        }
+        if (SITE == SITE_GRAD_LISTS && p.div_off) {
+            const int64_t n = p.div_off[s_list[j] + 1] - p.div_off[s_list[j]];
+            if (n > 0) {
+#pragma unroll
+                for (int i = 0; i < NACC; i++)
+                    vals[i] = vals[i] / (float)n;
+            }
         }
         if (g == 0 && piece_ok) {
             char *dst = static_cast<char *>(p.out) + s_list[j] * out_row_bytes;
@@ -593,6 +604,7 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     p.ends = a.ends;
     p.count_dev = a.count_dev;
     p.lens = a.lens;
+    p.div_off = a.div_off;
     p.F = a.F;
     p.D = a.D;
     const int epv = a.table_dt == RECD_F32 ? 4 : 8;

@@ -36,6 +36,7 @@ EXPORTED = [
     "recd_jagged_expand_inverse", "recd_kjt_sequence_lookup", "recd_build_ikjt_grouped",
     "recd_group_sum_unique", "recd_pooled_lookup_unique_mode", "recd_kjt_pooled_lookup_mode",
     "recd_build_partial_ikjt", "recd_pooled_lookup_partial", "recd_backward_sequence_dedup",
+    "recd_backward_dedup_mode",
 ]
 
 _vp = C.c_void_p
@@ -56,6 +57,7 @@ _lib.recd_kjt_pooled_lookup.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, C.c_in
 _lib.recd_backward_dedup.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, _vp, _vp, _vp, _vp, _vp, _vp,
                                      C.c_int64, C.c_int64, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float,
                                      _vp]
+_lib.recd_backward_dedup_mode.argtypes = [_vp, C.c_int] + _lib.recd_backward_dedup.argtypes[1:]
 _lib.recd_sequence_lookup_unique.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, _vp,
                                              _vp, C.c_int64, C.c_int64, _vp]
 _lib.recd_jagged_expand_inverse.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, _vp,
@@ -186,16 +188,19 @@ class Context:
     def backward_dedup(self, F: int, B: int, grad_out, inverse, feat_uoff, u_values, u_offsets,
                        rows: Sequence[int], U_cap: int, M_cap: int, touched_rows, feat_roff, grad_rows,
                        tables=None, adagrad_state=None, lr: float = 0.0, eps: float = 0.0,
-                       want_count: bool = False):
+                       want_count: bool = False, mode: str = "sum"):
         D = grad_out.shape[-1]
         rows_arr = (C.c_int64 * len(rows))(*rows)
         tabs = self._table_array(tables) if tables is not None else None
         state = self._table_array(adagrad_state) if adagrad_state is not None else None
         host = (C.c_int64 * 1)(0) if want_count else None
-        self._check(_lib.recd_backward_dedup(
-            self._h, F, B, D, _ptr(grad_out), _ptr(inverse), _ptr(feat_uoff), _ptr(u_values),
-            _ptr(u_offsets), rows_arr, U_cap, M_cap, _ptr(touched_rows), _ptr(feat_roff), _ptr(grad_rows),
-            tabs, state, lr, eps, host))
+        args = (F, B, D, _ptr(grad_out), _ptr(inverse), _ptr(feat_uoff), _ptr(u_values),
+                _ptr(u_offsets), rows_arr, U_cap, M_cap, _ptr(touched_rows), _ptr(feat_roff), _ptr(grad_rows),
+                tabs, state, lr, eps, host)
+        if mode == "sum":
+            self._check(_lib.recd_backward_dedup(self._h, *args))
+        else:
+            self._check(_lib.recd_backward_dedup_mode(self._h, POOLING[mode], *args))
         return int(host[0]) if want_count else None
 
     # -- sequence (unpooled) features ---------------------------------------------------------

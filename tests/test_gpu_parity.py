@@ -315,7 +315,7 @@ def test_validation_reports_bad_inputs(ctx, recd):
 
 
 # ------------------------------------------------------------------ backward
-def _backward_case(ctx, w, batch_index, with_adagrad=True):
+def _backward_case(ctx, w, batch_index, with_adagrad=True, mode="sum"):
     batch = synth.make_batch(w, batch_index)
     F, B, D = w.F, w.B, w.D
     gout = synth.make_grad_out(w, batch_index)
@@ -336,8 +336,8 @@ def _backward_case(ctx, w, batch_index, with_adagrad=True):
                            [w.rows] * F, ik.U, ik.M, touched, feat_roff, grad_rows,
                            tables=d_tabs if with_adagrad else None,
                            adagrad_state=d_state if with_adagrad else None, lr=lr, eps=eps,
-                           want_count=True)
-    tr, fr, gr = orc.backward_dedup(F, B, gout, inv, fu, uv, uo)
+                           want_count=True, mode=mode)
+    tr, fr, gr = orc.backward_kjt(F, B, gout, batch.values, batch.offsets, mode=mode)
     assert R == len(tr)
     assert np.array_equal(touched[:R].cpu().numpy(), tr)
     assert np.array_equal(feat_roff.cpu().numpy(), fr)
@@ -426,6 +426,26 @@ def test_backward_fused_update_without_stored_gradient(ctx):
     for a, b in zip(results[0][0] + results[0][1], results[1][0] + results[1][1]):
         assert torch.equal(a, b)
     assert torch.equal(results[0][2], results[1][2])
+
+
+@pytest.mark.parametrize("name,kw", [("cfg1", dict(F=3, B=357, rows=900, D=32)),
+                                     ("cfg2", dict(F=4, B=1024, rows=20_000, D=64, len_max=150)),
+                                     ("cfg5", dict(F=3, B=2048, rows=30_000, D=128))])
+def test_backward_mean_pooling(ctx, name, kw):
+    """Average pooling: the row gradients and the fused update against the oracle's KJT form."""
+    _backward_case(ctx, synth.scaled(synth.WORKLOADS[name], **kw), 0, mode="mean")
+
+
+def test_backward_mode_errors(ctx, recd):
+    batch = synth.batch_from_lists([[[1], [2]]])
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    feat_roff = torch.zeros(2, dtype=torch.int64, device="cuda")
+    touched = torch.zeros(2, dtype=torch.int64, device="cuda")
+    grad_rows = torch.zeros(2, 8, device="cuda")
+    with pytest.raises(recd.RecdError) as e:
+        ctx.backward_dedup(1, 2, torch.zeros(1, 2, 8, device="cuda"), ik.inverse, ik.feat_uoff, ik.u_values,
+                           ik.u_offsets, [5], ik.U, ik.M, touched, feat_roff, grad_rows, mode="max")
+    assert e.value.status == recd.RECD_EINVAL
 
 
 def test_backward_no_ids(ctx):

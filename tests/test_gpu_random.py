@@ -127,11 +127,12 @@ def test_random_configuration(ctx, recd, seed):
         touched = torch.full((max(ik.M, 1),), -1, dtype=torch.int64, device="cuda")
         feat_roff = torch.zeros(F + 1, dtype=torch.int64, device="cuda")
         grad_rows = torch.zeros(max(ik.M, 1), D, device="cuda")
+        bmode = "mean" if rng.random() < 0.5 else "sum"
         R = ctx.backward_dedup(F, B, gu.to_dev(gout), ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets,
-                               [rows] * F, ik.U, ik.M, touched, feat_roff, grad_rows, want_count=True)
-        tr, fr, gr = orc.backward_kjt(F, B, gout, batch.values, batch.offsets)
+                               [rows] * F, ik.U, ik.M, touched, feat_roff, grad_rows, want_count=True, mode=bmode)
+        tr, fr, gr = orc.backward_kjt(F, B, gout, batch.values, batch.offsets, mode=bmode)
         assert R == len(tr) and np.array_equal(touched[:R].cpu().numpy(), tr)
-        gu.assert_close_f32(gu.out_to_f64(grad_rows[:R]), gr, "row gradients")
+        gu.assert_close_f32(gu.out_to_f64(grad_rows[:R]), gr, f"row gradients ({bmode})")
         sg = (rng.standard_normal((max(N, 1), D), dtype=np.float32) * np.float32(0.01))[:N]
         grad_emb = torch.zeros(max(ik.M, 1), D, device="cuda")
         d_sg = gu.to_dev(sg) if N else torch.zeros(1, D, device="cuda")[:0]
