@@ -338,6 +338,69 @@ int oracle_pooled_lookup_mode(int mode, int F, int D, int dtype, const void *con
     return 0;
 }
 
+/* ---- per-id weights (this build's reading; the paper's KJT carries ids only, Sec. 4.2) --------
+ * A weighted KJT holds one fp32 weight per id, weights[j] beside values[j]; the pooled output of a
+ * list is sum_j weights[j] * W_f[values[j],:].  Two rows are duplicates iff they hold the same ids
+ * AND the same weights, position by position (weights compared as bit patterns, so +0 and -0
+ * differ and a NaN equals itself): only then is the pooled output the same whatever the table
+ * holds.  The IKJT stores u_weights beside u_values.  Slot numbering as oracle_build_ikjt.
+ */
+int oracle_build_ikjt_weighted(int F, int64_t B, const int64_t *values, const float *weights,
+                               const int64_t *offsets, int64_t *u_values, float *u_weights,
+                               int64_t *u_offsets, int32_t *inverse, int64_t *feat_uoff)
+{
+    int64_t U = 0, M = 0;
+    u_offsets[0] = 0;
+    for (int f = 0; f < F; f++) {
+        int64_t first_slot = U;
+        feat_uoff[f] = U;
+        for (int64_t b = 0; b < B; b++) {
+            int64_t at = offsets[(int64_t)f * B + b];
+            int64_t len = offsets[(int64_t)f * B + b + 1] - at;
+            int64_t found = -1;
+            for (int64_t s = first_slot; s < U && found < 0; s++) {
+                if (u_offsets[s + 1] - u_offsets[s] != len)
+                    continue;
+                if (memcmp(u_values + u_offsets[s], values + at, sizeof(int64_t) * len) == 0 &&
+                    memcmp(u_weights + u_offsets[s], weights + at, sizeof(float) * len) == 0)
+                    found = s;
+            }
+            if (found < 0) {
+                memcpy(u_values + M, values + at, sizeof(int64_t) * len);
+                memcpy(u_weights + M, weights + at, sizeof(float) * len);
+                M += len;
+                found = U++;
+                u_offsets[U] = M;
+            }
+            inverse[(int64_t)f * B + b] = (int32_t)(found - first_slot);
+        }
+    }
+    feat_uoff[F] = U;
+    return 0;
+}
+
+/* out[l,:] = sum over the ids j of list l, in list order, of weights[j] * W_f[values[j],:], in
+ * double.  Lists addressed as in oracle_pooled_lookup. */
+int oracle_pooled_lookup_weighted(int F, int D, int dtype, const void *const *tables,
+                                  const int64_t *rows, const int64_t *values, const float *weights,
+                                  const int64_t *offsets, const int64_t *list_off, double *out)
+{
+    for (int f = 0; f < F; f++)
+        for (int64_t l = list_off[f]; l < list_off[f + 1]; l++) {
+            double *o = out + l * D;
+            for (int d = 0; d < D; d++)
+                o[d] = 0.0;
+            for (int64_t j = offsets[l]; j < offsets[l + 1]; j++) {
+                int64_t id = values[j];
+                if (id < 0 || id >= rows[f])
+                    return -4;
+                for (int d = 0; d < D; d++)
+                    o[d] += (double)weights[j] * elem(tables[f], dtype, id * D + d);
+            }
+        }
+    return 0;
+}
+
 /* ---- a compute module on a grouped IKJT (Sec. 5 "Deduplicated Pooling": the element-wise sum
  * over the features of a group, computed once per unique row) ----------------------------------
  * combined[group_uoff[g] + k, :] = sum over the features f of group g, in feature order, of
@@ -598,6 +661,77 @@ int oracle_backward_kjt_mean(int F, int64_t B, int D, const float *grad_out, con
                 int64_t k = find_row(touched_rows + R, r_f, values[j]);
                 for (int d = 0; d < D; d++)
                     G[k * D + d] += (double)grad_out[l * D + d] / len;
+            }
+        }
+        R += r_f;
+    }
+    feat_roff[F] = R;
+    return 0;
+}
+
+/* ---- backward of expand + WEIGHTED pooled lookup: position j of unique list u hands
+ * u_weights[j] * g_u[u,:] to table row u_values[j]
+ * step 1  as oracle_backward_dedup
+ * step 2  G_f[r,:] = sum over positions j ascending with u_values[j] == r of
+ *                    u_weights[j] * g_u[list containing j, :]
+ */
+int oracle_backward_dedup_weighted(int F, int64_t B, int D, const float *grad_out,
+                                   const int32_t *inverse, const int64_t *feat_uoff,
+                                   const int64_t *u_values, const float *u_weights,
+                                   const int64_t *u_offsets, int64_t *touched_rows,
+                                   int64_t *feat_roff, double *grad_rows)
+{
+    int64_t U = feat_uoff[F];
+    double *g_u = (double *)calloc((size_t)(U > 0 ? U : 1) * D, sizeof(double));
+    if (!g_u)
+        return -9;
+    for (int f = 0; f < F; f++)
+        for (int64_t b = 0; b < B; b++) {
+            int64_t u = feat_uoff[f] + inverse[(int64_t)f * B + b];
+            for (int d = 0; d < D; d++)
+                g_u[u * D + d] += (double)grad_out[((int64_t)f * B + b) * D + d];
+        }
+    int64_t R = 0;
+    for (int f = 0; f < F; f++) {
+        feat_roff[f] = R;
+        int64_t j0 = u_offsets[feat_uoff[f]], j1 = u_offsets[feat_uoff[f + 1]];
+        int64_t r_f = sorted_distinct(u_values + j0, j1 - j0, touched_rows + R);
+        double *G = grad_rows + R * D;
+        for (int64_t i = 0; i < r_f * D; i++)
+            G[i] = 0.0;
+        for (int64_t u = feat_uoff[f]; u < feat_uoff[f + 1]; u++)
+            for (int64_t j = u_offsets[u]; j < u_offsets[u + 1]; j++) {
+                int64_t k = find_row(touched_rows + R, r_f, u_values[j]);
+                for (int d = 0; d < D; d++)
+                    G[k * D + d] += (double)u_weights[j] * g_u[u * D + d];
+            }
+        R += r_f;
+    }
+    feat_roff[F] = R;
+    free(g_u);
+    return 0;
+}
+
+/* the same gradient straight from the weighted KJT */
+int oracle_backward_kjt_weighted(int F, int64_t B, int D, const float *grad_out,
+                                 const int64_t *values, const float *weights,
+                                 const int64_t *offsets, int64_t *touched_rows, int64_t *feat_roff,
+                                 double *grad_rows)
+{
+    int64_t R = 0;
+    for (int f = 0; f < F; f++) {
+        feat_roff[f] = R;
+        int64_t j0 = offsets[(int64_t)f * B], j1 = offsets[(int64_t)(f + 1) * B];
+        int64_t r_f = sorted_distinct(values + j0, j1 - j0, touched_rows + R);
+        double *G = grad_rows + R * D;
+        for (int64_t i = 0; i < r_f * D; i++)
+            G[i] = 0.0;
+        for (int64_t b = 0; b < B; b++) {
+            int64_t l = (int64_t)f * B + b;
+            for (int64_t j = offsets[l]; j < offsets[l + 1]; j++) {
+                int64_t k = find_row(touched_rows + R, r_f, values[j]);
+                for (int d = 0; d < D; d++)
+                    G[k * D + d] += (double)weights[j] * (double)grad_out[l * D + d];
             }
         }
         R += r_f;

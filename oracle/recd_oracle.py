@@ -326,6 +326,86 @@ def backward_sequence_kjt(F: int, B: int, grad_out: np.ndarray, values, offsets)
     return touched[:R].copy(), feat_roff, grad_rows[:R].copy()
 
 
+# ---- per-id weights (this build's reading: a weighted KJT holds one fp32 weight beside every id) ----
+def _f32(a) -> np.ndarray:
+    return np.ascontiguousarray(a, dtype=np.float32)
+
+
+def build_ikjt_weighted(F: int, B: int, values, weights, offsets):
+    """Weighted KJT -> IKJT: rows are duplicates iff ids and weight bit patterns agree position by
+    position.  Returns (u_values[M], u_weights[M] float32, u_offsets[U+1], inverse[F*B], feat_uoff[F+1])."""
+    values, offsets, weights = _i64(values), _i64(offsets), _f32(weights)
+    _check(check_kjt(F, B, values, offsets), "build_ikjt_weighted")
+    assert weights.shape == values.shape
+    N, L = values.shape[0], F * B
+    u_values = np.zeros(max(N, 1), dtype=np.int64)
+    u_weights = np.zeros(max(N, 1), dtype=np.float32)
+    u_offsets = np.zeros(L + 1, dtype=np.int64)
+    inverse = np.zeros(max(L, 1), dtype=np.int32)
+    feat_uoff = np.zeros(F + 1, dtype=np.int64)
+    rc = _lib.oracle_build_ikjt_weighted(C.c_int(F), C.c_int64(B), _p(values, _i64p), _p(weights, _f32p),
+                                         _p(offsets, _i64p), _p(u_values, _i64p), _p(u_weights, _f32p),
+                                         _p(u_offsets, _i64p), _p(inverse, _i32p), _p(feat_uoff, _i64p))
+    _check(rc, "build_ikjt_weighted")
+    U = int(feat_uoff[F])
+    M = int(u_offsets[U])
+    return u_values[:M].copy(), u_weights[:M].copy(), u_offsets[:U + 1].copy(), inverse[:L].copy(), feat_uoff
+
+
+def pooled_lookup_weighted(tables: Sequence[np.ndarray], dtype: str, values, weights, offsets, list_off) -> np.ndarray:
+    """out[l] = sum_j weights[j] * W_f[values[j]] over the ids of list l.  Returns float64 [L, D]."""
+    F = len(tables)
+    values, offsets, list_off, weights = _i64(values), _i64(offsets), _i64(list_off), _f32(weights)
+    D = int(tables[0].shape[1]) if F else 1
+    rows = _i64([t.shape[0] for t in tables])
+    L = int(list_off[F]) if F else 0
+    out = np.zeros((max(L, 1), D), dtype=np.float64)
+    ptrs, keep = _table_ptrs(tables, dtype)
+    rc = _lib.oracle_pooled_lookup_weighted(C.c_int(F), C.c_int(D), C.c_int(DTYPES[dtype]), ptrs, _p(rows, _i64p),
+                                            _p(values, _i64p), _p(weights, _f32p), _p(offsets, _i64p),
+                                            _p(list_off, _i64p), _p(out, _f64p))
+    _check(rc, "pooled_lookup_weighted")
+    del keep
+    return out[:L]
+
+
+def backward_dedup_weighted(F: int, B: int, grad_out: np.ndarray, inverse, feat_uoff, u_values, u_weights,
+                            u_offsets):
+    """Backward of expand + weighted pooled lookup.  Returns (touched_rows, feat_roff, grad_rows float64)."""
+    grad_out = _f32(grad_out)
+    D = grad_out.shape[-1]
+    inverse = np.ascontiguousarray(inverse, dtype=np.int32)
+    feat_uoff, u_values, u_offsets, u_weights = _i64(feat_uoff), _i64(u_values), _i64(u_offsets), _f32(u_weights)
+    M = u_values.shape[0]
+    touched = np.zeros(max(M, 1), dtype=np.int64)
+    feat_roff = np.zeros(F + 1, dtype=np.int64)
+    grad_rows = np.zeros((max(M, 1), D), dtype=np.float64)
+    rc = _lib.oracle_backward_dedup_weighted(C.c_int(F), C.c_int64(B), C.c_int(D), _p(grad_out, _f32p),
+                                             _p(inverse, _i32p), _p(feat_uoff, _i64p), _p(u_values, _i64p),
+                                             _p(u_weights, _f32p), _p(u_offsets, _i64p), _p(touched, _i64p),
+                                             _p(feat_roff, _i64p), _p(grad_rows, _f64p))
+    _check(rc, "backward_dedup_weighted")
+    R = int(feat_roff[F])
+    return touched[:R].copy(), feat_roff, grad_rows[:R].copy()
+
+
+def backward_kjt_weighted(F: int, B: int, grad_out: np.ndarray, values, weights, offsets):
+    """The same gradient from the weighted KJT alone."""
+    grad_out = _f32(grad_out)
+    D = grad_out.shape[-1]
+    values, offsets, weights = _i64(values), _i64(offsets), _f32(weights)
+    N = values.shape[0]
+    touched = np.zeros(max(N, 1), dtype=np.int64)
+    feat_roff = np.zeros(F + 1, dtype=np.int64)
+    grad_rows = np.zeros((max(N, 1), D), dtype=np.float64)
+    rc = _lib.oracle_backward_kjt_weighted(C.c_int(F), C.c_int64(B), C.c_int(D), _p(grad_out, _f32p),
+                                           _p(values, _i64p), _p(weights, _f32p), _p(offsets, _i64p),
+                                           _p(touched, _i64p), _p(feat_roff, _i64p), _p(grad_rows, _f64p))
+    _check(rc, "backward_kjt_weighted")
+    R = int(feat_roff[F])
+    return touched[:R].copy(), feat_roff, grad_rows[:R].copy()
+
+
 def rowwise_adagrad(grad_rows, w_rows, m_rows, lr: float, eps: float) -> Tuple[np.ndarray, np.ndarray]:
     """Row-wise Adagrad on the touched rows: returns (w_new[R,D], m_new[R]) in float64."""
     grad_rows = np.ascontiguousarray(grad_rows, dtype=np.float64)

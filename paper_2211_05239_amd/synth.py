@@ -215,6 +215,23 @@ def make_grad_out(w: Workload, batch_index: int = 0, seed: Optional[int] = None)
     return rng.standard_normal((w.F, w.B, w.D), dtype=np.float32) * np.float32(0.01)
 
 
+def make_weights(batch: "Batch", seed: int = 0, perturb: float = 0.0) -> np.ndarray:
+    """Per-id weights, fp32 [N], beside batch.values: one of eight levels 0.25 .. 2.0 chosen by the
+    id, its position in the list and the seed, so rows that hold the same list hold the same weights
+    (the duplication of the batch is kept).  With probability `perturb` a non-empty row gets another
+    level on its first id: such a row differs from its copies in the weights only."""
+    N = batch.values.shape[0]
+    lens = np.diff(batch.offsets)
+    pos = np.arange(N, dtype=np.int64) - np.repeat(batch.offsets[:-1], lens)
+    level = (batch.values * 2654435761 + pos * 40503 + seed) % 8
+    if perturb > 0.0:
+        rng = np.random.default_rng(BASE_SEED + 77 + seed)
+        hit = (rng.random(lens.shape[0]) < perturb) & (lens > 0)
+        first = batch.offsets[:-1][hit]
+        level[first] = (level[first] + 1 + rng.integers(0, 7, size=first.shape[0])) % 8
+    return ((level + 1).astype(np.float32) * np.float32(0.25))
+
+
 def tiny_batch(rng: np.random.Generator, F: int, B: int, alphabet: int, max_len: int) -> Batch:
     """Small-alphabet batch where lists coincide by content often (brute-force test food)."""
     vals, offs, base = [], [np.zeros(1, dtype=np.int64)], 0

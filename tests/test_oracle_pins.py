@@ -755,6 +755,131 @@ def test_dedup_gradient_gives_same_update_as_kjt_gradient():
     np.testing.assert_allclose(a[1], b[1], rtol=1e-12)
 
 
+# ------------------------------------------------------------------ per-id weights
+def _bits32(w):
+    return np.ascontiguousarray(w, dtype=np.float32).view(np.uint32)
+
+
+def _brute_ikjt_weighted(F, B, values, weights, offsets):
+    uv, uw, uo, inv, fu = [], [], [0], [], [0]
+    for f in range(F):
+        seen = {}
+        for b in range(B):
+            lo, hi = offsets[f * B + b], offsets[f * B + b + 1]
+            key = (tuple(values[lo:hi].tolist()), tuple(_bits32(weights[lo:hi]).tolist()))
+            if key not in seen:
+                seen[key] = len(seen)
+                uv += list(key[0])
+                uw += weights[lo:hi].tolist()
+                uo.append(len(uv))
+            inv.append(seen[key])
+        fu.append(fu[-1] + len(seen))
+    return uv, uw, uo, inv, fu
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_weighted_builder_matches_brute_force(seed):
+    F, B = 3, 41
+    batch, _ = _rand_problem(300 + seed, F=F, B=B, max_len=3, alphabet=3)
+    weights = synth.make_weights(batch, seed, perturb=0.3)
+    uv, uw, uo, inv, fu = orc.build_ikjt_weighted(F, B, batch.values, weights, batch.offsets)
+    b_uv, b_uw, b_uo, b_inv, b_fu = _brute_ikjt_weighted(F, B, batch.values, weights, batch.offsets)
+    assert uv.tolist() == b_uv and uo.tolist() == b_uo and inv.tolist() == b_inv and fu.tolist() == b_fu
+    assert np.array_equal(_bits32(uw), _bits32(np.array(b_uw, dtype=np.float32)))
+    # the perturbed rows split slots: more unique lists than the ids alone give, never fewer
+    assert fu[-1] > orc.build_ikjt(F, B, batch.values, batch.offsets)[3][-1]
+    # decoding the weighted IKJT gives the weighted KJT back
+    for f in range(F):
+        for b in range(B):
+            u = fu[f] + inv[f * B + b]
+            lo, hi = batch.offsets[f * B + b], batch.offsets[f * B + b + 1]
+            assert np.array_equal(uv[uo[u]:uo[u + 1]], batch.values[lo:hi])
+            assert np.array_equal(_bits32(uw[uo[u]:uo[u + 1]]), _bits32(weights[lo:hi]))
+
+
+def test_weighted_builder_hand_cases():
+    batch = synth.batch_from_lists([[[1, 2], [1, 2], [1, 2], [], [1, 2], [2, 1]]])
+    w = np.array([.5, .5, .5, .5, .5, 1., .5, .5, .5, .5], dtype=np.float32)
+    uv, uw, uo, inv, fu = orc.build_ikjt_weighted(1, 6, batch.values, w, batch.offsets)
+    assert inv.tolist() == [0, 0, 1, 2, 0, 3] and uo.tolist() == [0, 2, 4, 4, 6]
+    assert uw.tolist() == [.5, .5, .5, 1., .5, .5]
+    # bit patterns: +0 and -0 are different weights, a NaN equals itself
+    batch = synth.batch_from_lists([[[7], [7], [7], [7]]])
+    w = np.array([0.0, -0.0, np.nan, np.nan], dtype=np.float32)
+    _, _, _, inv, _ = orc.build_ikjt_weighted(1, 4, batch.values, w, batch.offsets)
+    assert inv.tolist() == [0, 1, 2, 2]
+    # all weights equal: the unweighted IKJT
+    batch, _ = _rand_problem(5, F=2, B=30, max_len=3, alphabet=3)
+    ones = np.ones(batch.N, dtype=np.float32)
+    uv, uw, uo, inv, fu = orc.build_ikjt_weighted(2, 30, batch.values, ones, batch.offsets)
+    for a, b in zip((uv, uo, inv, fu), orc.build_ikjt(2, 30, batch.values, batch.offsets)):
+        assert np.array_equal(a, b)
+    assert np.all(uw == 1.0)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_weighted_lookup_matches_embedding_bag(dtype):
+    batch, tabs = _rand_problem(11, dtype=dtype)
+    F, B = batch.F, batch.B
+    weights = synth.make_weights(batch, 1, perturb=0.2)
+    lo_kjt = np.arange(F + 1, dtype=np.int64) * B
+    got = orc.pooled_lookup_weighted(tabs, dtype, batch.values, weights, batch.offsets, lo_kjt).reshape(F, B, -1)
+    t64 = _tables_as_f64(tabs, dtype)
+    for f in range(F):
+        lo, hi = batch.offsets[f * B], batch.offsets[(f + 1) * B]
+        ref = torch.nn.functional.embedding_bag(
+            torch.from_numpy(batch.values[lo:hi]), t64[f], torch.from_numpy(batch.offsets[f * B:(f + 1) * B] - lo),
+            mode="sum", per_sample_weights=torch.from_numpy(weights[lo:hi]).double())
+        np.testing.assert_allclose(got[f], ref.numpy(), rtol=1e-13, atol=1e-14)
+    # unit weights: the plain sum, exactly
+    ones = np.ones(batch.N, dtype=np.float32)
+    assert np.array_equal(orc.pooled_lookup_weighted(tabs, dtype, batch.values, ones, batch.offsets, lo_kjt),
+                          orc.pooled_lookup(tabs, dtype, batch.values, batch.offsets, lo_kjt))
+    # the deduplicated path gives the KJT result back
+    uv, uw, uo, inv, fu = orc.build_ikjt_weighted(F, B, batch.values, weights, batch.offsets)
+    out = orc.expand_inverse(F, B, orc.pooled_lookup_weighted(tabs, dtype, uv, uw, uo, fu), fu, inv)
+    assert np.array_equal(out, got)
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_weighted_backward_matches_autograd_and_kjt_form(seed):
+    F, B, rows, D = 2, 31, 9, 4
+    batch, tabs = _rand_problem(320 + seed, F=F, B=B, rows=rows, D=D, max_len=4, alphabet=rows)
+    weights = synth.make_weights(batch, seed, perturb=0.2)
+    gout = np.random.default_rng(seed).standard_normal((F, B, D)).astype(np.float32)
+    uv, uw, uo, inv, fu = orc.build_ikjt_weighted(F, B, batch.values, weights, batch.offsets)
+    tr, fr, gr = orc.backward_dedup_weighted(F, B, gout, inv, fu, uv, uw, uo)
+    tr2, fr2, gr2 = orc.backward_kjt_weighted(F, B, gout, batch.values, weights, batch.offsets)
+    assert np.array_equal(tr, tr2) and np.array_equal(fr, fr2)
+    np.testing.assert_allclose(gr, gr2, rtol=1e-12, atol=1e-14)
+    G = _dense_grad(F, rows, D, tr, fr, gr)
+    for f in range(F):
+        W = torch.from_numpy(tabs[f]).double().requires_grad_(True)
+        lo, hi = batch.offsets[f * B], batch.offsets[(f + 1) * B]
+        out = torch.nn.functional.embedding_bag(
+            torch.from_numpy(batch.values[lo:hi]), W, torch.from_numpy(batch.offsets[f * B:(f + 1) * B] - lo),
+            mode="sum", per_sample_weights=torch.from_numpy(weights[lo:hi]).double())
+        (out * torch.from_numpy(gout[f]).double()).sum().backward()
+        np.testing.assert_allclose(G[f], W.grad.numpy(), rtol=1e-12, atol=1e-13)
+    # unit weights: the unweighted gradient, exactly
+    ones = np.ones(batch.N, dtype=np.float32)
+    a = orc.backward_kjt_weighted(F, B, gout, batch.values, ones, batch.offsets)
+    b = orc.backward_kjt(F, B, gout, batch.values, batch.offsets)
+    assert np.array_equal(a[0], b[0]) and np.array_equal(a[2], b[2])
+
+
+def test_weighted_closed_form():
+    # one table whose row r is r+1 in every element; list [0, 2] with weights [0.5, 2] pools to 6.5
+    tab = (np.arange(4, dtype=np.float32)[:, None] + 1) * np.ones((1, 2), dtype=np.float32)
+    batch = synth.batch_from_lists([[[0, 2], [3]]])
+    w = np.array([0.5, 2.0, 4.0], dtype=np.float32)
+    out = orc.pooled_lookup_weighted([tab], "f32", batch.values, w, batch.offsets, [0, 2])
+    assert out.tolist() == [[6.5, 6.5], [16.0, 16.0]]
+    g = np.array([[[1.0, 2.0], [3.0, 5.0]]], dtype=np.float32)
+    tr, fr, gr = orc.backward_kjt_weighted(1, 2, g, batch.values, w, batch.offsets)
+    assert tr.tolist() == [0, 2, 3] and gr.tolist() == [[0.5, 1.0], [2.0, 4.0], [12.0, 20.0]]
+
+
 # ------------------------------------------------------------------ generator statistics vs the paper's model
 def test_generator_matches_duplication_model():
     w = synth.scaled(synth.WORKLOADS["cfg2"], F=4, rows=1_000_000)
