@@ -16,6 +16,7 @@
  * other pooling functions (11), and partial IKJTs whose lists share storage when one continues
  * another (Sec. 7): 12. partial builder   13. pooled lookup on the windows
  *   14. backward of the sequence path   15. backward of the averaged pooled lookup
+ *   16-19. per-id weights: builder, unique and KJT lookups, backward
  *
  * General rules
  *   - Every array argument marked "device" is a pointer into GPU memory owned by the caller and
@@ -348,6 +349,55 @@ recd_status recd_backward_dedup_mode(recd_ctx *ctx, recd_pooling mode, int F, in
                                      float *grad_rows, void *const *tables,
                                      float *const *adagrad_state, float lr, float eps,
                                      int64_t *host_R);
+
+/* 16-19. Per-id weights (this build's reading; the paper's KJT carries ids only, Sec. 4.2): a
+ *    weighted KJT holds one fp32 weight beside every id, `weights` device fp32 [N] aligned with
+ *    `values`, and the pooled output of a list is the weighted sum
+ *      out = sum over the ids j of the list, in list order, of weights[j] * W_f[values[j], :]
+ *    (fp32, one fused multiply-add per element and id).  Two rows hold the same list only when ids
+ *    AND weights agree position by position; weights are compared as bit patterns (+0 and -0
+ *    differ, a NaN equals itself), which is what makes the pooled outputs equal whatever the table
+ *    holds.
+ *
+ * 16. Call 1 for a weighted KJT.  u_weights: device fp32, capacity N: the weights of the unique
+ *    lists, aligned with u_values.  All else as in call 1 (same slot numbering; with all weights
+ *    equal the result is call 1's).  weights / u_weights may be NULL when N = 0. */
+recd_status recd_build_ikjt_weighted(recd_ctx *ctx, int F, int64_t B, int64_t N,
+                                     const int64_t *values, const float *weights,
+                                     const int64_t *offsets, int64_t *u_values, float *u_weights,
+                                     int64_t *u_offsets, int32_t *inverse, int64_t *feat_uoff,
+                                     int64_t *host_U_M);
+
+/* 17. Call 2 with weights: pooled[u,:] = weighted sum over unique list u.  The order of operations
+ *    depends on the list alone, so call 3 on the result equals call 18 on the KJT bit for bit.
+ *    u_weights may be NULL only when u_values is (no id anywhere). */
+recd_status recd_pooled_lookup_unique_weighted(recd_ctx *ctx, int F, int D, recd_dtype table_dt,
+                                               recd_dtype out_dt, const void *const *tables,
+                                               const int64_t *rows, const int64_t *u_values,
+                                               const float *u_weights, const int64_t *u_offsets,
+                                               const int64_t *feat_uoff, int64_t max_lists,
+                                               void *pooled);
+
+/* 18. Call 4 with weights: the comparison path over every row of the weighted KJT. */
+recd_status recd_kjt_pooled_lookup_weighted(recd_ctx *ctx, int F, int64_t B, int D,
+                                            recd_dtype table_dt, recd_dtype out_dt,
+                                            const void *const *tables, const int64_t *rows,
+                                            const int64_t *values, const float *weights,
+                                            const int64_t *offsets, void *out);
+
+/* 19. Call 5 for the weighted lookup: position j of unique list u hands u_weights[j] * g_u[u,:] to
+ *    table row u_values[j]:
+ *      G_f[r,:] = sum over positions j (ascending) with u_values[j] = r of
+ *                 u_weights[j] * g_u[list of j, :]      (fp32 fused multiply-adds)
+ *    Same machinery and guarantees as call 5; all other arguments as there. */
+recd_status recd_backward_dedup_weighted(recd_ctx *ctx, int F, int64_t B, int D,
+                                         const float *grad_out, const int32_t *inverse,
+                                         const int64_t *feat_uoff, const int64_t *u_values,
+                                         const float *u_weights, const int64_t *u_offsets,
+                                         const int64_t *rows, int64_t U_cap, int64_t M_cap,
+                                         int64_t *touched_rows, int64_t *feat_roff, float *grad_rows,
+                                         void *const *tables, float *const *adagrad_state, float lr,
+                                         float eps, int64_t *host_R);
 
 #ifdef __cplusplus
 }

@@ -251,7 +251,8 @@ __global__ __launch_bounds__(256) void k_keys_ids(const int64_t *__restrict__ u_
                                                   const int64_t *__restrict__ feat_uoff, int F,
                                                   int row_bits, int64_t lists_cap, int64_t M_cap,
                                                   KeyT *__restrict__ keys, uint32_t *__restrict__ pay,
-                                                  int64_t *n_out, int pay_positions)
+                                                  int64_t *n_out, int pay_positions,
+                                                  uint32_t *__restrict__ pos_list = nullptr)
 {
     const int s = threadIdx.x % SG;
     const int64_t u = (int64_t)blockIdx.x * (256 / SG) + threadIdx.x / SG;
@@ -278,6 +279,26 @@ __global__ __launch_bounds__(256) void k_keys_ids(const int64_t *__restrict__ u_
     for (int64_t j = j0 + s; j < j1; j += SG) {
         keys[j] = fkey | (KeyT)u_values[j];
         pay[j] = pay_positions ? (uint32_t)j : (uint32_t)u;  // source row of the later sum: g_emb[j] or g_u[u]
+        if (pos_list)
+            pos_list[j] = (uint32_t)u;
+    }
+}
+
+// Weighted lookup: the sort carried the position j of every entry.  Replace it by the entry's
+// source row (the unique list of j) and fetch the entry's weight, both in sorted order, so that the
+// segment sums read them as streams.
+__global__ __launch_bounds__(256) void k_weight_payload(uint32_t *__restrict__ pay,
+                                                        const uint32_t *__restrict__ pos_list,
+                                                        const float *__restrict__ u_weights,
+                                                        const int64_t *__restrict__ n_dev,
+                                                        float *__restrict__ pay_w)
+{
+    const int64_t n = *n_dev;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const uint32_t j = pay[i];
+        pay_w[i] = u_weights[j];
+        pay[i] = pos_list[j];
     }
 }
 
@@ -459,6 +480,7 @@ __global__ __launch_bounds__(256) void k_adagrad(const float *__restrict__ grad_
 struct RowSumParams {
     const float *table;        // g_u [U, D]
     const uint32_t *pay;       // sorted payload: unique-list index of every position
+    const float *pay_w;        // weighted lookup: the weight of every sorted entry, else nullptr
     const int64_t *seg_start;  // [R+1]
     const int64_t *n_seg;      // device: R
     float *out;                // grad_rows [R, D] or nullptr
@@ -554,7 +576,8 @@ __global__ __launch_bounds__(256) void k_find_long(const RowSumParams p)
 // FINALIZE = false: segments of at most 64 entries are summed here (longer ones are skipped).
 // FINALIZE = true: the "segments" are the cut ones; their entries are the chunk partial sums, in
 // chunk order.
-template <int LPR, bool FINALIZE>
+// WT (with FINALIZE = false): entry j contributes pay_w[j] times its source row.
+template <int LPR, bool FINALIZE, bool WT = false>
 __global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const OptAdagrad opt)
 {
     constexpr int G = 64 / LPR, VPL = 4, US = 2;
@@ -607,10 +630,12 @@ __global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const
             acc[w] = make_float4(0.f, 0.f, 0.f, 0.f);
         for (int i = 0; i < n; i += US) {
             int64_t id[US];
+            float wt[US];
 #pragma unroll
             for (int u = 0; u < US; u++) {
                 const int64_t j = start + (i + u < n ? i + u : i);
                 id[u] = FINALIZE ? j : (int64_t)p.pay[j];
+                wt[u] = WT ? p.pay_w[j] : 1.f;
             }
             float4 v[US][VPL];
 #pragma unroll
@@ -625,10 +650,17 @@ __global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const
 #pragma unroll
                     for (int w = 0; w < VPL; w++)
                         if (piece[w]) {
-                            acc[w].x += v[u][w].x;
-                            acc[w].y += v[u][w].y;
-                            acc[w].z += v[u][w].z;
-                            acc[w].w += v[u][w].w;
+                            if (WT) {
+                                acc[w].x = __fmaf_rn(wt[u], v[u][w].x, acc[w].x);
+                                acc[w].y = __fmaf_rn(wt[u], v[u][w].y, acc[w].y);
+                                acc[w].z = __fmaf_rn(wt[u], v[u][w].z, acc[w].z);
+                                acc[w].w = __fmaf_rn(wt[u], v[u][w].w, acc[w].w);
+                            } else {
+                                acc[w].x += v[u][w].x;
+                                acc[w].y += v[u][w].y;
+                                acc[w].z += v[u][w].z;
+                                acc[w].w += v[u][w].w;
+                            }
                         }
         }
         if (mine)
@@ -782,6 +814,8 @@ struct BwdWs {
     int32_t *seg_feat, *lseg_t, *lseg_first, *lseg_n;
     int64_t *long_count, *item_start, *item_end;
     float *g_u, *partials;
+    uint32_t *pos_list;  // weighted lookup: unique list of every position of u_values
+    float *pay_w;        // weighted lookup: weight of every sorted entry of step B
     size_t bytes;
 };
 
@@ -827,6 +861,8 @@ BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D)
     w.item_end = c.take<int64_t>(item_cap);
     w.partials = c.take<float>((size_t)item_cap * D);
     w.g_u = c.take<float>((size_t)u_cap * D);
+    w.pos_list = c.take<uint32_t>(M_cap);
+    w.pay_w = c.take<float>(M_cap);
     w.bytes = c.off;
     return w;
 }
@@ -853,7 +889,8 @@ template <typename KeyT>
 recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, const KeyT *ks,
                             const uint32_t *ps, int64_t n_cap, int64_t seg_bound, int row_bits, int F,
                             const void *table, int D, void *out, int64_t *touched_rows,
-                            int64_t *feat_roff, const OptAdagrad *opt, const int64_t *div_off = nullptr)
+                            int64_t *feat_roff, const OptAdagrad *opt, const int64_t *div_off = nullptr,
+                            const float *pay_w = nullptr)
 {
     hipStream_t st = ctx->stream;
     RECD_TRY(number_segments<KeyT>(ctx, w, set, ks, n_cap, row_bits, F, touched_rows, feat_roff));
@@ -878,6 +915,7 @@ recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, c
         RowSumParams rp;
         rp.table = static_cast<const float *>(table);
         rp.pay = ps;
+        rp.pay_w = pay_w;
         rp.seg_start = w.seg_start;
         rp.n_seg = w.list_off + 1;
         rp.out = static_cast<float *>(out);
@@ -907,15 +945,15 @@ recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, c
         if (nblk < 1)
             nblk = 1;
         const dim3 block(256);
-        auto launch_rows = [&](auto fin, unsigned nb, hipStream_t stream) {
-            constexpr bool FIN = decltype(fin)::value;
+        auto launch_rows = [&](auto fin, auto wt, unsigned nb, hipStream_t stream) {
+            constexpr bool FIN = decltype(fin)::value, WT = decltype(wt)::value;
             const dim3 grid(nb);
             switch (lpr) {
-            case 4: hipLaunchKernelGGL((k_segsum_rows<4, FIN>), grid, block, 0, stream, rp, o); break;
-            case 8: hipLaunchKernelGGL((k_segsum_rows<8, FIN>), grid, block, 0, stream, rp, o); break;
-            case 16: hipLaunchKernelGGL((k_segsum_rows<16, FIN>), grid, block, 0, stream, rp, o); break;
-            case 32: hipLaunchKernelGGL((k_segsum_rows<32, FIN>), grid, block, 0, stream, rp, o); break;
-            default: hipLaunchKernelGGL((k_segsum_rows<64, FIN>), grid, block, 0, stream, rp, o); break;
+            case 4: hipLaunchKernelGGL((k_segsum_rows<4, FIN, WT>), grid, block, 0, stream, rp, o); break;
+            case 8: hipLaunchKernelGGL((k_segsum_rows<8, FIN, WT>), grid, block, 0, stream, rp, o); break;
+            case 16: hipLaunchKernelGGL((k_segsum_rows<16, FIN, WT>), grid, block, 0, stream, rp, o); break;
+            case 32: hipLaunchKernelGGL((k_segsum_rows<32, FIN, WT>), grid, block, 0, stream, rp, o); break;
+            default: hipLaunchKernelGGL((k_segsum_rows<64, FIN, WT>), grid, block, 0, stream, rp, o); break;
             }
         };
         // 1. long segments cut into chunks (a short pass over the segment starts)
@@ -939,12 +977,19 @@ recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, c
         c.lists_bound = n_cap / 256 + n_cap / 65 + 1;
         c.out = w.partials;
         c.stream = side;
+        if (pay_w) {  // the chunk partials carry the weights; adding the partials does not
+            c.mode = 3;
+            c.weights = pay_w;
+        }
         RECD_TRY(recd_launch_segsum(ctx, c));
-        launch_rows(std::true_type(), (unsigned)ctx->num_cu, side);
+        launch_rows(std::true_type(), std::false_type(), (unsigned)ctx->num_cu, side);
         RECD_HIP(ctx, hipGetLastError());
         RECD_HIP(ctx, hipEventRecord(ctx->ev_join, side));
         // 3. short segments summed and updated
-        launch_rows(std::false_type(), (unsigned)nblk, st);
+        if (pay_w)
+            launch_rows(std::false_type(), std::true_type(), (unsigned)nblk, st);
+        else
+            launch_rows(std::false_type(), std::false_type(), (unsigned)nblk, st);
         RECD_HIP(ctx, hipGetLastError());
         RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
         return RECD_OK;
@@ -963,10 +1008,12 @@ size_t recd_backward_workspace(int F, int64_t B, int64_t M_cap, int D)
 // true: grad_out is [N,D], one row per KJT position; kjt_offsets, N and grad_emb are used).
 // mean: the pooled path averaged, so g_u[u] is divided by the length of unique list u (every
 // segment of step A is one unique list, in order: each has at least one row).
+// u_weights: the pooled path's lookup was the weighted sum: position j hands u_weights[j] * g_u on.
 static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, int64_t B, int64_t N, int D,
                                    const float *grad_out, const int64_t *kjt_offsets,
                                    const int32_t *inverse, const int64_t *feat_uoff,
-                                   const int64_t *u_values, const int64_t *u_offsets,
+                                   const int64_t *u_values, const float *u_weights,
+                                   const int64_t *u_offsets,
                                    const int64_t *rows, int64_t U_cap, int64_t M_cap, float *grad_emb,
                                    int64_t *touched_rows, int64_t *feat_roff, float *grad_rows,
                                    void *const *tables, float *const *adagrad_state, float lr,
@@ -1056,17 +1103,26 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
         if (!wide) {
             uint32_t *k0 = static_cast<uint32_t *>(w.b.k0), *k1 = static_cast<uint32_t *>(w.b.k1), *ks;
             hipLaunchKernelGGL((k_keys_ids<uint32_t, SG>), dim3(kb), dim3(256), 0, side, u_values,
-                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev, seq ? 1 : 0);
+                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev,
+                               (seq || u_weights) ? 1 : 0, u_weights ? w.pos_list : nullptr);
             RECD_TRY(radix_sort_pairs<uint32_t>(ctx, side, k0, w.b.p0, k1, w.b.p1, w.b.n_dev, M_cap, bits_b,
                                                 w.b.hist, w.b.bsum, &ks, &ps_b));
             ks_b = ks;
         } else {
             uint64_t *k0 = static_cast<uint64_t *>(w.b.k0), *k1 = static_cast<uint64_t *>(w.b.k1), *ks;
             hipLaunchKernelGGL((k_keys_ids<uint64_t, SG>), dim3(kb), dim3(256), 0, side, u_values,
-                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev, seq ? 1 : 0);
+                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev,
+                               (seq || u_weights) ? 1 : 0, u_weights ? w.pos_list : nullptr);
             RECD_TRY(radix_sort_pairs<uint64_t>(ctx, side, k0, w.b.p0, k1, w.b.p1, w.b.n_dev, M_cap, bits_b,
                                                 w.b.hist, w.b.bsum, &ks, &ps_b));
             ks_b = ks;
+        }
+        if (u_weights) {
+            int64_t wb = (M_cap + 255) / 256;
+            if (wb > (int64_t)ctx->num_cu * 16)
+                wb = (int64_t)ctx->num_cu * 16;
+            hipLaunchKernelGGL(k_weight_payload, dim3((unsigned)(wb < 1 ? 1 : wb)), dim3(256), 0, side, ps_b,
+                               w.pos_list, u_weights, w.b.n_dev, w.pay_w);
         }
         RECD_HIP(ctx, hipGetLastError());
         RECD_HIP(ctx, hipEventRecord(ctx->ev_join, side));
@@ -1116,11 +1172,13 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
     if (!wide)
         RECD_TRY(segment_and_sum<uint32_t>(ctx, w, w.b, static_cast<const uint32_t *>(ks_b), ps_b, M_cap,
                                            M_cap, row_bits, F, b_table, D, grad_rows, touched_rows,
-                                           feat_roff, fused ? &oa : nullptr));
+                                           feat_roff, fused ? &oa : nullptr, nullptr,
+                                           u_weights ? w.pay_w : nullptr));
     else
         RECD_TRY(segment_and_sum<uint64_t>(ctx, w, w.b, static_cast<const uint64_t *>(ks_b), ps_b, M_cap,
                                            M_cap, row_bits, F, b_table, D, grad_rows, touched_rows,
-                                           feat_roff, fused ? &oa : nullptr));
+                                           feat_roff, fused ? &oa : nullptr, nullptr,
+                                           u_weights ? w.pay_w : nullptr));
     // ---- optimizer -------------------------------------------------------------------------------
     if (tables && !fused) {
         for (int f0 = 0; f0 < F; f0 += RECD_F_PER_LAUNCH) {
@@ -1158,7 +1216,7 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
                                            int64_t *host_R)
 {
     return backward_common(ctx, false, false, F, B, 0, D, grad_out, nullptr, inverse, feat_uoff, u_values,
-                           u_offsets, rows, U_cap, M_cap, nullptr, touched_rows, feat_roff, grad_rows, tables,
+                           nullptr, u_offsets, rows, U_cap, M_cap, nullptr, touched_rows, feat_roff, grad_rows, tables,
                            adagrad_state, lr, eps, host_R);
 }
 
@@ -1177,7 +1235,7 @@ extern "C" recd_status recd_backward_dedup_mode(recd_ctx *ctx, recd_pooling mode
         return recd_fail(ctx, RECD_EINVAL,
                          "backward: pooling mode %d is not supported (sum and mean are)", (int)mode);
     return backward_common(ctx, false, mode == RECD_POOL_MEAN, F, B, 0, D, grad_out, nullptr, inverse,
-                           feat_uoff, u_values, u_offsets, rows, U_cap, M_cap, nullptr, touched_rows,
+                           feat_uoff, u_values, nullptr, u_offsets, rows, U_cap, M_cap, nullptr, touched_rows,
                            feat_roff, grad_rows, tables, adagrad_state, lr, eps, host_R);
 }
 
@@ -1191,9 +1249,28 @@ extern "C" recd_status recd_backward_sequence_dedup(recd_ctx *ctx, int F, int64_
                                                     void *const *tables, float *const *adagrad_state,
                                                     float lr, float eps, int64_t *host_R)
 {
-    return backward_common(ctx, true, false, F, B, N, D, grad_out, offsets, inverse, feat_uoff, u_values, u_offsets,
-                           rows, U_cap, M_cap, grad_emb, touched_rows, feat_roff, grad_rows, tables,
+    return backward_common(ctx, true, false, F, B, N, D, grad_out, offsets, inverse, feat_uoff, u_values, nullptr,
+                           u_offsets, rows, U_cap, M_cap, grad_emb, touched_rows, feat_roff, grad_rows, tables,
                            adagrad_state, lr, eps, host_R);
+}
+
+extern "C" recd_status recd_backward_dedup_weighted(recd_ctx *ctx, int F, int64_t B, int D,
+                                                    const float *grad_out, const int32_t *inverse,
+                                                    const int64_t *feat_uoff, const int64_t *u_values,
+                                                    const float *u_weights, const int64_t *u_offsets,
+                                                    const int64_t *rows, int64_t U_cap, int64_t M_cap,
+                                                    int64_t *touched_rows, int64_t *feat_roff,
+                                                    float *grad_rows, void *const *tables,
+                                                    float *const *adagrad_state, float lr, float eps,
+                                                    int64_t *host_R)
+{
+    if (!ctx)
+        return RECD_EINVAL;
+    if (M_cap > 0 && !u_weights)
+        return recd_fail(ctx, RECD_EINVAL, "null u_weights");
+    return backward_common(ctx, false, false, F, B, 0, D, grad_out, nullptr, inverse, feat_uoff, u_values,
+                           M_cap > 0 ? u_weights : nullptr, u_offsets, rows, U_cap, M_cap, nullptr,
+                           touched_rows, feat_roff, grad_rows, tables, adagrad_state, lr, eps, host_R);
 }
 
 size_t recd_build_workspace(int F, int64_t B);

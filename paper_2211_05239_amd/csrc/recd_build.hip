@@ -48,8 +48,18 @@ __global__ void k_fill_u64(uint64_t *p, int64_t n, uint64_t v)
 constexpr int kLPG = 1;
 constexpr int kHU = 4;   // strides of the long-list loop whose loads are issued together
 
-template <int SG>
+// An id and (WT) the bit pattern of its weight as one hash input.
+template <bool WT>
+__device__ __forceinline__ uint64_t hash_item(int64_t id, uint32_t wbits)
+{
+    return WT ? (uint64_t)id + (uint64_t)wbits * 0xc2b2ae3d27d4eb4full : (uint64_t)id;
+}
+
+// WT: the lists carry one weight per id (wbits: their bit patterns); two lists are the same only if
+// the weights agree too, so they enter the hash and every comparison.
+template <int SG, bool WT>
 __global__ __launch_bounds__(256) void k_hash_insert(const int64_t *__restrict__ values,
+                                                     const uint32_t *__restrict__ wbits,
                                                      const int64_t *__restrict__ offsets, int64_t B,
                                                      int64_t n_lists, uint64_t *table,
                                                      uint32_t cap_mask, int32_t *__restrict__ slot_of,
@@ -85,32 +95,38 @@ __global__ __launch_bounds__(256) void k_hash_insert(const int64_t *__restrict__
     }
     // first SG ids of every list and of its predecessor: all loads in flight together
     int64_t v[kLPG], pv[kLPG];
+    uint32_t wv[kLPG], pwv[kLPG];
 #pragma unroll
     for (int k = 0; k < kLPG; k++) {
         v[k] = s < len[k] ? values[start[k] + s] : 0;
         pv[k] = (follows[k] && s < len[k]) ? values[pstart[k] + s] : 0;
+        wv[k] = (WT && s < len[k]) ? wbits[start[k] + s] : 0u;
+        pwv[k] = (WT && follows[k] && s < len[k]) ? wbits[pstart[k] + s] : 0u;
     }
 #pragma unroll
     for (int k = 0; k < kLPG; k++) {
         if (s < len[k]) {
-            follows[k] &= pv[k] == v[k];
-            h[k] = mix64((uint64_t)v[k] + (uint64_t)(s + 1) * 0x9e3779b97f4a7c15ull);
+            follows[k] &= pv[k] == v[k] && pwv[k] == wv[k];
+            h[k] = mix64(hash_item<WT>(v[k], wv[k]) + (uint64_t)(s + 1) * 0x9e3779b97f4a7c15ull);
         }
         // lists longer than the group: kHU strides per trip, all loads issued before use
         for (int64_t t0 = s + SG; t0 < len[k]; t0 += kHU * SG) {
             int64_t x[kHU], px[kHU];
+            uint32_t wx[kHU], pwx[kHU];
 #pragma unroll
             for (int u = 0; u < kHU; u++) {
                 const int64_t t = t0 + u * SG;
                 x[u] = t < len[k] ? values[start[k] + t] : 0;
                 px[u] = (follows[k] && t < len[k]) ? values[pstart[k] + t] : 0;
+                wx[u] = (WT && t < len[k]) ? wbits[start[k] + t] : 0u;
+                pwx[u] = (WT && follows[k] && t < len[k]) ? wbits[pstart[k] + t] : 0u;
             }
 #pragma unroll
             for (int u = 0; u < kHU; u++) {
                 const int64_t t = t0 + u * SG;
                 if (t < len[k]) {
-                    follows[k] &= px[u] == x[u];
-                    h[k] += mix64((uint64_t)x[u] + (uint64_t)(t + 1) * 0x9e3779b97f4a7c15ull);
+                    follows[k] &= px[u] == x[u] && pwx[u] == wx[u];
+                    h[k] += mix64(hash_item<WT>(x[u], wx[u]) + (uint64_t)(t + 1) * 0x9e3779b97f4a7c15ull);
                 }
             }
         }
@@ -157,7 +173,8 @@ __global__ __launch_bounds__(256) void k_hash_insert(const int64_t *__restrict__
                 int eq = (offsets[ol + 1] - ostart) == len[k];
                 if (eq)
                     for (int64_t t = s; t < len[k]; t += SG)
-                        if (values[start[k] + t] != values[ostart + t]) {
+                        if (values[start[k] + t] != values[ostart + t] ||
+                            (WT && wbits[start[k] + t] != wbits[ostart + t])) {
                             eq = 0;
                             break;
                         }
@@ -357,7 +374,9 @@ __global__ __launch_bounds__(256) void k_emit(const int64_t *__restrict__ values
                                               const int64_t *__restrict__ u_offsets,
                                               const int64_t *__restrict__ counts,
                                               int64_t *__restrict__ u_values,
-                                              int32_t *__restrict__ inverse, unsigned inv_blocks)
+                                              int32_t *__restrict__ inverse, unsigned inv_blocks,
+                                              const uint32_t *__restrict__ wbits = nullptr,
+                                              uint32_t *__restrict__ u_wbits = nullptr)
 {
     if (blockIdx.x < inv_blocks) {
         const int64_t l = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -377,6 +396,9 @@ __global__ __launch_bounds__(256) void k_emit(const int64_t *__restrict__ values
         const int64_t dst = u_offsets[u];
         for (int64_t t = s; t < len; t += SG)
             u_values[dst + t] = values[start + t];
+        if (wbits)  // the weights of a weighted KJT travel with the ids
+            for (int64_t t = s; t < len; t += SG)
+                u_wbits[dst + t] = wbits[start + t];
     }
 }
 
@@ -767,14 +789,18 @@ void clear_table(hipStream_t st, const SlotWs &w, int tables)
 
 // Lists of a KJT into the per-feature tables: slot_of[l] (or -1 for a follower).
 void insert_lists(recd_ctx *ctx, hipStream_t st, const SlotWs &w, int F, int64_t B,
-                  const int64_t *values, const int64_t *offsets)
+                  const int64_t *values, const int64_t *offsets, const uint32_t *wbits = nullptr)
 {
     constexpr int SG = 8;
     const int64_t n_lists = (int64_t)F * B;
     clear_table(st, w, F);
     const int64_t hblocks = (n_lists + (256 / SG) * kLPG - 1) / ((256 / SG) * kLPG);
-    hipLaunchKernelGGL((k_hash_insert<SG>), dim3((unsigned)hblocks), dim3(256), 0, st, values, offsets, B,
-                       n_lists, w.table, (uint32_t)(w.cap - 1), w.slot_of, ctx->weak_hash);
+    if (wbits)
+        hipLaunchKernelGGL((k_hash_insert<SG, true>), dim3((unsigned)hblocks), dim3(256), 0, st, values, wbits,
+                           offsets, B, n_lists, w.table, (uint32_t)(w.cap - 1), w.slot_of, ctx->weak_hash);
+    else
+        hipLaunchKernelGGL((k_hash_insert<SG, false>), dim3((unsigned)hblocks), dim3(256), 0, st, values, wbits,
+                           offsets, B, n_lists, w.table, (uint32_t)(w.cap - 1), w.slot_of, ctx->weak_hash);
 }
 
 // After the insertion: representative and first-occurrence number of every item, first row of
@@ -806,10 +832,11 @@ unsigned copy_blocks_for(const recd_ctx *ctx, int64_t n_lists)
 } // namespace
 
 
-extern "C" recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t N,
-                                       const int64_t *values, const int64_t *offsets,
-                                       int64_t *u_values, int64_t *u_offsets, int32_t *inverse,
-                                       int64_t *feat_uoff, int64_t *host_U_M)
+// weights / u_weights: null for a plain KJT
+static recd_status build_plain(recd_ctx *ctx, int F, int64_t B, int64_t N, const int64_t *values,
+                               const uint32_t *weights, const int64_t *offsets, int64_t *u_values,
+                               uint32_t *u_weights, int64_t *u_offsets, int32_t *inverse,
+                               int64_t *feat_uoff, int64_t *host_U_M)
 {
     if (!ctx)
         return RECD_EINVAL;
@@ -834,17 +861,42 @@ extern "C" recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t 
     if (n_lists == 0) {
         hipLaunchKernelGGL(k_empty_ikjt, dim3(1), dim3(256), 0, st, F, u_offsets, feat_uoff, counts);
     } else {
-        insert_lists(ctx, st, w, F, B, values, offsets);
+        insert_lists(ctx, st, w, F, B, values, offsets, weights);
         number_slots(st, w, F, B, offsets, u_offsets, feat_uoff);
         const unsigned inv_blocks = (unsigned)((n_lists + 255) / 256);
         hipLaunchKernelGGL((k_emit<16>), dim3(inv_blocks + copy_blocks_for(ctx, n_lists)), dim3(256), 0, st,
                            values, offsets, B, n_lists, w.rep, w.number, w.src_of, u_offsets, counts,
-                           u_values, inverse, inv_blocks);
+                           u_values, inverse, inv_blocks, weights, u_weights);
     }
     RECD_HIP(ctx, hipGetLastError());
     if (host_U_M)
         RECD_TRY(recd_fetch_scalars(ctx, counts, 2, host_U_M));
     return RECD_OK;
+}
+
+extern "C" recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t N,
+                                       const int64_t *values, const int64_t *offsets,
+                                       int64_t *u_values, int64_t *u_offsets, int32_t *inverse,
+                                       int64_t *feat_uoff, int64_t *host_U_M)
+{
+    return build_plain(ctx, F, B, N, values, nullptr, offsets, u_values, nullptr, u_offsets, inverse, feat_uoff,
+                       host_U_M);
+}
+
+extern "C" recd_status recd_build_ikjt_weighted(recd_ctx *ctx, int F, int64_t B, int64_t N,
+                                                const int64_t *values, const float *weights,
+                                                const int64_t *offsets, int64_t *u_values,
+                                                float *u_weights, int64_t *u_offsets, int32_t *inverse,
+                                                int64_t *feat_uoff, int64_t *host_U_M)
+{
+    if (!ctx)
+        return RECD_EINVAL;
+    if (N > 0 && (!weights || !u_weights))
+        return recd_fail(ctx, RECD_EINVAL, "null weights");
+    // with no id there is no weight either: the plain builder
+    return build_plain(ctx, F, B, N, values, N > 0 ? reinterpret_cast<const uint32_t *>(weights) : nullptr,
+                       offsets, u_values, reinterpret_cast<uint32_t *>(u_weights), u_offsets, inverse,
+                       feat_uoff, host_U_M);
 }
 
 

@@ -102,6 +102,7 @@ struct SegSumArgs {
     const int64_t *ends;            // optional (single table, flat): list l ends at ends[l] ...
     const int64_t *count_dev;       // ... and the number of lists lives on the device
     const int64_t *lens;            // optional: list l spans offsets[l] .. offsets[l] + lens[l]
+    const float *weights;           // mode 3 (weighted sum): one fp32 weight per id, beside values
     const int64_t *div_off;         // optional (backward sums only): the finished row of list l is
                                     // divided by div_off[l+1] - div_off[l] when that is positive
     int site;                 // RECD_SITE_*: which call site (each has its own kernel instantiation)

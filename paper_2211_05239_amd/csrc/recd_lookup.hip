@@ -55,37 +55,40 @@ __device__ __forceinline__ uint32_t f32_to_bf16(float f)
 }
 
 // Pooling functions (Sec. 2.2: sum, average, max).  The average is the sum scaled at the end.
-enum { POOL_SUM = 0, POOL_MEAN = 1, POOL_MAX = 2 };
-template <int MODE> __device__ __forceinline__ float pool2(float a, float x)
+// POOL_WSUM: the sum with one fp32 weight per id, acc = fma(weight, row element, acc).
+enum { POOL_SUM = 0, POOL_MEAN = 1, POOL_MAX = 2, POOL_WSUM = 3 };
+template <int MODE> __device__ __forceinline__ float pool2(float a, float x, float wt = 1.f)
 {
-    return MODE == POOL_MAX ? fmaxf(a, x) : a + x;
+    return MODE == POOL_MAX ? fmaxf(a, x) : (MODE == POOL_WSUM ? __fmaf_rn(wt, x, a) : a + x);
 }
 template <int MODE> __device__ __forceinline__ float pool_identity()
 {
     return MODE == POOL_MAX ? -INFINITY : 0.f;
 }
 
-// fold the elements of one 16-byte vector into acc[0..per_vec)
-template <int TT, int MODE = POOL_SUM> __device__ __forceinline__ void accumulate(float *acc, const uint4 &v)
+// fold the elements of one 16-byte vector into acc[0..per_vec); wt: the id's weight (POOL_WSUM)
+template <int TT, int MODE = POOL_SUM>
+__device__ __forceinline__ void accumulate(float *acc, const uint4 &v, float wt = 1.f)
 {
     if constexpr (TT == RECD_F32) {
-        acc[0] = pool2<MODE>(acc[0], __uint_as_float(v.x));
-        acc[1] = pool2<MODE>(acc[1], __uint_as_float(v.y));
-        acc[2] = pool2<MODE>(acc[2], __uint_as_float(v.z));
-        acc[3] = pool2<MODE>(acc[3], __uint_as_float(v.w));
+        acc[0] = pool2<MODE>(acc[0], __uint_as_float(v.x), wt);
+        acc[1] = pool2<MODE>(acc[1], __uint_as_float(v.y), wt);
+        acc[2] = pool2<MODE>(acc[2], __uint_as_float(v.z), wt);
+        acc[3] = pool2<MODE>(acc[3], __uint_as_float(v.w), wt);
     } else if constexpr (TT == RECD_F16) {
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            acc[2 * i] = pool2<MODE>(acc[2 * i], __half2float(__ushort_as_half((unsigned short)(w[i] & 0xffffu))));
-            acc[2 * i + 1] = pool2<MODE>(acc[2 * i + 1], __half2float(__ushort_as_half((unsigned short)(w[i] >> 16))));
+            acc[2 * i] = pool2<MODE>(acc[2 * i], __half2float(__ushort_as_half((unsigned short)(w[i] & 0xffffu))), wt);
+            acc[2 * i + 1] =
+                pool2<MODE>(acc[2 * i + 1], __half2float(__ushort_as_half((unsigned short)(w[i] >> 16))), wt);
         }
     } else {
         const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
         for (int i = 0; i < 4; i++) {
-            acc[2 * i] = pool2<MODE>(acc[2 * i], bf16_to_f32(w[i] & 0xffffu));
-            acc[2 * i + 1] = pool2<MODE>(acc[2 * i + 1], bf16_to_f32(w[i] >> 16));
+            acc[2 * i] = pool2<MODE>(acc[2 * i], bf16_to_f32(w[i] & 0xffffu), wt);
+            acc[2 * i + 1] = pool2<MODE>(acc[2 * i + 1], bf16_to_f32(w[i] >> 16), wt);
         }
     }
 }
@@ -155,6 +158,8 @@ struct SegSumParams {
     // optional (SITE_GRAD_LISTS only): the finished row of list l is divided by
     // div_off[l+1] - div_off[l] when that is positive (backward of average pooling)
     const int64_t *div_off;
+    // POOL_WSUM: one fp32 weight per id, aligned with values
+    const float *weights;
 };
 
 // Adds the rows of NL chunks (chunk j: ns[j] <= 64 ids starting at values[starts[j]], rows of the
@@ -167,15 +172,18 @@ template <int LPR, int VPL, int TT, typename IdxT, int NL, int US, int MODE = PO
 __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL],
                                            const char *const *bases, const IdxT *values,
                                            const int64_t *starts, const int *ns, uint32_t row_bytes,
-                                           int lane, int g)
+                                           int lane, int g, const float *weights = nullptr)
 {
     constexpr int EPV = Elem<TT>::per_vec;
     constexpr int G = 64 / LPR;
+    constexpr bool WT = MODE == POOL_WSUM;
     uint32_t my_id[NL];
+    float my_wt[NL];
     int nmax = 0;
 #pragma unroll
     for (int j = 0; j < NL; j++) {
         my_id[j] = lane < ns[j] ? (uint32_t)values[starts[j] + lane] : 0u;
+        my_wt[j] = (WT && lane < ns[j]) ? weights[starts[j] + lane] : 0.f;
         nmax = ns[j] > nmax ? ns[j] : nmax;
     }
     for (int k0 = 0; k0 < nmax; k0 += G * US) {
@@ -196,15 +204,18 @@ __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL]
         for (int j = 0; j < NL; j++)
 #pragma unroll
             for (int u = 0; u < US; u++) {
+                // the weight is fetched from its lane only now: held since the loads were issued it
+                // would cost a register per load slot
+                const float wt = (WT && k0 + u * G < ns[j]) ? __shfl(my_wt[j], k0 + u * G + g) : 1.f;
                 if (k0 + u * G + G <= ns[j]) {  // scalar test: every lane group holds a real id
 #pragma unroll
                     for (int w = 0; w < VPL; w++)
-                        accumulate<TT, MODE>(acc[j] + w * EPV, v[j][u][w]);
+                        accumulate<TT, MODE>(acc[j] + w * EPV, v[j][u][w], wt);
                 } else if (k0 + u * G < ns[j]) {
                     if (k0 + u * G + g < ns[j]) {
 #pragma unroll
                         for (int w = 0; w < VPL; w++)
-                            accumulate<TT, MODE>(acc[j] + w * EPV, v[j][u][w]);
+                            accumulate<TT, MODE>(acc[j] + w * EPV, v[j][u][w], wt);
                     }
                 }
             }
@@ -214,7 +225,9 @@ __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL]
 // Occupancy target: 7 waves per SIMD (71 VGPRs) measured best for one-vector-per-lane rows; more
 // loads in flight per wave at lower occupancy, or fewer at 8 waves, were both slower.
 template <int LPR, int VPL, int TT, int OT, typename IdxT, int SITE, int MODE = POOL_SUM>
-__global__ __launch_bounds__(kBlock) __attribute__((amdgpu_waves_per_eu(VPL == 1 ? 7 : 1)))
+// The weighted sum needs a few registers more: 6 waves (80 VGPRs) instead of spilling.
+__global__ __launch_bounds__(kBlock)
+__attribute__((amdgpu_waves_per_eu(VPL == 1 ? (MODE == POOL_WSUM ? 6 : 7) : 1)))
 void k_segsum(const SegSumParams p)
 {
     constexpr int kWaves = kBlock / 64;
@@ -290,7 +303,7 @@ void k_segsum(const SegSumParams p)
 
     // A finished row: lanes of group 0 hold its NACC-element pieces in vals.
     auto finish_row = [&](int j, float *vals) {
-        if (MODE != POOL_SUM) {
+        if (MODE == POOL_MEAN || MODE == POOL_MAX) {
             const int64_t len = s_end[j] - s_start[j];
 #pragma unroll
             for (int i = 0; i < NACC; i++)
@@ -351,7 +364,8 @@ void k_segsum(const SegSumParams p)
                     acc[0][i] = pool_identity<MODE>();
                 for (int64_t base = start + (int64_t)wv * kChunk; base < end; base += kWaves * kChunk) {
                     const int n = (int)(end - base < kChunk ? end - base : kChunk);
-                    add_chunks<LPR, VPL, TT, IdxT, 1, UNR, MODE>(acc, &table, values, &base, &n, row_bytes, lane, g);
+                    add_chunks<LPR, VPL, TT, IdxT, 1, UNR, MODE>(acc, &table, values, &base, &n, row_bytes, lane, g,
+                                                                 p.weights);
                 }
                 fold_groups(acc[0]);
                 if (g == 0) {
@@ -397,7 +411,7 @@ void k_segsum(const SegSumParams p)
 #pragma unroll
             for (int i = 0; i < NACC; i++)
                 acc[0][i] = pool_identity<MODE>();
-            add_chunks<LPR, VPL, TT, IdxT, 1, UNR, MODE>(acc, &table, values, &start, &n, row_bytes, lane, g);
+            add_chunks<LPR, VPL, TT, IdxT, 1, UNR, MODE>(acc, &table, values, &start, &n, row_bytes, lane, g, p.weights);
             fold_groups(acc[0]);
             finish_row(j, acc[0]);
         }
@@ -605,6 +619,7 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     p.count_dev = a.count_dev;
     p.lens = a.lens;
     p.div_off = a.div_off;
+    p.weights = a.weights;
     p.F = a.F;
     p.D = a.D;
     const int epv = a.table_dt == RECD_F32 ? 4 : 8;
@@ -644,9 +659,16 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
         ok = launch_forward<SITE_UNIQUE, POOL_MAX>(st, blocks, v, a, p);
     else if (a.site == RECD_SITE_KJT && fwd && a.mode == POOL_MAX)
         ok = launch_forward<SITE_KJT, POOL_MAX>(st, blocks, v, a, p);
+    else if (a.site == RECD_SITE_UNIQUE && fwd && a.mode == POOL_WSUM && a.weights)
+        ok = launch_forward<SITE_UNIQUE, POOL_WSUM>(st, blocks, v, a, p);
+    else if (a.site == RECD_SITE_KJT && fwd && a.mode == POOL_WSUM && a.weights)
+        ok = launch_forward<SITE_KJT, POOL_WSUM>(st, blocks, v, a, p);
     else if (a.site == RECD_SITE_GRAD_LISTS && a.values_are_i32 && a.table_dt == RECD_F32 &&
              a.out_dt == RECD_F32 && a.mode == POOL_SUM)
         ok = launch_shape<RECD_F32, RECD_F32, int32_t, SITE_GRAD_LISTS>(st, blocks, v, p);
+    else if (a.site == RECD_SITE_GRAD_LISTS && a.values_are_i32 && a.table_dt == RECD_F32 &&
+             a.out_dt == RECD_F32 && a.mode == POOL_WSUM && a.weights)
+        ok = launch_shape<RECD_F32, RECD_F32, int32_t, SITE_GRAD_LISTS, POOL_WSUM>(st, blocks, v, p);
     if (!ok)
         return recd_fail(ctx, RECD_EINVAL, "unsupported row shape: D=%d table dtype %d out dtype %d",
                          a.D, (int)a.table_dt, (int)a.out_dt);
@@ -765,14 +787,18 @@ recd_status recd_validate_unique_lists(recd_ctx *ctx, int F, const int64_t *rows
     return validate_lists(ctx, F, rows, u_values, u_offsets, feat_uoff, 0, U, -1);
 }
 
+// weights: null, or one fp32 weight per id (then the pooling is the weighted sum, mode ignored)
 static recd_status lookup_unique(recd_ctx *ctx, int mode, int F, int D, recd_dtype table_dt,
                                  recd_dtype out_dt, const void *const *tables, const int64_t *rows,
                                  const int64_t *u_values, const int64_t *u_offsets,
-                                 const int64_t *feat_uoff, int64_t max_lists, void *pooled)
+                                 const int64_t *feat_uoff, int64_t max_lists, void *pooled,
+                                 const float *weights = nullptr)
 {
     RECD_TRY(check_lookup_shape(ctx, F, D, table_dt, out_dt));
     if (mode < 0 || mode > 2)
         return recd_fail(ctx, RECD_EINVAL, "unknown pooling mode %d", mode);
+    if (weights)
+        mode = POOL_WSUM;
     if (max_lists < 0)
         return recd_fail(ctx, RECD_EINVAL, "max_lists < 0");
     if (F == 0 || max_lists == 0)
@@ -800,6 +826,7 @@ static recd_status lookup_unique(recd_ctx *ctx, int mode, int F, int D, recd_dty
         a.lists_bound = max_lists;
         a.site = RECD_SITE_UNIQUE;
         a.mode = mode;
+        a.weights = weights;
         a.out = pooled;
         RECD_TRY(recd_launch_segsum(ctx, a));
     }
@@ -808,11 +835,14 @@ static recd_status lookup_unique(recd_ctx *ctx, int mode, int F, int D, recd_dty
 
 static recd_status lookup_kjt(recd_ctx *ctx, int mode, int F, int64_t B, int D, recd_dtype table_dt,
                               recd_dtype out_dt, const void *const *tables, const int64_t *rows,
-                              const int64_t *values, const int64_t *offsets, void *out)
+                              const int64_t *values, const int64_t *offsets, void *out,
+                              const float *weights = nullptr)
 {
     RECD_TRY(check_lookup_shape(ctx, F, D, table_dt, out_dt));
     if (mode < 0 || mode > 2)
         return recd_fail(ctx, RECD_EINVAL, "unknown pooling mode %d", mode);
+    if (weights)
+        mode = POOL_WSUM;
     if (B < 0)
         return recd_fail(ctx, RECD_EINVAL, "B < 0");
     if (F == 0 || B == 0)
@@ -845,6 +875,7 @@ static recd_status lookup_kjt(recd_ctx *ctx, int mode, int F, int64_t B, int D, 
         a.lists_bound = (int64_t)a.F * B;
         a.site = RECD_SITE_KJT;
         a.mode = mode;
+        a.weights = weights;
         a.out = out;
         RECD_TRY(recd_launch_segsum(ctx, a));
     }
@@ -869,6 +900,31 @@ recd_status recd_kjt_pooled_lookup(recd_ctx *ctx, int F, int64_t B, int D, recd_
                                    const int64_t *offsets, void *out)
 {
     return lookup_kjt(ctx, RECD_POOL_SUM, F, B, D, table_dt, out_dt, tables, rows, values, offsets, out);
+}
+
+// With no id there is no weight to read: a null weights pointer then selects the plain sum, which
+// stores the same zeros.
+recd_status recd_pooled_lookup_unique_weighted(recd_ctx *ctx, int F, int D, recd_dtype table_dt,
+                                               recd_dtype out_dt, const void *const *tables,
+                                               const int64_t *rows, const int64_t *u_values,
+                                               const float *u_weights, const int64_t *u_offsets,
+                                               const int64_t *feat_uoff, int64_t max_lists, void *pooled)
+{
+    if (ctx && u_values && !u_weights)
+        return recd_fail(ctx, RECD_EINVAL, "null u_weights");
+    return lookup_unique(ctx, RECD_POOL_SUM, F, D, table_dt, out_dt, tables, rows, u_values, u_offsets,
+                         feat_uoff, max_lists, pooled, u_weights);
+}
+
+recd_status recd_kjt_pooled_lookup_weighted(recd_ctx *ctx, int F, int64_t B, int D, recd_dtype table_dt,
+                                            recd_dtype out_dt, const void *const *tables,
+                                            const int64_t *rows, const int64_t *values,
+                                            const float *weights, const int64_t *offsets, void *out)
+{
+    if (ctx && values && !weights)
+        return recd_fail(ctx, RECD_EINVAL, "null weights");
+    return lookup_kjt(ctx, RECD_POOL_SUM, F, B, D, table_dt, out_dt, tables, rows, values, offsets, out,
+                      weights);
 }
 
 recd_status recd_pooled_lookup_unique_mode(recd_ctx *ctx, recd_pooling mode, int F, int D,

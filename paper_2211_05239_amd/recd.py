@@ -36,7 +36,8 @@ EXPORTED = [
     "recd_jagged_expand_inverse", "recd_kjt_sequence_lookup", "recd_build_ikjt_grouped",
     "recd_group_sum_unique", "recd_pooled_lookup_unique_mode", "recd_kjt_pooled_lookup_mode",
     "recd_build_partial_ikjt", "recd_pooled_lookup_partial", "recd_backward_sequence_dedup",
-    "recd_backward_dedup_mode",
+    "recd_backward_dedup_mode", "recd_build_ikjt_weighted", "recd_pooled_lookup_unique_weighted",
+    "recd_kjt_pooled_lookup_weighted", "recd_backward_dedup_weighted",
 ]
 
 _vp = C.c_void_p
@@ -58,6 +59,14 @@ _lib.recd_backward_dedup.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, _vp, _vp,
                                      C.c_int64, C.c_int64, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float,
                                      _vp]
 _lib.recd_backward_dedup_mode.argtypes = [_vp, C.c_int] + _lib.recd_backward_dedup.argtypes[1:]
+_lib.recd_build_ikjt_weighted.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64] + [_vp] * 9
+_lib.recd_pooled_lookup_unique_weighted.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, _vp,
+                                                    _vp, _vp, C.c_int64, _vp]
+_lib.recd_kjt_pooled_lookup_weighted.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, C.c_int, C.c_int, _vp, _vp,
+                                                 _vp, _vp, _vp, _vp]
+_lib.recd_backward_dedup_weighted.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
+                                              C.c_int64, C.c_int64, _vp, _vp, _vp, _vp, _vp, C.c_float,
+                                              C.c_float, _vp]
 _lib.recd_sequence_lookup_unique.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, _vp,
                                              _vp, C.c_int64, C.c_int64, _vp]
 _lib.recd_jagged_expand_inverse.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, _vp,
@@ -201,6 +210,47 @@ class Context:
             self._check(_lib.recd_backward_dedup(self._h, *args))
         else:
             self._check(_lib.recd_backward_dedup_mode(self._h, POOLING[mode], *args))
+        return int(host[0]) if want_count else None
+
+    # -- per-id weights -----------------------------------------------------------------------
+    def build_ikjt_weighted(self, F: int, B: int, values, weights, offsets, u_values, u_weights, u_offsets,
+                            inverse, feat_uoff, want_counts: bool = False):
+        host = (C.c_int64 * 2)(0, 0) if want_counts else None
+        self._check(_lib.recd_build_ikjt_weighted(
+            self._h, F, B, values.numel(), _ptr(values), _ptr(weights), _ptr(offsets), _ptr(u_values),
+            _ptr(u_weights), _ptr(u_offsets), _ptr(inverse), _ptr(feat_uoff), host))
+        return (int(host[0]), int(host[1])) if want_counts else None
+
+    def pooled_lookup_unique_weighted(self, tables, u_values, u_weights, u_offsets, feat_uoff, max_lists: int,
+                                      pooled):
+        F = len(tables)
+        D = tables[0].shape[1] if F else pooled.shape[-1]
+        tdt = _DT[tables[0].dtype] if F else _DT[pooled.dtype]
+        self._check(_lib.recd_pooled_lookup_unique_weighted(
+            self._h, F, D, tdt, _DT[pooled.dtype], self._table_array(tables), self._rows_array(tables),
+            _ptr(u_values), _ptr(u_weights), _ptr(u_offsets), _ptr(feat_uoff), max_lists, _ptr(pooled)))
+
+    def kjt_pooled_lookup_weighted(self, tables, B: int, values, weights, offsets, out):
+        F = len(tables)
+        D = tables[0].shape[1] if F else out.shape[-1]
+        tdt = _DT[tables[0].dtype] if F else _DT[out.dtype]
+        self._check(_lib.recd_kjt_pooled_lookup_weighted(
+            self._h, F, B, D, tdt, _DT[out.dtype], self._table_array(tables), self._rows_array(tables),
+            _ptr(values), _ptr(weights), _ptr(offsets), _ptr(out)))
+
+    def backward_dedup_weighted(self, F: int, B: int, grad_out, inverse, feat_uoff, u_values, u_weights,
+                                u_offsets, rows: Sequence[int], U_cap: int, M_cap: int, touched_rows, feat_roff,
+                                grad_rows, tables=None, adagrad_state=None, lr: float = 0.0, eps: float = 0.0,
+                                want_count: bool = False):
+        D = grad_out.shape[-1]
+        rows_arr = (C.c_int64 * len(rows))(*rows)
+        tabs = self._table_array(tables) if tables is not None else None
+        state = self._table_array(adagrad_state) if adagrad_state is not None else None
+        host = (C.c_int64 * 1)(0) if want_count else None
+        self._check(_lib.recd_backward_dedup_weighted(
+            self._h, F, B, D, _ptr(grad_out), _ptr(inverse), _ptr(feat_uoff), _ptr(u_values), _ptr(u_weights),
+            _ptr(u_offsets), rows_arr, U_cap, M_cap, _ptr(touched_rows), _ptr(feat_roff), _ptr(grad_rows),
+            tabs, state, lr, eps, host))
         return int(host[0]) if want_count else None
 
     # -- sequence (unpooled) features ---------------------------------------------------------

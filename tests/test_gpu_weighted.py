@@ -1,0 +1,204 @@
+"""GPU parity of the per-id-weight calls (weighted builder, weighted unique / KJT lookups, the
+backward of the weighted lookup) against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import recd_oracle as orc
+from paper_2211_05239_amd import synth
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def recd():
+    from paper_2211_05239_amd import recd as mod
+    return mod
+
+
+@pytest.fixture(scope="module")
+def ctx(recd):
+    c = recd.Context(0)
+    yield c
+    c.close()
+
+
+def _bits(t):
+    return t.view(torch.int32 if t.element_size() == 4 else torch.int16)
+
+
+def _build(ctx, batch, weights):
+    F, B, N = batch.F, batch.B, batch.N
+    values, offsets = gu.to_dev(batch.values), gu.to_dev(batch.offsets)
+    d_w = gu.to_dev(weights)
+    if N == 0:
+        values = torch.zeros(1, dtype=torch.int64, device="cuda")[:0]
+        d_w = torch.zeros(1, device="cuda")[:0]
+    ik = gu.DeviceIKJT(F, B, N)
+    u_weights = torch.full((max(N, 1),), float("nan"), device="cuda")
+    ik.U, ik.M = ctx.build_ikjt_weighted(F, B, values, d_w, offsets, ik.u_values, u_weights, ik.u_offsets,
+                                         ik.inverse, ik.feat_uoff, want_counts=True)
+    ref = orc.build_ikjt_weighted(F, B, batch.values, weights, batch.offsets)
+    uv, uw, uo, inv, fu = ref
+    assert (ik.U, ik.M) == (int(fu[-1]), len(uv))
+    g_uv, g_uo, g_inv, g_fu = ik.numpy()
+    assert np.array_equal(g_uv, uv) and np.array_equal(g_uo, uo)
+    assert np.array_equal(g_inv, inv) and np.array_equal(g_fu, fu)
+    assert np.array_equal(u_weights[:ik.M].cpu().numpy().view(np.uint32), uw.view(np.uint32))
+    return values, d_w, offsets, ik, u_weights, ref
+
+
+def _forward_case(ctx, w, batch, weights, odt=None):
+    F, B, D, dt = batch.F, batch.B, w.D, w.table_dtype
+    tabs = synth.make_tables(w)
+    d_tabs = gu.tables_to_dev(tabs, dt)
+    odt = odt or gu.TORCH_DT[dt]
+    close = gu.assert_close_f32 if odt == torch.float32 else gu.assert_close_16
+    values, d_w, offsets, ik, u_weights, (uv, uw, uo, inv, fu) = _build(ctx, batch, weights)
+    pooled = torch.full((max(F * B, 1), D), float("nan"), dtype=odt, device="cuda")
+    out = torch.full((F, B, D), float("nan"), dtype=odt, device="cuda")
+    kjt = torch.full((F, B, D), float("nan"), dtype=odt, device="cuda")
+    ctx.pooled_lookup_unique_weighted(d_tabs, ik.u_values, u_weights, ik.u_offsets, ik.feat_uoff, F * B, pooled)
+    ctx.expand_inverse(F, B, pooled, ik.feat_uoff, ik.inverse, out)
+    ctx.kjt_pooled_lookup_weighted(d_tabs, B, values, d_w, offsets, kjt)
+    assert torch.equal(_bits(out), _bits(kjt))  # same order of operations per list on both paths
+    ref_u = orc.pooled_lookup_weighted(tabs, dt, uv, uw, uo, fu)
+    close(gu.out_to_f64(pooled[:ik.U]), ref_u, "weighted pooled unique")
+    ref_k = orc.pooled_lookup_weighted(tabs, dt, batch.values, weights, batch.offsets,
+                                       np.arange(F + 1, dtype=np.int64) * B)
+    close(gu.out_to_f64(kjt).reshape(F * B, D), ref_k, "weighted KJT lookup")
+    return ik
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_weighted_builder_tiny(ctx, recd, seed):
+    rng = np.random.default_rng(700 + seed)
+    batch = synth.tiny_batch(rng, 3, 61 + 40 * seed, 3, 4)
+    weights = synth.make_weights(batch, seed, perturb=0.3)
+    for weak in (0, 1):  # with the hash reduced to the list length only the exact comparison decides
+        ctx.set_option(recd.RECD_OPT_WEAK_HASH, weak)
+        try:
+            _build(ctx, batch, weights)
+        finally:
+            ctx.set_option(recd.RECD_OPT_WEAK_HASH, 0)
+
+
+def test_weighted_builder_degenerate(ctx):
+    # equal ids, weights decide; +0 / -0 / NaN bit patterns; empty lists; one row; no ids at all
+    batch = synth.batch_from_lists([[[1, 2], [1, 2], [1, 2], [], [1, 2], [2, 1], []]])
+    w = np.array([.5, .5, .5, .5, .5, 1., .5, .5, .5, .5], dtype=np.float32)
+    _, _, _, ik, _, ref = _build(ctx, batch, w)
+    assert ref[3].tolist() == [0, 0, 1, 2, 0, 3, 2]
+    batch = synth.batch_from_lists([[[7], [7], [7], [7]]])
+    _build(ctx, batch, np.array([0.0, -0.0, np.nan, np.nan], dtype=np.float32))
+    _build(ctx, synth.batch_from_lists([[[3, 3, 3]]]), np.array([1, 2, 3], dtype=np.float32))
+    _build(ctx, synth.batch_from_lists([[[], []], [[], []]]), np.zeros(0, dtype=np.float32))
+    # all weights equal: the unweighted IKJT
+    rng = np.random.default_rng(1)
+    batch = synth.tiny_batch(rng, 2, 300, 3, 3)
+    _, _, _, ik, _, _ = _build(ctx, batch, np.ones(batch.N, dtype=np.float32))
+    _, _, plain = gu.gpu_build(ctx, batch)
+    assert (ik.U, ik.M) == (plain.U, plain.M) and torch.equal(ik.inverse, plain.inverse)
+
+
+@pytest.mark.parametrize("name,kw", [("cfg1", dict(F=3, B=500, rows=2000)),
+                                     ("cfg2", dict(F=4, B=1024, rows=20_000, D=64, len_max=150)),
+                                     ("cfg3", dict(F=2, B=512, rows=5000, len_max=300)),
+                                     ("cfg5", dict(F=8, B=2048, rows=30_000))])
+@pytest.mark.parametrize("perturb", [0.0, 0.2])
+def test_weighted_forward_workloads(ctx, name, kw, perturb):
+    w = synth.scaled(synth.WORKLOADS[name], **kw)
+    batch = synth.make_batch(w, 0)
+    weights = synth.make_weights(batch, 3, perturb=perturb)
+    ik = _forward_case(ctx, w, batch, weights)
+    _, _, plain = gu.gpu_build(ctx, batch)
+    assert ik.U == plain.U if perturb == 0.0 else ik.U > plain.U
+
+
+@pytest.mark.parametrize("dt,odt,D", [("f32", None, 4), ("f32", None, 24), ("f32", None, 256), ("f32", None, 512),
+                                      ("f32", None, 1024), ("f16", None, 64), ("f16", torch.float32, 128),
+                                      ("bf16", None, 256), ("bf16", torch.float32, 1024), ("f16", None, 2048)])
+def test_weighted_forward_shapes(ctx, dt, odt, D):
+    w = synth.scaled(synth.WORKLOADS["cfg2"], F=3, B=300, rows=3000, D=D, table_dtype=dt, len_max=100)
+    batch = synth.make_batch(w, 1)
+    _forward_case(ctx, w, batch, synth.make_weights(batch, 1, perturb=0.1), odt)
+
+
+def test_weighted_unit_weights_equal_plain_sum(ctx):
+    w = synth.scaled(synth.WORKLOADS["cfg5"], F=4, B=1024, rows=20_000)
+    batch = synth.make_batch(w, 0)
+    d_tabs = gu.tables_to_dev(synth.make_tables(w), "f32")
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    ones = torch.ones(max(batch.N, 1), device="cuda")
+    a = torch.zeros(w.F, w.B, w.D, device="cuda")
+    b = torch.zeros(w.F, w.B, w.D, device="cuda")
+    ctx.kjt_pooled_lookup_weighted(d_tabs, w.B, values, ones, offsets, a)
+    ctx.kjt_pooled_lookup(d_tabs, w.B, values, offsets, b)
+    assert torch.equal(a, b)  # fma(1, x, acc) = acc + x, same order
+
+
+def _backward_case(ctx, w, batch, weights, with_adagrad=True):
+    F, B, D = w.F, w.B, w.D
+    gout = synth.make_grad_out(w, 0)
+    values, d_w, offsets, ik, u_weights, (uv, uw, uo, inv, fu) = _build(ctx, batch, weights)
+    M = max(ik.M, 1)
+    touched = torch.full((M,), -7, dtype=torch.int64, device="cuda")
+    feat_roff = torch.full((F + 1,), -7, dtype=torch.int64, device="cuda")
+    grad_rows = torch.full((M, D), float("nan"), device="cuda")
+    tabs = synth.make_tables(w)
+    d_tabs = gu.tables_to_dev(tabs, "f32")
+    state0 = [np.abs(np.random.default_rng(5 + f).standard_normal(w.rows)).astype(np.float32) * 1e-4
+              for f in range(F)]
+    d_state = [gu.to_dev(s) for s in state0]
+    lr, eps = 0.01, 1e-8
+    R = ctx.backward_dedup_weighted(F, B, gu.to_dev(gout), ik.inverse, ik.feat_uoff, ik.u_values, u_weights,
+                                    ik.u_offsets, [w.rows] * F, ik.U, ik.M, touched, feat_roff, grad_rows,
+                                    tables=d_tabs if with_adagrad else None,
+                                    adagrad_state=d_state if with_adagrad else None, lr=lr, eps=eps,
+                                    want_count=True)
+    tr, fr, gr = orc.backward_kjt_weighted(F, B, gout, batch.values, weights, batch.offsets)
+    assert R == len(tr) and np.array_equal(touched[:R].cpu().numpy(), tr)
+    assert np.array_equal(feat_roff.cpu().numpy(), fr)
+    gu.assert_close_f32(gu.out_to_f64(grad_rows[:R]), gr, "weighted grad_rows")
+    if with_adagrad:
+        for f in range(F):
+            rows_f = tr[fr[f]:fr[f + 1]]
+            w_new, m_new = orc.rowwise_adagrad(gr[fr[f]:fr[f + 1]], tabs[f][rows_f].astype(np.float64),
+                                               state0[f][rows_f].astype(np.float64), lr, eps)
+            gu.assert_close_f32(d_tabs[f].cpu().numpy()[rows_f].astype(np.float64), w_new, "adagrad rows")
+            gu.assert_close_f32(d_state[f].cpu().numpy()[rows_f].astype(np.float64), m_new, "adagrad state")
+    return touched[:R].clone(), grad_rows[:R].clone()
+
+
+@pytest.mark.parametrize("name,kw", [("cfg1", dict(F=3, B=357, rows=900, D=32)),
+                                     ("cfg2", dict(F=4, B=1024, rows=20_000, D=64, len_max=150)),
+                                     ("cfg5", dict(F=3, B=2048, rows=30_000, D=128))])
+def test_weighted_backward(ctx, name, kw):
+    """cfg5's Zipf ids give segments far longer than 64 entries: the chunked pass carries the weights."""
+    w = synth.scaled(synth.WORKLOADS[name], **kw)
+    batch = synth.make_batch(w, 0)
+    _backward_case(ctx, w, batch, synth.make_weights(batch, 2, perturb=0.1))
+
+
+def test_weighted_backward_giant_segment_and_determinism(ctx):
+    B = 20000
+    batch = synth.batch_from_lists([[[7, 100 + i] for i in range(B)]])
+    w = synth.scaled(synth.WORKLOADS["cfg1"], F=1, B=B, rows=100 + B, D=8)
+    weights = synth.make_weights(batch, 4)
+    a = _backward_case(ctx, w, batch, weights, with_adagrad=False)
+    b = _backward_case(ctx, w, batch, weights, with_adagrad=False)
+    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+
+
+def test_weighted_argument_errors(ctx, recd):
+    batch = synth.batch_from_lists([[[1], [2]]])
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    tabs = [torch.zeros(5, 8, device="cuda")]
+    out = torch.zeros(1, 2, 8, device="cuda")
+    with pytest.raises(recd.RecdError) as e:
+        ctx.kjt_pooled_lookup_weighted(tabs, 2, values, None, offsets, out)
+    assert e.value.status == recd.RECD_EINVAL
+    with pytest.raises(recd.RecdError) as e:
+        ctx.pooled_lookup_unique_weighted(tabs, ik.u_values, None, ik.u_offsets, ik.feat_uoff, 2, out)
+    assert e.value.status == recd.RECD_EINVAL
