@@ -343,3 +343,85 @@ def test_cfg5_sequence_backward_full(recd):
         untouched[tr_f] = False
         assert np.array_equal(after[untouched], before[f][untouched])
     ctx.close()
+
+
+def test_cfg5_weighted_full(recd):
+    """Per-id weights at the benchmark size: the weighted builder in full, the weighted lookup on both
+    paths bit for bit and on sampled features against the oracle, the weighted backward with the
+    fused update on sampled features."""
+    w = synth.WORKLOADS["cfg5"]
+    F, B, D = w.F, w.B, w.D
+    batch = synth.make_batch(w, 2)
+    weights = synth.make_weights(batch, 2, perturb=0.05)
+    tabs = _device_tables(w, torch.float32)
+    sample = (3, 57)
+    before = {f: tabs[f].cpu().numpy() for f in sample}
+    ctx = recd.Context(0)
+    values, offsets, d_w = gu.to_dev(batch.values), gu.to_dev(batch.offsets), gu.to_dev(weights)
+    ik = gu.DeviceIKJT(F, B, batch.N)
+    u_weights = torch.zeros(batch.N, device="cuda")
+    ik.U, ik.M = ctx.build_ikjt_weighted(F, B, values, d_w, offsets, ik.u_values, u_weights, ik.u_offsets,
+                                         ik.inverse, ik.feat_uoff, want_counts=True)
+    uv, uw, uo, inv, fu = orc.build_ikjt_weighted(F, B, batch.values, weights, batch.offsets)
+    for name, got, r in zip(("u_values", "u_offsets", "inverse", "feat_uoff"), ik.numpy(), (uv, uo, inv, fu)):
+        assert np.array_equal(got, r), name
+    assert np.array_equal(u_weights[:ik.M].cpu().numpy().view(np.uint32), uw.view(np.uint32))
+    pooled = torch.zeros(ik.U, D, device="cuda")
+    out = torch.zeros(F, B, D, device="cuda")
+    kjt = torch.zeros(F, B, D, device="cuda")
+    ctx.pooled_lookup_unique_weighted(tabs, ik.u_values, u_weights, ik.u_offsets, ik.feat_uoff, ik.U, pooled)
+    ctx.expand_inverse(F, B, pooled, ik.feat_uoff, ik.inverse, out)
+    ctx.kjt_pooled_lookup_weighted(tabs, B, values, d_w, offsets, kjt)
+    assert torch.equal(out, kjt)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(101)
+    grad_out = torch.empty(F, B, D, dtype=torch.float32, device="cuda")
+    grad_out.normal_(0.0, 0.01, generator=g)
+    state = [torch.zeros(w.rows, device="cuda") for _ in range(F)]
+    touched = torch.full((ik.M,), -1, dtype=torch.int64, device="cuda")
+    feat_roff = torch.zeros(F + 1, dtype=torch.int64, device="cuda")
+    grad_rows = torch.zeros(ik.M, D, device="cuda")
+    out_host = {f: gu.out_to_f64(out[f]) for f in sample}  # before the update changes the tables
+    R = ctx.backward_dedup_weighted(F, B, grad_out, ik.inverse, ik.feat_uoff, ik.u_values, u_weights,
+                                    ik.u_offsets, [w.rows] * F, ik.U, ik.M, touched, feat_roff, grad_rows,
+                                    tables=tabs, adagrad_state=state, lr=0.01, eps=1e-8, want_count=True)
+    fr = feat_roff.cpu().numpy()
+    tr = touched[:R].cpu().numpy()
+    for f in sample:
+        v_f, o_f = _feature_slice(batch, f)
+        lo, hi = int(batch.offsets[f * B]), int(batch.offsets[(f + 1) * B])
+        ref = orc.pooled_lookup_weighted([before[f]], "f32", v_f, weights[lo:hi], o_f, np.array([0, B]))
+        gu.assert_close_f32(out_host[f], ref, f"weighted lookup of feature {f}")
+        tr_f, _, gr_f = orc.backward_kjt_weighted(1, B, grad_out[f:f + 1].cpu().numpy(), v_f, weights[lo:hi], o_f)
+        assert np.array_equal(tr_f, tr[fr[f]:fr[f + 1]])
+        gu.assert_close_f32(grad_rows[fr[f]:fr[f + 1]].double().cpu().numpy(), gr_f, f"grad rows {f}")
+        w_new, m_new = orc.rowwise_adagrad(gr_f, before[f][tr_f].astype(np.float64), np.zeros(len(tr_f)),
+                                           0.01, 1e-8)
+        gu.assert_close_f32(tabs[f].cpu().numpy()[tr_f].astype(np.float64), w_new, f"updated rows {f}")
+        gu.assert_close_f32(state[f].cpu().numpy()[tr_f].astype(np.float64), m_new, f"state {f}")
+    ctx.close()
+
+
+def test_cfg5_mean_backward_full(recd):
+    w = synth.WORKLOADS["cfg5"]
+    F, B, D = w.F, w.B, w.D
+    batch = synth.make_batch(w, 3)
+    ctx = recd.Context(0)
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(102)
+    grad_out = torch.empty(F, B, D, dtype=torch.float32, device="cuda")
+    grad_out.normal_(0.0, 0.01, generator=g)
+    touched = torch.full((ik.M,), -1, dtype=torch.int64, device="cuda")
+    feat_roff = torch.zeros(F + 1, dtype=torch.int64, device="cuda")
+    grad_rows = torch.zeros(ik.M, D, device="cuda")
+    R = ctx.backward_dedup(F, B, grad_out, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F,
+                           ik.U, ik.M, touched, feat_roff, grad_rows, want_count=True, mode="mean")
+    fr = feat_roff.cpu().numpy()
+    tr = touched[:R].cpu().numpy()
+    for f in (5, 62):
+        v_f, o_f = _feature_slice(batch, f)
+        tr_f, _, gr_f = orc.backward_kjt(1, B, grad_out[f:f + 1].cpu().numpy(), v_f, o_f, mode="mean")
+        assert np.array_equal(tr_f, tr[fr[f]:fr[f + 1]])
+        gu.assert_close_f32(grad_rows[fr[f]:fr[f + 1]].double().cpu().numpy(), gr_f, f"mean grad rows {f}")
+    ctx.close()

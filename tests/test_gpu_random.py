@@ -121,6 +121,24 @@ def test_random_configuration(ctx, recd, seed):
     ctx.pooled_lookup_unique(d_tabs, ik.u_values, ik.u_offsets, ik.feat_uoff, F * B, pooled_s)
     assert torch.equal(_bits(pooled_p[:pU]), _bits(pooled_s[:ik.U]))
 
+    # per-id weights: builder, both lookups, backward
+    weights = synth.make_weights(batch, seed, perturb=float(rng.choice([0.0, 0.3])))
+    d_w = gu.to_dev(weights) if N else torch.zeros(1, device="cuda")[:0]
+    wik = gu.DeviceIKJT(F, B, N)
+    u_w = torch.full((max(N, 1),), float("nan"), device="cuda")
+    wik.U, wik.M = ctx.build_ikjt_weighted(F, B, values, d_w, offsets, wik.u_values, u_w, wik.u_offsets,
+                                           wik.inverse, wik.feat_uoff, want_counts=True)
+    w_uv, w_uw, w_uo, w_inv, w_fu = orc.build_ikjt_weighted(F, B, batch.values, weights, batch.offsets)
+    for name, g, r in zip(("u_values", "u_offsets", "inverse", "feat_uoff"), wik.numpy(), (w_uv, w_uo, w_inv, w_fu)):
+        assert np.array_equal(g, r), "weighted " + name
+    assert np.array_equal(u_w[:wik.M].cpu().numpy().view(np.uint32), w_uw.view(np.uint32))
+    ctx.pooled_lookup_unique_weighted(d_tabs, wik.u_values, u_w, wik.u_offsets, wik.feat_uoff, F * B, pooled)
+    ctx.expand_inverse(F, B, pooled, wik.feat_uoff, wik.inverse, out)
+    ctx.kjt_pooled_lookup_weighted(d_tabs, B, values, d_w, offsets, kjt)
+    assert torch.equal(_bits(out), _bits(kjt))
+    close(gu.out_to_f64(kjt).reshape(F * B, D),
+          orc.pooled_lookup_weighted(tabs, dt, batch.values, weights, batch.offsets, lo_kjt), "weighted kjt")
+
     # backward of both paths (fp32 tables)
     if dt == "f32":
         gout = (rng.standard_normal((F, B, D), dtype=np.float32) * np.float32(0.01))
@@ -133,6 +151,12 @@ def test_random_configuration(ctx, recd, seed):
         tr, fr, gr = orc.backward_kjt(F, B, gout, batch.values, batch.offsets, mode=bmode)
         assert R == len(tr) and np.array_equal(touched[:R].cpu().numpy(), tr)
         gu.assert_close_f32(gu.out_to_f64(grad_rows[:R]), gr, f"row gradients ({bmode})")
+        Rw = ctx.backward_dedup_weighted(F, B, gu.to_dev(gout), wik.inverse, wik.feat_uoff, wik.u_values, u_w,
+                                         wik.u_offsets, [rows] * F, wik.U, wik.M, touched, feat_roff, grad_rows,
+                                         want_count=True)
+        trw, frw, grw = orc.backward_kjt_weighted(F, B, gout, batch.values, weights, batch.offsets)
+        assert Rw == len(trw) and np.array_equal(touched[:Rw].cpu().numpy(), trw)
+        gu.assert_close_f32(gu.out_to_f64(grad_rows[:Rw]), grw, "weighted row gradients")
         sg = (rng.standard_normal((max(N, 1), D), dtype=np.float32) * np.float32(0.01))[:N]
         grad_emb = torch.zeros(max(ik.M, 1), D, device="cuda")
         d_sg = gu.to_dev(sg) if N else torch.zeros(1, D, device="cuda")[:0]
