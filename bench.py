@@ -50,6 +50,9 @@ def parse_args():
     ap.add_argument("--partial", type=float, default=0.0,
                     help="also time the partial IKJT path on the workload with this probability of a "
                          "sample's lists shifting by one id within a session (0 = skip)")
+    ap.add_argument("--weights", action="store_true",
+                    help="also time the per-id-weight calls (weighted builder, lookups, backward) on the same "
+                         "batches with seeded weights")
     ap.add_argument("--reader", action="store_true",
                     help="also report the builder alone (the conversion step of a reader) beside the CPU "
                          "oracle's builder run feature-parallel on the host cores")
@@ -298,7 +301,55 @@ def run_workload(torch, recd, synth, w, args, need_backward, detail=True, pipeli
         res["grouped"] = grouped_regions(torch, P, timed, reps, args.groups)
     if getattr(args, "partial", 0.0) > 0.0:
         res["partial"] = partial_regions(torch, synth, P, timed, reps, args.partial)
+    if getattr(args, "weights", False):
+        res["weighted"] = weighted_regions(torch, synth, P, timed, reps)
     return res, P
+
+
+def weighted_regions(torch, synth, P, timed, reps):
+    """Per-id weights: every id of the same batches carries a seeded fp32 weight (a function of id and
+    position, so the duplication of the batch is kept).  Times the weighted builder, the weighted
+    unique and KJT lookups and the weighted backward (fused update) beside their plain forms."""
+    w = P.w
+    F, B, D = w.F, w.B, w.D
+    nb = len(P.batches)
+    wts = [torch.from_numpy(synth.make_weights(b, i)).cuda() for i, b in enumerate(P.batches)]
+    u_w = [torch.zeros(b.N, dtype=torch.float32, device="cuda") for b in P.batches]
+
+    def build(i, counts=False):
+        return P.ctx.build_ikjt_weighted(F, B, P.values[i], wts[i], P.offsets[i], P.u_values[i], u_w[i],
+                                         P.u_offsets[i], P.inverse[i], P.feat_uoff[i], want_counts=counts)
+
+    cnt = [build(i, True) for i in range(nb)]
+
+    def lookup(i):
+        P.ctx.pooled_lookup_unique_weighted(P.tables, P.u_values[i], u_w[i], P.u_offsets[i], P.feat_uoff[i],
+                                            cnt[i][0], P.pooled)
+
+    def kjt(i):
+        P.ctx.kjt_pooled_lookup_weighted(P.tables, B, P.values[i], wts[i], P.offsets[i], P.kjt_out)
+
+    def backward(i):
+        P.ctx.backward_dedup_weighted(F, B, P.grad_out, P.inverse[i], P.feat_uoff[i], P.u_values[i], u_w[i],
+                                      P.u_offsets[i], P.rows, cnt[i][0], cnt[i][1], P.touched, P.feat_roff,
+                                      P.grad_rows, tables=P.tables, adagrad_state=P.state, lr=0.01, eps=1e-8)
+
+    names = {"build": build, "lookup": lookup, "kjt": kjt}
+    if P.need_backward:
+        names["backward"] = backward
+    t = {n: [] for n in names}
+    for _ in range(max(reps // 2, 2)):
+        for n, fn in names.items():
+            t[n].append(timed(fn))
+    ms = {n: float(np.mean(v)) for n, v in t.items()}
+    out = {"build_weighted_ms": ms["build"], "lookup_unique_weighted_ms": ms["lookup"],
+           "kjt_lookup_weighted_ms": ms["kjt"], "U": float(np.mean([c[0] for c in cnt])),
+           "M": float(np.mean([c[1] for c in cnt]))}
+    if P.need_backward:
+        out["backward_weighted_ms"] = ms["backward"]
+    for i in range(nb):   # leave the plain IKJTs behind
+        P.build(i)
+    return out
 
 
 def partial_regions(torch, synth, P, timed, reps, shift):

@@ -225,9 +225,10 @@ __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL]
 // Occupancy target: 7 waves per SIMD (71 VGPRs) measured best for one-vector-per-lane rows; more
 // loads in flight per wave at lower occupancy, or fewer at 8 waves, were both slower.
 template <int LPR, int VPL, int TT, int OT, typename IdxT, int SITE, int MODE = POOL_SUM>
-// The weighted sum needs a few registers more: 6 waves (80 VGPRs) instead of spilling.
+// The weighted sum needs a few registers more: 6 waves (80 VGPRs) instead of spilling measured best
+// for the KJT lookup, 5 for the unique lists (7 with spills was slower for both).
 __global__ __launch_bounds__(kBlock)
-__attribute__((amdgpu_waves_per_eu(VPL == 1 ? (MODE == POOL_WSUM ? 6 : 7) : 1)))
+__attribute__((amdgpu_waves_per_eu(VPL == 1 ? (MODE == POOL_WSUM ? (SITE == SITE_KJT ? 6 : 5) : 7) : 1)))
 void k_segsum(const SegSumParams p)
 {
     constexpr int kWaves = kBlock / 64;
