@@ -810,7 +810,10 @@ struct SortSet {
 
 struct BwdWs {
     SortSet a, b;
-    int64_t *list_off, *seg_start;
+    // Segment numbering of step A (list_off, seg_start, long_count_a) and of step B (the _b arrays,
+    // seg_feat, long_count and what follows): separate, the two are numbered on different streams.
+    int64_t *list_off, *seg_start, *long_count_a;
+    int64_t *list_off_b, *seg_start_b;
     int32_t *seg_feat, *lseg_t, *lseg_first, *lseg_n;
     int64_t *long_count, *item_start, *item_end;
     float *g_u, *partials;
@@ -849,8 +852,11 @@ BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D)
     w.a = carve_sort(c, n_lists, false);
     w.b = carve_sort(c, M_cap, true);
     w.list_off = c.take<int64_t>(2);
-    w.seg_start = c.take<int64_t>(n_max + 1);
-    w.seg_feat = c.take<int32_t>(n_max);
+    w.long_count_a = c.take<int64_t>(2);
+    w.seg_start = c.take<int64_t>(n_lists + 1);
+    w.list_off_b = c.take<int64_t>(2);
+    w.seg_start_b = c.take<int64_t>(M_cap + 1);
+    w.seg_feat = c.take<int32_t>(M_cap);
     // segments longer than 64 entries: at most n/65 of them, cut into at most n/256 + n/65 chunks
     const int64_t lseg_cap = n_max / 65 + 16, item_cap = n_max / 256 + n_max / 65 + 16;
     w.lseg_t = c.take<int32_t>(lseg_cap);
@@ -869,31 +875,78 @@ BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D)
 
 // Segments of equal keys in the sorted keys ks: seg_start, list_off = {0, R} and, for (feature, row)
 // keys, the row ids, the feature of every segment and feat_roff.
-template <typename KeyT>
-recd_status number_segments(recd_ctx *ctx, const BwdWs &w, const SortSet &set, const KeyT *ks, int64_t n_cap,
-                            int row_bits, int F, int64_t *touched_rows, int64_t *feat_roff)
+// (row_bits < 0: step A's arrays; row_bits >= 0: step B's.)
+struct SegBufs {
+    int64_t *seg_start, *list_off, *long_count;
+};
+
+SegBufs seg_bufs(const BwdWs &w, int row_bits)
 {
-    hipStream_t st = ctx->stream;
+    return row_bits < 0 ? SegBufs{w.seg_start, w.list_off, w.long_count_a}
+                        : SegBufs{w.seg_start_b, w.list_off_b, w.long_count};
+}
+
+template <typename KeyT>
+recd_status number_segments(recd_ctx *ctx, hipStream_t st, const BwdWs &w, const SortSet &set, const KeyT *ks,
+                            int64_t n_cap, int row_bits, int F, int64_t *touched_rows, int64_t *feat_roff)
+{
+    const SegBufs sb = seg_bufs(w, row_bits);
     const unsigned tiles = (unsigned)((n_cap + kScanTile - 1) / kScanTile > 0 ? (n_cap + kScanTile - 1) / kScanTile : 1);
     hipLaunchKernelGGL((k_head_count<KeyT>), dim3(tiles), dim3(256), 0, st, ks, set.n_dev, set.bsum,
-                       w.long_count);
+                       sb.long_count);
     hipLaunchKernelGGL(k_scan_small, dim3(1), dim3(1024), 0, st, set.bsum, (int64_t)tiles);
     hipLaunchKernelGGL((k_segments<KeyT>), dim3(tiles), dim3(256), 0, st, ks, set.n_dev, set.bsum,
-                       w.seg_start, w.list_off, row_bits, F, touched_rows, feat_roff, w.seg_feat);
+                       sb.seg_start, sb.list_off, row_bits, F, touched_rows, feat_roff, w.seg_feat);
     RECD_HIP(ctx, hipGetLastError());
     return RECD_OK;
 }
 
-// Segments of equal keys in the sorted pairs (ks, ps) of `set`, then the sum of every segment's rows.
-template <typename KeyT>
-recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, const KeyT *ks,
-                            const uint32_t *ps, int64_t n_cap, int64_t seg_bound, int row_bits, int F,
-                            const void *table, int D, void *out, int64_t *touched_rows,
-                            int64_t *feat_roff, const OptAdagrad *opt, const int64_t *div_off = nullptr,
-                            const float *pay_w = nullptr)
+// What the row-gradient kernels of step B need to know about its segments.
+RowSumParams row_params(const BwdWs &w, const uint32_t *ps, const float *pay_w, const void *table, int D, void *out)
 {
-    hipStream_t st = ctx->stream;
-    RECD_TRY(number_segments<KeyT>(ctx, w, set, ks, n_cap, row_bits, F, touched_rows, feat_roff));
+    RowSumParams rp;
+    rp.table = static_cast<const float *>(table);
+    rp.pay = ps;
+    rp.pay_w = pay_w;
+    rp.seg_start = w.seg_start_b;
+    rp.n_seg = w.list_off_b + 1;
+    rp.out = static_cast<float *>(out);
+    rp.D = D;
+    rp.pieces = D / 4;
+    rp.long_count = w.long_count;
+    rp.lseg_t = w.lseg_t;
+    rp.lseg_first = w.lseg_first;
+    rp.lseg_n = w.lseg_n;
+    rp.item_start = w.item_start;
+    rp.item_end = w.item_end;
+    rp.partials = w.partials;
+    return rp;
+}
+
+// Step B's segments need the sorted keys only, not the result of step A: numbered, and the long
+// ones cut into chunks, on the stream the sort ran on.
+template <typename KeyT>
+recd_status prepare_rows(recd_ctx *ctx, hipStream_t st, const BwdWs &w, const SortSet &set, const KeyT *ks,
+                         int64_t n_cap, int64_t seg_bound, int row_bits, int F, int64_t *touched_rows,
+                         int64_t *feat_roff)
+{
+    RECD_TRY(number_segments<KeyT>(ctx, st, w, set, ks, n_cap, row_bits, F, touched_rows, feat_roff));
+    const RowSumParams rp = row_params(w, nullptr, nullptr, nullptr, 4, nullptr);
+    int64_t fblk = (seg_bound + 255) / 256;
+    if (fblk > (int64_t)ctx->num_cu * 8)
+        fblk = (int64_t)ctx->num_cu * 8;
+    hipLaunchKernelGGL(k_find_long, dim3((unsigned)(fblk < 1 ? 1 : fblk)), dim3(256), 0, st, rp);
+    RECD_HIP(ctx, hipGetLastError());
+    return RECD_OK;
+}
+
+// Step A: segments of equal keys in the sorted pairs (ks, ps) of `set`, then the sum of every
+// segment's rows (the block-cooperative gather-sum kernel handles any segment length).
+recd_status segment_and_sum_lists(recd_ctx *ctx, const BwdWs &w, const SortSet &set, const uint32_t *ks,
+                                  const uint32_t *ps, int64_t n_cap, int64_t seg_bound, int F,
+                                  const void *table, int D, void *out, const int64_t *div_off)
+{
+    RECD_TRY(number_segments<uint32_t>(ctx, ctx->stream, w, set, ks, n_cap, -1, F, nullptr, nullptr));
     SegSumArgs a{};
     a.site = RECD_SITE_GRAD_LISTS;
     a.F = 1;
@@ -909,92 +962,83 @@ recd_status segment_and_sum(recd_ctx *ctx, const BwdWs &w, const SortSet &set, c
     a.flat = 1;
     a.out = out;
     a.div_off = div_off;
-    if (row_bits >= 0) {
-        // short segments: one lane group per segment; long ones are recorded and summed by the
-        // block-cooperative kernel right after
-        RowSumParams rp;
-        rp.table = static_cast<const float *>(table);
-        rp.pay = ps;
-        rp.pay_w = pay_w;
-        rp.seg_start = w.seg_start;
-        rp.n_seg = w.list_off + 1;
-        rp.out = static_cast<float *>(out);
-        rp.D = D;
-        rp.pieces = D / 4;
-        rp.long_count = w.long_count;
-        rp.lseg_t = w.lseg_t;
-        rp.lseg_first = w.lseg_first;
-        rp.lseg_n = w.lseg_n;
-        rp.item_start = w.item_start;
-        rp.item_end = w.item_end;
-        rp.partials = w.partials;
-        OptAdagrad o;
-        if (opt)
-            o = *opt;
-        else
-            o.n_feat = 0;
-        o.touched_rows = touched_rows;
-        o.seg_feat = w.seg_feat;
-        const int P = rp.pieces;
-        const int lpr = P <= 16 ? 4 : (P <= 32 ? 8 : (P <= 64 ? 16 : (P <= 128 ? 32 : 64)));
-        const int per_block = 4 * (64 / lpr);
-        int64_t nblk = (seg_bound + per_block - 1) / per_block;
-        const int64_t cap = (int64_t)ctx->num_cu * 64;
-        if (nblk > cap)
-            nblk = cap;
-        if (nblk < 1)
-            nblk = 1;
-        const dim3 block(256);
-        auto launch_rows = [&](auto fin, auto wt, unsigned nb, hipStream_t stream) {
-            constexpr bool FIN = decltype(fin)::value, WT = decltype(wt)::value;
-            const dim3 grid(nb);
-            switch (lpr) {
-            case 4: hipLaunchKernelGGL((k_segsum_rows<4, FIN, WT>), grid, block, 0, stream, rp, o); break;
-            case 8: hipLaunchKernelGGL((k_segsum_rows<8, FIN, WT>), grid, block, 0, stream, rp, o); break;
-            case 16: hipLaunchKernelGGL((k_segsum_rows<16, FIN, WT>), grid, block, 0, stream, rp, o); break;
-            case 32: hipLaunchKernelGGL((k_segsum_rows<32, FIN, WT>), grid, block, 0, stream, rp, o); break;
-            default: hipLaunchKernelGGL((k_segsum_rows<64, FIN, WT>), grid, block, 0, stream, rp, o); break;
-            }
-        };
-        // 1. long segments cut into chunks (a short pass over the segment starts)
-        int64_t fblk = (seg_bound + 255) / 256;
-        if (fblk > (int64_t)ctx->num_cu * 8)
-            fblk = (int64_t)ctx->num_cu * 8;
-        hipLaunchKernelGGL(k_find_long, dim3((unsigned)(fblk < 1 ? 1 : fblk)), dim3(256), 0, st, rp);
-        RECD_HIP(ctx, hipGetLastError());
-        // 2. on the side stream, next to 3: partial sum of every chunk (block-cooperative
-        //    gather-sum, one block per chunk), then the chunk partials added in chunk order and the
-        //    same update / store as for short segments.  Long and short segments name different rows.
-        hipStream_t side = ctx->side_stream;
-        RECD_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
-        RECD_HIP(ctx, hipStreamWaitEvent(side, ctx->ev_fork, 0));
-        SegSumArgs c = a;
-        c.offsets = w.item_start;
-        c.ends = w.item_end;
-        c.count_dev = w.long_count + 1;
-        c.list_off = nullptr;
-        c.lists_per_feature = 0;
-        c.lists_bound = n_cap / 256 + n_cap / 65 + 1;
-        c.out = w.partials;
-        c.stream = side;
-        if (pay_w) {  // the chunk partials carry the weights; adding the partials does not
-            c.mode = 3;
-            c.weights = pay_w;
-        }
-        RECD_TRY(recd_launch_segsum(ctx, c));
-        launch_rows(std::true_type(), std::false_type(), (unsigned)ctx->num_cu, side);
-        RECD_HIP(ctx, hipGetLastError());
-        RECD_HIP(ctx, hipEventRecord(ctx->ev_join, side));
-        // 3. short segments summed and updated
-        if (pay_w)
-            launch_rows(std::false_type(), std::true_type(), (unsigned)nblk, st);
-        else
-            launch_rows(std::false_type(), std::false_type(), (unsigned)nblk, st);
-        RECD_HIP(ctx, hipGetLastError());
-        RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
-        return RECD_OK;
-    }
     return recd_launch_segsum(ctx, a);
+}
+
+// Step B after prepare_rows: short segments (at most 64 entries) by one lane group each, the cut
+// ones by the block-cooperative kernel on the side stream next to them; optimizer fused.
+recd_status sum_rows(recd_ctx *ctx, const BwdWs &w, const uint32_t *ps, int64_t n_cap, int64_t seg_bound,
+                     const void *table, int D, void *out, int64_t *touched_rows, const OptAdagrad *opt,
+                     const float *pay_w)
+{
+    hipStream_t st = ctx->stream;
+    const RowSumParams rp = row_params(w, ps, pay_w, table, D, out);
+    OptAdagrad o;
+    if (opt)
+        o = *opt;
+    else
+        o.n_feat = 0;
+    o.touched_rows = touched_rows;
+    o.seg_feat = w.seg_feat;
+    const int P = rp.pieces;
+    const int lpr = P <= 16 ? 4 : (P <= 32 ? 8 : (P <= 64 ? 16 : (P <= 128 ? 32 : 64)));
+    const int per_block = 4 * (64 / lpr);
+    int64_t nblk = (seg_bound + per_block - 1) / per_block;
+    const int64_t cap = (int64_t)ctx->num_cu * 64;
+    if (nblk > cap)
+        nblk = cap;
+    if (nblk < 1)
+        nblk = 1;
+    const dim3 block(256);
+    auto launch_rows = [&](auto fin, auto wt, unsigned nb, hipStream_t stream) {
+        constexpr bool FIN = decltype(fin)::value, WT = decltype(wt)::value;
+        const dim3 grid(nb);
+        switch (lpr) {
+        case 4: hipLaunchKernelGGL((k_segsum_rows<4, FIN, WT>), grid, block, 0, stream, rp, o); break;
+        case 8: hipLaunchKernelGGL((k_segsum_rows<8, FIN, WT>), grid, block, 0, stream, rp, o); break;
+        case 16: hipLaunchKernelGGL((k_segsum_rows<16, FIN, WT>), grid, block, 0, stream, rp, o); break;
+        case 32: hipLaunchKernelGGL((k_segsum_rows<32, FIN, WT>), grid, block, 0, stream, rp, o); break;
+        default: hipLaunchKernelGGL((k_segsum_rows<64, FIN, WT>), grid, block, 0, stream, rp, o); break;
+        }
+    };
+    // 1. on the side stream: partial sum of every chunk of the cut segments (block-cooperative
+    //    gather-sum, one block per chunk), then the chunk partials added in chunk order and the same
+    //    update / store as for short segments.  Long and short segments name different rows.
+    hipStream_t side = ctx->side_stream;
+    RECD_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
+    RECD_HIP(ctx, hipStreamWaitEvent(side, ctx->ev_fork, 0));
+    SegSumArgs c{};
+    c.site = RECD_SITE_GRAD_LISTS;
+    c.F = 1;
+    c.D = D;
+    c.table_dt = RECD_F32;
+    c.out_dt = RECD_F32;
+    c.tables.p[0] = table;
+    c.values = ps;
+    c.values_are_i32 = 1;
+    c.flat = 1;
+    c.offsets = w.item_start;
+    c.ends = w.item_end;
+    c.count_dev = w.long_count + 1;
+    c.lists_bound = n_cap / 256 + n_cap / 65 + 1;
+    c.out = w.partials;
+    c.stream = side;
+    if (pay_w) {  // the chunk partials carry the weights; adding the partials does not
+        c.mode = 3;
+        c.weights = pay_w;
+    }
+    RECD_TRY(recd_launch_segsum(ctx, c));
+    launch_rows(std::true_type(), std::false_type(), (unsigned)ctx->num_cu, side);
+    RECD_HIP(ctx, hipGetLastError());
+    RECD_HIP(ctx, hipEventRecord(ctx->ev_join, side));
+    // 2. short segments summed and updated
+    if (pay_w)
+        launch_rows(std::false_type(), std::true_type(), (unsigned)nblk, st);
+    else
+        launch_rows(std::false_type(), std::false_type(), (unsigned)nblk, st);
+    RECD_HIP(ctx, hipGetLastError());
+    RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
+    return RECD_OK;
 }
 
 } // namespace
@@ -1125,6 +1169,13 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
                                w.pos_list, u_weights, w.b.n_dev, w.pay_w);
         }
         RECD_HIP(ctx, hipGetLastError());
+        // the segments of step B (row ids, per-feature counts, chunks of the long ones) as well
+        if (!wide)
+            RECD_TRY(prepare_rows<uint32_t>(ctx, side, w, w.b, static_cast<const uint32_t *>(ks_b), M_cap, M_cap,
+                                            row_bits, F, touched_rows, feat_roff));
+        else
+            RECD_TRY(prepare_rows<uint64_t>(ctx, side, w, w.b, static_cast<const uint64_t *>(ks_b), M_cap, M_cap,
+                                            row_bits, F, touched_rows, feat_roff));
         RECD_HIP(ctx, hipEventRecord(ctx->ev_join, side));
     }
     // ---- step A: group rows (f,b) by unique list, sum grad_out rows into g_u --------------------
@@ -1135,10 +1186,10 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
         RECD_TRY(radix_sort_pairs<uint32_t>(ctx, st, k0, w.a.p0, k1, w.a.p1, w.a.n_dev, n_lists, bits_a,
                                             w.a.hist, w.a.bsum, &ks, &ps));
         if (!seq) {
-            RECD_TRY(segment_and_sum<uint32_t>(ctx, w, w.a, ks, ps, n_lists, U_cap, -1, F, grad_out, D, w.g_u,
-                                               nullptr, nullptr, nullptr, mean ? u_offsets : nullptr));
+            RECD_TRY(segment_and_sum_lists(ctx, w, w.a, ks, ps, n_lists, U_cap, F, grad_out, D, w.g_u,
+                                           mean ? u_offsets : nullptr));
         } else {
-            RECD_TRY(number_segments<uint32_t>(ctx, w, w.a, ks, n_lists, -1, F, nullptr, nullptr));
+            RECD_TRY(number_segments<uint32_t>(ctx, st, w, w.a, ks, n_lists, -1, F, nullptr, nullptr));
             // lists per block: about 128 positions
             const double avg = (double)M_cap / (double)(U_cap > 0 ? U_cap : 1);
             int lists = 1;
@@ -1169,16 +1220,8 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
     const float *b_table = seq ? grad_emb : w.g_u;
     // ---- step B: group unique-id positions by (feature, row), sum g_u rows into grad_rows --------
     RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
-    if (!wide)
-        RECD_TRY(segment_and_sum<uint32_t>(ctx, w, w.b, static_cast<const uint32_t *>(ks_b), ps_b, M_cap,
-                                           M_cap, row_bits, F, b_table, D, grad_rows, touched_rows,
-                                           feat_roff, fused ? &oa : nullptr, nullptr,
-                                           u_weights ? w.pay_w : nullptr));
-    else
-        RECD_TRY(segment_and_sum<uint64_t>(ctx, w, w.b, static_cast<const uint64_t *>(ks_b), ps_b, M_cap,
-                                           M_cap, row_bits, F, b_table, D, grad_rows, touched_rows,
-                                           feat_roff, fused ? &oa : nullptr, nullptr,
-                                           u_weights ? w.pay_w : nullptr));
+    RECD_TRY(sum_rows(ctx, w, ps_b, M_cap, M_cap, b_table, D, grad_rows, touched_rows, fused ? &oa : nullptr,
+                      u_weights ? w.pay_w : nullptr));
     // ---- optimizer -------------------------------------------------------------------------------
     if (tables && !fused) {
         for (int f0 = 0; f0 < F; f0 += RECD_F_PER_LAUNCH) {
@@ -1194,7 +1237,7 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
         RECD_HIP(ctx, hipGetLastError());
     }
     if (host_R) {
-        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, w.list_off + 1, sizeof(int64_t),
+        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, w.list_off_b + 1, sizeof(int64_t),
                                      hipMemcpyDeviceToHost, st));
         RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned + 1, w.b.n_dev + 1, sizeof(int64_t),
                                      hipMemcpyDeviceToHost, st));
