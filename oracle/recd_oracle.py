@@ -7,13 +7,16 @@ here because they are one line each.
 from __future__ import annotations
 
 import ctypes as C
+import os
 from typing import List, Sequence, Tuple
 
 import numpy as np
 
 from . import build as _build
 
-_lib = C.CDLL(_build.build())
+# RECD_ORACLE_LIB: load this library instead (the mutation test of the pins points it at copies of
+# the oracle with a planted mistake, in a process of its own).
+_lib = C.CDLL(os.environ.get("RECD_ORACLE_LIB") or _build.build())
 
 _i64p = C.POINTER(C.c_int64)
 _i32p = C.POINTER(C.c_int32)
