@@ -50,6 +50,9 @@ def parse_args():
     ap.add_argument("--partial", type=float, default=0.0,
                     help="also time the partial IKJT path on the workload with this probability of a "
                          "sample's lists shifting by one id within a session (0 = skip)")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the step replayed from captured HIP graphs (launches sized by host upper "
+                         "bounds of U and M; reported beside `value`)")
     ap.add_argument("--weights", action="store_true",
                     help="also time the per-id-weight calls (weighted builder, lookups, backward) on the same "
                          "batches with seeded weights")
@@ -190,6 +193,52 @@ def pipelined_steps(torch, recd, P, args):
     return ms
 
 
+def graph_steps(torch, recd, P, args, stats):
+    """The same K steps replayed from HIP graphs, one graph per resident batch, captured on a stream
+    of their own.  Inside a graph nothing can come back to the host, so the later calls are sized by
+    host upper bounds (the largest U and M of the rotated batches) instead of the builder's counts;
+    the kernels read the true counts on the device.  Returns ms per step."""
+    w = P.w
+    F, B = w.F, w.B
+    nb = len(P.batches)
+    U_cap = int(max(st[0] for st in stats))
+    M_cap = int(max(st[1] for st in stats))
+    s3 = torch.cuda.Stream()
+    ctx3 = recd.Context(0, workspace_hint_bytes=recd.workspace_bytes(F, B, max(b.N for b in P.batches), w.D),
+                        stream=s3.cuda_stream)
+
+    def step(i):
+        ctx3.build_ikjt(F, B, P.values[i], P.offsets[i], P.u_values[i], P.u_offsets[i], P.inverse[i], P.feat_uoff[i])
+        ctx3.pooled_lookup_unique(P.tables, P.u_values[i], P.u_offsets[i], P.feat_uoff[i], U_cap, P.pooled)
+        ctx3.expand_inverse(F, B, P.pooled, P.feat_uoff[i], P.inverse[i], P.out)
+        if P.need_backward:
+            ctx3.backward_dedup(F, B, P.grad_out, P.inverse[i], P.feat_uoff[i], P.u_values[i], P.u_offsets[i],
+                                P.rows, U_cap, M_cap, P.touched, P.feat_roff, P.grad_rows, tables=P.tables,
+                                adagrad_state=P.state, lr=0.01, eps=1e-8)
+
+    graphs = []
+    with torch.cuda.stream(s3):
+        for i in range(nb):
+            step(i)                      # eager once: sizes the workspace before any capture
+        torch.cuda.synchronize()
+        for i in range(nb):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=s3):
+                step(i)
+            graphs.append(g)
+        for k in range(max(args.warmup, 2)):
+            graphs[k % nb].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(args.steps):
+            graphs[k % nb].replay()
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    del graphs
+    ctx3.close()
+    return ms
+
+
 def event_ms(torch, fn, reps):
     """Average HIP-event time of fn() on torch's current stream (the stream the library uses)."""
     s = [torch.cuda.Event(enable_timing=True) for _ in range(reps)]
@@ -229,6 +278,8 @@ def run_workload(torch, recd, synth, w, args, need_backward, detail=True, pipeli
     res = {"step_ms": step_ms, "B": B, "F": F, "D": D}
     if detail and pipeline and getattr(args, "pipeline", True):
         res["pipelined_step_ms"] = pipelined_steps(torch, recd, P, args)
+    if detail and getattr(args, "graph", False):
+        res["graph_step_ms"] = graph_steps(torch, recd, P, args, stats)
     N = float(np.mean([b.N for b in P.batches]))
     U = float(np.mean([s[0] for s in stats]))
     M = float(np.mean([s[1] for s in stats]))
@@ -719,6 +770,11 @@ def main():
         line["pipelined"] = {"ms_per_step": res["pipelined_step_ms"],
                              "value": w.B * w.F / (res["pipelined_step_ms"] * 1e-3), "unit": "pooled lookups/s",
                              "note": "same K steps, builder of the next batch on a second stream; not `value`"}
+    if "graph_step_ms" in res:
+        line["graph"] = {"ms_per_step": res["graph_step_ms"],
+                         "value": w.B * w.F / (res["graph_step_ms"] * 1e-3), "unit": "pooled lookups/s",
+                         "note": "same K steps replayed from captured HIP graphs, later calls sized by host upper "
+                                 "bounds of U and M; not `value`"}
     if args.cpu_features > 0:
         line["cpu_baseline"] = cpu_baseline(torch, synth, P, args.cpu_features)
         line["cpu_baseline_parallel"] = cpu_baseline_parallel(torch, P)
