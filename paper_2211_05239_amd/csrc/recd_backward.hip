@@ -1089,6 +1089,7 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
                          RECD_F_PER_LAUNCH);
     if ((tables == nullptr) != (adagrad_state == nullptr))
         return recd_fail(ctx, RECD_EINVAL, "tables and adagrad_state must be given together");
+    RECD_TRY(recd_check_rows(ctx, F, rows));
     int64_t max_rows = 1;
     for (int f = 0; f < F; f++) {
         if (rows[f] <= 0)

@@ -19,6 +19,16 @@ recd_status recd_fail(recd_ctx *ctx, recd_status s, const char *fmt, ...)
     return s;
 }
 
+recd_status recd_check_rows(recd_ctx *ctx, int F, const int64_t *rows)
+{
+    if (rows)
+        for (int f = 0; f < F; f++)
+            if (rows[f] < 0 || rows[f] > ((int64_t)1 << 31))
+                return recd_fail(ctx, RECD_EINVAL, "rows[%d]=%lld: tables hold at most 2^31 rows", f,
+                                 (long long)rows[f]);
+    return RECD_OK;
+}
+
 recd_status recd_reserve(recd_ctx *ctx, size_t bytes)
 {
     if (bytes <= ctx->ws_bytes)

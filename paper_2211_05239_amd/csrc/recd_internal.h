@@ -34,6 +34,8 @@ struct recd_ctx {
 };
 
 recd_status recd_fail(recd_ctx *ctx, recd_status s, const char *fmt, ...);
+// Ids must lie in [0, 2^31): a table the caller describes as larger is refused (rows may be null).
+recd_status recd_check_rows(recd_ctx *ctx, int F, const int64_t *rows);
 recd_status recd_reserve(recd_ctx *ctx, size_t bytes);
 
 #define RECD_HIP(ctx, call)                                                                   \

@@ -796,6 +796,7 @@ static recd_status lookup_unique(recd_ctx *ctx, int mode, int F, int D, recd_dty
                                  const float *weights = nullptr)
 {
     RECD_TRY(check_lookup_shape(ctx, F, D, table_dt, out_dt));
+    RECD_TRY(recd_check_rows(ctx, F, rows));
     if (mode < 0 || mode > 2)
         return recd_fail(ctx, RECD_EINVAL, "unknown pooling mode %d", mode);
     if (weights)
@@ -840,6 +841,7 @@ static recd_status lookup_kjt(recd_ctx *ctx, int mode, int F, int64_t B, int D, 
                               const float *weights = nullptr)
 {
     RECD_TRY(check_lookup_shape(ctx, F, D, table_dt, out_dt));
+    RECD_TRY(recd_check_rows(ctx, F, rows));
     if (mode < 0 || mode > 2)
         return recd_fail(ctx, RECD_EINVAL, "unknown pooling mode %d", mode);
     if (weights)
@@ -1029,6 +1031,7 @@ recd_status recd_pooled_lookup_partial(recd_ctx *ctx, int F, int D, recd_dtype t
                                        const int64_t *feat_uoff, int64_t max_lists, void *pooled)
 {
     RECD_TRY(check_lookup_shape(ctx, F, D, table_dt, out_dt));
+    RECD_TRY(recd_check_rows(ctx, F, rows));
     if (max_lists < 0 || P_cap < 0)
         return recd_fail(ctx, RECD_EINVAL, "max_lists or P_cap < 0");
     if (F == 0 || max_lists == 0)

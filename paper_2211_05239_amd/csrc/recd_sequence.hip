@@ -346,6 +346,7 @@ recd_status recd_sequence_lookup_unique(recd_ctx *ctx, int F, int D, recd_dtype 
                                         int64_t max_lists, int64_t M_cap, void *emb)
 {
     RECD_TRY(check_row_shape(ctx, F, D, table_dt, out_dt));
+    RECD_TRY(recd_check_rows(ctx, F, rows));
     if (max_lists < 0 || M_cap < 0)
         return recd_fail(ctx, RECD_EINVAL, "max_lists or M_cap < 0");
     if (F == 0 || M_cap == 0)
@@ -368,6 +369,7 @@ recd_status recd_kjt_sequence_lookup(recd_ctx *ctx, int F, int64_t B, int64_t N,
                                      const int64_t *values, const int64_t *offsets, void *out)
 {
     RECD_TRY(check_row_shape(ctx, F, D, table_dt, out_dt));
+    RECD_TRY(recd_check_rows(ctx, F, rows));
     if (B < 0 || N < 0)
         return recd_fail(ctx, RECD_EINVAL, "B or N < 0");
     if (F == 0 || B == 0 || N == 0)

@@ -283,6 +283,18 @@ def test_argument_errors(ctx, recd):
     del t16
 
 
+def test_table_size_limit(ctx, recd):
+    """Ids lie in [0, 2^31): a table described as larger is refused on the host."""
+    tabs = [torch.zeros(4, 8, device="cuda")]
+    one = torch.zeros(1, dtype=torch.int64, device="cuda")
+    offs = torch.tensor([0, 1], dtype=torch.int64, device="cuda")
+    out = torch.zeros(1, 8, device="cuda")
+    rows_arr = (recd.C.c_int64 * 1)((1 << 31) + 1)
+    st = recd._lib.recd_kjt_pooled_lookup(ctx._h, 1, 1, 8, 0, 0, ctx._table_array(tabs), rows_arr, one.data_ptr(),
+                                          offs.data_ptr(), out.data_ptr())
+    assert st == recd.RECD_EINVAL and b"2^31" in recd._lib.recd_last_error(ctx._h)
+
+
 def test_validation_reports_bad_inputs(ctx, recd):
     tab = [torch.zeros(10, 8, device="cuda")]
     out = torch.zeros(1, 2, 8, device="cuda")
