@@ -527,7 +527,11 @@ __device__ __forceinline__ void finish_segment(const RowSumParams &p, const OptA
                 x.y -= scale * acc[w].y;
                 x.z -= scale * acc[w].z;
                 x.w -= scale * acc[w].w;
-                reinterpret_cast<float4 *>(wrow)[w * LPR + r] = x;
+                {
+                    typedef float f32x4s __attribute__((ext_vector_type(4)));
+                    const f32x4s xo = {x.x, x.y, x.z, x.w};
+                    __builtin_nontemporal_store(xo, reinterpret_cast<f32x4s *>(wrow) + w * LPR + r);
+                }
             }
         if (r == 0)
             *mp = mnew;
@@ -622,7 +626,11 @@ __global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const
 #pragma unroll
             for (int w = 0; w < VPL; w++)
                 if (piece[w])
-                    wreg[w] = reinterpret_cast<const float4 *>(wrow)[w * LPR + r];
+                {
+                    typedef float f32x4l __attribute__((ext_vector_type(4)));
+                    const f32x4l t = __builtin_nontemporal_load(reinterpret_cast<const f32x4l *>(wrow) + w * LPR + r);
+                    wreg[w] = make_float4(t.x, t.y, t.z, t.w);
+                }
         }
         float4 acc[VPL];
 #pragma unroll
@@ -785,7 +793,12 @@ __global__ __launch_bounds__(256) void k_jagged_reduce(const float4 *__restrict_
                     for (int k = 0; k < kFly; k++) {
                         int64_t src = off_s[a][i + k < n ? i + k : n - 1] + t;
                         src = src < n_rows ? src : n_rows - 1;  // only a malformed IKJT gets here
-                        v[k] = grad_out[src * vecs + piece];
+                        {   // every gradient row is read once: a streaming load
+                            typedef float f32x4g __attribute__((ext_vector_type(4)));
+                            const f32x4g t4 = __builtin_nontemporal_load(
+                                reinterpret_cast<const f32x4g *>(grad_out) + src * vecs + piece);
+                            v[k] = make_float4(t4.x, t4.y, t4.z, t4.w);
+                        }
                     }
 #pragma unroll
                     for (int k = 0; k < kFly; k++)
@@ -948,7 +961,7 @@ recd_status segment_and_sum_lists(recd_ctx *ctx, const BwdWs &w, const SortSet &
 {
     RECD_TRY(number_segments<uint32_t>(ctx, ctx->stream, w, set, ks, n_cap, -1, F, nullptr, nullptr));
     SegSumArgs a{};
-    a.site = RECD_SITE_GRAD_LISTS;
+    a.site = RECD_SITE_GRAD_STREAM;  // every grad_out row is read exactly once
     a.F = 1;
     a.D = D;
     a.table_dt = RECD_F32;

@@ -87,7 +87,9 @@ struct OptAdagrad {
 
 // ---- cross-file entry points (host side launchers) -------------------------------------------
 // Exclusive scan of n int64 pairs is private to each file; the segmented gather-sum is shared.
-enum { RECD_SITE_UNIQUE = 0, RECD_SITE_KJT = 1, RECD_SITE_GRAD_LISTS = 2 };
+// GRAD_STREAM: as GRAD_LISTS, for source rows that are read once (step A reads every grad_out row
+// exactly once): their loads bypass the caches' retention.
+enum { RECD_SITE_UNIQUE = 0, RECD_SITE_KJT = 1, RECD_SITE_GRAD_LISTS = 2, RECD_SITE_GRAD_STREAM = 3 };
 struct SegSumArgs {
     int F;                    // features in this launch (<= RECD_F_PER_LAUNCH)
     int D;

@@ -134,7 +134,7 @@ template <int OT, int N, bool NT> __device__ __forceinline__ void store_row_piec
 
 // Call sites of the gather-sum kernel.  Each gets its own instantiation (and symbol): the unique
 // lookup, the KJT comparison lookup, and the backward's sums over grad_out rows / chunk partials.
-enum { SITE_UNIQUE = 0, SITE_KJT = 1, SITE_GRAD_LISTS = 2 };
+enum { SITE_UNIQUE = 0, SITE_KJT = 1, SITE_GRAD_LISTS = 2, SITE_GRAD_STREAM = 3 };
 
 struct SegSumParams {
     TablePtrs tables;
@@ -168,7 +168,7 @@ struct SegSumParams {
 // ns[] and starts[] are wave-uniform, so every "is this load slot used" test is a scalar branch and
 // unused slots cost nothing; only a chunk's last slot can hold lane groups beyond the end (they
 // fetch row 0, which exists, and are masked out of the add).  Ids are used modulo 2^32.
-template <int LPR, int VPL, int TT, typename IdxT, int NL, int US, int MODE = POOL_SUM>
+template <int LPR, int VPL, int TT, typename IdxT, int NL, int US, int MODE = POOL_SUM, bool NTL = false>
 __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL],
                                            const char *const *bases, const IdxT *values,
                                            const int64_t *starts, const int *ns, uint32_t row_bytes,
@@ -196,8 +196,15 @@ __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL]
                     const uint32_t id = __shfl(my_id[j], k0 + u * G + g);
                     const char *src = bases[j] + (uint64_t)id * row_bytes;
 #pragma unroll
-                    for (int w = 0; w < VPL; w++)
-                        v[j][u][w] = *reinterpret_cast<const uint4 *>(src + w * LPR * 16);
+                    for (int w = 0; w < VPL; w++) {
+                        if constexpr (NTL) {  // rows read once: streaming loads
+                            const u32x4 t = __builtin_nontemporal_load(
+                                reinterpret_cast<const u32x4 *>(src + w * LPR * 16));
+                            v[j][u][w] = make_uint4(t.x, t.y, t.z, t.w);
+                        } else {
+                            v[j][u][w] = *reinterpret_cast<const uint4 *>(src + w * LPR * 16);
+                        }
+                    }
                 }
             }
 #pragma unroll
@@ -310,7 +317,7 @@ void k_segsum(const SegSumParams p)
             for (int i = 0; i < NACC; i++)
                 vals[i] = len == 0 ? 0.f : (MODE == POOL_MEAN ? vals[i] / (float)len : vals[i]);
         }
-        if (SITE == SITE_GRAD_LISTS && p.div_off) {
+        if ((SITE == SITE_GRAD_LISTS || SITE == SITE_GRAD_STREAM) && p.div_off) {
             const int64_t n = p.div_off[s_list[j] + 1] - p.div_off[s_list[j]];
             if (n > 0) {
 #pragma unroll
@@ -365,8 +372,8 @@ void k_segsum(const SegSumParams p)
                     acc[0][i] = pool_identity<MODE>();
                 for (int64_t base = start + (int64_t)wv * kChunk; base < end; base += kWaves * kChunk) {
                     const int n = (int)(end - base < kChunk ? end - base : kChunk);
-                    add_chunks<LPR, VPL, TT, IdxT, 1, UNR, MODE>(acc, &table, values, &base, &n, row_bytes, lane, g,
-                                                                 p.weights);
+                    add_chunks<LPR, VPL, TT, IdxT, 1, UNR, MODE, SITE == SITE_GRAD_STREAM>(acc, &table, values, &base, &n,
+                                                                                           row_bytes, lane, g, p.weights);
                 }
                 fold_groups(acc[0]);
                 if (g == 0) {
@@ -412,7 +419,8 @@ void k_segsum(const SegSumParams p)
 #pragma unroll
             for (int i = 0; i < NACC; i++)
                 acc[0][i] = pool_identity<MODE>();
-            add_chunks<LPR, VPL, TT, IdxT, 1, UNR, MODE>(acc, &table, values, &start, &n, row_bytes, lane, g, p.weights);
+            add_chunks<LPR, VPL, TT, IdxT, 1, UNR, MODE, SITE == SITE_GRAD_STREAM>(acc, &table, values, &start, &n,
+                                                                                   row_bytes, lane, g, p.weights);
             fold_groups(acc[0]);
             finish_row(j, acc[0]);
         }
@@ -667,6 +675,9 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     else if (a.site == RECD_SITE_GRAD_LISTS && a.values_are_i32 && a.table_dt == RECD_F32 &&
              a.out_dt == RECD_F32 && a.mode == POOL_SUM)
         ok = launch_shape<RECD_F32, RECD_F32, int32_t, SITE_GRAD_LISTS>(st, blocks, v, p);
+    else if (a.site == RECD_SITE_GRAD_STREAM && a.values_are_i32 && a.table_dt == RECD_F32 &&
+             a.out_dt == RECD_F32 && a.mode == POOL_SUM)
+        ok = launch_shape<RECD_F32, RECD_F32, int32_t, SITE_GRAD_STREAM>(st, blocks, v, p);
     else if (a.site == RECD_SITE_GRAD_LISTS && a.values_are_i32 && a.table_dt == RECD_F32 &&
              a.out_dt == RECD_F32 && a.mode == POOL_WSUM && a.weights)
         ok = launch_shape<RECD_F32, RECD_F32, int32_t, SITE_GRAD_LISTS, POOL_WSUM>(st, blocks, v, p);
