@@ -4,7 +4,7 @@
 //   hash+insert  a group of SG lanes per list.  A list equal to its predecessor in the batch (the
 //                common case once a session's samples are adjacent, Sec. 4.1) is only marked as a
 //                follower.  Any other list is a run head: its 64-bit hash (position-salted sum of mixed
-//                ids, so lanes hash strided pieces and add) is inserted by open addressing into a
+//                ids, so lanes hash strided pairs of ids and add) is inserted by open addressing into a
 //                per-feature table whose slots hold (hash tag, sample index).  A slot belongs to one
 //                list *content*: a newcomer whose tag matches compares its list element by element
 //                with the slot's current sample and, if equal, lowers the slot's sample index with
@@ -34,6 +34,16 @@ __device__ __forceinline__ uint64_t mix64(uint64_t x)
     return x;
 }
 
+// One list element's share of the list hash: cheaper than mix64 (one 64-bit multiply; the
+// multiplies are most of the insert kernel's arithmetic), enough because the per-list sum of the
+// terms goes through mix64 once more and an exact comparison follows every tag match anyway.
+__device__ __forceinline__ uint64_t hash_term(uint64_t x)
+{
+    x ^= x >> 31;
+    x *= 0xbf58476d1ce4e5b9ull;
+    return x ^ (x >> 29);
+}
+
 __global__ void k_copy_i64(const int64_t *src, int64_t *dst) { *dst = *src; }
 
 __global__ void k_fill_u64(uint64_t *p, int64_t n, uint64_t v)
@@ -46,7 +56,10 @@ __global__ void k_fill_u64(uint64_t *p, int64_t n, uint64_t v)
 // Lists per lane group and launch: the group's lists are consecutive, and the first loads of all of
 // them are issued together so that one group keeps several memory requests in flight.
 constexpr int kLPG = 1;
-constexpr int kHU = 4;   // strides of the long-list loop whose loads are issued together
+constexpr int kHU = 2;   // strides of the long-list loop whose loads are issued together
+constexpr int kFirst = 3;  // strides of a list loaded up front
+// two adjacent ids; lists start on 8-byte boundaries only (global loads need no more)
+typedef long long id2 __attribute__((ext_vector_type(2), aligned(8)));
 
 // An id and (WT) the bit pattern of its weight as one hash input.
 template <bool WT>
@@ -93,42 +106,75 @@ __global__ __launch_bounds__(256) void k_hash_insert(const int64_t *__restrict__
         follows[k] = live[k] && (l % B) != 0 && (start[k] - pstart[k]) == len[k];
         h[k] = 0;
     }
-    // first SG ids of every list and of its predecessor: all loads in flight together
-    int64_t v[kLPG], pv[kLPG];
-    uint32_t wv[kLPG], pwv[kLPG];
-#pragma unroll
-    for (int k = 0; k < kLPG; k++) {
-        v[k] = s < len[k] ? values[start[k] + s] : 0;
-        pv[k] = (follows[k] && s < len[k]) ? values[pstart[k] + s] : 0;
-        wv[k] = (WT && s < len[k]) ? wbits[start[k] + s] : 0u;
-        pwv[k] = (WT && follows[k] && s < len[k]) ? wbits[pstart[k] + s] : 0u;
-    }
-#pragma unroll
-    for (int k = 0; k < kLPG; k++) {
-        if (s < len[k]) {
-            follows[k] &= pv[k] == v[k] && pwv[k] == wv[k];
-            h[k] = mix64(hash_item<WT>(v[k], wv[k]) + (uint64_t)(s + 1) * 0x9e3779b97f4a7c15ull);
+    // A lane takes two adjacent ids (and weights) per stride, one 16-byte load; a stride of the
+    // group covers 2 * SG ids.  The hash is a position-salted sum, so which lane adds which id does
+    // not matter.  The first kFirst strides of every list and of its predecessor are loaded up
+    // front, all in flight together; longer lists continue kHU strides per trip.
+    auto load2 = [&](const int64_t *base, int64_t t, int64_t n, bool on, int64_t &a, int64_t &b) {
+        a = 0;
+        b = 0;
+        if (on && t + 1 < n) {
+            const id2 p = *reinterpret_cast<const id2 *>(base + t);
+            a = p.x;
+            b = p.y;
+        } else if (on && t < n) {
+            a = base[t];
         }
-        // lists longer than the group: kHU strides per trip, all loads issued before use
-        for (int64_t t0 = s + SG; t0 < len[k]; t0 += kHU * SG) {
-            int64_t x[kHU], px[kHU];
-            uint32_t wx[kHU], pwx[kHU];
+    };
+    auto loadw2 = [&](const uint32_t *base, int64_t t, int64_t n, bool on, uint32_t &a, uint32_t &b) {
+        a = 0;
+        b = 0;
+        if (WT && on && t < n)
+            a = base[t];
+        if (WT && on && t + 1 < n)
+            b = base[t + 1];
+    };
+    auto fold2 = [&](int k, int64_t t, int64_t a, int64_t b, int64_t pa, int64_t pb, uint32_t wa, uint32_t wb,
+                     uint32_t pwa, uint32_t pwb) {
+        // position salt (t + 1) * phi from the low 32 bits of the position (one 32 x 64-bit product;
+        // it only has to be the same for equal lists)
+        const uint64_t salt = (uint64_t)(uint32_t)(t + 1) * 0x9e3779b97f4a7c15ull;
+        if (t < len[k]) {
+            follows[k] &= pa == a && pwa == wa;
+            h[k] += hash_term(hash_item<WT>(a, wa) + salt);
+        }
+        if (t + 1 < len[k]) {
+            follows[k] &= pb == b && pwb == wb;
+            h[k] += hash_term(hash_item<WT>(b, wb) + salt + 0x9e3779b97f4a7c15ull);
+        }
+    };
+    int64_t va[kLPG][kFirst], vb[kLPG][kFirst], pa[kLPG][kFirst], pb[kLPG][kFirst];
+    uint32_t wa[kLPG][kFirst], wb[kLPG][kFirst], pwa[kLPG][kFirst], pwb[kLPG][kFirst];
+#pragma unroll
+    for (int k = 0; k < kLPG; k++)
+#pragma unroll
+        for (int u = 0; u < kFirst; u++) {
+            const int64_t t = 2 * s + u * 2 * SG;
+            load2(values + start[k], t, len[k], true, va[k][u], vb[k][u]);
+            load2(values + pstart[k], t, len[k], follows[k], pa[k][u], pb[k][u]);
+            loadw2(wbits + start[k], t, len[k], true, wa[k][u], wb[k][u]);
+            loadw2(wbits + pstart[k], t, len[k], follows[k], pwa[k][u], pwb[k][u]);
+        }
+#pragma unroll
+    for (int k = 0; k < kLPG; k++) {
+#pragma unroll
+        for (int u = 0; u < kFirst; u++)
+            fold2(k, 2 * s + u * 2 * SG, va[k][u], vb[k][u], pa[k][u], pb[k][u], wa[k][u], wb[k][u], pwa[k][u],
+                  pwb[k][u]);
+        for (int64_t t0 = 2 * s + kFirst * 2 * SG; t0 < len[k]; t0 += kHU * 2 * SG) {
+            int64_t xa[kHU], xb[kHU], qa[kHU], qb[kHU];
+            uint32_t ya[kHU], yb[kHU], za[kHU], zb[kHU];
 #pragma unroll
             for (int u = 0; u < kHU; u++) {
-                const int64_t t = t0 + u * SG;
-                x[u] = t < len[k] ? values[start[k] + t] : 0;
-                px[u] = (follows[k] && t < len[k]) ? values[pstart[k] + t] : 0;
-                wx[u] = (WT && t < len[k]) ? wbits[start[k] + t] : 0u;
-                pwx[u] = (WT && follows[k] && t < len[k]) ? wbits[pstart[k] + t] : 0u;
+                const int64_t t = t0 + u * 2 * SG;
+                load2(values + start[k], t, len[k], true, xa[u], xb[u]);
+                load2(values + pstart[k], t, len[k], follows[k], qa[u], qb[u]);
+                loadw2(wbits + start[k], t, len[k], true, ya[u], yb[u]);
+                loadw2(wbits + pstart[k], t, len[k], follows[k], za[u], zb[u]);
             }
 #pragma unroll
-            for (int u = 0; u < kHU; u++) {
-                const int64_t t = t0 + u * SG;
-                if (t < len[k]) {
-                    follows[k] &= px[u] == x[u] && pwx[u] == wx[u];
-                    h[k] += mix64(hash_item<WT>(x[u], wx[u]) + (uint64_t)(t + 1) * 0x9e3779b97f4a7c15ull);
-                }
-            }
+            for (int u = 0; u < kHU; u++)
+                fold2(k, t0 + u * 2 * SG, xa[u], xb[u], qa[u], qb[u], ya[u], yb[u], za[u], zb[u]);
         }
     }
 #pragma unroll
