@@ -584,7 +584,7 @@ __global__ __launch_bounds__(256) void k_find_long(const RowSumParams p)
 template <int LPR, bool FINALIZE, bool WT = false>
 __global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const OptAdagrad opt)
 {
-    constexpr int G = 64 / LPR, VPL = 4, US = 2;
+    constexpr int G = 64 / LPR, VPL = 4, US = 1;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int g = lane / LPR, r = lane % LPR;
     const int64_t R = FINALIZE ? p.long_count[0] : *p.n_seg;
