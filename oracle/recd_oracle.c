@@ -740,6 +740,89 @@ int oracle_backward_kjt_weighted(int F, int64_t B, int D, const float *grad_out,
     return 0;
 }
 
+/* ---- backward of expand + MAX-pooled lookup (pooling modes: Sec. 2.2) ------------------------
+ * Forward: pooled[u,d] = max over the positions t of list u of W_f[id_t, d] (0 for an empty list).
+ * The gradient of element d flows to the position that holds the maximum; among equal values the
+ * first position of the list takes it (this build's reading; the paper does not say):
+ * step 1  as oracle_backward_dedup
+ * step 2  for every unique list u and element d: t* = first position with the largest
+ *         W_f[id_t, d];  G_f[id_t*, d] += g_u[u, d]           (u ascending)
+ * The tables are the fp32 tables of the forward pass.
+ */
+int oracle_backward_dedup_max(int F, int64_t B, int D, const float *grad_out, const int32_t *inverse,
+                              const int64_t *feat_uoff, const int64_t *u_values,
+                              const int64_t *u_offsets, const float *const *tables,
+                              int64_t *touched_rows, int64_t *feat_roff, double *grad_rows)
+{
+    int64_t U = feat_uoff[F];
+    double *g_u = (double *)calloc((size_t)(U > 0 ? U : 1) * D, sizeof(double));
+    if (!g_u)
+        return -9;
+    for (int f = 0; f < F; f++)
+        for (int64_t b = 0; b < B; b++) {
+            int64_t u = feat_uoff[f] + inverse[(int64_t)f * B + b];
+            for (int d = 0; d < D; d++)
+                g_u[u * D + d] += (double)grad_out[((int64_t)f * B + b) * D + d];
+        }
+    int64_t R = 0;
+    for (int f = 0; f < F; f++) {
+        feat_roff[f] = R;
+        int64_t j0 = u_offsets[feat_uoff[f]], j1 = u_offsets[feat_uoff[f + 1]];
+        int64_t r_f = sorted_distinct(u_values + j0, j1 - j0, touched_rows + R);
+        double *G = grad_rows + R * D;
+        for (int64_t i = 0; i < r_f * D; i++)
+            G[i] = 0.0;
+        for (int64_t u = feat_uoff[f]; u < feat_uoff[f + 1]; u++)
+            for (int d = 0; d < D; d++) {
+                int64_t best = -1;
+                for (int64_t j = u_offsets[u]; j < u_offsets[u + 1]; j++)
+                    if (best < 0 || tables[f][u_values[j] * D + d] > tables[f][u_values[best] * D + d])
+                        best = j;
+                if (best >= 0) {
+                    int64_t k = find_row(touched_rows + R, r_f, u_values[best]);
+                    G[k * D + d] += g_u[u * D + d];
+                }
+            }
+        R += r_f;
+    }
+    feat_roff[F] = R;
+    free(g_u);
+    return 0;
+}
+
+/* the same gradient straight from the KJT: row (f,b) hands grad_out[f,b,d] to the id at the first
+ * position of its own list with the largest table element d */
+int oracle_backward_kjt_max(int F, int64_t B, int D, const float *grad_out, const int64_t *values,
+                            const int64_t *offsets, const float *const *tables,
+                            int64_t *touched_rows, int64_t *feat_roff, double *grad_rows)
+{
+    int64_t R = 0;
+    for (int f = 0; f < F; f++) {
+        feat_roff[f] = R;
+        int64_t j0 = offsets[(int64_t)f * B], j1 = offsets[(int64_t)(f + 1) * B];
+        int64_t r_f = sorted_distinct(values + j0, j1 - j0, touched_rows + R);
+        double *G = grad_rows + R * D;
+        for (int64_t i = 0; i < r_f * D; i++)
+            G[i] = 0.0;
+        for (int64_t b = 0; b < B; b++) {
+            int64_t l = (int64_t)f * B + b;
+            for (int d = 0; d < D; d++) {
+                int64_t best = -1;
+                for (int64_t j = offsets[l]; j < offsets[l + 1]; j++)
+                    if (best < 0 || tables[f][values[j] * D + d] > tables[f][values[best] * D + d])
+                        best = j;
+                if (best >= 0) {
+                    int64_t k = find_row(touched_rows + R, r_f, values[best]);
+                    G[k * D + d] += (double)grad_out[l * D + d];
+                }
+            }
+        }
+        R += r_f;
+    }
+    feat_roff[F] = R;
+    return 0;
+}
+
 /* ---- backward of the jagged expand + unpooled lookup (chain rule of the two forward steps of
  * the sequence path; the paper describes the forward side only, Sec. 5) ---------------------------
  * grad_out holds one gradient row per KJT position (the layout of the expanded activations).

@@ -409,6 +409,51 @@ def backward_kjt_weighted(F: int, B: int, grad_out: np.ndarray, values, weights,
     return touched[:R].copy(), feat_roff, grad_rows[:R].copy()
 
 
+def _f32_table_ptrs(tables):
+    keep = [np.ascontiguousarray(t, dtype=np.float32) for t in tables]
+    return (C.c_void_p * len(keep))(*[t.ctypes.data for t in keep]), keep
+
+
+def backward_dedup_max(F: int, B: int, grad_out: np.ndarray, inverse, feat_uoff, u_values, u_offsets, tables):
+    """Backward of expand + max-pooled lookup (fp32 tables of the forward pass; the first position
+    wins a tie).  Returns (touched_rows, feat_roff, grad_rows float64)."""
+    grad_out = _f32(grad_out)
+    D = grad_out.shape[-1]
+    inverse = np.ascontiguousarray(inverse, dtype=np.int32)
+    feat_uoff, u_values, u_offsets = _i64(feat_uoff), _i64(u_values), _i64(u_offsets)
+    M = u_values.shape[0]
+    touched = np.zeros(max(M, 1), dtype=np.int64)
+    feat_roff = np.zeros(F + 1, dtype=np.int64)
+    grad_rows = np.zeros((max(M, 1), D), dtype=np.float64)
+    ptrs, keep = _f32_table_ptrs(tables)
+    rc = _lib.oracle_backward_dedup_max(C.c_int(F), C.c_int64(B), C.c_int(D), _p(grad_out, _f32p), _p(inverse, _i32p),
+                                        _p(feat_uoff, _i64p), _p(u_values, _i64p), _p(u_offsets, _i64p), ptrs,
+                                        _p(touched, _i64p), _p(feat_roff, _i64p), _p(grad_rows, _f64p))
+    _check(rc, "backward_dedup_max")
+    del keep
+    R = int(feat_roff[F])
+    return touched[:R].copy(), feat_roff, grad_rows[:R].copy()
+
+
+def backward_kjt_max(F: int, B: int, grad_out: np.ndarray, values, offsets, tables):
+    """The same gradient from the KJT alone."""
+    grad_out = _f32(grad_out)
+    D = grad_out.shape[-1]
+    values, offsets = _i64(values), _i64(offsets)
+    N = values.shape[0]
+    touched = np.zeros(max(N, 1), dtype=np.int64)
+    feat_roff = np.zeros(F + 1, dtype=np.int64)
+    grad_rows = np.zeros((max(N, 1), D), dtype=np.float64)
+    ptrs, keep = _f32_table_ptrs(tables)
+    rc = _lib.oracle_backward_kjt_max(C.c_int(F), C.c_int64(B), C.c_int(D), _p(grad_out, _f32p), _p(values, _i64p),
+                                      _p(offsets, _i64p), ptrs, _p(touched, _i64p), _p(feat_roff, _i64p),
+                                      _p(grad_rows, _f64p))
+    _check(rc, "backward_kjt_max")
+    del keep
+    R = int(feat_roff[F])
+    return touched[:R].copy(), feat_roff, grad_rows[:R].copy()
+
+
 def rowwise_adagrad(grad_rows, w_rows, m_rows, lr: float, eps: float) -> Tuple[np.ndarray, np.ndarray]:
     """Row-wise Adagrad on the touched rows: returns (w_new[R,D], m_new[R]) in float64."""
     grad_rows = np.ascontiguousarray(grad_rows, dtype=np.float64)

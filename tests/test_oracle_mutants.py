@@ -66,6 +66,10 @@ MUTANTS = [
     ("adagrad_sum_instead_of_mean", "double m = m_rows[r] + ss / (double)D;", "double m = m_rows[r] + ss;", 0),
     ("adagrad_eps_inside_root", "double denom = sqrt(m) + eps;", "double denom = sqrt(m + eps);", 0),
     ("adagrad_sign", "w_rows[r * D + d] - lr * grad_rows[r * D + d] / denom;", "w_rows[r * D + d] + lr * grad_rows[r * D + d] / denom;", 0),
+    ("max_backward_last_wins", "if (best < 0 || tables[f][u_values[j] * D + d] > tables[f][u_values[best] * D + d])",
+     "if (best < 0 || tables[f][u_values[j] * D + d] >= tables[f][u_values[best] * D + d])", 0),
+    ("max_backward_kjt_minimum", "if (best < 0 || tables[f][values[j] * D + d] > tables[f][values[best] * D + d])",
+     "if (best < 0 || tables[f][values[j] * D + d] < tables[f][values[best] * D + d])", 0),
     ("touched_rows_unsorted", "qsort(tmp, n, sizeof(int64_t), cmp_i64);\n    int64_t r = 0;",
      "int64_t r = 0;", 0),
 ]

@@ -679,6 +679,45 @@ def test_mean_backward_closed_form():
     np.testing.assert_allclose(gr[3], g[2])
 
 
+@pytest.mark.parametrize("seed", range(3))
+def test_max_backward_matches_autograd_and_kjt_form(seed):
+    """Max pooling (Sec. 2.2): the gradient of the IKJT path against the KJT form and against autograd
+    through embedding_bag(max) in fp64 on the same fp32 table values (random values: no ties between
+    different rows; a repeated id ties with itself and names the same row either way)."""
+    F, B, rows, D = 2, 27, 9, 4
+    batch, tabs = _rand_problem(280 + seed, F=F, B=B, rows=rows, D=D, max_len=5, alphabet=rows)
+    gout = np.random.default_rng(seed).standard_normal((F, B, D)).astype(np.float32)
+    uv, uo, inv, fu = orc.build_ikjt(F, B, batch.values, batch.offsets)
+    tr, fr, gr = orc.backward_dedup_max(F, B, gout, inv, fu, uv, uo, tabs)
+    tr2, fr2, gr2 = orc.backward_kjt_max(F, B, gout, batch.values, batch.offsets, tabs)
+    assert np.array_equal(tr, tr2) and np.array_equal(fr, fr2)
+    np.testing.assert_allclose(gr, gr2, rtol=1e-12, atol=1e-14)
+    G = _dense_grad(F, rows, D, tr, fr, gr)
+    for f in range(F):
+        W = torch.from_numpy(tabs[f]).double().requires_grad_(True)
+        lo, hi = batch.offsets[f * B], batch.offsets[(f + 1) * B]
+        out = torch.nn.functional.embedding_bag(
+            torch.from_numpy(batch.values[lo:hi]), W,
+            torch.from_numpy(batch.offsets[f * B:(f + 1) * B] - lo), mode="max")
+        (out * torch.from_numpy(gout[f]).double()).sum().backward()
+        np.testing.assert_allclose(G[f], W.grad.numpy(), rtol=1e-12, atol=1e-13)
+
+
+def test_max_backward_closed_form_and_ties():
+    # table rows: 0 -> (1, 9), 1 -> (5, 2), 2 -> (5, 7); lists [0,1,2], [2,1], [], [1]
+    tab = np.array([[1, 9], [5, 2], [5, 7]], dtype=np.float32)
+    batch = synth.batch_from_lists([[[0, 1, 2], [2, 1], [], [1]]])
+    g = np.array([[[1, 10], [2, 20], [4, 40], [8, 80]]], dtype=np.float32)
+    tr, fr, gr = orc.backward_kjt_max(1, 4, g, batch.values, batch.offsets, [tab])
+    assert tr.tolist() == [0, 1, 2]
+    # element 0: list [0,1,2] has 5 twice: the first position (row 1) takes it; list [2,1]: row 2 is first
+    # element 1: list [0,1,2] -> row 0 (9); list [2,1] -> row 2 (7); list [1] -> row 1
+    assert gr.tolist() == [[0, 10], [1 + 8, 80], [2, 20]]
+    uv, uo, inv, fu = orc.build_ikjt(1, 4, batch.values, batch.offsets)
+    tr2, _, gr2 = orc.backward_dedup_max(1, 4, g, inv, fu, uv, uo, [tab])
+    assert tr2.tolist() == tr.tolist() and gr2.tolist() == gr.tolist()
+
+
 def test_backward_finite_difference():
     F, B, rows, D = 1, 6, 5, 3
     batch = synth.batch_from_lists([[[0, 1], [0, 1], [4], [], [1, 1, 2], [0, 1]]])
