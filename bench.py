@@ -55,7 +55,7 @@ def parse_args():
                          "bounds of U and M; reported beside `value`)")
     ap.add_argument("--weights", action="store_true",
                     help="also time the per-id-weight calls (weighted builder, lookups, backward) on the same "
-                         "batches with seeded weights")
+                         "batches with seeded weights, and the backward of average and max pooling")
     ap.add_argument("--reader", action="store_true",
                     help="also report the builder alone (the conversion step of a reader) beside the CPU "
                          "oracle's builder run feature-parallel on the host cores")
@@ -398,8 +398,25 @@ def weighted_regions(torch, synth, P, timed, reps):
            "M": float(np.mean([c[1] for c in cnt]))}
     if P.need_backward:
         out["backward_weighted_ms"] = ms["backward"]
-    for i in range(nb):   # leave the plain IKJTs behind
-        P.build(i)
+    cnt_plain = [P.build(i) for i in range(nb)]   # leave the plain IKJTs behind
+    if P.need_backward:
+        # the backward of the other pooling functions on the plain IKJTs (same batches, fused update)
+        def bwd_mean(i):
+            P.ctx.backward_dedup(F, B, P.grad_out, P.inverse[i], P.feat_uoff[i], P.u_values[i], P.u_offsets[i],
+                                 P.rows, cnt_plain[i][0], cnt_plain[i][1], P.touched, P.feat_roff, P.grad_rows,
+                                 tables=P.tables, adagrad_state=P.state, lr=0.01, eps=1e-8, mode="mean")
+
+        def bwd_max(i):
+            P.ctx.backward_dedup_max(F, B, P.grad_out, P.inverse[i], P.feat_uoff[i], P.u_values[i], P.u_offsets[i],
+                                     P.rows, cnt_plain[i][0], cnt_plain[i][1], P.tables, P.touched, P.feat_roff,
+                                     P.grad_rows, tables=P.tables, adagrad_state=P.state, lr=0.01, eps=1e-8)
+
+        bwd_max(0)   # grows the workspace once, outside the timing
+        tm = {"backward_mean_ms": [], "backward_max_ms": []}
+        for _ in range(max(reps // 2, 2)):
+            tm["backward_mean_ms"].append(timed(bwd_mean))
+            tm["backward_max_ms"].append(timed(bwd_max))
+        out.update({k: float(np.mean(v)) for k, v in tm.items()})
     return out
 
 

@@ -17,6 +17,7 @@
  * another (Sec. 7): 12. partial builder   13. pooled lookup on the windows
  *   14. backward of the sequence path   15. backward of the averaged pooled lookup
  *   16-19. per-id weights: builder, unique and KJT lookups, backward
+ *   20. backward of the max-pooled lookup
  *
  * General rules
  *   - Every array argument marked "device" is a pointer into GPU memory owned by the caller and
@@ -339,8 +340,8 @@ recd_status recd_backward_sequence_dedup(recd_ctx *ctx, int F, int64_t B, int64_
  *    and max).  RECD_POOL_SUM is exactly call 5.  RECD_POOL_MEAN: the backward of the averaged
  *    lookup of call 11: every position of unique list u receives g_u[u,:] / len(u), i.e.
  *      G_f[r,:] = sum over positions j (ascending) with u_values[j] = r of g_u[list of j, :] / len
- *    (g_u is divided once, in fp32, when it is formed).  RECD_POOL_MAX needs the forward's
- *    arg-max and is not built: RECD_EINVAL.  All arguments as in call 5. */
+ *    (g_u is divided once, in fp32, when it is formed).  RECD_POOL_MAX needs the looked-up tables:
+ *    call 20; here it returns RECD_EINVAL.  All arguments as in call 5. */
 recd_status recd_backward_dedup_mode(recd_ctx *ctx, recd_pooling mode, int F, int64_t B, int D,
                                      const float *grad_out, const int32_t *inverse,
                                      const int64_t *feat_uoff, const int64_t *u_values,
@@ -398,6 +399,26 @@ recd_status recd_backward_dedup_weighted(recd_ctx *ctx, int F, int64_t B, int D,
                                          int64_t *touched_rows, int64_t *feat_roff, float *grad_rows,
                                          void *const *tables, float *const *adagrad_state, float lr,
                                          float eps, int64_t *host_R);
+
+/* 20. Call 5 for the max-pooled lookup of call 11 (Sec. 2.2 names max among the pooling functions):
+ *    element d of g_u[u,:] goes to the table row at the position of unique list u that holds the
+ *    largest table element d; among equal values the first position of the list takes it (this
+ *    build's reading):
+ *      G_f[r, d] = sum over the unique lists u (ascending) whose winning position for d holds id r
+ *                  of g_u[u, d]
+ *    lookup_tables: HOST array of F device pointers to the fp32 tables [rows_f, D] the forward pass
+ *    looked up (fp32 only); they are read before any update, so they may be the same as `tables`.
+ *    The call materialises one masked gradient row per position of u_values in the workspace
+ *    (M_cap * D * 4 bytes more than recd_workspace_bytes reports; the workspace grows on demand, which
+ *    synchronises and allocates).  All other arguments, and the guarantees, as in call 5. */
+recd_status recd_backward_dedup_max(recd_ctx *ctx, int F, int64_t B, int D, const float *grad_out,
+                                    const int32_t *inverse, const int64_t *feat_uoff,
+                                    const int64_t *u_values, const int64_t *u_offsets,
+                                    const int64_t *rows, int64_t U_cap, int64_t M_cap,
+                                    const void *const *lookup_tables, int64_t *touched_rows,
+                                    int64_t *feat_roff, float *grad_rows, void *const *tables,
+                                    float *const *adagrad_state, float lr, float eps,
+                                    int64_t *host_R);
 
 #ifdef __cplusplus
 }

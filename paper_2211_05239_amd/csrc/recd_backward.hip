@@ -676,6 +676,91 @@ __global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const
     }
 }
 
+// ---------------------------------------------------------------- max pooling: route g_u to the winners
+// Backward of the max-pooled lookup: element d of g_u[u] belongs to the position of list u that holds
+// the largest table element d (the first such position).  A group of LPR lanes owns a unique list
+// (lane r: pieces r, r + LPR, ... of the row, 16 bytes each): pass 1 walks the list's table rows and
+// keeps the running maximum and its position per element, pass 2 writes one row per position,
+// g_u[u] masked to the elements that position won, into emb[M, D].  The row-gradient segment sum
+// then adds those rows per table row exactly as it does for the sequence path.
+struct MaxTables {
+    const float *w[RECD_F_PER_LAUNCH];
+};
+
+template <int LPR>
+__global__ __launch_bounds__(256) void k_max_route(const int64_t *__restrict__ u_values,
+                                                   const int64_t *__restrict__ u_offsets,
+                                                   const int64_t *__restrict__ feat_uoff, int f0, int nf,
+                                                   MaxTables tabs, const float4 *__restrict__ g_u,
+                                                   float4 *__restrict__ emb, int pieces, int64_t lists_cap,
+                                                   int64_t m_cap)
+{
+    constexpr int G = 64 / LPR, VPL = 4;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int g = lane / LPR, r = lane % LPR;
+    const int per_block = (256 / 64) * G;
+    const int64_t u_lo = feat_uoff[f0];
+    int64_t u_hi = feat_uoff[f0 + nf];
+    u_hi = u_hi < lists_cap ? u_hi : lists_cap;
+    bool piece[VPL];
+#pragma unroll
+    for (int w = 0; w < VPL; w++)
+        piece[w] = w * LPR + r < pieces;
+    for (int64_t u = u_lo + (int64_t)blockIdx.x * per_block + wv * G + g; u < u_hi;
+         u += (int64_t)gridDim.x * per_block) {
+        int lo = 0, hi = nf;  // feature of u inside [f0, f0 + nf)
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (feat_uoff[f0 + mid] <= u)
+                lo = mid;
+            else
+                hi = mid;
+        }
+        const float4 *table = reinterpret_cast<const float4 *>(tabs.w[lo]);
+        const int64_t j0 = u_offsets[u];
+        int64_t j1 = u_offsets[u + 1];
+        j1 = j1 < m_cap ? j1 : m_cap;
+        float4 best[VPL];
+        int4 arg[VPL];
+#pragma unroll
+        for (int w = 0; w < VPL; w++) {
+            best[w] = make_float4(0.f, 0.f, 0.f, 0.f);
+            arg[w] = make_int4(0, 0, 0, 0);
+        }
+        for (int64_t j = j0; j < j1; j++) {
+            const int64_t id = u_values[j];
+            const int t = (int)(j - j0);
+#pragma unroll
+            for (int w = 0; w < VPL; w++)
+                if (piece[w]) {
+                    const float4 v = table[id * pieces + w * LPR + r];
+                    if (t == 0 || v.x > best[w].x) { best[w].x = v.x; arg[w].x = t; }
+                    if (t == 0 || v.y > best[w].y) { best[w].y = v.y; arg[w].y = t; }
+                    if (t == 0 || v.z > best[w].z) { best[w].z = v.z; arg[w].z = t; }
+                    if (t == 0 || v.w > best[w].w) { best[w].w = v.w; arg[w].w = t; }
+                }
+        }
+        float4 gu[VPL];
+#pragma unroll
+        for (int w = 0; w < VPL; w++)
+            if (piece[w])
+                gu[w] = g_u[u * pieces + w * LPR + r];
+        for (int64_t j = j0; j < j1; j++) {
+            const int t = (int)(j - j0);
+#pragma unroll
+            for (int w = 0; w < VPL; w++)
+                if (piece[w]) {
+                    float4 o;
+                    o.x = arg[w].x == t ? gu[w].x : 0.f;
+                    o.y = arg[w].y == t ? gu[w].y : 0.f;
+                    o.z = arg[w].z == t ? gu[w].z : 0.f;
+                    o.w = arg[w].w == t ? gu[w].w : 0.f;
+                    emb[j * pieces + w * LPR + r] = o;
+                }
+        }
+    }
+}
+
 __global__ void k_no_rows(int F, int64_t *feat_roff, int64_t *list_off)
 {
     for (int f = threadIdx.x; f <= F; f += blockDim.x)
@@ -832,6 +917,7 @@ struct BwdWs {
     float *g_u, *partials;
     uint32_t *pos_list;  // weighted lookup: unique list of every position of u_values
     float *pay_w;        // weighted lookup: weight of every sorted entry of step B
+    float *emb;          // max pooling: one masked gradient row per position of u_values [M, D]
     size_t bytes;
 };
 
@@ -856,7 +942,7 @@ SortSet carve_sort(WsCarver &c, int64_t n, bool wide_keys)
     return s;
 }
 
-BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D)
+BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D, bool with_emb = false)
 {
     WsCarver c(base);
     BwdWs w;
@@ -882,6 +968,7 @@ BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D)
     w.g_u = c.take<float>((size_t)u_cap * D);
     w.pos_list = c.take<uint32_t>(M_cap);
     w.pay_w = c.take<float>(M_cap);
+    w.emb = with_emb ? c.take<float>((size_t)M_cap * D) : nullptr;
     w.bytes = c.off;
     return w;
 }
@@ -1066,11 +1153,13 @@ size_t recd_backward_workspace(int F, int64_t B, int64_t M_cap, int D)
 // mean: the pooled path averaged, so g_u[u] is divided by the length of unique list u (every
 // segment of step A is one unique list, in order: each has at least one row).
 // u_weights: the pooled path's lookup was the weighted sum: position j hands u_weights[j] * g_u on.
+// max_tables: the pooled path's lookup was the maximum over these fp32 tables: element d of g_u
+// goes to the position that won it (k_max_route), then step B adds per-position rows.
 static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, int64_t B, int64_t N, int D,
                                    const float *grad_out, const int64_t *kjt_offsets,
                                    const int32_t *inverse, const int64_t *feat_uoff,
                                    const int64_t *u_values, const float *u_weights,
-                                   const int64_t *u_offsets,
+                                   const void *const *max_tables, const int64_t *u_offsets,
                                    const int64_t *rows, int64_t U_cap, int64_t M_cap, float *grad_emb,
                                    int64_t *touched_rows, int64_t *feat_roff, float *grad_rows,
                                    void *const *tables, float *const *adagrad_state, float lr,
@@ -1115,8 +1204,9 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
     RECD_HIP(ctx, hipSetDevice(ctx->device));
     if (ctx->validate && n_lists > 0)
         RECD_TRY(recd_validate_inverse(ctx, F, B, feat_uoff, inverse));
-    RECD_TRY(recd_reserve(ctx, recd_backward_workspace(F, B, M_cap, D)));
-    const BwdWs w = carve_bwd(ctx->ws, n_lists, M_cap, F, D);
+    const bool maxmode = max_tables != nullptr;
+    RECD_TRY(recd_reserve(ctx, carve_bwd(nullptr, n_lists, M_cap, F, D, maxmode).bytes));
+    const BwdWs w = carve_bwd(ctx->ws, n_lists, M_cap, F, D, maxmode);
     hipStream_t st = ctx->stream;
 
     if (n_lists == 0 || M_cap == 0) {
@@ -1162,7 +1252,7 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
             uint32_t *k0 = static_cast<uint32_t *>(w.b.k0), *k1 = static_cast<uint32_t *>(w.b.k1), *ks;
             hipLaunchKernelGGL((k_keys_ids<uint32_t, SG>), dim3(kb), dim3(256), 0, side, u_values,
                                u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev,
-                               (seq || u_weights) ? 1 : 0, u_weights ? w.pos_list : nullptr);
+                               (seq || u_weights || maxmode) ? 1 : 0, u_weights ? w.pos_list : nullptr);
             RECD_TRY(radix_sort_pairs<uint32_t>(ctx, side, k0, w.b.p0, k1, w.b.p1, w.b.n_dev, M_cap, bits_b,
                                                 w.b.hist, w.b.bsum, &ks, &ps_b));
             ks_b = ks;
@@ -1170,7 +1260,7 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
             uint64_t *k0 = static_cast<uint64_t *>(w.b.k0), *k1 = static_cast<uint64_t *>(w.b.k1), *ks;
             hipLaunchKernelGGL((k_keys_ids<uint64_t, SG>), dim3(kb), dim3(256), 0, side, u_values,
                                u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev,
-                               (seq || u_weights) ? 1 : 0, u_weights ? w.pos_list : nullptr);
+                               (seq || u_weights || maxmode) ? 1 : 0, u_weights ? w.pos_list : nullptr);
             RECD_TRY(radix_sort_pairs<uint64_t>(ctx, side, k0, w.b.p0, k1, w.b.p1, w.b.n_dev, M_cap, bits_b,
                                                 w.b.hist, w.b.bsum, &ks, &ps_b));
             ks_b = ks;
@@ -1231,7 +1321,35 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
             RECD_HIP(ctx, hipGetLastError());
         }
     }
-    const float *b_table = seq ? grad_emb : w.g_u;
+    if (maxmode) {
+        const int P = D / 4;
+        const int lpr = P <= 16 ? 4 : (P <= 32 ? 8 : (P <= 64 ? 16 : (P <= 128 ? 32 : 64)));
+        const int per_block = 4 * (64 / lpr);
+        for (int f0 = 0; f0 < F; f0 += RECD_F_PER_LAUNCH) {
+            MaxTables mt;
+            const int nf = F - f0 < RECD_F_PER_LAUNCH ? F - f0 : RECD_F_PER_LAUNCH;
+            for (int f = 0; f < nf; f++)
+                mt.w[f] = static_cast<const float *>(max_tables[f0 + f]);
+            int64_t nblk = (U_cap + per_block - 1) / per_block;
+            if (nblk > (int64_t)ctx->num_cu * 64)
+                nblk = (int64_t)ctx->num_cu * 64;
+            const dim3 grid((unsigned)(nblk < 1 ? 1 : nblk)), block(256);
+#define RECD_MR(L)                                                                                   \
+    hipLaunchKernelGGL((k_max_route<L>), grid, block, 0, st, u_values, u_offsets, feat_uoff, f0, nf, mt, \
+                       reinterpret_cast<const float4 *>(w.g_u), reinterpret_cast<float4 *>(w.emb), P, U_cap,  \
+                       M_cap)
+            switch (lpr) {
+            case 4: RECD_MR(4); break;
+            case 8: RECD_MR(8); break;
+            case 16: RECD_MR(16); break;
+            case 32: RECD_MR(32); break;
+            default: RECD_MR(64); break;
+            }
+#undef RECD_MR
+        }
+        RECD_HIP(ctx, hipGetLastError());
+    }
+    const float *b_table = seq ? grad_emb : (maxmode ? w.emb : w.g_u);
     // ---- step B: group unique-id positions by (feature, row), sum g_u rows into grad_rows --------
     RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
     RECD_TRY(sum_rows(ctx, w, ps_b, M_cap, M_cap, b_table, D, grad_rows, touched_rows, fused ? &oa : nullptr,
@@ -1273,7 +1391,7 @@ extern "C" recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int 
                                            int64_t *host_R)
 {
     return backward_common(ctx, false, false, F, B, 0, D, grad_out, nullptr, inverse, feat_uoff, u_values,
-                           nullptr, u_offsets, rows, U_cap, M_cap, nullptr, touched_rows, feat_roff, grad_rows, tables,
+                           nullptr, nullptr, u_offsets, rows, U_cap, M_cap, nullptr, touched_rows, feat_roff, grad_rows, tables,
                            adagrad_state, lr, eps, host_R);
 }
 
@@ -1292,7 +1410,7 @@ extern "C" recd_status recd_backward_dedup_mode(recd_ctx *ctx, recd_pooling mode
         return recd_fail(ctx, RECD_EINVAL,
                          "backward: pooling mode %d is not supported (sum and mean are)", (int)mode);
     return backward_common(ctx, false, mode == RECD_POOL_MEAN, F, B, 0, D, grad_out, nullptr, inverse,
-                           feat_uoff, u_values, nullptr, u_offsets, rows, U_cap, M_cap, nullptr, touched_rows,
+                           feat_uoff, u_values, nullptr, nullptr, u_offsets, rows, U_cap, M_cap, nullptr, touched_rows,
                            feat_roff, grad_rows, tables, adagrad_state, lr, eps, host_R);
 }
 
@@ -1307,7 +1425,7 @@ extern "C" recd_status recd_backward_sequence_dedup(recd_ctx *ctx, int F, int64_
                                                     float lr, float eps, int64_t *host_R)
 {
     return backward_common(ctx, true, false, F, B, N, D, grad_out, offsets, inverse, feat_uoff, u_values, nullptr,
-                           u_offsets, rows, U_cap, M_cap, grad_emb, touched_rows, feat_roff, grad_rows, tables,
+                           nullptr, u_offsets, rows, U_cap, M_cap, grad_emb, touched_rows, feat_roff, grad_rows, tables,
                            adagrad_state, lr, eps, host_R);
 }
 
@@ -1326,8 +1444,30 @@ extern "C" recd_status recd_backward_dedup_weighted(recd_ctx *ctx, int F, int64_
     if (M_cap > 0 && !u_weights)
         return recd_fail(ctx, RECD_EINVAL, "null u_weights");
     return backward_common(ctx, false, false, F, B, 0, D, grad_out, nullptr, inverse, feat_uoff, u_values,
-                           M_cap > 0 ? u_weights : nullptr, u_offsets, rows, U_cap, M_cap, nullptr,
+                           M_cap > 0 ? u_weights : nullptr, nullptr, u_offsets, rows, U_cap, M_cap, nullptr,
                            touched_rows, feat_roff, grad_rows, tables, adagrad_state, lr, eps, host_R);
+}
+
+extern "C" recd_status recd_backward_dedup_max(recd_ctx *ctx, int F, int64_t B, int D,
+                                               const float *grad_out, const int32_t *inverse,
+                                               const int64_t *feat_uoff, const int64_t *u_values,
+                                               const int64_t *u_offsets, const int64_t *rows,
+                                               int64_t U_cap, int64_t M_cap,
+                                               const void *const *lookup_tables, int64_t *touched_rows,
+                                               int64_t *feat_roff, float *grad_rows, void *const *tables,
+                                               float *const *adagrad_state, float lr, float eps,
+                                               int64_t *host_R)
+{
+    if (!ctx)
+        return RECD_EINVAL;
+    if (F > 0 && !lookup_tables)
+        return recd_fail(ctx, RECD_EINVAL, "null lookup_tables");
+    for (int f = 0; f < F; f++)
+        if (!lookup_tables[f])
+            return recd_fail(ctx, RECD_EINVAL, "lookup_tables[%d] is null", f);
+    return backward_common(ctx, false, false, F, B, 0, D, grad_out, nullptr, inverse, feat_uoff, u_values,
+                           nullptr, M_cap > 0 && F > 0 ? lookup_tables : nullptr, u_offsets, rows, U_cap, M_cap,
+                           nullptr, touched_rows, feat_roff, grad_rows, tables, adagrad_state, lr, eps, host_R);
 }
 
 size_t recd_build_workspace(int F, int64_t B);

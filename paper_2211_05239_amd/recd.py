@@ -37,7 +37,7 @@ EXPORTED = [
     "recd_group_sum_unique", "recd_pooled_lookup_unique_mode", "recd_kjt_pooled_lookup_mode",
     "recd_build_partial_ikjt", "recd_pooled_lookup_partial", "recd_backward_sequence_dedup",
     "recd_backward_dedup_mode", "recd_build_ikjt_weighted", "recd_pooled_lookup_unique_weighted",
-    "recd_kjt_pooled_lookup_weighted", "recd_backward_dedup_weighted",
+    "recd_kjt_pooled_lookup_weighted", "recd_backward_dedup_weighted", "recd_backward_dedup_max",
 ]
 
 _vp = C.c_void_p
@@ -67,6 +67,8 @@ _lib.recd_kjt_pooled_lookup_weighted.argtypes = [_vp, C.c_int, C.c_int64, C.c_in
 _lib.recd_backward_dedup_weighted.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, _vp, _vp, _vp, _vp, _vp, _vp, _vp,
                                               C.c_int64, C.c_int64, _vp, _vp, _vp, _vp, _vp, C.c_float,
                                               C.c_float, _vp]
+_lib.recd_backward_dedup_max.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, _vp, _vp, _vp, _vp, _vp, _vp, C.c_int64,
+                                         C.c_int64, _vp, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]
 _lib.recd_sequence_lookup_unique.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, _vp,
                                              _vp, C.c_int64, C.c_int64, _vp]
 _lib.recd_jagged_expand_inverse.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, _vp,
@@ -251,6 +253,21 @@ class Context:
             self._h, F, B, D, _ptr(grad_out), _ptr(inverse), _ptr(feat_uoff), _ptr(u_values), _ptr(u_weights),
             _ptr(u_offsets), rows_arr, U_cap, M_cap, _ptr(touched_rows), _ptr(feat_roff), _ptr(grad_rows),
             tabs, state, lr, eps, host))
+        return int(host[0]) if want_count else None
+
+    def backward_dedup_max(self, F: int, B: int, grad_out, inverse, feat_uoff, u_values, u_offsets,
+                           rows: Sequence[int], U_cap: int, M_cap: int, lookup_tables, touched_rows, feat_roff,
+                           grad_rows, tables=None, adagrad_state=None, lr: float = 0.0, eps: float = 0.0,
+                           want_count: bool = False):
+        D = grad_out.shape[-1]
+        rows_arr = (C.c_int64 * len(rows))(*rows)
+        tabs = self._table_array(tables) if tables is not None else None
+        state = self._table_array(adagrad_state) if adagrad_state is not None else None
+        host = (C.c_int64 * 1)(0) if want_count else None
+        self._check(_lib.recd_backward_dedup_max(
+            self._h, F, B, D, _ptr(grad_out), _ptr(inverse), _ptr(feat_uoff), _ptr(u_values), _ptr(u_offsets),
+            rows_arr, U_cap, M_cap, self._table_array(lookup_tables), _ptr(touched_rows), _ptr(feat_roff),
+            _ptr(grad_rows), tabs, state, lr, eps, host))
         return int(host[0]) if want_count else None
 
     # -- sequence (unpooled) features ---------------------------------------------------------

@@ -425,3 +425,29 @@ def test_cfg5_mean_backward_full(recd):
         assert np.array_equal(tr_f, tr[fr[f]:fr[f + 1]])
         gu.assert_close_f32(grad_rows[fr[f]:fr[f + 1]].double().cpu().numpy(), gr_f, f"mean grad rows {f}")
     ctx.close()
+
+
+def test_cfg5_max_backward_full(recd):
+    w = synth.WORKLOADS["cfg5"]
+    F, B, D = w.F, w.B, w.D
+    batch = synth.make_batch(w, 1)
+    tabs = _device_tables(w, torch.float32)
+    ctx = recd.Context(0)
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    g = torch.Generator(device="cuda")
+    g.manual_seed(103)
+    grad_out = torch.empty(F, B, D, dtype=torch.float32, device="cuda")
+    grad_out.normal_(0.0, 0.01, generator=g)
+    touched = torch.full((ik.M,), -1, dtype=torch.int64, device="cuda")
+    feat_roff = torch.zeros(F + 1, dtype=torch.int64, device="cuda")
+    grad_rows = torch.zeros(ik.M, D, device="cuda")
+    R = ctx.backward_dedup_max(F, B, grad_out, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F,
+                               ik.U, ik.M, tabs, touched, feat_roff, grad_rows, want_count=True)
+    fr = feat_roff.cpu().numpy()
+    tr = touched[:R].cpu().numpy()
+    for f in (7, 33):
+        v_f, o_f = _feature_slice(batch, f)
+        tr_f, _, gr_f = orc.backward_kjt_max(1, B, grad_out[f:f + 1].cpu().numpy(), v_f, o_f, [tabs[f].cpu().numpy()])
+        assert np.array_equal(tr_f, tr[fr[f]:fr[f + 1]])
+        gu.assert_close_f32(grad_rows[fr[f]:fr[f + 1]].double().cpu().numpy(), gr_f, f"max grad rows {f}")
+    ctx.close()

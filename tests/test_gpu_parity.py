@@ -448,6 +448,70 @@ def test_backward_mean_pooling(ctx, name, kw):
     _backward_case(ctx, synth.scaled(synth.WORKLOADS[name], **kw), 0, mode="mean")
 
 
+def _max_backward_case(ctx, w, batch, with_adagrad):
+    F, B, D = w.F, w.B, w.D
+    gout = synth.make_grad_out(w, 0)
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    M = max(ik.M, 1)
+    touched = torch.full((M,), -7, dtype=torch.int64, device="cuda")
+    feat_roff = torch.full((F + 1,), -7, dtype=torch.int64, device="cuda")
+    grad_rows = torch.full((M, D), float("nan"), device="cuda")
+    tabs = synth.make_tables(w)
+    d_tabs = gu.tables_to_dev(tabs, "f32")
+    d_state = [torch.zeros(w.rows, device="cuda") for _ in range(F)]
+    R = ctx.backward_dedup_max(F, B, gu.to_dev(gout), ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets,
+                               [w.rows] * F, ik.U, ik.M, d_tabs, touched, feat_roff, grad_rows,
+                               tables=d_tabs if with_adagrad else None,
+                               adagrad_state=d_state if with_adagrad else None, lr=0.01, eps=1e-8, want_count=True)
+    tr, fr, gr = orc.backward_kjt_max(F, B, gout, batch.values, batch.offsets, tabs)
+    assert R == len(tr) and np.array_equal(touched[:R].cpu().numpy(), tr)
+    assert np.array_equal(feat_roff.cpu().numpy(), fr)
+    gu.assert_close_f32(gu.out_to_f64(grad_rows[:R]), gr, "max-pooling grad_rows")
+    if with_adagrad:  # the arg-max was taken on the tables before the update
+        for f in range(F):
+            rows_f = tr[fr[f]:fr[f + 1]]
+            w_new, m_new = orc.rowwise_adagrad(gr[fr[f]:fr[f + 1]], tabs[f][rows_f].astype(np.float64),
+                                               np.zeros(len(rows_f)), 0.01, 1e-8)
+            gu.assert_close_f32(d_tabs[f].cpu().numpy()[rows_f].astype(np.float64), w_new, "adagrad rows")
+    return grad_rows[:R].clone()
+
+
+@pytest.mark.parametrize("name,kw", [("cfg1", dict(F=3, B=357, rows=900, D=32)),
+                                     ("cfg2", dict(F=4, B=1024, rows=20_000, D=64, len_max=150)),
+                                     ("cfg5", dict(F=3, B=2048, rows=30_000, D=128)),
+                                     ("cfg1", dict(F=2, B=200, rows=500, D=256)),
+                                     ("cfg1", dict(F=2, B=200, rows=500, D=4))])
+@pytest.mark.parametrize("with_adagrad", [False, True])
+def test_backward_max_pooling(ctx, name, kw, with_adagrad):
+    w = synth.scaled(synth.WORKLOADS[name], **kw)
+    _max_backward_case(ctx, w, synth.make_batch(w, 0), with_adagrad)
+
+
+def test_backward_max_pooling_ties_and_determinism(ctx):
+    """Tables with few distinct values: many exact ties between different rows; the first position of a
+    list wins, as in the oracle.  Two runs agree bit for bit."""
+    w = synth.scaled(synth.WORKLOADS["cfg2"], F=2, B=512, rows=300, D=16, len_max=40)
+    batch = synth.make_batch(w, 0)
+    F, B, D = w.F, w.B, w.D
+    rng = np.random.default_rng(9)
+    tabs = [rng.integers(-2, 3, size=(w.rows, D)).astype(np.float32) for _ in range(F)]
+    gout = synth.make_grad_out(w, 0)
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    d_tabs = gu.tables_to_dev(tabs, "f32")
+    outs = []
+    for _ in range(2):
+        touched = torch.zeros(ik.M, dtype=torch.int64, device="cuda")
+        feat_roff = torch.zeros(F + 1, dtype=torch.int64, device="cuda")
+        grad_rows = torch.zeros(ik.M, D, device="cuda")
+        R = ctx.backward_dedup_max(F, B, gu.to_dev(gout), ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets,
+                                   [w.rows] * F, ik.U, ik.M, d_tabs, touched, feat_roff, grad_rows, want_count=True)
+        outs.append(grad_rows[:R].clone())
+    tr, fr, gr = orc.backward_kjt_max(F, B, gout, batch.values, batch.offsets, tabs)
+    assert R == len(tr)
+    gu.assert_close_f32(gu.out_to_f64(outs[0]), gr, "grad_rows with ties")
+    assert torch.equal(outs[0], outs[1])
+
+
 def test_backward_mode_errors(ctx, recd):
     batch = synth.batch_from_lists([[[1], [2]]])
     values, offsets, ik = gu.gpu_build(ctx, batch)

@@ -151,6 +151,11 @@ def test_random_configuration(ctx, recd, seed):
         tr, fr, gr = orc.backward_kjt(F, B, gout, batch.values, batch.offsets, mode=bmode)
         assert R == len(tr) and np.array_equal(touched[:R].cpu().numpy(), tr)
         gu.assert_close_f32(gu.out_to_f64(grad_rows[:R]), gr, f"row gradients ({bmode})")
+        Rm = ctx.backward_dedup_max(F, B, gu.to_dev(gout), ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets,
+                                    [rows] * F, ik.U, ik.M, d_tabs, touched, feat_roff, grad_rows, want_count=True)
+        trm, frm, grm = orc.backward_kjt_max(F, B, gout, batch.values, batch.offsets, tabs)
+        assert Rm == len(trm) and np.array_equal(touched[:Rm].cpu().numpy(), trm)
+        gu.assert_close_f32(gu.out_to_f64(grad_rows[:Rm]), grm, "max-pooling row gradients")
         Rw = ctx.backward_dedup_weighted(F, B, gu.to_dev(gout), wik.inverse, wik.feat_uoff, wik.u_values, u_w,
                                          wik.u_offsets, [rows] * F, wik.U, wik.M, touched, feat_roff, grad_rows,
                                          want_count=True)
