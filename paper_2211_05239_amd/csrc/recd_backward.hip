@@ -679,15 +679,16 @@ __global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const
 // ---------------------------------------------------------------- max pooling: route g_u to the winners
 // Backward of the max-pooled lookup: element d of g_u[u] belongs to the position of list u that holds
 // the largest table element d (the first such position).  A group of LPR lanes owns a unique list
-// (lane r: pieces r, r + LPR, ... of the row, 16 bytes each): pass 1 walks the list's table rows and
-// keeps the running maximum and its position per element, pass 2 writes one row per position,
+// (lane r: pieces r, r + LPR, ... of the row, 16 bytes each; one piece per lane up to 1 KiB rows):
+// pass 1 walks the list's table rows, eight loads in flight per lane, and keeps the running
+// maximum and its position per element, pass 2 writes one row per position,
 // g_u[u] masked to the elements that position won, into emb[M, D].  The row-gradient segment sum
 // then adds those rows per table row exactly as it does for the sequence path.
 struct MaxTables {
     const float *w[RECD_F_PER_LAUNCH];
 };
 
-template <int LPR>
+template <int LPR, int VPL>
 __global__ __launch_bounds__(256) void k_max_route(const int64_t *__restrict__ u_values,
                                                    const int64_t *__restrict__ u_offsets,
                                                    const int64_t *__restrict__ feat_uoff, int f0, int nf,
@@ -695,7 +696,7 @@ __global__ __launch_bounds__(256) void k_max_route(const int64_t *__restrict__ u
                                                    float4 *__restrict__ emb, int pieces, int64_t lists_cap,
                                                    int64_t m_cap)
 {
-    constexpr int G = 64 / LPR, VPL = 4;
+    constexpr int G = 64 / LPR, US = 8 / VPL;  // US positions of a list in flight per lane
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int g = lane / LPR, r = lane % LPR;
     const int per_block = (256 / 64) * G;
@@ -727,19 +728,34 @@ __global__ __launch_bounds__(256) void k_max_route(const int64_t *__restrict__ u
             best[w] = make_float4(0.f, 0.f, 0.f, 0.f);
             arg[w] = make_int4(0, 0, 0, 0);
         }
-        for (int64_t j = j0; j < j1; j++) {
-            const int64_t id = u_values[j];
-            const int t = (int)(j - j0);
+        // pass 1: positions in ascending order, US rows in flight
+        for (int64_t jb = j0; jb < j1; jb += US) {
+            float4 v[US][VPL];
 #pragma unroll
-            for (int w = 0; w < VPL; w++)
-                if (piece[w]) {
-                    const float4 v = table[id * pieces + w * LPR + r];
-                    if (t == 0 || v.x > best[w].x) { best[w].x = v.x; arg[w].x = t; }
-                    if (t == 0 || v.y > best[w].y) { best[w].y = v.y; arg[w].y = t; }
-                    if (t == 0 || v.z > best[w].z) { best[w].z = v.z; arg[w].z = t; }
-                    if (t == 0 || v.w > best[w].w) { best[w].w = v.w; arg[w].w = t; }
+            for (int k = 0; k < US; k++) {
+                const int64_t j = jb + k < j1 ? jb + k : j1 - 1;
+                const int64_t id = u_values[j];
+#pragma unroll
+                for (int w = 0; w < VPL; w++)
+                    if (piece[w])
+                        v[k][w] = table[id * pieces + w * LPR + r];
+            }
+#pragma unroll
+            for (int k = 0; k < US; k++)
+                if (jb + k < j1) {
+                    const int t = (int)(jb + k - j0);
+#pragma unroll
+                    for (int w = 0; w < VPL; w++)
+                        if (piece[w]) {
+                            const float4 x = v[k][w];
+                            if (t == 0 || x.x > best[w].x) { best[w].x = x.x; arg[w].x = t; }
+                            if (t == 0 || x.y > best[w].y) { best[w].y = x.y; arg[w].y = t; }
+                            if (t == 0 || x.z > best[w].z) { best[w].z = x.z; arg[w].z = t; }
+                            if (t == 0 || x.w > best[w].w) { best[w].w = x.w; arg[w].w = t; }
+                        }
                 }
         }
+        // pass 2: one masked row per position
         float4 gu[VPL];
 #pragma unroll
         for (int w = 0; w < VPL; w++)
@@ -755,7 +771,11 @@ __global__ __launch_bounds__(256) void k_max_route(const int64_t *__restrict__ u
                     o.y = arg[w].y == t ? gu[w].y : 0.f;
                     o.z = arg[w].z == t ? gu[w].z : 0.f;
                     o.w = arg[w].w == t ? gu[w].w : 0.f;
-                    emb[j * pieces + w * LPR + r] = o;
+                    {   // written once, read back once by the row-gradient sum: a streaming store
+                        typedef float f32x4m __attribute__((ext_vector_type(4)));
+                        const f32x4m ov = {o.x, o.y, o.z, o.w};
+                        __builtin_nontemporal_store(ov, reinterpret_cast<f32x4m *>(emb) + j * pieces + w * LPR + r);
+                    }
                 }
         }
     }
@@ -1322,8 +1342,9 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
         }
     }
     if (maxmode) {
-        const int P = D / 4;
-        const int lpr = P <= 16 ? 4 : (P <= 32 ? 8 : (P <= 64 ? 16 : (P <= 128 ? 32 : 64)));
+        const int P = D / 4;  // 16-byte pieces of a row: up to 64 one per lane, else 128 or 256
+        const int lpr = P <= 4 ? 4 : (P <= 8 ? 8 : (P <= 16 ? 16 : (P <= 32 ? 32 : 64)));
+        const int vpl = P <= 64 ? 1 : (P == 128 ? 2 : 4);
         const int per_block = 4 * (64 / lpr);
         for (int f0 = 0; f0 < F; f0 += RECD_F_PER_LAUNCH) {
             MaxTables mt;
@@ -1334,17 +1355,17 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
             if (nblk > (int64_t)ctx->num_cu * 64)
                 nblk = (int64_t)ctx->num_cu * 64;
             const dim3 grid((unsigned)(nblk < 1 ? 1 : nblk)), block(256);
-#define RECD_MR(L)                                                                                   \
-    hipLaunchKernelGGL((k_max_route<L>), grid, block, 0, st, u_values, u_offsets, feat_uoff, f0, nf, mt, \
-                       reinterpret_cast<const float4 *>(w.g_u), reinterpret_cast<float4 *>(w.emb), P, U_cap,  \
+#define RECD_MR(L, V)                                                                                    \
+    hipLaunchKernelGGL((k_max_route<L, V>), grid, block, 0, st, u_values, u_offsets, feat_uoff, f0, nf, mt,  \
+                       reinterpret_cast<const float4 *>(w.g_u), reinterpret_cast<float4 *>(w.emb), P, U_cap, \
                        M_cap)
-            switch (lpr) {
-            case 4: RECD_MR(4); break;
-            case 8: RECD_MR(8); break;
-            case 16: RECD_MR(16); break;
-            case 32: RECD_MR(32); break;
-            default: RECD_MR(64); break;
-            }
+            if (vpl == 4) RECD_MR(64, 4);
+            else if (vpl == 2) RECD_MR(64, 2);
+            else if (lpr == 4) RECD_MR(4, 1);
+            else if (lpr == 8) RECD_MR(8, 1);
+            else if (lpr == 16) RECD_MR(16, 1);
+            else if (lpr == 32) RECD_MR(32, 1);
+            else RECD_MR(64, 1);
 #undef RECD_MR
         }
         RECD_HIP(ctx, hipGetLastError());
