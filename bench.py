@@ -314,6 +314,23 @@ def run_workload(torch, recd, synth, w, args, need_backward, detail=True, pipeli
         build_t.append(timed(lambda i: P.build(i, counts=False)))
         if need_backward:
             bwd_t.append(timed(lambda i: P.backward(i, cnt[i][0], cnt[i][1])))
+    if need_backward:
+        # Comparison path of the backward: the same call on the KJT taken as an IKJT in which every row
+        # is its own unique list (identity inverse): no deduplication, every id position sorted and summed.
+        ident_inv = torch.arange(B, dtype=torch.int32, device="cuda").repeat(F)
+        ident_uoff = torch.arange(F + 1, dtype=torch.int64, device="cuda") * B
+        Nmax = max(b.N for b in P.batches)
+        touched_kjt = torch.zeros(Nmax, dtype=torch.int64, device="cuda")
+
+        def kjt_backward(i):
+            P.ctx.backward_dedup(F, B, P.grad_out, ident_inv, ident_uoff, P.values[i], P.offsets[i], P.rows,
+                                 F * B, P.batches[i].N, touched_kjt, P.feat_roff, None, tables=P.tables,
+                                 adagrad_state=P.state, lr=0.01, eps=1e-8)
+
+        kjt_backward(0)   # grows the workspace once, outside the timing
+        kjt_bwd_t = [timed(kjt_backward) for _ in range(max(reps // 3, 2))]
+        res["kjt_backward_ms"] = float(np.mean(kjt_bwd_t))
+        del touched_kjt, ident_inv
     build_ms = float(np.mean(build_t))
     lookup_ms, expand_ms, kjt_ms = (float(np.mean(x)) for x in (lookup_t, expand_t, kjt_t))
     res.update({"build_ms": build_ms, "lookup_unique_ms": lookup_ms, "expand_ms": expand_ms,
@@ -343,6 +360,8 @@ def run_workload(torch, recd, synth, w, args, need_backward, detail=True, pipeli
     if R is not None:
         res["gbs"]["lookup_unique_compulsory"] = res["bytes"]["lookup_unique_compulsory"] / lookup_ms / 1e6
         res["gbs"]["kjt_compulsory"] = res["bytes"]["kjt_compulsory"] / kjt_ms / 1e6
+    if need_backward:
+        res["backward_speedup_vs_kjt"] = res["kjt_backward_ms"] / res["backward_ms"]
     res["speedup_vs_kjt"] = kjt_ms / (lookup_ms + expand_ms)
     res["speedup_vs_kjt_with_build"] = kjt_ms / (build_ms + lookup_ms + expand_ms)
     res["predicted_speedup_bytes_model"] = kjt_upper / (look_upper + F * B * 4 + 2 * F * B * D * o)
