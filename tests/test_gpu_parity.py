@@ -512,6 +512,15 @@ def test_backward_max_pooling_ties_and_determinism(ctx):
     assert torch.equal(outs[0], outs[1])
 
 
+def test_backward_many_features(ctx):
+    """More features than one launch carries: the optimizer runs as a kernel of its own, the max
+    routing in groups of features."""
+    w = synth.scaled(synth.WORKLOADS["cfg1"], F=131, B=67, rows=500, D=16)
+    _backward_case(ctx, w, 0)
+    _backward_case(ctx, w, 0, mode="mean")
+    _max_backward_case(ctx, w, synth.make_batch(w, 0), True)
+
+
 def test_backward_mode_errors(ctx, recd):
     batch = synth.batch_from_lists([[[1], [2]]])
     values, offsets, ik = gu.gpu_build(ctx, batch)

@@ -181,6 +181,14 @@ def test_weighted_backward(ctx, name, kw):
     _backward_case(ctx, w, batch, synth.make_weights(batch, 2, perturb=0.1))
 
 
+def test_weighted_many_features(ctx):
+    w = synth.scaled(synth.WORKLOADS["cfg1"], F=131, B=67, rows=500, D=16)
+    batch = synth.make_batch(w, 0)
+    weights = synth.make_weights(batch, 5, perturb=0.2)
+    _forward_case(ctx, w, batch, weights)
+    _backward_case(ctx, w, batch, weights)
+
+
 def test_weighted_backward_giant_segment_and_determinism(ctx):
     B = 20000
     batch = synth.batch_from_lists([[[7, 100 + i] for i in range(B)]])
