@@ -23,7 +23,7 @@ constexpr int kSortThreads = 256;
 constexpr int kIPT = 8;                       // keys per thread in a tile
 constexpr int kTile = kSortThreads * kIPT;    // keys per tile
 constexpr int kRadixMax = 512;                // digits of up to 9 bits
-constexpr int kScanItems = 16;                // items per thread in the generic scan
+constexpr int kScanItems = 4;                 // items per thread in the generic scan
 constexpr int kScanTile = 256 * kScanItems;
 
 // ---------------------------------------------------------------- block-wide exclusive scan (uint32)
