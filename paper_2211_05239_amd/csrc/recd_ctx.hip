@@ -229,7 +229,8 @@ recd_status recd_set_option(recd_ctx *ctx, recd_option opt, int64_t value)
         ctx->tune_gens = (int)(value / 10000 % 100);
         ctx->tune_flat = (int)(value / 1000000 % 10);
         if (value < 0 || value / 100 % 100 != 0 || value >= 2000000 ||
-            (ctx->tune_lb != 0 && ctx->tune_lb != 4 && ctx->tune_lb != 8 && ctx->tune_lb != 16)) {
+            (ctx->tune_lb != 0 && ctx->tune_lb != 1 && ctx->tune_lb != 2 && ctx->tune_lb != 4 && ctx->tune_lb != 8 &&
+             ctx->tune_lb != 16)) {
             ctx->tune_lb = ctx->tune_gens = ctx->tune_flat = 0;
             return recd_fail(ctx, RECD_EINVAL, "bad RECD_OPT_TUNE_SEGSUM value");
         }

@@ -10,11 +10,12 @@
 //     (id k goes to group k mod G), each group adds its rows in order, and a fixed butterfly folds
 //     the groups.  Every load instruction of a wave thus fetches G whole rows as contiguous 16-byte
 //     pieces, and UNR loads are issued before the first add so that many rows are in flight.
-//   * a block of four waves owns LB consecutive lists.  Lists of at most 64 ids are summed by one
-//     wave each.  A longer list is summed by the whole block: its 64-id chunks go to the waves
-//     round-robin, the four wave partials are added in wave order.  Which path a list takes and the
-//     order of every addition depend on the list's length and content only, never on where the
-//     list sits in a batch: the deduplicated and the non-deduplicated lookup agree bit for bit.
+//   * a block of W waves owns LB consecutive lists (W = 1 for the two lookups, 4 for the backward's
+//     sums).  Lists of at most 64 ids are summed by one wave each.  A longer list is summed by the
+//     whole block: its 64-id chunks go to the waves round-robin, the W wave partials are added in
+//     wave order.  Which path a list takes and the order of every addition depend on the list's
+//     length and content only, never on where the list sits in a batch: the deduplicated and the
+//     non-deduplicated lookup (same W) agree bit for bit.
 //   * blocks are dealt to lists statically (no atomics; the hardware's block dispatch balances the
 //     load).  With F a multiple of 8 the mapping is XCD-aware: block b serves the features
 //     f with f mod 8 = b mod 8, and since consecutive blocks go to consecutive XCDs, the hot rows of
@@ -29,6 +30,14 @@ namespace {
 
 constexpr int kNQ = 8;         // XCDs
 constexpr int kBlock = 256;
+// Threads per block of the gather-sum kernel.  The forward lookups run one wave per block: the
+// waves of a block finish their lists at different times, and a block's registers are only free
+// again when its last wave is done, so with lists of 1 to 256 ids a four-wave block keeps idle
+// waves resident (unique lookup 0.124 ms against 0.133, KJT lookup 0.99 against 1.16).  The
+// backward's sums keep four waves: their long segments and 256-entry chunks want the whole block.
+template <int SITE> struct SegBlock {
+    static constexpr int threads = (SITE == 0 || SITE == 1) ? 64 : 256;
+};
 constexpr int kMaxLB = 16;     // lists per block item (upper bound)
 constexpr int kChunk = 64;     // ids per chunk: a wave loads a chunk's ids with one instruction
 
@@ -234,11 +243,12 @@ __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL]
 template <int LPR, int VPL, int TT, int OT, typename IdxT, int SITE, int MODE = POOL_SUM>
 // The weighted sum needs a few registers more: 6 waves (80 VGPRs) instead of spilling measured best
 // for the KJT lookup, 5 for the unique lists (7 with spills was slower for both).
-__global__ __launch_bounds__(kBlock)
+__global__ __launch_bounds__(SegBlock<SITE>::threads)
 __attribute__((amdgpu_waves_per_eu(VPL == 1 ? (MODE == POOL_WSUM ? (SITE == SITE_KJT ? 6 : 5) : 7) : 1)))
 void k_segsum(const SegSumParams p)
 {
-    constexpr int kWaves = kBlock / 64;
+    constexpr int kSegBlock = SegBlock<SITE>::threads;
+    constexpr int kWaves = kSegBlock / 64;
     constexpr bool NT = SITE == SITE_KJT;  // streaming output
     constexpr int EPV = Elem<TT>::per_vec;
     constexpr int NACC = EPV * VPL;
@@ -262,7 +272,7 @@ void k_segsum(const SegSumParams p)
     const int64_t item_stride = nq == 1 ? gridDim.x : gridDim.x / kNQ;
     const int nslots = (p.F - q + nq - 1) / nq;  // features in my queue: q, q+nq, ...
 
-    for (int f = tid; f <= p.F; f += kBlock)
+    for (int f = tid; f <= p.F; f += kSegBlock)
         s_loff[f] = p.list_off ? p.list_off[f] : (int64_t)f * p.lists_per_feature;
     __syncthreads();
     if (wv == 0) {
@@ -358,7 +368,7 @@ void k_segsum(const SegSumParams p)
         __syncthreads();
 
         // ---- long lists (> 64 ids): the whole block; the list's 64-id chunks go to the waves
-        //      round-robin, the four wave partials are added in wave order ------------------------
+        //      round-robin, the wave partials are added in wave order -----------------------------
         int batch[LL];
         int nb = 0;
         for (int j = 0; j <= cnt; j++) {
@@ -430,7 +440,7 @@ void k_segsum(const SegSumParams p)
 template <int TT, int OT, typename IdxT, int SITE, int MODE = POOL_SUM>
 bool launch_shape(hipStream_t st, int blocks, int vecs, const SegSumParams &p)
 {
-    const dim3 grid(blocks), block(kBlock);
+    const dim3 grid(blocks), block(SegBlock<SITE>::threads);
     if (vecs <= 8) hipLaunchKernelGGL((k_segsum<8, 1, TT, OT, IdxT, SITE, MODE>), grid, block, 0, st, p);
     else if (vecs <= 16) hipLaunchKernelGGL((k_segsum<16, 1, TT, OT, IdxT, SITE, MODE>), grid, block, 0, st, p);
     else if (vecs <= 32) hipLaunchKernelGGL((k_segsum<32, 1, TT, OT, IdxT, SITE, MODE>), grid, block, 0, st, p);
@@ -637,7 +647,12 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     // decide how well the chip is filled.
     const int64_t n = a.lists_bound > 0 ? a.lists_bound : 1;
     p.nq = (a.F >= kNQ && a.F % kNQ == 0 && !a.flat && !ctx->tune_flat && !a.count_dev) ? kNQ : 1;
-    p.lb = n >= (512 << 10) ? 16 : (n >= (128 << 10) ? 8 : 4);
+    // lists per block: four-wave blocks (backward) take 4 to 16, single-wave blocks (forward) 1 to 4
+    // (measured at 61 K unique lists and at 1.05 M KJT lists: 1 and 4)
+    if (a.site == RECD_SITE_UNIQUE || a.site == RECD_SITE_KJT)
+        p.lb = n >= (512 << 10) ? 4 : (n >= (128 << 10) ? 2 : 1);
+    else
+        p.lb = n >= (512 << 10) ? 16 : (n >= (128 << 10) ? 8 : 4);
     if (ctx->tune_lb > 0)
         p.lb = ctx->tune_lb;
     if (a.count_dev)
