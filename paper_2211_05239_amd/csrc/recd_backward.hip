@@ -1259,49 +1259,11 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
     const int bits_a = bits_for((uint64_t)(U_cap > 1 ? U_cap - 1 : 1));
     const bool wide = bits_b > 32;
 
-    // ---- the sort of step B needs nothing from step A: it runs on the side stream meanwhile ------
+    // The sort of step B needs nothing from step A: it runs on the side stream meanwhile, forked from
+    // the point before step A.  Step A's launches are issued first: its chain is the longer one, and
+    // while the host issues the side stream's fifteen short launches the main stream would idle.
     hipStream_t side = ctx->side_stream;
     RECD_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
-    RECD_HIP(ctx, hipStreamWaitEvent(side, ctx->ev_fork, 0));
-    void *ks_b = nullptr;
-    uint32_t *ps_b = nullptr;
-    {
-        constexpr int SG = 16;
-        const unsigned kb = (unsigned)((n_lists + (256 / SG) - 1) / (256 / SG));
-        if (!wide) {
-            uint32_t *k0 = static_cast<uint32_t *>(w.b.k0), *k1 = static_cast<uint32_t *>(w.b.k1), *ks;
-            hipLaunchKernelGGL((k_keys_ids<uint32_t, SG>), dim3(kb), dim3(256), 0, side, u_values,
-                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev,
-                               (seq || u_weights || maxmode) ? 1 : 0, u_weights ? w.pos_list : nullptr);
-            RECD_TRY(radix_sort_pairs<uint32_t>(ctx, side, k0, w.b.p0, k1, w.b.p1, w.b.n_dev, M_cap, bits_b,
-                                                w.b.hist, w.b.bsum, &ks, &ps_b));
-            ks_b = ks;
-        } else {
-            uint64_t *k0 = static_cast<uint64_t *>(w.b.k0), *k1 = static_cast<uint64_t *>(w.b.k1), *ks;
-            hipLaunchKernelGGL((k_keys_ids<uint64_t, SG>), dim3(kb), dim3(256), 0, side, u_values,
-                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev,
-                               (seq || u_weights || maxmode) ? 1 : 0, u_weights ? w.pos_list : nullptr);
-            RECD_TRY(radix_sort_pairs<uint64_t>(ctx, side, k0, w.b.p0, k1, w.b.p1, w.b.n_dev, M_cap, bits_b,
-                                                w.b.hist, w.b.bsum, &ks, &ps_b));
-            ks_b = ks;
-        }
-        if (u_weights) {
-            int64_t wb = (M_cap + 255) / 256;
-            if (wb > (int64_t)ctx->num_cu * 16)
-                wb = (int64_t)ctx->num_cu * 16;
-            hipLaunchKernelGGL(k_weight_payload, dim3((unsigned)(wb < 1 ? 1 : wb)), dim3(256), 0, side, ps_b,
-                               w.pos_list, u_weights, w.b.n_dev, w.pay_w);
-        }
-        RECD_HIP(ctx, hipGetLastError());
-        // the segments of step B (row ids, per-feature counts, chunks of the long ones) as well
-        if (!wide)
-            RECD_TRY(prepare_rows<uint32_t>(ctx, side, w, w.b, static_cast<const uint32_t *>(ks_b), M_cap, M_cap,
-                                            row_bits, F, touched_rows, feat_roff));
-        else
-            RECD_TRY(prepare_rows<uint64_t>(ctx, side, w, w.b, static_cast<const uint64_t *>(ks_b), M_cap, M_cap,
-                                            row_bits, F, touched_rows, feat_roff));
-        RECD_HIP(ctx, hipEventRecord(ctx->ev_join, side));
-    }
     // ---- step A: group rows (f,b) by unique list, sum grad_out rows into g_u --------------------
     {
         uint32_t *k0 = static_cast<uint32_t *>(w.a.k0), *k1 = static_cast<uint32_t *>(w.a.k1), *ks, *ps;
@@ -1369,6 +1331,47 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
 #undef RECD_MR
         }
         RECD_HIP(ctx, hipGetLastError());
+    }
+    // ---- step B's keys, sort and segment numbering on the side stream ------------------------------
+    RECD_HIP(ctx, hipStreamWaitEvent(side, ctx->ev_fork, 0));
+    void *ks_b = nullptr;
+    uint32_t *ps_b = nullptr;
+    {
+        constexpr int SG = 16;
+        const unsigned kb = (unsigned)((n_lists + (256 / SG) - 1) / (256 / SG));
+        if (!wide) {
+            uint32_t *k0 = static_cast<uint32_t *>(w.b.k0), *k1 = static_cast<uint32_t *>(w.b.k1), *ks;
+            hipLaunchKernelGGL((k_keys_ids<uint32_t, SG>), dim3(kb), dim3(256), 0, side, u_values,
+                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev,
+                               (seq || u_weights || maxmode) ? 1 : 0, u_weights ? w.pos_list : nullptr);
+            RECD_TRY(radix_sort_pairs<uint32_t>(ctx, side, k0, w.b.p0, k1, w.b.p1, w.b.n_dev, M_cap, bits_b,
+                                                w.b.hist, w.b.bsum, &ks, &ps_b));
+            ks_b = ks;
+        } else {
+            uint64_t *k0 = static_cast<uint64_t *>(w.b.k0), *k1 = static_cast<uint64_t *>(w.b.k1), *ks;
+            hipLaunchKernelGGL((k_keys_ids<uint64_t, SG>), dim3(kb), dim3(256), 0, side, u_values,
+                               u_offsets, feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev,
+                               (seq || u_weights || maxmode) ? 1 : 0, u_weights ? w.pos_list : nullptr);
+            RECD_TRY(radix_sort_pairs<uint64_t>(ctx, side, k0, w.b.p0, k1, w.b.p1, w.b.n_dev, M_cap, bits_b,
+                                                w.b.hist, w.b.bsum, &ks, &ps_b));
+            ks_b = ks;
+        }
+        if (u_weights) {
+            int64_t wb = (M_cap + 255) / 256;
+            if (wb > (int64_t)ctx->num_cu * 16)
+                wb = (int64_t)ctx->num_cu * 16;
+            hipLaunchKernelGGL(k_weight_payload, dim3((unsigned)(wb < 1 ? 1 : wb)), dim3(256), 0, side, ps_b,
+                               w.pos_list, u_weights, w.b.n_dev, w.pay_w);
+        }
+        RECD_HIP(ctx, hipGetLastError());
+        // the segments of step B (row ids, per-feature counts, chunks of the long ones) as well
+        if (!wide)
+            RECD_TRY(prepare_rows<uint32_t>(ctx, side, w, w.b, static_cast<const uint32_t *>(ks_b), M_cap, M_cap,
+                                            row_bits, F, touched_rows, feat_roff));
+        else
+            RECD_TRY(prepare_rows<uint64_t>(ctx, side, w, w.b, static_cast<const uint64_t *>(ks_b), M_cap, M_cap,
+                                            row_bits, F, touched_rows, feat_roff));
+        RECD_HIP(ctx, hipEventRecord(ctx->ev_join, side));
     }
     const float *b_table = seq ? grad_emb : (maxmode ? w.emb : w.g_u);
     // ---- step B: group unique-id positions by (feature, row), sum g_u rows into grad_rows --------
