@@ -113,6 +113,7 @@ class DeviceProblem:
             self.grad_rows = torch.zeros(Mmax, D, dtype=torch.float32, device="cuda") if store_grad else None
             self.state = [torch.zeros(w.rows, dtype=torch.float32, device="cuda") for _ in range(F)]
         self.rows = [w.rows] * F
+        self.u_hint = F * B
 
     # --- the calls of one step; each returns nothing and enqueues on torch's current stream ----
     def build(self, i, counts=True):
@@ -143,9 +144,14 @@ class DeviceProblem:
         self.ctx.kjt_pooled_lookup(self.tables, w.B, self.values[i], self.offsets[i], self.kjt_out)
 
     def step(self, i):
-        U, M = self.build(i)           # U and M come back to the host: they size the later launches
-        self.lookup(i, U)
+        # The lookup and the expand need no host-side count (any max_lists sizes the launch; the last
+        # step's U is the estimate), so they are enqueued right behind the build; U and M come back to
+        # the host while they run and bound the backward's sorts.
+        self.build(i, counts=False)
+        self.lookup(i, self.u_hint)
         self.expand(i)
+        U, M = self.ctx.last_ikjt_counts()
+        self.u_hint = max(U, 1)
         if self.need_backward:
             self.backward(i, U, M)
         return U, M

@@ -114,8 +114,9 @@ recd_status recd_workspace_bytes(int F, int64_t B, int64_t N, int D, size_t *out
  *    values [N], offsets [F*B+1]: device, read-only.
  *    u_values: device, capacity N.  u_offsets: device, capacity F*B+1.  inverse: device [F*B].
  *    feat_uoff: device [F+1].  Entries of u_values / u_offsets beyond M / U+1 are left untouched.
- *    host_U_M: optional host int64[2]; if non-NULL the call synchronises the stream and stores
- *    U and M there. */
+ *    host_U_M: optional host int64[2]; if non-NULL the call waits for the build and stores U and M
+ *    there.  If NULL the build publishes them when it finishes on the GPU and
+ *    recd_last_ikjt_counts returns them later. */
 recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t N,
                             const int64_t *values, const int64_t *offsets,
                             int64_t *u_values, int64_t *u_offsets, int32_t *inverse,
@@ -127,8 +128,11 @@ recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t N,
  *    tables: HOST array of F device pointers, table f is [rows[f], D] of table_dt.
  *    rows: HOST int64 [F] (used by validation only, may be NULL when validation is off).
  *    u_values, u_offsets, feat_uoff: device (outputs of recd_build_ikjt).
- *    max_lists: any upper bound of U known to the host (F*B always is); sizes nothing the caller
- *    sees.  pooled: device [U, D] of out_dt, capacity max_lists rows.
+ *    max_lists: the host's bound or estimate of U (F*B always bounds it).  It sizes the launch only:
+ *    the kernel reads U on the device and every block strides until all lists are done, so any
+ *    positive value gives the same result (an estimate near U gives the best launch shape); with
+ *    validation on it is also checked as the capacity of pooled.  pooled: device [U, D] of out_dt;
+ *    the caller provides room for U rows (F*B when U is not known yet).
  *    D*sizeof(element) must be a multiple of 16 and at most RECD_MAX_ROW_BYTES for both dtypes.
  *    out_dt must be table_dt or RECD_F32. */
 recd_status recd_pooled_lookup_unique(recd_ctx *ctx, int F, int D, recd_dtype table_dt,
@@ -399,6 +403,14 @@ recd_status recd_backward_dedup_weighted(recd_ctx *ctx, int F, int64_t B, int D,
                                          int64_t *touched_rows, int64_t *feat_roff, float *grad_rows,
                                          void *const *tables, float *const *adagrad_state, float lr,
                                          float eps, int64_t *host_R);
+
+/* Counts of the most recent call 1 / call 16 on this context: host_U_M[0] = U, host_U_M[1] = M.
+ *    A builder called with host_U_M = NULL publishes its counts to the host by itself when it
+ *    finishes on the GPU; this call waits for that publication only, not for work enqueued after the
+ *    build.  It lets a caller enqueue the lookup and the expand (which need no host-side count: any
+ *    max_lists sizes the launch, see call 2) behind the build and read U and M, which the backward's
+ *    bounds want, while they run.  Blocks the calling thread; RECD_EINVAL before the first build. */
+recd_status recd_last_ikjt_counts(recd_ctx *ctx, int64_t *host_U_M);
 
 /* 20. Call 5 for the max-pooled lookup of call 11 (Sec. 2.2 names max among the pooling functions):
  *    element d of g_u[u,:] goes to the table row at the position of unique list u that holds the

@@ -903,7 +903,8 @@ static recd_status build_plain(recd_ctx *ctx, int F, int64_t B, int64_t N, const
 
     RECD_TRY(recd_reserve(ctx, recd_build_workspace(F, B)));
     WsCarver c(ctx->ws);
-    const SlotWs w = carve_slots(c, F, B, n_lists, n_lists);
+    SlotWs w = carve_slots(c, F, B, n_lists, n_lists);
+    w.counts = ctx->build_counts_dev;  // {U, M}: outlives the workspace's reuse by later calls
     int64_t *counts = w.counts;
     hipStream_t st = ctx->stream;
 
@@ -918,8 +919,13 @@ static recd_status build_plain(recd_ctx *ctx, int F, int64_t B, int64_t N, const
                            u_values, inverse, inv_blocks, weights, u_weights);
     }
     RECD_HIP(ctx, hipGetLastError());
-    if (host_U_M)
+    ctx->build_valid = true;
+    if (host_U_M) {
+        ctx->build_published = false;  // fetched here; recd_last_ikjt_counts reads the device array
         RECD_TRY(recd_fetch_scalars(ctx, counts, 2, host_U_M));
+    } else {
+        RECD_TRY(recd_publish_build_counts(ctx));
+    }
     return RECD_OK;
 }
 

@@ -85,6 +85,19 @@ __global__ void k_publish(const int64_t *__restrict__ src, int n, int64_t *mailb
     __threadfence_system();
 }
 
+recd_status recd_publish_build_counts(recd_ctx *ctx)
+{
+    ctx->build_published = false;
+    if (!ctx->mailbox)
+        return RECD_OK;  // no mapped mailbox: recd_last_ikjt_counts copies from the device array
+    const int64_t seq = ++ctx->build_seq;
+    ctx->build_published = true;
+    hipLaunchKernelGGL(k_publish, dim3(1), dim3(1), 0, ctx->stream, ctx->build_counts_dev, 2,
+                       ctx->mailbox_dev + 8, seq);
+    RECD_HIP(ctx, hipGetLastError());
+    return RECD_OK;
+}
+
 recd_status recd_fetch_scalars(recd_ctx *ctx, const int64_t *dev, int n, int64_t *host_out)
 {
     if (n < 0 || n > 6)
@@ -165,11 +178,11 @@ recd_status recd_create(recd_ctx **out, int device, void *hip_stream, size_t wor
     ok = ok && hipHostMalloc(&p, 8 * sizeof(int64_t), hipHostMallocDefault) == hipSuccess;
     ctx->host_pinned = static_cast<int64_t *>(p);
     void *mb = nullptr, *mb_dev = nullptr;
-    if (ok && hipHostMalloc(&mb, 8 * sizeof(int64_t), hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess) {
+    if (ok && hipHostMalloc(&mb, 16 * sizeof(int64_t), hipHostMallocMapped | hipHostMallocCoherent) == hipSuccess) {
         if (hipHostGetDevicePointer(&mb_dev, mb, 0) == hipSuccess) {
             ctx->mailbox = static_cast<volatile int64_t *>(mb);
             ctx->mailbox_dev = static_cast<int64_t *>(mb_dev);
-            for (int i = 0; i < 8; i++)
+            for (int i = 0; i < 16; i++)
                 ctx->mailbox[i] = 0;
         } else {
             (void)hipGetLastError();
@@ -178,6 +191,9 @@ recd_status recd_create(recd_ctx **out, int device, void *hip_stream, size_t wor
     } else if (ok) {
         (void)hipGetLastError();
     }
+    void *bc = nullptr;
+    ok = ok && hipMalloc(&bc, 4 * sizeof(int64_t)) == hipSuccess;
+    ctx->build_counts_dev = static_cast<int64_t *>(bc);
     if (ok && workspace_hint_bytes)
         ok = recd_reserve(ctx, workspace_hint_bytes) == RECD_OK;
     if (!ok) {
@@ -207,6 +223,8 @@ recd_status recd_destroy(recd_ctx *ctx)
         (void)hipFree(ctx->ws);
     if (ctx->group_map_dev)
         (void)hipFree(ctx->group_map_dev);
+    if (ctx->build_counts_dev)
+        (void)hipFree(ctx->build_counts_dev);
     if (ctx->host_pinned)
         (void)hipHostFree(ctx->host_pinned);
     if (ctx->mailbox)
@@ -237,6 +255,33 @@ recd_status recd_set_option(recd_ctx *ctx, recd_option opt, int64_t value)
         return RECD_OK;
     }
     return recd_fail(ctx, RECD_EINVAL, "unknown option %d", (int)opt);
+}
+
+recd_status recd_last_ikjt_counts(recd_ctx *ctx, int64_t *host_U_M)
+{
+    if (!ctx || !host_U_M)
+        return RECD_EINVAL;
+    if (!ctx->build_valid)
+        return recd_fail(ctx, RECD_EINVAL, "no recd_build_ikjt / recd_build_ikjt_weighted call on this context yet");
+    RECD_HIP(ctx, hipSetDevice(ctx->device));
+    if (ctx->mailbox && ctx->build_published) {
+        // wait for the build's own publication, not for what was enqueued after it
+        const auto t0 = std::chrono::steady_clock::now();
+        for (uint64_t spin = 0;; spin++) {
+            if (ctx->mailbox[15] == ctx->build_seq) {
+                std::atomic_thread_fence(std::memory_order_acquire);
+                host_U_M[0] = ctx->mailbox[8];
+                host_U_M[1] = ctx->mailbox[9];
+                return RECD_OK;
+            }
+            if ((spin & 0xfff) == 0xfff &&
+                std::chrono::steady_clock::now() - t0 > std::chrono::milliseconds(200))
+                break;  // a long queue ahead of the build, a replayed graph, or an error
+        }
+    }
+    RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    RECD_HIP(ctx, hipMemcpy(host_U_M, ctx->build_counts_dev, 2 * sizeof(int64_t), hipMemcpyDeviceToHost));
+    return RECD_OK;
 }
 
 const char *recd_last_error(const recd_ctx *ctx) { return ctx ? ctx->err.c_str() : "null context"; }

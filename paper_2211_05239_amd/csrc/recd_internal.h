@@ -22,6 +22,14 @@ struct recd_ctx {
     volatile int64_t *mailbox = nullptr;
     int64_t *mailbox_dev = nullptr;
     int64_t mailbox_seq = 0;
+    // Counts {U, M} of the most recent plain or weighted IKJT build: a device array that outlives the
+    // workspace's reuse, and the second half of the mailbox (entries 8..15, sequence number in 15),
+    // which the builder fills without being asked so that recd_last_ikjt_counts can wait for the
+    // build alone.
+    int64_t *build_counts_dev = nullptr;
+    int64_t build_seq = 0;        // sequence number of the latest publication (never reused)
+    bool build_published = false; // the last build published its counts (else: read the device array)
+    bool build_valid = false;     // a plain / weighted build has written build_counts_dev
     int validate = 0;
     int weak_hash = 0;
     int tune_lb = 0, tune_gens = 0, tune_flat = 0;  // launch-shape overrides of the gather-sum kernel (0 = automatic)
@@ -36,6 +44,8 @@ struct recd_ctx {
 recd_status recd_fail(recd_ctx *ctx, recd_status s, const char *fmt, ...);
 // Ids must lie in [0, 2^31): a table the caller describes as larger is refused (rows may be null).
 recd_status recd_check_rows(recd_ctx *ctx, int F, const int64_t *rows);
+// After a builder wrote {U, M} into ctx->build_counts_dev: publish them to the host asynchronously.
+recd_status recd_publish_build_counts(recd_ctx *ctx);
 recd_status recd_reserve(recd_ctx *ctx, size_t bytes);
 
 #define RECD_HIP(ctx, call)                                                                   \

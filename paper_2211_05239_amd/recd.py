@@ -38,6 +38,7 @@ EXPORTED = [
     "recd_build_partial_ikjt", "recd_pooled_lookup_partial", "recd_backward_sequence_dedup",
     "recd_backward_dedup_mode", "recd_build_ikjt_weighted", "recd_pooled_lookup_unique_weighted",
     "recd_kjt_pooled_lookup_weighted", "recd_backward_dedup_weighted", "recd_backward_dedup_max",
+    "recd_last_ikjt_counts",
 ]
 
 _vp = C.c_void_p
@@ -69,6 +70,7 @@ _lib.recd_backward_dedup_weighted.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, 
                                               C.c_float, _vp]
 _lib.recd_backward_dedup_max.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, _vp, _vp, _vp, _vp, _vp, _vp, C.c_int64,
                                          C.c_int64, _vp, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]
+_lib.recd_last_ikjt_counts.argtypes = [_vp, _vp]
 _lib.recd_sequence_lookup_unique.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, _vp,
                                              _vp, C.c_int64, C.c_int64, _vp]
 _lib.recd_jagged_expand_inverse.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, _vp,
@@ -153,6 +155,12 @@ class Context:
                                          _ptr(u_values), _ptr(u_offsets), _ptr(inverse),
                                          _ptr(feat_uoff), host))
         return (int(host[0]), int(host[1])) if want_counts else None
+
+    def last_ikjt_counts(self):
+        """(U, M) of the most recent build_ikjt / build_ikjt_weighted call; waits for that build only."""
+        host = (C.c_int64 * 2)(0, 0)
+        self._check(_lib.recd_last_ikjt_counts(self._h, host))
+        return int(host[0]), int(host[1])
 
     @staticmethod
     def _table_array(tables: Sequence[torch.Tensor]):

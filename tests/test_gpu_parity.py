@@ -283,6 +283,30 @@ def test_argument_errors(ctx, recd):
     del t16
 
 
+def test_deferred_counts_and_any_max_lists(ctx):
+    """A build without host counts publishes them by itself; the lookup gives the same bits whatever
+    max_lists is (it only sizes the launch), so it can be enqueued before the counts are read."""
+    w = synth.scaled(synth.WORKLOADS["cfg2"], F=16, B=1024, rows=20_000, D=64)
+    batch = synth.make_batch(w, 0)
+    d_tabs = gu.tables_to_dev(synth.make_tables(w), "f32")
+    F, B, D = w.F, w.B, w.D
+    values, offsets, ik = gu.gpu_build(ctx, batch)          # counts fetched by the build itself
+    assert ctx.last_ikjt_counts() == (ik.U, ik.M)
+    ik2 = gu.DeviceIKJT(F, B, batch.N)
+    ctx.build_ikjt(F, B, values, offsets, ik2.u_values, ik2.u_offsets, ik2.inverse, ik2.feat_uoff)
+    pooled = [torch.full((F * B, D), float("nan"), device="cuda") for _ in range(5)]
+    for t, max_lists in zip(pooled, (F * B, 1, ik.U // 2, ik.U, 3 * ik.U)):
+        ctx.pooled_lookup_unique(d_tabs, ik2.u_values, ik2.u_offsets, ik2.feat_uoff, max_lists, t)
+    assert ctx.last_ikjt_counts() == (ik.U, ik.M)             # after more work was enqueued
+    assert ctx.last_ikjt_counts() == (ik.U, ik.M)             # and again
+    for t in pooled[1:]:
+        assert torch.equal(t[:ik.U], pooled[0][:ik.U])
+    batch0 = synth.batch_from_lists([[[], []]])
+    v0, o0, ik0 = gu.gpu_build(ctx, batch0)
+    ctx.build_ikjt(1, 2, v0, o0, ik0.u_values, ik0.u_offsets, ik0.inverse, ik0.feat_uoff)
+    assert ctx.last_ikjt_counts() == (1, 0)
+
+
 def test_table_size_limit(ctx, recd):
     """Ids lie in [0, 2^31): a table described as larger is refused on the host."""
     tabs = [torch.zeros(4, 8, device="cuda")]
