@@ -50,6 +50,9 @@ def parse_args():
     ap.add_argument("--partial", type=float, default=0.0,
                     help="also time the partial IKJT path on the workload with this probability of a "
                          "sample's lists shifting by one id within a session (0 = skip)")
+    ap.add_argument("--one-call-backward", dest="planned", action="store_false",
+                    help="run the backward as one call after the expand instead of plan (next to the forward "
+                         "calls) + apply")
     ap.add_argument("--graph", action="store_true",
                     help="also time the step replayed from captured HIP graphs (launches sized by host upper "
                          "bounds of U and M; reported beside `value`)")
@@ -114,6 +117,7 @@ class DeviceProblem:
             self.state = [torch.zeros(w.rows, dtype=torch.float32, device="cuda") for _ in range(F)]
         self.rows = [w.rows] * F
         self.u_hint = F * B
+        self.planned = True
 
     # --- the calls of one step; each returns nothing and enqueues on torch's current stream ----
     def build(self, i, counts=True):
@@ -153,7 +157,16 @@ class DeviceProblem:
         U, M = self.ctx.last_ikjt_counts()
         self.u_hint = max(U, 1)
         if self.need_backward:
-            self.backward(i, U, M)
+            if self.planned:
+                # the backward's grouping half depends on the IKJT only: it runs on the context's side
+                # streams from the end of the build on, next to lookup and expand; the sums follow
+                w = self.w
+                self.ctx.backward_plan(w.F, w.B, w.D, self.inverse[i], self.feat_uoff[i], self.u_values[i],
+                                       self.u_offsets[i], self.rows, U, M, self.touched, self.feat_roff)
+                self.ctx.backward_apply(self.grad_out, self.grad_rows, tables=self.tables,
+                                        adagrad_state=self.state, lr=0.01, eps=1e-8)
+            else:
+                self.backward(i, U, M)
         return U, M
 
 
@@ -260,6 +273,7 @@ def event_ms(torch, fn, reps):
 
 def run_workload(torch, recd, synth, w, args, need_backward, detail=True, pipeline=True):
     P = DeviceProblem(torch, recd, synth, w, args.batches, need_backward, getattr(args, "store_grad", False), getattr(args, "tune", 0))
+    P.planned = getattr(args, "planned", True)
     nb = len(P.batches)
     F, B, D = w.F, w.B, w.D
     e = 4 if w.table_dtype == "f32" else 2

@@ -17,7 +17,7 @@
  * another (Sec. 7): 12. partial builder   13. pooled lookup on the windows
  *   14. backward of the sequence path   15. backward of the averaged pooled lookup
  *   16-19. per-id weights: builder, unique and KJT lookups, backward
- *   20. backward of the max-pooled lookup
+ *   20. backward of the max-pooled lookup   21, 22. the backward in two halves (plan / apply)
  *
  * General rules
  *   - Every array argument marked "device" is a pointer into GPU memory owned by the caller and
@@ -411,6 +411,27 @@ recd_status recd_backward_dedup_weighted(recd_ctx *ctx, int F, int64_t B, int D,
  *    max_lists sizes the launch, see call 2) behind the build and read U and M, which the backward's
  *    bounds want, while they run.  Blocks the calling thread; RECD_EINVAL before the first build. */
 recd_status recd_last_ikjt_counts(recd_ctx *ctx, int64_t *host_U_M);
+
+/* 21, 22. Call 5 in two halves.  What the backward does before it touches a gradient (keys, the two
+ *    stable sorts, the numbering of the segments, touched_rows and feat_roff) depends on the IKJT
+ *    alone.  recd_backward_plan enqueues that half on the context's two side streams and returns; if
+ *    inverse and u_values are the outputs of the context's most recent call 1 / 16, the side streams
+ *    start where that build ended, so the plan runs next to calls 2 and 3 enqueued meanwhile on the
+ *    context's stream; otherwise they start at the stream's current position.
+ *    recd_backward_apply makes the stream wait for the plan and runs the two segment sums (and the
+ *    optimizer) exactly as call 5 / call 15 would: same kernels, same results bit for bit.
+ *    Between the two calls the context's workspace holds the plan: no other call that uses the
+ *    workspace (builders, backward calls, a validation pass) may come in between — calls 2, 3, 4 and
+ *    recd_last_ikjt_counts may; the IKJT arrays, touched_rows and feat_roff must stay as they are.
+ *    recd_backward_apply returns RECD_EINVAL if no valid plan exists.  mode: RECD_POOL_SUM or
+ *    RECD_POOL_MEAN.  Arguments as in call 5. */
+recd_status recd_backward_plan(recd_ctx *ctx, int F, int64_t B, int D, const int32_t *inverse,
+                               const int64_t *feat_uoff, const int64_t *u_values,
+                               const int64_t *u_offsets, const int64_t *rows, int64_t U_cap,
+                               int64_t M_cap, int64_t *touched_rows, int64_t *feat_roff);
+recd_status recd_backward_apply(recd_ctx *ctx, recd_pooling mode, const float *grad_out,
+                                float *grad_rows, void *const *tables, float *const *adagrad_state,
+                                float lr, float eps, int64_t *host_R);
 
 /* 20. Call 5 for the max-pooled lookup of call 11 (Sec. 2.2 names max among the pooling functions):
  *    element d of g_u[u,:] goes to the table row at the position of unique list u that holds the

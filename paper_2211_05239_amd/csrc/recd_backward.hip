@@ -1225,6 +1225,7 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
     if (ctx->validate && n_lists > 0)
         RECD_TRY(recd_validate_inverse(ctx, F, B, feat_uoff, inverse));
     const bool maxmode = max_tables != nullptr;
+    ctx->plan.valid = false;  // this call reuses the workspace a plan would live in
     RECD_TRY(recd_reserve(ctx, carve_bwd(nullptr, n_lists, M_cap, F, D, maxmode).bytes));
     const BwdWs w = carve_bwd(ctx->ws, n_lists, M_cap, F, D, maxmode);
     hipStream_t st = ctx->stream;
@@ -1397,6 +1398,217 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
                                      hipMemcpyDeviceToHost, st));
         RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned + 1, w.b.n_dev + 1, sizeof(int64_t),
                                      hipMemcpyDeviceToHost, st));
+        RECD_HIP(ctx, hipStreamSynchronize(st));
+        host_R[0] = ctx->host_pinned[0];
+        if (ctx->host_pinned[1])
+            return recd_fail(ctx, RECD_ECAPACITY, "M_cap=%lld is smaller than M", (long long)M_cap);
+    }
+    return RECD_OK;
+}
+
+// ---------------------------------------------------------------- planned backward
+// The backward's grouping work (keys, sorts, segment numbering of both steps) depends on the IKJT
+// only, not on the gradient.  recd_backward_plan runs it on the two side streams, starting where the
+// IKJT's build ended, so that it overlaps the forward calls (which are bandwidth-bound, while the
+// plan is a chain of short latency-bound kernels); recd_backward_apply then waits for the plan on the
+// main stream and runs the two segment sums with the fused update.  Same kernels, same inputs, same
+// results as the one-call form.
+extern "C" recd_status recd_backward_plan(recd_ctx *ctx, int F, int64_t B, int D, const int32_t *inverse,
+                                          const int64_t *feat_uoff, const int64_t *u_values,
+                                          const int64_t *u_offsets, const int64_t *rows, int64_t U_cap,
+                                          int64_t M_cap, int64_t *touched_rows, int64_t *feat_roff)
+{
+    if (!ctx)
+        return RECD_EINVAL;
+    ctx->plan.valid = false;
+    if (F < 0 || F > RECD_MAX_FEATURES || B < 0 || M_cap < 0 || U_cap < 0)
+        return recd_fail(ctx, RECD_EINVAL, "bad sizes");
+    if (U_cap > (int64_t)F * B)
+        U_cap = (int64_t)F * B;
+    if (D <= 0 || D % 4 != 0 || (size_t)D * 4 > RECD_MAX_ROW_BYTES ||
+        (D * 4 / 16 > 64 && D * 4 / 16 != 128 && D * 4 / 16 != 256))
+        return recd_fail(ctx, RECD_EINVAL, "unsupported D=%d", D);
+    const int64_t n_lists = (int64_t)F * B;
+    if (n_lists >= (int64_t)1 << 31 || M_cap >= (int64_t)1 << 31)
+        return recd_fail(ctx, RECD_EINVAL, "F*B and M_cap must stay below 2^31");
+    if (!feat_roff || !feat_uoff || !u_offsets || (F > 0 && !rows) || (n_lists > 0 && !inverse) ||
+        (M_cap > 0 && (!u_values || !touched_rows)))
+        return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
+    RECD_TRY(recd_check_rows(ctx, F, rows));
+    int64_t max_rows = 1;
+    for (int f = 0; f < F; f++) {
+        if (rows[f] <= 0)
+            return recd_fail(ctx, RECD_EINVAL, "rows[%d] <= 0", f);
+        if (rows[f] > max_rows)
+            max_rows = rows[f];
+    }
+    RECD_HIP(ctx, hipSetDevice(ctx->device));
+    if (ctx->validate && n_lists > 0)
+        RECD_TRY(recd_validate_inverse(ctx, F, B, feat_uoff, inverse));
+    RECD_TRY(recd_reserve(ctx, recd_backward_workspace(F, B, M_cap, D)));
+    const BwdWs w = carve_bwd(ctx->ws, n_lists, M_cap, F, D);
+    recd_ctx::BackwardPlan &pl = ctx->plan;
+    pl.F = F;
+    pl.B = B;
+    pl.D = D;
+    pl.U_cap = U_cap;
+    pl.M_cap = M_cap;
+    pl.u_offsets = u_offsets;
+    pl.touched_rows = touched_rows;
+    pl.feat_roff = feat_roff;
+    pl.ws = ctx->ws;
+    pl.empty = n_lists == 0 || M_cap == 0;
+    hipStream_t st = ctx->stream, sa = ctx->side_stream2, sb = ctx->side_stream;
+    // Where the side streams may start: at the end of the build that produced this IKJT if it is the
+    // context's most recent one, else at the main stream's current position.
+    hipEvent_t from = ctx->ev_fork;
+    if (ctx->build_valid && ctx->built_inverse == inverse && ctx->built_u_values == u_values && n_lists > 0)
+        from = ctx->ev_built;
+    else
+        RECD_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
+    RECD_HIP(ctx, hipStreamWaitEvent(sa, from, 0));
+    RECD_HIP(ctx, hipStreamWaitEvent(sb, from, 0));
+    if (!pl.empty) {
+        const int row_bits = bits_for((uint64_t)(max_rows - 1));
+        const int bits_b = row_bits + bits_for((uint64_t)(F > 1 ? F - 1 : 1));
+        const int bits_a = bits_for((uint64_t)(U_cap > 1 ? U_cap - 1 : 1));
+        pl.row_bits = row_bits;
+        pl.wide = bits_b > 32;
+        // step A's grouping on the second side stream
+        {
+            uint32_t *k0 = static_cast<uint32_t *>(w.a.k0), *k1 = static_cast<uint32_t *>(w.a.k1), *ks, *ps;
+            hipLaunchKernelGGL(k_keys_rows, dim3((unsigned)((n_lists + 255) / 256)), dim3(256), 0, sa, inverse,
+                               feat_uoff, B, n_lists, k0, w.a.p0, w.a.n_dev);
+            RECD_TRY(radix_sort_pairs<uint32_t>(ctx, sa, k0, w.a.p0, k1, w.a.p1, w.a.n_dev, n_lists, bits_a,
+                                                w.a.hist, w.a.bsum, &ks, &ps));
+            RECD_TRY(number_segments<uint32_t>(ctx, sa, w, w.a, ks, n_lists, -1, F, nullptr, nullptr));
+            pl.ks_a = ks;
+            pl.ps_a = ps;
+        }
+        // step B's grouping on the first
+        {
+            constexpr int SG = 16;
+            const unsigned kb = (unsigned)((n_lists + (256 / SG) - 1) / (256 / SG));
+            if (!pl.wide) {
+                uint32_t *k0 = static_cast<uint32_t *>(w.b.k0), *k1 = static_cast<uint32_t *>(w.b.k1), *ks, *ps;
+                hipLaunchKernelGGL((k_keys_ids<uint32_t, SG>), dim3(kb), dim3(256), 0, sb, u_values, u_offsets,
+                                   feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev, 0, nullptr);
+                RECD_TRY(radix_sort_pairs<uint32_t>(ctx, sb, k0, w.b.p0, k1, w.b.p1, w.b.n_dev, M_cap, bits_b,
+                                                    w.b.hist, w.b.bsum, &ks, &ps));
+                RECD_TRY(prepare_rows<uint32_t>(ctx, sb, w, w.b, ks, M_cap, M_cap, row_bits, F, touched_rows,
+                                                feat_roff));
+                pl.ps_b = ps;
+            } else {
+                uint64_t *k0 = static_cast<uint64_t *>(w.b.k0), *k1 = static_cast<uint64_t *>(w.b.k1), *ks;
+                uint32_t *ps;
+                hipLaunchKernelGGL((k_keys_ids<uint64_t, SG>), dim3(kb), dim3(256), 0, sb, u_values, u_offsets,
+                                   feat_uoff, F, row_bits, n_lists, M_cap, k0, w.b.p0, w.b.n_dev, 0, nullptr);
+                RECD_TRY(radix_sort_pairs<uint64_t>(ctx, sb, k0, w.b.p0, k1, w.b.p1, w.b.n_dev, M_cap, bits_b,
+                                                    w.b.hist, w.b.bsum, &ks, &ps));
+                RECD_TRY(prepare_rows<uint64_t>(ctx, sb, w, w.b, ks, M_cap, M_cap, row_bits, F, touched_rows,
+                                                feat_roff));
+                pl.ps_b = ps;
+            }
+        }
+        RECD_HIP(ctx, hipGetLastError());
+    }
+    RECD_HIP(ctx, hipEventRecord(ctx->ev_plan_a, sa));
+    RECD_HIP(ctx, hipEventRecord(ctx->ev_plan_b, sb));
+    pl.valid = true;
+    return RECD_OK;
+}
+
+extern "C" recd_status recd_backward_apply(recd_ctx *ctx, recd_pooling mode, const float *grad_out,
+                                           float *grad_rows, void *const *tables,
+                                           float *const *adagrad_state, float lr, float eps,
+                                           int64_t *host_R)
+{
+    if (!ctx)
+        return RECD_EINVAL;
+    recd_ctx::BackwardPlan &pl = ctx->plan;
+    if (!pl.valid || pl.ws != ctx->ws)
+        return recd_fail(ctx, RECD_EINVAL,
+                         "no valid plan: recd_backward_plan must be the context's last workspace-using call");
+    pl.valid = false;
+    if (mode != RECD_POOL_SUM && mode != RECD_POOL_MEAN)
+        return recd_fail(ctx, RECD_EINVAL, "planned backward: pooling mode %d is not supported", (int)mode);
+    const int F = pl.F, D = pl.D;
+    const int64_t B = pl.B, n_lists = (int64_t)F * B, M_cap = pl.M_cap;
+    if (n_lists > 0 && !grad_out)
+        return recd_fail(ctx, RECD_EINVAL, "null grad_out");
+    if ((tables == nullptr) != (adagrad_state == nullptr))
+        return recd_fail(ctx, RECD_EINVAL, "tables and adagrad_state must be given together");
+    if (M_cap > 0 && !grad_rows && !(tables && F <= RECD_F_PER_LAUNCH))
+        return recd_fail(ctx, RECD_EINVAL,
+                         "grad_rows may be NULL only with the optimizer and at most %d features",
+                         RECD_F_PER_LAUNCH);
+    for (int f = 0; f < F && tables; f++)
+        if (!tables[f] || !adagrad_state[f])
+            return recd_fail(ctx, RECD_EINVAL, "tables[%d] or adagrad_state[%d] is null", f, f);
+    RECD_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t st = ctx->stream;
+    const BwdWs w = carve_bwd(ctx->ws, n_lists, M_cap, F, D);
+    RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_plan_a, 0));
+    RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_plan_b, 0));
+    if (pl.empty) {
+        hipLaunchKernelGGL(k_no_rows, dim3(1), dim3(64), 0, st, F, pl.feat_roff, w.list_off_b);
+        RECD_HIP(ctx, hipGetLastError());
+        if (host_R) {
+            RECD_HIP(ctx, hipStreamSynchronize(st));
+            host_R[0] = 0;
+        }
+        return RECD_OK;
+    }
+    const bool fused = tables != nullptr && F <= RECD_F_PER_LAUNCH;
+    OptAdagrad oa;
+    oa.n_feat = 0;
+    if (fused) {
+        oa.n_feat = F;
+        for (int f = 0; f < F; f++) {
+            oa.w[f] = static_cast<float *>(tables[f]);
+            oa.m[f] = adagrad_state[f];
+        }
+        oa.lr = lr;
+        oa.eps = eps;
+    }
+    // step A's sum over the planned segments
+    {
+        SegSumArgs a{};
+        a.site = RECD_SITE_GRAD_STREAM;
+        a.F = 1;
+        a.D = D;
+        a.table_dt = RECD_F32;
+        a.out_dt = RECD_F32;
+        a.tables.p[0] = grad_out;
+        a.values = pl.ps_a;
+        a.values_are_i32 = 1;
+        a.offsets = w.seg_start;
+        a.list_off = w.list_off;
+        a.lists_bound = pl.U_cap;
+        a.flat = 1;
+        a.out = w.g_u;
+        a.div_off = mode == RECD_POOL_MEAN ? pl.u_offsets : nullptr;
+        RECD_TRY(recd_launch_segsum(ctx, a));
+    }
+    RECD_TRY(sum_rows(ctx, w, pl.ps_b, M_cap, M_cap, w.g_u, D, grad_rows, pl.touched_rows, fused ? &oa : nullptr,
+                      nullptr));
+    if (tables && !fused) {
+        for (int f0 = 0; f0 < F; f0 += RECD_F_PER_LAUNCH) {
+            OptPtrs ptrs;
+            const int nf = F - f0 < RECD_F_PER_LAUNCH ? F - f0 : RECD_F_PER_LAUNCH;
+            for (int f = 0; f < nf; f++) {
+                ptrs.w[f] = static_cast<float *>(tables[f0 + f]);
+                ptrs.m[f] = adagrad_state[f0 + f];
+            }
+            hipLaunchKernelGGL(k_adagrad, dim3(ctx->num_cu * 8), dim3(256), 0, st, grad_rows, pl.touched_rows,
+                               pl.feat_roff, f0, nf, D, ptrs, lr, eps);
+        }
+        RECD_HIP(ctx, hipGetLastError());
+    }
+    if (host_R) {
+        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, w.list_off_b + 1, sizeof(int64_t), hipMemcpyDeviceToHost, st));
+        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned + 1, w.b.n_dev + 1, sizeof(int64_t), hipMemcpyDeviceToHost,
+                                     st));
         RECD_HIP(ctx, hipStreamSynchronize(st));
         host_R[0] = ctx->host_pinned[0];
         if (ctx->host_pinned[1])

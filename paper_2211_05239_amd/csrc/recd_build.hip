@@ -920,6 +920,10 @@ static recd_status build_plain(recd_ctx *ctx, int F, int64_t B, int64_t N, const
     }
     RECD_HIP(ctx, hipGetLastError());
     ctx->build_valid = true;
+    ctx->plan.valid = false;  // the builder reused the workspace a plan would live in
+    RECD_HIP(ctx, hipEventRecord(ctx->ev_built, st));
+    ctx->built_inverse = inverse;
+    ctx->built_u_values = u_values;
     if (host_U_M) {
         ctx->build_published = false;  // fetched here; recd_last_ikjt_counts reads the device array
         RECD_TRY(recd_fetch_scalars(ctx, counts, 2, host_U_M));
@@ -982,6 +986,7 @@ extern "C" recd_status recd_build_ikjt_grouped(recd_ctx *ctx, int F, int64_t B, 
     if (ctx->validate && n_lists > 0)
         RECD_TRY(recd_validate_kjt_offsets(ctx, F, B, N, offsets));
 
+    ctx->plan.valid = false;  // this call reuses the workspace a backward plan would live in
     RECD_TRY(recd_reserve(ctx, recd_build_workspace(F, B)));
     WsCarver c(ctx->ws);
     const SlotWs w = carve_slots(c, G, B, n_items, n_lists);  // slots of the group rows
@@ -1057,6 +1062,7 @@ extern "C" recd_status recd_build_partial_ikjt(recd_ctx *ctx, int F, int64_t B, 
         RECD_TRY(recd_validate_kjt_offsets(ctx, F, B, N, offsets));
 
     const int64_t nblk = (n_lists + kScanBlock - 1) / kScanBlock;
+    ctx->plan.valid = false;  // this call reuses the workspace a backward plan would live in
     RECD_TRY(recd_reserve(ctx, recd_build_workspace(F, B)));
     WsCarver c(ctx->ws);
     const SlotWs w = carve_slots(c, F, B, n_lists, n_lists);

@@ -33,8 +33,13 @@ recd_status recd_reserve(recd_ctx *ctx, size_t bytes)
 {
     if (bytes <= ctx->ws_bytes)
         return RECD_OK;
-    // Growing: earlier kernels may still use the old block.
+    // Growing: earlier kernels may still use the old block; a backward plan lives in it.
     RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if (ctx->side_stream)
+        RECD_HIP(ctx, hipStreamSynchronize(ctx->side_stream));
+    if (ctx->side_stream2)
+        RECD_HIP(ctx, hipStreamSynchronize(ctx->side_stream2));
+    ctx->plan.valid = false;
     if (ctx->ws) {
         RECD_HIP(ctx, hipFree(ctx->ws));
         ctx->ws = nullptr;
@@ -172,6 +177,10 @@ recd_status recd_create(recd_ctx **out, int device, void *hip_stream, size_t wor
     if (ok && hipGetDeviceProperties(&prop, device) == hipSuccess && prop.multiProcessorCount > 0)
         ctx->num_cu = prop.multiProcessorCount;
     ok = ok && hipStreamCreateWithFlags(&ctx->side_stream, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipStreamCreateWithFlags(&ctx->side_stream2, hipStreamNonBlocking) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ctx->ev_built, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ctx->ev_plan_a, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ctx->ev_plan_b, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) == hipSuccess;
     void *p = nullptr;
@@ -215,6 +224,16 @@ recd_status recd_destroy(recd_ctx *ctx)
         (void)hipStreamSynchronize(ctx->side_stream);
         (void)hipStreamDestroy(ctx->side_stream);
     }
+    if (ctx->side_stream2) {
+        (void)hipStreamSynchronize(ctx->side_stream2);
+        (void)hipStreamDestroy(ctx->side_stream2);
+    }
+    if (ctx->ev_built)
+        (void)hipEventDestroy(ctx->ev_built);
+    if (ctx->ev_plan_a)
+        (void)hipEventDestroy(ctx->ev_plan_a);
+    if (ctx->ev_plan_b)
+        (void)hipEventDestroy(ctx->ev_plan_b);
     if (ctx->ev_fork)
         (void)hipEventDestroy(ctx->ev_fork);
     if (ctx->ev_join)

@@ -14,6 +14,22 @@ struct recd_ctx {
     hipStream_t stream = nullptr;
     hipStream_t side_stream = nullptr;   // independent work of one call (default priority, non-blocking)
     hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+    // Planned backward: the gradient-independent half (sorts, segment numbering) of a backward pass
+    // runs on two side streams from the end of the last build on, next to the forward calls.
+    hipStream_t side_stream2 = nullptr;
+    hipEvent_t ev_built = nullptr;                    // end of the most recent plain / weighted build
+    hipEvent_t ev_plan_a = nullptr, ev_plan_b = nullptr;
+    const void *built_inverse = nullptr, *built_u_values = nullptr;  // outputs of that build
+    struct BackwardPlan {
+        bool valid = false, empty = false, wide = false;
+        int F = 0, D = 0, row_bits = 0;
+        int64_t B = 0, U_cap = 0, M_cap = 0;
+        const void *ks_a = nullptr;
+        const uint32_t *ps_a = nullptr, *ps_b = nullptr;
+        const int64_t *u_offsets = nullptr;
+        int64_t *touched_rows = nullptr, *feat_roff = nullptr;
+        const char *ws = nullptr;   // the workspace the plan lives in must still be the context's
+    } plan;
     char *ws = nullptr;          // device workspace
     size_t ws_bytes = 0;
     int64_t *host_pinned = nullptr;  // 8 x int64 pinned staging for scalar results

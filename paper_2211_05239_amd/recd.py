@@ -38,7 +38,7 @@ EXPORTED = [
     "recd_build_partial_ikjt", "recd_pooled_lookup_partial", "recd_backward_sequence_dedup",
     "recd_backward_dedup_mode", "recd_build_ikjt_weighted", "recd_pooled_lookup_unique_weighted",
     "recd_kjt_pooled_lookup_weighted", "recd_backward_dedup_weighted", "recd_backward_dedup_max",
-    "recd_last_ikjt_counts",
+    "recd_last_ikjt_counts", "recd_backward_plan", "recd_backward_apply",
 ]
 
 _vp = C.c_void_p
@@ -71,6 +71,9 @@ _lib.recd_backward_dedup_weighted.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, 
 _lib.recd_backward_dedup_max.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, _vp, _vp, _vp, _vp, _vp, _vp, C.c_int64,
                                          C.c_int64, _vp, _vp, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]
 _lib.recd_last_ikjt_counts.argtypes = [_vp, _vp]
+_lib.recd_backward_plan.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, _vp, _vp, _vp, _vp, _vp, C.c_int64, C.c_int64,
+                                    _vp, _vp]
+_lib.recd_backward_apply.argtypes = [_vp, C.c_int, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]
 _lib.recd_sequence_lookup_unique.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, _vp,
                                              _vp, C.c_int64, C.c_int64, _vp]
 _lib.recd_jagged_expand_inverse.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, C.c_int, C.c_int, _vp,
@@ -261,6 +264,22 @@ class Context:
             self._h, F, B, D, _ptr(grad_out), _ptr(inverse), _ptr(feat_uoff), _ptr(u_values), _ptr(u_weights),
             _ptr(u_offsets), rows_arr, U_cap, M_cap, _ptr(touched_rows), _ptr(feat_roff), _ptr(grad_rows),
             tabs, state, lr, eps, host))
+        return int(host[0]) if want_count else None
+
+    def backward_plan(self, F: int, B: int, D: int, inverse, feat_uoff, u_values, u_offsets, rows: Sequence[int],
+                      U_cap: int, M_cap: int, touched_rows, feat_roff):
+        rows_arr = (C.c_int64 * len(rows))(*rows)
+        self._check(_lib.recd_backward_plan(self._h, F, B, D, _ptr(inverse), _ptr(feat_uoff), _ptr(u_values),
+                                            _ptr(u_offsets), rows_arr, U_cap, M_cap, _ptr(touched_rows),
+                                            _ptr(feat_roff)))
+
+    def backward_apply(self, grad_out, grad_rows, tables=None, adagrad_state=None, lr: float = 0.0,
+                       eps: float = 0.0, want_count: bool = False, mode: str = "sum"):
+        tabs = self._table_array(tables) if tables is not None else None
+        state = self._table_array(adagrad_state) if adagrad_state is not None else None
+        host = (C.c_int64 * 1)(0) if want_count else None
+        self._check(_lib.recd_backward_apply(self._h, POOLING[mode], _ptr(grad_out), _ptr(grad_rows), tabs, state,
+                                             lr, eps, host))
         return int(host[0]) if want_count else None
 
     def backward_dedup_max(self, F: int, B: int, grad_out, inverse, feat_uoff, u_values, u_offsets,

@@ -545,6 +545,72 @@ def test_backward_many_features(ctx):
     _max_backward_case(ctx, w, synth.make_batch(w, 0), True)
 
 
+@pytest.mark.parametrize("mode", ["sum", "mean"])
+@pytest.mark.parametrize("name,kw", [("cfg1", dict(F=3, B=357, rows=900, D=32)),
+                                     ("cfg5", dict(F=8, B=2048, rows=30_000, D=128)),
+                                     ("cfg1", dict(F=131, B=67, rows=500, D=16))])
+def test_backward_plan_apply_equals_one_call(ctx, recd, name, kw, mode):
+    """The planned backward (grouping next to the forward calls, sums afterwards) against the one-call
+    form: identical bits for the row gradients, the touched rows and the updated tables."""
+    w = synth.scaled(synth.WORKLOADS[name], **kw)
+    batch = synth.make_batch(w, 0)
+    F, B, D = w.F, w.B, w.D
+    gout = gu.to_dev(synth.make_grad_out(w, 0))
+    tabs = synth.make_tables(w)
+    values, offsets = gu.to_dev(batch.values), gu.to_dev(batch.offsets)
+    results = []
+    for planned in (False, True):
+        d_tabs = gu.tables_to_dev(tabs, "f32")
+        d_state = [torch.zeros(w.rows, device="cuda") for _ in range(F)]
+        ik = gu.DeviceIKJT(F, B, batch.N)
+        ctx.build_ikjt(F, B, values, offsets, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff)
+        pooled = torch.zeros(F * B, D, device="cuda")
+        out = torch.zeros(F, B, D, device="cuda")
+        ctx.pooled_lookup_unique(d_tabs, ik.u_values, ik.u_offsets, ik.feat_uoff, F * B, pooled, mode=mode)
+        U, M = ctx.last_ikjt_counts()
+        touched = torch.full((M,), -7, dtype=torch.int64, device="cuda")
+        feat_roff = torch.full((F + 1,), -7, dtype=torch.int64, device="cuda")
+        grad_rows = torch.full((M, D), float("nan"), device="cuda")
+        if planned:
+            ctx.backward_plan(F, B, D, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F, U, M,
+                              touched, feat_roff)
+            ctx.expand_inverse(F, B, pooled, ik.feat_uoff, ik.inverse, out)   # forward work next to the plan
+            R = ctx.backward_apply(gout, grad_rows, tables=d_tabs, adagrad_state=d_state, lr=0.01, eps=1e-8,
+                                   want_count=True, mode=mode)
+        else:
+            ctx.expand_inverse(F, B, pooled, ik.feat_uoff, ik.inverse, out)
+            R = ctx.backward_dedup(F, B, gout, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F,
+                                   U, M, touched, feat_roff, grad_rows, tables=d_tabs, adagrad_state=d_state,
+                                   lr=0.01, eps=1e-8, want_count=True, mode=mode)
+        torch.cuda.synchronize()
+        results.append((R, touched[:R].clone(), feat_roff.clone(), grad_rows[:R].clone(), d_tabs, d_state, out))
+    a, b = results
+    assert a[0] == b[0]
+    for x, y in zip(a[1:4], b[1:4]):
+        assert torch.equal(x, y)
+    for x, y in zip(a[4] + a[5], b[4] + b[5]):
+        assert torch.equal(x, y)
+    assert torch.equal(a[6], b[6])
+    tr, fr, gr = orc.backward_kjt(F, B, synth.make_grad_out(w, 0), batch.values, batch.offsets, mode=mode)
+    assert a[0] == len(tr) and np.array_equal(b[1].cpu().numpy(), tr)
+    gu.assert_close_f32(gu.out_to_f64(b[3]), gr, "planned grad_rows")
+
+
+def test_backward_apply_needs_a_plan(ctx, recd):
+    batch = synth.batch_from_lists([[[1], [2]]])
+    values, offsets, ik = gu.gpu_build(ctx, batch)   # a build invalidates any plan
+    with pytest.raises(recd.RecdError) as e:
+        ctx.backward_apply(torch.zeros(1, 2, 8, device="cuda"), torch.zeros(2, 8, device="cuda"))
+    assert e.value.status == recd.RECD_EINVAL
+    # an IKJT without ids: the plan is empty, apply reports no rows
+    batch = synth.batch_from_lists([[[], []]])
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    feat_roff = torch.full((2,), -7, dtype=torch.int64, device="cuda")
+    ctx.backward_plan(1, 2, 8, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [5], ik.U, 0, None, feat_roff)
+    assert ctx.backward_apply(torch.zeros(1, 2, 8, device="cuda"), None, want_count=True) == 0
+    assert feat_roff.cpu().tolist() == [0, 0]
+
+
 def test_backward_mode_errors(ctx, recd):
     batch = synth.batch_from_lists([[[1], [2]]])
     values, offsets, ik = gu.gpu_build(ctx, batch)
