@@ -809,7 +809,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B}, F={w.F}, mean session {w.S}, rows={w.rows}, D={w.D}, "
                                f"{w.table_dtype} tables; step = build_ikjt + pooled_lookup_unique + "
-                               f"expand_inverse" + (" + backward_dedup with fused row-wise Adagrad"
+                               f"expand_inverse" + ((" + backward_plan / backward_apply" if getattr(args, "planned", True)
+                                                      else " + backward_dedup") + " with fused row-wise Adagrad"
                                                      + ("" if args.store_grad else " (gradient rows consumed in registers, not stored)")
                                                      if need_backward else ""),
                    "batches_rotated": len(P.batches)},
