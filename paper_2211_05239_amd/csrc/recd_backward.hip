@@ -1549,8 +1549,8 @@ extern "C" recd_status recd_backward_apply(recd_ctx *ctx, recd_pooling mode, con
     hipStream_t st = ctx->stream;
     const BwdWs w = carve_bwd(ctx->ws, n_lists, M_cap, F, D);
     RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_plan_a, 0));
-    RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_plan_b, 0));
     if (pl.empty) {
+        RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_plan_b, 0));
         hipLaunchKernelGGL(k_no_rows, dim3(1), dim3(64), 0, st, F, pl.feat_roff, w.list_off_b);
         RECD_HIP(ctx, hipGetLastError());
         if (host_R) {
@@ -1590,6 +1590,8 @@ extern "C" recd_status recd_backward_apply(recd_ctx *ctx, recd_pooling mode, con
         a.div_off = mode == RECD_POOL_MEAN ? pl.u_offsets : nullptr;
         RECD_TRY(recd_launch_segsum(ctx, a));
     }
+    // step B's grouping may still be running next to the sum above
+    RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_plan_b, 0));
     RECD_TRY(sum_rows(ctx, w, pl.ps_b, M_cap, M_cap, w.g_u, D, grad_rows, pl.touched_rows, fused ? &oa : nullptr,
                       nullptr));
     if (tables && !fused) {
