@@ -421,8 +421,9 @@ recd_status recd_last_ikjt_counts(recd_ctx *ctx, int64_t *host_U_M);
  *    recd_backward_apply makes the stream wait for the plan and runs the two segment sums (and the
  *    optimizer) exactly as call 5 / call 15 would: same kernels, same results bit for bit.
  *    Between the two calls the context's workspace holds the plan: no other call that uses the
- *    workspace (builders, backward calls, a validation pass) may come in between — calls 2, 3, 4 and
- *    recd_last_ikjt_counts may; the IKJT arrays, touched_rows and feat_roff must stay as they are.
+ *    workspace (builders, other backward calls, the sequence lookups) may come in between: such a call
+ *    is safe (its kernels go behind the plan's) but drops the plan.  Calls 2, 3, 4 and
+ *    recd_last_ikjt_counts may come in between; the IKJT arrays, touched_rows and feat_roff must stay as they are.
  *    recd_backward_apply returns RECD_EINVAL if no valid plan exists.  mode: RECD_POOL_SUM or
  *    RECD_POOL_MEAN.  Arguments as in call 5. */
 recd_status recd_backward_plan(recd_ctx *ctx, int F, int64_t B, int D, const int32_t *inverse,

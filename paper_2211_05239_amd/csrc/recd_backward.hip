@@ -966,6 +966,7 @@ BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D, bool w
 {
     WsCarver c(base);
     BwdWs w;
+    (void)c.take<char>(1024);  // the head of the workspace stays with the validation passes' flags
     const int64_t n_max = n_lists > M_cap ? n_lists : M_cap;
     int64_t u_cap = M_cap + F < n_lists ? M_cap + F : n_lists;
     w.a = carve_sort(c, n_lists, false);
@@ -1514,6 +1515,7 @@ extern "C" recd_status recd_backward_plan(recd_ctx *ctx, int F, int64_t B, int D
     }
     RECD_HIP(ctx, hipEventRecord(ctx->ev_plan_a, sa));
     RECD_HIP(ctx, hipEventRecord(ctx->ev_plan_b, sb));
+    pl.pending = true;
     pl.valid = true;
     return RECD_OK;
 }
@@ -1551,6 +1553,7 @@ extern "C" recd_status recd_backward_apply(recd_ctx *ctx, recd_pooling mode, con
     RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_plan_a, 0));
     if (pl.empty) {
         RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_plan_b, 0));
+        pl.pending = false;
         hipLaunchKernelGGL(k_no_rows, dim3(1), dim3(64), 0, st, F, pl.feat_roff, w.list_off_b);
         RECD_HIP(ctx, hipGetLastError());
         if (host_R) {
@@ -1592,6 +1595,7 @@ extern "C" recd_status recd_backward_apply(recd_ctx *ctx, recd_pooling mode, con
     }
     // step B's grouping may still be running next to the sum above
     RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_plan_b, 0));
+    pl.pending = false;
     RECD_TRY(sum_rows(ctx, w, pl.ps_b, M_cap, M_cap, w.g_u, D, grad_rows, pl.touched_rows, fused ? &oa : nullptr,
                       nullptr));
     if (tables && !fused) {

@@ -31,6 +31,14 @@ recd_status recd_check_rows(recd_ctx *ctx, int F, const int64_t *rows)
 
 recd_status recd_reserve(recd_ctx *ctx, size_t bytes)
 {
+    // Every call that is about to use the workspace comes through here first.  A plan that was never
+    // applied may still be running on the side streams, in the same memory: the caller's kernels go
+    // behind it.
+    if (ctx->plan.pending) {
+        RECD_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_plan_a, 0));
+        RECD_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_plan_b, 0));
+        ctx->plan.pending = false;
+    }
     if (bytes <= ctx->ws_bytes)
         return RECD_OK;
     // Growing: earlier kernels may still use the old block; a backward plan lives in it.

@@ -22,6 +22,9 @@ struct recd_ctx {
     const void *built_inverse = nullptr, *built_u_values = nullptr;  // outputs of that build
     struct BackwardPlan {
         bool valid = false, empty = false, wide = false;
+        // the side streams may still be working in the workspace: set by recd_backward_plan, cleared
+        // once the context's stream has been made to wait for both of the plan's events
+        bool pending = false;
         int F = 0, D = 0, row_bits = 0;
         int64_t B = 0, U_cap = 0, M_cap = 0;
         const void *ks_a = nullptr;

@@ -295,6 +295,7 @@ recd_status sequence_gather(recd_ctx *ctx, int F, int D, recd_dtype table_dt, re
                             void *out, bool stream_out)
 {
     RECD_TRY(recd_reserve(ctx, 256 + (size_t)(F + 1) * sizeof(int64_t)));
+    ctx->plan.valid = false;  // the position bounds below overwrite the workspace a backward plan would live in
     int64_t *pb = reinterpret_cast<int64_t *>(ctx->ws);
     hipLaunchKernelGGL(k_seq_bounds, dim3((unsigned)(F / 256 + 1)), dim3(256), 0, ctx->stream, offsets,
                        list_off, lists_per_feature, F, pb);

@@ -611,6 +611,37 @@ def test_backward_apply_needs_a_plan(ctx, recd):
     assert feat_roff.cpu().tolist() == [0, 0]
 
 
+def test_abandoned_plan_is_waited_for(ctx, recd):
+    """A plan that is never applied may still be running on the side streams when the next call wants
+    the workspace: that call's kernels go behind it.  Several build + plan rounds without a
+    synchronisation, then a planned backward, against the one-call form on a fresh context."""
+    w = synth.scaled(synth.WORKLOADS["cfg5"], F=8, B=2048, rows=30_000, D=64)
+    F, B, D = w.F, w.B, w.D
+    batches = [synth.make_batch(w, i) for i in range(3)]
+    dev = [(gu.to_dev(b.values), gu.to_dev(b.offsets), gu.DeviceIKJT(F, B, b.N)) for b in batches]
+    gout = gu.to_dev(synth.make_grad_out(w, 0))
+    Mmax = max(b.N for b in batches)
+    touched = torch.zeros(Mmax, dtype=torch.int64, device="cuda")
+    feat_roff = torch.zeros(F + 1, dtype=torch.int64, device="cuda")
+    grad_rows = torch.zeros(Mmax, D, device="cuda")
+    for rnd in range(4):
+        for (values, offsets, ik) in dev:
+            ctx.build_ikjt(F, B, values, offsets, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff)
+            U, M = ctx.last_ikjt_counts()
+            ctx.backward_plan(F, B, D, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F, U, M,
+                              touched, feat_roff)
+    R = ctx.backward_apply(gout, grad_rows, want_count=True)   # the plan of the last batch
+    values, offsets, ik = dev[-1]
+    c2 = recd.Context(0)
+    t2, f2, g2 = torch.zeros_like(touched), torch.zeros_like(feat_roff), torch.zeros_like(grad_rows)
+    R2 = c2.backward_dedup(F, B, gout, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F, U, M,
+                           t2, f2, g2, want_count=True)
+    torch.cuda.synchronize()
+    c2.close()
+    assert R == R2 and torch.equal(touched[:R], t2[:R]) and torch.equal(feat_roff, f2)
+    assert torch.equal(grad_rows[:R], g2[:R])
+
+
 def test_backward_mode_errors(ctx, recd):
     batch = synth.batch_from_lists([[[1], [2]]])
     values, offsets, ik = gu.gpu_build(ctx, batch)
