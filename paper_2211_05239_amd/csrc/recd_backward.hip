@@ -255,33 +255,46 @@ __global__ __launch_bounds__(256) void k_keys_ids(const int64_t *__restrict__ u_
                                                   uint32_t *__restrict__ pos_list = nullptr)
 {
     const int s = threadIdx.x % SG;
-    const int64_t u = (int64_t)blockIdx.x * (256 / SG) + threadIdx.x / SG;
-    const int64_t U = feat_uoff[F];
-    if (u == 0 && s == 0) {
+    const int per_block = blockDim.x / SG;
+    int64_t U = feat_uoff[F];
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
         // never write past the caller's capacity; n_out[1] tells the host that M_cap was too small
         const int64_t M = u_offsets[U];
         n_out[0] = M < M_cap ? M : M_cap;
         n_out[1] = M > M_cap ? 1 : 0;
     }
-    if (u >= U || u >= lists_cap)
-        return;
-    int lo = 0, hi = F;  // feature of u: feat_uoff[f] <= u < feat_uoff[f+1]
-    while (hi - lo > 1) {
-        const int mid = (lo + hi) >> 1;
-        if (feat_uoff[mid] <= u)
-            lo = mid;
-        else
-            hi = mid;
+    if (U > lists_cap)
+        U = lists_cap;
+    // the grid is sized by the caller's bound on U and strides, so any bound gives the same keys
+    for (int64_t u = (int64_t)blockIdx.x * per_block + threadIdx.x / SG; u < U; u += (int64_t)gridDim.x * per_block) {
+        int lo = 0, hi = F;  // feature of u: feat_uoff[f] <= u < feat_uoff[f+1]
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (feat_uoff[mid] <= u)
+                lo = mid;
+            else
+                hi = mid;
+        }
+        const KeyT fkey = (KeyT)lo << row_bits;
+        const int64_t j0 = u_offsets[u];
+        const int64_t j1 = u_offsets[u + 1] < M_cap ? u_offsets[u + 1] : M_cap;
+        for (int64_t j = j0 + s; j < j1; j += SG) {
+            keys[j] = fkey | (KeyT)u_values[j];
+            pay[j] = pay_positions ? (uint32_t)j : (uint32_t)u;  // source row of the later sum: g_emb[j] or g_u[u]
+            if (pos_list)
+                pos_list[j] = (uint32_t)u;
+        }
     }
-    const KeyT fkey = (KeyT)lo << row_bits;
-    const int64_t j0 = u_offsets[u];
-    const int64_t j1 = u_offsets[u + 1] < M_cap ? u_offsets[u + 1] : M_cap;
-    for (int64_t j = j0 + s; j < j1; j += SG) {
-        keys[j] = fkey | (KeyT)u_values[j];
-        pay[j] = pay_positions ? (uint32_t)j : (uint32_t)u;  // source row of the later sum: g_emb[j] or g_u[u]
-        if (pos_list)
-            pos_list[j] = (uint32_t)u;
-    }
+}
+
+// Blocks of k_keys_ids for a caller's bound on U (at least one; never more than the lists there are).
+static unsigned keys_ids_blocks(int64_t U_cap, int64_t n_lists, int SG, int block)
+{
+    int64_t lists = U_cap < n_lists ? U_cap : n_lists;
+    if (lists < 1)
+        lists = 1;
+    const int per_block = block / SG;
+    return (unsigned)((lists + per_block - 1) / per_block);
 }
 
 // Weighted lookup: the sort carried the position j of every entry.  Replace it by the entry's
@@ -1340,7 +1353,7 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
     uint32_t *ps_b = nullptr;
     {
         constexpr int SG = 16;
-        const unsigned kb = (unsigned)((n_lists + (256 / SG) - 1) / (256 / SG));
+        const unsigned kb = keys_ids_blocks(U_cap, n_lists, SG, 256);
         if (!wide) {
             uint32_t *k0 = static_cast<uint32_t *>(w.b.k0), *k1 = static_cast<uint32_t *>(w.b.k1), *ks;
             hipLaunchKernelGGL((k_keys_ids<uint32_t, SG>), dim3(kb), dim3(256), 0, side, u_values,
@@ -1478,7 +1491,8 @@ extern "C" recd_status recd_backward_plan(recd_ctx *ctx, int F, int64_t B, int D
         // step A's grouping on the second side stream
         {
             uint32_t *k0 = static_cast<uint32_t *>(w.a.k0), *k1 = static_cast<uint32_t *>(w.a.k1), *ks, *ps;
-            hipLaunchKernelGGL(k_keys_rows, dim3((unsigned)((n_lists + 255) / 256)), dim3(256), 0, sa, inverse,
+            hipLaunchKernelGGL(k_keys_rows, dim3((unsigned)((n_lists + 255) / 256)),
+                               dim3(256), 0, sa, inverse,
                                feat_uoff, B, n_lists, k0, w.a.p0, w.a.n_dev);
             RECD_TRY(radix_sort_pairs<uint32_t>(ctx, sa, k0, w.a.p0, k1, w.a.p1, w.a.n_dev, n_lists, bits_a,
                                                 w.a.hist, w.a.bsum, &ks, &ps));
@@ -1489,7 +1503,7 @@ extern "C" recd_status recd_backward_plan(recd_ctx *ctx, int F, int64_t B, int D
         // step B's grouping on the first
         {
             constexpr int SG = 16;
-            const unsigned kb = (unsigned)((n_lists + (256 / SG) - 1) / (256 / SG));
+            const unsigned kb = keys_ids_blocks(U_cap, n_lists, SG, 256);
             if (!pl.wide) {
                 uint32_t *k0 = static_cast<uint32_t *>(w.b.k0), *k1 = static_cast<uint32_t *>(w.b.k1), *ks, *ps;
                 hipLaunchKernelGGL((k_keys_ids<uint32_t, SG>), dim3(kb), dim3(256), 0, sb, u_values, u_offsets,
