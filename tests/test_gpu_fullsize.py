@@ -148,6 +148,69 @@ def test_cfg5_training_step_full(recd):
     ctx.close()
 
 
+def test_cfg5_bench_step_full(recd):
+    """Two consecutive steps exactly as bench.py issues them: build without a host count, lookup
+    sized by the previous step's U, expand, U and M read back while those run, planned backward
+    with the fused update and no stored gradient rows.  Integer outputs in full; the expanded rows
+    and the tables after both steps on sampled features, where the oracle runs both steps too (the
+    second step looks up the rows the first one updated)."""
+    w = synth.WORKLOADS["cfg5"]
+    F, B, D = w.F, w.B, w.D
+    batches = [synth.make_batch(w, i) for i in (1, 2)]
+    tabs = _device_tables(w, torch.float32)
+    sample = (3, 63)
+    host_tab = {f: tabs[f].cpu().numpy().copy() for f in sample}   # the oracle's own fp32 copy, updated by the oracle
+    host_state = {f: np.zeros(w.rows) for f in sample}
+    g = torch.Generator(device="cuda")
+    g.manual_seed(7)
+    grad_out = torch.empty(F, B, D, dtype=torch.float32, device="cuda")
+    grad_out.normal_(0.0, 0.01, generator=g)
+    gout_host = {f: grad_out[f:f + 1].cpu().numpy() for f in sample}
+    state = [torch.zeros(w.rows, device="cuda") for _ in range(F)]
+    Nmax = max(b.N for b in batches)
+    ctx = recd.Context(0, workspace_hint_bytes=recd.workspace_bytes(F, B, Nmax, D))
+    pooled = torch.zeros(F * B, D, device="cuda")
+    out = torch.zeros(F, B, D, device="cuda")
+    touched = torch.zeros(Nmax, dtype=torch.int64, device="cuda")
+    feat_roff = torch.zeros(F + 1, dtype=torch.int64, device="cuda")
+    u_hint = F * B
+    for step, batch in enumerate(batches):
+        values, offsets = gu.to_dev(batch.values), gu.to_dev(batch.offsets)
+        ik = gu.DeviceIKJT(F, B, batch.N)
+        ctx.build_ikjt(F, B, values, offsets, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff)
+        ctx.pooled_lookup_unique(tabs, ik.u_values, ik.u_offsets, ik.feat_uoff, u_hint, pooled)
+        ctx.expand_inverse(F, B, pooled, ik.feat_uoff, ik.inverse, out)
+        U, M = ctx.last_ikjt_counts()
+        u_hint = max(U, 1)
+        ctx.backward_plan(F, B, D, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F, U, M,
+                          touched, feat_roff)
+        ctx.backward_apply(grad_out, None, tables=tabs, adagrad_state=state, lr=0.01, eps=1e-8)
+        torch.cuda.synchronize()
+        ik.U, ik.M = U, M
+        ref = orc.build_ikjt(F, B, batch.values, batch.offsets)
+        assert (U, M) == (int(ref[3][-1]), len(ref[0]))
+        for name, got, r in zip(("u_values", "u_offsets", "inverse", "feat_uoff"), ik.numpy(), ref):
+            assert np.array_equal(got, r), (step, name)
+        fr = feat_roff.cpu().numpy()
+        tr = touched[:fr[-1]].cpu().numpy()
+        for f in sample:
+            v_f, o_f = _feature_slice(batch, f)
+            uv_f, uo_f, inv_f, fu_f = orc.build_ikjt(1, B, v_f, o_f)
+            # forward of this step on the table as the previous step left it
+            ref_out = orc.expand_inverse(1, B, orc.pooled_lookup([host_tab[f]], "f32", uv_f, uo_f, fu_f), fu_f, inv_f)
+            gu.assert_close_f32(gu.out_to_f64(out[f:f + 1]), ref_out, f"step {step}: expanded feature {f}")
+            tr_f, _, gr_f = orc.backward_dedup(1, B, gout_host[f], inv_f, fu_f, uv_f, uo_f)
+            assert np.array_equal(tr_f, tr[fr[f]:fr[f + 1]]), (step, f)
+            w_new, m_new = orc.rowwise_adagrad(gr_f, host_tab[f][tr_f].astype(np.float64), host_state[f][tr_f],
+                                               0.01, 1e-8)
+            host_tab[f][tr_f] = w_new.astype(np.float32)   # stored as fp32, as the tables are
+            host_state[f][tr_f] = m_new
+            gu.assert_close_f32(tabs[f].cpu().numpy().astype(np.float64), host_tab[f].astype(np.float64),
+                                f"step {step}: table {f}")
+            gu.assert_close_f32(state[f].cpu().numpy().astype(np.float64), host_state[f], f"step {step}: state {f}")
+    ctx.close()
+
+
 def _run_sequence(recd, w, batch_index, sample_features):
     """Unpooled path at full size: every output row against the non-deduplicated lookup (bit for
     bit), sampled features against the oracle (exact: the path only copies)."""
