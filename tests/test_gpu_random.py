@@ -1,5 +1,7 @@
 """Randomised differential test: every entry point on randomly drawn shapes, dtypes, duplication
 patterns and groupings, against the CPU oracle (same bars as the fixed-shape parity tests)."""
+import os
+
 import numpy as np
 import pytest
 import torch
@@ -52,7 +54,8 @@ def _draw(seed):
     return rng, F, B, D, dt, rows, batch, tabs, [0] + cuts
 
 
-@pytest.mark.parametrize("seed", range(24))
+# RECD_RANDOM_SEEDS=<n> draws more configurations for a longer run
+@pytest.mark.parametrize("seed", range(int(os.environ.get("RECD_RANDOM_SEEDS", "24"))))
 def test_random_configuration(ctx, recd, seed):
     rng, F, B, D, dt, rows, batch, tabs, groups = _draw(seed)
     N = batch.N
