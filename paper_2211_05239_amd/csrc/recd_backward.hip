@@ -129,8 +129,13 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const uint32_t radix = 1u << dbits;
     const int64_t n = count_of(n_dev, n_host);
-    const int64_t base = (int64_t)blockIdx.x * kTile;
-    if (base >= n)
+    // Blocks go to the XCDs in turn; every XCD takes a contiguous eighth of the tiles, so that the
+    // short runs that neighbouring tiles append to one digit's output meet in one L2 and leave it
+    // as whole lines.
+    const int tiles_per_xcd = (ntiles + 7) / 8;
+    const int tile = (int)(blockIdx.x % 8) * tiles_per_xcd + (int)(blockIdx.x / 8);
+    const int64_t base = (int64_t)tile * kTile;
+    if (tile >= ntiles || base >= n)
         return;  // whole block: nothing in this tile
     // digit bases = exclusive scan of the digit totals (two digits per thread), plus this tile's
     // offset inside the digit
@@ -140,9 +145,9 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_scatter(
         uint32_t total;
         const uint32_t e = block_excl_scan_u32(t0 + t1, total);
         if (d0 < radix)
-            s_base[d0] = e + hist_scanned[(int64_t)d0 * ntiles + blockIdx.x];
+            s_base[d0] = e + hist_scanned[(int64_t)d0 * ntiles + tile];
         if (d1 < radix)
-            s_base[d1] = e + t0 + hist_scanned[(int64_t)d1 * ntiles + blockIdx.x];
+            s_base[d1] = e + t0 + hist_scanned[(int64_t)d1 * ntiles + tile];
     }
     for (int i = tid; i < W * kRadixMax; i += kSortThreads)
         (&s_run[0][0])[i] = 0;
@@ -218,7 +223,7 @@ recd_status radix_sort_pairs(recd_ctx *ctx, hipStream_t st, KeyT *k0, uint32_t *
         hipLaunchKernelGGL((k_sort_hist<KeyT>), dim3(ntiles), dim3(kSortThreads), 0, st, ka, n_dev,
                            n_cap, shift, dbits, hist, ntiles);
         hipLaunchKernelGGL(k_sort_rowscan, dim3(1u << dbits), dim3(256), 0, st, hist, ntiles, bsum);
-        hipLaunchKernelGGL((k_sort_scatter<KeyT>), dim3(ntiles), dim3(kSortThreads), 0, st, ka, pa, kb,
+        hipLaunchKernelGGL((k_sort_scatter<KeyT>), dim3(8 * ((ntiles + 7) / 8)), dim3(kSortThreads), 0, st, ka, pa, kb,
                            pb, n_dev, n_cap, shift, dbits, hist, bsum, ntiles);
         KeyT *tk = ka; ka = kb; kb = tk;
         uint32_t *tp = pa; pa = pb; pb = tp;
