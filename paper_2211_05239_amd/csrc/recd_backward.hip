@@ -80,12 +80,18 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_hist(const KeyT *__restri
                                                             uint32_t *__restrict__ hist, int ntiles)
 {
     __shared__ uint32_t s_h[kRadixMax];
+    // every XCD takes a contiguous eighth of the tiles (see k_sort_scatter): the counters that
+    // neighbouring tiles write lie next to each other in a digit's row
+    const int tiles_per_xcd = (ntiles + 7) / 8;
+    const int tile = (int)(blockIdx.x % 8) * tiles_per_xcd + (int)(blockIdx.x / 8);
+    if (tile >= ntiles)
+        return;
     const uint32_t radix = 1u << dbits;
     for (uint32_t d = threadIdx.x; d < radix; d += kSortThreads)
         s_h[d] = 0;
     __syncthreads();
     const int64_t n = count_of(n_dev, n_host);
-    const int64_t base = (int64_t)blockIdx.x * kTile;
+    const int64_t base = (int64_t)tile * kTile;
 #pragma unroll
     for (int k = 0; k < kIPT; k++) {
         const int64_t i = base + k * kSortThreads + threadIdx.x;
@@ -94,7 +100,7 @@ __global__ __launch_bounds__(kSortThreads) void k_sort_hist(const KeyT *__restri
     }
     __syncthreads();
     for (uint32_t d = threadIdx.x; d < radix; d += kSortThreads)
-        hist[(int64_t)d * ntiles + blockIdx.x] = s_h[d];
+        hist[(int64_t)d * ntiles + tile] = s_h[d];
 }
 
 // one block per digit: in-place exclusive scan of the digit's row of tile counts; row total out
@@ -220,7 +226,7 @@ recd_status radix_sort_pairs(recd_ctx *ctx, hipStream_t st, KeyT *k0, uint32_t *
     const int passes = (bits + 8) / 9;
     const int dbits = passes > 0 ? (bits + passes - 1) / passes : 0;
     for (int shift = 0; shift < bits && ntiles > 0; shift += dbits) {
-        hipLaunchKernelGGL((k_sort_hist<KeyT>), dim3(ntiles), dim3(kSortThreads), 0, st, ka, n_dev,
+        hipLaunchKernelGGL((k_sort_hist<KeyT>), dim3(8 * ((ntiles + 7) / 8)), dim3(kSortThreads), 0, st, ka, n_dev,
                            n_cap, shift, dbits, hist, ntiles);
         hipLaunchKernelGGL(k_sort_rowscan, dim3(1u << dbits), dim3(256), 0, st, hist, ntiles, bsum);
         hipLaunchKernelGGL((k_sort_scatter<KeyT>), dim3(8 * ((ntiles + 7) / 8)), dim3(kSortThreads), 0, st, ka, pa, kb,
