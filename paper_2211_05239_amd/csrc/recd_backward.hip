@@ -619,7 +619,19 @@ __global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const
     for (int w = 0; w < VPL; w++)
         piece[w] = w * LPR + r < p.pieces;
 
-    for (int64_t t0 = (int64_t)blockIdx.x * per_block; t0 < R; t0 += (int64_t)gridDim.x * per_block) {
+    // The segments are ordered by (feature, row) and their entries name rows of the source array that
+    // belong to the same feature.  Blocks go to the XCDs in turn; every XCD takes a contiguous eighth
+    // of the segments and its blocks stride through it side by side, so that the source rows an XCD
+    // gathers at one time are a few features' worth and stay in its L2.  (The grid is a multiple
+    // of 8 blocks.)
+    // The few cut segments of the FINALIZE pass are dealt to the blocks in turn instead.
+    const int64_t groups = (R + per_block - 1) / per_block;
+    const int64_t per_xcd = (groups + 7) / 8;
+    const int64_t g_first = FINALIZE ? 0 : (int64_t)(blockIdx.x % 8) * per_xcd;
+    const int64_t g_count = FINALIZE ? groups : (per_xcd < groups - g_first ? per_xcd : groups - g_first);
+    const int64_t g_step = FINALIZE ? gridDim.x : gridDim.x / 8;
+    for (int64_t gi = FINALIZE ? blockIdx.x : blockIdx.x / 8; gi < g_count; gi += g_step) {
+        const int64_t t0 = (g_first + gi) * per_block;
         const int64_t k = t0 + wv * G + g;
         int64_t t = k;       // destination segment
         int64_t start = 0;
@@ -1132,8 +1144,9 @@ recd_status sum_rows(recd_ctx *ctx, const BwdWs &w, const uint32_t *ps, int64_t 
     const int64_t cap = (int64_t)ctx->num_cu * 64;
     if (nblk > cap)
         nblk = cap;
-    if (nblk < 1)
-        nblk = 1;
+    nblk = (nblk + 7) / 8 * 8;  // the kernel deals its blocks to 8 XCDs
+    if (nblk < 8)
+        nblk = 8;
     const dim3 block(256);
     auto launch_rows = [&](auto fin, auto wt, unsigned nb, hipStream_t stream) {
         constexpr bool FIN = decltype(fin)::value, WT = decltype(wt)::value;
@@ -1173,7 +1186,7 @@ recd_status sum_rows(recd_ctx *ctx, const BwdWs &w, const uint32_t *ps, int64_t 
         c.weights = pay_w;
     }
     RECD_TRY(recd_launch_segsum(ctx, c));
-    launch_rows(std::true_type(), std::false_type(), (unsigned)ctx->num_cu, side);
+    launch_rows(std::true_type(), std::false_type(), (unsigned)((ctx->num_cu + 7) / 8 * 8), side);
     RECD_HIP(ctx, hipGetLastError());
     RECD_HIP(ctx, hipEventRecord(ctx->ev_join, side));
     // 2. short segments summed and updated
