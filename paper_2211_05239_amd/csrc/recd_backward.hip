@@ -622,15 +622,16 @@ __global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const
     // The segments are ordered by (feature, row) and their entries name rows of the source array that
     // belong to the same feature.  Blocks go to the XCDs in turn; every XCD takes a contiguous eighth
     // of the segments and its blocks stride through it side by side, so that the source rows an XCD
-    // gathers at one time are a few features' worth and stay in its L2.  (The grid is a multiple
-    // of 8 blocks.)
-    // The few cut segments of the FINALIZE pass are dealt to the blocks in turn instead.
+    // gathers at one time are a few features' worth and stay in its L2.
+    // The few cut segments of the FINALIZE pass, and any grid that is not a multiple of 8 blocks, are
+    // dealt to the blocks in turn instead.
+    const bool by_xcd = !FINALIZE && gridDim.x % 8 == 0;
     const int64_t groups = (R + per_block - 1) / per_block;
     const int64_t per_xcd = (groups + 7) / 8;
-    const int64_t g_first = FINALIZE ? 0 : (int64_t)(blockIdx.x % 8) * per_xcd;
-    const int64_t g_count = FINALIZE ? groups : (per_xcd < groups - g_first ? per_xcd : groups - g_first);
-    const int64_t g_step = FINALIZE ? gridDim.x : gridDim.x / 8;
-    for (int64_t gi = FINALIZE ? blockIdx.x : blockIdx.x / 8; gi < g_count; gi += g_step) {
+    const int64_t g_first = by_xcd ? (int64_t)(blockIdx.x % 8) * per_xcd : 0;
+    const int64_t g_count = by_xcd ? (per_xcd < groups - g_first ? per_xcd : groups - g_first) : groups;
+    const int64_t g_step = by_xcd ? gridDim.x / 8 : gridDim.x;
+    for (int64_t gi = by_xcd ? blockIdx.x / 8 : blockIdx.x; gi < g_count; gi += g_step) {
         const int64_t t0 = (g_first + gi) * per_block;
         const int64_t k = t0 + wv * G + g;
         int64_t t = k;       // destination segment
