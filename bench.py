@@ -380,6 +380,14 @@ def run_workload(torch, recd, synth, w, args, need_backward, detail=True, pipeli
     if R is not None:
         res["gbs"]["lookup_unique_compulsory"] = res["bytes"]["lookup_unique_compulsory"] / lookup_ms / 1e6
         res["gbs"]["kjt_compulsory"] = res["bytes"]["kjt_compulsory"] / kjt_ms / 1e6
+        # lookup + expand together (the region the 60 %-of-peak target is stated for): compulsory
+        # algorithmic bytes, and the HBM traffic rocprofv3 measured for the two kernels
+        res["gbs"]["lookup_plus_expand_compulsory"] = ((res["bytes"]["lookup_unique_compulsory"] + exp_bytes)
+                                                       / (lookup_ms + expand_ms) / 1e6)
+        t_l, t_e = measured_traffic(w.name), measured_traffic(w.name, "expand")
+        if t_l is not None and t_e is not None:
+            res["bytes"]["lookup_plus_expand_traffic"] = t_l + t_e
+            res["gbs"]["lookup_plus_expand_traffic"] = (t_l + t_e) / (lookup_ms + expand_ms) / 1e6
     if need_backward:
         res["backward_speedup_vs_kjt"] = res["kjt_backward_ms"] / res["backward_ms"]
     res["speedup_vs_kjt"] = kjt_ms / (lookup_ms + expand_ms)
@@ -755,13 +763,14 @@ def cpu_baseline_parallel(torch, P, max_seconds=20.0):
             "seconds": wall, "sample": f"features 0..{n_feat - 1} of batch 0, one task per feature on {cores} threads"}
 
 
-def measured_traffic(workload_name):
-    """HBM bytes per launch of the unique-lookup kernel, from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE and WRITE_SIZE, calibrated against a plain copy); None if there is none."""
+def measured_traffic(workload_name, kernel="lookup_unique"):
+    """HBM bytes per launch of the unique-lookup (or the expand) kernel, from the committed
+    rocprofv3 --pmc summary (FETCH_SIZE and WRITE_SIZE, calibrated against a plain copy); None if
+    there is none."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload_name}.md")
     try:
         for line in open(path):
-            if line.startswith("lookup_unique_traffic_bytes:"):
+            if line.startswith(f"{kernel}_traffic_bytes:"):
                 return float(line.split(":")[1])
     except OSError:
         pass
