@@ -12,6 +12,7 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++20", "-fPIC", "-shared",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-function", "-Wno-pass-failed",
          "-I", os.path.join(ROOT, "include"), "-I", os.path.join(HERE, "csrc")]
+FLAGS += os.environ.get("RECD_EXTRA_HIPCC_FLAGS", "").split()  # e.g. -D switches of an experiment
 
 
 def build(verbose: bool = False) -> str:
