@@ -1086,9 +1086,13 @@ RowSumParams row_params(const BwdWs &w, const uint32_t *ps, const float *pay_w, 
 template <typename KeyT>
 recd_status prepare_rows(recd_ctx *ctx, hipStream_t st, const BwdWs &w, const SortSet &set, const KeyT *ks,
                          int64_t n_cap, int64_t seg_bound, int row_bits, int F, int64_t *touched_rows,
-                         int64_t *feat_roff)
+                         int64_t *feat_roff, hipEvent_t numbered = nullptr)
 {
     RECD_TRY(number_segments<KeyT>(ctx, st, w, set, ks, n_cap, row_bits, F, touched_rows, feat_roff));
+    // the sum of the short segments needs nothing of what follows: whoever waits for `numbered`
+    // instead of the end of this stream's work starts it one kernel earlier
+    if (numbered)
+        RECD_HIP(ctx, hipEventRecord(numbered, st));
     const RowSumParams rp = row_params(w, nullptr, nullptr, nullptr, 4, nullptr);
     int64_t fblk = (seg_bound + 255) / 256;
     if (fblk > (int64_t)ctx->num_cu * 8)
@@ -1536,7 +1540,7 @@ extern "C" recd_status recd_backward_plan(recd_ctx *ctx, int F, int64_t B, int D
                 RECD_TRY(radix_sort_pairs<uint32_t>(ctx, sb, k0, w.b.p0, k1, w.b.p1, w.b.n_dev, M_cap, bits_b,
                                                     w.b.hist, w.b.bsum, &ks, &ps));
                 RECD_TRY(prepare_rows<uint32_t>(ctx, sb, w, w.b, ks, M_cap, M_cap, row_bits, F, touched_rows,
-                                                feat_roff));
+                                                feat_roff, ctx->ev_plan_rows));
                 pl.ps_b = ps;
             } else {
                 uint64_t *k0 = static_cast<uint64_t *>(w.b.k0), *k1 = static_cast<uint64_t *>(w.b.k1), *ks;
@@ -1546,7 +1550,7 @@ extern "C" recd_status recd_backward_plan(recd_ctx *ctx, int F, int64_t B, int D
                 RECD_TRY(radix_sort_pairs<uint64_t>(ctx, sb, k0, w.b.p0, k1, w.b.p1, w.b.n_dev, M_cap, bits_b,
                                                     w.b.hist, w.b.bsum, &ks, &ps));
                 RECD_TRY(prepare_rows<uint64_t>(ctx, sb, w, w.b, ks, M_cap, M_cap, row_bits, F, touched_rows,
-                                                feat_roff));
+                                                feat_roff, ctx->ev_plan_rows));
                 pl.ps_b = ps;
             }
         }
@@ -1632,11 +1636,13 @@ extern "C" recd_status recd_backward_apply(recd_ctx *ctx, recd_pooling mode, con
         a.div_off = mode == RECD_POOL_MEAN ? pl.u_offsets : nullptr;
         RECD_TRY(recd_launch_segsum(ctx, a));
     }
-    // step B's grouping may still be running next to the sum above
-    RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_plan_b, 0));
-    pl.pending = false;
+    // Step B's grouping may still be running next to the sum above.  The cut of the long segments,
+    // the last kernel of that chain, is needed only by the chunk passes, which sum_rows enqueues on
+    // the same side stream behind it; the stream joins that side stream at the end of sum_rows.
+    RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_plan_rows, 0));
     RECD_TRY(sum_rows(ctx, w, pl.ps_b, M_cap, M_cap, w.g_u, D, grad_rows, pl.touched_rows, fused ? &oa : nullptr,
                       nullptr));
+    pl.pending = false;  // the stream now waits for everything the plan enqueued
     if (tables && !fused) {
         for (int f0 = 0; f0 < F; f0 += RECD_F_PER_LAUNCH) {
             OptPtrs ptrs;

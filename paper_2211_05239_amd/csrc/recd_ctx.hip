@@ -189,6 +189,7 @@ recd_status recd_create(recd_ctx **out, int device, void *hip_stream, size_t wor
     ok = ok && hipEventCreateWithFlags(&ctx->ev_built, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&ctx->ev_plan_a, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&ctx->ev_plan_b, hipEventDisableTiming) == hipSuccess;
+    ok = ok && hipEventCreateWithFlags(&ctx->ev_plan_rows, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&ctx->ev_fork, hipEventDisableTiming) == hipSuccess;
     ok = ok && hipEventCreateWithFlags(&ctx->ev_join, hipEventDisableTiming) == hipSuccess;
     void *p = nullptr;
@@ -242,6 +243,8 @@ recd_status recd_destroy(recd_ctx *ctx)
         (void)hipEventDestroy(ctx->ev_plan_a);
     if (ctx->ev_plan_b)
         (void)hipEventDestroy(ctx->ev_plan_b);
+    if (ctx->ev_plan_rows)
+        (void)hipEventDestroy(ctx->ev_plan_rows);
     if (ctx->ev_fork)
         (void)hipEventDestroy(ctx->ev_fork);
     if (ctx->ev_join)

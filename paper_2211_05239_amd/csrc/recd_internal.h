@@ -18,7 +18,8 @@ struct recd_ctx {
     // runs on two side streams from the end of the last build on, next to the forward calls.
     hipStream_t side_stream2 = nullptr;
     hipEvent_t ev_built = nullptr;                    // end of the most recent plain / weighted build
-    hipEvent_t ev_plan_a = nullptr, ev_plan_b = nullptr;
+    hipEvent_t ev_plan_a = nullptr, ev_plan_b = nullptr;   // end of each of the plan's two chains
+    hipEvent_t ev_plan_rows = nullptr;  // step B's segments numbered (before the cut of the long ones)
     const void *built_inverse = nullptr, *built_u_values = nullptr;  // outputs of that build
     struct BackwardPlan {
         bool valid = false, empty = false, wide = false;
