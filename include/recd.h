@@ -405,9 +405,10 @@ recd_status recd_backward_dedup_weighted(recd_ctx *ctx, int F, int64_t B, int D,
                                          float eps, int64_t *host_R);
 
 /* Counts of the most recent call 1 / call 16 on this context: host_U_M[0] = U, host_U_M[1] = M.
- *    A builder called with host_U_M = NULL publishes its counts to the host by itself when it
- *    finishes on the GPU; this call waits for that publication only, not for work enqueued after the
- *    build.  It lets a caller enqueue the lookup and the expand (which need no host-side count: any
+ *    A builder called with host_U_M = NULL publishes its counts to the host by itself as soon as
+ *    they are final on the GPU (its last kernel, which copies the ids, may still be running: calls
+ *    that read the IKJT must be enqueued on the context's stream, as always); this call waits for
+ *    that publication only, not for work enqueued after the build.  It lets a caller enqueue the lookup and the expand (which need no host-side count: any
  *    max_lists sizes the launch, see call 2) behind the build and read U and M, which the backward's
  *    bounds want, while they run.  Blocks the calling thread; RECD_EINVAL before the first build. */
 recd_status recd_last_ikjt_counts(recd_ctx *ctx, int64_t *host_U_M);

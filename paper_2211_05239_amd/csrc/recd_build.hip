@@ -361,7 +361,8 @@ __global__ __launch_bounds__(kScanBlock) void k_number(const int64_t *__restrict
                                                        int32_t *__restrict__ src_of,
                                                        int64_t *__restrict__ u_offsets,
                                                        int64_t *__restrict__ feat_uoff,
-                                                       int64_t *__restrict__ counts)
+                                                       int64_t *__restrict__ counts,
+                                                       int64_t *mailbox, int64_t seq)
 {
     const int64_t l = (int64_t)blockIdx.x * kScanBlock + threadIdx.x;
     int64_t first = 0, flen = 0, head = -1, b = -1, f = 0, my_rep = -1;
@@ -406,6 +407,16 @@ __global__ __launch_bounds__(kScanBlock) void k_number(const int64_t *__restrict
             feat_uoff[F] = U;
             counts[0] = U;
             counts[1] = M;
+            if (mailbox) {
+                // U and M are final here: the host may have them while the last builder kernel still
+                // copies ids (values first, the sequence number last, each visible to the host
+                // before the next)
+                mailbox[0] = U;
+                mailbox[1] = M;
+                __threadfence_system();
+                mailbox[7] = seq;
+                __threadfence_system();
+            }
         }
     }
 }
@@ -856,7 +867,7 @@ void insert_lists(recd_ctx *ctx, hipStream_t st, const SlotWs &w, int F, int64_t
 // every slot, prefix of the slot counts per table (uoff) and, from the lengths that `offsets`
 // gives, the position of every slot's ids (u_off); counts = {slots, ids}.
 void number_slots(hipStream_t st, const SlotWs &w, int tables, int64_t B, const int64_t *offsets,
-                  int64_t *u_off, int64_t *uoff)
+                  int64_t *u_off, int64_t *uoff, int64_t *mailbox = nullptr, int64_t seq = 0)
 {
     const int64_t n = (int64_t)tables * B;
     const unsigned nblk = (unsigned)((n + kScanBlock - 1) / kScanBlock);
@@ -867,7 +878,7 @@ void number_slots(hipStream_t st, const SlotWs &w, int tables, int64_t B, const 
                        (int64_t)nblk);
     hipLaunchKernelGGL(k_number, dim3(nblk), dim3(kScanBlock), 0, st, offsets, B, n, tables, w.table, mask,
                        w.slot_of, w.bs_cnt, w.bs_len, w.bs_head, w.rep, w.number, w.src_of, u_off, uoff,
-                       w.counts);
+                       w.counts, mailbox, seq);
 }
 
 unsigned copy_blocks_for(const recd_ctx *ctx, int64_t n_lists)
@@ -907,12 +918,22 @@ static recd_status build_plain(recd_ctx *ctx, int F, int64_t B, int64_t N, const
     w.counts = ctx->build_counts_dev;  // {U, M}: outlives the workspace's reuse by later calls
     int64_t *counts = w.counts;
     hipStream_t st = ctx->stream;
+    bool published = false;
 
     if (n_lists == 0) {
         hipLaunchKernelGGL(k_empty_ikjt, dim3(1), dim3(256), 0, st, F, u_offsets, feat_uoff, counts);
     } else {
         insert_lists(ctx, st, w, F, B, values, offsets, weights);
-        number_slots(st, w, F, B, offsets, u_offsets, feat_uoff);
+        // without a host destination the counts go to the mailbox from the kernel that computes
+        // them (no kernel of its own between the build and what the caller enqueues next)
+        int64_t *mailbox = nullptr;
+        int64_t seq = 0;
+        if (!host_U_M && ctx->mailbox) {
+            mailbox = ctx->mailbox_dev + 8;
+            seq = ++ctx->build_seq;
+            published = true;
+        }
+        number_slots(st, w, F, B, offsets, u_offsets, feat_uoff, mailbox, seq);
         const unsigned inv_blocks = (unsigned)((n_lists + 255) / 256);
         hipLaunchKernelGGL((k_emit<16>), dim3(inv_blocks + copy_blocks_for(ctx, n_lists)), dim3(256), 0, st,
                            values, offsets, B, n_lists, w.rep, w.number, w.src_of, u_offsets, counts,
@@ -927,8 +948,10 @@ static recd_status build_plain(recd_ctx *ctx, int F, int64_t B, int64_t N, const
     if (host_U_M) {
         ctx->build_published = false;  // fetched here; recd_last_ikjt_counts reads the device array
         RECD_TRY(recd_fetch_scalars(ctx, counts, 2, host_U_M));
+    } else if (published) {
+        ctx->build_published = true;
     } else {
-        RECD_TRY(recd_publish_build_counts(ctx));
+        RECD_TRY(recd_publish_build_counts(ctx));  // the empty batch, or no mailbox
     }
     return RECD_OK;
 }
