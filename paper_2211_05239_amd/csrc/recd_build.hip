@@ -436,10 +436,19 @@ __global__ __launch_bounds__(256) void k_emit(const int64_t *__restrict__ values
                                               int64_t *__restrict__ u_values,
                                               int32_t *__restrict__ inverse, unsigned inv_blocks,
                                               const uint32_t *__restrict__ wbits = nullptr,
-                                              uint32_t *__restrict__ u_wbits = nullptr)
+                                              uint32_t *__restrict__ u_wbits = nullptr,
+                                              unsigned fill_blocks = 0, uint64_t *fill = nullptr,
+                                              int64_t fill_n = 0)
 {
-    if (blockIdx.x < inv_blocks) {
-        const int64_t l = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (blockIdx.x < fill_blocks) {
+        // the hash tables are no longer needed: leave them empty for the next build
+        for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < fill_n; i += (int64_t)fill_blocks * 256)
+            fill[i] = kEmpty;
+        return;
+    }
+    const unsigned bid = blockIdx.x - fill_blocks;
+    if (bid < inv_blocks) {
+        const int64_t l = (int64_t)bid * 256 + threadIdx.x;
         if (l < n_lists) {
             const int64_t f = l / B;
             inverse[l] = number[f * B + rep[l]] - number[f * B];
@@ -448,8 +457,8 @@ __global__ __launch_bounds__(256) void k_emit(const int64_t *__restrict__ values
     }
     const int s = threadIdx.x % SG;
     const int64_t U = counts[0];
-    const int64_t stride = (int64_t)(gridDim.x - inv_blocks) * (256 / SG);
-    for (int64_t u = (int64_t)(blockIdx.x - inv_blocks) * (256 / SG) + threadIdx.x / SG; u < U;
+    const int64_t stride = (int64_t)(gridDim.x - fill_blocks - inv_blocks) * (256 / SG);
+    for (int64_t u = (int64_t)(bid - inv_blocks) * (256 / SG) + threadIdx.x / SG; u < U;
          u += stride) {
         const int64_t l = src_of[u];
         const int64_t start = offsets[l], len = offsets[l + 1] - start;
@@ -849,11 +858,13 @@ void clear_table(hipStream_t st, const SlotWs &w, int tables)
 
 // Lists of a KJT into the per-feature tables: slot_of[l] (or -1 for a follower).
 void insert_lists(recd_ctx *ctx, hipStream_t st, const SlotWs &w, int F, int64_t B,
-                  const int64_t *values, const int64_t *offsets, const uint32_t *wbits = nullptr)
+                  const int64_t *values, const int64_t *offsets, const uint32_t *wbits = nullptr,
+                  bool table_is_empty = false)
 {
     constexpr int SG = 8;
     const int64_t n_lists = (int64_t)F * B;
-    clear_table(st, w, F);
+    if (!table_is_empty)
+        clear_table(st, w, F);
     const int64_t hblocks = (n_lists + (kHashBlock / SG) * kLPG - 1) / ((kHashBlock / SG) * kLPG);
     if (wbits)
         hipLaunchKernelGGL((k_hash_insert<SG, true>), dim3((unsigned)hblocks), dim3(kHashBlock), 0, st, values, wbits,
@@ -923,7 +934,31 @@ static recd_status build_plain(recd_ctx *ctx, int F, int64_t B, int64_t N, const
     if (n_lists == 0) {
         hipLaunchKernelGGL(k_empty_ikjt, dim3(1), dim3(256), 0, st, F, u_offsets, feat_uoff, counts);
     } else {
-        insert_lists(ctx, st, w, F, B, values, offsets, weights);
+        // the context's own tables (kept empty between builds) instead of the workspace's
+        const size_t slots = (size_t)F * w.cap;
+        if (slots > ctx->build_table_slots) {
+            RECD_HIP(ctx, hipStreamSynchronize(st));
+            if (ctx->build_table)
+                RECD_HIP(ctx, hipFree(ctx->build_table));
+            ctx->build_table = nullptr;
+            ctx->build_table_slots = 0;
+            const size_t want = slots + slots / 4;
+            void *tp = nullptr;
+            if (hipMalloc(&tp, want * sizeof(uint64_t)) != hipSuccess) {
+                (void)hipGetLastError();
+                return recd_fail(ctx, RECD_ENOMEM, "hash tables of %zu bytes: allocation failed", want * sizeof(uint64_t));
+            }
+            ctx->build_table = static_cast<uint64_t *>(tp);
+            ctx->build_table_slots = want;
+            ctx->table_clean = false;
+        }
+        if (!ctx->table_clean) {
+            const int64_t all = (int64_t)ctx->build_table_slots;
+            hipLaunchKernelGGL(k_fill_u64, dim3(4096), dim3(256), 0, st, ctx->build_table, all, kEmpty);
+        }
+        w.table = ctx->build_table;
+        ctx->table_clean = false;  // until this build's last kernel is enqueued
+        insert_lists(ctx, st, w, F, B, values, offsets, weights, true);
         // without a host destination the counts go to the mailbox from the kernel that computes
         // them (no kernel of its own between the build and what the caller enqueues next)
         int64_t *mailbox = nullptr;
@@ -935,9 +970,13 @@ static recd_status build_plain(recd_ctx *ctx, int F, int64_t B, int64_t N, const
         }
         number_slots(st, w, F, B, offsets, u_offsets, feat_uoff, mailbox, seq);
         const unsigned inv_blocks = (unsigned)((n_lists + 255) / 256);
-        hipLaunchKernelGGL((k_emit<16>), dim3(inv_blocks + copy_blocks_for(ctx, n_lists)), dim3(256), 0, st,
-                           values, offsets, B, n_lists, w.rep, w.number, w.src_of, u_offsets, counts,
-                           u_values, inverse, inv_blocks, weights, u_weights);
+        const unsigned fill_blocks = (unsigned)((slots + 4095) / 4096 < 2048 ? (slots + 4095) / 4096 : 2048);
+        hipLaunchKernelGGL((k_emit<16>), dim3(fill_blocks + inv_blocks + copy_blocks_for(ctx, n_lists)), dim3(256), 0,
+                           st, values, offsets, B, n_lists, w.rep, w.number, w.src_of, u_offsets, counts,
+                           u_values, inverse, inv_blocks, weights, u_weights, fill_blocks, ctx->build_table,
+                           (int64_t)slots);
+        RECD_HIP(ctx, hipGetLastError());
+        ctx->table_clean = true;
     }
     RECD_HIP(ctx, hipGetLastError());
     ctx->build_valid = true;

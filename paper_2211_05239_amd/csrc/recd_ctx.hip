@@ -255,6 +255,8 @@ recd_status recd_destroy(recd_ctx *ctx)
         (void)hipFree(ctx->group_map_dev);
     if (ctx->build_counts_dev)
         (void)hipFree(ctx->build_counts_dev);
+    if (ctx->build_table)
+        (void)hipFree(ctx->build_table);
     if (ctx->host_pinned)
         (void)hipHostFree(ctx->host_pinned);
     if (ctx->mailbox)

@@ -34,6 +34,13 @@ struct recd_ctx {
         int64_t *touched_rows = nullptr, *feat_roff = nullptr;
         const char *ws = nullptr;   // the workspace the plan lives in must still be the context's
     } plan;
+    // Hash tables of the plain / weighted builder: memory of their own that is all "empty" whenever
+    // no build is running on the stream, because the builder's last kernel clears what the build
+    // used (so no clearing kernel stands at the head of the next build).  table_clean is false
+    // while that cannot be relied on (first use, or a build that failed half way).
+    uint64_t *build_table = nullptr;
+    size_t build_table_slots = 0;
+    bool table_clean = false;
     char *ws = nullptr;          // device workspace
     size_t ws_bytes = 0;
     int64_t *host_pinned = nullptr;  // 8 x int64 pinned staging for scalar results
