@@ -95,8 +95,10 @@ typedef enum {
 
 /* Create a context bound to `device` and to `hip_stream` (a hipStream_t passed as void*; NULL =
  * the default stream).  `workspace_hint_bytes` pre-allocates the device workspace (0 = grow on
- * demand; growth synchronises the stream and reallocates).  The context is owned by the caller
- * and released with recd_destroy. */
+ * demand; growth synchronises the stream and reallocates).  Besides the workspace a context keeps
+ * the hash tables of calls 1 and 16 (8 bytes for each of F * cap slots, cap = the power of two that
+ * holds 2 * B): allocated by the first such call of a size, which synchronises the stream, and
+ * held until recd_destroy.  The context is owned by the caller and released with recd_destroy. */
 recd_status recd_create(recd_ctx **out, int device, void *hip_stream, size_t workspace_hint_bytes);
 recd_status recd_destroy(recd_ctx *ctx);
 recd_status recd_set_option(recd_ctx *ctx, recd_option opt, int64_t value);
