@@ -165,7 +165,9 @@ recd_status recd_kjt_pooled_lookup(recd_ctx *ctx, int F, int64_t B, int D, recd_
  *      G_f[r,:] = sum over the positions j (ascending) of feature f's unique ids with
  *                 u_values[j] = r of g_u[list of j, :]
  *    computed as stable radix sorts followed by segment sums in sorted order: no floating-point
- *    atomics, bit-identical from run to run.
+ *    atomics, bit-identical from run to run.  (How the sum of a table row with many entries is
+ *    associated depends on its number of entries and on whether the bound M_cap reaches 2^23; on
+ *    nothing else.)
  *    grad_out: device fp32 [F, B, D].  rows: HOST int64 [F] table sizes (bounds the sort key).
  *    U_cap, M_cap: host upper bounds of U and M (F*B and N always are; the exact values, as
  *    returned by recd_build_ikjt, avoid idle work).

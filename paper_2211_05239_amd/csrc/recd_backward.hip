@@ -499,7 +499,7 @@ __global__ __launch_bounds__(256) void k_adagrad(const float *__restrict__ grad_
 // few hot rows by thousands).  Here a group of LPR lanes owns a whole segment: G = 64/LPR segments
 // advance side by side in one wave, each lane carries up to four 16-byte pieces of the row, no
 // cross-lane fold is needed, and the Adagrad update of the destination row follows in the same
-// lanes.  Segments longer than 64 entries are only recorded; the block-cooperative gather-sum
+// lanes.  Segments longer than the cut (32 or 64 entries, see long_seg_cut) are only recorded; the block-cooperative gather-sum
 // kernel sums them afterwards.  Order of additions inside a segment: ascending position.
 struct RowSumParams {
     const float *table;        // g_u [U, D]
@@ -510,12 +510,13 @@ struct RowSumParams {
     float *out;                // grad_rows [R, D] or nullptr
     int D;
     int pieces;                // D / 4
-    // segments longer than 64 entries are cut into chunks (work items) whose partial sums another
+    // segments longer than long_seg entries are cut into chunks (work items) whose partial sums another
     // kernel computes; lseg_* describe the cut segments, item_* the chunks
     int64_t *long_count;       // [0] cut segments, [1] chunks
     int32_t *lseg_t, *lseg_first, *lseg_n;
     int64_t *item_start, *item_end;
     const float *partials;     // [chunks, D] (k_long_finalize)
+    int long_seg;              // segments with more entries than this are the cut ones
 };
 
 // Tail of a row-gradient segment held by a lane group: acc = the segment's sum (piece w of lane r).
@@ -572,7 +573,7 @@ __device__ __forceinline__ void finish_segment(const RowSumParams &p, const OptA
     }
 }
 
-// Segments longer than 64 entries are cut into chunks of 256 entries, or larger ones if that would
+// Segments longer than p.long_seg entries are cut into chunks of 256 entries, or larger ones if that would
 // give more than 64 chunks.  The cut depends on the segment's length only; the order in which
 // segments and chunks are listed does not matter for the sums.
 __global__ __launch_bounds__(256) void k_find_long(const RowSumParams p)
@@ -582,7 +583,7 @@ __global__ __launch_bounds__(256) void k_find_long(const RowSumParams p)
          k += (int64_t)gridDim.x * blockDim.x) {
         const int64_t start = p.seg_start[k], end = p.seg_start[k + 1];
         const int64_t len = end - start;
-        if (len <= 64)
+        if (len <= p.long_seg)
             continue;
         int64_t ch = 256;
         if ((len + ch - 1) / ch > 64)
@@ -601,7 +602,7 @@ __global__ __launch_bounds__(256) void k_find_long(const RowSumParams p)
     }
 }
 
-// FINALIZE = false: segments of at most 64 entries are summed here (longer ones are skipped).
+// FINALIZE = false: segments of at most p.long_seg entries are summed here (longer ones are skipped).
 // FINALIZE = true: the "segments" are the cut ones; their entries are the chunk partial sums, in
 // chunk order.
 // WT (with FINALIZE = false): entry j contributes pay_w[j] times its source row.
@@ -646,7 +647,7 @@ __global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const
                 start = p.seg_start[k];
                 const int64_t end = p.seg_start[k + 1];
                 const int64_t len = end - start;
-                n = len <= 64 ? (int)len : 0;  // longer segments were cut into chunks by k_find_long
+                n = len <= p.long_seg ? (int)len : 0;  // longer segments were cut into chunks by k_find_long
             }
         }
         const bool mine = n > 0;  // uniform inside the lane group
@@ -975,8 +976,19 @@ struct BwdWs {
     uint32_t *pos_list;  // weighted lookup: unique list of every position of u_values
     float *pay_w;        // weighted lookup: weight of every sorted entry of step B
     float *emb;          // max pooling: one masked gradient row per position of u_values [M, D]
+    int long_seg;        // step B: segments with more entries are cut into chunks
     size_t bytes;
 };
+
+// Step B's lane groups walk a segment entry by entry, eight segments to a wave, so a wave lasts as
+// long as its longest segment; longer segments go to the block-cooperative chunk passes on the side
+// stream.  Where to cut (measured at 2.2 M entries: 0.847 ms per step with 64, 0.838 with 32, 0.836
+// with 24 or 16; at 35 M entries, where the chunk passes are the larger part: 4.28 ms with 64, 4.55
+// with 32).
+static int long_seg_cut(int64_t n_entries)
+{
+    return n_entries >= ((int64_t)8 << 20) ? 64 : 32;
+}
 
 SortSet carve_sort(WsCarver &c, int64_t n, bool wide_keys)
 {
@@ -1014,8 +1026,10 @@ BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D, bool w
     w.list_off_b = c.take<int64_t>(2);
     w.seg_start_b = c.take<int64_t>(M_cap + 1);
     w.seg_feat = c.take<int32_t>(M_cap);
-    // segments longer than 64 entries: at most n/65 of them, cut into at most n/256 + n/65 chunks
-    const int64_t lseg_cap = n_max / 65 + 16, item_cap = n_max / 256 + n_max / 65 + 16;
+    // cut segments (more than long_seg entries): at most n/(long_seg+1) of them, in at most
+    // n/256 + n/(long_seg+1) chunks
+    w.long_seg = long_seg_cut(M_cap);
+    const int64_t lseg_cap = n_max / (w.long_seg + 1) + 16, item_cap = n_max / 256 + n_max / (w.long_seg + 1) + 16;
     w.lseg_t = c.take<int32_t>(lseg_cap);
     w.lseg_first = c.take<int32_t>(lseg_cap);
     w.lseg_n = c.take<int32_t>(lseg_cap);
@@ -1078,6 +1092,7 @@ RowSumParams row_params(const BwdWs &w, const uint32_t *ps, const float *pay_w, 
     rp.item_start = w.item_start;
     rp.item_end = w.item_end;
     rp.partials = w.partials;
+    rp.long_seg = w.long_seg;
     return rp;
 }
 
@@ -1127,7 +1142,7 @@ recd_status segment_and_sum_lists(recd_ctx *ctx, const BwdWs &w, const SortSet &
     return recd_launch_segsum(ctx, a);
 }
 
-// Step B after prepare_rows: short segments (at most 64 entries) by one lane group each, the cut
+// Step B after prepare_rows: short segments (at most long_seg entries) by one lane group each, the cut
 // ones by the block-cooperative kernel on the side stream next to them; optimizer fused.
 recd_status sum_rows(recd_ctx *ctx, const BwdWs &w, const uint32_t *ps, int64_t n_cap, int64_t seg_bound,
                      const void *table, int D, void *out, int64_t *touched_rows, const OptAdagrad *opt,
@@ -1183,7 +1198,7 @@ recd_status sum_rows(recd_ctx *ctx, const BwdWs &w, const uint32_t *ps, int64_t 
     c.offsets = w.item_start;
     c.ends = w.item_end;
     c.count_dev = w.long_count + 1;
-    c.lists_bound = n_cap / 256 + n_cap / 65 + 1;
+    c.lists_bound = n_cap / 256 + n_cap / (w.long_seg + 1) + 1;
     c.out = w.partials;
     c.stream = side;
     if (pay_w) {  // the chunk partials carry the weights; adding the partials does not
