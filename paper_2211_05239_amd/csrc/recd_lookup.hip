@@ -181,7 +181,8 @@ template <int LPR, int VPL, int TT, typename IdxT, int NL, int US, int MODE = PO
 __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL],
                                            const char *const *bases, const IdxT *values,
                                            const int64_t *starts, const int *ns, uint32_t row_bytes,
-                                           int lane, int g, const float *weights = nullptr)
+                                           int lane, int g, const float *weights = nullptr,
+                                           const uint32_t *pre_id = nullptr)
 {
     constexpr int EPV = Elem<TT>::per_vec;
     constexpr int G = 64 / LPR;
@@ -191,7 +192,8 @@ __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL]
     int nmax = 0;
 #pragma unroll
     for (int j = 0; j < NL; j++) {
-        my_id[j] = lane < ns[j] ? (uint32_t)values[starts[j] + lane] : 0u;
+        // pre_id: the caller fetched this lane's id earlier (while the previous chunk's rows were in flight)
+        my_id[j] = pre_id ? pre_id[j] : (lane < ns[j] ? (uint32_t)values[starts[j] + lane] : 0u);
         my_wt[j] = (WT && lane < ns[j]) ? weights[starts[j] + lane] : 0.f;
         nmax = ns[j] > nmax ? ns[j] : nmax;
     }
@@ -380,10 +382,31 @@ void k_segsum(const SegSumParams p)
 #pragma unroll
                 for (int i = 0; i < NACC; i++)
                     acc[0][i] = pool_identity<MODE>();
-                for (int64_t base = start + (int64_t)wv * kChunk; base < end; base += kWaves * kChunk) {
-                    const int n = (int)(end - base < kChunk ? end - base : kChunk);
-                    add_chunks<LPR, VPL, TT, IdxT, 1, UNR, MODE, SITE == SITE_GRAD_STREAM>(acc, &table, values, &base, &n,
-                                                                                           row_bytes, lane, g, p.weights);
+                if constexpr (kWaves == 1) {
+                    // one wave walks the whole list: the ids of the next chunk are fetched before
+                    // the rows of this one, so their latency hides behind the row loads
+                    int64_t base = start;
+                    int n = (int)(end - base < kChunk ? end - base : kChunk);
+                    uint32_t cur = lane < n ? (uint32_t)values[base + lane] : 0u;
+                    for (;;) {
+                        const int64_t nbase = base + kChunk;
+                        const bool more = nbase < end;
+                        const int nn = more ? (int)(end - nbase < kChunk ? end - nbase : kChunk) : 0;
+                        const uint32_t nxt = (more && lane < nn) ? (uint32_t)values[nbase + lane] : 0u;
+                        add_chunks<LPR, VPL, TT, IdxT, 1, UNR, MODE, SITE == SITE_GRAD_STREAM>(
+                            acc, &table, values, &base, &n, row_bytes, lane, g, p.weights, &cur);
+                        if (!more)
+                            break;
+                        base = nbase;
+                        n = nn;
+                        cur = nxt;
+                    }
+                } else {
+                    for (int64_t base = start + (int64_t)wv * kChunk; base < end; base += kWaves * kChunk) {
+                        const int n = (int)(end - base < kChunk ? end - base : kChunk);
+                        add_chunks<LPR, VPL, TT, IdxT, 1, UNR, MODE, SITE == SITE_GRAD_STREAM>(
+                            acc, &table, values, &base, &n, row_bytes, lane, g, p.weights);
+                    }
                 }
                 fold_groups(acc[0]);
                 if (g == 0) {
