@@ -409,14 +409,18 @@ void k_segsum(const SegSumParams p)
                     }
                 }
                 fold_groups(acc[0]);
-                if (g == 0) {
+                if constexpr (kWaves == 1) {
+                    finish_row(j, acc[0]);  // no other wave's partial to add
+                } else {
+                    if (g == 0) {
 #pragma unroll
-                    for (int w = 0; w < VPL; w++)
+                        for (int w = 0; w < VPL; w++)
 #pragma unroll
-                        for (int i = 0; i < EPV; i++)
-                            s_part[nb][wv][(w * LPR + r) * EPV + i] = acc[0][w * EPV + i];
+                            for (int i = 0; i < EPV; i++)
+                                s_part[nb][wv][(w * LPR + r) * EPV + i] = acc[0][w * EPV + i];
+                    }
+                    batch[nb++] = j;
                 }
-                batch[nb++] = j;
             }
             if (nb == LL || (j == cnt && nb > 0)) {
                 __syncthreads();
