@@ -65,7 +65,7 @@ def parse_args():
     ap.add_argument("--no-pipeline", dest="pipeline", action="store_false",
                     help="skip the extra run with the builder on a second stream (reported beside the step, "
                          "never as `value`)")
-    ap.add_argument("--tune", type=int, default=0, help="RECD_OPT_TUNE_SEGSUM value (0 = automatic)")
+    ap.add_argument("--tune", type=int, default=0, help="launch-shape override of the gather-sum kernel (tuning runs; 0 = automatic)")
     ap.add_argument("--calib-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (calibrates hardware byte counters)")
     return ap.parse_args()
@@ -102,7 +102,7 @@ class DeviceProblem:
         ws = recd.workspace_bytes(F, B, Nmax, D)
         self.ctx = recd.Context(0, workspace_hint_bytes=ws)
         if tune:
-            self.ctx.set_option(recd.RECD_OPT_TUNE_SEGSUM, tune)
+            self.ctx.set_option(recd._OPT_INTERNAL_TUNE_SEGSUM, tune)
         # unique-list counts of every batch (U, M): size the backward outputs by the largest M
         self.counts = [self.build(i) for i in range(n_batches)]
         if need_backward:

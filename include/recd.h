@@ -82,11 +82,13 @@ typedef enum {
     RECD_OPT_WEAK_HASH = 2, /* test hook, value != 0: the builder hashes a list to its length only,
                                so that unequal lists collide constantly and only the exact list
                                comparison keeps them apart.  Results must not change.            */
-    RECD_OPT_TUNE_SEGSUM = 3 /* tuning knob of the gather-sum kernel's launch shape, 0 = automatic:
-                               value = lists per block (4, 8 or 16) + 10000 * block generations per
-                               CU (< 100) + 1000000 * (1 = no XCD-aware block mapping); the hundreds
-                               and thousands digits must be 0.  Results must not change (the
-                               summation order of a list never depends on it).                     */
+    RECD_OPT_LONG_SEGMENT_CUT = 4 /* backward, step "sum per table row": a table row named by more
+                               than this many entries of the unique lists is summed in chunks by
+                               whole blocks instead of by one lane group.  16, 32 (default), 64 or
+                               128.  The cut is part of how such a row's sum is associated, so the
+                               low bits of its gradient depend on this option (and on nothing else
+                               the caller passes); larger values suit batches without duplication,
+                               where most of the work is in long rows.                            */
 } recd_option;
 
 /* Largest number of features per call and largest row size in bytes (D * element size). */
@@ -166,8 +168,8 @@ recd_status recd_kjt_pooled_lookup(recd_ctx *ctx, int F, int64_t B, int D, recd_
  *                 u_values[j] = r of g_u[list of j, :]
  *    computed as stable radix sorts followed by segment sums in sorted order: no floating-point
  *    atomics, bit-identical from run to run.  (How the sum of a table row with many entries is
- *    associated depends on its number of entries and on whether the bound M_cap reaches 2^23; on
- *    nothing else.)
+ *    associated depends on its number of entries and on RECD_OPT_LONG_SEGMENT_CUT; on nothing
+ *    else: in particular not on the bounds U_cap and M_cap.)
  *    grad_out: device fp32 [F, B, D].  rows: HOST int64 [F] table sizes (bounds the sort key).
  *    U_cap, M_cap: host upper bounds of U and M (F*B and N always are; the exact values, as
  *    returned by recd_build_ikjt, avoid idle work).
@@ -181,6 +183,9 @@ recd_status recd_kjt_pooled_lookup(recd_ctx *ctx, int F, int64_t B, int D, recd_
  *      m[r] += mean_d G[r,d]^2 ;  W[r,d] -= lr * G[r,d] / (sqrt(m[r]) + eps)
  *    tables: HOST array of F device pointers to fp32 [rows_f, D], updated in place;
  *    adagrad_state: HOST array of F device pointers to fp32 [rows_f], updated in place.
+ *    Each feature needs a table and an accumulator array of its own: repeated pointers in either
+ *    array are refused (RECD_EINVAL), since the rows of different features are updated at the
+ *    same time.
  *    host_R: optional host int64[1]; if non-NULL the call synchronises and stores R. */
 recd_status recd_backward_dedup(recd_ctx *ctx, int F, int64_t B, int D, const float *grad_out,
                                 const int32_t *inverse, const int64_t *feat_uoff,

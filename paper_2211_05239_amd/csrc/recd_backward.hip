@@ -15,6 +15,7 @@
 // among the wave's earlier keys, and a prefix over the four waves completes the stable rank.
 #include "recd_internal.h"
 
+#include <algorithm>
 #include <type_traits>
 
 namespace {
@@ -981,14 +982,12 @@ struct BwdWs {
 };
 
 // Step B's lane groups walk a segment entry by entry, eight segments to a wave, so a wave lasts as
-// long as its longest segment; longer segments go to the block-cooperative chunk passes on the side
-// stream.  Where to cut (measured at 2.2 M entries: 0.847 ms per step with 64, 0.838 with 32, 0.836
-// with 24 or 16; at 35 M entries, where the chunk passes are the larger part: 4.28 ms with 64, 4.55
-// with 32).
-static int long_seg_cut(int64_t n_entries)
-{
-    return n_entries >= ((int64_t)8 << 20) ? 64 : 32;
-}
+// long as its longest segment; segments with more entries than the context's cut
+// (RECD_OPT_LONG_SEGMENT_CUT, default 32) go to the block-cooperative chunk passes on the side
+// stream.  Measured at 2.2 M entries: 0.847 ms per step with 64, 0.838 with 32, 0.836 with 24 or 16;
+// at 35 M entries (no deduplication), where the chunk passes are the larger part: 4.28 ms with 64,
+// 4.55 with 32.
+constexpr int kDefaultLongSeg = 32;
 
 SortSet carve_sort(WsCarver &c, int64_t n, bool wide_keys)
 {
@@ -1011,7 +1010,7 @@ SortSet carve_sort(WsCarver &c, int64_t n, bool wide_keys)
     return s;
 }
 
-BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D, bool with_emb = false)
+BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D, int long_seg, bool with_emb = false)
 {
     WsCarver c(base);
     BwdWs w;
@@ -1028,7 +1027,7 @@ BwdWs carve_bwd(char *base, int64_t n_lists, int64_t M_cap, int F, int D, bool w
     w.seg_feat = c.take<int32_t>(M_cap);
     // cut segments (more than long_seg entries): at most n/(long_seg+1) of them, in at most
     // n/256 + n/(long_seg+1) chunks
-    w.long_seg = long_seg_cut(M_cap);
+    w.long_seg = long_seg;
     const int64_t lseg_cap = n_max / (w.long_seg + 1) + 16, item_cap = n_max / 256 + n_max / (w.long_seg + 1) + 16;
     w.lseg_t = c.take<int32_t>(lseg_cap);
     w.lseg_first = c.take<int32_t>(lseg_cap);
@@ -1223,7 +1222,25 @@ recd_status sum_rows(recd_ctx *ctx, const BwdWs &w, const uint32_t *ps, int64_t 
 
 size_t recd_backward_workspace(int F, int64_t B, int64_t M_cap, int D)
 {
-    return carve_bwd(nullptr, (int64_t)F * B, M_cap, F, D).bytes;
+    return carve_bwd(nullptr, (int64_t)F * B, M_cap, F, D, kDefaultLongSeg).bytes;
+}
+
+// The fused update reads and writes a table row (and its accumulator) once per (feature, row)
+// segment, from different lane groups and two streams at the same time: two features must not name
+// the same table or the same accumulator array.
+static recd_status check_distinct_tables(recd_ctx *ctx, int F, void *const *tables, float *const *state)
+{
+    if (!tables)
+        return RECD_OK;
+    std::vector<const void *> t(tables, tables + F), m(state, state + F);
+    std::sort(t.begin(), t.end());
+    std::sort(m.begin(), m.end());
+    for (int f = 1; f < F; f++)
+        if (t[f] == t[f - 1] || m[f] == m[f - 1])
+            return recd_fail(ctx, RECD_EINVAL,
+                             "tables[] and adagrad_state[] must each hold pairwise distinct pointers "
+                             "(one table per feature)");
+    return RECD_OK;
 }
 
 // Backward of the pooled path (seq = false: grad_out is [F,B,D]) and of the sequence path (seq =
@@ -1279,13 +1296,14 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
         if (tables && (!tables[f] || !adagrad_state[f]))
             return recd_fail(ctx, RECD_EINVAL, "tables[%d] or adagrad_state[%d] is null", f, f);
     }
+    RECD_TRY(check_distinct_tables(ctx, F, tables, adagrad_state));
     RECD_HIP(ctx, hipSetDevice(ctx->device));
     if (ctx->validate && n_lists > 0)
         RECD_TRY(recd_validate_inverse(ctx, F, B, feat_uoff, inverse));
     const bool maxmode = max_tables != nullptr;
     ctx->plan.valid = false;  // this call reuses the workspace a plan would live in
-    RECD_TRY(recd_reserve(ctx, carve_bwd(nullptr, n_lists, M_cap, F, D, maxmode).bytes));
-    const BwdWs w = carve_bwd(ctx->ws, n_lists, M_cap, F, D, maxmode);
+    RECD_TRY(recd_reserve(ctx, carve_bwd(nullptr, n_lists, M_cap, F, D, ctx->long_seg_cut, maxmode).bytes));
+    const BwdWs w = carve_bwd(ctx->ws, n_lists, M_cap, F, D, ctx->long_seg_cut, maxmode);
     hipStream_t st = ctx->stream;
 
     if (n_lists == 0 || M_cap == 0) {
@@ -1503,8 +1521,11 @@ extern "C" recd_status recd_backward_plan(recd_ctx *ctx, int F, int64_t B, int D
     RECD_HIP(ctx, hipSetDevice(ctx->device));
     if (ctx->validate && n_lists > 0)
         RECD_TRY(recd_validate_inverse(ctx, F, B, feat_uoff, inverse));
-    RECD_TRY(recd_reserve(ctx, recd_backward_workspace(F, B, M_cap, D)));
-    const BwdWs w = carve_bwd(ctx->ws, n_lists, M_cap, F, D);
+    // the side streams may start at the end of the build only if nothing on the stream has used the
+    // workspace since (this call's own reservation does not count)
+    const bool ws_idle_since_build = !ctx->ws_used_since_build;
+    RECD_TRY(recd_reserve(ctx, carve_bwd(nullptr, n_lists, M_cap, F, D, ctx->long_seg_cut).bytes));
+    const BwdWs w = carve_bwd(ctx->ws, n_lists, M_cap, F, D, ctx->long_seg_cut);
     recd_ctx::BackwardPlan &pl = ctx->plan;
     pl.F = F;
     pl.B = B;
@@ -1520,7 +1541,8 @@ extern "C" recd_status recd_backward_plan(recd_ctx *ctx, int F, int64_t B, int D
     // Where the side streams may start: at the end of the build that produced this IKJT if it is the
     // context's most recent one, else at the main stream's current position.
     hipEvent_t from = ctx->ev_fork;
-    if (ctx->build_valid && ctx->built_inverse == inverse && ctx->built_u_values == u_values && n_lists > 0)
+    if (ctx->build_valid && ws_idle_since_build && ctx->built_inverse == inverse &&
+        ctx->built_u_values == u_values && n_lists > 0)
         from = ctx->ev_built;
     else
         RECD_HIP(ctx, hipEventRecord(ctx->ev_fork, st));
@@ -1605,9 +1627,10 @@ extern "C" recd_status recd_backward_apply(recd_ctx *ctx, recd_pooling mode, con
     for (int f = 0; f < F && tables; f++)
         if (!tables[f] || !adagrad_state[f])
             return recd_fail(ctx, RECD_EINVAL, "tables[%d] or adagrad_state[%d] is null", f, f);
+    RECD_TRY(check_distinct_tables(ctx, F, tables, adagrad_state));
     RECD_HIP(ctx, hipSetDevice(ctx->device));
     hipStream_t st = ctx->stream;
-    const BwdWs w = carve_bwd(ctx->ws, n_lists, M_cap, F, D);
+    const BwdWs w = carve_bwd(ctx->ws, n_lists, M_cap, F, D, ctx->long_seg_cut);
     RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_plan_a, 0));
     if (pl.empty) {
         RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_plan_b, 0));

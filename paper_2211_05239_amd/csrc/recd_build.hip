@@ -924,6 +924,7 @@ static recd_status build_plain(recd_ctx *ctx, int F, int64_t B, int64_t N, const
         RECD_TRY(recd_validate_kjt_offsets(ctx, F, B, N, offsets));
 
     RECD_TRY(recd_reserve(ctx, recd_build_workspace(F, B)));
+    ctx->ws_used_since_build = false;  // from here on: set again by the next workspace user
     WsCarver c(ctx->ws);
     SlotWs w = carve_slots(c, F, B, n_lists, n_lists);
     w.counts = ctx->build_counts_dev;  // {U, M}: outlives the workspace's reuse by later calls

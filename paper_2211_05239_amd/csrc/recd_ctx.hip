@@ -34,6 +34,7 @@ recd_status recd_reserve(recd_ctx *ctx, size_t bytes)
     // Every call that is about to use the workspace comes through here first.  A plan that was never
     // applied may still be running on the side streams, in the same memory: the caller's kernels go
     // behind it.
+    ctx->ws_used_since_build = true;
     if (ctx->plan.pending) {
         RECD_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_plan_a, 0));
         RECD_HIP(ctx, hipStreamWaitEvent(ctx->stream, ctx->ev_plan_b, 0));
@@ -272,9 +273,16 @@ recd_status recd_set_option(recd_ctx *ctx, recd_option opt, int64_t value)
     switch (opt) {
     case RECD_OPT_VALIDATE: ctx->validate = value != 0; return RECD_OK;
     case RECD_OPT_WEAK_HASH: ctx->weak_hash = value != 0; return RECD_OK;
-    case RECD_OPT_TUNE_SEGSUM:
-        // value = lists_per_block + 10000 * block_generations
-        //         + 1000000 * (1 = never use the XCD-aware mapping)
+    case RECD_OPT_LONG_SEGMENT_CUT:
+        if (value != 16 && value != 32 && value != 64 && value != 128)
+            return recd_fail(ctx, RECD_EINVAL, "RECD_OPT_LONG_SEGMENT_CUT must be 16, 32, 64 or 128");
+        ctx->long_seg_cut = (int)value;
+        ctx->plan.valid = false;  // a plan made with another cut no longer fits the buffers
+        return RECD_OK;
+    default: break;
+    }
+    switch ((int)opt) {
+    case RECD_OPT_INTERNAL_TUNE_SEGSUM:
         ctx->tune_lb = (int)(value % 100);
         ctx->tune_gens = (int)(value / 10000 % 100);
         ctx->tune_flat = (int)(value / 1000000 % 10);
@@ -282,7 +290,7 @@ recd_status recd_set_option(recd_ctx *ctx, recd_option opt, int64_t value)
             (ctx->tune_lb != 0 && ctx->tune_lb != 1 && ctx->tune_lb != 2 && ctx->tune_lb != 4 && ctx->tune_lb != 8 &&
              ctx->tune_lb != 16)) {
             ctx->tune_lb = ctx->tune_gens = ctx->tune_flat = 0;
-            return recd_fail(ctx, RECD_EINVAL, "bad RECD_OPT_TUNE_SEGSUM value");
+            return recd_fail(ctx, RECD_EINVAL, "bad launch-shape override");
         }
         return RECD_OK;
     }

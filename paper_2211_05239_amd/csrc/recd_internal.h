@@ -21,6 +21,13 @@ struct recd_ctx {
     hipEvent_t ev_plan_a = nullptr, ev_plan_b = nullptr;   // end of each of the plan's two chains
     hipEvent_t ev_plan_rows = nullptr;  // step B's segments numbered (before the cut of the long ones)
     const void *built_inverse = nullptr, *built_u_values = nullptr;  // outputs of that build
+    // A call that uses the workspace has been enqueued on the context's stream since that build (set
+    // by recd_reserve, cleared by the builder): a plan must then start at the stream's current
+    // position, not at ev_built, or its side streams would write the workspace under that call.
+    bool ws_used_since_build = true;
+    // Step B of the backward: table rows with more entries than this are cut into chunks that whole
+    // blocks sum (RECD_OPT_LONG_SEGMENT_CUT).
+    int long_seg_cut = 32;
     struct BackwardPlan {
         bool valid = false, empty = false, wide = false;
         // the side streams may still be working in the workspace: set by recd_backward_plan, cleared
@@ -67,6 +74,12 @@ struct recd_ctx {
     std::vector<int32_t> group_map_host;
     std::string err;
 };
+
+// Not part of the public interface: launch-shape override of the gather-sum kernel, used by the
+// tuning runs and by the test that shows results do not depend on the launch shape.
+//   value = lists per block (1, 2, 4, 8 or 16) + 10000 * block generations per CU (< 100)
+//           + 1000000 * (1 = no XCD-aware block mapping); 0 = automatic
+#define RECD_OPT_INTERNAL_TUNE_SEGSUM 1003
 
 recd_status recd_fail(recd_ctx *ctx, recd_status s, const char *fmt, ...);
 // Ids must lie in [0, 2^31): a table the caller describes as larger is refused (rows may be null).

@@ -25,7 +25,10 @@ _lib = C.CDLL(LIB_PATH)
 RECD_OK = 0
 RECD_EINVAL, RECD_ENOMEM, RECD_EHIP, RECD_EBOUNDS, RECD_ECAPACITY = -1, -2, -3, -4, -5
 RECD_F32, RECD_F16, RECD_BF16 = 0, 1, 2
-RECD_OPT_VALIDATE, RECD_OPT_WEAK_HASH, RECD_OPT_TUNE_SEGSUM = 1, 2, 3
+RECD_OPT_VALIDATE, RECD_OPT_WEAK_HASH, RECD_OPT_LONG_SEGMENT_CUT = 1, 2, 4
+# not in the public header: launch-shape override of the gather-sum kernel (tuning runs, and the
+# test that results do not depend on the launch shape)
+_OPT_INTERNAL_TUNE_SEGSUM = 1003
 RECD_POOL_SUM, RECD_POOL_MEAN, RECD_POOL_MAX = 0, 1, 2
 POOLING = {"sum": RECD_POOL_SUM, "mean": RECD_POOL_MEAN, "max": RECD_POOL_MAX}
 

@@ -82,3 +82,28 @@ def assert_close_16(got, ref, what=""):
     bound = 1e-2 * np.abs(ref) + 1e-6
     bad = err > bound
     assert not bad.any(), f"{what}: {bad.sum()} elements beyond 1e-2 relative, max err {err.max()}"
+
+
+def long_sum_depth(n, lane_groups, cut=32):
+    """Largest number of fp32 additions any one term of a table row's gradient passes through when
+    the row has n > cut entries (the backward's chunked two-level sum): the entries are cut into
+    chunks of ch = 256 entries (ceil(n/64) if that would give more than 64 chunks); a chunk is
+    summed by a four-wave block, wave w taking the 64-entry pieces w, w+4, ... and lane group g
+    of `lane_groups` adding the piece's entries g, g+G, ... into one accumulator; then a butterfly
+    over the lane groups, the four wave partials in wave order, and the chunk partials in chunk
+    order."""
+    assert n > cut
+    ch = 256 if (n + 255) // 256 <= 64 else (n + 63) // 64
+    nch = (n + ch - 1) // ch
+    pieces = (ch + 63) // 64
+    per_wave = (pieces + 3) // 4
+    return per_wave * (64 // lane_groups) + int(np.log2(lane_groups)) + 3 + nch
+
+
+def assert_long_sum(got, ref, abs_terms, depth, what=""):
+    """Bar of a long fp32 sum: the stated 1e-5 * (1 + |ref|) or, where it is larger, the first-order
+    worst-case bound of the summation tree, depth * 2^-24 * sum |terms|."""
+    err = np.abs(got - ref)
+    bound = np.maximum(1e-5 * (1.0 + np.abs(ref)), depth * 2.0 ** -24 * abs_terms)
+    bad = err > bound
+    assert not bad.any(), f"{what}: {bad.sum()} elements beyond the bound, max err {err.max()}, bound {bound.min()}"

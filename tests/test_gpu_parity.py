@@ -185,7 +185,7 @@ def test_launch_shape_knob_keeps_results(ctx, recd):
     ref = None
     try:
         for tune in (0, 4, 8, 16, 1000004, 20016):
-            ctx.set_option(recd.RECD_OPT_TUNE_SEGSUM, tune)
+            ctx.set_option(recd._OPT_INTERNAL_TUNE_SEGSUM, tune)
             got = _forward_case(ctx, w, 0)[3:]
             if ref is None:
                 ref = got
@@ -193,10 +193,10 @@ def test_launch_shape_knob_keeps_results(ctx, recd):
                 assert torch.equal(_bits(x), _bits(y)), tune
         for bad in (5, 104, -1, 3000000):
             with pytest.raises(recd.RecdError) as e:
-                ctx.set_option(recd.RECD_OPT_TUNE_SEGSUM, bad)
+                ctx.set_option(recd._OPT_INTERNAL_TUNE_SEGSUM, bad)
             assert e.value.status == recd.RECD_EINVAL
     finally:
-        ctx.set_option(recd.RECD_OPT_TUNE_SEGSUM, 0)
+        ctx.set_option(recd._OPT_INTERNAL_TUNE_SEGSUM, 0)
 
 
 def test_empty_lists_pool_to_zero(ctx):
@@ -407,15 +407,19 @@ def test_backward_skewed_ids(ctx):
     _backward_case(ctx, w, 0)
 
 
-def test_backward_giant_segment(ctx):
+@pytest.mark.parametrize("scale", [1.0, 0.01])
+def test_backward_giant_segment(ctx, scale):
     """One table row named by 20000 different unique lists: its gradient segment is cut into chunks
-    larger than the default (more than 64 default-sized chunks), summed in two levels."""
+    larger than the default (more than 64 default-sized chunks), summed in two levels.  Every other
+    row has one entry and meets the stated bar; the giant row is a sum of 20000 terms that cancel to
+    ~sqrt(20000) times their size, for which fp32 accumulation in any order cannot promise
+    1e-5 * (1 + |ref|): it is held to the worst-case bound of its summation tree."""
     B = 20000
     lists = [[7, 100 + i] for i in range(B)]
     batch = synth.batch_from_lists([lists])
     rows, D = 100 + B, 8
     rng = np.random.default_rng(17)
-    gout = rng.standard_normal((1, B, D)).astype(np.float32)
+    gout = (rng.standard_normal((1, B, D)) * scale).astype(np.float32)
     values, offsets, ik = gu.gpu_build(ctx, batch)
     assert ik.U == B
     touched = torch.zeros(ik.M, dtype=torch.int64, device="cuda")
@@ -427,9 +431,11 @@ def test_backward_giant_segment(ctx):
     tr, fr, gr = orc.backward_dedup(1, B, gout, inv, fu, uv, uo)
     assert R == len(tr) == B + 1 and np.array_equal(touched[:R].cpu().numpy(), tr)
     got = grad_rows[:R].double().cpu().numpy()
-    # the giant row sums 20000 terms of magnitude ~1: fp32 accumulation in chunks stays within the bar
     gu.assert_close_f32(got[1:], gr[1:], "single-entry rows")
-    assert np.all(np.abs(got[0] - gr[0]) <= 1e-5 * np.abs(gout).sum(axis=(0, 1))), "giant row"
+    # rows of D = 8 fp32 elements: two 16-byte pieces, 8 lanes per row, 8 lane groups per wave
+    depth = gu.long_sum_depth(B, lane_groups=8)
+    assert depth == 86
+    gu.assert_long_sum(got[0], gr[0], np.abs(gout.astype(np.float64)).sum(axis=(0, 1)), depth, "giant row")
 
 
 def test_backward_deterministic(ctx):
@@ -640,6 +646,94 @@ def test_abandoned_plan_is_waited_for(ctx, recd):
     c2.close()
     assert R == R2 and torch.equal(touched[:R], t2[:R]) and torch.equal(feat_roff, f2)
     assert torch.equal(grad_rows[:R], g2[:R])
+
+
+def test_plan_after_a_workspace_user_since_the_build(ctx, recd):
+    """build -> one-call backward (no synchronisation) -> plan -> apply on the same IKJT: the one-call
+    backward still works in the workspace when the plan is enqueued, so the plan's side streams must
+    start behind it, not at the end of the build.  Checked against a fresh context."""
+    w = synth.scaled(synth.WORKLOADS["cfg5"], F=8, B=4096, rows=50_000, D=64)
+    F, B, D = w.F, w.B, w.D
+    batch = synth.make_batch(w, 0)
+    values, offsets = gu.to_dev(batch.values), gu.to_dev(batch.offsets)
+    gout = gu.to_dev(synth.make_grad_out(w, 0))
+    ik = gu.DeviceIKJT(F, B, batch.N)
+    for rnd in range(3):
+        ctx.build_ikjt(F, B, values, offsets, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff)
+        U, M = ctx.last_ikjt_counts()
+        t1 = torch.zeros(M, dtype=torch.int64, device="cuda")
+        f1 = torch.zeros(F + 1, dtype=torch.int64, device="cuda")
+        g1 = torch.zeros(M, D, device="cuda")
+        ctx.backward_dedup(F, B, gout, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F, U, M,
+                           t1, f1, g1)
+        t2, f2, g2 = torch.zeros_like(t1), torch.zeros_like(f1), torch.zeros_like(g1)
+        ctx.backward_plan(F, B, D, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F, U, M, t2, f2)
+        R = ctx.backward_apply(gout, g2, want_count=True)
+        c2 = recd.Context(0)
+        t3, f3, g3 = torch.zeros_like(t1), torch.zeros_like(f1), torch.zeros_like(g1)
+        R3 = c2.backward_dedup(F, B, gout, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F, U, M,
+                               t3, f3, g3, want_count=True)
+        torch.cuda.synchronize()
+        c2.close()
+        assert R == R3
+        for t, f, g in ((t1, f1, g1), (t2, f2, g2)):
+            assert torch.equal(t[:R], t3[:R]) and torch.equal(f, f3) and torch.equal(g[:R], g3[:R])
+
+
+def test_backward_refuses_shared_tables(ctx, recd):
+    """The fused update works on all features at once: two features naming one table (or one
+    accumulator array) would race, so the call refuses them."""
+    batch = synth.batch_from_lists([[[1], [2]], [[1], [3]]])
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    gout = torch.zeros(2, 2, 8, device="cuda")
+    touched = torch.zeros(4, dtype=torch.int64, device="cuda")
+    feat_roff = torch.zeros(3, dtype=torch.int64, device="cuda")
+    tab, tab2 = torch.zeros(5, 8, device="cuda"), torch.zeros(5, 8, device="cuda")
+    st, st2 = torch.zeros(5, device="cuda"), torch.zeros(5, device="cuda")
+    for tables, state in (([tab, tab], [st, st2]), ([tab, tab2], [st, st])):
+        with pytest.raises(recd.RecdError) as e:
+            ctx.backward_dedup(2, 2, gout, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [5, 5], ik.U, ik.M,
+                               touched, feat_roff, None, tables=tables, adagrad_state=state, lr=0.01, eps=1e-8)
+        assert e.value.status == recd.RECD_EINVAL
+    ctx.backward_dedup(2, 2, gout, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [5, 5], ik.U, ik.M,
+                       touched, feat_roff, None, tables=[tab, tab2], adagrad_state=[st, st2], lr=0.01, eps=1e-8)
+
+
+def test_backward_bits_do_not_depend_on_capacity_bounds(ctx, recd):
+    """Any upper bounds U_cap, M_cap give the same bits (how a long row's sum is associated depends on
+    its length and on RECD_OPT_LONG_SEGMENT_CUT alone); another cut is allowed to change the low bits
+    of rows longer than the smaller cut and must still meet the bar."""
+    w = synth.scaled(synth.WORKLOADS["cfg5"], F=3, B=2048, rows=30_000, D=32)
+    F, B, D = w.F, w.B, w.D
+    batch = synth.make_batch(w, 0)
+    gout_h = synth.make_grad_out(w, 0)
+    gout = gu.to_dev(gout_h)
+    values, offsets, ik = gu.gpu_build(ctx, batch)
+    tr, fr, gr = orc.backward_kjt(F, B, gout_h, batch.values, batch.offsets)
+
+    def run(U_cap, M_cap):
+        touched = torch.zeros(M_cap, dtype=torch.int64, device="cuda")
+        feat_roff = torch.zeros(F + 1, dtype=torch.int64, device="cuda")
+        grad_rows = torch.zeros(M_cap, D, device="cuda")
+        R = ctx.backward_dedup(F, B, gout, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F,
+                               U_cap, M_cap, touched, feat_roff, grad_rows, want_count=True)
+        assert R == len(tr)
+        return touched[:R].clone(), grad_rows[:R].clone()
+
+    exact = run(ik.U, ik.M)
+    loose = run(F * B, (9 << 20) + 5)   # beyond 2^23 entries of capacity
+    assert torch.equal(exact[0], loose[0]) and torch.equal(exact[1], loose[1])
+    try:
+        for cut in (16, 64, 128):
+            ctx.set_option(recd.RECD_OPT_LONG_SEGMENT_CUT, cut)
+            t, g = run(ik.U, ik.M)
+            assert torch.equal(t, exact[0])
+            gu.assert_close_f32(gu.out_to_f64(g), gr, f"cut {cut}")
+        with pytest.raises(recd.RecdError) as e:
+            ctx.set_option(recd.RECD_OPT_LONG_SEGMENT_CUT, 33)
+        assert e.value.status == recd.RECD_EINVAL
+    finally:
+        ctx.set_option(recd.RECD_OPT_LONG_SEGMENT_CUT, 32)
 
 
 def test_backward_mode_errors(ctx, recd):

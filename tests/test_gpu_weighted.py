@@ -189,14 +189,33 @@ def test_weighted_many_features(ctx):
     _backward_case(ctx, w, batch, weights)
 
 
-def test_weighted_backward_giant_segment_and_determinism(ctx):
-    B = 20000
+@pytest.mark.parametrize("scale", [1.0, 0.01])
+def test_weighted_backward_giant_segment_and_determinism(ctx, scale):
+    """The weighted twin of the plain giant-segment test: one table row with 20000 entries, upstream
+    gradients of size ~scale, held to the same bar (the stated one for single-entry rows, the
+    worst-case bound of the chunked sum for the giant row); two runs give the same bits."""
+    B, D = 20000, 8
     batch = synth.batch_from_lists([[[7, 100 + i] for i in range(B)]])
-    w = synth.scaled(synth.WORKLOADS["cfg1"], F=1, B=B, rows=100 + B, D=8)
     weights = synth.make_weights(batch, 4)
-    a = _backward_case(ctx, w, batch, weights, with_adagrad=False)
-    b = _backward_case(ctx, w, batch, weights, with_adagrad=False)
-    assert torch.equal(a[0], b[0]) and torch.equal(a[1], b[1])
+    gout = (np.random.default_rng(23).standard_normal((1, B, D)) * scale).astype(np.float32)
+    values, d_w, offsets, ik, u_weights, _ = _build(ctx, batch, weights)
+    runs = []
+    for _ in range(2):
+        touched = torch.full((ik.M,), -7, dtype=torch.int64, device="cuda")
+        feat_roff = torch.full((2,), -7, dtype=torch.int64, device="cuda")
+        grad_rows = torch.full((ik.M, D), float("nan"), device="cuda")
+        R = ctx.backward_dedup_weighted(1, B, gu.to_dev(gout), ik.inverse, ik.feat_uoff, ik.u_values, u_weights,
+                                        ik.u_offsets, [100 + B], ik.U, ik.M, touched, feat_roff, grad_rows,
+                                        want_count=True)
+        runs.append((touched, grad_rows))
+    assert torch.equal(runs[0][0], runs[1][0]) and torch.equal(runs[0][1][:R], runs[1][1][:R])
+    tr, fr, gr = orc.backward_kjt_weighted(1, B, gout, batch.values, weights, batch.offsets)
+    assert R == len(tr) == B + 1 and np.array_equal(runs[0][0][:R].cpu().numpy(), tr)
+    got = gu.out_to_f64(runs[0][1][:R])
+    gu.assert_close_f32(got[1:], gr[1:], "single-entry rows")
+    # the giant row: entry b contributes weights[2 * b] * gout[0, b, :] (id 7 is position 0 of list b)
+    terms = np.abs(weights[0::2].astype(np.float64))[:, None] * np.abs(gout[0].astype(np.float64))
+    gu.assert_long_sum(got[0], gr[0], terms.sum(axis=0), gu.long_sum_depth(B, lane_groups=8), "giant row")
 
 
 def test_weighted_argument_errors(ctx, recd):
