@@ -464,6 +464,24 @@ recd_status recd_backward_dedup_max(recd_ctx *ctx, int F, int64_t B, int D, cons
                                     float *const *adagrad_state, float lr, float eps,
                                     int64_t *host_R);
 
+/* Call 1 for callers that cannot allocate: code under HIP graph capture, serving loops and harnesses
+ *    in which hipMalloc is forbidden.  Same arguments, same outputs bit for bit as recd_build_ikjt,
+ *    but the builder's scratch (hash tables, per-list numbering arrays, block sums) lives in a
+ *    file-scope device array of the library, about 3.1 MB, which every GPU the library runs on holds
+ *    until the process ends; the call allocates and frees nothing, records no memset, does not
+ *    synchronise and does not touch the context's workspace (a pending backward plan stays valid).
+ *    Limit: F*B <= RECD_NOALLOC_MAX_LISTS, else RECD_ECAPACITY (nothing is enqueued).  No host
+ *    counts: U = feat_uoff[F] and M = u_offsets[U] are on the device; recd_last_ikjt_counts and the
+ *    "most recent build" of recd_backward_plan do not see this call.
+ *    All calls on one GPU share the one array, whatever their context: calls that overlap on a GPU
+ *    (two streams, two contexts) race; calls on one stream are ordered and safe.  The array keeps
+ *    the previous call's contents; the call clears what it needs cleared. */
+#define RECD_NOALLOC_MAX_LISTS 65536
+recd_status recd_build_ikjt_noalloc(recd_ctx *ctx, int F, int64_t B, int64_t N,
+                                    const int64_t *values, const int64_t *offsets,
+                                    int64_t *u_values, int64_t *u_offsets, int32_t *inverse,
+                                    int64_t *feat_uoff);
+
 #ifdef __cplusplus
 }
 #endif

@@ -1005,6 +1005,79 @@ extern "C" recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t 
                        host_U_M);
 }
 
+// ---- allocation-free builder -------------------------------------------------------------------
+// Scratch of recd_build_ikjt_noalloc: hash tables, per-list slot / representative / number / first
+// row, block sums and counts for at most RECD_NOALLOC_MAX_LISTS lists.  One copy per GPU the library
+// runs on, held until the process ends; every call on a GPU uses it (overlapping calls race).
+namespace {
+constexpr size_t kStaticTableSlots = 4 * (size_t)RECD_NOALLOC_MAX_LISTS;  // F * cap(B) <= max(64 F, 4 F B)
+constexpr size_t kStaticScratchBytes =
+    kStaticTableSlots * sizeof(uint64_t) + 4 * ((size_t)RECD_NOALLOC_MAX_LISTS * sizeof(int32_t) + 256) +
+    3 * ((RECD_NOALLOC_MAX_LISTS / kScanBlock + 2) * sizeof(int64_t) + 256) + 2 * 256;
+constexpr int kMaxDevices = 64;
+char *g_scratch_ptr[kMaxDevices];  // device address of this GPU's copy of `scratch`
+}
+static __device__ __align__(256) char scratch[kStaticScratchBytes];
+
+// The device address of the current device's copy of `scratch` (looked up once per device; the
+// array's name itself is only a host-side stand-in).  Called with `device` current.
+recd_status recd_static_scratch(recd_ctx *ctx, int device)
+{
+    if (device < 0 || device >= kMaxDevices)
+        return recd_fail(ctx, RECD_EINVAL, "device %d: at most %d devices", device, kMaxDevices);
+    char *p = __atomic_load_n(&g_scratch_ptr[device], __ATOMIC_ACQUIRE);
+    if (!p) {
+        void *sym = nullptr;
+        RECD_HIP(ctx, hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch)));
+        if (!sym)
+            return recd_fail(ctx, RECD_EHIP, "hipGetSymbolAddress returned a null address");
+        p = static_cast<char *>(sym);
+        __atomic_store_n(&g_scratch_ptr[device], p, __ATOMIC_RELEASE);  // every thread finds the same address
+    }
+    ctx->static_scratch = p;
+    return RECD_OK;
+}
+
+extern "C" recd_status recd_build_ikjt_noalloc(recd_ctx *ctx, int F, int64_t B, int64_t N,
+                                               const int64_t *values, const int64_t *offsets,
+                                               int64_t *u_values, int64_t *u_offsets, int32_t *inverse,
+                                               int64_t *feat_uoff)
+{
+    if (!ctx)
+        return RECD_EINVAL;
+    if (F < 0 || F > RECD_MAX_FEATURES || B < 0 || N < 0)
+        return recd_fail(ctx, RECD_EINVAL, "bad sizes F=%d B=%lld N=%lld", F, (long long)B, (long long)N);
+    const int64_t n_lists = (int64_t)F * B;
+    if (B > RECD_NOALLOC_MAX_LISTS || n_lists > RECD_NOALLOC_MAX_LISTS)
+        return recd_fail(ctx, RECD_ECAPACITY, "F*B=%lld exceeds RECD_NOALLOC_MAX_LISTS=%d", (long long)n_lists,
+                         RECD_NOALLOC_MAX_LISTS);
+    if (!u_offsets || !feat_uoff || (n_lists > 0 && (!offsets || !inverse)) || (N > 0 && (!values || !u_values)))
+        return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
+    if (!ctx->static_scratch)
+        return recd_fail(ctx, RECD_EHIP, "the static scratch array was not found when the context was created");
+    RECD_HIP(ctx, hipSetDevice(ctx->device));
+    WsCarver c(ctx->static_scratch);
+    const SlotWs w = carve_slots(c, F, B, n_lists, n_lists);
+    if ((size_t)F * w.cap > kStaticTableSlots || c.off > kStaticScratchBytes)
+        return recd_fail(ctx, RECD_ECAPACITY, "sizes exceed the static scratch array");
+    hipStream_t st = ctx->stream;
+    if (n_lists == 0) {
+        hipLaunchKernelGGL(k_empty_ikjt, dim3(1), dim3(256), 0, st, F, u_offsets, feat_uoff, w.counts);
+    } else {
+        // the array keeps the last call's contents: the tables are cleared by a fill kernel first (no
+        // memset, so that the call can be captured into a graph); every other piece is written
+        // before it is read
+        insert_lists(ctx, st, w, F, B, values, offsets, nullptr, false);
+        number_slots(st, w, F, B, offsets, u_offsets, feat_uoff);
+        const unsigned inv_blocks = (unsigned)((n_lists + 255) / 256);
+        hipLaunchKernelGGL((k_emit<16>), dim3(inv_blocks + copy_blocks_for(ctx, n_lists)), dim3(256), 0, st, values,
+                           offsets, B, n_lists, w.rep, w.number, w.src_of, u_offsets, w.counts, u_values, inverse,
+                           inv_blocks);
+    }
+    RECD_HIP(ctx, hipGetLastError());
+    return RECD_OK;
+}
+
 extern "C" recd_status recd_build_ikjt_weighted(recd_ctx *ctx, int F, int64_t B, int64_t N,
                                                 const int64_t *values, const float *weights,
                                                 const int64_t *offsets, int64_t *u_values,

@@ -213,6 +213,7 @@ recd_status recd_create(recd_ctx **out, int device, void *hip_stream, size_t wor
     void *bc = nullptr;
     ok = ok && hipMalloc(&bc, 4 * sizeof(int64_t)) == hipSuccess;
     ctx->build_counts_dev = static_cast<int64_t *>(bc);
+    ok = ok && recd_static_scratch(ctx, device) == RECD_OK;
     if (ok && workspace_hint_bytes)
         ok = recd_reserve(ctx, workspace_hint_bytes) == RECD_OK;
     if (!ok) {

@@ -64,6 +64,8 @@ struct recd_ctx {
     int64_t build_seq = 0;        // sequence number of the latest publication (never reused)
     bool build_published = false; // the last build published its counts (else: read the device array)
     bool build_valid = false;     // a plain / weighted build has written build_counts_dev
+    // this device's copy of the static scratch array of recd_build_ikjt_noalloc (found at creation)
+    char *static_scratch = nullptr;
     int validate = 0;
     int weak_hash = 0;
     int tune_lb = 0, tune_gens = 0, tune_flat = 0;  // launch-shape overrides of the gather-sum kernel (0 = automatic)
@@ -87,6 +89,8 @@ recd_status recd_check_rows(recd_ctx *ctx, int F, const int64_t *rows);
 // After a builder wrote {U, M} into ctx->build_counts_dev: publish them to the host asynchronously.
 recd_status recd_publish_build_counts(recd_ctx *ctx);
 recd_status recd_reserve(recd_ctx *ctx, size_t bytes);
+// Looks up the current device's copy of the static scratch array (with `device` current).
+recd_status recd_static_scratch(recd_ctx *ctx, int device);
 
 #define RECD_HIP(ctx, call)                                                                   \
     do {                                                                                      \

@@ -30,6 +30,7 @@ RECD_OPT_VALIDATE, RECD_OPT_WEAK_HASH, RECD_OPT_LONG_SEGMENT_CUT = 1, 2, 4
 # test that results do not depend on the launch shape)
 _OPT_INTERNAL_TUNE_SEGSUM = 1003
 RECD_POOL_SUM, RECD_POOL_MEAN, RECD_POOL_MAX = 0, 1, 2
+RECD_NOALLOC_MAX_LISTS = 65536
 POOLING = {"sum": RECD_POOL_SUM, "mean": RECD_POOL_MEAN, "max": RECD_POOL_MAX}
 
 EXPORTED = [
@@ -41,7 +42,7 @@ EXPORTED = [
     "recd_build_partial_ikjt", "recd_pooled_lookup_partial", "recd_backward_sequence_dedup",
     "recd_backward_dedup_mode", "recd_build_ikjt_weighted", "recd_pooled_lookup_unique_weighted",
     "recd_kjt_pooled_lookup_weighted", "recd_backward_dedup_weighted", "recd_backward_dedup_max",
-    "recd_last_ikjt_counts", "recd_backward_plan", "recd_backward_apply",
+    "recd_last_ikjt_counts", "recd_backward_plan", "recd_backward_apply", "recd_build_ikjt_noalloc",
 ]
 
 _vp = C.c_void_p
@@ -54,6 +55,7 @@ _lib.recd_status_string.argtypes = [C.c_int]
 _lib.recd_status_string.restype = C.c_char_p
 _lib.recd_workspace_bytes.argtypes = [C.c_int, C.c_int64, C.c_int64, C.c_int, C.POINTER(C.c_size_t)]
 _lib.recd_build_ikjt.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.recd_build_ikjt_noalloc.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.recd_pooled_lookup_unique.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, _vp,
                                            _vp, C.c_int64, _vp]
 _lib.recd_expand_inverse.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, C.c_int, _vp, _vp, _vp, _vp]
@@ -161,6 +163,12 @@ class Context:
                                          _ptr(u_values), _ptr(u_offsets), _ptr(inverse),
                                          _ptr(feat_uoff), host))
         return (int(host[0]), int(host[1])) if want_counts else None
+
+    def build_ikjt_noalloc(self, F: int, B: int, values, offsets, u_values, u_offsets, inverse, feat_uoff):
+        """build_ikjt on the library's static scratch array: allocates nothing, returns no counts."""
+        self._check(_lib.recd_build_ikjt_noalloc(self._h, F, B, values.numel(), _ptr(values), _ptr(offsets),
+                                                 _ptr(u_values), _ptr(u_offsets), _ptr(inverse),
+                                                 _ptr(feat_uoff)))
 
     def last_ikjt_counts(self):
         """(U, M) of the most recent build_ikjt / build_ikjt_weighted call; waits for that build only."""
