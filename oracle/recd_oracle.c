@@ -445,6 +445,27 @@ int oracle_expand_inverse(int F, int64_t B, int D, const double *pooled, const i
     return 0;
 }
 
+/* ---- where every unique list first occurs (Sec. 4.2: a session's rows are clustered, so the
+ * duplicates of a list follow its first occurrence) -------------------------------------------------
+ * first_row[feat_uoff[f] + k] = f*B + b for the smallest b with inverse[f,b] = k; -1 if no row of
+ * feature f names slot k.
+ */
+int oracle_first_rows(int F, int64_t B, const int32_t *inverse, const int64_t *feat_uoff,
+                      int64_t *first_row)
+{
+    for (int64_t u = 0; u < feat_uoff[F]; u++)
+        first_row[u] = -1;
+    for (int f = 0; f < F; f++)
+        for (int64_t b = 0; b < B; b++) {
+            int64_t k = inverse[(int64_t)f * B + b];
+            if (k < 0 || k >= feat_uoff[f + 1] - feat_uoff[f])
+                return -5;
+            if (first_row[feat_uoff[f] + k] < 0)
+                first_row[feat_uoff[f] + k] = (int64_t)f * B + b;
+        }
+    return 0;
+}
+
 /* ---- per-id activations (Sec. 2.2: an EMB produces a dense activation vector for each list
  * element; Sec. 5 "EMB Inputs and Activations": with an IKJT only the unique values are looked up) --
  * emb[j,:] = W_f[values[j],:] for every position j of the lists [list_off[f], list_off[f+1]) of

@@ -208,6 +208,17 @@ def expand_inverse(F: int, B: int, pooled: np.ndarray, feat_uoff, inverse) -> np
     return out
 
 
+def first_rows(F: int, B: int, inverse, feat_uoff) -> np.ndarray:
+    """first_row[u] = f*B + b of the first row of feature f that names unique list u (-1: none)."""
+    inverse = np.ascontiguousarray(inverse, dtype=np.int32)
+    feat_uoff = _i64(feat_uoff)
+    out = np.full(max(int(feat_uoff[F]), 1), -1, dtype=np.int64)
+    inv = inverse if inverse.size else np.zeros(1, dtype=np.int32)
+    _check(_lib.oracle_first_rows(C.c_int(F), C.c_int64(B), _p(inv, _i32p), _p(feat_uoff, _i64p),
+                                  _p(out, _i64p)), "first_rows")
+    return out[:int(feat_uoff[F])]
+
+
 def group_sum(group_off, pooled: np.ndarray, feat_uoff, group_uoff) -> np.ndarray:
     """Element-wise sum over the features of every group on the unique rows (Sec. 5 "Deduplicated
     Pooling").  pooled float64 [U, D] -> float64 [sum of U_g, D]."""

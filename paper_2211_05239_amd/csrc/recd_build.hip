@@ -907,7 +907,7 @@ unsigned copy_blocks_for(const recd_ctx *ctx, int64_t n_lists)
 static recd_status build_plain(recd_ctx *ctx, int F, int64_t B, int64_t N, const int64_t *values,
                                const uint32_t *weights, const int64_t *offsets, int64_t *u_values,
                                uint32_t *u_weights, int64_t *u_offsets, int32_t *inverse,
-                               int64_t *feat_uoff, int64_t *host_U_M)
+                               int64_t *feat_uoff, int64_t *host_U_M, int32_t *u_first_row = nullptr)
 {
     if (!ctx)
         return RECD_EINVAL;
@@ -928,6 +928,8 @@ static recd_status build_plain(recd_ctx *ctx, int F, int64_t B, int64_t N, const
     WsCarver c(ctx->ws);
     SlotWs w = carve_slots(c, F, B, n_lists, n_lists);
     w.counts = ctx->build_counts_dev;  // {U, M}: outlives the workspace's reuse by later calls
+    if (u_first_row)
+        w.src_of = u_first_row;  // the first row of every unique list, kept for the caller
     int64_t *counts = w.counts;
     hipStream_t st = ctx->stream;
     bool published = false;
@@ -1076,6 +1078,17 @@ extern "C" recd_status recd_build_ikjt_noalloc(recd_ctx *ctx, int F, int64_t B, 
     }
     RECD_HIP(ctx, hipGetLastError());
     return RECD_OK;
+}
+
+extern "C" recd_status recd_build_ikjt_rows(recd_ctx *ctx, int F, int64_t B, int64_t N,
+                                            const int64_t *values, const int64_t *offsets,
+                                            int64_t *u_values, int64_t *u_offsets, int32_t *inverse,
+                                            int64_t *feat_uoff, int32_t *u_first_row, int64_t *host_U_M)
+{
+    if (ctx && (int64_t)F * B > 0 && !u_first_row)
+        return recd_fail(ctx, RECD_EINVAL, "null u_first_row");
+    return build_plain(ctx, F, B, N, values, nullptr, offsets, u_values, nullptr, u_offsets, inverse, feat_uoff,
+                       host_U_M, u_first_row);
 }
 
 extern "C" recd_status recd_build_ikjt_weighted(recd_ctx *ctx, int F, int64_t B, int64_t N,

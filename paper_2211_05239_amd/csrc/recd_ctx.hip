@@ -259,6 +259,8 @@ recd_status recd_destroy(recd_ctx *ctx)
         (void)hipFree(ctx->build_counts_dev);
     if (ctx->build_table)
         (void)hipFree(ctx->build_table);
+    if (ctx->cover)
+        (void)hipFree(ctx->cover);
     if (ctx->host_pinned)
         (void)hipHostFree(ctx->host_pinned);
     if (ctx->mailbox)

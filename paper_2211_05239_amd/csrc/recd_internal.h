@@ -45,6 +45,10 @@ struct recd_ctx {
     // no build is running on the stream, because the builder's last kernel clears what the build
     // used (so no clearing kernel stands at the head of the next build).  table_clean is false
     // while that cannot be relied on (first use, or a build that failed half way).
+    // Fused lookup + expand: per unique list the range of output rows the lookup kernel wrote
+    // (memory of its own, so that the call leaves the workspace and a pending backward plan alone).
+    int2 *cover = nullptr;
+    size_t cover_lists = 0;
     uint64_t *build_table = nullptr;
     size_t build_table_slots = 0;
     bool table_clean = false;
@@ -143,7 +147,9 @@ struct OptAdagrad {
 // Exclusive scan of n int64 pairs is private to each file; the segmented gather-sum is shared.
 // GRAD_STREAM: as GRAD_LISTS, for source rows that are read once (step A reads every grad_out row
 // exactly once): their loads bypass the caches' retention.
-enum { RECD_SITE_UNIQUE = 0, RECD_SITE_KJT = 1, RECD_SITE_GRAD_LISTS = 2, RECD_SITE_GRAD_STREAM = 3 };
+// UNIQUE_EXPAND: the unique lookup that also writes the output rows of every list's first run.
+enum { RECD_SITE_UNIQUE = 0, RECD_SITE_KJT = 1, RECD_SITE_GRAD_LISTS = 2, RECD_SITE_GRAD_STREAM = 3,
+       RECD_SITE_UNIQUE_EXPAND = 4 };
 struct SegSumArgs {
     int F;                    // features in this launch (<= RECD_F_PER_LAUNCH)
     int D;
@@ -163,6 +169,14 @@ struct SegSumArgs {
     const float *weights;           // mode 3 (weighted sum): one fp32 weight per id, beside values
     const int64_t *div_off;         // optional (backward sums only): the finished row of list l is
                                     // divided by div_off[l+1] - div_off[l] when that is positive
+    // RECD_SITE_UNIQUE_EXPAND only: the IKJT's inverse, the first row of every unique list, the
+    // expanded output, rows per feature, the launch's first feature, the written row range per list
+    const int32_t *inverse;
+    const int32_t *first_row;
+    void *expanded;
+    int2 *cover;
+    int64_t B;
+    int feat_base;
     int site;                 // RECD_SITE_*: which call site (each has its own kernel instantiation)
     int mode;                 // recd_pooling (forward sites only; 0 = sum)
     void *out;                // [lists, D]
@@ -171,6 +185,8 @@ struct SegSumArgs {
 recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a);
 recd_status recd_validate_inverse(recd_ctx *ctx, int F, int64_t B, const int64_t *feat_uoff,
                                   const int32_t *inverse);
+recd_status recd_validate_first_rows(recd_ctx *ctx, int F, int64_t B, const int64_t *feat_uoff,
+                                     const int32_t *inverse, const int32_t *first_row);
 recd_status recd_validate_kjt_offsets(recd_ctx *ctx, int F, int64_t B, int64_t N, const int64_t *offsets);
 recd_status recd_validate_kjt_lists(recd_ctx *ctx, int F, int64_t B, int64_t N, const int64_t *rows,
                                     const int64_t *values, const int64_t *offsets);

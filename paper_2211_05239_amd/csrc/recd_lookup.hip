@@ -36,7 +36,7 @@ constexpr int kBlock = 256;
 // waves resident (unique lookup 0.124 ms against 0.133, KJT lookup 0.99 against 1.16).  The
 // backward's sums keep four waves: their long segments and 256-entry chunks want the whole block.
 template <int SITE> struct SegBlock {
-    static constexpr int threads = (SITE == 0 || SITE == 1) ? 64 : 256;
+    static constexpr int threads = (SITE == 0 || SITE == 1 || SITE == 4) ? 64 : 256;
 };
 constexpr int kMaxLB = 16;     // lists per block item (upper bound)
 constexpr int kChunk = 64;     // ids per chunk: a wave loads a chunk's ids with one instruction
@@ -143,7 +143,10 @@ template <int OT, int N, bool NT> __device__ __forceinline__ void store_row_piec
 
 // Call sites of the gather-sum kernel.  Each gets its own instantiation (and symbol): the unique
 // lookup, the KJT comparison lookup, and the backward's sums over grad_out rows / chunk partials.
-enum { SITE_UNIQUE = 0, SITE_KJT = 1, SITE_GRAD_LISTS = 2, SITE_GRAD_STREAM = 3 };
+// SITE_UNIQUE_EXPAND: the unique lookup whose waves also store a finished row to the output rows of
+// the run of adjacent samples that starts at the list's first row (Sec. 5: lookup on the unique
+// lists, then the index select back to the batch - here for the samples a session put side by side).
+enum { SITE_UNIQUE = 0, SITE_KJT = 1, SITE_GRAD_LISTS = 2, SITE_GRAD_STREAM = 3, SITE_UNIQUE_EXPAND = 4 };
 
 struct SegSumParams {
     TablePtrs tables;
@@ -169,6 +172,15 @@ struct SegSumParams {
     const int64_t *div_off;
     // POOL_WSUM: one fp32 weight per id, aligned with values
     const float *weights;
+    // SITE_UNIQUE_EXPAND: the IKJT's inverse [F*B], the first row of every unique list, the expanded
+    // output [F*B, D], rows per feature, the launch's first feature, and per unique list the range of
+    // output rows this kernel wrote (for the pass that copies the remaining rows)
+    const int32_t *inverse;
+    const int32_t *first_row;
+    void *expanded;
+    int2 *cover;
+    int64_t B;
+    int feat_base;
 };
 
 // Adds the rows of NL chunks (chunk j: ns[j] <= 64 ids starting at values[starts[j]], rows of the
@@ -240,13 +252,29 @@ __device__ __forceinline__ void add_chunks(float (*acc)[Elem<TT>::per_vec * VPL]
     }
 }
 
-// Occupancy target: 7 waves per SIMD (71 VGPRs) measured best for one-vector-per-lane rows; more
-// loads in flight per wave at lower occupancy, or fewer at 8 waves, were both slower.
+// Occupancy target: 7 waves per SIMD (72 VGPRs) measured best for one-vector-per-lane fp32 rows; more
+// loads in flight per wave at lower occupancy, or fewer at 8 waves, were both slower.  The
+// instantiations that need more registers than that (16-bit tables decode into twice the
+// accumulators, rows of at most 128 bytes put 8 rows into every load, the weighted sum carries
+// the weights: 6 waves for the KJT lookup, 5 for the unique lists) get a lower target instead of
+// spilling: a spilled accumulator costs more than the lost wave.
+template <int LPR, int VPL, int TT, int OT, int SITE, int MODE> constexpr int segsum_waves()
+{
+    if (VPL > 1)
+        return 1;
+    int w = MODE == POOL_WSUM ? (SITE == SITE_KJT ? 6 : 5) : 7;
+    if (LPR == 8)
+        w -= 2;
+    else if (TT != RECD_F32 && SITE == SITE_UNIQUE_EXPAND)
+        w -= 2;
+    else if (TT != RECD_F32 && (MODE != POOL_SUM || OT == RECD_BF16))
+        w -= 1;
+    return w < 3 ? 3 : w;
+}
+
 template <int LPR, int VPL, int TT, int OT, typename IdxT, int SITE, int MODE = POOL_SUM>
-// The weighted sum needs a few registers more: 6 waves (80 VGPRs) instead of spilling measured best
-// for the KJT lookup, 5 for the unique lists (7 with spills was slower for both).
 __global__ __launch_bounds__(SegBlock<SITE>::threads)
-__attribute__((amdgpu_waves_per_eu(VPL == 1 ? (MODE == POOL_WSUM ? (SITE == SITE_KJT ? 6 : 5) : 7) : 1)))
+__attribute__((amdgpu_waves_per_eu(segsum_waves<LPR, VPL, TT, OT, SITE, MODE>())))
 void k_segsum(const SegSumParams p)
 {
     constexpr int kSegBlock = SegBlock<SITE>::threads;
@@ -263,7 +291,10 @@ void k_segsum(const SegSumParams p)
     __shared__ int64_t s_qpref[RECD_F_PER_LAUNCH + 1];
     __shared__ int64_t s_start[kMaxLB], s_end[kMaxLB], s_list[kMaxLB];
     __shared__ int s_feat[kMaxLB];
+    __shared__ int32_t s_first[kMaxLB];
     __shared__ float s_part[LL][kWaves][ROWF];
+    constexpr bool EXPAND = SITE == SITE_UNIQUE_EXPAND;
+    static_assert(!EXPAND || kWaves == 1, "a finished row is in the registers of one wave");
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -343,6 +374,36 @@ void k_segsum(const SegSumParams p)
             for (int w = 0; w < VPL; w++)
                 store_row_piece<OT, EPV, NT>(dst + ((int64_t)w * LPR + r) * OB, vals + w * EPV);
         }
+        if constexpr (EXPAND) {
+            // Every lane group holds the finished row (the butterfly leaves the sum in all of them).
+            // The run: the list's first row and the rows right behind it, in the same feature, that
+            // name the same slot.  The whole wave looks 64 rows ahead at a time.
+            const int f = s_feat[j];
+            const int64_t l0 = s_first[j];
+            const int64_t lend = (int64_t)(p.feat_base + f + 1) * p.B;
+            const int32_t slot = (int32_t)(s_list[j] - s_loff[f]);
+            int64_t c = 1;
+            for (;;) {
+                const int64_t l = l0 + c + lane;
+                const bool same = l < lend && p.inverse[l] == slot;
+                const uint64_t m = __ballot(same);
+                const int k = m == ~0ull ? 64 : __builtin_ctzll(~m);
+                c += k;
+                if (k < 64)
+                    break;
+            }
+            if (lane == 0)
+                p.cover[s_list[j]] = make_int2((int)l0, (int)(l0 + c));
+            if (piece_ok) {
+                char *dst = static_cast<char *>(p.expanded) + l0 * out_row_bytes;
+                for (int64_t k = g; k < c; k += 64 / LPR) {
+#pragma unroll
+                    for (int w = 0; w < VPL; w++)
+                        store_row_piece<OT, EPV, true>(dst + k * out_row_bytes + ((int64_t)w * LPR + r) * OB,
+                                                       vals + w * EPV);
+                }
+            }
+        }
     };
 
     for (int64_t item = item0; item * lb < total; item += item_stride) {
@@ -366,6 +427,8 @@ void k_segsum(const SegSumParams p)
             const int64_t start = p.offsets[l];
             s_start[tid] = start;
             s_end[tid] = p.ends ? p.ends[l] : (p.lens ? start + p.lens[l] : p.offsets[l + 1]);
+            if constexpr (EXPAND)
+                s_first[tid] = p.first_row[l];
         }
         __syncthreads();
 
@@ -546,6 +609,82 @@ __global__ __launch_bounds__(kBlock) void k_expand(const u32x4 *__restrict__ poo
     }
 }
 
+// ---- the rest of the expand after the fused lookup ---------------------------------------------
+// cover[u] = [first, end) rows the lookup kernel wrote for unique list u.  A thread checks one output
+// row; the rows outside their list's range (a list that turns up again later in the batch, not
+// next to its first run) are collected per block and copied from pooled by the whole block.
+// With session-adjacent duplicates that is a few percent of the rows; in the worst case this
+// kernel is the whole expand.
+__global__ __launch_bounds__(kBlock) void k_expand_uncovered(const u32x4 *__restrict__ pooled,
+                                                             const int64_t *__restrict__ feat_uoff,
+                                                             const int32_t *__restrict__ inverse,
+                                                             const int2 *__restrict__ cover,
+                                                             u32x4 *__restrict__ out, uint32_t B,
+                                                             uint32_t n_rows, int vecs_per_row)
+{
+    __shared__ uint32_t s_row[kBlock], s_src[kBlock];
+    __shared__ uint32_t s_wcnt[kBlock / 64];
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const uint32_t row = blockIdx.x * kBlock + tid;
+    bool need = false;
+    uint32_t u = 0;
+    if (row < n_rows) {
+        u = (uint32_t)(feat_uoff[row / B] + inverse[row]);
+        const int2 cv = cover[u];
+        need = (int)row < cv.x || (int)row >= cv.y;
+    }
+    const uint64_t m = __ballot(need);
+    if (lane == 0)
+        s_wcnt[wv] = (uint32_t)__popcll(m);
+    __syncthreads();
+    uint32_t before = 0, total = 0;
+#pragma unroll
+    for (int i = 0; i < kBlock / 64; i++) {
+        before += i < wv ? s_wcnt[i] : 0;
+        total += s_wcnt[i];
+    }
+    if (total == 0)
+        return;  // whole block
+    if (need) {
+        const uint32_t k = before + (uint32_t)__popcll(m & ((1ull << lane) - 1));
+        s_row[k] = row;
+        s_src[k] = u;
+    }
+    __syncthreads();
+    const uint32_t vecs = (uint32_t)vecs_per_row;
+    for (uint32_t idx = tid; idx < total * vecs; idx += kBlock) {
+        const uint32_t k = idx / vecs, piece = idx - k * vecs;
+        __builtin_nontemporal_store(pooled[(int64_t)s_src[k] * vecs + piece],
+                                    &out[(int64_t)s_row[k] * vecs + piece]);
+    }
+}
+
+// ---- first row of every unique list from the inverse index alone ---------------------------------
+// A row is a run head if it is row 0 of its feature or names another slot than the row before it;
+// the first row of a slot is the smallest of its run heads.
+__global__ __launch_bounds__(kBlock) void k_fill_i32(int32_t *p, int64_t n, int32_t v)
+{
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (int64_t)gridDim.x * kBlock)
+        p[i] = v;
+}
+
+__global__ __launch_bounds__(kBlock) void k_first_rows(const int32_t *__restrict__ inverse,
+                                                       const int64_t *__restrict__ feat_uoff, uint32_t B,
+                                                       uint32_t n_rows, int64_t max_lists,
+                                                       int32_t *__restrict__ first_row)
+{
+    const uint32_t row = blockIdx.x * kBlock + threadIdx.x;
+    if (row >= n_rows)
+        return;
+    const uint32_t f = row / B;
+    const int32_t inv = inverse[row];
+    if (row - f * B != 0 && inverse[row - 1] == inv)
+        return;
+    const int64_t u = feat_uoff[f] + inv;
+    if (u < max_lists)
+        atomicMin(&first_row[u], (int32_t)row);
+}
+
 // ---- a compute module on a grouped IKJT: element-wise sum over the features of a group ----------
 // combined[group_uoff[g] + k, :] = sum over f in group g, feature order, of pooled[feat_uoff[f] + k, :]
 // (fp32 accumulation, rounded once).  Thread = one 16-byte piece of one unique row of a group.
@@ -649,7 +788,44 @@ __global__ void k_validate_inverse(const int32_t *inverse, const int64_t *feat_u
     }
 }
 
+// err[0] |= 32: the first row recorded for a unique list lies outside the list's feature or does
+// not name the list
+__global__ void k_validate_first_rows(const int32_t *inverse, const int64_t *feat_uoff, int F, int64_t B,
+                                      const int32_t *first_row, int *err)
+{
+    const int64_t U = feat_uoff[F];
+    for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < U; u += (int64_t)gridDim.x * blockDim.x) {
+        int lo = 0, hi = F;  // feature of u
+        while (hi - lo > 1) {
+            const int mid = (lo + hi) >> 1;
+            if (feat_uoff[mid] <= u)
+                lo = mid;
+            else
+                hi = mid;
+        }
+        const int64_t l = first_row[u];
+        if (l < (int64_t)lo * B || l >= (int64_t)(lo + 1) * B || inverse[l] != (int32_t)(u - feat_uoff[lo]))
+            atomicOr(err, 32);
+    }
+}
+
 } // namespace
+
+recd_status recd_validate_first_rows(recd_ctx *ctx, int F, int64_t B, const int64_t *feat_uoff,
+                                     const int32_t *inverse, const int32_t *first_row)
+{
+    RECD_TRY(recd_reserve(ctx, 512));
+    int *err = reinterpret_cast<int *>(ctx->ws);
+    RECD_HIP(ctx, hipMemsetAsync(err, 0, sizeof(int), ctx->stream));
+    hipLaunchKernelGGL(k_validate_first_rows, dim3(256), dim3(256), 0, ctx->stream, inverse, feat_uoff, F, B,
+                       first_row, err);
+    ctx->host_pinned[0] = 0;
+    RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, err, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+    RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
+    if ((int)ctx->host_pinned[0] & 32)
+        return recd_fail(ctx, RECD_EBOUNDS, "u_first_row does not hold a row of every unique list");
+    return RECD_OK;
+}
 
 recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
 {
@@ -666,6 +842,12 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     p.lens = a.lens;
     p.div_off = a.div_off;
     p.weights = a.weights;
+    p.inverse = a.inverse;
+    p.first_row = a.first_row;
+    p.expanded = a.expanded;
+    p.cover = a.cover;
+    p.B = a.B;
+    p.feat_base = a.feat_base;
     p.F = a.F;
     p.D = a.D;
     const int epv = a.table_dt == RECD_F32 ? 4 : 8;
@@ -676,7 +858,7 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     p.nq = (a.F >= kNQ && a.F % kNQ == 0 && !a.flat && !ctx->tune_flat && !a.count_dev) ? kNQ : 1;
     // lists per block: four-wave blocks (backward) take 4 to 16, single-wave blocks (forward) 1 to 4
     // (measured at 61 K unique lists and at 1.05 M KJT lists: 1 and 4)
-    if (a.site == RECD_SITE_UNIQUE || a.site == RECD_SITE_KJT)
+    if (a.site == RECD_SITE_UNIQUE || a.site == RECD_SITE_KJT || a.site == RECD_SITE_UNIQUE_EXPAND)
         p.lb = n >= (512 << 10) ? 4 : (n >= (128 << 10) ? 2 : 1);
     else
         p.lb = n >= (512 << 10) ? 16 : (n >= (128 << 10) ? 8 : 4);
@@ -702,6 +884,9 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
         ok = launch_forward<SITE_UNIQUE>(st, blocks, v, a, p);
     else if (a.site == RECD_SITE_KJT && fwd && a.mode == POOL_SUM)
         ok = launch_forward<SITE_KJT>(st, blocks, v, a, p);
+    else if (a.site == RECD_SITE_UNIQUE_EXPAND && fwd && a.mode == POOL_SUM && a.inverse && a.first_row &&
+             a.expanded && a.cover)
+        ok = launch_forward<SITE_UNIQUE_EXPAND>(st, blocks, v, a, p);
     else if (a.site == RECD_SITE_UNIQUE && fwd && a.mode == POOL_MEAN)
         ok = launch_forward<SITE_UNIQUE, POOL_MEAN>(st, blocks, v, a, p);
     else if (a.site == RECD_SITE_KJT && fwd && a.mode == POOL_MEAN)
@@ -1031,6 +1216,110 @@ recd_status recd_expand_inverse(recd_ctx *ctx, int F, int64_t B, int D, recd_dty
         hipLaunchKernelGGL(k_expand<false>, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
                            static_cast<const u32x4 *>(pooled), feat_uoff, inverse,
                            static_cast<u32x4 *>(out), (uint32_t)B, (uint32_t)n_rows, vecs);
+    RECD_HIP(ctx, hipGetLastError());
+    return RECD_OK;
+}
+
+recd_status recd_ikjt_first_rows(recd_ctx *ctx, int F, int64_t B, const int32_t *inverse,
+                                 const int64_t *feat_uoff, int64_t max_lists, int32_t *u_first_row)
+{
+    if (!ctx)
+        return RECD_EINVAL;
+    if (F < 0 || F > RECD_MAX_FEATURES || B < 0 || max_lists < 0)
+        return recd_fail(ctx, RECD_EINVAL, "bad sizes F=%d B=%lld max_lists=%lld", F, (long long)B,
+                         (long long)max_lists);
+    const int64_t n_rows = (int64_t)F * B;
+    if (n_rows >= (int64_t)1 << 31)
+        return recd_fail(ctx, RECD_EINVAL, "F*B must stay below 2^31");
+    if (n_rows == 0 || max_lists == 0)
+        return RECD_OK;
+    if (!inverse || !feat_uoff || !u_first_row)
+        return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
+    RECD_HIP(ctx, hipSetDevice(ctx->device));
+    if (ctx->validate)
+        RECD_TRY(recd_validate_inverse(ctx, F, B, feat_uoff, inverse));
+    if (max_lists > n_rows)
+        max_lists = n_rows;
+    const int64_t fb = (max_lists + kBlock - 1) / kBlock;
+    hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)(fb < 4096 ? fb : 4096)), dim3(kBlock), 0, ctx->stream,
+                       u_first_row, max_lists, 0x7fffffff);
+    hipLaunchKernelGGL(k_first_rows, dim3((unsigned)((n_rows + kBlock - 1) / kBlock)), dim3(kBlock), 0,
+                       ctx->stream, inverse, feat_uoff, (uint32_t)B, (uint32_t)n_rows, max_lists, u_first_row);
+    RECD_HIP(ctx, hipGetLastError());
+    return RECD_OK;
+}
+
+recd_status recd_pooled_lookup_expand(recd_ctx *ctx, int F, int64_t B, int D, recd_dtype table_dt,
+                                      recd_dtype out_dt, const void *const *tables, const int64_t *rows,
+                                      const int64_t *u_values, const int64_t *u_offsets,
+                                      const int64_t *feat_uoff, const int32_t *inverse,
+                                      const int32_t *u_first_row, int64_t max_lists, void *pooled, void *out)
+{
+    RECD_TRY(check_lookup_shape(ctx, F, D, table_dt, out_dt));
+    RECD_TRY(recd_check_rows(ctx, F, rows));
+    if (B < 0 || max_lists < 0)
+        return recd_fail(ctx, RECD_EINVAL, "B or max_lists < 0");
+    const int64_t n_rows = (int64_t)F * B;
+    if (n_rows >= (int64_t)1 << 31)
+        return recd_fail(ctx, RECD_EINVAL, "F*B must stay below 2^31");
+    if (n_rows == 0)
+        return RECD_OK;
+    if (max_lists == 0 || max_lists > n_rows)
+        max_lists = n_rows;  // every feature of a batch with rows holds at least one list
+    if (!tables || !u_offsets || !feat_uoff || !inverse || !u_first_row || !pooled || !out)
+        return recd_fail(ctx, RECD_EINVAL, "null pointer argument");  // u_values may be null when M = 0
+    for (int f = 0; f < F; f++)
+        if (!tables[f])
+            return recd_fail(ctx, RECD_EINVAL, "tables[%d] is null", f);
+    RECD_HIP(ctx, hipSetDevice(ctx->device));
+    if (ctx->validate) {
+        RECD_TRY(recd_validate_unique_lists(ctx, F, rows, u_values, u_offsets, feat_uoff, max_lists, -1));
+        RECD_TRY(recd_validate_inverse(ctx, F, B, feat_uoff, inverse));
+        RECD_TRY(recd_validate_first_rows(ctx, F, B, feat_uoff, inverse, u_first_row));
+    }
+    // the row ranges the lookup kernel writes, one per unique list: U <= F*B of them
+    if ((size_t)n_rows > ctx->cover_lists) {
+        RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        if (ctx->cover)
+            RECD_HIP(ctx, hipFree(ctx->cover));
+        ctx->cover = nullptr;
+        ctx->cover_lists = 0;
+        void *cp = nullptr;
+        if (hipMalloc(&cp, (size_t)n_rows * sizeof(int2)) != hipSuccess) {
+            (void)hipGetLastError();
+            return recd_fail(ctx, RECD_ENOMEM, "row ranges of %lld lists: allocation failed", (long long)n_rows);
+        }
+        ctx->cover = static_cast<int2 *>(cp);
+        ctx->cover_lists = (size_t)n_rows;
+    }
+    for (int f0 = 0; f0 < F; f0 += RECD_F_PER_LAUNCH) {
+        SegSumArgs a{};
+        a.F = F - f0 < RECD_F_PER_LAUNCH ? F - f0 : RECD_F_PER_LAUNCH;
+        a.D = D;
+        a.table_dt = table_dt;
+        a.out_dt = out_dt;
+        for (int f = 0; f < a.F; f++)
+            a.tables.p[f] = tables[f0 + f];
+        a.values = u_values;
+        a.values_are_i32 = 0;
+        a.offsets = u_offsets;
+        a.list_off = feat_uoff + f0;
+        a.lists_bound = max_lists;
+        a.site = RECD_SITE_UNIQUE_EXPAND;
+        a.mode = RECD_POOL_SUM;
+        a.out = pooled;
+        a.inverse = inverse;
+        a.first_row = u_first_row;
+        a.expanded = out;
+        a.cover = ctx->cover;
+        a.B = B;
+        a.feat_base = f0;
+        RECD_TRY(recd_launch_segsum(ctx, a));
+    }
+    const int vecs = (int)((size_t)D * elem_size(out_dt) / 16);
+    hipLaunchKernelGGL(k_expand_uncovered, dim3((unsigned)((n_rows + kBlock - 1) / kBlock)), dim3(kBlock), 0,
+                       ctx->stream, static_cast<const u32x4 *>(pooled), feat_uoff, inverse, ctx->cover,
+                       static_cast<u32x4 *>(out), (uint32_t)B, (uint32_t)n_rows, vecs);
     RECD_HIP(ctx, hipGetLastError());
     return RECD_OK;
 }

@@ -43,6 +43,7 @@ EXPORTED = [
     "recd_backward_dedup_mode", "recd_build_ikjt_weighted", "recd_pooled_lookup_unique_weighted",
     "recd_kjt_pooled_lookup_weighted", "recd_backward_dedup_weighted", "recd_backward_dedup_max",
     "recd_last_ikjt_counts", "recd_backward_plan", "recd_backward_apply", "recd_build_ikjt_noalloc",
+    "recd_build_ikjt_rows", "recd_ikjt_first_rows", "recd_pooled_lookup_expand",
 ]
 
 _vp = C.c_void_p
@@ -56,6 +57,10 @@ _lib.recd_status_string.restype = C.c_char_p
 _lib.recd_workspace_bytes.argtypes = [C.c_int, C.c_int64, C.c_int64, C.c_int, C.POINTER(C.c_size_t)]
 _lib.recd_build_ikjt.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.recd_build_ikjt_noalloc.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp, _vp, _vp]
+_lib.recd_build_ikjt_rows.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64] + [_vp] * 8
+_lib.recd_ikjt_first_rows.argtypes = [_vp, C.c_int, C.c_int64, _vp, _vp, C.c_int64, _vp]
+_lib.recd_pooled_lookup_expand.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, _vp,
+                                           _vp, _vp, _vp, C.c_int64, _vp, _vp]
 _lib.recd_pooled_lookup_unique.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, _vp,
                                            _vp, C.c_int64, _vp]
 _lib.recd_expand_inverse.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, C.c_int, _vp, _vp, _vp, _vp]
@@ -169,6 +174,30 @@ class Context:
         self._check(_lib.recd_build_ikjt_noalloc(self._h, F, B, values.numel(), _ptr(values), _ptr(offsets),
                                                  _ptr(u_values), _ptr(u_offsets), _ptr(inverse),
                                                  _ptr(feat_uoff)))
+
+    def build_ikjt_rows(self, F: int, B: int, values, offsets, u_values, u_offsets, inverse, feat_uoff,
+                        u_first_row, want_counts: bool = False):
+        """build_ikjt that also records the first row of every unique list."""
+        host = (C.c_int64 * 2)(0, 0) if want_counts else None
+        self._check(_lib.recd_build_ikjt_rows(self._h, F, B, values.numel(), _ptr(values), _ptr(offsets),
+                                              _ptr(u_values), _ptr(u_offsets), _ptr(inverse),
+                                              _ptr(feat_uoff), _ptr(u_first_row), host))
+        return (int(host[0]), int(host[1])) if want_counts else None
+
+    def ikjt_first_rows(self, F: int, B: int, inverse, feat_uoff, u_first_row):
+        self._check(_lib.recd_ikjt_first_rows(self._h, F, B, _ptr(inverse), _ptr(feat_uoff),
+                                              u_first_row.numel(), _ptr(u_first_row)))
+
+    def pooled_lookup_expand(self, tables, B: int, u_values, u_offsets, feat_uoff, inverse, u_first_row,
+                             max_lists: int, pooled, out):
+        F = len(tables)
+        D = tables[0].shape[1] if F else pooled.shape[-1]
+        tdt = _DT[tables[0].dtype] if F else _DT[pooled.dtype]
+        assert out.dtype == pooled.dtype
+        self._check(_lib.recd_pooled_lookup_expand(
+            self._h, F, B, D, tdt, _DT[pooled.dtype], self._table_array(tables), self._rows_array(tables),
+            _ptr(u_values), _ptr(u_offsets), _ptr(feat_uoff), _ptr(inverse), _ptr(u_first_row), max_lists,
+            _ptr(pooled), _ptr(out)))
 
     def last_ikjt_counts(self):
         """(U, M) of the most recent build_ikjt / build_ikjt_weighted call; waits for that build only."""

@@ -1,0 +1,242 @@
+"""GPU parity of the one-pass lookup + expand (recd_build_ikjt_rows, recd_ikjt_first_rows,
+recd_pooled_lookup_expand) against the CPU oracle and against the two-kernel path, through the C ABI.
+The copies are exact, so `out` and `pooled` must equal calls 2 + 3 (and the KJT lookup) bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import recd_oracle as orc
+from paper_2211_05239_amd import synth
+from tests import gpu_util as gu
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def recd():
+    from paper_2211_05239_amd import recd as mod
+    return mod
+
+
+@pytest.fixture(scope="module")
+def ctx(recd):
+    c = recd.Context(0)
+    yield c
+    c.close()
+
+
+def _bits(t):
+    return t.view(torch.int32 if t.element_size() == 4 else torch.int16)
+
+
+def _build_rows(ctx, batch):
+    F, B = batch.F, batch.B
+    values, offsets = gu.to_dev(batch.values), gu.to_dev(batch.offsets)
+    if values.numel() == 0:
+        values = torch.zeros(1, dtype=torch.int64, device="cuda")[:0]
+    ik = gu.DeviceIKJT(F, B, batch.N)
+    first = torch.full((max(F * B, 1),), -7, dtype=torch.int32, device="cuda")
+    ik.U, ik.M = ctx.build_ikjt_rows(F, B, values, offsets, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff,
+                                     first, want_counts=True)
+    uv, uo, inv, fu = orc.build_ikjt(F, B, batch.values, batch.offsets)
+    assert (ik.U, ik.M) == (int(fu[-1]), len(uv))
+    for a, b in zip(ik.numpy(), (uv, uo, inv, fu)):
+        assert np.array_equal(a, b)
+    ref_first = orc.first_rows(F, B, inv, fu)
+    assert np.array_equal(first[:ik.U].cpu().numpy(), ref_first)
+    assert (first[ik.U:] == -7).all()
+    # the same array from the inverse index alone
+    first2 = torch.full((max(F * B, 1),), -7, dtype=torch.int32, device="cuda")
+    ctx.ikjt_first_rows(F, B, ik.inverse, ik.feat_uoff, first2)
+    assert np.array_equal(first2[:ik.U].cpu().numpy(), ref_first)
+    return values, offsets, ik, first, (uv, uo, inv, fu)
+
+
+def _fused_case(ctx, w, batch, out_dtype=None, first_override=None):
+    F, B, D, dt = batch.F, batch.B, w.D, w.table_dtype
+    tabs = synth.make_tables(w)
+    d_tabs = gu.tables_to_dev(tabs, dt)
+    odt = out_dtype or gu.TORCH_DT[dt]
+    values, offsets, ik, first, (uv, uo, inv, fu) = _build_rows(ctx, batch)
+    if first_override is not None:
+        first = first_override(ik, first)
+    L = max(F * B, 1)
+    pooled = torch.full((L, D), float("nan"), dtype=odt, device="cuda")
+    out = torch.full((F, B, D), float("nan"), dtype=odt, device="cuda")
+    ctx.pooled_lookup_expand(d_tabs, B, ik.u_values, ik.u_offsets, ik.feat_uoff, ik.inverse, first, F * B,
+                             pooled, out)
+    pooled2 = torch.full((L, D), float("nan"), dtype=odt, device="cuda")
+    out2 = torch.full((F, B, D), float("nan"), dtype=odt, device="cuda")
+    kjt = torch.full((F, B, D), float("nan"), dtype=odt, device="cuda")
+    ctx.pooled_lookup_unique(d_tabs, ik.u_values, ik.u_offsets, ik.feat_uoff, F * B, pooled2)
+    ctx.expand_inverse(F, B, pooled2, ik.feat_uoff, ik.inverse, out2)
+    ctx.kjt_pooled_lookup(d_tabs, B, values, offsets, kjt)
+    torch.cuda.synchronize()
+    assert torch.equal(_bits(pooled), _bits(pooled2))   # rows beyond U keep their fill in both
+    assert torch.equal(_bits(out), _bits(out2))
+    assert torch.equal(_bits(out), _bits(kjt))
+    ref = orc.expand_inverse(F, B, orc.pooled_lookup(tabs, dt, uv, uo, fu), fu, inv)
+    close = gu.assert_close_f32 if odt == torch.float32 else gu.assert_close_16
+    close(gu.out_to_f64(out), ref, "fused lookup + expand")
+    return ik
+
+
+@pytest.mark.parametrize("name,kw", [("cfg1", dict()),
+                                     ("cfg2", dict(F=6, B=4096, rows=200_000)),
+                                     ("cfg3", dict(F=8, B=2048, rows=50_000)),
+                                     ("cfg5", dict(F=8, B=3000, rows=50_000))])
+def test_fused_workloads(ctx, name, kw):
+    """cfg2's redraws bring a session's list back after an interruption: rows outside the first run."""
+    w = synth.scaled(synth.WORKLOADS[name], **kw)
+    _fused_case(ctx, w, synth.make_batch(w, 0))
+
+
+@pytest.mark.parametrize("dt,odt,D", [("f32", None, 4), ("f32", None, 24), ("f32", None, 64), ("f32", None, 256),
+                                      ("f32", None, 512), ("f32", None, 1024), ("f16", None, 8), ("f16", None, 64),
+                                      ("f16", torch.float32, 128), ("bf16", None, 256),
+                                      ("bf16", torch.float32, 1024), ("f16", None, 2048)])
+def test_fused_row_shapes(ctx, dt, odt, D):
+    w = synth.scaled(synth.WORKLOADS["cfg2"], F=3, B=500, rows=3000, D=D, table_dtype=dt, len_max=100)
+    _fused_case(ctx, w, synth.make_batch(w, 1), odt)
+
+
+def test_fused_many_features(ctx):
+    """More features than one launch carries: the second launch's rows start at feature 128."""
+    w = synth.scaled(synth.WORKLOADS["cfg1"], F=131, B=67, rows=500, D=16)
+    _fused_case(ctx, w, synth.make_batch(w, 0))
+
+
+def test_fused_runs_longer_than_a_wave(ctx):
+    """Runs of 1, 64, 65, 128, 129 and 300 identical rows, a run that ends with its feature, and the
+    same list coming back later."""
+    lists, k = [], 0
+    for n in (1, 64, 65, 128, 129, 300, 7):
+        lists += [[10 + k, 3, 10 + k]] * n
+        k += 1
+    lists += [[10, 3, 10]] * 5 + [[]] * 70 + [[11, 3, 11]] * 66
+    batch = synth.batch_from_lists([lists, list(reversed(lists))])
+    w = synth.scaled(synth.WORKLOADS["cfg1"], F=2, B=len(lists), rows=40, D=128)
+    ik = _fused_case(ctx, w, batch)
+    assert ik.U == 2 * 8
+
+
+def test_fused_without_adjacency(ctx):
+    """A batch whose duplicates are never adjacent: the first pass covers one row per list and the
+    second pass is the whole expand."""
+    rng = np.random.default_rng(3)
+    base = [[int(x) for x in rng.integers(0, 50, size=rng.integers(0, 6))] for _ in range(40)]
+    order = rng.integers(0, 40, size=1500)
+    for i in range(1, len(order)):   # break up accidental neighbours
+        if order[i] == order[i - 1]:
+            order[i] = (order[i] + 1) % 40
+    lists = [base[i] for i in order]
+    batch = synth.batch_from_lists([lists, lists[::-1], lists])
+    w = synth.scaled(synth.WORKLOADS["cfg1"], F=3, B=len(lists), rows=50, D=64)
+    _fused_case(ctx, w, batch)
+
+
+def test_fused_accepts_any_row_of_a_list_as_its_first(ctx):
+    """u_first_row may name any row that holds the list (here: the last one); the output is the same,
+    only more of it is copied by the second pass."""
+    w = synth.scaled(synth.WORKLOADS["cfg2"], F=4, B=1024, rows=20_000, D=64)
+    batch = synth.make_batch(w, 2)
+
+    def last_rows(ik, first):
+        inv = ik.inverse.cpu().numpy().astype(np.int64)
+        fu = ik.feat_uoff.cpu().numpy()
+        u = inv + np.repeat(fu[:-1], batch.B)
+        last = np.zeros(ik.U, dtype=np.int32)
+        last[u] = np.arange(batch.F * batch.B, dtype=np.int32)   # later rows overwrite earlier ones
+        return gu.to_dev(last)
+
+    _fused_case(ctx, w, batch, first_override=last_rows)
+
+
+def test_fused_edge_sizes(ctx):
+    for lists in ([[[], [], []]], [[[5]]], [[[1, 2], [1, 2]], [[], [3]]]):
+        batch = synth.batch_from_lists(lists)
+        w = synth.scaled(synth.WORKLOADS["cfg1"], F=batch.F, B=batch.B, rows=10, D=8)
+        _fused_case(ctx, w, batch)
+    # no rows at all: a no-op
+    z = torch.zeros(4, dtype=torch.int64, device="cuda")
+    zi = torch.zeros(4, dtype=torch.int32, device="cuda")
+    tab = [torch.zeros(5, 8, device="cuda")]
+    o = torch.zeros(1, 0, 8, device="cuda")
+    ctx.pooled_lookup_expand(tab, 0, z, z, z, zi, zi, 0, torch.zeros(1, 8, device="cuda"), o)
+
+
+def test_fused_on_a_grouped_ikjt(ctx):
+    """First rows from the inverse alone serve the IKJT of another builder."""
+    w = synth.scaled(synth.WORKLOADS["cfg5"], F=6, B=1024, rows=20_000, D=64)
+    batch = synth.make_batch(w, 0)
+    F, B, D = w.F, w.B, w.D
+    values, offsets = gu.to_dev(batch.values), gu.to_dev(batch.offsets)
+    ik = gu.DeviceIKJT(F, B, batch.N)
+    inv_g = torch.zeros(2 * B, dtype=torch.int32, device="cuda")
+    g_uoff = torch.zeros(3, dtype=torch.int64, device="cuda")
+    cnt = ctx.build_ikjt_grouped(F, B, [0, 3, 6], values, offsets, ik.u_values, ik.u_offsets, inv_g, g_uoff,
+                                 ik.feat_uoff, ik.inverse, want_counts=True)
+    first = torch.zeros(F * B, dtype=torch.int32, device="cuda")
+    ctx.ikjt_first_rows(F, B, ik.inverse, ik.feat_uoff, first)
+    d_tabs = gu.tables_to_dev(synth.make_tables(w), "f32")
+    pooled = torch.zeros(F * B, D, device="cuda")
+    out = torch.zeros(F, B, D, device="cuda")
+    kjt = torch.zeros(F, B, D, device="cuda")
+    ctx.pooled_lookup_expand(d_tabs, B, ik.u_values, ik.u_offsets, ik.feat_uoff, ik.inverse, first, cnt[0], pooled, out)
+    ctx.kjt_pooled_lookup(d_tabs, B, values, offsets, kjt)
+    assert torch.equal(out, kjt)
+
+
+def test_fused_validation_and_argument_errors(ctx, recd):
+    batch = synth.batch_from_lists([[[1], [2], [1]]])
+    w = synth.scaled(synth.WORKLOADS["cfg1"], F=1, B=3, rows=10, D=8)
+    values, offsets, ik, first, _ = _build_rows(ctx, batch)
+    tab = gu.tables_to_dev(synth.make_tables(w), "f32")
+    pooled = torch.zeros(3, 8, device="cuda")
+    out = torch.zeros(1, 3, 8, device="cuda")
+    with pytest.raises(recd.RecdError) as e:
+        ctx.pooled_lookup_expand(tab, 3, ik.u_values, ik.u_offsets, ik.feat_uoff, ik.inverse, None, 3, pooled, out)
+    assert e.value.status == recd.RECD_EINVAL
+    ctx.set_option(recd.RECD_OPT_VALIDATE, 1)
+    try:
+        ctx.pooled_lookup_expand(tab, 3, ik.u_values, ik.u_offsets, ik.feat_uoff, ik.inverse, first, 3, pooled, out)
+        bad = first.clone()
+        bad[1] = 0   # row 0 holds slot 0, not slot 1
+        with pytest.raises(recd.RecdError) as e:
+            ctx.pooled_lookup_expand(tab, 3, ik.u_values, ik.u_offsets, ik.feat_uoff, ik.inverse, bad, 3, pooled, out)
+        assert e.value.status == recd.RECD_EBOUNDS
+        bad[1] = 2 ** 31 - 1
+        with pytest.raises(recd.RecdError) as e:
+            ctx.pooled_lookup_expand(tab, 3, ik.u_values, ik.u_offsets, ik.feat_uoff, ik.inverse, bad, 3, pooled, out)
+        assert e.value.status == recd.RECD_EBOUNDS
+    finally:
+        ctx.set_option(recd.RECD_OPT_VALIDATE, 0)
+
+
+def test_fused_leaves_a_pending_plan_alone(ctx, recd):
+    """The fused forward does not use the workspace: a backward plan enqueued before it stays valid
+    and starts at the end of the build."""
+    w = synth.scaled(synth.WORKLOADS["cfg5"], F=8, B=2048, rows=30_000, D=64)
+    F, B, D = w.F, w.B, w.D
+    batch = synth.make_batch(w, 0)
+    gout = gu.to_dev(synth.make_grad_out(w, 0))
+    d_tabs = gu.tables_to_dev(synth.make_tables(w), "f32")
+    values, offsets, ik, first, _ = _build_rows(ctx, batch)
+    U, M = ik.U, ik.M
+    touched = torch.zeros(M, dtype=torch.int64, device="cuda")
+    feat_roff = torch.zeros(F + 1, dtype=torch.int64, device="cuda")
+    grad_rows = torch.zeros(M, D, device="cuda")
+    pooled = torch.zeros(F * B, D, device="cuda")
+    out = torch.zeros(F, B, D, device="cuda")
+    ctx.build_ikjt_rows(F, B, values, offsets, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff, first)
+    ctx.backward_plan(F, B, D, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F, U, M, touched,
+                      feat_roff)
+    ctx.pooled_lookup_expand(d_tabs, B, ik.u_values, ik.u_offsets, ik.feat_uoff, ik.inverse, first, U, pooled, out)
+    R = ctx.backward_apply(gout, grad_rows, want_count=True)
+    c2 = recd.Context(0)
+    t2, f2, g2 = torch.zeros_like(touched), torch.zeros_like(feat_roff), torch.zeros_like(grad_rows)
+    R2 = c2.backward_dedup(F, B, gout, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F, U, M,
+                           t2, f2, g2, want_count=True)
+    torch.cuda.synchronize()
+    c2.close()
+    assert R == R2 and torch.equal(touched[:R], t2[:R]) and torch.equal(grad_rows[:R], g2[:R])

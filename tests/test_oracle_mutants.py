@@ -70,6 +70,8 @@ MUTANTS = [
      "if (best < 0 || tables[f][u_values[j] * D + d] >= tables[f][u_values[best] * D + d])", 0),
     ("max_backward_kjt_minimum", "if (best < 0 || tables[f][values[j] * D + d] > tables[f][values[best] * D + d])",
      "if (best < 0 || tables[f][values[j] * D + d] < tables[f][values[best] * D + d])", 0),
+    ("first_rows_keeps_last", "if (first_row[feat_uoff[f] + k] < 0)\n", "if (1)\n", 0),
+    ("first_rows_local_row", "first_row[feat_uoff[f] + k] = (int64_t)f * B + b;", "first_row[feat_uoff[f] + k] = b;", 0),
     ("touched_rows_unsorted", "qsort(tmp, n, sizeof(int64_t), cmp_i64);\n    int64_t r = 0;",
      "int64_t r = 0;", 0),
 ]

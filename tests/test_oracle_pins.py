@@ -261,6 +261,52 @@ def test_lookup_special_cases():
     assert out[0, 0, 0] == 1.0 + 2.0 ** -29
 
 
+def test_first_rows_paper_example_and_unique_index(golden_dir):
+    """Where each unique list first occurs: the paper's feature b (rows 0 and 2 share slot 0, row 1
+    holds slot 1) gives rows [0, 1]; in general it is numpy's unique(return_index) per feature."""
+    g = _golden(golden_dir, "paper_ikjt_feature_b.json")
+    kjt = synth.batch_from_lists([g["rows"]])
+    uv, uo, inv, fu = orc.build_ikjt(1, 3, kjt.values, kjt.offsets)
+    assert orc.first_rows(1, 3, inv, fu).tolist() == [0, 1]
+    rng = np.random.default_rng(11)
+    F, B = 4, 57
+    U = [5, 1, 57, 9]
+    fu = np.concatenate([[0], np.cumsum(U)])
+    cols = []
+    for u in U:   # every slot is named at least once, in any order, with repeats anywhere
+        c = np.concatenate([np.arange(u), rng.integers(0, u, size=B - u)])
+        cols.append(rng.permutation(c))
+    inv = np.concatenate(cols).astype(np.int32)
+    got = orc.first_rows(F, B, inv, fu)
+    for f in range(F):
+        slots, idx = np.unique(inv[f * B:(f + 1) * B], return_index=True)
+        assert slots.tolist() == list(range(U[f]))
+        assert np.array_equal(got[fu[f]:fu[f + 1]], idx + f * B)
+    # brute force, written differently: no earlier row of the feature names the slot
+    for f in range(F):
+        for k in range(U[f]):
+            r = int(got[fu[f] + k]) - f * B
+            assert inv[f * B + r] == k and not (inv[f * B:f * B + r] == k).any()
+    # a slot nobody names is reported as -1; a slot outside the feature is refused
+    assert orc.first_rows(1, 2, np.array([1, 1], np.int32), np.array([0, 2])).tolist() == [-1, 0]
+    with pytest.raises(orc.OracleError):
+        orc.first_rows(1, 2, np.array([0, 2], np.int32), np.array([0, 2]))
+
+
+def test_first_rows_of_an_ikjt_increase_with_the_slot():
+    """Slots are numbered in order of first occurrence (Sec. 4.2 example), so within a feature the
+    first rows increase with the slot, and decoding the row gives the stored list."""
+    w = synth.scaled(synth.WORKLOADS["cfg2"], F=3, B=200, rows=500)
+    b = synth.make_batch(w, 0)
+    uv, uo, inv, fu = orc.build_ikjt(w.F, w.B, b.values, b.offsets)
+    fr = orc.first_rows(w.F, w.B, inv, fu)
+    for f in range(w.F):
+        seg = fr[fu[f]:fu[f + 1]]
+        assert seg[0] == f * w.B and np.all(np.diff(seg) > 0)
+    for u, l in enumerate(fr):
+        assert np.array_equal(b.values[b.offsets[l]:b.offsets[l + 1]], uv[uo[u]:uo[u + 1]])
+
+
 def test_expand_matches_index_select():
     rng = np.random.default_rng(5)
     F, B, D = 3, 29, 5
