@@ -18,7 +18,7 @@
  *   14. backward of the sequence path   15. backward of the averaged pooled lookup
  *   16-19. per-id weights: builder, unique and KJT lookups, backward
  *   20. backward of the max-pooled lookup   21, 22. the backward in two halves (plan / apply)
- *   23, 24. first row of every unique list   25. lookup and expand in one pass
+ *   23, 24. run index of a batch (adjacent rows holding one list)   25. lookup and expand in one pass
  *
  * General rules
  *   - Every array argument marked "device" is a pointer into GPU memory owned by the caller and
@@ -465,46 +465,50 @@ recd_status recd_backward_dedup_max(recd_ctx *ctx, int F, int64_t B, int D, cons
                                     float *const *adagrad_state, float lr, float eps,
                                     int64_t *host_R);
 
-/* 23. Call 1 that also returns where every unique list first occurs (Sec. 4.2: the batch's rows are
- *    clustered by session, so the duplicates of a list sit right behind its first occurrence; calls
- *    25 and the backward use that).
- *    u_first_row: device int32, capacity F*B: u_first_row[u] = f*B + b of the first row (smallest b)
- *    of feature f that holds unique list u; entries at and beyond U are left untouched.
- *    Everything else as in call 1 (same kernels; the array is the builder's own record of the
- *    first occurrences, written to the caller's memory instead of the workspace). */
-recd_status recd_build_ikjt_rows(recd_ctx *ctx, int F, int64_t B, int64_t N,
+/* 23. Call 1 that also returns the batch's run index (Sec. 4.2: the rows of a batch are clustered
+ *    by session, so the duplicates of a list sit right behind its first occurrence; a run is a
+ *    maximal block of adjacent rows of one feature that hold the same list).  Calls 25 and the
+ *    backward work run by run.
+ *    run_index: device int64, capacity 3 * (F*B + 2), triples:
+ *      triple 0           {number of runs R, U, M}
+ *      triple 1 + r       run r, in (feature, row) order:
+ *                         {row | (u | first << 31) << 32,  position of list u's ids in u_values,
+ *                          number of ids}   with row = f*B + b of the run's first row (low 32 bits), u
+ *                         the global unique-list index (feat_uoff[f] + inverse[row]) and first = 1 iff
+ *                         the run starts at the first row of the batch that holds list u
+ *      triple 1 + R       closing entry {F*B, M, 0}: run r covers the rows [row_r, row_{r+1})
+ *    Everything else as in call 1 (same kernels; the entries are written by the builder's last
+ *    kernel from what it holds anyway). */
+recd_status recd_build_ikjt_runs(recd_ctx *ctx, int F, int64_t B, int64_t N,
                                  const int64_t *values, const int64_t *offsets,
                                  int64_t *u_values, int64_t *u_offsets, int32_t *inverse,
-                                 int64_t *feat_uoff, int32_t *u_first_row, int64_t *host_U_M);
+                                 int64_t *feat_uoff, int64_t *run_index, int64_t *host_U_M);
 
-/* 24. The same array from an inverse index alone, for IKJTs of the other builders (calls 9, 12, 16)
- *    or of another producer: u_first_row[u] = the smallest row f*B + b with
- *    feat_uoff[f] + inverse[f*B+b] = u.  max_lists: capacity of u_first_row in entries (F*B always
- *    suffices; entries of slots that no row names are set to 2^31-1). */
-recd_status recd_ikjt_first_rows(recd_ctx *ctx, int F, int64_t B, const int32_t *inverse,
-                                 const int64_t *feat_uoff, int64_t max_lists, int32_t *u_first_row);
+/* 24. The same run index from an IKJT's arrays alone, for IKJTs of the other builders (calls 9, 12,
+ *    16) or of another producer.  inverse [F*B], feat_uoff [F+1], u_offsets [U+1]: device.
+ *    Uses the context's workspace. */
+recd_status recd_ikjt_run_index(recd_ctx *ctx, int F, int64_t B, const int32_t *inverse,
+                                const int64_t *feat_uoff, const int64_t *u_offsets,
+                                int64_t *run_index);
 
 /* 25. Calls 2 and 3 in one pass (Sec. 5 "EMB Lookups": the lookup runs on the unique lists only;
  *    "Jagged Index Select": the index select back to the batch is the only work deduplication adds
- *    - here most of it rides on the lookup).  The wave that finishes unique list u stores the row to
- *    pooled[u,:] and, while other waves wait for their table rows, to out[f,b,:] of the run of rows
- *    that starts at u_first_row[u] and names u (with session-clustered batches that is nearly every
- *    row of u); a second short kernel copies pooled[u,:] to the rows of u that are not in that run.
- *    Results: pooled and out hold exactly the bits calls 2 and 3 produce.
- *    u_first_row: device int32 [U] from call 23 or 24 (any row of list u's feature that names u is
- *    accepted; the first one makes the first pass cover the most).
- *    inverse: device int32 [F*B].  max_lists: as in call 2 (sizes the launch only; 0 = F*B).
+ *    - here most of it rides on the lookup).  The wave that sums unique list u, for the run that
+ *    starts at u's first row, stores the finished row to pooled[u,:] and to out[f,b,:] of every row
+ *    of the run; a second short kernel copies pooled[u,:] to the runs of u that come later in the
+ *    batch.  One entry of the run index tells a wave all it needs (the ids' position and count, the
+ *    rows to write), so a list costs two dependent memory round trips before its first table row
+ *    instead of three.  Results: pooled and out hold exactly the bits calls 2 and 3 produce.
+ *    run_index: device, from call 23 or 24.  max_runs: the host's estimate of the number of runs
+ *    (sizes the launch only, as max_lists in call 2; 0 = F*B).  u_values: device [M].
  *    pooled: device [U, D] of out_dt (room for U rows; F*B when U is not known).
  *    out: device [F, B, D] of out_dt.  Sum pooling; dtypes and D as in call 2.
- *    The context keeps 8 bytes per row of the batch (F*B) for the row ranges the first pass wrote:
- *    allocated by the first call of a size (which synchronises the stream), held until
- *    recd_destroy; the call does not use the workspace. */
+ *    The call does not use the context's workspace (a pending backward plan stays valid). */
 recd_status recd_pooled_lookup_expand(recd_ctx *ctx, int F, int64_t B, int D, recd_dtype table_dt,
                                       recd_dtype out_dt, const void *const *tables,
                                       const int64_t *rows, const int64_t *u_values,
-                                      const int64_t *u_offsets, const int64_t *feat_uoff,
-                                      const int32_t *inverse, const int32_t *u_first_row,
-                                      int64_t max_lists, void *pooled, void *out);
+                                      const int64_t *run_index, int64_t max_runs, void *pooled,
+                                      void *out);
 
 /* Call 1 for callers that cannot allocate: code under HIP graph capture, serving loops and harnesses
  *    in which hipMalloc is forbidden.  Same arguments, same outputs bit for bit as recd_build_ikjt,

@@ -466,6 +466,41 @@ int oracle_first_rows(int F, int64_t B, const int32_t *inverse, const int64_t *f
     return 0;
 }
 
+/* ---- runs of a batch (Sec. 4.2: a session's rows are adjacent, so duplicates come in runs) ------
+ * A run is a maximal block of adjacent rows of one feature that name the same slot.  For run r, in
+ * (feature, row) order: run_row[r] = f*B + b of its first row, run_list[r] = feat_uoff[f] + slot,
+ * run_first[r] = 1 iff no earlier row of the feature names the slot, run_start[r] / run_ids[r] =
+ * position and count of the list's ids in u_values.  run_row[R] = F*B closes the last run.
+ * Returns R, or a negative code.
+ */
+int64_t oracle_run_index(int F, int64_t B, const int32_t *inverse, const int64_t *feat_uoff,
+                         const int64_t *u_offsets, int64_t *run_row, int64_t *run_list,
+                         int32_t *run_first, int64_t *run_start, int64_t *run_ids)
+{
+    int64_t R = 0;
+    for (int f = 0; f < F; f++)
+        for (int64_t b = 0; b < B; b++) {
+            const int64_t l = (int64_t)f * B + b;
+            const int64_t k = inverse[l];
+            if (k < 0 || k >= feat_uoff[f + 1] - feat_uoff[f])
+                return -5;
+            if (b > 0 && inverse[l - 1] == k)
+                continue; /* the row continues the run of the row before it */
+            int seen = 0;
+            for (int64_t b2 = 0; b2 < b && !seen; b2++)
+                seen = inverse[(int64_t)f * B + b2] == k;
+            const int64_t u = feat_uoff[f] + k;
+            run_row[R] = l;
+            run_list[R] = u;
+            run_first[R] = !seen;
+            run_start[R] = u_offsets[u];
+            run_ids[R] = u_offsets[u + 1] - u_offsets[u];
+            R++;
+        }
+    run_row[R] = (int64_t)F * B;
+    return R;
+}
+
 /* ---- per-id activations (Sec. 2.2: an EMB produces a dense activation vector for each list
  * element; Sec. 5 "EMB Inputs and Activations": with an IKJT only the unique values are looked up) --
  * emb[j,:] = W_f[values[j],:] for every position j of the lists [list_off[f], list_off[f+1]) of

@@ -219,6 +219,41 @@ def first_rows(F: int, B: int, inverse, feat_uoff) -> np.ndarray:
     return out[:int(feat_uoff[F])]
 
 
+def run_index(F: int, B: int, inverse, feat_uoff, u_offsets):
+    """Runs of adjacent rows naming one unique list, in (feature, row) order.  Returns
+    (run_row[R+1], run_list[R], run_first[R], run_start[R], run_ids[R]); run_row[R] = F*B."""
+    inverse = np.ascontiguousarray(inverse, dtype=np.int32)
+    feat_uoff, u_offsets = _i64(feat_uoff), _i64(u_offsets)
+    L = F * B
+    row = np.zeros(L + 1, dtype=np.int64)
+    lst = np.zeros(max(L, 1), dtype=np.int64)
+    first = np.zeros(max(L, 1), dtype=np.int32)
+    start = np.zeros(max(L, 1), dtype=np.int64)
+    ids = np.zeros(max(L, 1), dtype=np.int64)
+    inv = inverse if inverse.size else np.zeros(1, dtype=np.int32)
+    _lib.oracle_run_index.restype = C.c_int64
+    R = int(_lib.oracle_run_index(C.c_int(F), C.c_int64(B), _p(inv, _i32p), _p(feat_uoff, _i64p),
+                                  _p(u_offsets, _i64p), _p(row, _i64p), _p(lst, _i64p), _p(first, _i32p),
+                                  _p(start, _i64p), _p(ids, _i64p)))
+    if R < 0:
+        raise OracleError(f"run_index: precondition violated (code {R})")
+    return row[:R + 1], lst[:R], first[:R], start[:R], ids[:R]
+
+
+def pack_run_index(row, lst, first, start, ids, U: int, M: int) -> np.ndarray:
+    """The run index in the library's int64 triples: {R, U, M}, then per run
+    {row | (list | first << 31) << 32, ids at, ids}, then the closing entry {F*B, M, 0}."""
+    R = len(lst)
+    out = np.zeros(3 * (R + 2), dtype=np.uint64)
+    out[0:3] = (R, U, M)
+    uf = lst.astype(np.uint64) | (first.astype(np.uint64) << np.uint64(31))
+    out[3:3 + 3 * R:3] = row[:R].astype(np.uint64) | (uf << np.uint64(32))
+    out[4:4 + 3 * R:3] = start.astype(np.uint64)
+    out[5:5 + 3 * R:3] = ids.astype(np.uint64)
+    out[3 + 3 * R:6 + 3 * R] = (int(row[R]), M, 0)
+    return out.view(np.int64)
+
+
 def group_sum(group_off, pooled: np.ndarray, feat_uoff, group_uoff) -> np.ndarray:
     """Element-wise sum over the features of every group on the unique rows (Sec. 5 "Deduplicated
     Pooling").  pooled float64 [U, D] -> float64 [sum of U_g, D]."""

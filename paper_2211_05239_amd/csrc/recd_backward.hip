@@ -1209,10 +1209,12 @@ recd_status sum_rows(recd_ctx *ctx, const BwdWs &w, const uint32_t *ps, int64_t 
     RECD_HIP(ctx, hipGetLastError());
     RECD_HIP(ctx, hipEventRecord(ctx->ev_join, side));
     // 2. short segments summed and updated
+    recd_time_begin(ctx, RECD_T_GRAD_ROWS, st);
     if (pay_w)
         launch_rows(std::false_type(), std::true_type(), (unsigned)nblk, st);
     else
         launch_rows(std::false_type(), std::false_type(), (unsigned)nblk, st);
+    recd_time_end(ctx, RECD_T_GRAD_ROWS, st);
     RECD_HIP(ctx, hipGetLastError());
     RECD_HIP(ctx, hipStreamWaitEvent(st, ctx->ev_join, 0));
     return RECD_OK;

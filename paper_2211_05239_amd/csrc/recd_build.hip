@@ -309,8 +309,10 @@ __global__ __launch_bounds__(kScanBlock) void k_flags(const int64_t *__restrict_
             }
         }
     }
+    // two counts ride in one sum: first occurrences in the low half, run heads in the high half
+    // (both stay below 2^31)
     int64_t ea, eb, ic, ta, tb, tc;
-    block_scan3(first, flen, head, ea, eb, ic, ta, tb, tc);
+    block_scan3(first + ((int64_t)(head >= 0) << 32), flen, head, ea, eb, ic, ta, tb, tc);
     if (threadIdx.x == 0) {
         bs_cnt[blockIdx.x] = ta;
         bs_len[blockIdx.x] = tb;
@@ -362,7 +364,9 @@ __global__ __launch_bounds__(kScanBlock) void k_number(const int64_t *__restrict
                                                        int64_t *__restrict__ u_offsets,
                                                        int64_t *__restrict__ feat_uoff,
                                                        int64_t *__restrict__ counts,
-                                                       int64_t *mailbox, int64_t seq)
+                                                       int64_t *mailbox, int64_t seq,
+                                                       int32_t *__restrict__ hrank = nullptr,
+                                                       int64_t *__restrict__ run_index = nullptr)
 {
     const int64_t l = (int64_t)blockIdx.x * kScanBlock + threadIdx.x;
     int64_t first = 0, flen = 0, head = -1, b = -1, f = 0, my_rep = -1;
@@ -381,8 +385,11 @@ __global__ __launch_bounds__(kScanBlock) void k_number(const int64_t *__restrict
         }
     }
     int64_t ea, eb, ic, ta, tb, tc;
-    block_scan3(first, flen, head, ea, eb, ic, ta, tb, tc);
+    block_scan3(first + ((int64_t)(head >= 0) << 32), flen, head, ea, eb, ic, ta, tb, tc);
     if (l < n_lists) {
+        const int64_t packed = bs_cnt[blockIdx.x] + ea;   // first occurrences | run heads before l
+        if (hrank)
+            hrank[l] = head >= 0 ? (int32_t)(packed >> 32) : -1;
         if (head < 0) {
             // follower: copy the representative of the run head (the nearest head at or before l;
             // row 0 of a feature is always a head, so the run never leaves the feature)
@@ -392,7 +399,7 @@ __global__ __launch_bounds__(kScanBlock) void k_number(const int64_t *__restrict
             my_rep = (int64_t)(e & 0xffffffffull);
         }
         rep[l] = (int32_t)my_rep;
-        const int64_t num = bs_cnt[blockIdx.x] + ea;  // unique lists before (f,b), all features
+        const int64_t num = packed & 0xffffffffll;  // unique lists before (f,b), all features
         const int64_t pos = bs_len[blockIdx.x] + eb;  // their ids
         number[l] = (int32_t)num;
         if (first) {
@@ -407,6 +414,16 @@ __global__ __launch_bounds__(kScanBlock) void k_number(const int64_t *__restrict
             feat_uoff[F] = U;
             counts[0] = U;
             counts[1] = M;
+            if (run_index) {
+                // header {runs, U, M} and the closing entry (a run ends where the next one starts)
+                const int64_t n_runs = (packed >> 32) + (head >= 0);
+                run_index[0] = n_runs;
+                run_index[1] = U;
+                run_index[2] = M;
+                run_index[3 * (1 + n_runs)] = n_lists;
+                run_index[3 * (1 + n_runs) + 1] = M;
+                run_index[3 * (1 + n_runs) + 2] = 0;
+            }
             if (mailbox) {
                 // U and M are final here: the host may have them while the last builder kernel still
                 // copies ids (values first, the sequence number last, each visible to the host
@@ -438,7 +455,8 @@ __global__ __launch_bounds__(256) void k_emit(const int64_t *__restrict__ values
                                               const uint32_t *__restrict__ wbits = nullptr,
                                               uint32_t *__restrict__ u_wbits = nullptr,
                                               unsigned fill_blocks = 0, uint64_t *fill = nullptr,
-                                              int64_t fill_n = 0)
+                                              int64_t fill_n = 0, const int32_t *__restrict__ hrank = nullptr,
+                                              int64_t *__restrict__ run_index = nullptr)
 {
     if (blockIdx.x < fill_blocks) {
         // the hash tables are no longer needed: leave them empty for the next build
@@ -451,7 +469,16 @@ __global__ __launch_bounds__(256) void k_emit(const int64_t *__restrict__ values
         const int64_t l = (int64_t)bid * 256 + threadIdx.x;
         if (l < n_lists) {
             const int64_t f = l / B;
-            inverse[l] = number[f * B + rep[l]] - number[f * B];
+            const int32_t u = number[f * B + rep[l]];
+            inverse[l] = u - number[f * B];
+            if (run_index && hrank[l] >= 0) {
+                // run entry: {row | (unique list, first-occurrence flag) << 32, ids at, ids}
+                int64_t *e = run_index + 3 * (1 + (int64_t)hrank[l]);
+                const uint32_t uf = (uint32_t)u | (rep[l] == (int32_t)(l - f * B) ? 0x80000000u : 0u);
+                e[0] = (int64_t)(((uint64_t)uf << 32) | (uint32_t)l);
+                e[1] = u_offsets[u];
+                e[2] = offsets[l + 1] - offsets[l];
+            }
         }
         return;
     }
@@ -793,6 +820,84 @@ __global__ void k_empty_partial(int F, int64_t *feat_uoff, int64_t *feat_poff, i
         counts[0] = counts[1] = counts[2] = 0;
 }
 
+// ---- run index of an IKJT from its arrays alone ------------------------------------------------
+// A run is a maximal block of adjacent rows of a feature that name the same slot; its head is row 0
+// of the feature or a row whose predecessor names another slot.  The first row of a slot is the
+// smallest of its run heads.
+__global__ __launch_bounds__(256) void k_fill_i32(int32_t *p, int64_t n, int32_t v)
+{
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256)
+        p[i] = v;
+}
+
+__global__ __launch_bounds__(256) void k_run_first(const int32_t *__restrict__ inverse,
+                                                   const int64_t *__restrict__ feat_uoff, int64_t B,
+                                                   int64_t n_rows, int32_t *__restrict__ first_row)
+{
+    const int64_t l = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (l >= n_rows)
+        return;
+    const int64_t f = l / B;
+    const int32_t inv = inverse[l];
+    if (l - f * B != 0 && inverse[l - 1] == inv)
+        return;
+    atomicMin(&first_row[feat_uoff[f] + inv], (int32_t)l);
+}
+
+// EMIT = false: per-block counts of run heads.  EMIT = true, after the scan of the block counts:
+// the entries {row | (unique list, first-occurrence flag) << 32, ids at, ids}, the header
+// {runs, U, M} and the closing entry.
+template <bool EMIT>
+__global__ __launch_bounds__(kScanBlock) void k_run_entries(const int32_t *__restrict__ inverse,
+                                                            const int64_t *__restrict__ feat_uoff,
+                                                            const int64_t *__restrict__ u_offsets, int64_t B,
+                                                            int64_t n_rows, int F,
+                                                            const int32_t *__restrict__ first_row,
+                                                            int64_t *__restrict__ bs_cnt,
+                                                            int64_t *__restrict__ bs_len,
+                                                            int64_t *__restrict__ bs_head,
+                                                            int64_t *__restrict__ run_index)
+{
+    const int64_t l = (int64_t)blockIdx.x * kScanBlock + threadIdx.x;
+    int64_t head = 0, f = 0;
+    int32_t inv = 0;
+    if (l < n_rows) {
+        f = l / B;
+        inv = inverse[l];
+        head = (l - f * B == 0 || inverse[l - 1] != inv) ? 1 : 0;
+    }
+    int64_t ea, eb, ic, ta, tb, tc;
+    block_scan3(head, 0, -1, ea, eb, ic, ta, tb, tc);
+    if (!EMIT) {
+        if (threadIdx.x == 0) {
+            bs_cnt[blockIdx.x] = ta;
+            bs_len[blockIdx.x] = 0;
+            bs_head[blockIdx.x] = -1;
+        }
+        return;
+    }
+    if (l < n_rows) {
+        const int64_t r = bs_cnt[blockIdx.x] + ea;
+        if (head) {
+            const int64_t u = feat_uoff[f] + inv;
+            int64_t *e = run_index + 3 * (1 + r);
+            const uint32_t uf = (uint32_t)u | (first_row[u] == (int32_t)l ? 0x80000000u : 0u);
+            e[0] = (int64_t)(((uint64_t)uf << 32) | (uint32_t)l);
+            e[1] = u_offsets[u];
+            e[2] = u_offsets[u + 1] - u_offsets[u];
+        }
+        if (l == n_rows - 1) {
+            const int64_t n_runs = r + head, U = feat_uoff[F], M = u_offsets[U];
+            run_index[0] = n_runs;
+            run_index[1] = U;
+            run_index[2] = M;
+            run_index[3 * (1 + n_runs)] = n_rows;
+            run_index[3 * (1 + n_runs) + 1] = M;
+            run_index[3 * (1 + n_runs) + 2] = 0;
+        }
+    }
+}
+
 uint64_t table_cap(int64_t B)
 {
     uint64_t cap = 64;
@@ -805,14 +910,14 @@ uint64_t table_cap(int64_t B)
 
 size_t recd_build_workspace(int F, int64_t B)
 {
-    // Covers the three builders (plain, grouped with up to F groups, partial): the hash table, six
+    // Covers the three builders (plain, grouped with up to F groups, partial): the hash table, seven
     // int32 and three int64 arrays of one entry per list, the block sums and the small maps, each
     // rounded up to the carver's 256-byte pieces.
     const int64_t n_lists = (int64_t)F * B;
     const int64_t nblk = (n_lists + kScanBlock - 1) / kScanBlock;
     size_t bytes = 0;
     bytes += (size_t)F * table_cap(B) * sizeof(uint64_t);
-    bytes += 6 * ((size_t)n_lists * sizeof(int32_t) + 256);
+    bytes += 7 * ((size_t)n_lists * sizeof(int32_t) + 256);
     bytes += 3 * ((size_t)(n_lists + 1) * sizeof(int64_t) + 256);
     bytes += 3 * ((size_t)(nblk + 1) * sizeof(int64_t) + 256);
     bytes += 2 * ((size_t)(F + 2) * sizeof(int64_t) + 256);
@@ -828,7 +933,7 @@ struct SlotWs {
     int64_t *counts;
     uint64_t *table;
     uint64_t cap;
-    int32_t *slot_of, *rep, *number, *src_of;
+    int32_t *slot_of, *rep, *number, *src_of, *hrank;
     int64_t *bs_cnt, *bs_len, *bs_head;
 };
 
@@ -843,6 +948,7 @@ SlotWs carve_slots(WsCarver &c, int tables, int64_t B, int64_t items, int64_t sc
     w.rep = c.take<int32_t>(items);
     w.number = c.take<int32_t>(items);
     w.src_of = c.take<int32_t>(items);
+    w.hrank = c.take<int32_t>(items);
     w.bs_cnt = c.take<int64_t>(nblk + 1);
     w.bs_len = c.take<int64_t>(nblk + 1);
     w.bs_head = c.take<int64_t>(nblk + 1);
@@ -866,19 +972,22 @@ void insert_lists(recd_ctx *ctx, hipStream_t st, const SlotWs &w, int F, int64_t
     if (!table_is_empty)
         clear_table(st, w, F);
     const int64_t hblocks = (n_lists + (kHashBlock / SG) * kLPG - 1) / ((kHashBlock / SG) * kLPG);
+    recd_time_begin(ctx, RECD_T_HASH, st);
     if (wbits)
         hipLaunchKernelGGL((k_hash_insert<SG, true>), dim3((unsigned)hblocks), dim3(kHashBlock), 0, st, values, wbits,
                            offsets, B, n_lists, w.table, (uint32_t)(w.cap - 1), w.slot_of, ctx->weak_hash);
     else
         hipLaunchKernelGGL((k_hash_insert<SG, false>), dim3((unsigned)hblocks), dim3(kHashBlock), 0, st, values, wbits,
                            offsets, B, n_lists, w.table, (uint32_t)(w.cap - 1), w.slot_of, ctx->weak_hash);
+    recd_time_end(ctx, RECD_T_HASH, st);
 }
 
 // After the insertion: representative and first-occurrence number of every item, first row of
 // every slot, prefix of the slot counts per table (uoff) and, from the lengths that `offsets`
 // gives, the position of every slot's ids (u_off); counts = {slots, ids}.
 void number_slots(hipStream_t st, const SlotWs &w, int tables, int64_t B, const int64_t *offsets,
-                  int64_t *u_off, int64_t *uoff, int64_t *mailbox = nullptr, int64_t seq = 0)
+                  int64_t *u_off, int64_t *uoff, int64_t *mailbox = nullptr, int64_t seq = 0,
+                  int64_t *run_index = nullptr)
 {
     const int64_t n = (int64_t)tables * B;
     const unsigned nblk = (unsigned)((n + kScanBlock - 1) / kScanBlock);
@@ -889,7 +998,7 @@ void number_slots(hipStream_t st, const SlotWs &w, int tables, int64_t B, const 
                        (int64_t)nblk);
     hipLaunchKernelGGL(k_number, dim3(nblk), dim3(kScanBlock), 0, st, offsets, B, n, tables, w.table, mask,
                        w.slot_of, w.bs_cnt, w.bs_len, w.bs_head, w.rep, w.number, w.src_of, u_off, uoff,
-                       w.counts, mailbox, seq);
+                       w.counts, mailbox, seq, run_index ? w.hrank : nullptr, run_index);
 }
 
 unsigned copy_blocks_for(const recd_ctx *ctx, int64_t n_lists)
@@ -907,7 +1016,7 @@ unsigned copy_blocks_for(const recd_ctx *ctx, int64_t n_lists)
 static recd_status build_plain(recd_ctx *ctx, int F, int64_t B, int64_t N, const int64_t *values,
                                const uint32_t *weights, const int64_t *offsets, int64_t *u_values,
                                uint32_t *u_weights, int64_t *u_offsets, int32_t *inverse,
-                               int64_t *feat_uoff, int64_t *host_U_M, int32_t *u_first_row = nullptr)
+                               int64_t *feat_uoff, int64_t *host_U_M, int64_t *run_index = nullptr)
 {
     if (!ctx)
         return RECD_EINVAL;
@@ -928,14 +1037,15 @@ static recd_status build_plain(recd_ctx *ctx, int F, int64_t B, int64_t N, const
     WsCarver c(ctx->ws);
     SlotWs w = carve_slots(c, F, B, n_lists, n_lists);
     w.counts = ctx->build_counts_dev;  // {U, M}: outlives the workspace's reuse by later calls
-    if (u_first_row)
-        w.src_of = u_first_row;  // the first row of every unique list, kept for the caller
     int64_t *counts = w.counts;
     hipStream_t st = ctx->stream;
     bool published = false;
 
     if (n_lists == 0) {
         hipLaunchKernelGGL(k_empty_ikjt, dim3(1), dim3(256), 0, st, F, u_offsets, feat_uoff, counts);
+        if (run_index)  // no runs: the header and the closing entry, all zero
+            hipLaunchKernelGGL(k_fill_u64, dim3(1), dim3(64), 0, st, reinterpret_cast<uint64_t *>(run_index),
+                               (int64_t)6, 0ull);
     } else {
         // the context's own tables (kept empty between builds) instead of the workspace's
         const size_t slots = (size_t)F * w.cap;
@@ -971,13 +1081,15 @@ static recd_status build_plain(recd_ctx *ctx, int F, int64_t B, int64_t N, const
             seq = ++ctx->build_seq;
             published = true;
         }
-        number_slots(st, w, F, B, offsets, u_offsets, feat_uoff, mailbox, seq);
+        number_slots(st, w, F, B, offsets, u_offsets, feat_uoff, mailbox, seq, run_index);
         const unsigned inv_blocks = (unsigned)((n_lists + 255) / 256);
         const unsigned fill_blocks = (unsigned)((slots + 4095) / 4096 < 2048 ? (slots + 4095) / 4096 : 2048);
+        recd_time_begin(ctx, RECD_T_EMIT, st);
         hipLaunchKernelGGL((k_emit<16>), dim3(fill_blocks + inv_blocks + copy_blocks_for(ctx, n_lists)), dim3(256), 0,
                            st, values, offsets, B, n_lists, w.rep, w.number, w.src_of, u_offsets, counts,
                            u_values, inverse, inv_blocks, weights, u_weights, fill_blocks, ctx->build_table,
-                           (int64_t)slots);
+                           (int64_t)slots, w.hrank, run_index);
+        recd_time_end(ctx, RECD_T_EMIT, st);
         RECD_HIP(ctx, hipGetLastError());
         ctx->table_clean = true;
     }
@@ -1014,7 +1126,7 @@ extern "C" recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t 
 namespace {
 constexpr size_t kStaticTableSlots = 4 * (size_t)RECD_NOALLOC_MAX_LISTS;  // F * cap(B) <= max(64 F, 4 F B)
 constexpr size_t kStaticScratchBytes =
-    kStaticTableSlots * sizeof(uint64_t) + 4 * ((size_t)RECD_NOALLOC_MAX_LISTS * sizeof(int32_t) + 256) +
+    kStaticTableSlots * sizeof(uint64_t) + 5 * ((size_t)RECD_NOALLOC_MAX_LISTS * sizeof(int32_t) + 256) +
     3 * ((RECD_NOALLOC_MAX_LISTS / kScanBlock + 2) * sizeof(int64_t) + 256) + 2 * 256;
 constexpr int kMaxDevices = 64;
 char *g_scratch_ptr[kMaxDevices];  // device address of this GPU's copy of `scratch`
@@ -1080,15 +1192,57 @@ extern "C" recd_status recd_build_ikjt_noalloc(recd_ctx *ctx, int F, int64_t B, 
     return RECD_OK;
 }
 
-extern "C" recd_status recd_build_ikjt_rows(recd_ctx *ctx, int F, int64_t B, int64_t N,
+extern "C" recd_status recd_build_ikjt_runs(recd_ctx *ctx, int F, int64_t B, int64_t N,
                                             const int64_t *values, const int64_t *offsets,
                                             int64_t *u_values, int64_t *u_offsets, int32_t *inverse,
-                                            int64_t *feat_uoff, int32_t *u_first_row, int64_t *host_U_M)
+                                            int64_t *feat_uoff, int64_t *run_index, int64_t *host_U_M)
 {
-    if (ctx && (int64_t)F * B > 0 && !u_first_row)
-        return recd_fail(ctx, RECD_EINVAL, "null u_first_row");
+    if (ctx && !run_index)
+        return recd_fail(ctx, RECD_EINVAL, "null run_index");
     return build_plain(ctx, F, B, N, values, nullptr, offsets, u_values, nullptr, u_offsets, inverse, feat_uoff,
-                       host_U_M, u_first_row);
+                       host_U_M, run_index);
+}
+
+extern "C" recd_status recd_ikjt_run_index(recd_ctx *ctx, int F, int64_t B, const int32_t *inverse,
+                                           const int64_t *feat_uoff, const int64_t *u_offsets,
+                                           int64_t *run_index)
+{
+    if (!ctx)
+        return RECD_EINVAL;
+    if (F < 0 || F > RECD_MAX_FEATURES || B < 0)
+        return recd_fail(ctx, RECD_EINVAL, "bad sizes F=%d B=%lld", F, (long long)B);
+    const int64_t n_rows = (int64_t)F * B;
+    if (n_rows >= (int64_t)1 << 31)
+        return recd_fail(ctx, RECD_EINVAL, "F*B must stay below 2^31");
+    if (!run_index || (n_rows > 0 && (!inverse || !feat_uoff || !u_offsets)))
+        return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
+    RECD_HIP(ctx, hipSetDevice(ctx->device));
+    hipStream_t st = ctx->stream;
+    if (n_rows == 0) {
+        hipLaunchKernelGGL(k_fill_u64, dim3(1), dim3(64), 0, st, reinterpret_cast<uint64_t *>(run_index), (int64_t)6,
+                           0ull);
+        RECD_HIP(ctx, hipGetLastError());
+        return RECD_OK;
+    }
+    if (ctx->validate)
+        RECD_TRY(recd_validate_inverse(ctx, F, B, feat_uoff, inverse));
+    const int64_t nblk = (n_rows + kScanBlock - 1) / kScanBlock;
+    ctx->plan.valid = false;  // this call reuses the workspace a backward plan would live in
+    RECD_TRY(recd_reserve(ctx, 1024 + (size_t)n_rows * sizeof(int32_t) + 3 * ((size_t)(nblk + 1) * sizeof(int64_t) + 256) + 1024));
+    WsCarver c(ctx->ws);
+    (void)c.take<char>(1024);  // the head of the workspace stays with the validation passes' flags
+    int32_t *first_row = c.take<int32_t>(n_rows);
+    int64_t *bs_cnt = c.take<int64_t>(nblk + 1), *bs_len = c.take<int64_t>(nblk + 1), *bs_head = c.take<int64_t>(nblk + 1);
+    const unsigned rb = (unsigned)((n_rows + 255) / 256);
+    hipLaunchKernelGGL(k_fill_i32, dim3(rb < 4096 ? rb : 4096), dim3(256), 0, st, first_row, n_rows, 0x7fffffff);
+    hipLaunchKernelGGL(k_run_first, dim3(rb), dim3(256), 0, st, inverse, feat_uoff, B, n_rows, first_row);
+    hipLaunchKernelGGL((k_run_entries<false>), dim3((unsigned)nblk), dim3(kScanBlock), 0, st, inverse, feat_uoff,
+                       u_offsets, B, n_rows, F, first_row, bs_cnt, bs_len, bs_head, run_index);
+    hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(kScanBlock), 0, st, bs_cnt, bs_len, bs_head, nblk);
+    hipLaunchKernelGGL((k_run_entries<true>), dim3((unsigned)nblk), dim3(kScanBlock), 0, st, inverse, feat_uoff,
+                       u_offsets, B, n_rows, F, first_row, bs_cnt, bs_len, bs_head, run_index);
+    RECD_HIP(ctx, hipGetLastError());
+    return RECD_OK;
 }
 
 extern "C" recd_status recd_build_ikjt_weighted(recd_ctx *ctx, int F, int64_t B, int64_t N,

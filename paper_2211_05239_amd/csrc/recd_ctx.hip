@@ -3,6 +3,7 @@
 
 #include "recd_internal.h"
 
+#include <algorithm>
 #include <atomic>
 #include <chrono>
 
@@ -62,6 +63,71 @@ recd_status recd_reserve(recd_ctx *ctx, size_t bytes)
     }
     ctx->ws = static_cast<char *>(p);
     ctx->ws_bytes = want;
+    return RECD_OK;
+}
+
+constexpr int kTimerPairs = 1024;
+
+void recd_time_begin(recd_ctx *ctx, int slot, hipStream_t st)
+{
+    if (!ctx->timing)
+        return;
+    KernelTimer &t = ctx->timers[slot];
+    if (t.n >= kTimerPairs)
+        return;
+    if ((int)t.a.size() <= t.n) {
+        hipEvent_t ea = nullptr, eb = nullptr;
+        if (hipEventCreate(&ea) != hipSuccess || hipEventCreate(&eb) != hipSuccess) {
+            (void)hipGetLastError();
+            return;
+        }
+        t.a.push_back(ea);
+        t.b.push_back(eb);
+    }
+    (void)hipEventRecord(t.a[t.n], st);
+}
+
+void recd_time_end(recd_ctx *ctx, int slot, hipStream_t st)
+{
+    if (!ctx->timing)
+        return;
+    KernelTimer &t = ctx->timers[slot];
+    if (t.n >= kTimerPairs || (int)t.a.size() <= t.n)
+        return;
+    (void)hipEventRecord(t.b[t.n], st);
+    t.n++;
+}
+
+// Not declared in the public header.  Average (and median) milliseconds of the event pairs recorded
+// for `slot` since the last reset; synchronises the device.  count = pairs averaged.
+extern "C" recd_status recd_internal_kernel_ms(recd_ctx *ctx, int slot, int reset, double *avg_ms, double *median_ms,
+                                               int *count)
+{
+    if (!ctx || slot < 0 || slot >= RECD_T_COUNT)
+        return RECD_EINVAL;
+    KernelTimer &t = ctx->timers[slot];
+    RECD_HIP(ctx, hipSetDevice(ctx->device));
+    RECD_HIP(ctx, hipDeviceSynchronize());
+    std::vector<float> ms;
+    for (int i = 0; i < t.n; i++) {
+        float x = 0.f;
+        if (hipEventElapsedTime(&x, t.a[i], t.b[i]) == hipSuccess)
+            ms.push_back(x);
+        else
+            (void)hipGetLastError();
+    }
+    double sum = 0.0;
+    for (float x : ms)
+        sum += x;
+    std::sort(ms.begin(), ms.end());
+    if (avg_ms)
+        *avg_ms = ms.empty() ? 0.0 : sum / (double)ms.size();
+    if (median_ms)
+        *median_ms = ms.empty() ? 0.0 : (double)ms[ms.size() / 2];
+    if (count)
+        *count = (int)ms.size();
+    if (reset)
+        t.n = 0;
     return RECD_OK;
 }
 
@@ -239,6 +305,11 @@ recd_status recd_destroy(recd_ctx *ctx)
         (void)hipStreamSynchronize(ctx->side_stream2);
         (void)hipStreamDestroy(ctx->side_stream2);
     }
+    for (KernelTimer &t : ctx->timers)
+        for (size_t i = 0; i < t.a.size(); i++) {
+            (void)hipEventDestroy(t.a[i]);
+            (void)hipEventDestroy(t.b[i]);
+        }
     if (ctx->ev_built)
         (void)hipEventDestroy(ctx->ev_built);
     if (ctx->ev_plan_a)
@@ -259,8 +330,6 @@ recd_status recd_destroy(recd_ctx *ctx)
         (void)hipFree(ctx->build_counts_dev);
     if (ctx->build_table)
         (void)hipFree(ctx->build_table);
-    if (ctx->cover)
-        (void)hipFree(ctx->cover);
     if (ctx->host_pinned)
         (void)hipHostFree(ctx->host_pinned);
     if (ctx->mailbox)
@@ -285,6 +354,7 @@ recd_status recd_set_option(recd_ctx *ctx, recd_option opt, int64_t value)
     default: break;
     }
     switch ((int)opt) {
+    case RECD_OPT_INTERNAL_TIMING: ctx->timing = value != 0; return RECD_OK;
     case RECD_OPT_INTERNAL_TUNE_SEGSUM:
         ctx->tune_lb = (int)(value % 100);
         ctx->tune_gens = (int)(value / 10000 % 100);

@@ -9,6 +9,26 @@
 
 #include "recd.h"
 
+// Optional HIP-event brackets around single kernel launches (benchmark instrumentation, off by
+// default): `slot` names the kernel, every bracket is one pair of events on the stream the kernel is
+// launched on; recd_internal_kernel_ms averages the pairs recorded since the last reset.
+enum {
+    RECD_T_LOOKUP_EXPAND = 0,  // fused unique lookup + first-run expand
+    RECD_T_UNCOVERED = 1,      // second pass of the fused expand
+    RECD_T_LOOKUP = 2,         // unique lookup (two-kernel path)
+    RECD_T_EXPAND = 3,         // expand (two-kernel path)
+    RECD_T_KJT = 4,            // KJT comparison lookup
+    RECD_T_HASH = 5,           // builder: hash + insert
+    RECD_T_GRAD_LISTS = 6,     // backward step A: sum of grad_out rows per unique list
+    RECD_T_GRAD_ROWS = 7,      // backward step B: row-gradient segment sum with the fused update
+    RECD_T_EMIT = 8,           // builder: inverse + copy of the unique lists
+    RECD_T_COUNT = 9
+};
+struct KernelTimer {
+    std::vector<hipEvent_t> a, b;
+    int n = 0;
+};
+
 struct recd_ctx {
     int device = 0;
     hipStream_t stream = nullptr;
@@ -45,10 +65,6 @@ struct recd_ctx {
     // no build is running on the stream, because the builder's last kernel clears what the build
     // used (so no clearing kernel stands at the head of the next build).  table_clean is false
     // while that cannot be relied on (first use, or a build that failed half way).
-    // Fused lookup + expand: per unique list the range of output rows the lookup kernel wrote
-    // (memory of its own, so that the call leaves the workspace and a pending backward plan alone).
-    int2 *cover = nullptr;
-    size_t cover_lists = 0;
     uint64_t *build_table = nullptr;
     size_t build_table_slots = 0;
     bool table_clean = false;
@@ -70,6 +86,8 @@ struct recd_ctx {
     bool build_valid = false;     // a plain / weighted build has written build_counts_dev
     // this device's copy of the static scratch array of recd_build_ikjt_noalloc (found at creation)
     char *static_scratch = nullptr;
+    int timing = 0;  // RECD_OPT_INTERNAL_TIMING
+    KernelTimer timers[RECD_T_COUNT];
     int validate = 0;
     int weak_hash = 0;
     int tune_lb = 0, tune_gens = 0, tune_flat = 0;  // launch-shape overrides of the gather-sum kernel (0 = automatic)
@@ -86,6 +104,10 @@ struct recd_ctx {
 //   value = lists per block (1, 2, 4, 8 or 16) + 10000 * block generations per CU (< 100)
 //           + 1000000 * (1 = no XCD-aware block mapping); 0 = automatic
 #define RECD_OPT_INTERNAL_TUNE_SEGSUM 1003
+// value != 0: bracket the kernels named by RECD_T_* with HIP events (see recd_internal_kernel_ms)
+#define RECD_OPT_INTERNAL_TIMING 1004
+void recd_time_begin(recd_ctx *ctx, int slot, hipStream_t st);
+void recd_time_end(recd_ctx *ctx, int slot, hipStream_t st);
 
 recd_status recd_fail(recd_ctx *ctx, recd_status s, const char *fmt, ...);
 // Ids must lie in [0, 2^31): a table the caller describes as larger is refused (rows may be null).
@@ -169,14 +191,13 @@ struct SegSumArgs {
     const float *weights;           // mode 3 (weighted sum): one fp32 weight per id, beside values
     const int64_t *div_off;         // optional (backward sums only): the finished row of list l is
                                     // divided by div_off[l+1] - div_off[l] when that is positive
-    // RECD_SITE_UNIQUE_EXPAND only: the IKJT's inverse, the first row of every unique list, the
-    // expanded output, rows per feature, the launch's first feature, the written row range per list
-    const int32_t *inverse;
-    const int32_t *first_row;
+    // RECD_SITE_UNIQUE_EXPAND only: the IKJT's run index, the expanded output, rows per feature, the
+    // launch's first feature and the call's feature count (lists_bound = host estimate of the runs)
+    const int64_t *run_index;
     void *expanded;
-    int2 *cover;
     int64_t B;
     int feat_base;
+    int F_all;
     int site;                 // RECD_SITE_*: which call site (each has its own kernel instantiation)
     int mode;                 // recd_pooling (forward sites only; 0 = sum)
     void *out;                // [lists, D]
@@ -185,8 +206,6 @@ struct SegSumArgs {
 recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a);
 recd_status recd_validate_inverse(recd_ctx *ctx, int F, int64_t B, const int64_t *feat_uoff,
                                   const int32_t *inverse);
-recd_status recd_validate_first_rows(recd_ctx *ctx, int F, int64_t B, const int64_t *feat_uoff,
-                                     const int32_t *inverse, const int32_t *first_row);
 recd_status recd_validate_kjt_offsets(recd_ctx *ctx, int F, int64_t B, int64_t N, const int64_t *offsets);
 recd_status recd_validate_kjt_lists(recd_ctx *ctx, int F, int64_t B, int64_t N, const int64_t *rows,
                                     const int64_t *values, const int64_t *offsets);

@@ -172,14 +172,14 @@ struct SegSumParams {
     const int64_t *div_off;
     // POOL_WSUM: one fp32 weight per id, aligned with values
     const float *weights;
-    // SITE_UNIQUE_EXPAND: the IKJT's inverse [F*B], the first row of every unique list, the expanded
-    // output [F*B, D], rows per feature, the launch's first feature, and per unique list the range of
-    // output rows this kernel wrote (for the pass that copies the remaining rows)
-    const int32_t *inverse;
-    const int32_t *first_row;
+    // SITE_UNIQUE_EXPAND: the IKJT's run index (header, one entry per run of adjacent rows that name
+    // the same unique list, closing entry), the expanded output [F*B, D], rows per feature, the
+    // launch's first feature, and how the runs are dealt to the eight block queues
+    const int64_t *run_index;
     void *expanded;
-    int2 *cover;
     int64_t B;
+    int64_t run_cap;         // no run number reaches this (F*B)
+    int64_t runs_per_queue;  // queue q takes the runs [q * runs_per_queue, (q+1) * runs_per_queue) first
     int feat_base;
 };
 
@@ -262,7 +262,10 @@ template <int LPR, int VPL, int TT, int OT, int SITE, int MODE> constexpr int se
 {
     if (VPL > 1)
         return 1;
-    int w = MODE == POOL_WSUM ? (SITE == SITE_KJT ? 6 : 5) : 7;
+#ifndef RECD_BASE_WAVES
+#define RECD_BASE_WAVES 7
+#endif
+    int w = MODE == POOL_WSUM ? (SITE == SITE_KJT ? 6 : 5) : RECD_BASE_WAVES;
     if (LPR == 8)
         w -= 2;
     else if (TT != RECD_F32 && SITE == SITE_UNIQUE_EXPAND)
@@ -291,7 +294,6 @@ void k_segsum(const SegSumParams p)
     __shared__ int64_t s_qpref[RECD_F_PER_LAUNCH + 1];
     __shared__ int64_t s_start[kMaxLB], s_end[kMaxLB], s_list[kMaxLB];
     __shared__ int s_feat[kMaxLB];
-    __shared__ int32_t s_first[kMaxLB];
     __shared__ float s_part[LL][kWaves][ROWF];
     constexpr bool EXPAND = SITE == SITE_UNIQUE_EXPAND;
     static_assert(!EXPAND || kWaves == 1, "a finished row is in the registers of one wave");
@@ -305,6 +307,7 @@ void k_segsum(const SegSumParams p)
     const int64_t item_stride = nq == 1 ? gridDim.x : gridDim.x / kNQ;
     const int nslots = (p.F - q + nq - 1) / nq;  // features in my queue: q, q+nq, ...
 
+    if constexpr (!EXPAND) {
     for (int f = tid; f <= p.F; f += kSegBlock)
         s_loff[f] = p.list_off ? p.list_off[f] : (int64_t)f * p.lists_per_feature;
     __syncthreads();
@@ -331,7 +334,8 @@ void k_segsum(const SegSumParams p)
             s_qpref[nslots] = all;
     }
     __syncthreads();
-    const int64_t total = p.count_dev ? *p.count_dev : s_qpref[nslots];
+    }
+    const int64_t total = EXPAND ? 0 : (p.count_dev ? *p.count_dev : s_qpref[nslots]);
 
     const int g = lane / LPR;   // lane group = which of the G rows of a load
     const int r = lane % LPR;   // 16-byte piece of the row
@@ -374,37 +378,100 @@ void k_segsum(const SegSumParams p)
             for (int w = 0; w < VPL; w++)
                 store_row_piece<OT, EPV, NT>(dst + ((int64_t)w * LPR + r) * OB, vals + w * EPV);
         }
-        if constexpr (EXPAND) {
-            // Every lane group holds the finished row (the butterfly leaves the sum in all of them).
-            // The run: the list's first row and the rows right behind it, in the same feature, that
-            // name the same slot.  The whole wave looks 64 rows ahead at a time.
-            const int f = s_feat[j];
-            const int64_t l0 = s_first[j];
-            const int64_t lend = (int64_t)(p.feat_base + f + 1) * p.B;
-            const int32_t slot = (int32_t)(s_list[j] - s_loff[f]);
-            int64_t c = 1;
-            for (;;) {
-                const int64_t l = l0 + c + lane;
-                const bool same = l < lend && p.inverse[l] == slot;
-                const uint64_t m = __ballot(same);
-                const int k = m == ~0ull ? 64 : __builtin_ctzll(~m);
-                c += k;
-                if (k < 64)
-                    break;
+    };
+
+    // One wave walks a whole list of more than 64 ids: the ids of the next chunk are fetched before
+    // the rows of this one, so their latency hides behind the row loads.
+    auto walk_long_list = [&](float (*acc)[NACC], const char *table, int64_t start, int64_t end) {
+        int64_t base = start;
+        int n = (int)(end - base < kChunk ? end - base : kChunk);
+        uint32_t cur = lane < n ? (uint32_t)values[base + lane] : 0u;
+        for (;;) {
+            const int64_t nbase = base + kChunk;
+            const bool more = nbase < end;
+            const int nn = more ? (int)(end - nbase < kChunk ? end - nbase : kChunk) : 0;
+            const uint32_t nxt = (more && lane < nn) ? (uint32_t)values[nbase + lane] : 0u;
+            add_chunks<LPR, VPL, TT, IdxT, 1, UNR, MODE, SITE == SITE_GRAD_STREAM>(acc, &table, values, &base, &n,
+                                                                                   row_bytes, lane, g, p.weights, &cur);
+            if (!more)
+                break;
+            base = nbase;
+            n = nn;
+            cur = nxt;
+        }
+    };
+
+    if constexpr (EXPAND) {
+        // Work item = a run of the batch: adjacent rows of a feature that name the same unique list
+        // (the samples of a session).  The wave of a list's first run sums the list, stores the row
+        // to pooled and to every output row of the run; the runs of a list that comes back later in
+        // the batch are left to the copy kernel that follows.  One load round trip brings the run's
+        // entry, the start of the next run and the number of runs; no other index is read.
+        // Queue q = blockIdx mod 8 (one XCD) takes a contiguous stretch of the runs, which are in
+        // (feature, row) order, so a table's hot rows stay in one L2.
+        const int64_t *ri = p.run_index;
+        const int64_t per = p.runs_per_queue;
+        const int qx = (int)(blockIdx.x % kNQ);
+        const int64_t stride = gridDim.x / kNQ;
+        for (int64_t item = blockIdx.x / kNQ;; item += stride) {
+            const int64_t rr = item < per ? (int64_t)qx * per + item : (int64_t)kNQ * per + (item - per) * kNQ + qx;
+            if (rr >= p.run_cap)
+                break;
+            int64_t word = 0;  // lanes 0..2: the entry, lane 3: first word of the next entry, lane 4: header
+            if (lane < 4)
+                word = ri[3 * (1 + rr) + lane];
+            else if (lane == 4)
+                word = ri[0];
+            const uint32_t wlo = (uint32_t)(uint64_t)word, whi = (uint32_t)((uint64_t)word >> 32);
+            auto lane64 = [&](int k) {
+                return (int64_t)(((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)whi, k) << 32) |
+                                 (uint32_t)__builtin_amdgcn_readlane((int)wlo, k));
+            };
+            if (rr >= lane64(4))
+                break;  // runs beyond the last: so are all later items of this block
+            const int64_t w0 = lane64(0);
+            const uint32_t uf = (uint32_t)((uint64_t)w0 >> 32);
+            if (!(uf >> 31))
+                continue;  // not the list's first run
+            const uint32_t row0 = (uint32_t)(uint64_t)w0;
+            const int64_t u = uf & 0x7fffffffu;
+            const int64_t start = lane64(1);
+            const int64_t len_ids = lane64(2);
+            const uint32_t run_rows = (uint32_t)(uint64_t)lane64(3) - row0;
+            const int f = (int)(row0 / (uint32_t)p.B) - p.feat_base;
+            if (f < 0 || f >= p.F)
+                continue;  // a feature of another launch
+            const char *table = static_cast<const char *>(p.tables.p[f]) + lane_off;
+            float acc[1][NACC];
+#pragma unroll
+            for (int i = 0; i < NACC; i++)
+                acc[0][i] = pool_identity<MODE>();
+            if (len_ids > kChunk) {
+                walk_long_list(acc, table, start, start + len_ids);
+            } else {
+                const int n = (int)len_ids;
+                add_chunks<LPR, VPL, TT, IdxT, 1, UNR, MODE, false>(acc, &table, values, &start, &n, row_bytes, lane,
+                                                                    g, p.weights);
             }
-            if (lane == 0)
-                p.cover[s_list[j]] = make_int2((int)l0, (int)(l0 + c));
+            fold_groups(acc[0]);  // the butterfly leaves the finished row in every lane group
             if (piece_ok) {
-                char *dst = static_cast<char *>(p.expanded) + l0 * out_row_bytes;
-                for (int64_t k = g; k < c; k += 64 / LPR) {
+                if (g == 0) {
+                    char *dst = static_cast<char *>(p.out) + u * out_row_bytes;
 #pragma unroll
                     for (int w = 0; w < VPL; w++)
-                        store_row_piece<OT, EPV, true>(dst + k * out_row_bytes + ((int64_t)w * LPR + r) * OB,
-                                                       vals + w * EPV);
+                        store_row_piece<OT, EPV, false>(dst + ((int64_t)w * LPR + r) * OB, acc[0] + w * EPV);
+                }
+                char *dst = static_cast<char *>(p.expanded) + (int64_t)row0 * out_row_bytes;
+                for (uint32_t k = g; k < run_rows; k += 64 / LPR) {
+#pragma unroll
+                    for (int w = 0; w < VPL; w++)
+                        store_row_piece<OT, EPV, true>(dst + (int64_t)k * out_row_bytes + ((int64_t)w * LPR + r) * OB,
+                                                       acc[0] + w * EPV);
                 }
             }
         }
-    };
+        return;
+    }
 
     for (int64_t item = item0; item * lb < total; item += item_stride) {
         const int64_t t0 = item * lb;
@@ -427,8 +494,6 @@ void k_segsum(const SegSumParams p)
             const int64_t start = p.offsets[l];
             s_start[tid] = start;
             s_end[tid] = p.ends ? p.ends[l] : (p.lens ? start + p.lens[l] : p.offsets[l + 1]);
-            if constexpr (EXPAND)
-                s_first[tid] = p.first_row[l];
         }
         __syncthreads();
 
@@ -446,24 +511,7 @@ void k_segsum(const SegSumParams p)
                 for (int i = 0; i < NACC; i++)
                     acc[0][i] = pool_identity<MODE>();
                 if constexpr (kWaves == 1) {
-                    // one wave walks the whole list: the ids of the next chunk are fetched before
-                    // the rows of this one, so their latency hides behind the row loads
-                    int64_t base = start;
-                    int n = (int)(end - base < kChunk ? end - base : kChunk);
-                    uint32_t cur = lane < n ? (uint32_t)values[base + lane] : 0u;
-                    for (;;) {
-                        const int64_t nbase = base + kChunk;
-                        const bool more = nbase < end;
-                        const int nn = more ? (int)(end - nbase < kChunk ? end - nbase : kChunk) : 0;
-                        const uint32_t nxt = (more && lane < nn) ? (uint32_t)values[nbase + lane] : 0u;
-                        add_chunks<LPR, VPL, TT, IdxT, 1, UNR, MODE, SITE == SITE_GRAD_STREAM>(
-                            acc, &table, values, &base, &n, row_bytes, lane, g, p.weights, &cur);
-                        if (!more)
-                            break;
-                        base = nbase;
-                        n = nn;
-                        cur = nxt;
-                    }
+                    walk_long_list(acc, table, start, end);
                 } else {
                     for (int64_t base = start + (int64_t)wv * kChunk; base < end; base += kWaves * kChunk) {
                         const int n = (int)(end - base < kChunk ? end - base : kChunk);
@@ -610,79 +658,110 @@ __global__ __launch_bounds__(kBlock) void k_expand(const u32x4 *__restrict__ poo
 }
 
 // ---- the rest of the expand after the fused lookup ---------------------------------------------
-// cover[u] = [first, end) rows the lookup kernel wrote for unique list u.  A thread checks one output
-// row; the rows outside their list's range (a list that turns up again later in the batch, not
-// next to its first run) are collected per block and copied from pooled by the whole block.
-// With session-adjacent duplicates that is a few percent of the rows; in the worst case this
-// kernel is the whole expand.
-__global__ __launch_bounds__(kBlock) void k_expand_uncovered(const u32x4 *__restrict__ pooled,
-                                                             const int64_t *__restrict__ feat_uoff,
-                                                             const int32_t *__restrict__ inverse,
-                                                             const int2 *__restrict__ cover,
-                                                             u32x4 *__restrict__ out, uint32_t B,
-                                                             uint32_t n_rows, int vecs_per_row)
+// Runs whose list was first seen earlier in the batch (the list came back after other rows): their
+// output rows are copies of pooled[u].  A block takes 64 runs: its first wave lists the runs that
+// are not first runs and numbers their rows, then the whole block copies them, a 16-byte piece per
+// thread and step.  With session-clustered batches these are a few percent of the rows.
+__global__ __launch_bounds__(kBlock) void k_expand_runs(const u32x4 *__restrict__ pooled,
+                                                        const int64_t *__restrict__ run_index,
+                                                        u32x4 *__restrict__ out, int vecs_per_row)
 {
-    __shared__ uint32_t s_row[kBlock], s_src[kBlock];
-    __shared__ uint32_t s_wcnt[kBlock / 64];
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const uint32_t row = blockIdx.x * kBlock + tid;
-    bool need = false;
-    uint32_t u = 0;
-    if (row < n_rows) {
-        u = (uint32_t)(feat_uoff[row / B] + inverse[row]);
-        const int2 cv = cover[u];
-        need = (int)row < cv.x || (int)row >= cv.y;
-    }
-    const uint64_t m = __ballot(need);
-    if (lane == 0)
-        s_wcnt[wv] = (uint32_t)__popcll(m);
-    __syncthreads();
-    uint32_t before = 0, total = 0;
-#pragma unroll
-    for (int i = 0; i < kBlock / 64; i++) {
-        before += i < wv ? s_wcnt[i] : 0;
-        total += s_wcnt[i];
-    }
-    if (total == 0)
-        return;  // whole block
-    if (need) {
-        const uint32_t k = before + (uint32_t)__popcll(m & ((1ull << lane) - 1));
-        s_row[k] = row;
-        s_src[k] = u;
-    }
-    __syncthreads();
+    __shared__ uint32_t s_row[64], s_src[64], s_off[65];
+    __shared__ uint32_t s_cnt;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int64_t n_runs = run_index[0];
     const uint32_t vecs = (uint32_t)vecs_per_row;
-    for (uint32_t idx = tid; idx < total * vecs; idx += kBlock) {
-        const uint32_t k = idx / vecs, piece = idx - k * vecs;
-        __builtin_nontemporal_store(pooled[(int64_t)s_src[k] * vecs + piece],
-                                    &out[(int64_t)s_row[k] * vecs + piece]);
+    for (int64_t r0 = (int64_t)blockIdx.x * 64; r0 < n_runs; r0 += (int64_t)gridDim.x * 64) {
+        __syncthreads();  // the previous round is done with the shared arrays
+        if (tid < 64) {
+            const int64_t rr = r0 + lane;
+            uint32_t rows = 0, row = 0, u = 0;
+            if (rr < n_runs) {
+                const uint64_t w0 = (uint64_t)run_index[3 * (1 + rr)];
+                const uint64_t w3 = (uint64_t)run_index[3 * (2 + rr)];
+                row = (uint32_t)w0;
+                u = (uint32_t)(w0 >> 32);
+                rows = (u >> 31) ? 0u : (uint32_t)w3 - row;  // first runs were written by the lookup
+                u &= 0x7fffffffu;
+            }
+            const uint64_t m = __ballot(rows != 0);
+            uint32_t inc = rows;  // inclusive prefix of the rows to copy
+#pragma unroll
+            for (int d = 1; d < 64; d <<= 1) {
+                const uint32_t x = __shfl_up(inc, d);
+                if (lane >= d)
+                    inc += x;
+            }
+            if (rows != 0) {
+                const uint32_t k = (uint32_t)__popcll(m & ((1ull << lane) - 1));
+                s_row[k] = row;
+                s_src[k] = u;
+                s_off[k] = inc - rows;
+            }
+            if (lane == 63) {
+                s_cnt = (uint32_t)__popcll(m);
+                s_off[__popcll(m)] = inc;
+            }
+        }
+        __syncthreads();
+        const uint32_t cnt = s_cnt;
+        if (cnt == 0)
+            continue;
+        const uint32_t total = s_off[cnt] * vecs;
+        for (uint32_t idx = tid; idx < total; idx += kBlock) {
+            const uint32_t k = idx / vecs, piece = idx - k * vecs;
+            uint32_t j = 0;  // the last listed run with s_off[j] <= k
+#pragma unroll
+            for (uint32_t st = 32; st >= 1; st >>= 1)
+                if (j + st < cnt && s_off[j + st] <= k)
+                    j += st;
+            __builtin_nontemporal_store(pooled[(int64_t)s_src[j] * vecs + piece],
+                                        &out[(int64_t)(s_row[j] + (k - s_off[j])) * vecs + piece]);
+        }
     }
 }
 
-// ---- first row of every unique list from the inverse index alone ---------------------------------
-// A row is a run head if it is row 0 of its feature or names another slot than the row before it;
-// the first row of a slot is the smallest of its run heads.
-__global__ __launch_bounds__(kBlock) void k_fill_i32(int32_t *p, int64_t n, int32_t v)
+// err[0] |= 64: the run index is malformed (run count, row order, list positions)
+__global__ void k_validate_runs(const int64_t *run_index, int64_t n_rows, int64_t B, int *err)
 {
-    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n; i += (int64_t)gridDim.x * kBlock)
-        p[i] = v;
+    const int64_t n_runs = run_index[0], U = run_index[1], M = run_index[2];
+    if (n_runs < 0 || n_runs > n_rows || U < 0 || U > n_rows || M < 0) {
+        if (blockIdx.x == 0 && threadIdx.x == 0)
+            atomicOr(err, 64);
+        return;
+    }
+    for (int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; r <= n_runs; r += (int64_t)gridDim.x * blockDim.x) {
+        const uint64_t w0 = (uint64_t)run_index[3 * (1 + r)];
+        const int64_t row = (uint32_t)w0, u = (uint32_t)(w0 >> 32) & 0x7fffffffu;
+        const int64_t start = run_index[3 * (1 + r) + 1], n = run_index[3 * (1 + r) + 2];
+        bool bad = false;
+        if (r == n_runs) {
+            bad = row != n_rows;
+        } else {
+            const int64_t next = (uint32_t)(uint64_t)run_index[3 * (2 + r)];
+            // a run lies in one feature, the first run starts at row 0
+            bad = row >= n_rows || next <= row || next > n_rows || (r == 0 && row != 0) ||
+                  (next - 1) / B != row / B || u >= U || start < 0 || n < 0 || start > M || n > M - start;
+        }
+        if (bad)
+            atomicOr(err, 64);
+    }
 }
 
-__global__ __launch_bounds__(kBlock) void k_first_rows(const int32_t *__restrict__ inverse,
-                                                       const int64_t *__restrict__ feat_uoff, uint32_t B,
-                                                       uint32_t n_rows, int64_t max_lists,
-                                                       int32_t *__restrict__ first_row)
+// err[0] |= 2: an id of a first run lies outside its table (rows_f of the feature of launch f0 + f)
+__global__ void k_validate_run_ids(const int64_t *run_index, const int64_t *values, int64_t B, int f,
+                                   int64_t rows_f, int *err)
 {
-    const uint32_t row = blockIdx.x * kBlock + threadIdx.x;
-    if (row >= n_rows)
-        return;
-    const uint32_t f = row / B;
-    const int32_t inv = inverse[row];
-    if (row - f * B != 0 && inverse[row - 1] == inv)
-        return;
-    const int64_t u = feat_uoff[f] + inv;
-    if (u < max_lists)
-        atomicMin(&first_row[u], (int32_t)row);
+    const int64_t n_runs = run_index[0];
+    for (int64_t r = blockIdx.x; r < n_runs; r += gridDim.x) {
+        const uint64_t w0 = (uint64_t)run_index[3 * (1 + r)];
+        if ((int64_t)((uint32_t)w0 / B) != f || !((w0 >> 63) & 1))
+            continue;
+        const int64_t start = run_index[3 * (1 + r) + 1], n = run_index[3 * (1 + r) + 2];
+        for (int64_t t = threadIdx.x; t < n; t += blockDim.x)
+            if (values[start + t] < 0 || values[start + t] >= rows_f)
+                atomicOr(err, 2);
+    }
 }
 
 // ---- a compute module on a grouped IKJT: element-wise sum over the features of a group ----------
@@ -788,42 +867,30 @@ __global__ void k_validate_inverse(const int32_t *inverse, const int64_t *feat_u
     }
 }
 
-// err[0] |= 32: the first row recorded for a unique list lies outside the list's feature or does
-// not name the list
-__global__ void k_validate_first_rows(const int32_t *inverse, const int64_t *feat_uoff, int F, int64_t B,
-                                      const int32_t *first_row, int *err)
-{
-    const int64_t U = feat_uoff[F];
-    for (int64_t u = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; u < U; u += (int64_t)gridDim.x * blockDim.x) {
-        int lo = 0, hi = F;  // feature of u
-        while (hi - lo > 1) {
-            const int mid = (lo + hi) >> 1;
-            if (feat_uoff[mid] <= u)
-                lo = mid;
-            else
-                hi = mid;
-        }
-        const int64_t l = first_row[u];
-        if (l < (int64_t)lo * B || l >= (int64_t)(lo + 1) * B || inverse[l] != (int32_t)(u - feat_uoff[lo]))
-            atomicOr(err, 32);
-    }
-}
-
 } // namespace
 
-recd_status recd_validate_first_rows(recd_ctx *ctx, int F, int64_t B, const int64_t *feat_uoff,
-                                     const int32_t *inverse, const int32_t *first_row)
+// Checks a run index before the fused lookup reads through it.  Synchronises.
+static recd_status validate_run_index(recd_ctx *ctx, int F, int64_t B, const int64_t *rows,
+                                      const int64_t *u_values, const int64_t *run_index)
 {
     RECD_TRY(recd_reserve(ctx, 512));
     int *err = reinterpret_cast<int *>(ctx->ws);
     RECD_HIP(ctx, hipMemsetAsync(err, 0, sizeof(int), ctx->stream));
-    hipLaunchKernelGGL(k_validate_first_rows, dim3(256), dim3(256), 0, ctx->stream, inverse, feat_uoff, F, B,
-                       first_row, err);
+    hipLaunchKernelGGL(k_validate_runs, dim3(256), dim3(256), 0, ctx->stream, run_index, (int64_t)F * B, B, err);
     ctx->host_pinned[0] = 0;
     RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, err, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
     RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    if ((int)ctx->host_pinned[0] & 32)
-        return recd_fail(ctx, RECD_EBOUNDS, "u_first_row does not hold a row of every unique list");
+    if ((int)ctx->host_pinned[0] & 64)
+        return recd_fail(ctx, RECD_EBOUNDS, "the run index is malformed");
+    if (rows && u_values) {
+        for (int f = 0; f < F; f++)
+            hipLaunchKernelGGL(k_validate_run_ids, dim3(64), dim3(256), 0, ctx->stream, run_index, u_values, B, f,
+                               rows[f], err);
+        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, err, sizeof(int), hipMemcpyDeviceToHost, ctx->stream));
+        RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
+        if ((int)ctx->host_pinned[0] & 2)
+            return recd_fail(ctx, RECD_EBOUNDS, "an id lies outside its embedding table");
+    }
     return RECD_OK;
 }
 
@@ -842,12 +909,12 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     p.lens = a.lens;
     p.div_off = a.div_off;
     p.weights = a.weights;
-    p.inverse = a.inverse;
-    p.first_row = a.first_row;
+    p.run_index = a.run_index;
     p.expanded = a.expanded;
-    p.cover = a.cover;
     p.B = a.B;
+    p.run_cap = (int64_t)a.F_all * a.B;
     p.feat_base = a.feat_base;
+    p.runs_per_queue = 0;
     p.F = a.F;
     p.D = a.D;
     const int epv = a.table_dt == RECD_F32 ? 4 : 8;
@@ -875,17 +942,33 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     // resident-sized grid that strides wastes no blocks
     if (a.count_dev && nblk > (int64_t)ctx->num_cu * 8)
         nblk = (int64_t)ctx->num_cu * 8;
+    if (a.site == RECD_SITE_UNIQUE_EXPAND) {
+        // one run per block; queue q of eight takes the runs [q * per, (q + 1) * per) of the host's
+        // estimate first and shares whatever lies beyond it with the other queues
+        p.lb = 1;
+        p.nq = kNQ;
+        p.runs_per_queue = (n + kNQ - 1) / kNQ;
+        nblk = kNQ * (p.runs_per_queue + p.runs_per_queue / 16 + 1);
+        if (nblk > cap)
+            nblk = cap / kNQ * kNQ;
+    }
     const int blocks = (int)nblk;
     bool ok = false;
     hipStream_t st = a.stream ? a.stream : ctx->stream;
     const int v = p.vecs_per_row;
     const bool fwd = !a.values_are_i32;
+    const int slot = a.site == RECD_SITE_UNIQUE_EXPAND ? RECD_T_LOOKUP_EXPAND
+                     : a.site == RECD_SITE_UNIQUE      ? RECD_T_LOOKUP
+                     : a.site == RECD_SITE_KJT         ? RECD_T_KJT
+                     : a.site == RECD_SITE_GRAD_STREAM ? RECD_T_GRAD_LISTS
+                                                       : -1;
+    if (slot >= 0)
+        recd_time_begin(ctx, slot, st);
     if (a.site == RECD_SITE_UNIQUE && fwd && a.mode == POOL_SUM)
         ok = launch_forward<SITE_UNIQUE>(st, blocks, v, a, p);
     else if (a.site == RECD_SITE_KJT && fwd && a.mode == POOL_SUM)
         ok = launch_forward<SITE_KJT>(st, blocks, v, a, p);
-    else if (a.site == RECD_SITE_UNIQUE_EXPAND && fwd && a.mode == POOL_SUM && a.inverse && a.first_row &&
-             a.expanded && a.cover)
+    else if (a.site == RECD_SITE_UNIQUE_EXPAND && fwd && a.mode == POOL_SUM && a.run_index && a.expanded)
         ok = launch_forward<SITE_UNIQUE_EXPAND>(st, blocks, v, a, p);
     else if (a.site == RECD_SITE_UNIQUE && fwd && a.mode == POOL_MEAN)
         ok = launch_forward<SITE_UNIQUE, POOL_MEAN>(st, blocks, v, a, p);
@@ -908,6 +991,8 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     else if (a.site == RECD_SITE_GRAD_LISTS && a.values_are_i32 && a.table_dt == RECD_F32 &&
              a.out_dt == RECD_F32 && a.mode == POOL_WSUM && a.weights)
         ok = launch_shape<RECD_F32, RECD_F32, int32_t, SITE_GRAD_LISTS, POOL_WSUM>(st, blocks, v, p);
+    if (slot >= 0)
+        recd_time_end(ctx, slot, st);
     if (!ok)
         return recd_fail(ctx, RECD_EINVAL, "unsupported row shape: D=%d table dtype %d out dtype %d",
                          a.D, (int)a.table_dt, (int)a.out_dt);
@@ -1208,6 +1293,7 @@ recd_status recd_expand_inverse(recd_ctx *ctx, int F, int64_t B, int D, recd_dty
         return recd_fail(ctx, RECD_EINVAL, "F*B too large");
     if (n_rows >= (int64_t)1 << 31)
         return recd_fail(ctx, RECD_EINVAL, "F*B must stay below 2^31");
+    recd_time_begin(ctx, RECD_T_EXPAND, ctx->stream);
     if (B >= rows_per_block)
         hipLaunchKernelGGL(k_expand<true>, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
                            static_cast<const u32x4 *>(pooled), feat_uoff, inverse,
@@ -1216,85 +1302,44 @@ recd_status recd_expand_inverse(recd_ctx *ctx, int F, int64_t B, int D, recd_dty
         hipLaunchKernelGGL(k_expand<false>, dim3((unsigned)blocks), dim3(kBlock), 0, ctx->stream,
                            static_cast<const u32x4 *>(pooled), feat_uoff, inverse,
                            static_cast<u32x4 *>(out), (uint32_t)B, (uint32_t)n_rows, vecs);
-    RECD_HIP(ctx, hipGetLastError());
-    return RECD_OK;
-}
-
-recd_status recd_ikjt_first_rows(recd_ctx *ctx, int F, int64_t B, const int32_t *inverse,
-                                 const int64_t *feat_uoff, int64_t max_lists, int32_t *u_first_row)
-{
-    if (!ctx)
-        return RECD_EINVAL;
-    if (F < 0 || F > RECD_MAX_FEATURES || B < 0 || max_lists < 0)
-        return recd_fail(ctx, RECD_EINVAL, "bad sizes F=%d B=%lld max_lists=%lld", F, (long long)B,
-                         (long long)max_lists);
-    const int64_t n_rows = (int64_t)F * B;
-    if (n_rows >= (int64_t)1 << 31)
-        return recd_fail(ctx, RECD_EINVAL, "F*B must stay below 2^31");
-    if (n_rows == 0 || max_lists == 0)
-        return RECD_OK;
-    if (!inverse || !feat_uoff || !u_first_row)
-        return recd_fail(ctx, RECD_EINVAL, "null pointer argument");
-    RECD_HIP(ctx, hipSetDevice(ctx->device));
-    if (ctx->validate)
-        RECD_TRY(recd_validate_inverse(ctx, F, B, feat_uoff, inverse));
-    if (max_lists > n_rows)
-        max_lists = n_rows;
-    const int64_t fb = (max_lists + kBlock - 1) / kBlock;
-    hipLaunchKernelGGL(k_fill_i32, dim3((unsigned)(fb < 4096 ? fb : 4096)), dim3(kBlock), 0, ctx->stream,
-                       u_first_row, max_lists, 0x7fffffff);
-    hipLaunchKernelGGL(k_first_rows, dim3((unsigned)((n_rows + kBlock - 1) / kBlock)), dim3(kBlock), 0,
-                       ctx->stream, inverse, feat_uoff, (uint32_t)B, (uint32_t)n_rows, max_lists, u_first_row);
+    recd_time_end(ctx, RECD_T_EXPAND, ctx->stream);
     RECD_HIP(ctx, hipGetLastError());
     return RECD_OK;
 }
 
 recd_status recd_pooled_lookup_expand(recd_ctx *ctx, int F, int64_t B, int D, recd_dtype table_dt,
                                       recd_dtype out_dt, const void *const *tables, const int64_t *rows,
-                                      const int64_t *u_values, const int64_t *u_offsets,
-                                      const int64_t *feat_uoff, const int32_t *inverse,
-                                      const int32_t *u_first_row, int64_t max_lists, void *pooled, void *out)
+                                      const int64_t *u_values, const int64_t *run_index, int64_t max_runs,
+                                      void *pooled, void *out)
 {
     RECD_TRY(check_lookup_shape(ctx, F, D, table_dt, out_dt));
     RECD_TRY(recd_check_rows(ctx, F, rows));
-    if (B < 0 || max_lists < 0)
-        return recd_fail(ctx, RECD_EINVAL, "B or max_lists < 0");
+    if (B < 0 || max_runs < 0)
+        return recd_fail(ctx, RECD_EINVAL, "B or max_runs < 0");
     const int64_t n_rows = (int64_t)F * B;
     if (n_rows >= (int64_t)1 << 31)
         return recd_fail(ctx, RECD_EINVAL, "F*B must stay below 2^31");
     if (n_rows == 0)
         return RECD_OK;
-    if (max_lists == 0 || max_lists > n_rows)
-        max_lists = n_rows;  // every feature of a batch with rows holds at least one list
-    if (!tables || !u_offsets || !feat_uoff || !inverse || !u_first_row || !pooled || !out)
+    if (max_runs == 0 || max_runs > n_rows)
+        max_runs = n_rows;
+    if (max_runs < F)
+        max_runs = F;  // every feature of a batch with rows starts a run
+    if (!tables || !run_index || !pooled || !out)
         return recd_fail(ctx, RECD_EINVAL, "null pointer argument");  // u_values may be null when M = 0
     for (int f = 0; f < F; f++)
         if (!tables[f])
             return recd_fail(ctx, RECD_EINVAL, "tables[%d] is null", f);
     RECD_HIP(ctx, hipSetDevice(ctx->device));
     if (ctx->validate) {
-        RECD_TRY(recd_validate_unique_lists(ctx, F, rows, u_values, u_offsets, feat_uoff, max_lists, -1));
-        RECD_TRY(recd_validate_inverse(ctx, F, B, feat_uoff, inverse));
-        RECD_TRY(recd_validate_first_rows(ctx, F, B, feat_uoff, inverse, u_first_row));
-    }
-    // the row ranges the lookup kernel writes, one per unique list: U <= F*B of them
-    if ((size_t)n_rows > ctx->cover_lists) {
-        RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
-        if (ctx->cover)
-            RECD_HIP(ctx, hipFree(ctx->cover));
-        ctx->cover = nullptr;
-        ctx->cover_lists = 0;
-        void *cp = nullptr;
-        if (hipMalloc(&cp, (size_t)n_rows * sizeof(int2)) != hipSuccess) {
-            (void)hipGetLastError();
-            return recd_fail(ctx, RECD_ENOMEM, "row ranges of %lld lists: allocation failed", (long long)n_rows);
-        }
-        ctx->cover = static_cast<int2 *>(cp);
-        ctx->cover_lists = (size_t)n_rows;
+        if (!rows)
+            return recd_fail(ctx, RECD_EINVAL, "validation needs rows[]");
+        RECD_TRY(validate_run_index(ctx, F, B, rows, u_values, run_index));
     }
     for (int f0 = 0; f0 < F; f0 += RECD_F_PER_LAUNCH) {
         SegSumArgs a{};
         a.F = F - f0 < RECD_F_PER_LAUNCH ? F - f0 : RECD_F_PER_LAUNCH;
+        a.F_all = F;
         a.D = D;
         a.table_dt = table_dt;
         a.out_dt = out_dt;
@@ -1302,24 +1347,24 @@ recd_status recd_pooled_lookup_expand(recd_ctx *ctx, int F, int64_t B, int D, re
             a.tables.p[f] = tables[f0 + f];
         a.values = u_values;
         a.values_are_i32 = 0;
-        a.offsets = u_offsets;
-        a.list_off = feat_uoff + f0;
-        a.lists_bound = max_lists;
+        a.lists_bound = max_runs;
         a.site = RECD_SITE_UNIQUE_EXPAND;
         a.mode = RECD_POOL_SUM;
         a.out = pooled;
-        a.inverse = inverse;
-        a.first_row = u_first_row;
+        a.run_index = run_index;
         a.expanded = out;
-        a.cover = ctx->cover;
         a.B = B;
         a.feat_base = f0;
         RECD_TRY(recd_launch_segsum(ctx, a));
     }
     const int vecs = (int)((size_t)D * elem_size(out_dt) / 16);
-    hipLaunchKernelGGL(k_expand_uncovered, dim3((unsigned)((n_rows + kBlock - 1) / kBlock)), dim3(kBlock), 0,
-                       ctx->stream, static_cast<const u32x4 *>(pooled), feat_uoff, inverse, ctx->cover,
-                       static_cast<u32x4 *>(out), (uint32_t)B, (uint32_t)n_rows, vecs);
+    int64_t cb = (max_runs + 63) / 64;
+    if (cb > (int64_t)ctx->num_cu * 16)
+        cb = (int64_t)ctx->num_cu * 16;
+    recd_time_begin(ctx, RECD_T_UNCOVERED, ctx->stream);
+    hipLaunchKernelGGL(k_expand_runs, dim3((unsigned)cb), dim3(kBlock), 0, ctx->stream,
+                       static_cast<const u32x4 *>(pooled), run_index, static_cast<u32x4 *>(out), vecs);
+    recd_time_end(ctx, RECD_T_UNCOVERED, ctx->stream);
     RECD_HIP(ctx, hipGetLastError());
     return RECD_OK;
 }

@@ -13,7 +13,8 @@ from typing import Optional, Sequence
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "librecd.so")
+# RECD_LIB: load this build of the library instead (comparing two builds in one session)
+LIB_PATH = os.environ.get("RECD_LIB") or os.path.join(_HERE, "librecd.so")
 
 if not os.path.exists(LIB_PATH):
     raise ImportError(
@@ -29,6 +30,10 @@ RECD_OPT_VALIDATE, RECD_OPT_WEAK_HASH, RECD_OPT_LONG_SEGMENT_CUT = 1, 2, 4
 # not in the public header: launch-shape override of the gather-sum kernel (tuning runs, and the
 # test that results do not depend on the launch shape)
 _OPT_INTERNAL_TUNE_SEGSUM = 1003
+# benchmark instrumentation (not in the public header): HIP-event brackets around single kernels
+_OPT_INTERNAL_TIMING = 1004
+KERNEL_SLOTS = {"lookup_expand": 0, "expand_uncovered": 1, "lookup_unique": 2, "expand": 3, "kjt_lookup": 4,
+                "hash_insert": 5, "grad_lists_sum": 6, "grad_rows_sum": 7, "emit": 8}
 RECD_POOL_SUM, RECD_POOL_MEAN, RECD_POOL_MAX = 0, 1, 2
 RECD_NOALLOC_MAX_LISTS = 65536
 POOLING = {"sum": RECD_POOL_SUM, "mean": RECD_POOL_MEAN, "max": RECD_POOL_MAX}
@@ -43,7 +48,7 @@ EXPORTED = [
     "recd_backward_dedup_mode", "recd_build_ikjt_weighted", "recd_pooled_lookup_unique_weighted",
     "recd_kjt_pooled_lookup_weighted", "recd_backward_dedup_weighted", "recd_backward_dedup_max",
     "recd_last_ikjt_counts", "recd_backward_plan", "recd_backward_apply", "recd_build_ikjt_noalloc",
-    "recd_build_ikjt_rows", "recd_ikjt_first_rows", "recd_pooled_lookup_expand",
+    "recd_build_ikjt_runs", "recd_ikjt_run_index", "recd_pooled_lookup_expand",
 ]
 
 _vp = C.c_void_p
@@ -57,10 +62,10 @@ _lib.recd_status_string.restype = C.c_char_p
 _lib.recd_workspace_bytes.argtypes = [C.c_int, C.c_int64, C.c_int64, C.c_int, C.POINTER(C.c_size_t)]
 _lib.recd_build_ikjt.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp, _vp, _vp, _vp]
 _lib.recd_build_ikjt_noalloc.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp, _vp, _vp]
-_lib.recd_build_ikjt_rows.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64] + [_vp] * 8
-_lib.recd_ikjt_first_rows.argtypes = [_vp, C.c_int, C.c_int64, _vp, _vp, C.c_int64, _vp]
+_lib.recd_build_ikjt_runs.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64] + [_vp] * 8
+_lib.recd_ikjt_run_index.argtypes = [_vp, C.c_int, C.c_int64, _vp, _vp, _vp, _vp]
 _lib.recd_pooled_lookup_expand.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, _vp,
-                                           _vp, _vp, _vp, C.c_int64, _vp, _vp]
+                                           C.c_int64, _vp, _vp]
 _lib.recd_pooled_lookup_unique.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, _vp,
                                            _vp, C.c_int64, _vp]
 _lib.recd_expand_inverse.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, C.c_int, _vp, _vp, _vp, _vp]
@@ -102,6 +107,9 @@ _lib.recd_pooled_lookup_partial.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_
 _lib.recd_backward_sequence_dedup.argtypes = [_vp, C.c_int, C.c_int64, C.c_int64, C.c_int, _vp, _vp, _vp, _vp, _vp,
                                               _vp, _vp, C.c_int64, C.c_int64, _vp, _vp, _vp, _vp, _vp, _vp,
                                               C.c_float, C.c_float, _vp]
+_lib.recd_internal_kernel_ms.argtypes = [_vp, C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                         C.POINTER(C.c_int)]
+_lib.recd_internal_kernel_ms.restype = C.c_int
 for _n in EXPORTED:
     if _n not in ("recd_last_error", "recd_status_string"):
         getattr(_lib, _n).restype = C.c_int
@@ -157,6 +165,14 @@ class Context:
         if st != RECD_OK:
             raise RecdError(st, _lib.recd_last_error(self._h).decode())
 
+    def kernel_ms(self, slot: str, reset: bool = True):
+        """(average ms, median ms, count) of the event-bracketed launches of one kernel since the last
+        reset (needs _OPT_INTERNAL_TIMING); synchronises the device."""
+        avg, med, n = C.c_double(0), C.c_double(0), C.c_int(0)
+        self._check(_lib.recd_internal_kernel_ms(self._h, KERNEL_SLOTS[slot], int(reset), C.byref(avg),
+                                                 C.byref(med), C.byref(n)))
+        return avg.value, med.value, n.value
+
     def set_option(self, opt: int, value: int):
         self._check(_lib.recd_set_option(self._h, opt, value))
 
@@ -175,29 +191,29 @@ class Context:
                                                  _ptr(u_values), _ptr(u_offsets), _ptr(inverse),
                                                  _ptr(feat_uoff)))
 
-    def build_ikjt_rows(self, F: int, B: int, values, offsets, u_values, u_offsets, inverse, feat_uoff,
-                        u_first_row, want_counts: bool = False):
-        """build_ikjt that also records the first row of every unique list."""
+    def build_ikjt_runs(self, F: int, B: int, values, offsets, u_values, u_offsets, inverse, feat_uoff,
+                        run_index, want_counts: bool = False):
+        """build_ikjt that also writes the batch's run index (int64 [3 * (F*B + 2)])."""
+        assert run_index.numel() >= 3 * (F * B + 2)
         host = (C.c_int64 * 2)(0, 0) if want_counts else None
-        self._check(_lib.recd_build_ikjt_rows(self._h, F, B, values.numel(), _ptr(values), _ptr(offsets),
+        self._check(_lib.recd_build_ikjt_runs(self._h, F, B, values.numel(), _ptr(values), _ptr(offsets),
                                               _ptr(u_values), _ptr(u_offsets), _ptr(inverse),
-                                              _ptr(feat_uoff), _ptr(u_first_row), host))
+                                              _ptr(feat_uoff), _ptr(run_index), host))
         return (int(host[0]), int(host[1])) if want_counts else None
 
-    def ikjt_first_rows(self, F: int, B: int, inverse, feat_uoff, u_first_row):
-        self._check(_lib.recd_ikjt_first_rows(self._h, F, B, _ptr(inverse), _ptr(feat_uoff),
-                                              u_first_row.numel(), _ptr(u_first_row)))
+    def ikjt_run_index(self, F: int, B: int, inverse, feat_uoff, u_offsets, run_index):
+        assert run_index.numel() >= 3 * (F * B + 2)
+        self._check(_lib.recd_ikjt_run_index(self._h, F, B, _ptr(inverse), _ptr(feat_uoff), _ptr(u_offsets),
+                                             _ptr(run_index)))
 
-    def pooled_lookup_expand(self, tables, B: int, u_values, u_offsets, feat_uoff, inverse, u_first_row,
-                             max_lists: int, pooled, out):
+    def pooled_lookup_expand(self, tables, B: int, u_values, run_index, max_runs: int, pooled, out):
         F = len(tables)
         D = tables[0].shape[1] if F else pooled.shape[-1]
         tdt = _DT[tables[0].dtype] if F else _DT[pooled.dtype]
         assert out.dtype == pooled.dtype
         self._check(_lib.recd_pooled_lookup_expand(
             self._h, F, B, D, tdt, _DT[pooled.dtype], self._table_array(tables), self._rows_array(tables),
-            _ptr(u_values), _ptr(u_offsets), _ptr(feat_uoff), _ptr(inverse), _ptr(u_first_row), max_lists,
-            _ptr(pooled), _ptr(out)))
+            _ptr(u_values), _ptr(run_index), max_runs, _ptr(pooled), _ptr(out)))
 
     def last_ikjt_counts(self):
         """(U, M) of the most recent build_ikjt / build_ikjt_weighted call; waits for that build only."""

@@ -1,4 +1,4 @@
-"""GPU parity of the one-pass lookup + expand (recd_build_ikjt_rows, recd_ikjt_first_rows,
+"""GPU parity of the one-pass lookup + expand (recd_build_ikjt_runs, recd_ikjt_run_index,
 recd_pooled_lookup_expand) against the CPU oracle and against the two-kernel path, through the C ABI.
 The copies are exact, so `out` and `pooled` must equal calls 2 + 3 (and the KJT lookup) bit for bit."""
 import numpy as np
@@ -29,42 +29,44 @@ def _bits(t):
     return t.view(torch.int32 if t.element_size() == 4 else torch.int16)
 
 
-def _build_rows(ctx, batch):
+def _run_cap(F, B):
+    return 3 * (F * B + 2)
+
+
+def _build_runs(ctx, batch):
     F, B = batch.F, batch.B
     values, offsets = gu.to_dev(batch.values), gu.to_dev(batch.offsets)
     if values.numel() == 0:
         values = torch.zeros(1, dtype=torch.int64, device="cuda")[:0]
     ik = gu.DeviceIKJT(F, B, batch.N)
-    first = torch.full((max(F * B, 1),), -7, dtype=torch.int32, device="cuda")
-    ik.U, ik.M = ctx.build_ikjt_rows(F, B, values, offsets, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff,
-                                     first, want_counts=True)
+    runs = torch.full((_run_cap(F, B),), -7, dtype=torch.int64, device="cuda")
+    ik.U, ik.M = ctx.build_ikjt_runs(F, B, values, offsets, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff,
+                                     runs, want_counts=True)
     uv, uo, inv, fu = orc.build_ikjt(F, B, batch.values, batch.offsets)
     assert (ik.U, ik.M) == (int(fu[-1]), len(uv))
     for a, b in zip(ik.numpy(), (uv, uo, inv, fu)):
         assert np.array_equal(a, b)
-    ref_first = orc.first_rows(F, B, inv, fu)
-    assert np.array_equal(first[:ik.U].cpu().numpy(), ref_first)
-    assert (first[ik.U:] == -7).all()
-    # the same array from the inverse index alone
-    first2 = torch.full((max(F * B, 1),), -7, dtype=torch.int32, device="cuda")
-    ctx.ikjt_first_rows(F, B, ik.inverse, ik.feat_uoff, first2)
-    assert np.array_equal(first2[:ik.U].cpu().numpy(), ref_first)
-    return values, offsets, ik, first, (uv, uo, inv, fu)
+    ref = orc.pack_run_index(*orc.run_index(F, B, inv, fu, uo), ik.U, ik.M)
+    got = runs.cpu().numpy()
+    assert np.array_equal(got[:len(ref)], ref)
+    assert (got[len(ref):] == -7).all()
+    # the same index from the IKJT's arrays alone
+    runs2 = torch.full((_run_cap(F, B),), -7, dtype=torch.int64, device="cuda")
+    ctx.ikjt_run_index(F, B, ik.inverse, ik.feat_uoff, ik.u_offsets, runs2)
+    assert np.array_equal(runs2.cpu().numpy()[:len(ref)], ref)
+    return values, offsets, ik, runs, (uv, uo, inv, fu)
 
 
-def _fused_case(ctx, w, batch, out_dtype=None, first_override=None):
+def _fused_case(ctx, w, batch, out_dtype=None, max_runs=None):
     F, B, D, dt = batch.F, batch.B, w.D, w.table_dtype
     tabs = synth.make_tables(w)
     d_tabs = gu.tables_to_dev(tabs, dt)
     odt = out_dtype or gu.TORCH_DT[dt]
-    values, offsets, ik, first, (uv, uo, inv, fu) = _build_rows(ctx, batch)
-    if first_override is not None:
-        first = first_override(ik, first)
+    values, offsets, ik, runs, (uv, uo, inv, fu) = _build_runs(ctx, batch)
     L = max(F * B, 1)
     pooled = torch.full((L, D), float("nan"), dtype=odt, device="cuda")
     out = torch.full((F, B, D), float("nan"), dtype=odt, device="cuda")
-    ctx.pooled_lookup_expand(d_tabs, B, ik.u_values, ik.u_offsets, ik.feat_uoff, ik.inverse, first, F * B,
-                             pooled, out)
+    ctx.pooled_lookup_expand(d_tabs, B, ik.u_values, runs, F * B if max_runs is None else max_runs, pooled, out)
     pooled2 = torch.full((L, D), float("nan"), dtype=odt, device="cuda")
     out2 = torch.full((F, B, D), float("nan"), dtype=odt, device="cuda")
     kjt = torch.full((F, B, D), float("nan"), dtype=odt, device="cuda")
@@ -135,21 +137,12 @@ def test_fused_without_adjacency(ctx):
     _fused_case(ctx, w, batch)
 
 
-def test_fused_accepts_any_row_of_a_list_as_its_first(ctx):
-    """u_first_row may name any row that holds the list (here: the last one); the output is the same,
-    only more of it is copied by the second pass."""
+@pytest.mark.parametrize("est", [0, 1, 7, 300, 5000, 10 ** 9])
+def test_fused_any_estimate_of_the_run_count(ctx, est):
+    """max_runs only sizes the launch and deals the runs to the block queues: far too small, exact
+    or far too large, the outputs are the same bits."""
     w = synth.scaled(synth.WORKLOADS["cfg2"], F=4, B=1024, rows=20_000, D=64)
-    batch = synth.make_batch(w, 2)
-
-    def last_rows(ik, first):
-        inv = ik.inverse.cpu().numpy().astype(np.int64)
-        fu = ik.feat_uoff.cpu().numpy()
-        u = inv + np.repeat(fu[:-1], batch.B)
-        last = np.zeros(ik.U, dtype=np.int32)
-        last[u] = np.arange(batch.F * batch.B, dtype=np.int32)   # later rows overwrite earlier ones
-        return gu.to_dev(last)
-
-    _fused_case(ctx, w, batch, first_override=last_rows)
+    _fused_case(ctx, w, synth.make_batch(w, 2), max_runs=est)
 
 
 def test_fused_edge_sizes(ctx):
@@ -162,11 +155,19 @@ def test_fused_edge_sizes(ctx):
     zi = torch.zeros(4, dtype=torch.int32, device="cuda")
     tab = [torch.zeros(5, 8, device="cuda")]
     o = torch.zeros(1, 0, 8, device="cuda")
-    ctx.pooled_lookup_expand(tab, 0, z, z, z, zi, zi, 0, torch.zeros(1, 8, device="cuda"), o)
+    ctx.pooled_lookup_expand(tab, 0, z, torch.zeros(6, dtype=torch.int64, device="cuda"), 0,
+                             torch.zeros(1, 8, device="cuda"), o)
+    # the run index of an empty batch: header and closing entry, all zero
+    runs = torch.full((6,), -7, dtype=torch.int64, device="cuda")
+    ctx.build_ikjt_runs(1, 0, z[:0], z[:1], z, z, zi, z[:2], runs)
+    assert runs.cpu().tolist() == [0] * 6
+    runs.fill_(-7)
+    ctx.ikjt_run_index(1, 0, zi, z[:2], z[:1], runs)
+    assert runs.cpu().tolist() == [0] * 6
 
 
 def test_fused_on_a_grouped_ikjt(ctx):
-    """First rows from the inverse alone serve the IKJT of another builder."""
+    """The run index from the IKJT's arrays alone serves the IKJT of another builder."""
     w = synth.scaled(synth.WORKLOADS["cfg5"], F=6, B=1024, rows=20_000, D=64)
     batch = synth.make_batch(w, 0)
     F, B, D = w.F, w.B, w.D
@@ -176,13 +177,13 @@ def test_fused_on_a_grouped_ikjt(ctx):
     g_uoff = torch.zeros(3, dtype=torch.int64, device="cuda")
     cnt = ctx.build_ikjt_grouped(F, B, [0, 3, 6], values, offsets, ik.u_values, ik.u_offsets, inv_g, g_uoff,
                                  ik.feat_uoff, ik.inverse, want_counts=True)
-    first = torch.zeros(F * B, dtype=torch.int32, device="cuda")
-    ctx.ikjt_first_rows(F, B, ik.inverse, ik.feat_uoff, first)
+    runs = torch.zeros(_run_cap(F, B), dtype=torch.int64, device="cuda")
+    ctx.ikjt_run_index(F, B, ik.inverse, ik.feat_uoff, ik.u_offsets, runs)
     d_tabs = gu.tables_to_dev(synth.make_tables(w), "f32")
     pooled = torch.zeros(F * B, D, device="cuda")
     out = torch.zeros(F, B, D, device="cuda")
     kjt = torch.zeros(F, B, D, device="cuda")
-    ctx.pooled_lookup_expand(d_tabs, B, ik.u_values, ik.u_offsets, ik.feat_uoff, ik.inverse, first, cnt[0], pooled, out)
+    ctx.pooled_lookup_expand(d_tabs, B, ik.u_values, runs, cnt[0], pooled, out)
     ctx.kjt_pooled_lookup(d_tabs, B, values, offsets, kjt)
     assert torch.equal(out, kjt)
 
@@ -190,24 +191,26 @@ def test_fused_on_a_grouped_ikjt(ctx):
 def test_fused_validation_and_argument_errors(ctx, recd):
     batch = synth.batch_from_lists([[[1], [2], [1]]])
     w = synth.scaled(synth.WORKLOADS["cfg1"], F=1, B=3, rows=10, D=8)
-    values, offsets, ik, first, _ = _build_rows(ctx, batch)
+    values, offsets, ik, runs, _ = _build_runs(ctx, batch)
     tab = gu.tables_to_dev(synth.make_tables(w), "f32")
     pooled = torch.zeros(3, 8, device="cuda")
     out = torch.zeros(1, 3, 8, device="cuda")
     with pytest.raises(recd.RecdError) as e:
-        ctx.pooled_lookup_expand(tab, 3, ik.u_values, ik.u_offsets, ik.feat_uoff, ik.inverse, None, 3, pooled, out)
+        ctx.pooled_lookup_expand(tab, 3, ik.u_values, None, 3, pooled, out)
     assert e.value.status == recd.RECD_EINVAL
     ctx.set_option(recd.RECD_OPT_VALIDATE, 1)
     try:
-        ctx.pooled_lookup_expand(tab, 3, ik.u_values, ik.u_offsets, ik.feat_uoff, ik.inverse, first, 3, pooled, out)
-        bad = first.clone()
-        bad[1] = 0   # row 0 holds slot 0, not slot 1
+        ctx.pooled_lookup_expand(tab, 3, ik.u_values, runs, 3, pooled, out)
+        for at, val in ((0, 4), (3, 1), (4, 3), (5, 4), (6, 2 - 2 ** 63)):   # count, first row, ids at, ids, row order
+            bad = runs.clone()
+            bad[at] = val
+            with pytest.raises(recd.RecdError) as e:
+                ctx.pooled_lookup_expand(tab, 3, ik.u_values, bad, 3, pooled, out)
+            assert e.value.status == recd.RECD_EBOUNDS, (at, val)
+        uv = ik.u_values.clone()
+        uv[0] = 10   # an id outside the table
         with pytest.raises(recd.RecdError) as e:
-            ctx.pooled_lookup_expand(tab, 3, ik.u_values, ik.u_offsets, ik.feat_uoff, ik.inverse, bad, 3, pooled, out)
-        assert e.value.status == recd.RECD_EBOUNDS
-        bad[1] = 2 ** 31 - 1
-        with pytest.raises(recd.RecdError) as e:
-            ctx.pooled_lookup_expand(tab, 3, ik.u_values, ik.u_offsets, ik.feat_uoff, ik.inverse, bad, 3, pooled, out)
+            ctx.pooled_lookup_expand(tab, 3, uv, runs, 3, pooled, out)
         assert e.value.status == recd.RECD_EBOUNDS
     finally:
         ctx.set_option(recd.RECD_OPT_VALIDATE, 0)
@@ -221,17 +224,17 @@ def test_fused_leaves_a_pending_plan_alone(ctx, recd):
     batch = synth.make_batch(w, 0)
     gout = gu.to_dev(synth.make_grad_out(w, 0))
     d_tabs = gu.tables_to_dev(synth.make_tables(w), "f32")
-    values, offsets, ik, first, _ = _build_rows(ctx, batch)
+    values, offsets, ik, runs, _ = _build_runs(ctx, batch)
     U, M = ik.U, ik.M
     touched = torch.zeros(M, dtype=torch.int64, device="cuda")
     feat_roff = torch.zeros(F + 1, dtype=torch.int64, device="cuda")
     grad_rows = torch.zeros(M, D, device="cuda")
     pooled = torch.zeros(F * B, D, device="cuda")
     out = torch.zeros(F, B, D, device="cuda")
-    ctx.build_ikjt_rows(F, B, values, offsets, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff, first)
+    ctx.build_ikjt_runs(F, B, values, offsets, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff, runs)
     ctx.backward_plan(F, B, D, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F, U, M, touched,
                       feat_roff)
-    ctx.pooled_lookup_expand(d_tabs, B, ik.u_values, ik.u_offsets, ik.feat_uoff, ik.inverse, first, U, pooled, out)
+    ctx.pooled_lookup_expand(d_tabs, B, ik.u_values, runs, U, pooled, out)
     R = ctx.backward_apply(gout, grad_rows, want_count=True)
     c2 = recd.Context(0)
     t2, f2, g2 = torch.zeros_like(touched), torch.zeros_like(feat_roff), torch.zeros_like(grad_rows)

@@ -72,6 +72,11 @@ MUTANTS = [
      "if (best < 0 || tables[f][values[j] * D + d] < tables[f][values[best] * D + d])", 0),
     ("first_rows_keeps_last", "if (first_row[feat_uoff[f] + k] < 0)\n", "if (1)\n", 0),
     ("first_rows_local_row", "first_row[feat_uoff[f] + k] = (int64_t)f * B + b;", "first_row[feat_uoff[f] + k] = b;", 0),
+    ("run_crosses_feature", "if (b > 0 && inverse[l - 1] == k)\n                continue; /* the row continues",
+     "if (l > 0 && inverse[l - 1] == k)\n                continue; /* the row continues", 0),
+    ("run_first_flag_always", "run_first[R] = !seen;", "run_first[R] = 1;", 0),
+    ("run_list_local", "const int64_t u = feat_uoff[f] + k;\n            run_row[R] = l;",
+     "const int64_t u = k;\n            run_row[R] = l;", 0),
     ("touched_rows_unsorted", "qsort(tmp, n, sizeof(int64_t), cmp_i64);\n    int64_t r = 0;",
      "int64_t r = 0;", 0),
 ]

@@ -261,6 +261,65 @@ def test_lookup_special_cases():
     assert out[0, 0, 0] == 1.0 + 2.0 ** -29
 
 
+def test_run_index_paper_example_and_brute_force(golden_dir):
+    """Runs of adjacent rows that hold one list.  The paper's feature b (rows 0 and 2 hold the same
+    list, row 1 another) has three runs, the last one not a first run; features c and d (rows 0 and 1
+    alike) have two runs each.  In general: numpy's run-length encoding of the slot sequence per
+    feature, unique(return_index) for the first-occurrence flag."""
+    g = _golden(golden_dir, "paper_ikjt_feature_b.json")
+    kjt = synth.batch_from_lists([g["rows"]])
+    uv, uo, inv, fu = orc.build_ikjt(1, 3, kjt.values, kjt.offsets)
+    row, lst, first, start, ids = orc.run_index(1, 3, inv, fu, uo)
+    assert row.tolist() == [0, 1, 2, 3] and lst.tolist() == [0, 1, 0] and first.tolist() == [1, 1, 0]
+    assert start.tolist() == [0, 3, 0] and ids.tolist() == [3, 3, 3]
+    g = _golden(golden_dir, "paper_ikjt_features_cd.json")
+    split = g["row2_splits"][0]
+    kjt = synth.batch_from_lists([[g["c_rows01"], g["c_rows01"], split["c"]],
+                                  [g["d_rows01"], g["d_rows01"], split["d"]]])
+    uv, uo, inv, fu = orc.build_ikjt(2, 3, kjt.values, kjt.offsets)
+    row, lst, first, start, ids = orc.run_index(2, 3, inv, fu, uo)
+    assert row.tolist() == [0, 2, 3, 5, 6] and first.tolist() == [1, 1, 1, 1]
+    assert lst.tolist() == [0, 1, int(fu[1]), int(fu[1]) + 1]
+
+    rng = np.random.default_rng(21)
+    F, B = 3, 120
+    U = [7, 1, 30]
+    fu = np.concatenate([[0], np.cumsum(U)])
+    lens = rng.integers(0, 6, size=int(fu[-1]))
+    uo = np.concatenate([[0], np.cumsum(lens)])
+    cols = []
+    for u in U:   # slots repeated in blocks of random length, coming back later
+        seq = np.repeat(rng.integers(0, u, size=B), rng.integers(1, 5, size=B))[:B]
+        seq[:0] = 0
+        cols.append(seq)
+    inv = np.concatenate(cols).astype(np.int32)
+    row, lst, first, start, ids = orc.run_index(F, B, inv, fu, uo)
+    exp_row, exp_lst, exp_first = [], [], []
+    for f in range(F):
+        s = inv[f * B:(f + 1) * B]
+        heads = np.flatnonzero(np.concatenate([[True], s[1:] != s[:-1]]))
+        slots, idx = np.unique(s, return_index=True)
+        first_at = dict(zip(slots.tolist(), idx.tolist()))
+        exp_row += (heads + f * B).tolist()
+        exp_lst += (s[heads] + fu[f]).tolist()
+        exp_first += [int(first_at[int(s[h])] == h) for h in heads]
+    assert row.tolist() == exp_row + [F * B]
+    assert lst.tolist() == exp_lst and first.tolist() == exp_first
+    assert np.array_equal(start, uo[lst]) and np.array_equal(ids, uo[lst + 1] - uo[lst])
+    # the runs tile the batch and give back the inverse index
+    back = np.repeat(lst - fu[row[:-1] // B], np.diff(row))
+    assert np.array_equal(back, inv)
+    # packing: header, one triple per run, closing entry
+    packed = orc.pack_run_index(row, lst, first, start, ids, int(fu[-1]), int(uo[-1])).view(np.uint64)
+    assert packed[:3].tolist() == [len(lst), int(fu[-1]), int(uo[-1])]
+    assert packed[-3:].tolist() == [F * B, int(uo[-1]), 0]
+    r = 5
+    assert int(packed[3 + 3 * r]) == int(row[r]) | ((int(lst[r]) | (int(first[r]) << 31)) << 32)
+    assert int(packed[4 + 3 * r]) == int(start[r]) and int(packed[5 + 3 * r]) == int(ids[r])
+    with pytest.raises(orc.OracleError):
+        orc.run_index(1, 2, np.array([0, 2], np.int32), np.array([0, 2]), np.array([0, 1, 2]))
+
+
 def test_first_rows_paper_example_and_unique_index(golden_dir):
     """Where each unique list first occurs: the paper's feature b (rows 0 and 2 share slot 0, row 1
     holds slot 1) gives rows [0, 1]; in general it is numpy's unique(return_index) per feature."""
