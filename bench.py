@@ -63,6 +63,10 @@ def parse_args():
     ap.add_argument("--partial", type=float, default=0.0,
                     help="also time the partial IKJT path on the workload with this probability of a "
                          "sample's lists shifting by one id within a session (0 = skip)")
+    ap.add_argument("--plan-all-rows", dest="run_plan", action="store_false",
+                    help="the backward's plan sorts all F*B rows by unique list (recd_build_ikjt + "
+                         "recd_backward_plan) instead of the batch's runs (recd_build_ikjt_runs + "
+                         "recd_backward_plan_runs)")
     ap.add_argument("--one-call-backward", dest="planned", action="store_false",
                     help="run the backward as one call after the expand instead of plan (next to the forward "
                          "calls) + apply")
@@ -128,6 +132,9 @@ class DeviceProblem:
         self.out = torch.zeros(F, B, D, dtype=self.tdt, device="cuda")
         self.kjt_out = torch.zeros(F, B, D, dtype=self.tdt, device="cuda")
         self.need_backward = need_backward
+        self.planned = True
+        self.fused_forward = False
+        self.run_plan = True
         ws = recd.workspace_bytes(F, B, Nmax, D)
         self.ctx = recd.Context(0, workspace_hint_bytes=ws)
         if tune:
@@ -146,13 +153,13 @@ class DeviceProblem:
             self.state = [torch.zeros(w.rows, dtype=torch.float32, device="cuda") for _ in range(F)]
         self.rows = [w.rows] * F
         self.u_hint = F * B
-        self.planned = True
-        self.fused_forward = False
 
     # --- the calls of one step; each returns nothing and enqueues on torch's current stream ----
     def build(self, i, counts=True, runs=None):
         w = self.w
-        if not (self.fused_forward if runs is None else runs):
+        if runs is None:
+            runs = self.fused_forward or (self.run_plan and self.planned and self.need_backward)
+        if not runs:
             return self.ctx.build_ikjt(w.F, w.B, self.values[i], self.offsets[i], self.u_values[i],
                                        self.u_offsets[i], self.inverse[i], self.feat_uoff[i], want_counts=counts)
         return self.ctx.build_ikjt_runs(w.F, w.B, self.values[i], self.offsets[i], self.u_values[i],
@@ -206,8 +213,13 @@ class DeviceProblem:
                 # the backward's grouping half depends on the IKJT only: it runs on the context's side
                 # streams from the end of the build on, next to lookup and expand; the sums follow
                 w = self.w
-                self.ctx.backward_plan(w.F, w.B, w.D, self.inverse[i], self.feat_uoff[i], self.u_values[i],
-                                       self.u_offsets[i], self.rows, U, M, self.touched, self.feat_roff)
+                if self.run_plan:
+                    self.ctx.backward_plan_runs(w.F, w.B, w.D, self.inverse[i], self.feat_uoff[i], self.u_values[i],
+                                                self.u_offsets[i], self.rows, U, M, self.runs[i],
+                                                self.ctx.last_ikjt_run_count(), self.touched, self.feat_roff)
+                else:
+                    self.ctx.backward_plan(w.F, w.B, w.D, self.inverse[i], self.feat_uoff[i], self.u_values[i],
+                                           self.u_offsets[i], self.rows, U, M, self.touched, self.feat_roff)
                 self.ctx.backward_apply(self.grad_out, self.grad_rows, tables=self.tables,
                                         adagrad_state=self.state, lr=0.01, eps=1e-8)
             else:
@@ -366,6 +378,7 @@ def run_workload(torch, recd, synth, w, args, need_backward, detail=True, pipeli
     P = DeviceProblem(torch, recd, synth, w, args.batches, need_backward, getattr(args, "store_grad", False), getattr(args, "tune", 0))
     P.planned = getattr(args, "planned", True)
     P.fused_forward = getattr(args, "fused", False)
+    P.run_plan = getattr(args, "run_plan", True)
     nb = len(P.batches)
     F, B, D = w.F, w.B, w.D
     e = 4 if w.table_dtype == "f32" else 2
@@ -965,8 +978,9 @@ def main():
     # the kernel that takes the most time in the timed steps, by the library's own event pairs
     live = res["kernels_in_timed_steps"]
     dom = max(live, key=lambda k: live[k]["avg_ms"])
-    forward = ("build_ikjt_runs + pooled_lookup_expand (one pass)" if args.fused
-               else "build_ikjt + pooled_lookup_unique + expand_inverse")
+    with_runs = args.fused or (args.run_plan and args.planned and need_backward)
+    forward = ("build_ikjt_runs" if with_runs else "build_ikjt") + (
+        " + pooled_lookup_expand (one pass)" if args.fused else " + pooled_lookup_unique + expand_inverse")
     line = {
         "metric": "deduped pooled lookups/sec",
         "value": value,
@@ -982,8 +996,9 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B}, F={w.F}, mean session {w.S}, rows={w.rows}, D={w.D}, "
                                f"{w.table_dtype} tables; step = {forward}"
-                               + ((" + backward_plan / backward_apply" if getattr(args, "planned", True)
-                                   else " + backward_dedup") + " with fused row-wise Adagrad"
+                               + (((" + backward_plan_runs / backward_apply" if args.run_plan else " + backward_plan / backward_apply")
+                                    if getattr(args, "planned", True)
+                                    else " + backward_dedup") + " with fused row-wise Adagrad"
                                   + ("" if args.store_grad else " (gradient rows consumed in registers, not stored)")
                                   if need_backward else " (forward only)"),
                    "batches_rotated": len(P.batches)},

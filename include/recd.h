@@ -19,6 +19,7 @@
  *   16-19. per-id weights: builder, unique and KJT lookups, backward
  *   20. backward of the max-pooled lookup   21, 22. the backward in two halves (plan / apply)
  *   23, 24. run index of a batch (adjacent rows holding one list)   25. lookup and expand in one pass
+ *   26. the backward's plan from the run index
  *
  * General rules
  *   - Every array argument marked "device" is a pointer into GPU memory owned by the caller and
@@ -422,6 +423,10 @@ recd_status recd_backward_dedup_weighted(recd_ctx *ctx, int F, int64_t B, int D,
  *    max_lists sizes the launch, see call 2) behind the build and read U and M, which the backward's
  *    bounds want, while they run.  Blocks the calling thread; RECD_EINVAL before the first build. */
 recd_status recd_last_ikjt_counts(recd_ctx *ctx, int64_t *host_U_M);
+/* The number of runs (maximal blocks of adjacent rows of a feature that hold one list; call 23) of
+ *    the same build: host_runs[0] = R.  Counted by every call 1 / 16 / 23, whether or not it stores a
+ *    run index.  Same waiting rule as recd_last_ikjt_counts. */
+recd_status recd_last_ikjt_run_count(recd_ctx *ctx, int64_t *host_runs);
 
 /* 21, 22. Call 5 in two halves.  What the backward does before it touches a gradient (keys, the two
  *    stable sorts, the numbering of the segments, touched_rows and feat_roff) depends on the IKJT
@@ -441,6 +446,18 @@ recd_status recd_backward_plan(recd_ctx *ctx, int F, int64_t B, int D, const int
                                const int64_t *feat_uoff, const int64_t *u_values,
                                const int64_t *u_offsets, const int64_t *rows, int64_t U_cap,
                                int64_t M_cap, int64_t *touched_rows, int64_t *feat_roff);
+/* 26. Call 21 for a batch with a run index (call 23 / 24): the first grouping (rows by unique list)
+ *    sorts the runs, of which a session-clustered batch has about as many as unique lists, instead
+ *    of all F*B rows, and writes the sorted runs out as the row list the full sort would have given:
+ *    the plan is the same plan, recd_backward_apply and its results are unchanged bit for bit.
+ *    run_index: device, must describe `inverse`.  runs_cap: host upper bound of the number of runs
+ *    (recd_last_ikjt_run_count gives the exact value; F*B always bounds it; 0 = F*B); if it is too
+ *    small, recd_backward_apply with host_R reports RECD_ECAPACITY.  All else as in call 21. */
+recd_status recd_backward_plan_runs(recd_ctx *ctx, int F, int64_t B, int D, const int32_t *inverse,
+                                    const int64_t *feat_uoff, const int64_t *u_values,
+                                    const int64_t *u_offsets, const int64_t *rows, int64_t U_cap,
+                                    int64_t M_cap, const int64_t *run_index, int64_t runs_cap,
+                                    int64_t *touched_rows, int64_t *feat_roff);
 recd_status recd_backward_apply(recd_ctx *ctx, recd_pooling mode, const float *grad_out,
                                 float *grad_rows, void *const *tables, float *const *adagrad_state,
                                 float lr, float eps, int64_t *host_R);

@@ -248,8 +248,10 @@ __global__ void k_keys_rows(const int32_t *__restrict__ inverse, const int64_t *
                             uint32_t *__restrict__ pay, int64_t *n_out)
 {
     const int64_t l = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (l == 0)
-        *n_out = n_lists;
+    if (l == 0) {
+        n_out[0] = n_lists;
+        n_out[1] = 0;
+    }
     if (l < n_lists) {
         keys[l] = (uint32_t)(feat_uoff[l / B] + inverse[l]);
         pay[l] = (uint32_t)l;
@@ -324,6 +326,104 @@ __global__ __launch_bounds__(256) void k_weight_payload(uint32_t *__restrict__ p
         const uint32_t j = pay[i];
         pay_w[i] = u_weights[j];
         pay[i] = pos_list[j];
+    }
+}
+
+// ---------------------------------------------------------------- step A from the batch's runs
+// With session-clustered batches the rows that name one unique list come in runs of adjacent rows
+// (the run index of the builder).  Grouping the rows by unique list then only needs the runs: keys =
+// unique list of every run, payload = run number, the same stable sort (runs of a list stay in row
+// order), and an expansion of the sorted runs into the row list that the sort of all F*B rows would
+// have produced - the same rows in the same order, so the segment sums that follow are unchanged.
+__global__ __launch_bounds__(256) void k_run_keys(const int64_t *__restrict__ run_index, int64_t runs_cap,
+                                                  uint32_t *__restrict__ keys, uint32_t *__restrict__ pay,
+                                                  int64_t *n_out)
+{
+    const int64_t all = run_index[0];
+    const int64_t n = all < runs_cap ? all : runs_cap;
+    const int64_t r = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (r == 0) {
+        n_out[0] = n;
+        n_out[1] = all > runs_cap ? 1 : 0;  // the caller's bound on the runs was too small
+    }
+    if (r < n) {
+        keys[r] = (uint32_t)((uint64_t)run_index[3 * (1 + r)] >> 32) & 0x7fffffffu;
+        pay[r] = (uint32_t)r;
+    }
+}
+
+// Sorted runs (ks = unique list, ps = run number).  EMIT = false: per tile, the number of lists that
+// start in it and the rows of its runs.  EMIT = true, with both tile arrays scanned: seg_start of
+// every list (in rows), list_off = {0, lists}, and the rows of every run written out in order.
+template <bool EMIT>
+__global__ __launch_bounds__(256) void k_run_rows(const uint32_t *__restrict__ ks, const uint32_t *__restrict__ ps,
+                                                  const int64_t *__restrict__ run_index,
+                                                  const int64_t *__restrict__ n_dev,
+                                                  uint32_t *__restrict__ tile_heads,
+                                                  uint32_t *__restrict__ tile_rows,
+                                                  int64_t *__restrict__ seg_start,
+                                                  int64_t *__restrict__ list_off, uint32_t *__restrict__ rows_out,
+                                                  int64_t *long_count)
+{
+    const int64_t n = *n_dev;
+    if (EMIT && blockIdx.x == 0 && threadIdx.x == 0) {
+        long_count[0] = 0;
+        long_count[1] = 0;
+        if (n == 0) {
+            seg_start[0] = 0;
+            list_off[0] = 0;
+            list_off[1] = 0;
+        }
+    }
+    const int64_t base = (int64_t)blockIdx.x * kScanTile + (int64_t)threadIdx.x * kScanItems;
+    uint32_t prev = (base > 0 && base <= n) ? ks[base - 1] : 0u;
+    uint32_t head[kScanItems], row0[kScanItems], len[kScanItems];
+    uint32_t hs = 0, rs = 0;
+#pragma unroll
+    for (int k = 0; k < kScanItems; k++) {
+        const int64_t i = base + k;
+        head[k] = 0;
+        row0[k] = 0;
+        len[k] = 0;
+        if (i < n) {
+            const uint32_t key = ks[i];
+            const int64_t r = ps[i];
+            head[k] = (i == 0 || key != prev) ? 1u : 0u;
+            row0[k] = (uint32_t)(uint64_t)run_index[3 * (1 + r)];
+            len[k] = (uint32_t)(uint64_t)run_index[3 * (2 + r)] - row0[k];
+            prev = key;
+        }
+        hs += head[k];
+        rs += len[k];
+    }
+    uint32_t th, tr;
+    const uint32_t eh = block_excl_scan_u32(hs, th);
+    const uint32_t er = block_excl_scan_u32(rs, tr);
+    if (!EMIT) {
+        if (threadIdx.x == 0) {
+            tile_heads[blockIdx.x] = th;
+            tile_rows[blockIdx.x] = tr;
+        }
+        return;
+    }
+    int64_t h = (int64_t)tile_heads[blockIdx.x] + eh;  // lists that start before this thread's runs
+    int64_t at = (int64_t)tile_rows[blockIdx.x] + er;  // rows before them
+#pragma unroll
+    for (int k = 0; k < kScanItems; k++) {
+        const int64_t i = base + k;
+        if (i < n) {
+            if (head[k])
+                seg_start[h] = at;
+            for (uint32_t t = 0; t < len[k]; t++)
+                rows_out[at + t] = row0[k] + t;
+            h += head[k];
+            at += len[k];
+            if (i == n - 1) {
+                seg_start[h] = at;
+                list_off[0] = 0;
+                list_off[1] = h;
+            }
+        }
     }
 }
 
@@ -1491,14 +1591,18 @@ static recd_status backward_common(recd_ctx *ctx, bool seq, bool mean, int F, in
 // plan is a chain of short latency-bound kernels); recd_backward_apply then waits for the plan on the
 // main stream and runs the two segment sums with the fused update.  Same kernels, same inputs, same
 // results as the one-call form.
-extern "C" recd_status recd_backward_plan(recd_ctx *ctx, int F, int64_t B, int D, const int32_t *inverse,
-                                          const int64_t *feat_uoff, const int64_t *u_values,
-                                          const int64_t *u_offsets, const int64_t *rows, int64_t U_cap,
-                                          int64_t M_cap, int64_t *touched_rows, int64_t *feat_roff)
+// run_index: null, or the batch's run index (then step A's grouping sorts the runs, at most
+// runs_cap of them, instead of all F*B rows)
+static recd_status plan_common(recd_ctx *ctx, int F, int64_t B, int D, const int32_t *inverse,
+                               const int64_t *feat_uoff, const int64_t *u_values, const int64_t *u_offsets,
+                               const int64_t *rows, int64_t U_cap, int64_t M_cap, const int64_t *run_index,
+                               int64_t runs_cap, int64_t *touched_rows, int64_t *feat_roff)
 {
     if (!ctx)
         return RECD_EINVAL;
     ctx->plan.valid = false;
+    if (run_index && runs_cap < 0)
+        return recd_fail(ctx, RECD_EINVAL, "runs_cap < 0");
     if (F < 0 || F > RECD_MAX_FEATURES || B < 0 || M_cap < 0 || U_cap < 0)
         return recd_fail(ctx, RECD_EINVAL, "bad sizes");
     if (U_cap > (int64_t)F * B)
@@ -1556,8 +1660,29 @@ extern "C" recd_status recd_backward_plan(recd_ctx *ctx, int F, int64_t B, int D
         const int bits_a = bits_for((uint64_t)(U_cap > 1 ? U_cap - 1 : 1));
         pl.row_bits = row_bits;
         pl.wide = bits_b > 32;
+        auto chain_a = [&]() -> recd_status {
         // step A's grouping on the second side stream
-        {
+        if (run_index) {
+            // the runs sorted by unique list, then written out as the rows they stand for
+            if (runs_cap > n_lists || runs_cap == 0)
+                runs_cap = n_lists;
+            uint32_t *k0 = static_cast<uint32_t *>(w.a.k0), *k1 = static_cast<uint32_t *>(w.a.k1), *ks, *ps;
+            hipLaunchKernelGGL(k_run_keys, dim3((unsigned)((runs_cap + 255) / 256)), dim3(256), 0, sa, run_index,
+                               runs_cap, k0, w.a.p0, w.a.n_dev);
+            RECD_TRY(radix_sort_pairs<uint32_t>(ctx, sa, k0, w.a.p0, k1, w.a.p1, w.a.n_dev, runs_cap, bits_a,
+                                                w.a.hist, w.a.bsum, &ks, &ps));
+            const unsigned tiles = (unsigned)((runs_cap + kScanTile - 1) / kScanTile);
+            uint32_t *rows_out = ps == w.a.p0 ? w.a.p1 : w.a.p0;
+            hipLaunchKernelGGL((k_run_rows<false>), dim3(tiles), dim3(256), 0, sa, ks, ps, run_index, w.a.n_dev,
+                               w.a.bsum, w.a.hist, w.seg_start, w.list_off, rows_out, w.long_count_a);
+            hipLaunchKernelGGL(k_scan_small, dim3(1), dim3(1024), 0, sa, w.a.bsum, (int64_t)tiles);
+            hipLaunchKernelGGL(k_scan_small, dim3(1), dim3(1024), 0, sa, w.a.hist, (int64_t)tiles);
+            hipLaunchKernelGGL((k_run_rows<true>), dim3(tiles), dim3(256), 0, sa, ks, ps, run_index, w.a.n_dev,
+                               w.a.bsum, w.a.hist, w.seg_start, w.list_off, rows_out, w.long_count_a);
+            RECD_HIP(ctx, hipGetLastError());
+            pl.ks_a = ks;
+            pl.ps_a = rows_out;
+        } else {
             uint32_t *k0 = static_cast<uint32_t *>(w.a.k0), *k1 = static_cast<uint32_t *>(w.a.k1), *ks, *ps;
             hipLaunchKernelGGL(k_keys_rows, dim3((unsigned)((n_lists + 255) / 256)),
                                dim3(256), 0, sa, inverse,
@@ -1568,6 +1693,9 @@ extern "C" recd_status recd_backward_plan(recd_ctx *ctx, int F, int64_t B, int D
             pl.ks_a = ks;
             pl.ps_a = ps;
         }
+        return RECD_OK;
+        };
+        auto chain_b = [&]() -> recd_status {
         // step B's grouping on the first
         {
             constexpr int SG = 16;
@@ -1593,6 +1721,17 @@ extern "C" recd_status recd_backward_plan(recd_ctx *ctx, int F, int64_t B, int D
                 pl.ps_b = ps;
             }
         }
+        return RECD_OK;
+        };
+        // The host issues one chain after the other: the longer one first.  Sorting all F*B rows makes
+        // step A's chain the longer one; from the run index it is a fraction of step B's.
+        if (run_index) {
+            RECD_TRY(chain_b());
+            RECD_TRY(chain_a());
+        } else {
+            RECD_TRY(chain_a());
+            RECD_TRY(chain_b());
+        }
         RECD_HIP(ctx, hipGetLastError());
     }
     RECD_HIP(ctx, hipEventRecord(ctx->ev_plan_a, sa));
@@ -1600,6 +1739,27 @@ extern "C" recd_status recd_backward_plan(recd_ctx *ctx, int F, int64_t B, int D
     pl.pending = true;
     pl.valid = true;
     return RECD_OK;
+}
+
+extern "C" recd_status recd_backward_plan(recd_ctx *ctx, int F, int64_t B, int D, const int32_t *inverse,
+                                          const int64_t *feat_uoff, const int64_t *u_values,
+                                          const int64_t *u_offsets, const int64_t *rows, int64_t U_cap,
+                                          int64_t M_cap, int64_t *touched_rows, int64_t *feat_roff)
+{
+    return plan_common(ctx, F, B, D, inverse, feat_uoff, u_values, u_offsets, rows, U_cap, M_cap, nullptr, 0,
+                       touched_rows, feat_roff);
+}
+
+extern "C" recd_status recd_backward_plan_runs(recd_ctx *ctx, int F, int64_t B, int D, const int32_t *inverse,
+                                               const int64_t *feat_uoff, const int64_t *u_values,
+                                               const int64_t *u_offsets, const int64_t *rows, int64_t U_cap,
+                                               int64_t M_cap, const int64_t *run_index, int64_t runs_cap,
+                                               int64_t *touched_rows, int64_t *feat_roff)
+{
+    if (ctx && !run_index && (int64_t)F * B > 0)
+        return recd_fail(ctx, RECD_EINVAL, "null run_index");
+    return plan_common(ctx, F, B, D, inverse, feat_uoff, u_values, u_offsets, rows, U_cap, M_cap, run_index,
+                       runs_cap, touched_rows, feat_roff);
 }
 
 extern "C" recd_status recd_backward_apply(recd_ctx *ctx, recd_pooling mode, const float *grad_out,
@@ -1700,10 +1860,14 @@ extern "C" recd_status recd_backward_apply(recd_ctx *ctx, recd_pooling mode, con
         RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned, w.list_off_b + 1, sizeof(int64_t), hipMemcpyDeviceToHost, st));
         RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned + 1, w.b.n_dev + 1, sizeof(int64_t), hipMemcpyDeviceToHost,
                                      st));
+        RECD_HIP(ctx, hipMemcpyAsync(ctx->host_pinned + 2, w.a.n_dev + 1, sizeof(int64_t), hipMemcpyDeviceToHost,
+                                     st));
         RECD_HIP(ctx, hipStreamSynchronize(st));
         host_R[0] = ctx->host_pinned[0];
         if (ctx->host_pinned[1])
             return recd_fail(ctx, RECD_ECAPACITY, "M_cap=%lld is smaller than M", (long long)M_cap);
+        if (ctx->host_pinned[2])
+            return recd_fail(ctx, RECD_ECAPACITY, "runs_cap is smaller than the number of runs");
     }
     return RECD_OK;
 }

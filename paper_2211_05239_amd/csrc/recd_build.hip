@@ -82,8 +82,14 @@ __global__ __launch_bounds__(kHashBlock) void k_hash_insert(const int64_t *__res
                                                      int weak_hash)
 {
     const int s = threadIdx.x % SG;
-    const int64_t l0 = ((int64_t)blockIdx.x * (kHashBlock / SG) + threadIdx.x / SG) * kLPG;
-    if (l0 >= n_lists)
+    // Blocks go to the eight XCDs in turn; every XCD takes a contiguous eighth of the lists, so that
+    // the predecessor of a block's first list, and the cache lines that neighbouring lists share,
+    // were fetched by the block before it through the same L2 (with neighbouring blocks on different
+    // XCDs the kernel fetched 1.3 times the ids from memory).
+    const int64_t per_xcd = ((int64_t)gridDim.x + 7) / 8;
+    const int64_t blk = (int64_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    const int64_t l0 = (blk * (kHashBlock / SG) + threadIdx.x / SG) * kLPG;
+    if (blk >= (int64_t)gridDim.x || l0 >= n_lists)
         return;  // whole lane group leaves together
 
     // offsets of rows l0-1 .. l0+kLPG (clamped to the array)
@@ -286,6 +292,66 @@ __device__ __forceinline__ void block_scan3(int64_t a, int64_t b, int64_t c, int
     eb = ob + ib - b;
 }
 
+// The scan of the numbering kernels, made of ballots: per thread two flags (first occurrence, run
+// head), the length of a first occurrence and the row of a run head.  Exclusive counts of the flags
+// and the nearest head at or before the thread come from wave ballots (no data moves between lanes);
+// only the lengths take a shuffle scan.  Totals of the block are returned to every thread.
+struct ListScan {
+    int64_t firsts_before, heads_before, len_before;  // exclusive, inside the block
+    int64_t head_row;                                  // nearest run head at or before the thread, -1: none yet
+    int64_t firsts, heads, len, last_head;             // block totals
+};
+
+template <bool TOTALS_ONLY>
+__device__ __forceinline__ ListScan block_scan_lists(bool first, bool head, int64_t flen, int64_t row)
+{
+    __shared__ uint32_t s_first[kScanBlock / 64], s_heads[kScanBlock / 64];
+    __shared__ int64_t s_len[kScanBlock / 64], s_last[kScanBlock / 64];
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const uint64_t mf = __ballot(first), mh = __ballot(head);
+    const uint64_t le = lane == 63 ? ~0ull : ((1ull << (lane + 1)) - 1), lt = le >> 1;
+    ListScan r;
+    int64_t il = flen;  // inclusive sum of the lengths in the wave
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int64_t x = TOTALS_ONLY ? __shfl_xor(il, d) : __shfl_up(il, d);
+        if (TOTALS_ONLY || lane >= d)
+            il += x;
+    }
+    // row of the wave's lane k = row - lane + k
+    const uint64_t hb = mh & le;
+    r.head_row = hb ? row - lane + (63 - __builtin_clzll(hb)) : -1;
+    __syncthreads();  // the shared arrays are free again
+    if (lane == 63) {
+        s_first[w] = (uint32_t)__popcll(mf);
+        s_heads[w] = (uint32_t)__popcll(mh);
+        s_len[w] = il;  // lane 63 holds the wave's sum in either mode
+        s_last[w] = mh ? row - 63 + (63 - __builtin_clzll(mh)) : -1;
+    }
+    __syncthreads();
+    r.firsts_before = __popcll(mf & lt);
+    r.heads_before = __popcll(mh & lt);
+    r.len_before = il - flen;
+    r.firsts = r.heads = r.len = 0;
+    r.last_head = -1;
+    int64_t prev_last = -1;  // last head of the waves before this one (rows grow with the wave)
+    for (int i = 0; i < (int)(blockDim.x >> 6); i++) {
+        if (i < w) {
+            r.firsts_before += s_first[i];
+            r.heads_before += s_heads[i];
+            r.len_before += s_len[i];
+            prev_last = s_last[i] > prev_last ? s_last[i] : prev_last;
+        }
+        r.firsts += s_first[i];
+        r.heads += s_heads[i];
+        r.len += s_len[i];
+        r.last_head = s_last[i] > r.last_head ? s_last[i] : r.last_head;
+    }
+    if (r.head_row < 0)
+        r.head_row = prev_last;
+    return r;
+}
+
 __global__ __launch_bounds__(kScanBlock) void k_flags(const int64_t *__restrict__ offsets, int64_t B,
                                                       int64_t n_lists,
                                                       const uint64_t *__restrict__ table,
@@ -311,12 +377,11 @@ __global__ __launch_bounds__(kScanBlock) void k_flags(const int64_t *__restrict_
     }
     // two counts ride in one sum: first occurrences in the low half, run heads in the high half
     // (both stay below 2^31)
-    int64_t ea, eb, ic, ta, tb, tc;
-    block_scan3(first + ((int64_t)(head >= 0) << 32), flen, head, ea, eb, ic, ta, tb, tc);
+    const ListScan sc = block_scan_lists<true>(first != 0, head >= 0, flen, l);
     if (threadIdx.x == 0) {
-        bs_cnt[blockIdx.x] = ta;
-        bs_len[blockIdx.x] = tb;
-        bs_head[blockIdx.x] = tc;
+        bs_cnt[blockIdx.x] = sc.firsts + (sc.heads << 32);
+        bs_len[blockIdx.x] = sc.len;
+        bs_head[blockIdx.x] = sc.last_head;
     }
 }
 
@@ -384,23 +449,47 @@ __global__ __launch_bounds__(kScanBlock) void k_number(const int64_t *__restrict
             }
         }
     }
-    int64_t ea, eb, ic, ta, tb, tc;
-    block_scan3(first + ((int64_t)(head >= 0) << 32), flen, head, ea, eb, ic, ta, tb, tc);
+    const ListScan sc = block_scan_lists<false>(first != 0, head >= 0, flen, l);
+    // What the blocks before this one hold: the block's first wave adds up the per-block sums of
+    // k_flags itself (a few thousand values from L2) instead of a one-block scan kernel in between.
+    __shared__ int64_t s_carry[3];
+    if (threadIdx.x < 64) {
+        int64_t pa = 0, pb = 0, pc = -1;
+        for (int64_t i = threadIdx.x; i < (int64_t)blockIdx.x; i += 64) {
+            pa += bs_cnt[i];
+            pb += bs_len[i];
+            pc = bs_head[i] > pc ? bs_head[i] : pc;
+        }
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            pa += __shfl_xor(pa, d);
+            pb += __shfl_xor(pb, d);
+            const int64_t x = __shfl_xor(pc, d);
+            pc = x > pc ? x : pc;
+        }
+        if (threadIdx.x == 0) {
+            s_carry[0] = pa;
+            s_carry[1] = pb;
+            s_carry[2] = pc;
+        }
+    }
+    __syncthreads();
+    const int64_t carry_cnt = s_carry[0], carry_len = s_carry[1], carry_head = s_carry[2];
+    const int64_t ea = sc.firsts_before + (sc.heads_before << 32), eb = sc.len_before, ic = sc.head_row;
     if (l < n_lists) {
-        const int64_t packed = bs_cnt[blockIdx.x] + ea;   // first occurrences | run heads before l
+        const int64_t packed = carry_cnt + ea;   // first occurrences | run heads before l
         if (hrank)
             hrank[l] = head >= 0 ? (int32_t)(packed >> 32) : -1;
         if (head < 0) {
             // follower: copy the representative of the run head (the nearest head at or before l;
             // row 0 of a feature is always a head, so the run never leaves the feature)
-            const int64_t carry = bs_head[blockIdx.x];
-            const int64_t hl = ic > carry ? ic : carry;
+            const int64_t hl = ic > carry_head ? ic : carry_head;
             const uint64_t e = table[(uint64_t)f * ((uint64_t)cap_mask + 1) + (uint32_t)slot_of[hl]];
             my_rep = (int64_t)(e & 0xffffffffull);
         }
         rep[l] = (int32_t)my_rep;
         const int64_t num = packed & 0xffffffffll;  // unique lists before (f,b), all features
-        const int64_t pos = bs_len[blockIdx.x] + eb;  // their ids
+        const int64_t pos = carry_len + eb;  // their ids
         number[l] = (int32_t)num;
         if (first) {
             u_offsets[num] = pos;
@@ -412,11 +501,12 @@ __global__ __launch_bounds__(kScanBlock) void k_number(const int64_t *__restrict
             const int64_t U = num + first, M = pos + flen;
             u_offsets[U] = M;
             feat_uoff[F] = U;
+            const int64_t n_runs = (packed >> 32) + (head >= 0);  // runs of adjacent rows with one list
             counts[0] = U;
             counts[1] = M;
+            counts[2] = n_runs;
             if (run_index) {
                 // header {runs, U, M} and the closing entry (a run ends where the next one starts)
-                const int64_t n_runs = (packed >> 32) + (head >= 0);
                 run_index[0] = n_runs;
                 run_index[1] = U;
                 run_index[2] = M;
@@ -430,6 +520,7 @@ __global__ __launch_bounds__(kScanBlock) void k_number(const int64_t *__restrict
                 // before the next)
                 mailbox[0] = U;
                 mailbox[1] = M;
+                mailbox[2] = n_runs;
                 __threadfence_system();
                 mailbox[7] = seq;
                 __threadfence_system();
@@ -506,6 +597,7 @@ __global__ void k_empty_ikjt(int F, int64_t *u_offsets, int64_t *feat_uoff, int6
         u_offsets[0] = 0;
         counts[0] = 0;
         counts[1] = 0;
+        counts[2] = 0;
     }
 }
 
@@ -971,7 +1063,8 @@ void insert_lists(recd_ctx *ctx, hipStream_t st, const SlotWs &w, int F, int64_t
     const int64_t n_lists = (int64_t)F * B;
     if (!table_is_empty)
         clear_table(st, w, F);
-    const int64_t hblocks = (n_lists + (kHashBlock / SG) * kLPG - 1) / ((kHashBlock / SG) * kLPG);
+    int64_t hblocks = (n_lists + (kHashBlock / SG) * kLPG - 1) / ((kHashBlock / SG) * kLPG);
+    hblocks = (hblocks + 7) / 8 * 8;  // the kernel deals its blocks to 8 XCDs
     recd_time_begin(ctx, RECD_T_HASH, st);
     if (wbits)
         hipLaunchKernelGGL((k_hash_insert<SG, true>), dim3((unsigned)hblocks), dim3(kHashBlock), 0, st, values, wbits,
@@ -994,8 +1087,6 @@ void number_slots(hipStream_t st, const SlotWs &w, int tables, int64_t B, const 
     const uint32_t mask = (uint32_t)(w.cap - 1);
     hipLaunchKernelGGL(k_flags, dim3(nblk), dim3(kScanBlock), 0, st, offsets, B, n, w.table, mask, w.slot_of,
                        w.bs_cnt, w.bs_len, w.bs_head);
-    hipLaunchKernelGGL(k_scan_blocks, dim3(1), dim3(kScanBlock), 0, st, w.bs_cnt, w.bs_len, w.bs_head,
-                       (int64_t)nblk);
     hipLaunchKernelGGL(k_number, dim3(nblk), dim3(kScanBlock), 0, st, offsets, B, n, tables, w.table, mask,
                        w.slot_of, w.bs_cnt, w.bs_len, w.bs_head, w.rep, w.number, w.src_of, u_off, uoff,
                        w.counts, mailbox, seq, run_index ? w.hrank : nullptr, run_index);

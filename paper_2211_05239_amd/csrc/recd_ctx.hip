@@ -172,7 +172,7 @@ recd_status recd_publish_build_counts(recd_ctx *ctx)
         return RECD_OK;  // no mapped mailbox: recd_last_ikjt_counts copies from the device array
     const int64_t seq = ++ctx->build_seq;
     ctx->build_published = true;
-    hipLaunchKernelGGL(k_publish, dim3(1), dim3(1), 0, ctx->stream, ctx->build_counts_dev, 2,
+    hipLaunchKernelGGL(k_publish, dim3(1), dim3(1), 0, ctx->stream, ctx->build_counts_dev, 3,
                        ctx->mailbox_dev + 8, seq);
     RECD_HIP(ctx, hipGetLastError());
     return RECD_OK;
@@ -370,10 +370,10 @@ recd_status recd_set_option(recd_ctx *ctx, recd_option opt, int64_t value)
     return recd_fail(ctx, RECD_EINVAL, "unknown option %d", (int)opt);
 }
 
-recd_status recd_last_ikjt_counts(recd_ctx *ctx, int64_t *host_U_M)
+// {U, M, runs} of the most recent plain / weighted build: from the build's own publication if there
+// is one (waits for that build only), else from the device array (waits for the stream).
+static recd_status last_build_counts(recd_ctx *ctx, int64_t out[3])
 {
-    if (!ctx || !host_U_M)
-        return RECD_EINVAL;
     if (!ctx->build_valid)
         return recd_fail(ctx, RECD_EINVAL, "no recd_build_ikjt / recd_build_ikjt_weighted call on this context yet");
     RECD_HIP(ctx, hipSetDevice(ctx->device));
@@ -383,8 +383,9 @@ recd_status recd_last_ikjt_counts(recd_ctx *ctx, int64_t *host_U_M)
         for (uint64_t spin = 0;; spin++) {
             if (ctx->mailbox[15] == ctx->build_seq) {
                 std::atomic_thread_fence(std::memory_order_acquire);
-                host_U_M[0] = ctx->mailbox[8];
-                host_U_M[1] = ctx->mailbox[9];
+                out[0] = ctx->mailbox[8];
+                out[1] = ctx->mailbox[9];
+                out[2] = ctx->mailbox[10];
                 return RECD_OK;
             }
             if ((spin & 0xfff) == 0xfff &&
@@ -393,7 +394,28 @@ recd_status recd_last_ikjt_counts(recd_ctx *ctx, int64_t *host_U_M)
         }
     }
     RECD_HIP(ctx, hipStreamSynchronize(ctx->stream));
-    RECD_HIP(ctx, hipMemcpy(host_U_M, ctx->build_counts_dev, 2 * sizeof(int64_t), hipMemcpyDeviceToHost));
+    RECD_HIP(ctx, hipMemcpy(out, ctx->build_counts_dev, 3 * sizeof(int64_t), hipMemcpyDeviceToHost));
+    return RECD_OK;
+}
+
+recd_status recd_last_ikjt_counts(recd_ctx *ctx, int64_t *host_U_M)
+{
+    if (!ctx || !host_U_M)
+        return RECD_EINVAL;
+    int64_t c[3];
+    RECD_TRY(last_build_counts(ctx, c));
+    host_U_M[0] = c[0];
+    host_U_M[1] = c[1];
+    return RECD_OK;
+}
+
+recd_status recd_last_ikjt_run_count(recd_ctx *ctx, int64_t *host_runs)
+{
+    if (!ctx || !host_runs)
+        return RECD_EINVAL;
+    int64_t c[3];
+    RECD_TRY(last_build_counts(ctx, c));
+    host_runs[0] = c[2];
     return RECD_OK;
 }
 

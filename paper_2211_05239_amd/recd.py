@@ -48,7 +48,8 @@ EXPORTED = [
     "recd_backward_dedup_mode", "recd_build_ikjt_weighted", "recd_pooled_lookup_unique_weighted",
     "recd_kjt_pooled_lookup_weighted", "recd_backward_dedup_weighted", "recd_backward_dedup_max",
     "recd_last_ikjt_counts", "recd_backward_plan", "recd_backward_apply", "recd_build_ikjt_noalloc",
-    "recd_build_ikjt_runs", "recd_ikjt_run_index", "recd_pooled_lookup_expand",
+    "recd_build_ikjt_runs", "recd_ikjt_run_index", "recd_pooled_lookup_expand", "recd_last_ikjt_run_count",
+    "recd_backward_plan_runs",
 ]
 
 _vp = C.c_void_p
@@ -88,6 +89,9 @@ _lib.recd_backward_dedup_max.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, _vp, 
 _lib.recd_last_ikjt_counts.argtypes = [_vp, _vp]
 _lib.recd_backward_plan.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, _vp, _vp, _vp, _vp, _vp, C.c_int64, C.c_int64,
                                     _vp, _vp]
+_lib.recd_last_ikjt_run_count.argtypes = [_vp, _vp]
+_lib.recd_backward_plan_runs.argtypes = [_vp, C.c_int, C.c_int64, C.c_int, _vp, _vp, _vp, _vp, _vp, C.c_int64, C.c_int64,
+                                         _vp, C.c_int64, _vp, _vp]
 _lib.recd_backward_apply.argtypes = [_vp, C.c_int, _vp, _vp, _vp, _vp, C.c_float, C.c_float, _vp]
 _lib.recd_sequence_lookup_unique.argtypes = [_vp, C.c_int, C.c_int, C.c_int, C.c_int, _vp, _vp, _vp, _vp,
                                              _vp, C.c_int64, C.c_int64, _vp]
@@ -328,6 +332,19 @@ class Context:
         self._check(_lib.recd_backward_plan(self._h, F, B, D, _ptr(inverse), _ptr(feat_uoff), _ptr(u_values),
                                             _ptr(u_offsets), rows_arr, U_cap, M_cap, _ptr(touched_rows),
                                             _ptr(feat_roff)))
+
+    def last_ikjt_run_count(self) -> int:
+        host = (C.c_int64 * 1)(0)
+        self._check(_lib.recd_last_ikjt_run_count(self._h, host))
+        return int(host[0])
+
+    def backward_plan_runs(self, F: int, B: int, D: int, inverse, feat_uoff, u_values, u_offsets,
+                           rows: Sequence[int], U_cap: int, M_cap: int, run_index, runs_cap: int, touched_rows,
+                           feat_roff):
+        rows_arr = (C.c_int64 * len(rows))(*rows)
+        self._check(_lib.recd_backward_plan_runs(self._h, F, B, D, _ptr(inverse), _ptr(feat_uoff), _ptr(u_values),
+                                                 _ptr(u_offsets), rows_arr, U_cap, M_cap, _ptr(run_index), runs_cap,
+                                                 _ptr(touched_rows), _ptr(feat_roff)))
 
     def backward_apply(self, grad_out, grad_rows, tables=None, adagrad_state=None, lr: float = 0.0,
                        eps: float = 0.0, want_count: bool = False, mode: str = "sum"):

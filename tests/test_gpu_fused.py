@@ -243,3 +243,89 @@ def test_fused_leaves_a_pending_plan_alone(ctx, recd):
     torch.cuda.synchronize()
     c2.close()
     assert R == R2 and torch.equal(touched[:R], t2[:R]) and torch.equal(grad_rows[:R], g2[:R])
+
+
+def _plan_runs_case(ctx, recd, w, batch, runs_cap_of):
+    """recd_backward_plan_runs + apply against the one-call backward on a fresh context: the same
+    touched rows, gradient rows and updated tables, bit for bit."""
+    F, B, D = batch.F, batch.B, w.D
+    gout = gu.to_dev(synth.make_grad_out(w, 0))
+    tabs = synth.make_tables(w)
+    values, offsets, ik, runs, (uv, uo, inv, fu) = _build_runs(ctx, batch)
+    n_runs = len(orc.run_index(F, B, inv, fu, uo)[1])
+    # a build without a run index counts the runs all the same
+    ctx.build_ikjt(F, B, values, offsets, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff)
+    assert ctx.last_ikjt_run_count() == n_runs and ctx.last_ikjt_counts() == (ik.U, ik.M)
+    ctx.build_ikjt_runs(F, B, values, offsets, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff, runs)
+    assert ctx.last_ikjt_run_count() == n_runs
+    U, M = ik.U, ik.M
+    res = []
+    for planned in (True, False):
+        c = ctx if planned else recd.Context(0)
+        d_tabs = gu.tables_to_dev(tabs, "f32")
+        d_state = [torch.zeros(w.rows, device="cuda") for _ in range(F)]
+        touched = torch.full((max(M, 1),), -7, dtype=torch.int64, device="cuda")
+        feat_roff = torch.full((F + 1,), -7, dtype=torch.int64, device="cuda")
+        grad_rows = torch.full((max(M, 1), D), float("nan"), device="cuda")
+        if planned:
+            c.backward_plan_runs(F, B, D, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F, U, M,
+                                 runs, runs_cap_of(n_runs, F * B), touched, feat_roff)
+            R = c.backward_apply(gout, grad_rows, tables=d_tabs, adagrad_state=d_state, lr=0.01, eps=1e-8,
+                                 want_count=True)
+        else:
+            R = c.backward_dedup(F, B, gout, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F, U, M,
+                                 touched, feat_roff, grad_rows, tables=d_tabs, adagrad_state=d_state, lr=0.01,
+                                 eps=1e-8, want_count=True)
+            torch.cuda.synchronize()
+            c.close()
+        res.append((R, touched[:R].clone(), feat_roff.clone(), grad_rows[:R].clone(), d_tabs, d_state))
+    a, b = res
+    assert a[0] == b[0]
+    for x, y in zip(a[1:4], b[1:4]):
+        assert torch.equal(x, y)
+    for x, y in zip(a[4] + a[5], b[4] + b[5]):
+        assert torch.equal(x, y)
+    tr, fr, gr = orc.backward_kjt(F, B, synth.make_grad_out(w, 0), batch.values, batch.offsets)
+    assert a[0] == len(tr) and np.array_equal(a[1].cpu().numpy(), tr)
+    gu.assert_close_f32(gu.out_to_f64(a[3]), gr, "grad_rows of the run-based plan")
+
+
+@pytest.mark.parametrize("name,kw", [("cfg1", dict(F=3, B=357, rows=900, D=32)),
+                                     ("cfg2", dict(F=6, B=4096, rows=100_000, D=64)),
+                                     ("cfg5", dict(F=8, B=3000, rows=50_000, D=128))])
+@pytest.mark.parametrize("cap", ["exact", "loose", "zero"])
+def test_backward_plan_from_runs(ctx, recd, name, kw, cap):
+    w = synth.scaled(synth.WORKLOADS[name], **kw)
+    cap_of = {"exact": lambda n, fb: n, "loose": lambda n, fb: fb, "zero": lambda n, fb: 0}[cap]
+    _plan_runs_case(ctx, recd, w, synth.make_batch(w, 1), cap_of)
+
+
+def test_backward_plan_from_runs_without_adjacency(ctx, recd):
+    """Every row its own run, lists coming back all over the batch; and runs longer than a tile."""
+    rng = np.random.default_rng(5)
+    base = [[int(x) for x in rng.integers(0, 60, size=rng.integers(1, 5))] for _ in range(50)]
+    order = rng.integers(0, 50, size=2500)
+    for i in range(1, len(order)):
+        if order[i] == order[i - 1]:
+            order[i] = (order[i] + 1) % 50
+    lists = [base[i] for i in order]
+    w = synth.scaled(synth.WORKLOADS["cfg1"], F=2, B=len(lists), rows=60, D=16)
+    _plan_runs_case(ctx, recd, w, synth.batch_from_lists([lists, lists[::-1]]), lambda n, fb: n)
+    lists = [[1, 2]] * 3000 + [[3]] * 1500 + [[1, 2]] * 700
+    w = synth.scaled(synth.WORKLOADS["cfg1"], F=1, B=len(lists), rows=10, D=8)
+    _plan_runs_case(ctx, recd, w, synth.batch_from_lists([lists]), lambda n, fb: n)
+
+
+def test_backward_plan_from_runs_reports_a_small_bound(ctx, recd):
+    w = synth.scaled(synth.WORKLOADS["cfg2"], F=2, B=512, rows=5000, D=16)
+    batch = synth.make_batch(w, 0)
+    values, offsets, ik, runs, _ = _build_runs(ctx, batch)
+    gout = gu.to_dev(synth.make_grad_out(w, 0))
+    touched = torch.zeros(ik.M, dtype=torch.int64, device="cuda")
+    feat_roff = torch.zeros(w.F + 1, dtype=torch.int64, device="cuda")
+    grad_rows = torch.zeros(ik.M, w.D, device="cuda")
+    ctx.backward_plan_runs(w.F, w.B, w.D, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * w.F,
+                           ik.U, ik.M, runs, 5, touched, feat_roff)
+    with pytest.raises(recd.RecdError) as e:
+        ctx.backward_apply(gout, grad_rows, want_count=True)
+    assert e.value.status == recd.RECD_ECAPACITY
