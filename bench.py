@@ -63,10 +63,10 @@ def parse_args():
     ap.add_argument("--partial", type=float, default=0.0,
                     help="also time the partial IKJT path on the workload with this probability of a "
                          "sample's lists shifting by one id within a session (0 = skip)")
-    ap.add_argument("--plan-all-rows", dest="run_plan", action="store_false",
-                    help="the backward's plan sorts all F*B rows by unique list (recd_build_ikjt + "
-                         "recd_backward_plan) instead of the batch's runs (recd_build_ikjt_runs + "
-                         "recd_backward_plan_runs)")
+    ap.add_argument("--plan-from-runs", dest="run_plan", action="store_true",
+                    help="the backward's plan sorts the batch's runs (recd_build_ikjt_runs + "
+                         "recd_backward_plan_runs) instead of all F*B rows by unique list (recd_build_ikjt + "
+                         "recd_backward_plan); measured a few microseconds slower per step at cfg5")
     ap.add_argument("--one-call-backward", dest="planned", action="store_false",
                     help="run the backward as one call after the expand instead of plan (next to the forward "
                          "calls) + apply")
@@ -134,7 +134,7 @@ class DeviceProblem:
         self.need_backward = need_backward
         self.planned = True
         self.fused_forward = False
-        self.run_plan = True
+        self.run_plan = False
         ws = recd.workspace_bytes(F, B, Nmax, D)
         self.ctx = recd.Context(0, workspace_hint_bytes=ws)
         if tune:
@@ -378,7 +378,7 @@ def run_workload(torch, recd, synth, w, args, need_backward, detail=True, pipeli
     P = DeviceProblem(torch, recd, synth, w, args.batches, need_backward, getattr(args, "store_grad", False), getattr(args, "tune", 0))
     P.planned = getattr(args, "planned", True)
     P.fused_forward = getattr(args, "fused", False)
-    P.run_plan = getattr(args, "run_plan", True)
+    P.run_plan = getattr(args, "run_plan", False)
     nb = len(P.batches)
     F, B, D = w.F, w.B, w.D
     e = 4 if w.table_dtype == "f32" else 2

@@ -45,6 +45,10 @@ def _feature_slice(batch, f):
     return batch.values[lo:hi], batch.offsets[f * B:(f + 1) * B + 1] - lo
 
 
+# eight features, one for each of the eight block queues (feature mod 8) of the lookup kernels
+SPREAD_64 = (0, 9, 18, 27, 36, 45, 54, 63)
+
+
 def _run_forward(recd, w, batch_index, sample_features):
     batch = synth.make_batch(w, batch_index)
     F, B, D = w.F, w.B, w.D
@@ -71,6 +75,19 @@ def _run_forward(recd, w, batch_index, sample_features):
                        kjt.view(torch.int32 if tdt == torch.float32 else torch.int16))
     idx = torch.from_numpy(fu[:-1]).cuda().repeat_interleave(B) + ik.inverse.long()
     assert torch.equal(out.view(F * B, D), pooled[idx])
+    # the one-pass call on the builder's run index: the same bits in pooled and out
+    runs = torch.zeros(3 * (F * B + 2), dtype=torch.int64, device="cuda")
+    ik2 = gu.DeviceIKJT(F, B, batch.N)
+    ctx.build_ikjt_runs(F, B, values, offsets, ik2.u_values, ik2.u_offsets, ik2.inverse, ik2.feat_uoff, runs)
+    n_runs = ctx.last_ikjt_run_count()
+    assert torch.equal(ik2.inverse, ik.inverse) and torch.equal(ik2.u_values[:ik.M], ik.u_values[:ik.M])
+    ref_runs = orc.pack_run_index(*orc.run_index(F, B, inv, fu, uo), ik.U, ik.M)
+    assert n_runs == int(ref_runs[0]) and np.array_equal(runs[:len(ref_runs)].cpu().numpy(), ref_runs)
+    pooled2, out2 = torch.zeros_like(pooled), torch.zeros_like(out)
+    ctx.pooled_lookup_expand(tabs, B, ik2.u_values, runs, n_runs, pooled2, out2)
+    bits = torch.int32 if tdt == torch.float32 else torch.int16
+    assert torch.equal(out2.view(bits), out.view(bits)) and torch.equal(pooled2.view(bits), pooled.view(bits))
+    del pooled2, out2, runs
 
     close = gu.assert_close_f32 if w.table_dtype == "f32" else gu.assert_close_16
     for f in sample_features:
@@ -87,15 +104,15 @@ def _run_forward(recd, w, batch_index, sample_features):
 
 
 def test_cfg2_full(recd):
-    _run_forward(recd, synth.WORKLOADS["cfg2"], 0, sample_features=(0, 7, 15))
+    _run_forward(recd, synth.WORKLOADS["cfg2"], 0, sample_features=(0, 1, 2, 3, 12, 13, 14, 15))
 
 
 def test_cfg3_full_fp16(recd):
-    _run_forward(recd, synth.WORKLOADS["cfg3"], 0, sample_features=(3, 63))
+    _run_forward(recd, synth.WORKLOADS["cfg3"], 0, sample_features=SPREAD_64)
 
 
 def test_cfg4_sweep_member_full(recd):
-    _run_forward(recd, synth.sweep_workload(8), 0, sample_features=(0, 31))
+    _run_forward(recd, synth.sweep_workload(8), 0, sample_features=(0, 9, 18, 27, 4, 13, 22, 31))
 
 
 def test_cfg5_training_step_full(recd):
@@ -103,7 +120,7 @@ def test_cfg5_training_step_full(recd):
     F, B, D = w.F, w.B, w.D
     batch = synth.make_batch(w, 1)
     tabs = _device_tables(w, torch.float32)
-    sample = (0, 40)
+    sample = SPREAD_64
     before = {f: tabs[f].cpu().numpy() for f in sample}
     g = torch.Generator(device="cuda")
     g.manual_seed(99)
@@ -151,14 +168,15 @@ def test_cfg5_training_step_full(recd):
 def test_cfg5_bench_step_full(recd):
     """Two consecutive steps exactly as bench.py issues them: build without a host count, lookup
     sized by the previous step's U, expand, U and M read back while those run, planned backward
-    with the fused update and no stored gradient rows.  Integer outputs in full; the expanded rows
+    with the fused update and no stored gradient rows; the second step in bench.py's other form
+    (run index, one-pass lookup + expand, plan from the runs).  Integer outputs in full; the expanded rows
     and the tables after both steps on sampled features, where the oracle runs both steps too (the
     second step looks up the rows the first one updated)."""
     w = synth.WORKLOADS["cfg5"]
     F, B, D = w.F, w.B, w.D
     batches = [synth.make_batch(w, i) for i in (1, 2)]
     tabs = _device_tables(w, torch.float32)
-    sample = (3, 63)
+    sample = SPREAD_64
     host_tab = {f: tabs[f].cpu().numpy().copy() for f in sample}   # the oracle's own fp32 copy, updated by the oracle
     host_state = {f: np.zeros(w.rows) for f in sample}
     g = torch.Generator(device="cuda")
@@ -174,16 +192,24 @@ def test_cfg5_bench_step_full(recd):
     touched = torch.zeros(Nmax, dtype=torch.int64, device="cuda")
     feat_roff = torch.zeros(F + 1, dtype=torch.int64, device="cuda")
     u_hint = F * B
+    runs = torch.zeros(3 * (F * B + 2), dtype=torch.int64, device="cuda")
     for step, batch in enumerate(batches):
         values, offsets = gu.to_dev(batch.values), gu.to_dev(batch.offsets)
         ik = gu.DeviceIKJT(F, B, batch.N)
-        ctx.build_ikjt(F, B, values, offsets, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff)
-        ctx.pooled_lookup_unique(tabs, ik.u_values, ik.u_offsets, ik.feat_uoff, u_hint, pooled)
-        ctx.expand_inverse(F, B, pooled, ik.feat_uoff, ik.inverse, out)
-        U, M = ctx.last_ikjt_counts()
+        if step == 0:   # the default step of bench.py
+            ctx.build_ikjt(F, B, values, offsets, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff)
+            ctx.pooled_lookup_unique(tabs, ik.u_values, ik.u_offsets, ik.feat_uoff, u_hint, pooled)
+            ctx.expand_inverse(F, B, pooled, ik.feat_uoff, ik.inverse, out)
+            U, M = ctx.last_ikjt_counts()
+            ctx.backward_plan(F, B, D, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F, U, M,
+                              touched, feat_roff)
+        else:           # --one-pass-forward --plan-from-runs
+            ctx.build_ikjt_runs(F, B, values, offsets, ik.u_values, ik.u_offsets, ik.inverse, ik.feat_uoff, runs)
+            ctx.pooled_lookup_expand(tabs, B, ik.u_values, runs, u_hint + u_hint // 16, pooled, out)
+            U, M = ctx.last_ikjt_counts()
+            ctx.backward_plan_runs(F, B, D, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F, U, M,
+                                   runs, ctx.last_ikjt_run_count(), touched, feat_roff)
         u_hint = max(U, 1)
-        ctx.backward_plan(F, B, D, ik.inverse, ik.feat_uoff, ik.u_values, ik.u_offsets, [w.rows] * F, U, M,
-                          touched, feat_roff)
         ctx.backward_apply(grad_out, None, tables=tabs, adagrad_state=state, lr=0.01, eps=1e-8)
         torch.cuda.synchronize()
         ik.U, ik.M = U, M
