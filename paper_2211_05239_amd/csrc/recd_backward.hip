@@ -710,7 +710,7 @@ __global__ __launch_bounds__(256) void k_find_long(const RowSumParams p)
 template <int LPR, bool FINALIZE, bool WT = false>
 __global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const OptAdagrad opt)
 {
-    constexpr int G = 64 / LPR, VPL = 4, US = 1;
+    constexpr int G = 64 / LPR, VPL = 4;
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int g = lane / LPR, r = lane % LPR;
     const int64_t R = FINALIZE ? p.long_count[0] : *p.n_seg;
@@ -739,28 +739,48 @@ __global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const
         int64_t t = k;       // destination segment
         int64_t start = 0;
         int n = 0;
+        int f_seg = 0;
+        int64_t row_seg = 0;
         if (k < R) {
             if (FINALIZE) {
                 t = p.lseg_t[k];
                 start = p.lseg_first[k];
                 n = p.lseg_n[k];
             } else {
+                // one round trip: where the segment lies, and (for the update) which row it is
                 start = p.seg_start[k];
                 const int64_t end = p.seg_start[k + 1];
+                if (opt.n_feat > 0) {
+                    f_seg = opt.seg_feat[k];
+                    row_seg = opt.touched_rows[k];
+                }
                 const int64_t len = end - start;
                 n = len <= p.long_seg ? (int)len : 0;  // longer segments were cut into chunks by k_find_long
             }
         }
         const bool mine = n > 0;  // uniform inside the lane group
         const bool update = mine && opt.n_feat > 0;
+        // second round trip: the segment's entries (the first kPre * LPR of them, one load per lane
+        // and LPR entries) together with the destination row and its accumulator
+        constexpr int kPre = FINALIZE ? 0 : 4;
+        uint32_t pre[kPre > 0 ? kPre : 1];
+        float prew[kPre > 0 ? kPre : 1];
+#pragma unroll
+        for (int u = 0; u < kPre; u++) {
+            const int idx = u * LPR + r;
+            pre[u] = idx < n ? p.pay[start + idx] : 0u;
+            prew[u] = (WT && idx < n) ? p.pay_w[start + idx] : 1.f;
+        }
         float4 wreg[VPL];
         float mreg = 0.f;
         float *wrow = nullptr, *mp = nullptr;
         if (update) {
-            const int f = opt.seg_feat[t];
-            const int64_t row = opt.touched_rows[t];
-            mp = opt.m[f] + row;
-            wrow = opt.w[f] + row * p.D;
+            if (FINALIZE) {
+                f_seg = opt.seg_feat[t];
+                row_seg = opt.touched_rows[t];
+            }
+            mp = opt.m[f_seg] + row_seg;
+            wrow = opt.w[f_seg] + row_seg * p.D;
             mreg = *mp;
 #pragma unroll
             for (int w = 0; w < VPL; w++)
@@ -775,40 +795,44 @@ __global__ __launch_bounds__(256) void k_segsum_rows(const RowSumParams p, const
 #pragma unroll
         for (int w = 0; w < VPL; w++)
             acc[w] = make_float4(0.f, 0.f, 0.f, 0.f);
-        for (int i = 0; i < n; i += US) {
-            int64_t id[US];
-            float wt[US];
+        // one entry: the source row `id` (times wt) added to the segment's sum
+        auto add_entry = [&](int64_t id, float wt) {
+            float4 v[VPL];
 #pragma unroll
-            for (int u = 0; u < US; u++) {
-                const int64_t j = start + (i + u < n ? i + u : i);
-                id[u] = FINALIZE ? j : (int64_t)p.pay[j];
-                wt[u] = WT ? p.pay_w[j] : 1.f;
+            for (int w = 0; w < VPL; w++)
+                if (piece[w])
+                    v[w] = table[id * p.pieces + w * LPR + r];
+#pragma unroll
+            for (int w = 0; w < VPL; w++)
+                if (piece[w]) {
+                    if (WT) {
+                        acc[w].x = __fmaf_rn(wt, v[w].x, acc[w].x);
+                        acc[w].y = __fmaf_rn(wt, v[w].y, acc[w].y);
+                        acc[w].z = __fmaf_rn(wt, v[w].z, acc[w].z);
+                        acc[w].w = __fmaf_rn(wt, v[w].w, acc[w].w);
+                    } else {
+                        acc[w].x += v[w].x;
+                        acc[w].y += v[w].y;
+                        acc[w].z += v[w].z;
+                        acc[w].w += v[w].w;
+                    }
+                }
+        };
+        // entries in ascending order: the fetched ones come out of the lane group's registers, any
+        // further ones (cuts above kPre * LPR entries) are read one by one
+        const int gbase = lane - r;
+#pragma unroll
+        for (int u = 0; u < kPre; u++) {
+            const int cnt = n - u * LPR < LPR ? n - u * LPR : LPR;
+            for (int ii = 0; ii < cnt; ii++) {
+                const uint32_t id = __shfl(pre[u], gbase + ii);
+                const float wt = WT ? __shfl(prew[u], gbase + ii) : 1.f;
+                add_entry((int64_t)id, wt);
             }
-            float4 v[US][VPL];
-#pragma unroll
-            for (int u = 0; u < US; u++)
-#pragma unroll
-                for (int w = 0; w < VPL; w++)
-                    if (piece[w])
-                        v[u][w] = table[id[u] * p.pieces + w * LPR + r];
-#pragma unroll
-            for (int u = 0; u < US; u++)
-                if (i + u < n)
-#pragma unroll
-                    for (int w = 0; w < VPL; w++)
-                        if (piece[w]) {
-                            if (WT) {
-                                acc[w].x = __fmaf_rn(wt[u], v[u][w].x, acc[w].x);
-                                acc[w].y = __fmaf_rn(wt[u], v[u][w].y, acc[w].y);
-                                acc[w].z = __fmaf_rn(wt[u], v[u][w].z, acc[w].z);
-                                acc[w].w = __fmaf_rn(wt[u], v[u][w].w, acc[w].w);
-                            } else {
-                                acc[w].x += v[u][w].x;
-                                acc[w].y += v[u][w].y;
-                                acc[w].z += v[u][w].z;
-                                acc[w].w += v[u][w].w;
-                            }
-                        }
+        }
+        for (int i = kPre * LPR; i < n; i++) {
+            const int64_t j = start + i;
+            add_entry(FINALIZE ? j : (int64_t)p.pay[j], WT ? p.pay_w[j] : 1.f);
         }
         if (mine)
             finish_segment<LPR>(p, opt, t, acc, wreg, mreg, wrow, mp, piece, r, update);
