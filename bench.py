@@ -42,10 +42,15 @@ def parse_args():
                     help="skip the duplication sweep (cfg4, S in 1,2,4,8,32)")
     ap.add_argument("--no-others", dest="others", action="store_false",
                     help="skip the other configurations (cfg1, cfg2, cfg3, forward only)")
-    ap.add_argument("--one-pass-forward", dest="fused", action="store_true",
-                    help="the step runs the unique lookup and the expand as the one-pass call "
-                         "(recd_build_ikjt_runs + recd_pooled_lookup_expand) instead of two calls; measured "
-                         "slower on this chip, timed beside the two calls in `regions` either way")
+    ap.add_argument("--forward", choices=("auto", "two-call", "one-pass"), default="auto",
+                    help="how the step runs the unique lookup and the expand: as two calls (recd_build_ikjt + "
+                         "recd_pooled_lookup_unique + recd_expand_inverse), as the one-pass call "
+                         "(recd_build_ikjt_runs + recd_pooled_lookup_expand), or auto = whichever is the faster "
+                         "on this chip for the workload's shape (one pass for batches of at most 16384 rows, "
+                         "where launches count, and for 16-bit tables; two calls otherwise); the step is also "
+                         "timed in the other form, and both calls are timed alone in `regions` either way")
+    ap.add_argument("--one-pass-forward", dest="forward", action="store_const", const="one-pass",
+                    help="same as --forward one-pass")
     ap.add_argument("--steps-only", action="store_true",
                     help="run only the warm-up and the timed steps of the workload (the run to profile: no "
                          "per-call passes, no comparison path, no CPU baseline, no other configurations)")
@@ -374,10 +379,18 @@ def kernel_bytes(name, sh):
     }[name]
 
 
+def one_pass_forward(w, args):
+    """Whether the step of workload w runs the forward pass as the one-pass call."""
+    form = getattr(args, "forward", "auto")
+    if form == "auto":
+        return w.F * w.B <= 16384 or w.table_dtype != "f32"
+    return form == "one-pass"
+
+
 def run_workload(torch, recd, synth, w, args, need_backward, detail=True, pipeline=True, steps=None):
     P = DeviceProblem(torch, recd, synth, w, args.batches, need_backward, getattr(args, "store_grad", False), getattr(args, "tune", 0))
     P.planned = getattr(args, "planned", True)
-    P.fused_forward = getattr(args, "fused", False)
+    P.fused_forward = one_pass_forward(w, args)
     P.run_plan = getattr(args, "run_plan", False)
     nb = len(P.batches)
     F, B, D = w.F, w.B, w.D
@@ -408,6 +421,20 @@ def run_workload(torch, recd, synth, w, args, need_backward, detail=True, pipeli
     wall_ms = (time.perf_counter() - t0) * 1e3 / steps
     per_step = sorted(a.elapsed_time(b) for a, b in ev)
     step_ms = float(per_step[len(per_step) // 2])
+    # ... and in the other form of the forward pass (event-timed median), for comparison
+    P.fused_forward = not P.fused_forward
+    for k in range(max(args.warmup, 2)):
+        P.step(k % nb)
+    ev2 = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    for k in range(steps):
+        ev2[k][0].record()
+        P.step(k % nb)
+        ev2[k][1].record()
+    torch.cuda.synchronize()
+    other_ms = float(sorted(a.elapsed_time(b) for a, b in ev2)[steps // 2])
+    P.fused_forward = not P.fused_forward
+    for k in range(2):
+        P.step(k % nb)
     # The same K steps once more with the library's own event pairs around the step's main kernels
     # (on the stream each is launched on): per-kernel launch times inside the running step, next to
     # whatever the side streams do meanwhile.  Kept out of the pass above: a pair of events per kernel
@@ -426,6 +453,9 @@ def run_workload(torch, recd, synth, w, args, need_backward, detail=True, pipeli
     P.ctx.set_option(recd._OPT_INTERNAL_TIMING, 0)
 
     res = {"step_ms": step_ms, "step_ms_wall_mean": wall_ms, "step_ms_event_mean": float(np.mean(per_step)),
+           "forward": "one-pass" if P.fused_forward else "two-call",
+           "step_ms_one_pass_forward": step_ms if P.fused_forward else other_ms,
+           "step_ms_two_call_forward": other_ms if P.fused_forward else step_ms,
            "B": B, "F": F, "D": D}
     N = float(np.mean([b.N for b in P.batches]))
     U = float(np.mean([s[0] for s in stats]))
@@ -931,14 +961,15 @@ def measured_traffic(workload_name, kernel="lookup_expand"):
 
 def summary_of(r):
     """The figures of one forward-only configuration that the targets are judged on."""
-    keys = ("step_ms", "step_ms_wall_mean", "N", "U", "M", "R", "dedupe_factor", "mean_session", "build_ms",
-            "lookup_unique_ms", "expand_ms", "lookup_expand_one_pass_ms", "kjt_lookup_ms", "speedup_vs_kjt",
+    keys = ("step_ms", "step_ms_wall_mean", "forward", "step_ms_one_pass_forward", "step_ms_two_call_forward", "N", "U", "M", "R", "dedupe_factor", "mean_session", "build_ms",
+            "build_with_run_index_ms", "lookup_unique_ms", "expand_ms", "lookup_expand_one_pass_ms", "kjt_lookup_ms", "speedup_vs_kjt",
             "speedup_vs_kjt_one_pass", "speedup_vs_kjt_with_build", "predicted_speedup_bytes_model",
             "predicted_speedup_compulsory_bytes")
     out = {k: r[k] for k in keys}
     out["lookup_plus_expand_gbs_compulsory"] = r["gbs"]["lookup_plus_expand_compulsory"]
     out["lookup_plus_expand_frac_of_peak"] = r["frac_of_peak"]["lookup_plus_expand_compulsory"]
     out["lookup_plus_expand_one_pass_gbs_compulsory"] = r["gbs"]["lookup_plus_expand_one_pass_compulsory"]
+    out["lookup_plus_expand_one_pass_frac_of_peak"] = r["frac_of_peak"]["lookup_plus_expand_one_pass_compulsory"]
     out["kjt_gbs_upper"] = r["gbs"]["kjt_upper"]
     return out
 
@@ -978,9 +1009,10 @@ def main():
     # the kernel that takes the most time in the timed steps, by the library's own event pairs
     live = res["kernels_in_timed_steps"]
     dom = max(live, key=lambda k: live[k]["avg_ms"])
-    with_runs = args.fused or (args.run_plan and args.planned and need_backward)
+    fused = one_pass_forward(w, args)
+    with_runs = fused or (args.run_plan and args.planned and need_backward)
     forward = ("build_ikjt_runs" if with_runs else "build_ikjt") + (
-        " + pooled_lookup_expand (one pass)" if args.fused else " + pooled_lookup_unique + expand_inverse")
+        " + pooled_lookup_expand (one pass)" if fused else " + pooled_lookup_unique + expand_inverse")
     line = {
         "metric": "deduped pooled lookups/sec",
         "value": value,

@@ -589,6 +589,405 @@ __global__ __launch_bounds__(256) void k_emit(const int64_t *__restrict__ values
     }
 }
 
+// ---- small batches: the whole builder in one launch ---------------------------------------------
+// Up to kSmallB rows per feature: one block per feature does what the four kernels above do, with
+// the feature's hash table and per-row arrays in LDS.  The blocks meet once: every block publishes
+// its counts (unique lists, runs, ids) in two self-describing 64-bit words and then reads those of
+// the features before it, which were dispatched earlier and never wait for a later block.  The last
+// block to arrive adds up the batch's totals, publishes them and clears the words for the next
+// launch.  A wait is bounded; a block whose wait expires numbers from zero (every write stays inside
+// the outputs) and the totals are published as -1.
+// The outputs are the canonical ones (first-occurrence numbering), the same as the general path's.
+constexpr int kSmallB = 1024;
+constexpr int kSmallThreads = 1024;
+constexpr int kSmallSpinLimit = 1 << 20;
+constexpr int64_t kSmallIds = 1 << 20;  // beyond this the general path's parallelism wins
+constexpr uint32_t kSmallEmpty = 0xffffffffu;
+constexpr uint64_t kSmallValid = 1ull << 63;
+
+// Wave 0: sums of the published words of features [0, n); false if a word did not arrive in time.
+__device__ __forceinline__ bool small_gather(const uint64_t *agg, int n, int lane, int spin_limit, int64_t &u,
+                                             int64_t &r, int64_t &m)
+{
+    u = r = m = 0;
+    int ok = spin_limit >= 0;  // a negative limit makes every wait expire (test hook)
+    for (int i = lane; i < n; i += 64) {
+        uint64_t w0 = 0, w1 = 0;
+        int spins = 0;
+        for (;;) {
+            w0 = __hip_atomic_load(agg + 2 * i, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            w1 = __hip_atomic_load(agg + 2 * i + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((w0 & kSmallValid) && (w1 & kSmallValid))
+                break;
+            if (++spins > spin_limit) {
+                ok = 0;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(2);
+        }
+        if (ok) {
+            u += (int64_t)(w0 & 0xffffull);
+            r += (int64_t)((w0 >> 16) & 0xffffull);
+            m += (int64_t)(w1 & ~kSmallValid);
+        }
+    }
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        u += __shfl_xor(u, d);
+        r += __shfl_xor(r, d);
+        m += __shfl_xor(m, d);
+        ok &= __shfl_xor(ok, d);
+    }
+    return ok != 0;
+}
+
+// Inclusive sums over the wave's lanes: shifts inside the rows of 16 lanes (data-parallel primitives,
+// no LDS traffic), then the totals of the rows before the lane's own.
+__device__ __forceinline__ uint32_t wave_scan_add(uint32_t x, int lane)
+{
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, false);  // row_shr:1
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, false);  // row_shr:2
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, false);  // row_shr:4
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, false);  // row_shr:8
+    const uint32_t t0 = (uint32_t)__builtin_amdgcn_readlane((int)x, 15), t1 = (uint32_t)__builtin_amdgcn_readlane((int)x, 31),
+                   t2 = (uint32_t)__builtin_amdgcn_readlane((int)x, 47);
+    const int row = lane >> 4;
+    return x + (row >= 1 ? t0 : 0u) + (row >= 2 ? t1 : 0u) + (row >= 3 ? t2 : 0u);
+}
+
+// The same inside one row of 16 lanes only (lanes 0..15 of a wave hold the 16 values).
+__device__ __forceinline__ uint32_t row_scan_add(uint32_t x)
+{
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x111, 0xf, 0xf, false);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x112, 0xf, 0xf, false);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x114, 0xf, 0xf, false);
+    x += (uint32_t)__builtin_amdgcn_update_dpp(0, (int)x, 0x118, 0xf, 0xf, false);
+    return x;
+}
+__device__ __forceinline__ int row_scan_max(int x)
+{
+    int y = __builtin_amdgcn_update_dpp(-1, x, 0x111, 0xf, 0xf, false);
+    x = y > x ? y : x;
+    y = __builtin_amdgcn_update_dpp(-1, x, 0x112, 0xf, 0xf, false);
+    x = y > x ? y : x;
+    y = __builtin_amdgcn_update_dpp(-1, x, 0x114, 0xf, 0xf, false);
+    x = y > x ? y : x;
+    y = __builtin_amdgcn_update_dpp(-1, x, 0x118, 0xf, 0xf, false);
+    return y > x ? y : x;
+}
+
+// agg: 2 words per feature, then the arrival counter and the failure mark; all zero between launches.
+// A feature's ids are one contiguous stretch of `values`: up to kSmallStage of them are brought into
+// LDS with one round of coalesced loads, and hashing, comparing and copying read them there (longer
+// stretches are read from memory each time).  Small kernels run at low clocks, so the instruction
+// count matters here: 32-bit hashing (the exact comparison decides anyway), ballots and lane shifts
+// for the scans, one barrier per phase.
+constexpr int kSmallStage = 16384;
+
+template <int SG>
+__global__ __launch_bounds__(kSmallThreads) void k_build_small(const int64_t *__restrict__ values,
+                                                               const int64_t *__restrict__ offsets, int B, int F,
+                                                               uint32_t cap_mask, int weak_hash, int spin_limit,
+                                                               uint64_t *agg, int64_t *__restrict__ u_values,
+                                                               int64_t *__restrict__ u_offsets,
+                                                               int32_t *__restrict__ inverse,
+                                                               int64_t *__restrict__ feat_uoff,
+                                                               int64_t *__restrict__ counts, int64_t *mailbox,
+                                                               int64_t seq, int64_t *__restrict__ run_index)
+{
+    __shared__ int64_t s_ids[kSmallStage];
+    __shared__ uint32_t s_tab[2 * kSmallB];
+    __shared__ uint32_t s_off[kSmallB + 1], s_pos[kSmallB];  // a row's ids start at s_off, relative to the feature
+    __shared__ int16_t s_slot[kSmallB];
+    __shared__ uint16_t s_num[kSmallB], s_src[kSmallB];
+    __shared__ uint32_t s_wcnt[kSmallThreads / 64], s_wlen[kSmallThreads / 64];
+    __shared__ int s_wlast[kSmallThreads / 64];
+    __shared__ int64_t s_base[4];
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int f = blockIdx.x;
+    const int64_t l0 = (int64_t)f * B;
+
+    // offsets of the feature's rows (one load per thread), the empty table
+    const int64_t fstart = offsets[l0];
+    for (int i = tid; i <= B; i += kSmallThreads)
+        s_off[i] = (uint32_t)(offsets[l0 + i] - fstart);
+    for (int i = tid; i <= (int)cap_mask; i += kSmallThreads)
+        s_tab[i] = kSmallEmpty;
+    __syncthreads();
+    const int n_ids = (int)s_off[B];
+    const bool staged = n_ids <= kSmallStage;
+    const int64_t *gids = values + fstart;
+    if (staged) {
+        for (int i0 = tid; i0 < n_ids; i0 += 8 * kSmallThreads) {
+            int64_t v[8];
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+                const int i = i0 + k * kSmallThreads;
+                v[k] = i < n_ids ? gids[i] : 0;
+            }
+#pragma unroll
+            for (int k = 0; k < 8; k++) {
+                const int i = i0 + k * kSmallThreads;
+                if (i < n_ids)
+                    s_ids[i] = v[k];
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- hash + insert: SG lanes per row, all rows of the feature at once ---------------------------
+    // id(i): the feature's i-th id, from LDS or from memory
+    auto insert_rows = [&](auto id) {
+        const int s = tid % SG;
+        const int b = tid / SG;
+        if (b >= B)
+            return;
+        const int start = (int)s_off[b], len = (int)s_off[b + 1] - start;
+        const int pstart = b > 0 ? (int)s_off[b - 1] : start;
+        int follows = b > 0 && (start - pstart) == len;
+        uint32_t h = 0;
+        for (int t0 = s; t0 < len; t0 += 4 * SG) {
+            int64_t v[4], q[4];
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                const int t = t0 + k * SG;
+                v[k] = t < len ? id(start + t) : 0;
+                q[k] = (follows && t < len) ? id(pstart + t) : v[k];
+            }
+#pragma unroll
+            for (int k = 0; k < 4; k++) {
+                const int t = t0 + k * SG;
+                if (t < len) {
+                    follows &= q[k] == v[k];
+                    // position-salted sum of mixed ids: which lane adds which id does not matter
+                    uint32_t x = (uint32_t)v[k] ^ ((uint32_t)((uint64_t)v[k] >> 32) * 0x9e3779b1u);
+                    x = (x + (uint32_t)(t + 1) * 0x7feb352du) * 0x85ebca6bu;
+                    h += x ^ (x >> 15);
+                }
+            }
+        }
+#pragma unroll
+        for (int m = SG / 2; m > 0; m >>= 1) {
+            h += __shfl_xor(h, m, SG);
+            follows &= __shfl_xor(follows, m, SG);
+        }
+        if (follows) {
+            if (s == 0)
+                s_slot[b] = -1;
+            return;
+        }
+        uint32_t hh = h ^ ((uint32_t)len * 0xc2b2ae35u + 1u);
+        hh ^= hh >> 16;
+        hh *= 0x85ebca6bu;
+        hh ^= hh >> 13;
+        hh *= 0xc2b2ae35u;
+        hh ^= hh >> 16;
+        if (weak_hash)
+            hh = (uint32_t)len;  // test hook: only the exact comparison separates lists
+        const uint32_t tag = hh >> 11;                     // 21 bits
+        const uint32_t mine = (tag << 10) | (uint32_t)b;  // below 2^31: never the empty mark
+        uint32_t slot = hh & cap_mask;
+        // at least 2 * B slots: an empty slot or the list's own class is met
+        for (;;) {
+            uint32_t old = 0;
+            if (s == 0)
+                old = atomicCAS(&s_tab[slot], kSmallEmpty, mine);
+            old = __shfl(old, 0, SG);
+            if (old == kSmallEmpty)
+                break;
+            if ((old >> 10) == tag) {
+                const int ob = (int)(old & 1023u);
+                const int ostart = (int)s_off[ob];
+                int eq = ((int)s_off[ob + 1] - ostart) == len;
+                if (eq)
+                    for (int t = s; t < len; t += SG)
+                        if (id(start + t) != id(ostart + t)) {
+                            eq = 0;
+                            break;
+                        }
+#pragma unroll
+                for (int m = SG / 2; m > 0; m >>= 1)
+                    eq &= __shfl_xor(eq, m, SG);
+                if (eq) {
+                    if (s == 0)
+                        atomicMin(&s_tab[slot], mine);
+                    break;
+                }
+            }
+            slot = (slot + 1) & cap_mask;
+        }
+        if (s == 0)
+            s_slot[b] = (int16_t)slot;
+    };
+    if (staged)
+        insert_rows([&](int i) { return s_ids[i]; });
+    else
+        insert_rows([&](int i) { return gids[i]; });
+    __syncthreads();
+
+    // ---- numbering inside the feature: one row per thread -----------------------------------------
+    const int b = tid;
+    bool first = false, head = false;
+    int my_rep = -1, my_len = 0, my_slot = -1;
+    if (b < B) {
+        my_slot = s_slot[b];
+        my_len = (int)(s_off[b + 1] - s_off[b]);
+        if (my_slot >= 0) {
+            head = true;
+            my_rep = (int)(s_tab[my_slot] & 1023u);
+            first = my_rep == b;
+        }
+    }
+    const uint64_t mf = __ballot(first), mh = __ballot(head);
+    const uint64_t le = lane == 63 ? ~0ull : ((1ull << (lane + 1)) - 1), lt = le >> 1;
+    const uint32_t ilen = wave_scan_add(first ? (uint32_t)my_len : 0u, lane);  // inclusive in the wave
+    const uint64_t hb = mh & le;
+    int head_row = hb ? b - lane + (63 - __builtin_clzll(hb)) : -1;  // nearest head at or before me in the wave
+    if (lane == 63) {
+        s_wcnt[wv] = (uint32_t)__popcll(mf) | ((uint32_t)__popcll(mh) << 16);
+        s_wlen[wv] = ilen;
+        s_wlast[wv] = mh ? b - 63 + (63 - __builtin_clzll(mh)) : -1;
+    }
+    __syncthreads();
+    // every wave scans the 16 wave totals itself (lanes 0..15): no second barrier
+    const int wl = lane & 15;
+    const uint32_t wc_i = row_scan_add(s_wcnt[wl]), wn_i = row_scan_add(s_wlen[wl]);
+    const int wh_i = row_scan_max(s_wlast[wl]);
+    const uint32_t tot_cnt = (uint32_t)__builtin_amdgcn_readlane((int)wc_i, 15);
+    const uint32_t tot_len = (uint32_t)__builtin_amdgcn_readlane((int)wn_i, 15);
+    uint32_t pre_cnt = 0, pre_len = 0;
+    int pre_last = -1;
+    if (wv > 0) {
+        pre_cnt = (uint32_t)__builtin_amdgcn_readlane((int)wc_i, wv - 1);
+        pre_len = (uint32_t)__builtin_amdgcn_readlane((int)wn_i, wv - 1);
+        pre_last = __builtin_amdgcn_readlane(wh_i, wv - 1);
+    }
+    const uint32_t firsts_before = (pre_cnt & 0xffffu) + (uint32_t)__popcll(mf & lt);
+    const uint32_t heads_before = (pre_cnt >> 16) + (uint32_t)__popcll(mh & lt);
+    const uint32_t len_before = pre_len + ilen - (first ? (uint32_t)my_len : 0u);
+    const uint32_t n_first = tot_cnt & 0xffffu, n_heads = tot_cnt >> 16;
+    if (head_row < 0)
+        head_row = pre_last;
+    if (b < B) {
+        if (!head)  // follower: the representative of its run head (row 0 is always a head)
+            my_rep = (int)(s_tab[s_slot[head_row]] & 1023u);
+        if (first) {
+            s_num[b] = (uint16_t)firsts_before;
+            s_pos[b] = len_before;
+            s_src[firsts_before] = (uint16_t)b;
+        }
+    }
+    if (tid == 0) {
+        __hip_atomic_store(agg + 2 * f, kSmallValid | ((uint64_t)n_heads << 16) | (uint64_t)n_first,
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(agg + 2 * f + 1, kSmallValid | (uint64_t)tot_len, __ATOMIC_RELAXED,
+                           __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();  // s_num is complete
+    // what needs no other feature's counts goes out while they travel
+    uint32_t lu = 0;
+    if (b < B) {
+        lu = s_num[my_rep];
+        inverse[l0 + b] = (int32_t)lu;
+    }
+
+    // ---- the features before this one ----------------------------------------------------------------
+    bool ok = true;
+    if (wv == 0) {
+        int64_t bu, br, bm;
+        ok = small_gather(agg, f, lane, spin_limit, bu, br, bm);
+        if (!ok)
+            bu = br = bm = 0;
+        if (lane == 0) {
+            s_base[0] = bu;
+            s_base[1] = br;
+            s_base[2] = bm;
+        }
+    }
+    __syncthreads();
+    const int64_t base_u = s_base[0], base_r = s_base[1], base_m = s_base[2];
+
+    // ---- emit ---------------------------------------------------------------------------------------------
+    if (b < B) {
+        if (first)
+            u_offsets[base_u + lu] = base_m + s_pos[b];
+        if (b == 0)
+            feat_uoff[f] = base_u;
+        if (run_index && head) {
+            int64_t *e = run_index + 3 * (1 + base_r + heads_before);
+            const uint32_t uf = (uint32_t)(base_u + lu) | (first ? 0x80000000u : 0u);
+            e[0] = (int64_t)(((uint64_t)uf << 32) | (uint32_t)(l0 + b));
+            e[1] = base_m + s_pos[my_rep];
+            e[2] = (int64_t)my_len;
+        }
+    }
+    auto copy_lists = [&](auto id) {
+        constexpr int CG = 8;  // lanes per copied list
+        for (int k = tid / CG; k < (int)n_first; k += kSmallThreads / CG) {
+            const int sb = s_src[k];
+            const int start = (int)s_off[sb], len = (int)s_off[sb + 1] - start;
+            const int64_t dst = base_m + s_pos[sb];
+            for (int t = tid % CG; t < len; t += CG)
+                u_values[dst + t] = id(start + t);
+        }
+    };
+    if (staged)
+        copy_lists([&](int i) { return s_ids[i]; });
+    else
+        copy_lists([&](int i) { return gids[i]; });
+
+    // ---- arrival: the last block adds up the batch and leaves the words clear -----------------------------
+    if (wv == 0) {
+        uint64_t *arrived = agg + 2 * (size_t)F;
+        unsigned long long before = 0;
+        if (lane == 0) {
+            if (!ok)
+                __hip_atomic_store(agg + 2 * (size_t)F + 1, 1ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            // my words and my reads of the others' lie before the arrival
+            before = __hip_atomic_fetch_add(arrived, 1ull, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_AGENT);
+        }
+        before = __shfl(before, 0);
+        if (before == (unsigned long long)(F - 1)) {
+            int64_t U, R, M;
+            bool all = small_gather(agg, F, lane, spin_limit, U, R, M);
+            const uint64_t failed = __hip_atomic_load(agg + 2 * (size_t)F + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            all = all && failed == 0;
+            for (int i = lane; i < 2 * F + 2; i += 64)
+                __hip_atomic_store(agg + i, 0ull, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (lane == 0) {
+                if (all) {
+                    u_offsets[U] = M;
+                    feat_uoff[F] = U;
+                    if (run_index) {
+                        run_index[0] = R;
+                        run_index[1] = U;
+                        run_index[2] = M;
+                        run_index[3 * (1 + R)] = (int64_t)F * B;
+                        run_index[3 * (1 + R) + 1] = M;
+                        run_index[3 * (1 + R) + 2] = 0;
+                    }
+                } else {
+                    U = R = M = -1;
+                    if (run_index)
+                        run_index[0] = 0;  // no runs: the one-pass lookup does nothing
+                }
+                counts[0] = U;
+                counts[1] = M;
+                counts[2] = R;
+                if (mailbox) {
+                    // every word carries the build's sequence number: the host needs no ordering between them
+                    const uint64_t tag = (uint64_t)RECD_MAILBOX_TAG_BIT | ((uint64_t)seq & (RECD_MAILBOX_TAG_BIT - 1));
+                    mailbox[0] = (int64_t)((tag << 40) | ((uint64_t)U & 0xffffffffffull));
+                    mailbox[1] = (int64_t)((tag << 40) | ((uint64_t)M & 0xffffffffffull));
+                    mailbox[2] = (int64_t)((tag << 40) | ((uint64_t)R & 0xffffffffffull));
+                }
+            }
+        }
+    }
+}
+
 __global__ void k_empty_ikjt(int F, int64_t *u_offsets, int64_t *feat_uoff, int64_t *counts)
 {
     for (int f = threadIdx.x; f <= F; f += blockDim.x)
@@ -1123,6 +1522,55 @@ static recd_status build_plain(recd_ctx *ctx, int F, int64_t B, int64_t N, const
     if (ctx->validate && n_lists > 0)
         RECD_TRY(recd_validate_kjt_offsets(ctx, F, B, N, offsets));
 
+    if (ctx->small_path && !weights && n_lists > 0 && B <= kSmallB && F <= RECD_SMALL_MAX_FEATURES &&
+        N <= kSmallIds && ctx->small_agg) {
+        // one launch: a block per feature, tables in LDS
+        hipStream_t st = ctx->stream;
+        int64_t *mailbox = nullptr;
+        int64_t seq = 0;
+        if (!host_U_M && ctx->mailbox) {
+            mailbox = ctx->mailbox_dev + 8;
+            seq = ++ctx->build_seq;
+        }
+        uint32_t cap = 64;
+        while (cap < 2 * (uint32_t)B)
+            cap <<= 1;
+        const int spin = ctx->small_path == 2 ? -1 : kSmallSpinLimit;
+        const int sg = B * 8 <= kSmallThreads ? 8 : (B * 4 <= kSmallThreads ? 4 : (B * 2 <= kSmallThreads ? 2 : 1));
+#define RECD_SMALL(SG)                                                                                              \
+    hipLaunchKernelGGL((k_build_small<SG>), dim3((unsigned)F), dim3(kSmallThreads), 0, st, values, offsets, (int)B, F, \
+                       cap - 1, ctx->weak_hash, spin, ctx->small_agg, u_values, u_offsets, inverse, feat_uoff,      \
+                       ctx->build_counts_dev, mailbox, seq, run_index)
+        if (sg == 8)
+            RECD_SMALL(8);
+        else if (sg == 4)
+            RECD_SMALL(4);
+        else if (sg == 2)
+            RECD_SMALL(2);
+        else
+            RECD_SMALL(1);
+#undef RECD_SMALL
+        RECD_HIP(ctx, hipGetLastError());
+        ctx->ws_used_since_build = false;
+        ctx->build_valid = true;
+        ctx->plan.valid = false;
+        RECD_HIP(ctx, hipEventRecord(ctx->ev_built, st));
+        ctx->built_inverse = inverse;
+        ctx->built_u_values = u_values;
+        if (host_U_M) {
+            ctx->build_published = false;
+            RECD_TRY(recd_fetch_scalars(ctx, ctx->build_counts_dev, 2, host_U_M));
+            if (host_U_M[0] < 0)
+                return recd_fail(ctx, RECD_EHIP, "the builder's blocks did not receive each other's counts in time");
+        } else if (mailbox) {
+            ctx->build_published = true;
+            ctx->build_tagged = true;
+        } else {
+            RECD_TRY(recd_publish_build_counts(ctx));
+        }
+        return RECD_OK;
+    }
+
     RECD_TRY(recd_reserve(ctx, recd_build_workspace(F, B)));
     ctx->ws_used_since_build = false;  // from here on: set again by the next workspace user
     WsCarver c(ctx->ws);
@@ -1195,6 +1643,7 @@ static recd_status build_plain(recd_ctx *ctx, int F, int64_t B, int64_t N, const
         RECD_TRY(recd_fetch_scalars(ctx, counts, 2, host_U_M));
     } else if (published) {
         ctx->build_published = true;
+        ctx->build_tagged = false;
     } else {
         RECD_TRY(recd_publish_build_counts(ctx));  // the empty batch, or no mailbox
     }

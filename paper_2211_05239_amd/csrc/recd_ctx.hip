@@ -172,6 +172,7 @@ recd_status recd_publish_build_counts(recd_ctx *ctx)
         return RECD_OK;  // no mapped mailbox: recd_last_ikjt_counts copies from the device array
     const int64_t seq = ++ctx->build_seq;
     ctx->build_published = true;
+    ctx->build_tagged = false;
     hipLaunchKernelGGL(k_publish, dim3(1), dim3(1), 0, ctx->stream, ctx->build_counts_dev, 3,
                        ctx->mailbox_dev + 8, seq);
     RECD_HIP(ctx, hipGetLastError());
@@ -279,6 +280,11 @@ recd_status recd_create(recd_ctx **out, int device, void *hip_stream, size_t wor
     void *bc = nullptr;
     ok = ok && hipMalloc(&bc, 4 * sizeof(int64_t)) == hipSuccess;
     ctx->build_counts_dev = static_cast<int64_t *>(bc);
+    void *sa = nullptr;
+    const size_t sa_bytes = (2 * RECD_SMALL_MAX_FEATURES + 2) * sizeof(uint64_t);
+    ok = ok && hipMalloc(&sa, sa_bytes) == hipSuccess;
+    ok = ok && hipMemset(sa, 0, sa_bytes) == hipSuccess;
+    ctx->small_agg = static_cast<uint64_t *>(sa);
     ok = ok && recd_static_scratch(ctx, device) == RECD_OK;
     if (ok && workspace_hint_bytes)
         ok = recd_reserve(ctx, workspace_hint_bytes) == RECD_OK;
@@ -328,6 +334,8 @@ recd_status recd_destroy(recd_ctx *ctx)
         (void)hipFree(ctx->group_map_dev);
     if (ctx->build_counts_dev)
         (void)hipFree(ctx->build_counts_dev);
+    if (ctx->small_agg)
+        (void)hipFree(ctx->small_agg);
     if (ctx->build_table)
         (void)hipFree(ctx->build_table);
     if (ctx->host_pinned)
@@ -355,6 +363,11 @@ recd_status recd_set_option(recd_ctx *ctx, recd_option opt, int64_t value)
     }
     switch ((int)opt) {
     case RECD_OPT_INTERNAL_TIMING: ctx->timing = value != 0; return RECD_OK;
+    case RECD_OPT_INTERNAL_SMALL_PATH:
+        if (value < 0 || value > 2)
+            return recd_fail(ctx, RECD_EINVAL, "small-path option takes 0, 1 or 2");
+        ctx->small_path = (int)value;
+        return RECD_OK;
     case RECD_OPT_INTERNAL_TUNE_SEGSUM:
         ctx->tune_lb = (int)(value % 100);
         ctx->tune_gens = (int)(value / 10000 % 100);
@@ -372,7 +385,16 @@ recd_status recd_set_option(recd_ctx *ctx, recd_option opt, int64_t value)
 
 // {U, M, runs} of the most recent plain / weighted build: from the build's own publication if there
 // is one (waits for that build only), else from the device array (waits for the stream).
+static recd_status last_build_counts_raw(recd_ctx *ctx, int64_t out[3]);
 static recd_status last_build_counts(recd_ctx *ctx, int64_t out[3])
+{
+    RECD_TRY(last_build_counts_raw(ctx, out));
+    if (out[0] < 0)  // the one-launch builder of small batches reports a failed build this way
+        return recd_fail(ctx, RECD_EHIP, "the builder's blocks did not receive each other's counts in time");
+    return RECD_OK;
+}
+
+static recd_status last_build_counts_raw(recd_ctx *ctx, int64_t out[3])
 {
     if (!ctx->build_valid)
         return recd_fail(ctx, RECD_EINVAL, "no recd_build_ikjt / recd_build_ikjt_weighted call on this context yet");
@@ -381,7 +403,17 @@ static recd_status last_build_counts(recd_ctx *ctx, int64_t out[3])
         // wait for the build's own publication, not for what was enqueued after it
         const auto t0 = std::chrono::steady_clock::now();
         for (uint64_t spin = 0;; spin++) {
-            if (ctx->mailbox[15] == ctx->build_seq) {
+            if (ctx->build_tagged) {
+                const uint64_t tag = (uint64_t)RECD_MAILBOX_TAG_BIT | ((uint64_t)ctx->build_seq & (RECD_MAILBOX_TAG_BIT - 1));
+                const uint64_t w0 = (uint64_t)ctx->mailbox[8], w1 = (uint64_t)ctx->mailbox[9], w2 = (uint64_t)ctx->mailbox[10];
+                if ((w0 >> 40) == tag && (w1 >> 40) == tag && (w2 >> 40) == tag) {
+                    const uint64_t m = 0xffffffffffull;
+                    out[0] = (w0 & m) == m ? -1 : (int64_t)(w0 & m);
+                    out[1] = (w1 & m) == m ? -1 : (int64_t)(w1 & m);
+                    out[2] = (w2 & m) == m ? -1 : (int64_t)(w2 & m);
+                    return RECD_OK;
+                }
+            } else if (ctx->mailbox[15] == ctx->build_seq) {
                 std::atomic_thread_fence(std::memory_order_acquire);
                 out[0] = ctx->mailbox[8];
                 out[1] = ctx->mailbox[9];

@@ -83,9 +83,17 @@ struct recd_ctx {
     int64_t *build_counts_dev = nullptr;
     int64_t build_seq = 0;        // sequence number of the latest publication (never reused)
     bool build_published = false; // the last build published its counts (else: read the device array)
+    // that publication is three words that each carry the sequence number (RECD_MAILBOX_TAG_BIT)
+    // instead of values followed by the number
+    bool build_tagged = false;
     bool build_valid = false;     // a plain / weighted build has written build_counts_dev
     // this device's copy of the static scratch array of recd_build_ikjt_noalloc (found at creation)
     char *static_scratch = nullptr;
+    // Small batches are built by one launch (a block per feature): 2 words per feature + 2 that the
+    // blocks exchange their counts through, all zero between launches.  small_path: 0 = never, 1 =
+    // whenever the batch qualifies, 2 = as 1 with every wait between the blocks made to expire.
+    uint64_t *small_agg = nullptr;
+    int small_path = 1;
     int timing = 0;  // RECD_OPT_INTERNAL_TIMING
     KernelTimer timers[RECD_T_COUNT];
     int validate = 0;
@@ -106,6 +114,14 @@ struct recd_ctx {
 #define RECD_OPT_INTERNAL_TUNE_SEGSUM 1003
 // value != 0: bracket the kernels named by RECD_T_* with HIP events (see recd_internal_kernel_ms)
 #define RECD_OPT_INTERNAL_TIMING 1004
+// 0: small batches take the general builder too; 1 (default): the one-launch builder; 2: the
+// one-launch builder with the waits between its blocks forced to expire (tests of the error path)
+#define RECD_OPT_INTERNAL_SMALL_PATH 1005
+#define RECD_SMALL_MAX_FEATURES 256
+// Tagged mailbox words of the one-launch builder: bits 40..63 = RECD_MAILBOX_TAG_BIT | low 23 bits of
+// the build's sequence number, bits 0..39 = the value (all ones: the build failed).  A word of the
+// other builders (a plain count below 2^40) never carries a tag.
+#define RECD_MAILBOX_TAG_BIT (1u << 23)
 void recd_time_begin(recd_ctx *ctx, int slot, hipStream_t st);
 void recd_time_end(recd_ctx *ctx, int slot, hipStream_t st);
 
@@ -198,6 +214,7 @@ struct SegSumArgs {
     int64_t B;
     int feat_base;
     int F_all;
+    int all_runs;             // 1: runs that are not their list's first sum the list too (no copy pass follows)
     int site;                 // RECD_SITE_*: which call site (each has its own kernel instantiation)
     int mode;                 // recd_pooling (forward sites only; 0 = sum)
     void *out;                // [lists, D]

@@ -180,6 +180,7 @@ struct SegSumParams {
     int64_t B;
     int64_t run_cap;         // no run number reaches this (F*B)
     int64_t runs_per_queue;  // queue q takes the runs [q * runs_per_queue, (q+1) * runs_per_queue) first
+    int all_runs;            // later runs of a list sum it again instead of waiting for a copy pass
     int feat_base;
 };
 
@@ -431,7 +432,8 @@ void k_segsum(const SegSumParams p)
                 break;  // runs beyond the last: so are all later items of this block
             const int64_t w0 = lane64(0);
             const uint32_t uf = (uint32_t)((uint64_t)w0 >> 32);
-            if (!(uf >> 31))
+            const bool first_run = (uf >> 31) != 0;
+            if (!first_run && !p.all_runs)
                 continue;  // not the list's first run
             const uint32_t row0 = (uint32_t)(uint64_t)w0;
             const int64_t u = uf & 0x7fffffffu;
@@ -455,7 +457,7 @@ void k_segsum(const SegSumParams p)
             }
             fold_groups(acc[0]);  // the butterfly leaves the finished row in every lane group
             if (piece_ok) {
-                if (g == 0) {
+                if (g == 0 && first_run) {
                     char *dst = static_cast<char *>(p.out) + u * out_row_bytes;
 #pragma unroll
                     for (int w = 0; w < VPL; w++)
@@ -915,6 +917,7 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
     p.run_cap = (int64_t)a.F_all * a.B;
     p.feat_base = a.feat_base;
     p.runs_per_queue = 0;
+    p.all_runs = a.all_runs;
     p.F = a.F;
     p.D = a.D;
     const int epv = a.table_dt == RECD_F32 ? 4 : 8;
@@ -1307,6 +1310,8 @@ recd_status recd_expand_inverse(recd_ctx *ctx, int F, int64_t B, int D, recd_dty
     return RECD_OK;
 }
 
+static constexpr int64_t kAllRunsRows = 16384;
+
 recd_status recd_pooled_lookup_expand(recd_ctx *ctx, int F, int64_t B, int D, recd_dtype table_dt,
                                       recd_dtype out_dt, const void *const *tables, const int64_t *rows,
                                       const int64_t *u_values, const int64_t *run_index, int64_t max_runs,
@@ -1336,6 +1341,9 @@ recd_status recd_pooled_lookup_expand(recd_ctx *ctx, int F, int64_t B, int D, re
             return recd_fail(ctx, RECD_EINVAL, "validation needs rows[]");
         RECD_TRY(validate_run_index(ctx, F, B, rows, u_values, run_index));
     }
+    // A small batch is bound by its launches, not by its gathers: there every run sums its list
+    // itself (the same ids in the same order: the same bits as a copy) and no copy pass follows.
+    const int all_runs = ctx->small_path != 0 && n_rows <= kAllRunsRows;
     for (int f0 = 0; f0 < F; f0 += RECD_F_PER_LAUNCH) {
         SegSumArgs a{};
         a.F = F - f0 < RECD_F_PER_LAUNCH ? F - f0 : RECD_F_PER_LAUNCH;
@@ -1355,8 +1363,11 @@ recd_status recd_pooled_lookup_expand(recd_ctx *ctx, int F, int64_t B, int D, re
         a.expanded = out;
         a.B = B;
         a.feat_base = f0;
+        a.all_runs = all_runs;
         RECD_TRY(recd_launch_segsum(ctx, a));
     }
+    if (all_runs)
+        return RECD_OK;
     const int vecs = (int)((size_t)D * elem_size(out_dt) / 16);
     int64_t cb = (max_runs + 63) / 64;
     if (cb > (int64_t)ctx->num_cu * 16)

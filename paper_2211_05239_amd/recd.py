@@ -32,6 +32,9 @@ RECD_OPT_VALIDATE, RECD_OPT_WEAK_HASH, RECD_OPT_LONG_SEGMENT_CUT = 1, 2, 4
 _OPT_INTERNAL_TUNE_SEGSUM = 1003
 # benchmark instrumentation (not in the public header): HIP-event brackets around single kernels
 _OPT_INTERNAL_TIMING = 1004
+# tests only (not in the public header): 0 = small batches take the general builder and the two-pass
+# form of the one-pass forward too, 1 = default, 2 = the one-launch builder's waits are made to expire
+_OPT_INTERNAL_SMALL_PATH = 1005
 KERNEL_SLOTS = {"lookup_expand": 0, "expand_uncovered": 1, "lookup_unique": 2, "expand": 3, "kjt_lookup": 4,
                 "hash_insert": 5, "grad_lists_sum": 6, "grad_rows_sum": 7, "emit": 8}
 RECD_POOL_SUM, RECD_POOL_MEAN, RECD_POOL_MAX = 0, 1, 2
@@ -153,6 +156,7 @@ class Context:
         if st != RECD_OK:
             raise RecdError(st, "recd_create failed")
         self.device = device
+        self.options = {}
 
     def close(self):
         if self._h:
@@ -179,6 +183,7 @@ class Context:
 
     def set_option(self, opt: int, value: int):
         self._check(_lib.recd_set_option(self._h, opt, value))
+        self.options[opt] = value   # what was last set (the library has no getter)
 
     # -- the five calls; tensors are caller-allocated device tensors ---------------------------
     def build_ikjt(self, F: int, B: int, values, offsets, u_values, u_offsets, inverse, feat_uoff,

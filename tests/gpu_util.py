@@ -50,6 +50,20 @@ def gpu_build(ctx, batch):
     ik = DeviceIKJT(batch.F, batch.B, batch.N)
     ik.U, ik.M = ctx.build_ikjt(batch.F, batch.B, values, offsets, ik.u_values, ik.u_offsets,
                                 ik.inverse, ik.feat_uoff, want_counts=True)
+    from paper_2211_05239_amd import recd as mod
+    small = ctx.options.get(mod._OPT_INTERNAL_SMALL_PATH, 1)
+    if 0 < batch.B <= 1024 and batch.F > 0 and small != 0:
+        # a batch this small is built by the one-launch builder: the general one must give the same arrays
+        ik2 = DeviceIKJT(batch.F, batch.B, batch.N)
+        ctx.set_option(mod._OPT_INTERNAL_SMALL_PATH, 0)
+        try:
+            ik2.U, ik2.M = ctx.build_ikjt(batch.F, batch.B, values, offsets, ik2.u_values, ik2.u_offsets,
+                                          ik2.inverse, ik2.feat_uoff, want_counts=True)
+        finally:
+            ctx.set_option(mod._OPT_INTERNAL_SMALL_PATH, small)
+        assert (ik.U, ik.M) == (ik2.U, ik2.M)
+        for name in ("u_values", "u_offsets", "inverse", "feat_uoff"):
+            assert torch.equal(getattr(ik, name), getattr(ik2, name)), name
     return values, offsets, ik
 
 

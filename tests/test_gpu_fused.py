@@ -18,9 +18,13 @@ def recd():
     return mod
 
 
-@pytest.fixture(scope="module")
-def ctx(recd):
+@pytest.fixture(scope="module", params=[1, 0], ids=["small-batch-forms", "general-forms"])
+def ctx(recd, request):
+    """Batches of the tests' sizes take the one-launch builder and the form of the one-pass forward in
+    which every run sums its list; the second round switches both off so that the same cases also run
+    through the general builder and the copy pass."""
     c = recd.Context(0)
+    c.set_option(recd._OPT_INTERNAL_SMALL_PATH, request.param)
     yield c
     c.close()
 

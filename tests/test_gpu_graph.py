@@ -63,8 +63,9 @@ class _Step:
         return [x.clone() for x in (self.out, self.feat_roff, self.inverse, self.feat_uoff, *self.tables, *self.state)]
 
 
-def test_step_replays_as_a_graph(recd):
-    w = synth.scaled(synth.WORKLOADS["cfg2"], F=4, B=1024, rows=20_000, D=64)
+@pytest.mark.parametrize("B", [1024, 1536], ids=["one-launch-builder", "general-builder"])
+def test_step_replays_as_a_graph(recd, B):
+    w = synth.scaled(synth.WORKLOADS["cfg2"], F=4, B=B, rows=20_000, D=64)
     batches = [synth.make_batch(w, i) for i in range(4)]
     gouts = [synth.make_grad_out(w, i) for i in range(4)]
     tabs = synth.make_tables(w)
