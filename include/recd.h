@@ -519,7 +519,10 @@ recd_status recd_ikjt_run_index(recd_ctx *ctx, int F, int64_t B, const int32_t *
  *    run_index: device, from call 23 or 24.  max_runs: the host's estimate of the number of runs
  *    (sizes the launch only, as max_lists in call 2; 0 = F*B).  u_values: device [M].
  *    pooled: device [U, D] of out_dt (room for U rows; F*B when U is not known).
- *    out: device [F, B, D] of out_dt.  Sum pooling; dtypes and D as in call 2.
+ *    out: device [F, B, D] of out_dt, or NULL: then only pooled is written (call 2 driven by the
+ *    run index; call 3 can follow).  Sum pooling; dtypes and D as in call 2.
+ *    A batch of at most 16384 rows takes one kernel: every run sums its list, also the later runs of
+ *    a list (same ids in the same order: the same bits), and no copy follows.
  *    The call does not use the context's workspace (a pending backward plan stays valid). */
 recd_status recd_pooled_lookup_expand(recd_ctx *ctx, int F, int64_t B, int D, recd_dtype table_dt,
                                       recd_dtype out_dt, const void *const *tables,

@@ -464,7 +464,7 @@ void k_segsum(const SegSumParams p)
                         store_row_piece<OT, EPV, false>(dst + ((int64_t)w * LPR + r) * OB, acc[0] + w * EPV);
                 }
                 char *dst = static_cast<char *>(p.expanded) + (int64_t)row0 * out_row_bytes;
-                for (uint32_t k = g; k < run_rows; k += 64 / LPR) {
+                for (uint32_t k = g; p.expanded && k < run_rows; k += 64 / LPR) {
 #pragma unroll
                     for (int w = 0; w < VPL; w++)
                         store_row_piece<OT, EPV, true>(dst + (int64_t)k * out_row_bytes + ((int64_t)w * LPR + r) * OB,
@@ -971,7 +971,7 @@ recd_status recd_launch_segsum(recd_ctx *ctx, const SegSumArgs &a)
         ok = launch_forward<SITE_UNIQUE>(st, blocks, v, a, p);
     else if (a.site == RECD_SITE_KJT && fwd && a.mode == POOL_SUM)
         ok = launch_forward<SITE_KJT>(st, blocks, v, a, p);
-    else if (a.site == RECD_SITE_UNIQUE_EXPAND && fwd && a.mode == POOL_SUM && a.run_index && a.expanded)
+    else if (a.site == RECD_SITE_UNIQUE_EXPAND && fwd && a.mode == POOL_SUM && a.run_index)
         ok = launch_forward<SITE_UNIQUE_EXPAND>(st, blocks, v, a, p);
     else if (a.site == RECD_SITE_UNIQUE && fwd && a.mode == POOL_MEAN)
         ok = launch_forward<SITE_UNIQUE, POOL_MEAN>(st, blocks, v, a, p);
@@ -1330,7 +1330,7 @@ recd_status recd_pooled_lookup_expand(recd_ctx *ctx, int F, int64_t B, int D, re
         max_runs = n_rows;
     if (max_runs < F)
         max_runs = F;  // every feature of a batch with rows starts a run
-    if (!tables || !run_index || !pooled || !out)
+    if (!tables || !run_index || !pooled)
         return recd_fail(ctx, RECD_EINVAL, "null pointer argument");  // u_values may be null when M = 0
     for (int f = 0; f < F; f++)
         if (!tables[f])
@@ -1343,7 +1343,7 @@ recd_status recd_pooled_lookup_expand(recd_ctx *ctx, int F, int64_t B, int D, re
     }
     // A small batch is bound by its launches, not by its gathers: there every run sums its list
     // itself (the same ids in the same order: the same bits as a copy) and no copy pass follows.
-    const int all_runs = ctx->small_path != 0 && n_rows <= kAllRunsRows;
+    const int all_runs = out && ctx->small_path != 0 && n_rows <= kAllRunsRows;
     for (int f0 = 0; f0 < F; f0 += RECD_F_PER_LAUNCH) {
         SegSumArgs a{};
         a.F = F - f0 < RECD_F_PER_LAUNCH ? F - f0 : RECD_F_PER_LAUNCH;
@@ -1366,7 +1366,7 @@ recd_status recd_pooled_lookup_expand(recd_ctx *ctx, int F, int64_t B, int D, re
         a.all_runs = all_runs;
         RECD_TRY(recd_launch_segsum(ctx, a));
     }
-    if (all_runs)
+    if (all_runs || !out)
         return RECD_OK;
     const int vecs = (int)((size_t)D * elem_size(out_dt) / 16);
     int64_t cb = (max_runs + 63) / 64;

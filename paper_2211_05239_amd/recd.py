@@ -219,7 +219,7 @@ class Context:
         F = len(tables)
         D = tables[0].shape[1] if F else pooled.shape[-1]
         tdt = _DT[tables[0].dtype] if F else _DT[pooled.dtype]
-        assert out.dtype == pooled.dtype
+        assert out is None or out.dtype == pooled.dtype
         self._check(_lib.recd_pooled_lookup_expand(
             self._h, F, B, D, tdt, _DT[pooled.dtype], self._table_array(tables), self._rows_array(tables),
             _ptr(u_values), _ptr(run_index), max_runs, _ptr(pooled), _ptr(out)))

@@ -79,6 +79,11 @@ def _fused_case(ctx, w, batch, out_dtype=None, max_runs=None):
     ctx.kjt_pooled_lookup(d_tabs, B, values, offsets, kjt)
     torch.cuda.synchronize()
     assert torch.equal(_bits(pooled), _bits(pooled2))   # rows beyond U keep their fill in both
+    # without an output the call is the unique lookup alone
+    pooled3 = torch.full((L, D), float("nan"), dtype=odt, device="cuda")
+    ctx.pooled_lookup_expand(d_tabs, B, ik.u_values, runs, F * B if max_runs is None else max_runs, pooled3, None)
+    torch.cuda.synchronize()
+    assert torch.equal(_bits(pooled3), _bits(pooled2))
     assert torch.equal(_bits(out), _bits(out2))
     assert torch.equal(_bits(out), _bits(kjt))
     ref = orc.expand_inverse(F, B, orc.pooled_lookup(tabs, dt, uv, uo, fu), fu, inv)
