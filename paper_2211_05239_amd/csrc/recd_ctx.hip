@@ -284,6 +284,7 @@ recd_status recd_create(recd_ctx **out, int device, void *hip_stream, size_t wor
     const size_t sa_bytes = (2 * RECD_SMALL_MAX_FEATURES + 2) * sizeof(uint64_t);
     ok = ok && hipMalloc(&sa, sa_bytes) == hipSuccess;
     ok = ok && hipMemset(sa, 0, sa_bytes) == hipSuccess;
+    ok = ok && hipStreamSynchronize(nullptr) == hipSuccess;  // cleared before any stream of the context reads it
     ctx->small_agg = static_cast<uint64_t *>(sa);
     ok = ok && recd_static_scratch(ctx, device) == RECD_OK;
     if (ok && workspace_hint_bytes)
