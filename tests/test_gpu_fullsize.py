@@ -540,3 +540,73 @@ def test_cfg5_max_backward_full(recd):
         assert np.array_equal(tr_f, tr[fr[f]:fr[f + 1]])
         gu.assert_close_f32(grad_rows[fr[f]:fr[f + 1]].double().cpu().numpy(), gr_f, f"max grad rows {f}")
     ctx.close()
+
+
+def test_more_than_2_31_ids(recd):
+    """Positions beyond 2^31 in `values` and in `u_values` (the interface takes int64 positions; F*B and
+    the ids themselves stay below 2^31): 54 lists of about 5e7 ids each, 2.7e9 ids in all, almost all
+    lists distinct, a few repeated next to and far from their first occurrence.  Integer outputs against
+    the oracle; the lookups against each other bit for bit and, for three lists, against an exact sum
+    (table entries are -1, 0 or 1 and the partial sums stay far below 2^24, so fp32 adds exactly)."""
+    F, B, D, rows = 2, 27, 4, 1_000_003
+    rng = np.random.default_rng(20231)
+    lens = rng.integers(49_000_000, 51_000_000, size=F * B)
+    # which earlier row of the same feature a row repeats (-1: its own content)
+    src = np.full(F * B, -1)
+    for f in range(F):
+        src[f * B + 5] = f * B + 4      # adjacent
+        src[f * B + 17] = f * B + 2     # far apart
+        src[f * B + 23] = f * B + 17    # a repeat of a repeat
+    for l in range(F * B):
+        if src[l] >= 0:
+            lens[l] = lens[src[l]]
+    offsets = np.zeros(F * B + 1, dtype=np.int64)
+    np.cumsum(lens, out=offsets[1:])
+    N = int(offsets[-1])
+    assert N > 2**31 + 2**27
+    values = np.empty(N, dtype=np.int64)
+    for l in range(F * B):
+        a, b = offsets[l], offsets[l + 1]
+        if src[l] >= 0:
+            values[a:b] = values[offsets[src[l]]:offsets[src[l] + 1]]
+        else:   # cheap, position-dependent, different for every list
+            values[a:b] = (np.arange(b - a, dtype=np.int64) * (2 * l + 3) + 7 * l * l) % rows
+    print(f"  {N} ids generated", flush=True)   # progress lines: the stages take tens of seconds each
+    d_values, d_offsets = torch.from_numpy(values).cuda(), torch.from_numpy(offsets).cuda()
+    ctx = recd.Context(0)
+    u_values = torch.full((N,), -7, dtype=torch.int64, device="cuda")
+    u_offsets = torch.full((F * B + 1,), -7, dtype=torch.int64, device="cuda")
+    inverse = torch.full((F * B,), -7, dtype=torch.int32, device="cuda")
+    feat_uoff = torch.full((F + 1,), -7, dtype=torch.int64, device="cuda")
+    U, M = ctx.build_ikjt(F, B, d_values, d_offsets, u_values, u_offsets, inverse, feat_uoff, want_counts=True)
+    assert U == F * (B - 3) and M > 2**31
+    print(f"  built on the GPU: U={U} M={M}", flush=True)
+    uv, uo, inv, fu = orc.build_ikjt(F, B, values, offsets)
+    print("  built by the oracle", flush=True)
+    assert (U, M) == (int(fu[-1]), len(uv))
+    assert np.array_equal(u_offsets[:U + 1].cpu().numpy(), uo)
+    assert np.array_equal(inverse.cpu().numpy(), inv)
+    assert np.array_equal(feat_uoff.cpu().numpy(), fu)
+    got = u_values[:M].cpu().numpy()
+    assert np.array_equal(got, uv)
+    del got, uv
+    print("  unique lists compared", flush=True)
+    # lookups: tables of -1 / 0 / 1
+    tabs = [((np.arange(rows * D, dtype=np.int64).reshape(rows, D) * (f + 2) // 3) % 3 - 1).astype(np.float32)
+            for f in range(F)]
+    d_tabs = [torch.from_numpy(t).cuda() for t in tabs]
+    pooled = torch.full((F * B, D), float("nan"), device="cuda")
+    out = torch.full((F, B, D), float("nan"), device="cuda")
+    kjt = torch.full((F, B, D), float("nan"), device="cuda")
+    ctx.pooled_lookup_unique(d_tabs, u_values, u_offsets, feat_uoff, U, pooled)
+    ctx.expand_inverse(F, B, pooled, feat_uoff, inverse, out)
+    ctx.kjt_pooled_lookup(d_tabs, B, d_values, d_offsets, kjt)
+    torch.cuda.synchronize()
+    assert torch.equal(out.view(torch.int32), kjt.view(torch.int32))
+    for l in (0, B + 17, F * B - 1):   # the last one lies beyond position 2^31
+        f = l // B
+        exact = tabs[f][values[offsets[l]:offsets[l + 1]]].astype(np.float64).sum(axis=0)
+        assert np.abs(exact).max() < 2**22
+        assert np.array_equal(kjt[f, l - f * B].double().cpu().numpy(), exact), l
+    assert offsets[F * B - 1] > 2**31
+    ctx.close()
