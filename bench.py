@@ -564,6 +564,9 @@ def run_workload(torch, recd, synth, w, args, need_backward, detail=True, pipeli
     if all(x is not None for x in tr):
         res["bytes"]["lookup_plus_expand_traffic"] = sum(tr)
         res["gbs"]["lookup_plus_expand_traffic"] = sum(tr) / (lookup_ms + expand_ms) / 1e6
+        # the same region with the HBM bytes the profiler measured for the two kernels (read from the
+        # committed profile, see traffic_source) in the place of the algorithmic bytes
+        res["frac_of_peak"]["lookup_plus_expand_traffic"] = res["gbs"]["lookup_plus_expand_traffic"] / HBM_PEAK_GBS
     if need_backward and "kjt_backward_ms" in res:
         res["backward_speedup_vs_kjt"] = res["kjt_backward_ms"] / res["backward_ms"]
     # Speedup of the deduplicated forward over the KJT lookup, and what the bytes predict for it:
