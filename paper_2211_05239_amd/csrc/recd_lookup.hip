@@ -612,7 +612,13 @@ bool launch_forward(hipStream_t st, int blocks, int v, const SegSumArgs &a, cons
 // first loads the inverse entries of all its rows, then all its pooled pieces, then stores them
 // with streaming (non-temporal) stores: the output is written once and never re-read here, while
 // the pooled rows, shared by the consecutive samples of a session, should stay in L2.
-constexpr int kExpandRPT = 8;
+// Rows per thread, measured at 1.05 M rows of 512 bytes (same buffers, back to back): 3: 106 us, 4: 94,
+// 5: 92.5, 6: 90.5, 7: 93.5, 8: 98-100, 10: 100, 12: 103; blocks of 64, 128, 512 or 1024 threads
+// instead of 256 are no faster at their best row counts (90.8-92 us), and occupancy limits do not
+// help.  Fewer stores per wave reach memory in a more sequential order (a store-only kernel of this
+// shape runs at 5.5 TB/s with 8 stores per thread and at 6.9 with one), more rows per thread hide
+// the two dependent loads: six is where the two meet.
+constexpr int kExpandRPT = 6;
 
 template <bool TWO_FEATURES>
 __global__ __launch_bounds__(kBlock) void k_expand(const u32x4 *__restrict__ pooled,
