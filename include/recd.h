@@ -122,7 +122,11 @@ recd_status recd_workspace_bytes(int F, int64_t B, int64_t N, int D, size_t *out
  *    feat_uoff: device [F+1].  Entries of u_values / u_offsets beyond M / U+1 are left untouched.
  *    host_U_M: optional host int64[2]; if non-NULL the call waits for the build and stores U and M
  *    there.  If NULL the build publishes them when it finishes on the GPU and
- *    recd_last_ikjt_counts returns them later. */
+ *    recd_last_ikjt_counts returns them later.
+ *    A batch of at most 1024 rows per feature, 256 features and 2^20 ids is built by one kernel
+ *    launch (same outputs).  Its blocks exchange their counts once, with a bounded wait; should a
+ *    wait ever expire, the outputs are unspecified and the error is reported as RECD_EHIP where U
+ *    and M are handed over: by this call if host_U_M is given, else by recd_last_ikjt_counts. */
 recd_status recd_build_ikjt(recd_ctx *ctx, int F, int64_t B, int64_t N,
                             const int64_t *values, const int64_t *offsets,
                             int64_t *u_values, int64_t *u_offsets, int32_t *inverse,
